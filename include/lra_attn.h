@@ -1,0 +1,202 @@
+/*
+ * lra_attn.h - C ABI of the Flash-LoRA-Attention library for MI355X (gfx950).
+ *
+ * Method: LRAgent (arxiv 2602.01053), Sec. 3.3 and Alg. 1 ("Flash-LoRA-Attention
+ * forward"), App. B (reordering by associativity), App. D.1 (the same
+ * decomposition on the key side).
+ *
+ * Every agent of a multi-LoRA system attends over ONE shared base cache
+ * (K_base, V_base) and ONE shared low-rank cache L (n x r, the activations right
+ * after the shared LoRA down-projection; Sec. 3.2 "BaseLRShared").  Agent a's own
+ * keys and values are, by definition,
+ *
+ *     K^a = K_base + L . B_K^a        V^a = V_base + L . B_V^a
+ *
+ * and are never formed.  The library evaluates O = softmax(scale . Q K^a^T) V^a as
+ *
+ *     S = scale . ( Q K_base^T + (Q B_K^T) L^T )        (App. D.1 reordering)
+ *     O = ( P V_base + (P L) B_V ) / rowsum             (Sec. 3.3, Alg. 1)
+ *
+ * inside an online-softmax loop over key tiles, with the rank-r accumulator P.L
+ * carried next to the head-dimension accumulator and B_V applied once at the end.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers marked DEVICE point to memory of the current HIP device, pointers
+ *     marked HOST to ordinary host memory.  Nothing is copied across.
+ *   - Ownership: every buffer belongs to the caller.  The library allocates and
+ *     frees nothing and keeps no pointer after a call returns.
+ *   - Asynchronous: kernels are enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream).  No call synchronises.  Outputs are valid
+ *     once the stream has reached the end of the enqueued work.
+ *   - Errors: a status code is returned; nothing is thrown and nothing aborts.
+ *     All argument checks run before the first launch, so a status other than
+ *     LRA_OK (except LRA_ERR_HIP) means nothing was enqueued.  Inputs are never
+ *     written.
+ *   - Deterministic: equal arguments give bitwise equal outputs.
+ *   - The caches already contain the rows of the new query tokens: a sequence of
+ *     n tokens holds L_p old and L_c new ones, n = L_p + L_c (Alg. 1, first line).
+ *   - Element type `dtype` applies to Q, K_base, V_base, L, B_K, B_V and the
+ *     output alike.  Accumulation is always fp32.
+ *   - Alignment: all DEVICE tensor pointers 16-byte aligned; the cache strides
+ *     multiples of 8 elements.
+ *
+ * Supported: head_dim in {64, 128}; 1 <= rank <= 64; n_q_heads a multiple of
+ * n_kv_heads with a group of at most 16; q head g reads kv head g / (Hq/Hkv);
+ * block_size 0 (contiguous) or 16; dtype bf16 (MFMA kernels) or fp32 (vector-ALU
+ * kernels).  Anything else returns LRA_ERR_UNSUPPORTED.
+ */
+#ifndef LRA_ATTN_H
+#define LRA_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LRA_OK = 0,
+  LRA_ERR_NULL = 1,        /* a required pointer is NULL */
+  LRA_ERR_SHAPE = 2,       /* a size or stride is out of range or inconsistent */
+  LRA_ERR_DTYPE = 3,       /* dtype is not one of lra_dtype */
+  LRA_ERR_UNSUPPORTED = 4, /* valid, but outside the supported set above */
+  LRA_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than required */
+  LRA_ERR_HIP = 6          /* a HIP launch reported an error */
+} lra_status;
+
+typedef enum { LRA_BF16 = 0, LRA_F32 = 1 } lra_dtype;
+
+/* Attention shape of one layer. */
+typedef struct {
+  int32_t n_q_heads;  /* Hq */
+  int32_t n_kv_heads; /* Hkv */
+  int32_t head_dim;   /* d = d_head of Alg. 1 */
+  int32_t rank;       /* r, columns of the LR cache and rows of every B */
+  int32_t dtype;      /* lra_dtype */
+  float scale;        /* softmax scale; 0.0f selects 1/sqrt(head_dim) (Alg. 1 line 10).
+                         The rank never enters the scale. */
+} lra_shape;
+
+/*
+ * Shared base cache + shared LR cache (Sec. 3.2: one copy for all agents).
+ *
+ * Contiguous form (block_size == 0), exactly one sequence:
+ *   token j, kv head h of K_base is the d elements at
+ *       k_base + j*kv_token_stride + h*kv_head_stride        (units: elements)
+ *   token-major [n][Hkv][d] is token_stride = Hkv*d, head_stride = d;
+ *   head-major  [Hkv][n][d] is token_stride = d,     head_stride = n*d.
+ *   L is dense [n][rank].
+ *
+ * Paged form (block_size == 16): token j of sequence t lives in physical block
+ *   b = block_table[t*max_blocks_per_seq + j/16], slot j%16, at
+ *       k_base + b*kv_block_stride + h*kv_head_stride + (j%16)*kv_token_stride
+ *   ([num_blocks][Hkv][16][d] is block_stride = Hkv*16*d, head_stride = 16*d,
+ *   token_stride = d).  L is dense [num_blocks][16][rank].
+ *   Block-table entries past a sequence's last block are never read.  Entries that
+ *   are read must lie in [0, num_blocks); they are not checked on the device.
+ *   Slots past seq_lens[t] inside the last block may hold anything, NaN included.
+ *
+ * v_base uses the same strides as k_base.
+ */
+typedef struct {
+  const void* k_base;          /* DEVICE */
+  const void* v_base;          /* DEVICE */
+  const void* l;               /* DEVICE */
+  int64_t kv_token_stride;
+  int64_t kv_head_stride;
+  int64_t kv_block_stride;     /* paged only */
+  int32_t block_size;          /* 0 or 16 */
+  int32_t max_blocks_per_seq;  /* paged only: row length of block_table */
+  int32_t num_blocks;          /* paged only */
+  int32_t n_seqs;              /* 1 when contiguous */
+  const int32_t* block_table;  /* DEVICE int32 [n_seqs][max_blocks_per_seq]; NULL when contiguous */
+  const int32_t* seq_lens;     /* DEVICE int32 [n_seqs]: cached tokens n_t of each sequence, >= 1 */
+  int32_t max_seq_len;         /* HOST-known upper bound of every seq_lens[t]; sizes the launch.
+                                  Sequences longer than this are truncated to it. */
+} lra_cache;
+
+/*
+ * Per-agent adapter table (Sec. 3.2: "agent-specific outputs via their B_i").
+ * b_k / b_v: DEVICE [n_adapters][rank][Hkv*head_dim], row-major; kv head h owns
+ * columns h*d .. (h+1)*d-1 (Eq. 1: B is r x d_out).  Any LoRA scaling alpha/r is
+ * folded into B by the caller.  b_k == NULL means B_K = 0 for every adapter (the
+ * paper's main setting: keys fully shared); b_v == NULL means B_V = 0.
+ */
+typedef struct {
+  const void* b_k;
+  const void* b_v;
+  int32_t n_adapters;
+} lra_adapters;
+
+/*
+ * Bytes of DEVICE workspace that lra_attn_decode (n_new == 1) or lra_attn_prefill
+ * needs for these arguments; 0 is a valid answer.  Returns (size_t)-1 when the
+ * arguments themselves would be rejected.  max_queries_per_seq as for decode
+ * (pass 1 for prefill).
+ */
+size_t lra_workspace_bytes(const lra_shape* shape, const lra_cache* cache, int32_t n_queries,
+                           int32_t max_queries_per_seq, int32_t n_new);
+
+/*
+ * Decode step for many agents at once (Alg. 1 with L_c = 1 per query, the
+ * flash-decoding split over keys the paper builds on, and the adapter table).
+ *
+ * Query i is one new token of one agent.  It attends over all seq_lens[t] cached
+ * tokens of its sequence t (no mask) with adapter query_adapter[i].  Queries are
+ * grouped by sequence: sequence t owns queries seq_query_start[t] ..
+ * seq_query_start[t+1]-1, so all agents working on one sequence share a single
+ * pass over that sequence's K_base, V_base and L.
+ *
+ *   q                DEVICE [n_queries][Hq][d]
+ *   query_adapter    DEVICE int32 [n_queries], values in [0, n_adapters)
+ *   seq_query_start  DEVICE int32 [n_seqs+1], non-decreasing, [0] = 0, [n_seqs] = n_queries
+ *   max_queries_per_seq  HOST-known upper bound of the per-sequence query count
+ *   out              DEVICE [n_queries][Hq][d], same dtype as q
+ *   workspace        DEVICE, 256-byte aligned, >= lra_workspace_bytes(...); contents
+ *                    undefined afterwards.  Calls that overlap in time need
+ *                    separate workspaces.
+ */
+lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache,
+                           const lra_adapters* adapters, const void* q,
+                           const int32_t* query_adapter, const int32_t* seq_query_start,
+                           int32_t n_queries, int32_t max_queries_per_seq, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Causal prefill of one agent (Alg. 1 as printed: L_c = n_new query tokens after
+ * L_p cached ones).  The n_new query tokens are the LAST n_new tokens of sequence
+ * seq_index, whose cache rows are already in place; new token i sees keys
+ * 0 .. n_t - n_new + i ("Mask" of Alg. 1 line 10, aligned to the end).
+ *
+ *   q    DEVICE [n_new][Hq][d]        out  DEVICE [n_new][Hq][d]
+ *   seq_index in [0, n_seqs), adapter_index in [0, n_adapters)
+ *   1 <= n_new <= max_seq_len; the device-side seq_lens[seq_index] must be >= n_new.
+ */
+lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache,
+                            const lra_adapters* adapters, const void* q, int32_t seq_index,
+                            int32_t adapter_index, int32_t n_new, void* out, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* lra_status_string(lra_status status);
+
+/*
+ * Tuning and test hook: choose the kernel family for later calls from this
+ * process.  0 = automatic (MFMA kernels for bf16, vector-ALU kernels for fp32),
+ * 1 = force the vector-ALU kernels for every dtype.  Returns the previous value.
+ * Does not affect results beyond rounding.
+ */
+int32_t lra_set_kernel_variant(int32_t variant);
+
+/*
+ * Tuning hook: keys handled per workgroup in decode (the flash-decoding split
+ * size).  0 restores the automatic choice.  Values are rounded up to a multiple
+ * of the kernel's key tile.  Returns the previous value.
+ */
+int32_t lra_set_decode_split_keys(int32_t keys);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRA_ATTN_H */

@@ -1,0 +1,173 @@
+"""Thin ctypes binding over liblra_attn.so: argument marshalling only.
+
+Every step of the attention path runs inside the library's HIP kernels.  There is
+no CPU or PyTorch fallback: if the shared library is missing the first call
+raises.  torch is used for device memory and streams, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .build import LIB_PATH
+
+LRA_OK = 0
+LRA_BF16, LRA_F32 = 0, 1
+
+EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
+           "lra_set_kernel_variant", "lra_set_decode_split_keys")
+
+
+class LraShape(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("rank", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class LraCache(ctypes.Structure):
+    _fields_ = [("k_base", ctypes.c_void_p), ("v_base", ctypes.c_void_p), ("l", ctypes.c_void_p),
+                ("kv_token_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64),
+                ("kv_block_stride", ctypes.c_int64),
+                ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+                ("num_blocks", ctypes.c_int32), ("n_seqs", ctypes.c_int32),
+                ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+                ("max_seq_len", ctypes.c_int32)]
+
+
+class LraAdapters(ctypes.Structure):
+    _fields_ = [("b_k", ctypes.c_void_p), ("b_v", ctypes.c_void_p), ("n_adapters", ctypes.c_int32)]
+
+
+class LraError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"lra_attn status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen the in-tree library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2602_01053_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    sp, cp, ap = ctypes.POINTER(LraShape), ctypes.POINTER(LraCache), ctypes.POINTER(LraAdapters)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    lib.lra_workspace_bytes.restype = ctypes.c_size_t
+    lib.lra_workspace_bytes.argtypes = [sp, cp, i32, i32, i32]
+    lib.lra_attn_decode.restype = ctypes.c_int
+    lib.lra_attn_decode.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.lra_attn_prefill.restype = ctypes.c_int
+    lib.lra_attn_prefill.argtypes = [sp, cp, ap, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.lra_status_string.restype = ctypes.c_char_p
+    lib.lra_status_string.argtypes = [ctypes.c_int]
+    lib.lra_set_kernel_variant.restype = i32
+    lib.lra_set_kernel_variant.argtypes = [i32]
+    lib.lra_set_decode_split_keys.restype = i32
+    lib.lra_set_decode_split_keys.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def lra_status_string(status: int) -> str:
+    return load_library().lra_status_string(int(status)).decode()
+
+
+def lra_set_kernel_variant(variant: int) -> int:
+    return int(load_library().lra_set_kernel_variant(int(variant)))
+
+
+def lra_set_decode_split_keys(keys: int) -> int:
+    return int(load_library().lra_set_decode_split_keys(int(keys)))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return LRA_BF16
+    if t.dtype == torch.float32:
+        return LRA_F32
+    raise LraError(3, f"unsupported torch dtype {t.dtype}")
+
+
+def make_shape(q: torch.Tensor, n_kv_heads: int, rank: int, scale: float = 0.0) -> LraShape:
+    return LraShape(int(q.shape[-2]), int(n_kv_heads), int(q.shape[-1]), int(rank), _dtype_code(q),
+                    float(scale))
+
+
+def make_cache(k_base: torch.Tensor, v_base: torch.Tensor, l: torch.Tensor, seq_lens: torch.Tensor,
+               max_seq_len: int, block_table: Optional[torch.Tensor] = None) -> LraCache:
+    """Describe a cache held in torch tensors.
+
+    contiguous: k_base/v_base any strided view indexed [token][kv head][d] with a
+    unit stride on d; paged: k_base/v_base [num_blocks][Hkv][16][d] (strided view
+    allowed), block_table int32 [n_seqs][max_blocks]."""
+    if k_base.stride() != v_base.stride() or k_base.stride(-1) != 1:
+        raise LraError(2, "k_base and v_base must share strides, innermost stride 1")
+    if not l.is_contiguous():
+        raise LraError(2, "l must be dense")
+    if block_table is None:
+        return LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(0), k_base.stride(1), 0,
+                        0, 0, 0, 1, None, _ptr(seq_lens), int(max_seq_len))
+    return LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(2), k_base.stride(1),
+                    k_base.stride(0), int(k_base.shape[2]), int(block_table.shape[1]),
+                    int(k_base.shape[0]), int(block_table.shape[0]), _ptr(block_table),
+                    _ptr(seq_lens), int(max_seq_len))
+
+
+def lra_workspace_bytes(shape: LraShape, cache: LraCache, n_queries: int,
+                        max_queries_per_seq: int = 1, n_new: int = 1) -> int:
+    n = load_library().lra_workspace_bytes(ctypes.byref(shape), ctypes.byref(cache), int(n_queries),
+                                           int(max_queries_per_seq), int(n_new))
+    if n == ctypes.c_size_t(-1).value:
+        raise LraError(2, "lra_workspace_bytes rejected the arguments")
+    return int(n)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _check(status: int) -> None:
+    if status != LRA_OK:
+        raise LraError(status, lra_status_string(status))
+
+
+def lra_attn_decode(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor],
+                    b_v: Optional[torch.Tensor], n_adapters: int, q: torch.Tensor,
+                    query_adapter: torch.Tensor, seq_query_start: torch.Tensor,
+                    max_queries_per_seq: int, out: torch.Tensor, workspace: Optional[torch.Tensor],
+                    stream=None) -> None:
+    ad = LraAdapters(_ptr(b_k), _ptr(b_v), int(n_adapters))
+    ws_ptr = _ptr(workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().lra_attn_decode(
+        ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(ad), _ptr(q), _ptr(query_adapter),
+        _ptr(seq_query_start), int(q.shape[0]), int(max_queries_per_seq), _ptr(out), ws_ptr,
+        ws_bytes, _stream_ptr(stream)))
+
+
+def lra_attn_prefill(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor],
+                     b_v: Optional[torch.Tensor], n_adapters: int, q: torch.Tensor, seq_index: int,
+                     adapter_index: int, out: torch.Tensor, workspace: Optional[torch.Tensor],
+                     stream=None) -> None:
+    ad = LraAdapters(_ptr(b_k), _ptr(b_v), int(n_adapters))
+    ws_ptr = _ptr(workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().lra_attn_prefill(
+        ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(ad), _ptr(q), int(seq_index),
+        int(adapter_index), int(q.shape[0]), _ptr(out), ws_ptr, ws_bytes, _stream_ptr(stream)))

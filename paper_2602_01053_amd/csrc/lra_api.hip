@@ -1,0 +1,216 @@
+// C ABI of the Flash-LoRA-Attention library: argument checks, launch planning,
+// kernel selection.  Declarations and argument contracts are in lra_attn.h.
+#include <atomic>
+#include <cmath>
+#include <cstdlib>
+
+#include "lra_attn.h"
+#include "lra_common.h"
+
+namespace lra {
+
+std::atomic<int32_t> g_variant{0};
+std::atomic<int32_t> g_split_keys{0};
+
+constexpr int kCUs = 256;  // MI355X
+
+struct Plan {
+  bool mfma;
+  int rows;        // query rows = (queries | new tokens) x Hq
+  int split_keys;  // keys per split
+  int n_splits;    // splits per sequence at max_seq_len
+  size_t off_ml, off_o, off_lr, bytes;
+};
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static lra_status check_common(const lra_shape* sh, const lra_cache* c) {
+  if (!sh || !c) return LRA_ERR_NULL;
+  if (sh->dtype != LRA_BF16 && sh->dtype != LRA_F32) return LRA_ERR_DTYPE;
+  if (sh->n_q_heads < 1 || sh->n_kv_heads < 1 || sh->head_dim < 1 || sh->rank < 1) return LRA_ERR_SHAPE;
+  if (sh->n_q_heads % sh->n_kv_heads) return LRA_ERR_SHAPE;
+  if (!(sh->scale >= 0.f) || std::isinf(sh->scale)) return LRA_ERR_SHAPE;
+  if (sh->head_dim != 64 && sh->head_dim != 128) return LRA_ERR_UNSUPPORTED;
+  if (sh->rank > 64) return LRA_ERR_UNSUPPORTED;
+  if (sh->n_q_heads / sh->n_kv_heads > 16) return LRA_ERR_UNSUPPORTED;
+  if (!c->k_base || !c->v_base || !c->l || !c->seq_lens) return LRA_ERR_NULL;
+  if (c->n_seqs < 1 || c->max_seq_len < 1) return LRA_ERR_SHAPE;
+  if (c->block_size != 0 && c->block_size != 16) return LRA_ERR_UNSUPPORTED;
+  if (c->kv_token_stride < sh->head_dim || c->kv_head_stride < sh->head_dim) return LRA_ERR_SHAPE;
+  if ((c->kv_token_stride | c->kv_head_stride) & 7) return LRA_ERR_SHAPE;
+  if (c->block_size == 0) {
+    if (c->n_seqs != 1) return LRA_ERR_SHAPE;
+  } else {
+    if (!c->block_table) return LRA_ERR_NULL;
+    if (c->num_blocks < 1 || c->max_blocks_per_seq < 1) return LRA_ERR_SHAPE;
+    if (c->kv_block_stride < 16 * sh->head_dim || (c->kv_block_stride & 7)) return LRA_ERR_SHAPE;
+    if (static_cast<int64_t>(c->max_blocks_per_seq) * 16 < c->max_seq_len) return LRA_ERR_SHAPE;
+  }
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(c->k_base) | reinterpret_cast<uintptr_t>(c->v_base) |
+                         reinterpret_cast<uintptr_t>(c->l);
+  if (bits & 15) return LRA_ERR_SHAPE;
+  return LRA_OK;
+}
+
+static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int n_new) {
+  Plan pl{};
+  pl.mfma = false;
+  pl.rows = tokens * sh->n_q_heads;
+  const int tile = 64;
+  int split_keys = g_split_keys.load();
+  if (split_keys <= 0) {
+    // enough waves to cover the chip a few times over, never less than one tile each
+    const int want_waves = kCUs * 8;
+    int ns = (want_waves + pl.rows - 1) / pl.rows;
+    const int max_ns = (c->max_seq_len + tile - 1) / tile;
+    ns = ns < 1 ? 1 : (ns > max_ns ? max_ns : ns);
+    split_keys = (c->max_seq_len + ns - 1) / ns;
+  }
+  split_keys = (split_keys + tile - 1) / tile * tile;
+  pl.split_keys = split_keys;
+  pl.n_splits = (c->max_seq_len + split_keys - 1) / split_keys;
+  const size_t slots = static_cast<size_t>(pl.rows) * pl.n_splits;
+  pl.off_ml = 0;
+  pl.off_o = align_up(slots * 2 * sizeof(float), 256);
+  pl.off_lr = pl.off_o + align_up(slots * sh->head_dim * sizeof(float), 256);
+  pl.bytes = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
+  (void)n_new;
+  return pl;
+}
+
+static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, const lra_adapters* ad,
+                        const Plan& pl, void* workspace) {
+  p.k_base = c->k_base;
+  p.v_base = c->v_base;
+  p.l = c->l;
+  p.b_k = ad->b_k;
+  p.b_v = ad->b_v;
+  p.block_table = c->block_table;
+  p.seq_lens = c->seq_lens;
+  char* ws = static_cast<char*>(workspace);
+  p.part_ml = reinterpret_cast<float*>(ws + pl.off_ml);
+  p.part_o = reinterpret_cast<float*>(ws + pl.off_o);
+  p.part_lr = reinterpret_cast<float*>(ws + pl.off_lr);
+  p.kv_token_stride = c->kv_token_stride;
+  p.kv_head_stride = c->kv_head_stride;
+  p.kv_block_stride = c->kv_block_stride;
+  p.n_q_heads = sh->n_q_heads;
+  p.n_kv_heads = sh->n_kv_heads;
+  p.group = sh->n_q_heads / sh->n_kv_heads;
+  p.head_dim = sh->head_dim;
+  p.rank = sh->rank;
+  p.block_size = c->block_size;
+  p.max_blocks_per_seq = c->max_blocks_per_seq;
+  p.n_seqs = c->n_seqs;
+  p.max_seq_len = c->max_seq_len;
+  p.split_keys = pl.split_keys;
+  p.n_splits = pl.n_splits;
+  p.scale = sh->scale > 0.f ? sh->scale : 1.0f / std::sqrt(static_cast<float>(sh->head_dim));
+}
+
+static lra_status check_workspace(const Plan& pl, void* workspace, size_t workspace_bytes) {
+  if (pl.bytes == 0) return LRA_OK;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < pl.bytes)
+    return LRA_ERR_WORKSPACE;
+  return LRA_OK;
+}
+
+}  // namespace lra
+
+using namespace lra;
+
+extern "C" {
+
+size_t lra_workspace_bytes(const lra_shape* shape, const lra_cache* cache, int32_t n_queries,
+                           int32_t max_queries_per_seq, int32_t n_new) {
+  if (check_common(shape, cache) != LRA_OK) return static_cast<size_t>(-1);
+  if (n_queries < 1 || n_new < 1 || max_queries_per_seq < 1) return static_cast<size_t>(-1);
+  const int tokens = n_new > 1 ? n_new : n_queries;
+  return make_plan(shape, cache, tokens, n_new).bytes;
+}
+
+lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,
+                           const void* q, const int32_t* query_adapter, const int32_t* seq_query_start,
+                           int32_t n_queries, int32_t max_queries_per_seq, void* out, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  lra_status st = check_common(shape, cache);
+  if (st != LRA_OK) return st;
+  if (!adapters || !q || !query_adapter || !seq_query_start || !out) return LRA_ERR_NULL;
+  if (adapters->n_adapters < 1 || n_queries < 1) return LRA_ERR_SHAPE;
+  if (max_queries_per_seq < 1 || max_queries_per_seq > n_queries) return LRA_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out) |
+       reinterpret_cast<uintptr_t>(adapters->b_k) | reinterpret_cast<uintptr_t>(adapters->b_v)) & 15)
+    return LRA_ERR_SHAPE;
+  const Plan pl = make_plan(shape, cache, n_queries, 1);
+  st = check_workspace(pl, workspace, workspace_bytes);
+  if (st != LRA_OK) return st;
+
+  Params p{};
+  fill_params(p, shape, cache, adapters, pl, workspace);
+  p.q = q;
+  p.out = out;
+  p.query_adapter = query_adapter;
+  p.seq_query_start = seq_query_start;
+  p.n_queries = n_queries;
+  p.max_queries_per_seq = max_queries_per_seq;
+  p.n_new = 1;
+  p.is_prefill = 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool bf16 = shape->dtype == LRA_BF16;
+  if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+  if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+  return LRA_OK;
+}
+
+lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,
+                            const void* q, int32_t seq_index, int32_t adapter_index, int32_t n_new,
+                            void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  lra_status st = check_common(shape, cache);
+  if (st != LRA_OK) return st;
+  if (!adapters || !q || !out) return LRA_ERR_NULL;
+  if (adapters->n_adapters < 1) return LRA_ERR_SHAPE;
+  if (seq_index < 0 || seq_index >= cache->n_seqs) return LRA_ERR_SHAPE;
+  if (adapter_index < 0 || adapter_index >= adapters->n_adapters) return LRA_ERR_SHAPE;
+  if (n_new < 1 || n_new > cache->max_seq_len) return LRA_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out) |
+       reinterpret_cast<uintptr_t>(adapters->b_k) | reinterpret_cast<uintptr_t>(adapters->b_v)) & 15)
+    return LRA_ERR_SHAPE;
+  const Plan pl = make_plan(shape, cache, n_new, n_new);
+  st = check_workspace(pl, workspace, workspace_bytes);
+  if (st != LRA_OK) return st;
+
+  Params p{};
+  fill_params(p, shape, cache, adapters, pl, workspace);
+  p.q = q;
+  p.out = out;
+  p.n_queries = 1;
+  p.max_queries_per_seq = 1;
+  p.n_new = n_new;
+  p.is_prefill = 1;
+  p.seq_index = seq_index;
+  p.adapter_index = adapter_index;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool bf16 = shape->dtype == LRA_BF16;
+  if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+  if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+  return LRA_OK;
+}
+
+const char* lra_status_string(lra_status status) {
+  switch (status) {
+    case LRA_OK: return "ok";
+    case LRA_ERR_NULL: return "a required pointer is NULL";
+    case LRA_ERR_SHAPE: return "a size, stride or alignment is out of range or inconsistent";
+    case LRA_ERR_DTYPE: return "unknown dtype";
+    case LRA_ERR_UNSUPPORTED: return "valid arguments outside the supported set";
+    case LRA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LRA_ERR_HIP: return "a HIP launch failed";
+  }
+  return "unknown status";
+}
+
+int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant); }
+
+int32_t lra_set_decode_split_keys(int32_t keys) { return g_split_keys.exchange(keys < 0 ? 0 : keys); }
+
+}  // extern "C"

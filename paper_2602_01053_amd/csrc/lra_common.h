@@ -1,0 +1,94 @@
+// Shared declarations of the Flash-LoRA-Attention HIP library (gfx950 only).
+// Kernel parameter block, element conversion and wavefront (64 lanes) helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lra {
+
+constexpr int kWave = 64;
+
+// One parameter block for every kernel of the library.  Pointers are device
+// pointers; strides are in elements.
+struct Params {
+  const void* q;
+  const void* k_base;
+  const void* v_base;
+  const void* l;
+  const void* b_k;  // may be null: B_K = 0
+  const void* b_v;  // may be null: B_V = 0
+  void* out;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  const int32_t* query_adapter;
+  const int32_t* seq_query_start;
+  // split-KV partial state, fp32 (Alg. 1's m, l, O, O_lr per query row and split)
+  float* part_ml;  // [rows][n_splits][2]
+  float* part_o;   // [rows][n_splits][d]
+  float* part_lr;  // [rows][n_splits][r]
+  int64_t kv_token_stride, kv_head_stride, kv_block_stride;
+  int32_t n_q_heads, n_kv_heads, group, head_dim, rank;
+  int32_t block_size, max_blocks_per_seq, n_seqs, max_seq_len;
+  int32_t n_queries, max_queries_per_seq;
+  int32_t n_new;          // query tokens of the prefill call, 1 in decode
+  int32_t is_prefill;     // 0: decode (rows = queries x Hq), 1: prefill (rows = new tokens x Hq)
+  int32_t seq_index, adapter_index;  // prefill only
+  int32_t split_keys, n_splits;
+  float scale;
+};
+
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) {
+  return __uint_as_float(static_cast<uint32_t>(x) << 16);
+}
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T x);
+template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t x) { return bf16_to_f32(x); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f32_to_bf16(x); }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// Element offset of (sequence t, token j, kv head h) in K_base / V_base.
+__device__ __forceinline__ int64_t kv_offset(const Params& p, int t, int j, int h) {
+  if (p.block_size == 0) return static_cast<int64_t>(j) * p.kv_token_stride + static_cast<int64_t>(h) * p.kv_head_stride;
+  const int blk = p.block_table[static_cast<int64_t>(t) * p.max_blocks_per_seq + (j >> 4)];
+  return static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(h) * p.kv_head_stride +
+         static_cast<int64_t>(j & 15) * p.kv_token_stride;
+}
+
+// Element offset of (sequence t, token j) in L.
+__device__ __forceinline__ int64_t l_offset(const Params& p, int t, int j) {
+  if (p.block_size == 0) return static_cast<int64_t>(j) * p.rank;
+  const int blk = p.block_table[static_cast<int64_t>(t) * p.max_blocks_per_seq + (j >> 4)];
+  return (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank;
+}
+
+// Launchers (defined next to their kernels).
+hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipStream_t s);
+hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s);
+
+}  // namespace lra

@@ -1,0 +1,168 @@
+// Vector-ALU kernels of the Flash-LoRA-Attention library: a straightforward
+// wave-per-row partial-attention kernel for any dtype, and the split merge +
+// epilogue kernel every decode path ends with.
+//
+// Partial kernel: Alg. 1 (LRAgent, Sec. 3.3) for one query row and one range of
+// keys, with the key-side reordering of App. D.1:
+//     s_j  = scale * ( q . K_base[j] + (q B_K^T) . L[j] )
+//     m, l = online softmax statistics,  O += p_j V_base[j],  O_lr += p_j L[j]
+// The epilogue O += O_lr B_V and the division by l (Alg. 1 lines 19-20) happen in
+// the merge kernel, after the per-split states are combined.
+#include "lra_common.h"
+
+namespace lra {
+
+template <typename T>
+__device__ __forceinline__ float dot_row(const T* __restrict__ row, const float* __restrict__ vec, int len) {
+  float acc = 0.f;
+  for (int c = 0; c < len; ++c) acc = fmaf(to_f32<T>(row[c]), vec[c], acc);
+  return acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
+  const int row = blockIdx.x;
+  const int split = blockIdx.y;
+  const int lane = threadIdx.x;
+  const int Hq = p.n_q_heads, d = p.head_dim, r = p.rank;
+  const int tok = row / Hq;
+  const int g = row - tok * Hq;
+  const int h = g / p.group;
+
+  int t, a, n_vis;
+  if (p.is_prefill) {
+    t = p.seq_index;
+    a = p.adapter_index;
+    const int n_t = min(p.seq_lens[t], p.max_seq_len);
+    n_vis = n_t - p.n_new + tok + 1;
+  } else {
+    t = 0;
+    while (t + 1 < p.n_seqs && p.seq_query_start[t + 1] <= tok) ++t;
+    a = p.query_adapter[tok];
+    n_vis = min(p.seq_lens[t], p.max_seq_len);
+  }
+  const int j0 = split * p.split_keys;
+  const int j1 = min(j0 + p.split_keys, n_vis);
+
+  __shared__ float q_s[128];
+  __shared__ float qt_s[64];
+  const T* q = static_cast<const T*>(p.q) + static_cast<int64_t>(row) * d;
+  for (int c = lane; c < d; c += kWave) q_s[c] = to_f32<T>(q[c]);
+  __syncthreads();
+  if (lane < r) {
+    float acc = 0.f;
+    if (p.b_k != nullptr) {
+      const T* bk = static_cast<const T*>(p.b_k) +
+                    (static_cast<int64_t>(a) * r + lane) * (static_cast<int64_t>(p.n_kv_heads) * d) + h * d;
+      acc = dot_row<T>(bk, q_s, d);
+    }
+    qt_s[lane] = acc;
+  }
+  __syncthreads();
+
+  const T* kb = static_cast<const T*>(p.k_base);
+  const T* vb = static_cast<const T*>(p.v_base);
+  const T* lr = static_cast<const T*>(p.l);
+
+  float m = -INFINITY, ell = 0.f, o0 = 0.f, o1 = 0.f, olr = 0.f;
+  for (int jb = j0; jb < j1; jb += kWave) {
+    const int j = jb + lane;
+    const bool valid = j < j1;
+    float s = -INFINITY;
+    if (valid) {
+      const float sk = dot_row<T>(kb + kv_offset(p, t, j, h), q_s, d);
+      const float sl = dot_row<T>(lr + l_offset(p, t, j), qt_s, r);
+      s = p.scale * (sk + sl);
+    }
+    const float m_new = fmaxf(m, wave_max(s));  // finite: lane 0 is always valid here
+    const float alpha = (m == -INFINITY) ? 0.f : expf(m - m_new);
+    const float pj = valid ? expf(s - m_new) : 0.f;
+    ell = alpha * ell + wave_sum(pj);
+    o0 *= alpha;
+    o1 *= alpha;
+    olr *= alpha;
+    const int cnt = min(kWave, j1 - jb);
+    for (int jj = 0; jj < cnt; ++jj) {
+      const float pjj = __shfl(pj, jj, kWave);
+      const T* v = vb + kv_offset(p, t, jb + jj, h);
+      if (lane < d) o0 = fmaf(pjj, to_f32<T>(v[lane]), o0);
+      if (lane + kWave < d) o1 = fmaf(pjj, to_f32<T>(v[lane + kWave]), o1);
+      if (lane < r) olr = fmaf(pjj, to_f32<T>(lr[l_offset(p, t, jb + jj) + lane]), olr);
+    }
+    m = m_new;
+  }
+
+  const int64_t slot = static_cast<int64_t>(row) * p.n_splits + split;
+  if (lane == 0) {
+    p.part_ml[slot * 2 + 0] = m;
+    p.part_ml[slot * 2 + 1] = ell;
+  }
+  if (lane < d) p.part_o[slot * d + lane] = o0;
+  if (lane + kWave < d) p.part_o[slot * d + lane + kWave] = o1;
+  if (lane < r) p.part_lr[slot * r + lane] = olr;
+}
+
+// Flash-decoding merge of the per-split states followed by Alg. 1's epilogue:
+//   M = max_s m_s, w_s = exp(m_s - M), l = sum w_s l_s, O = sum w_s O_s,
+//   O_lr = sum w_s O_lr,s ;  out = (O + O_lr B_V) / l.
+// Splits are visited in index order, so the result does not depend on which
+// workgroup finished first.
+template <typename T>
+__global__ __launch_bounds__(128) void merge_kernel(Params p) {
+  const int row = blockIdx.x;
+  const int c = threadIdx.x;
+  const int Hq = p.n_q_heads, d = p.head_dim, r = p.rank;
+  const int tok = row / Hq;
+  const int g = row - tok * Hq;
+  const int h = g / p.group;
+  const int a = p.is_prefill ? p.adapter_index : p.query_adapter[tok];
+  const int ns = p.n_splits;
+  const float* ml = p.part_ml + static_cast<int64_t>(row) * ns * 2;
+
+  float big = -INFINITY;
+  for (int s = 0; s < ns; ++s)
+    if (ml[2 * s + 1] > 0.f) big = fmaxf(big, ml[2 * s]);
+
+  __shared__ float olr_s[64];
+  float ell = 0.f, o = 0.f, olr = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float ls = ml[2 * s + 1];
+    if (!(ls > 0.f)) continue;
+    const float w = expf(ml[2 * s] - big);
+    const int64_t slot = static_cast<int64_t>(row) * ns + s;
+    ell = fmaf(w, ls, ell);
+    if (c < d) o = fmaf(w, p.part_o[slot * d + c], o);
+    if (c < r) olr = fmaf(w, p.part_lr[slot * r + c], olr);
+  }
+  if (c < r) olr_s[c] = olr;
+  __syncthreads();
+  if (c < d) {
+    if (p.b_v != nullptr) {
+      const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * (static_cast<int64_t>(p.n_kv_heads) * d) +
+                    h * d + c;
+      const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * d;
+      for (int rho = 0; rho < r; ++rho) o = fmaf(olr_s[rho], to_f32<T>(bv[rho * ld]), o);
+    }
+    static_cast<T*>(p.out)[static_cast<int64_t>(row) * d + c] = from_f32<T>(o / ell);
+  }
+}
+
+hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipStream_t s) {
+  dim3 grid(rows, p.n_splits), block(kWave);
+  if (is_bf16)
+    hipLaunchKernelGGL(generic_partial_kernel<bf16_t>, grid, block, 0, s, p);
+  else
+    hipLaunchKernelGGL(generic_partial_kernel<float>, grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s) {
+  dim3 grid(rows), block(128);
+  if (is_bf16)
+    hipLaunchKernelGGL(merge_kernel<bf16_t>, grid, block, 0, s, p);
+  else
+    hipLaunchKernelGGL(merge_kernel<float>, grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace lra

@@ -1,0 +1,124 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_01053_amd as lra
+from paper_2602_01053_amd.binding import LraAdapters, LraCache, LraShape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(lra.binding.LIB_PATH):
+        from paper_2602_01053_amd.build import build_library
+        build_library()
+    return lra.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "lra_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(lra_[a-z_]+)\s*\(", text))
+    assert {"lra_attn_decode", "lra_attn_prefill", "lra_workspace_bytes"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in lra_attn.h but not exported"
+    assert declared == set(lra.binding.EXPORTS)
+
+
+def test_status_strings(lib):
+    seen = {lra.lra_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and lra.lra_status_string(0) == "ok"
+    assert lra.lra_status_string(99) == "unknown status"
+
+
+FAKE = 0x1000  # never dereferenced: every case below fails validation first
+
+
+def _good():
+    sh = LraShape(32, 8, 128, 16, 0, 0.0)
+    c = LraCache(FAKE, FAKE, FAKE, 1024, 128, 0, 0, 0, 0, 1, None, FAKE, 8192)
+    ad = LraAdapters(FAKE, FAKE, 4)
+    return sh, c, ad
+
+
+def _decode(lib, sh, c, ad, q=FAKE, qa=FAKE, sqs=FAKE, n_queries=4, mq=4, out=FAKE, ws=None, ws_bytes=0):
+    return lib.lra_attn_decode(ctypes.byref(sh), ctypes.byref(c), ctypes.byref(ad), q, qa, sqs,
+                               n_queries, mq, out, ws, ws_bytes, None)
+
+
+def _prefill(lib, sh, c, ad, q=FAKE, seq=0, a=0, n_new=16, out=FAKE, ws=None, ws_bytes=0):
+    return lib.lra_attn_prefill(ctypes.byref(sh), ctypes.byref(c), ctypes.byref(ad), q, seq, a, n_new,
+                                out, ws, ws_bytes, None)
+
+
+def test_rejects_bad_arguments_before_launch(lib):
+    NULL, SHAPE, DTYPE, UNSUP, WS = 1, 2, 3, 4, 5
+    sh, c, ad = _good()
+    assert lib.lra_attn_decode(None, ctypes.byref(c), ctypes.byref(ad), FAKE, FAKE, FAKE, 4, 4, FAKE,
+                               None, 0, None) == NULL
+    assert _decode(lib, sh, c, ad, q=None) == NULL
+    assert _decode(lib, sh, c, ad, out=None) == NULL
+    assert _decode(lib, sh, c, ad, qa=None) == NULL
+
+    def mutated(**kw):
+        s, cc, a = _good()
+        for k, v in kw.items():
+            for obj in (s, cc, a):
+                if hasattr(obj, k):
+                    setattr(obj, k, v)
+        return s, cc, a
+
+    assert _decode(lib, *mutated(dtype=7)) == DTYPE
+    assert _decode(lib, *mutated(n_q_heads=30)) == SHAPE          # not a multiple of Hkv
+    assert _decode(lib, *mutated(head_dim=96)) == UNSUP
+    assert _decode(lib, *mutated(rank=65)) == UNSUP
+    assert _decode(lib, *mutated(rank=0)) == SHAPE
+    assert _decode(lib, *mutated(n_q_heads=32, n_kv_heads=1)) == UNSUP   # group of 32
+    assert _decode(lib, *mutated(block_size=32)) == UNSUP
+    assert _decode(lib, *mutated(kv_token_stride=1023)) == SHAPE
+    assert _decode(lib, *mutated(kv_head_stride=64)) == SHAPE
+    assert _decode(lib, *mutated(k_base=None)) == NULL
+    assert _decode(lib, *mutated(seq_lens=None)) == NULL
+    assert _decode(lib, *mutated(l=FAKE + 2)) == SHAPE            # misaligned
+    assert _decode(lib, *mutated(max_seq_len=0)) == SHAPE
+    assert _decode(lib, *mutated(n_seqs=2)) == SHAPE              # contiguous holds one sequence
+    assert _decode(lib, *mutated(n_adapters=0)) == SHAPE
+    assert _decode(lib, *mutated(scale=float("nan"))) == SHAPE
+    assert _decode(lib, *mutated(block_size=16, n_seqs=2)) == NULL   # paged without a block table
+    assert _decode(lib, *mutated(block_size=16, block_table=FAKE, num_blocks=600, kv_block_stride=16384,
+                                 max_blocks_per_seq=8)) == SHAPE  # table row shorter than max_seq_len
+    assert _decode(lib, sh, c, ad, n_queries=0) == SHAPE
+    assert _decode(lib, sh, c, ad, mq=5) == SHAPE
+    # good arguments but no / small / misaligned workspace: refused, nothing launched
+    assert _decode(lib, sh, c, ad) == WS
+    need = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 4, 1)
+    assert 0 < need < (1 << 40)
+    assert _decode(lib, sh, c, ad, ws=0x10000, ws_bytes=need - 1) == WS
+    assert _decode(lib, sh, c, ad, ws=0x10010, ws_bytes=need) == WS
+
+    assert _prefill(lib, sh, c, ad, seq=1) == SHAPE
+    assert _prefill(lib, sh, c, ad, a=4) == SHAPE
+    assert _prefill(lib, sh, c, ad, n_new=0) == SHAPE
+    assert _prefill(lib, sh, c, ad, n_new=8193) == SHAPE
+    assert _prefill(lib, sh, c, ad, q=None) == NULL
+    bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 1)
+    assert bad == ctypes.c_size_t(-1).value
+
+
+def test_tuning_hooks_round_trip(lib):
+    old = lra.lra_set_decode_split_keys(512)
+    assert lra.lra_set_decode_split_keys(old) == 512
+    old = lra.lra_set_kernel_variant(1)
+    assert lra.lra_set_kernel_variant(old) == 1
+
+
+def test_binding_fails_loudly_without_library(monkeypatch):
+    monkeypatch.setattr(lra.binding, "_lib", None)
+    monkeypatch.setattr(lra.binding, "LIB_PATH", "/nonexistent/liblra_attn.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        lra.binding.load_library()

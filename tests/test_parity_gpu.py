@@ -1,0 +1,185 @@
+"""Parity of the HIP library against the fp64 oracle, through the C ABI.
+
+Bar (stated for bf16 inputs with fp32 accumulation): relative L2 <= 5e-3 over the
+whole output AND over every single query / new token, max-abs <= 2e-2.  fp32
+inputs are additionally held to relative L2 <= 2e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_01053_amd as lra
+from paper_2602_01053_amd import workloads as W
+from tests.harness import (MAX_ABS_TOL, REL_L2_TOL, DeviceWorkload, errors, oracle_decode,
+                           oracle_prefill, run_decode, run_prefill)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(params=[0, 1], ids=["auto", "valu"])
+def variant(request):
+    old = lra.lra_set_kernel_variant(request.param)
+    yield request.param
+    lra.lra_set_kernel_variant(old)
+
+
+def _gate(got, ref, fp32=False, label=""):
+    rel, mx = errors(got, ref)
+    print(f"{label}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL, (label, rel, mx)
+    if fp32:
+        assert rel <= 2e-5, (label, rel)
+
+
+# ---- the five named configurations at full size -----------------------------
+def test_config1_tiny_decode_fp32(variant):
+    w = W.config(1)
+    _gate(run_decode(w, DEV), oracle_decode(w), fp32=True, label=w.name)
+
+
+@pytest.mark.parametrize("head_major", [False, True], ids=["token_major", "head_major"])
+def test_config2_llama_decode(variant, head_major):
+    w = W.config(2)
+    _gate(run_decode(w, DEV, head_major), oracle_decode(w), label=w.name)
+
+
+def test_config4_long_multi_agent_decode(variant):
+    w = W.config(4)
+    _gate(run_decode(w, DEV), oracle_decode(w), label=w.name)
+
+
+def test_config5_ragged_paged_decode():
+    w = W.config(5)
+    print("sum of lengths", sum(w.seq_lens), flush=True)
+    _gate(run_decode(w, DEV), oracle_decode(w), label=w.name)
+
+
+def test_config3_prefill_sampled_rows():
+    """Full-size causal prefill in the launch configuration the benchmark times;
+    the oracle evaluates a spread of new-token rows (rows are independent): the
+    first and last rows, rows around every 128-row tile edge, and random ones."""
+    w = W.config(3)
+    got = run_prefill(w, DEV)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(3)
+    rows = sorted(set([0, 1, 2, 31, 32, 63, 64, 127, 128, 129, 255, 256, 1023, 1024, 2046, 2047]
+                      + rng.integers(0, w.n_new, 48).tolist()))
+    ref = oracle_prefill(w, rows=rows)
+    _gate(got[rows], ref, label=w.name)
+
+
+# ---- small shapes: several tiles, ragged tails, odd groups ------------------
+DECODE_CASES = [
+    # n, agents, Hq, Hkv, d, r
+    (1, 1, 4, 4, 64, 8),
+    (17, 3, 8, 2, 128, 16),
+    (63, 2, 4, 1, 64, 4),
+    (64, 5, 8, 8, 128, 1),
+    (65, 1, 14, 2, 128, 32),     # group of 7
+    (257, 4, 32, 8, 128, 16),
+    (1000, 7, 16, 4, 64, 24),
+    (1031, 9, 16, 1, 128, 64),   # group of 16, > 8 agents
+    (4099, 17, 4, 2, 128, 48),
+]
+
+
+@pytest.mark.parametrize("case", DECODE_CASES, ids=lambda c: "n%d_a%d_hq%d_hkv%d_d%d_r%d" % c)
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32], ids=["bf16", "fp32"])
+def test_decode_small_shapes(variant, case, dtype):
+    n, agents, hq, hkv, d, r = case
+    w = W.make_contiguous("small", "decode", seed=1000 + n, dtype=dtype, n_agents=agents,
+                          n_q_heads=hq, n_kv_heads=hkv, head_dim=d, rank=r, n=n, d_model=None,
+                          b_std=0.05)
+    _gate(run_decode(w, DEV), oracle_decode(w), fp32=dtype == torch.float32, label=str(case))
+
+
+PREFILL_CASES = [
+    # n, n_new, Hq, Hkv, d, r
+    (1, 1, 4, 4, 64, 8),
+    (40, 40, 4, 2, 128, 16),       # no old context
+    (130, 3, 8, 2, 128, 16),
+    (200, 129, 4, 4, 64, 8),
+    (513, 257, 14, 2, 128, 32),
+    (1500, 300, 8, 1, 128, 64),
+]
+
+
+@pytest.mark.parametrize("case", PREFILL_CASES, ids=lambda c: "n%d_new%d_hq%d_hkv%d_d%d_r%d" % c)
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32], ids=["bf16", "fp32"])
+def test_prefill_small_shapes(variant, case, dtype):
+    n, n_new, hq, hkv, d, r = case
+    w = W.make_contiguous("small", "prefill", seed=2000 + n, dtype=dtype, n_agents=1, n_q_heads=hq,
+                          n_kv_heads=hkv, head_dim=d, rank=r, n=n, n_new=n_new, d_model=None,
+                          b_std=0.05)
+    _gate(run_prefill(w, DEV), oracle_prefill(w), fp32=dtype == torch.float32, label=str(case))
+
+
+def test_paged_small_ragged_distinct_adapters(variant):
+    """Lengths that end inside a block, one adapter per query, NaN-poisoned free
+    slots: nothing outside a sequence's own tokens may reach its output."""
+    w = W.make_paged("paged_small", seed=77, seq_lens=[1, 15, 16, 17, 250, 1027], agents_per_seq=3,
+                     n_adapters=0, n_q_heads=14, n_kv_heads=2, head_dim=128, rank=32, d_model=None,
+                     distinct_adapter_per_query=True, b_std=0.05)
+    _gate(run_decode(w, DEV), oracle_decode(w), label=w.name)
+
+
+def test_uneven_queries_per_sequence(variant):
+    """Sequences with 0, 1 and many queries in one call."""
+    w = W.make_paged("uneven", seed=78, seq_lens=[300, 77, 129, 512], agents_per_seq=2, n_adapters=3,
+                     n_q_heads=8, n_kv_heads=2, head_dim=64, rank=16, d_model=None, b_std=0.05)
+    w.seq_query_start = torch.tensor([0, 5, 5, 6, 8], dtype=torch.int32)   # 5, 0, 1, 2 queries
+    _gate(run_decode(w, DEV), oracle_decode(w), label=w.name)
+
+
+def test_null_adapters_reduce_to_plain_attention(variant):
+    """b_k = b_v = NULL is the fully shared cache: equals the oracle with B = 0."""
+    w = W.config(2, shrink=8)
+    dw = DeviceWorkload(w, DEV)
+    dw.alloc_workspace()
+    dw.b_k = None
+    dw.b_v = None
+    dw.decode()
+    torch.cuda.synchronize()
+    w.b_k.zero_()
+    w.b_v.zero_()
+    _gate(dw.out.to(torch.float64).cpu().numpy(), oracle_decode(w), label="null adapters")
+
+
+def test_deterministic_and_inputs_untouched(variant):
+    w = W.config(2, shrink=4)
+    dw = DeviceWorkload(w, DEV)
+    dw.alloc_workspace()
+    dw.decode()
+    torch.cuda.synchronize()
+    first = dw.out.clone()
+    dw.workspace.fill_(0xFF)
+    dw.out.zero_()
+    dw.decode()
+    torch.cuda.synchronize()
+    assert torch.equal(first.view(torch.int16), dw.out.view(torch.int16))
+    assert torch.equal(dw.k_base.cpu(), w.k_base) and torch.equal(dw.l.cpu(), w.l)
+    assert torch.equal(dw.q.cpu(), w.q) and torch.equal(dw.b_v.cpu(), w.b_v)
+
+
+def test_split_size_does_not_change_result_beyond_rounding():
+    w = W.config(2, shrink=4)
+    ref = oracle_decode(w)
+    try:
+        for keys in (64, 192, 1024, 1 << 20):
+            lra.lra_set_decode_split_keys(keys)
+            _gate(run_decode(w, DEV), ref, label=f"split_keys={keys}")
+    finally:
+        lra.lra_set_decode_split_keys(0)
+
+
+def test_runs_on_a_side_stream():
+    w = W.config(2, shrink=8)
+    dw = DeviceWorkload(w, DEV)
+    dw.alloc_workspace()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        dw.decode(s)
+    s.synchronize()
+    _gate(dw.out.to(torch.float64).cpu().numpy(), oracle_decode(w), label="side stream")

@@ -1,0 +1,56 @@
+"""The generators are seeded, chunk-stable and produce the documented layouts."""
+import torch
+
+from paper_2602_01053_amd import workloads as W
+
+
+def test_config_shapes_and_byte_counts():
+    w = W.config(1)
+    assert w.dtype == torch.float32 and w.q.shape == (2, 4, 64) and w.l.shape == (512, 8)
+    assert w.scale == 0.125
+    w = W.config(2)
+    assert w.k_base.shape == (8192, 8, 128) and w.b_k.shape == (4, 16, 1024)
+    assert w.algorithmic_bytes() == 33554432 + 262144 + 262144 + 32768 + 32768
+    assert w.visible_pairs() == 4 * 32 * 8192
+    assert w.algorithmic_flops() == 4 * 144 * 4 * 32 * 8192 + 4 * 128 * 128 * 16
+    assert abs(float(w.l.float().std()) - 1.0) < 0.05          # L = X A is unit variance
+    assert abs(float(w.b_k.float().std()) - 0.02) < 0.002
+
+
+def test_prefill_pair_count_matches_closed_form():
+    w = W.config(3, shrink=16)
+    lc, n = w.n_new, w.seq_lens[0]
+    assert (lc, n) == (128, 1152)
+    assert w.visible_pairs() == 32 * (lc * (n - lc) + lc * (lc + 1) // 2)
+
+
+def test_seeded_and_repeatable():
+    a, b = W.config(2, shrink=16), W.config(2, shrink=16)
+    for name in ("q", "k_base", "v_base", "l", "b_k", "b_v"):
+        assert torch.equal(getattr(a, name), getattr(b, name))
+    c = W.config(4, shrink=16)
+    assert not torch.equal(a.q, c.q[:4])
+
+
+def test_paged_layout_scatter():
+    w = W.make_paged("t", seed=9, dtype=torch.float32, seq_lens=[5, 40, 16], agents_per_seq=2,
+                     n_adapters=2, n_q_heads=4, n_kv_heads=2, head_dim=8, rank=4, d_model=None)
+    assert w.k_base.shape == (w.num_blocks, 2, 16, 8) and w.l.shape == (w.num_blocks, 16, 4)
+    bt = w.block_table
+    used = bt[bt >= 0]
+    assert used.numel() == 1 + 3 + 1 and used.unique().numel() == used.numel()
+    # owned slots are finite, everything else is NaN poison
+    owned = torch.zeros(w.num_blocks, 16, dtype=torch.bool)
+    for t, n in enumerate(w.seq_lens):
+        for j in range(n):
+            owned[bt[t, j // 16], j % 16] = True
+    assert torch.isfinite(w.l[owned]).all() and torch.isnan(w.l[~owned]).all()
+    assert torch.isfinite(w.k_base.permute(0, 2, 1, 3)[owned]).all()
+    assert torch.isnan(w.v_base.permute(0, 2, 1, 3)[~owned]).all()
+    assert w.seq_query_start.tolist() == [0, 2, 4, 6] and w.query_seq().tolist() == [0, 0, 1, 1, 2, 2]
+
+
+def test_config5_lengths():
+    lens = W.ragged_lengths(W.BASE_SEED + 5, 16, 4096, 65536)
+    assert len(lens) == 16 and min(lens) >= 4096 and max(lens) <= 65536
+    assert any(n % 16 for n in lens)
