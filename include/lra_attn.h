@@ -130,10 +130,11 @@ typedef struct {
 } lra_adapters;
 
 /*
- * Bytes of DEVICE workspace that lra_attn_decode (n_new == 1) or lra_attn_prefill
- * needs for these arguments; 0 is a valid answer.  Returns (size_t)-1 when the
- * arguments themselves would be rejected.  max_queries_per_seq as for decode
- * (pass 1 for prefill).
+ * Bytes of DEVICE workspace a call needs; 0 is a valid answer.
+ *   n_new == 0 : for lra_attn_decode with these n_queries / max_queries_per_seq
+ *   n_new >= 1 : for lra_attn_prefill with this n_new (the two query counts are ignored)
+ * Returns (size_t)-1 when the arguments themselves would be rejected.  The answer
+ * depends on the tuning hooks below: set them before asking.
  */
 size_t lra_workspace_bytes(const lra_shape* shape, const lra_cache* cache, int32_t n_queries,
                            int32_t max_queries_per_seq, int32_t n_new);

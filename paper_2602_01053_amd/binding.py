@@ -128,7 +128,8 @@ def make_cache(k_base: torch.Tensor, v_base: torch.Tensor, l: torch.Tensor, seq_
 
 
 def lra_workspace_bytes(shape: LraShape, cache: LraCache, n_queries: int,
-                        max_queries_per_seq: int = 1, n_new: int = 1) -> int:
+                        max_queries_per_seq: int = 1, n_new: int = 0) -> int:
+    """n_new = 0: workspace of a decode call; n_new >= 1: of a prefill call."""
     n = load_library().lra_workspace_bytes(ctypes.byref(shape), ctypes.byref(cache), int(n_queries),
                                            int(max_queries_per_seq), int(n_new))
     if n == ctypes.c_size_t(-1).value:

@@ -11,6 +11,7 @@ namespace lra {
 
 std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
+std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
 
 constexpr int kCUs = 256;  // MI355X
 
@@ -19,6 +20,7 @@ struct Plan {
   int rows;        // query rows = (queries | new tokens) x Hq
   int split_keys;  // keys per split
   int n_splits;    // splits per sequence at max_seq_len
+  int group_pad, row_tiles, row_groups;  // MFMA decode row packing
   size_t off_ml, off_o, off_lr, bytes;
 };
 
@@ -52,19 +54,34 @@ static lra_status check_common(const lra_shape* sh, const lra_cache* c) {
   return LRA_OK;
 }
 
-static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int n_new) {
+static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_queries_per_seq, bool prefill) {
   Plan pl{};
-  pl.mfma = false;
+  const int G = sh->n_q_heads / sh->n_kv_heads;
+  pl.mfma = !prefill && sh->dtype == LRA_BF16 && g_variant.load() == 0;
   pl.rows = tokens * sh->n_q_heads;
-  const int tile = 64;
+  pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
+  pl.row_tiles = 1;
+  pl.row_groups = 1;
+  int tile = 64;       // keys per wave-step of the vector-ALU kernel
+  int64_t work;        // units that want a wave (vector-ALU) or a workgroup share (MFMA)
+  int want;
+  if (pl.mfma) {
+    const int rows_needed = max_queries_per_seq * pl.group_pad;
+    pl.row_tiles = decode_mfma_row_tiles(rows_needed);
+    pl.row_groups = (rows_needed + 16 * pl.row_tiles - 1) / (16 * pl.row_tiles);
+    tile = 128;        // 4 waves x 32 keys
+    work = static_cast<int64_t>(c->n_seqs) * sh->n_kv_heads * pl.row_groups;
+    want = kCUs * 2;
+  } else {
+    work = pl.rows;
+    want = kCUs * 8;
+  }
   int split_keys = g_split_keys.load();
   if (split_keys <= 0) {
-    // enough waves to cover the chip a few times over, never less than one tile each
-    const int want_waves = kCUs * 8;
-    int ns = (want_waves + pl.rows - 1) / pl.rows;
-    const int max_ns = (c->max_seq_len + tile - 1) / tile;
+    int64_t ns = (want + work - 1) / work;
+    const int64_t max_ns = (c->max_seq_len + tile - 1) / tile;
     ns = ns < 1 ? 1 : (ns > max_ns ? max_ns : ns);
-    split_keys = (c->max_seq_len + ns - 1) / ns;
+    split_keys = static_cast<int>((c->max_seq_len + ns - 1) / ns);
   }
   split_keys = (split_keys + tile - 1) / tile * tile;
   pl.split_keys = split_keys;
@@ -74,7 +91,6 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int n
   pl.off_o = align_up(slots * 2 * sizeof(float), 256);
   pl.off_lr = pl.off_o + align_up(slots * sh->head_dim * sizeof(float), 256);
   pl.bytes = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
-  (void)n_new;
   return pl;
 }
 
@@ -103,6 +119,8 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.max_blocks_per_seq = c->max_blocks_per_seq;
   p.n_seqs = c->n_seqs;
   p.max_seq_len = c->max_seq_len;
+  p.group_pad = pl.group_pad;
+  p.row_groups = pl.row_groups;
   p.split_keys = pl.split_keys;
   p.n_splits = pl.n_splits;
   p.scale = sh->scale > 0.f ? sh->scale : 1.0f / std::sqrt(static_cast<float>(sh->head_dim));
@@ -124,9 +142,11 @@ extern "C" {
 size_t lra_workspace_bytes(const lra_shape* shape, const lra_cache* cache, int32_t n_queries,
                            int32_t max_queries_per_seq, int32_t n_new) {
   if (check_common(shape, cache) != LRA_OK) return static_cast<size_t>(-1);
-  if (n_queries < 1 || n_new < 1 || max_queries_per_seq < 1) return static_cast<size_t>(-1);
-  const int tokens = n_new > 1 ? n_new : n_queries;
-  return make_plan(shape, cache, tokens, n_new).bytes;
+  if (n_new < 0 || n_new > cache->max_seq_len) return static_cast<size_t>(-1);
+  if (n_new == 0 && (n_queries < 1 || max_queries_per_seq < 1 || max_queries_per_seq > n_queries))
+    return static_cast<size_t>(-1);
+  const bool prefill = n_new > 0;
+  return make_plan(shape, cache, prefill ? n_new : n_queries, prefill ? 1 : max_queries_per_seq, prefill).bytes;
 }
 
 lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,
@@ -141,7 +161,7 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out) |
        reinterpret_cast<uintptr_t>(adapters->b_k) | reinterpret_cast<uintptr_t>(adapters->b_v)) & 15)
     return LRA_ERR_SHAPE;
-  const Plan pl = make_plan(shape, cache, n_queries, 1);
+  const Plan pl = make_plan(shape, cache, n_queries, max_queries_per_seq, false);
   st = check_workspace(pl, workspace, workspace_bytes);
   if (st != LRA_OK) return st;
 
@@ -157,7 +177,11 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   p.is_prefill = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
-  if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+  if (pl.mfma) {
+    if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
+  } else {
+    if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+  }
   if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
 }
@@ -175,7 +199,7 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out) |
        reinterpret_cast<uintptr_t>(adapters->b_k) | reinterpret_cast<uintptr_t>(adapters->b_v)) & 15)
     return LRA_ERR_SHAPE;
-  const Plan pl = make_plan(shape, cache, n_new, n_new);
+  const Plan pl = make_plan(shape, cache, n_new, 1, true);
   st = check_workspace(pl, workspace, workspace_bytes);
   if (st != LRA_OK) return st;
 

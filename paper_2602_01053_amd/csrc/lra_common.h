@@ -29,6 +29,8 @@ struct Params {
   float* part_lr;  // [rows][n_splits][r]
   int64_t kv_token_stride, kv_head_stride, kv_block_stride;
   int32_t n_q_heads, n_kv_heads, group, head_dim, rank;
+  int32_t group_pad;   // rows reserved per agent in the MFMA row tiles: 4, 8 or 16 (>= group)
+  int32_t row_groups;  // workgroups along the query-row axis per (sequence, kv head)
   int32_t block_size, max_blocks_per_seq, n_seqs, max_seq_len;
   int32_t n_queries, max_queries_per_seq;
   int32_t n_new;          // query tokens of the prefill call, 1 in decode
@@ -90,5 +92,7 @@ __device__ __forceinline__ int64_t l_offset(const Params& p, int t, int j) {
 // Launchers (defined next to their kernels).
 hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipStream_t s);
 hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s);
+int decode_mfma_row_tiles(int rows_needed);
+hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s);
 
 }  // namespace lra

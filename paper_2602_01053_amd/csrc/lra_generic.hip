@@ -115,9 +115,19 @@ __global__ __launch_bounds__(128) void merge_kernel(Params p) {
   const int tok = row / Hq;
   const int g = row - tok * Hq;
   const int h = g / p.group;
-  const int a = p.is_prefill ? p.adapter_index : p.query_adapter[tok];
-  const int ns = p.n_splits;
-  const float* ml = p.part_ml + static_cast<int64_t>(row) * ns * 2;
+  int a, n_vis;
+  if (p.is_prefill) {
+    a = p.adapter_index;
+    n_vis = min(p.seq_lens[p.seq_index], p.max_seq_len) - p.n_new + tok + 1;
+  } else {
+    int t = 0;
+    while (t + 1 < p.n_seqs && p.seq_query_start[t + 1] <= tok) ++t;
+    a = p.query_adapter[tok];
+    n_vis = min(p.seq_lens[t], p.max_seq_len);
+  }
+  // splits that start at or past this row's last visible key were never written
+  const int ns = min(p.n_splits, (n_vis + p.split_keys - 1) / p.split_keys);
+  const float* ml = p.part_ml + static_cast<int64_t>(row) * p.n_splits * 2;
 
   float big = -INFINITY;
   for (int s = 0; s < ns; ++s)
@@ -129,7 +139,7 @@ __global__ __launch_bounds__(128) void merge_kernel(Params p) {
     const float ls = ml[2 * s + 1];
     if (!(ls > 0.f)) continue;
     const float w = expf(ml[2 * s] - big);
-    const int64_t slot = static_cast<int64_t>(row) * ns + s;
+    const int64_t slot = static_cast<int64_t>(row) * p.n_splits + s;
     ell = fmaf(w, ls, ell);
     if (c < d) o = fmaf(w, p.part_o[slot * d + c], o);
     if (c < r) olr = fmaf(w, p.part_lr[slot * r + c], olr);

@@ -39,7 +39,7 @@ class DeviceWorkload:
     def alloc_workspace(self):
         w = self.w
         nbytes = lra.lra_workspace_bytes(self.shape, self.cache, w.n_queries,
-                                         self.max_queries_per_seq, w.n_new)
+                                         self.max_queries_per_seq, w.n_new if w.kind == "prefill" else 0)
         self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.q.device)
         return nbytes
 

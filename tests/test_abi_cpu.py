@@ -96,7 +96,7 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _decode(lib, sh, c, ad, mq=5) == SHAPE
     # good arguments but no / small / misaligned workspace: refused, nothing launched
     assert _decode(lib, sh, c, ad) == WS
-    need = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 4, 1)
+    need = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 4, 0)
     assert 0 < need < (1 << 40)
     assert _decode(lib, sh, c, ad, ws=0x10000, ws_bytes=need - 1) == WS
     assert _decode(lib, sh, c, ad, ws=0x10010, ws_bytes=need) == WS
@@ -106,7 +106,9 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _prefill(lib, sh, c, ad, n_new=0) == SHAPE
     assert _prefill(lib, sh, c, ad, n_new=8193) == SHAPE
     assert _prefill(lib, sh, c, ad, q=None) == NULL
-    bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 1)
+    bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 0)
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) > 0
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 5, 0) == ctypes.c_size_t(-1).value
     assert bad == ctypes.c_size_t(-1).value
 
 
