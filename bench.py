@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the Flash-LoRA-Attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one lra_attn_decode call (key-streaming kernel + split merge/epilogue)
+on the Llama-3-8B-shaped 4-agent decode workload: n = 8192 cached tokens, 32 q /
+8 kv heads, d = 128, r = 16, bf16.  Inputs are resident in HBM before the timed
+region.  The working set (34 MB) would fit the 256 MB memory-side cache, so the
+timed steps cycle through enough distinct copies of (K_base, V_base, L) that
+every step streams its cache from HBM ("cold"); the same-buffer ("hot") figure
+is reported next to it.  value = algorithmic bytes / step time.
+
+The JSON line also carries
+  roofline      the key-streaming kernel alone, timed with HIP events on its stream,
+  prefill       the causal prefill workload (2048 new tokens after 16384), TFLOP/s,
+  cpu_baseline  the fp64 oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+COLD_BYTES = 600e6             # cycle through more than twice the 256 MB memory-side cache
+
+
+def _hip():
+    lib = ctypes.CDLL("libamdhip64.so")
+    lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    lib.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    return lib
+
+
+class KernelTimer:
+    """HIP event pairs recorded by the library around its dominant kernel."""
+
+    def __init__(self, lra, n):
+        self.lra = lra
+        self.hip = _hip()
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def arm(self, i):
+        a, b = self.pairs[i]
+        self.lra.lra_set_profile_events(a, b)
+
+    def disarm(self):
+        self.lra.lra_set_profile_events(None, None)
+
+    def mean_ms(self):
+        tot = 0.0
+        for a, b in self.pairs:
+            ms = ctypes.c_float()
+            self.hip.hipEventSynchronize(b)
+            assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+            tot += ms.value
+        return tot / len(self.pairs)
+
+    def close(self):
+        self.disarm()
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def _load_traffic(name):
+    """HBM bytes per launch from committed rocprofv3 --pmc summaries, if any."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name)
+    except (OSError, ValueError):
+        return None
+
+
+def bench_decode(args, torch, lra, workloads):
+    from paper_2602_01053_amd.runner import DeviceWorkload
+    dev = torch.device("cuda:0")
+    w = workloads.config(2)
+    alg_bytes = w.algorithmic_bytes()
+    cache_bytes = 2 * w.k_base.numel() * 2 + w.l.numel() * 2
+    n_copies = int(math.ceil(COLD_BYTES / cache_bytes)) + 1
+    base = DeviceWorkload(w, dev)
+    base.alloc_workspace()
+    copies = [base]
+    for _ in range(n_copies - 1):
+        c = DeviceWorkload.__new__(DeviceWorkload)
+        c.__dict__.update(base.__dict__)
+        c.k_base, c.v_base, c.l = base.k_base.clone(), base.v_base.clone(), base.l.clone()
+        c.cache = lra.make_cache(c.k_base, c.v_base, c.l, c.seq_lens, max(w.seq_lens), None)
+        copies.append(c)
+
+    def run(n_steps, cold, timer=None):
+        for i in range(n_steps):
+            if timer is not None:
+                timer.arm(i)
+            copies[i % n_copies if cold else 0].decode()
+
+    def timed(n_steps, cold):
+        run(args.warmup, cold)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(n_steps, cold)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n_steps
+
+    sec_cold = timed(args.steps, True)
+    sec_hot = timed(args.steps, False)
+    # second pass over the same timed region with event pairs around the streaming kernel
+    n_ev = min(args.steps, 200)
+    out = {}
+    for label, cold in (("cold", True), ("hot", False)):
+        timer = KernelTimer(lra, n_ev)
+        run(args.warmup, cold)
+        torch.cuda.synchronize()
+        run(n_ev, cold, timer)
+        torch.cuda.synchronize()
+        out[label] = timer.mean_ms() * 1e-3
+        timer.close()
+    return w, alg_bytes, sec_cold, sec_hot, out, n_copies
+
+
+def bench_prefill(args, torch, lra, workloads):
+    from paper_2602_01053_amd.runner import DeviceWorkload
+    dev = torch.device("cuda:0")
+    w = workloads.config(3)
+    flops = w.algorithmic_flops()
+    dw = DeviceWorkload(w, dev)
+    dw.alloc_workspace()
+    steps = max(3, min(args.steps // 50, 20))
+    for _ in range(2):
+        dw.prefill()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        dw.prefill()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    timer = KernelTimer(lra, steps)
+    for i in range(steps):
+        timer.arm(i)
+        dw.prefill()
+    torch.cuda.synchronize()
+    ksec = timer.mean_ms() * 1e-3
+    timer.close()
+    return w, flops, sec, ksec, steps
+
+
+def cpu_baseline(workloads):
+    """The oracle as it stands, on the host cores, on the decode workload."""
+    import numpy as np  # noqa: F401
+    from tests.harness import oracle_decode
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    w = workloads.config(2)
+    best = float("inf")
+    reps = 0
+    t_all = time.perf_counter()
+    while reps < 3 or (time.perf_counter() - t_all < 10.0 and reps < 20):
+        t0 = time.perf_counter()
+        oracle_decode(w)
+        best = min(best, time.perf_counter() - t0)
+        reps += 1
+    return {"value": round(w.algorithmic_bytes() / best / 1e9, 4), "unit": "GB/s", "cores": int(cores),
+            "kind": "oracle", "seconds": round(best, 4),
+            "sample": f"the full decode workload ({w.name}: 4 queries x 32 heads x 8192 keys), "
+                      f"fp64 numpy oracle, best of {reps} runs"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_01053_amd as lra
+    from paper_2602_01053_amd import workloads
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    lra.load_library()
+
+    w, alg_bytes, sec_cold, sec_hot, ksec, n_copies = bench_decode(args, torch, lra, workloads)
+    gbs = alg_bytes / sec_cold / 1e9
+    k_gbs = alg_bytes / ksec["cold"] / 1e9
+    line = {
+        "metric": "LoRA-attn decode HBM GB/s + prefill TFLOP/s (frac of peak), Llama-3-8B shape",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec_cold * 1e3, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "call": "lra_attn_decode", "agents": 4, "n": 8192, "q_heads": 32,
+                   "kv_heads": 8, "head_dim": 128, "rank": 16, "algorithmic_bytes": alg_bytes,
+                   "cache_protocol": f"cold: {n_copies} rotating copies of K_base/V_base/L"},
+        "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": round(k_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(k_gbs / HBM_PEAK_GBS, 4),
+                     "kernel_us": round(ksec["cold"] * 1e6, 3), "traffic": _load_traffic("decode_cfg2")},
+        "hot_cache": {"value": round(alg_bytes / sec_hot / 1e9, 1), "unit": "GB/s",
+                      "ms_per_step": round(sec_hot * 1e3, 6), "kernel_us": round(ksec["hot"] * 1e6, 3),
+                      "note": "same buffers every step: served largely by the memory-side cache"},
+    }
+    if not args.no_prefill:
+        wp, flops, psec, pksec, psteps = bench_prefill(args, torch, lra, workloads)
+        tf = flops / psec / 1e12
+        ktf = flops / pksec / 1e12
+        line["prefill"] = {
+            "workload": wp.name, "call": "lra_attn_prefill", "steps": psteps,
+            "value": round(tf, 2), "unit": "TFLOP/s", "ms_per_step": round(psec * 1e3, 4),
+            "algorithmic_flops": flops, "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+            "roofline": {"bound": "mfma", "achieved": round(ktf, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": round(ktf / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "kernel_ms": round(pksec * 1e3, 4), "traffic": _load_traffic("prefill_cfg3")}}
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(workloads)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -197,6 +197,21 @@ int32_t lra_set_kernel_variant(int32_t variant);
  */
 int32_t lra_set_decode_split_keys(int32_t keys);
 
+/*
+ * Tuning hook: how many 32-key steps ahead the MFMA decode kernel keeps its global
+ * loads in registers (1 or 2; other values are clamped).  Returns the previous value.
+ */
+int32_t lra_set_decode_prefetch(int32_t steps);
+
+/*
+ * Measurement hook.  While both are non-NULL, every later call records
+ * start_event (a hipEvent_t) on its stream right before its dominant kernel (the
+ * key-streaming kernel, not the merge/epilogue) and stop_event right after it,
+ * so a benchmark can time that kernel alone with HIP events.  The events belong
+ * to the caller.  Pass NULL, NULL to switch off (the default).
+ */
+void lra_set_profile_events(void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,6 +13,8 @@ std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
 std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
 
+std::atomic<void*> g_ev_start{nullptr}, g_ev_stop{nullptr};
+
 constexpr int kCUs = 256;  // MI355X
 
 struct Plan {
@@ -57,7 +59,9 @@ static lra_status check_common(const lra_shape* sh, const lra_cache* c) {
 static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_queries_per_seq, bool prefill) {
   Plan pl{};
   const int G = sh->n_q_heads / sh->n_kv_heads;
-  pl.mfma = !prefill && sh->dtype == LRA_BF16 && g_variant.load() == 0;
+  // The MFMA decode kernel moves L in 16-byte pieces: ranks that are not a
+  // multiple of 8 take the vector-ALU kernels.
+  pl.mfma = !prefill && sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
   pl.rows = tokens * sh->n_q_heads;
   pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
   pl.row_tiles = 1;
@@ -84,6 +88,12 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     split_keys = static_cast<int>((c->max_seq_len + ns - 1) / ns);
   }
   split_keys = (split_keys + tile - 1) / tile * tile;
+  if (pl.mfma && c->block_size == 0) {
+    // the kernel addresses one split of a contiguous cache with 32-bit byte offsets
+    const int64_t cap = ((int64_t{1} << 31) - 4096) / (c->kv_token_stride * 2) / tile * tile;
+    if (cap < tile) pl.mfma = false;
+    else if (split_keys > cap) split_keys = static_cast<int>(cap);
+  }
   pl.split_keys = split_keys;
   pl.n_splits = (c->max_seq_len + split_keys - 1) / split_keys;
   const size_t slots = static_cast<size_t>(pl.rows) * pl.n_splits;
@@ -177,11 +187,14 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   p.is_prefill = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
+  hipEvent_t ev0 = static_cast<hipEvent_t>(g_ev_start.load()), ev1 = static_cast<hipEvent_t>(g_ev_stop.load());
+  if (ev0) (void)hipEventRecord(ev0, s);
   if (pl.mfma) {
     if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
   } else {
     if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   }
+  if (ev1) (void)hipEventRecord(ev1, s);
   if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
 }
@@ -215,7 +228,10 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   p.adapter_index = adapter_index;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
+  hipEvent_t ev0 = static_cast<hipEvent_t>(g_ev_start.load()), ev1 = static_cast<hipEvent_t>(g_ev_stop.load());
+  if (ev0) (void)hipEventRecord(ev0, s);
   if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+  if (ev1) (void)hipEventRecord(ev1, s);
   if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
 }
@@ -236,5 +252,12 @@ const char* lra_status_string(lra_status status) {
 int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant); }
 
 int32_t lra_set_decode_split_keys(int32_t keys) { return g_split_keys.exchange(keys < 0 ? 0 : keys); }
+
+int32_t lra_set_decode_prefetch(int32_t steps) { return g_prefetch.exchange(steps >= 2 ? 2 : 1); }
+
+void lra_set_profile_events(void* start_event, void* stop_event) {
+  g_ev_start.store(start_event);
+  g_ev_stop.store(stop_event);
+}
 
 }  // extern "C"

@@ -4,48 +4,54 @@
 // query rows that share that stream: every agent decoding on the sequence times
 // the q heads of the GQA group.  Those rows form the 16-wide N dimension of
 // v_mfma_f32_16x16x32_bf16, so K_base, V_base and L are read from HBM once for
-// all agents (LRAgent Sec. 3.2, one base cache and one LR cache for the system).
+// all agents (LRAgent Sec. 3.2: one base cache and one LR cache for the system).
 //
 // Per 32-key step (Alg. 1 lines 9-17 with the App. D.1 key-side reordering):
 //   S^T[key][row]  = K_base[key][:] . Q[row][:]  +  L[key][:] . Qt[row][:]     (MFMA)
 //   online softmax along keys (per row = per lane column)
 //   O^T[d][row]   += V_base^T[d][key] . P^T[key][row]                          (MFMA)
 //   Olr^T[p][row] += L^T[p][key]      . P^T[key][row]                          (MFMA)
-// with Qt = Q B_K^T computed once per workgroup in the prologue (MFMA).
-// Computing S transposed makes the C-layout of the score tile coincide with the
-// B-operand layout of the second product, so P never moves between lanes.
+// with Qt = Q B_K^T computed once per workgroup in the prologue (MFMA, shared
+// through LDS).  Computing S transposed makes the C-layout of the score tile
+// coincide with the B-operand layout of the second product, so P never moves
+// between lanes.
 //
-// Data path: coalesced 16-byte global loads into registers (one or two steps
-// ahead), a swizzled copy into wave-private LDS, ds_read_b128 for the K/L
-// A-operands and ds_read_b64_tr_b16 for the transposed V/L A-operands.  The
-// waves of a workgroup own disjoint key ranges and never synchronise inside the
-// loop; their states are merged through LDS at the end (flash-decoding rule) and
-// one partial (m, l, O, O_lr) per workgroup goes to the workspace.
+// Data path: buffer_load ... lds (16 bytes per lane, straight from HBM into
+// wave-private LDS, no staging registers).  Each lane fetches the 16-byte chunk
+// that belongs at ITS LDS slot under an XOR swizzle, so the later ds_read_b128
+// (K operand), ds_read_b64 (L operand) and ds_read_b64_tr_b16 (transposed V and
+// L operands) avoid bank conflicts.  Keys past the end of a wave's range are
+// outside the buffer resource: the hardware returns zeros for them and touches
+// no memory, so there is no tail branch on the load side.  A wave holds one
+// tile; latency is hidden by the eight waves a CU holds, not by a software
+// pipeline inside the wave.  The waves of a workgroup own disjoint key ranges
+// and never synchronise inside the loop; their states are merged through LDS at
+// the end (flash-decoding rule) and one partial (m, l, O, O_lr) per workgroup
+// goes to the workspace.
 #include "lra_common.h"
 
 namespace lra {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+#define LDS_AS(T, p) ((__attribute__((address_space(3))) T*)(p))
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__device__ __forceinline__ uint4 lds_read16(const unsigned char* base, int byte_off) {
-  return *reinterpret_cast<const uint4*>(base + byte_off);
-}
-
-__device__ __forceinline__ void lds_write16(unsigned char* base, int byte_off, uint4 v) {
-  *reinterpret_cast<uint4*>(base + byte_off) = v;
-}
+__device__ __forceinline__ uint4 lds_read16(const unsigned char* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ uint2 lds_read8(const unsigned char* p) { return *reinterpret_cast<const uint2*>(p); }
 
 // ds_read_b64_tr_b16: inside every group of 16 lanes, lane i receives for e = 0..3
 // element (i % 4) of the 8 bytes addressed by lane 4e + i/4.
-__device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* base, int byte_off) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, base + byte_off));
+__device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS(s16x4, p));
 }
 
 __device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
@@ -53,34 +59,88 @@ __device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  return static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {  // one v_cvt_pk_bf16_f32
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int D, int RT, int RP, int NW, int PF>
-__global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(Params p) {
-  constexpr int KS = D / 32;    // MFMA k-steps over the head dimension
-  constexpr int RKS = RP / 32;  // MFMA k-steps over the (padded) rank
-  constexpr int DB = D / 16;    // 16-wide output blocks over d
-  constexpr int RB = RP / 16;   // 16-wide output blocks over the rank
-  constexpr int KCH = D / 8;    // 16-byte chunks per K/V row
-  constexpr int RCH = RP / 8;   // 16-byte chunks per L row in LDS
-  constexpr int KVL = D / 16;   // wave-wide 16-byte loads per 32-key K (or V) tile
-  constexpr int LL = RP / 16;   // wave-wide 16-byte loads per 32-key L tile
+// Exchange between the four 16-lane groups of a wave (lanes l, l^16, l^32, l^48).
+// v_permlane16_swap exchanges the odd 16-lane rows of its first register with the
+// even rows of its second, v_permlane32_swap the upper half of the first with the
+// lower half of the second.  Started from two copies of one value, the two
+// registers afterwards hold, in every lane, the value and its partner's value.
+// Written as inline assembly because the compiler's builtin for these
+// instructions treats its two results as one and the same value.
+__device__ __forceinline__ void permlane16_swap(float& x, float& y) {
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+}
+__device__ __forceinline__ void permlane32_swap(float& x, float& y) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+}
+
+__device__ __forceinline__ float max_over_lane_groups(float v) {
+  float x = v, y = v;
+  permlane16_swap(x, y);
+  x = y = fmaxf(x, y);
+  permlane32_swap(x, y);
+  return fmaxf(x, y);
+}
+
+__device__ __forceinline__ float sum_over_lane_groups(float v) {
+  float x = v, y = v;
+  permlane16_swap(x, y);
+  x = y = x + y;
+  permlane32_swap(x, y);
+  return x + y;
+}
+
+// Raw buffer resource over [base, base + bytes): loads past the end return zero
+// and touch no memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t rs, uint32_t voff, uint32_t soff) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// 16 bytes per lane from the buffer straight into LDS at lds + lane*16.
+__device__ __forceinline__ void buf_load16_to_lds(__amdgpu_buffer_rsrc_t rs, unsigned char* lds, uint32_t voff,
+                                                  uint32_t soff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LDS_AS(void, lds), 16, voff, soff, 0, 0);
+}
+
+constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel builds
+
+template <int D, int RT, int RP, bool PAGED>
+__global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
+  constexpr int NW = 4;
+  constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
+  constexpr int RKS = RP / 32;     // MFMA k-steps over the (padded) rank
+  constexpr int DB = D / 16;       // 16-wide output blocks over d
+  constexpr int RB = RP / 16;      // 16-wide output blocks over the rank
+  constexpr int KCH = D / 8;       // 16-byte chunks per K/V row
+  constexpr int RCH = RP / 8;      // 16-byte chunks per L row in LDS
+  constexpr int KROWS = 64 / KCH;  // K/V rows one wave-wide load moves
+  constexpr int KVL = 32 / KROWS;  // wave-wide loads per 32-key K (or V) tile
+  constexpr int LROWS = 64 / RCH;
+  constexpr int LL = 32 / LROWS;
   constexpr int KV_BYTES = 32 * D * 2;
   constexpr int L_BYTES = 32 * RP * 2;
   constexpr int WAVE_BYTES = 2 * KV_BYTES + L_BYTES;
-  constexpr int QT_BYTES = RT * 16 * RP * 2;
   constexpr int NACC = RT * (DB + RB) * 4 + RT;
   constexpr int MERGE_SLOT = NACC * 64 * 4;
-  constexpr int STAGE_TOTAL = NW * WAVE_BYTES + QT_BYTES;
+  constexpr int STAGE_TOTAL = NW * WAVE_BYTES;
   constexpr int MERGE_TOTAL = (NW / 2) * MERGE_SLOT;
   constexpr int SMEM = STAGE_TOTAL > MERGE_TOTAL ? STAGE_TOTAL : MERGE_TOTAL;
   constexpr int LSW_SHIFT = (RP == 32) ? 1 : 0;
+  constexpr int QT_BYTES = RT * RKS * 1024;
 
   __shared__ __align__(16) unsigned char smem[SMEM];
+  __shared__ __align__(16) unsigned char qt_lds[QT_BYTES];
   __shared__ float m_sh[NW][RT][16];
 
   const int lane = threadIdx.x & 63;
@@ -101,153 +161,195 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(Params p) {
   const int j1 = min(j0 + p.split_keys, n_t);
   const int kpw = p.split_keys / NW;  // multiple of 32
   const int jw0 = j0 + wave * kpw;
-  const int jw1 = min(jw0 + kpw, j1);
+  const int jw1 = max(jw0, min(jw0 + kpw, j1));  // == jw0 for a wave without keys
 
   unsigned char* ks_lds = smem + wave * WAVE_BYTES;
   unsigned char* vs_lds = ks_lds + KV_BYTES;
   unsigned char* ls_lds = vs_lds + KV_BYTES;
-  unsigned char* qt_lds = smem + NW * WAVE_BYTES;
 
   const bf16_t* kb = static_cast<const bf16_t*>(p.k_base);
   const bf16_t* vb = static_cast<const bf16_t*>(p.v_base);
   const bf16_t* lr = static_cast<const bf16_t*>(p.l);
-  const int32_t* bt = p.block_table + static_cast<int64_t>(t) * p.max_blocks_per_seq;
-  const bool paged = p.block_size != 0;
-  const bool l_fast = (r & 7) == 0;
+  const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
+  const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
 
-  struct Stage {
-    uint4 k[KVL], v[KVL], l[LL];
-  };
-
-  // ---- global -> register loads of one 32-key step starting at token j ----
-  auto load_stage = [&](Stage& st, int j) {
-    int blk0 = 0, blk1 = 0;
-    if (paged) {
-      blk0 = bt[j >> 4];
-      blk1 = (j + 16 < n_t) ? bt[(j >> 4) + 1] : blk0;
-    }
-#pragma unroll
-    for (int i = 0; i < KVL; ++i) {
-      const int f = i * 64 + lane;
-      const int key = f / KCH, ch = f % KCH;
-      const int tok = min(j + key, n_t - 1);
-      int64_t off;
-      if (paged) {
-        const int blk = ((tok >> 4) == (j >> 4)) ? blk0 : blk1;
-        off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(tok & 15) * p.kv_token_stride;
-      } else {
-        off = static_cast<int64_t>(tok) * p.kv_token_stride;
-      }
-      off += static_cast<int64_t>(h) * p.kv_head_stride + ch * 8;
-      st.k[i] = *reinterpret_cast<const uint4*>(kb + off);
-      st.v[i] = *reinterpret_cast<const uint4*>(vb + off);
-    }
-#pragma unroll
-    for (int i = 0; i < LL; ++i) {
-      const int f = i * 64 + lane;
-      const int key = f / RCH, ch = f % RCH;
-      const int tok = min(j + key, n_t - 1);
-      int64_t row;
-      if (paged) {
-        const int blk = ((tok >> 4) == (j >> 4)) ? blk0 : blk1;
-        row = static_cast<int64_t>(blk) * 16 + (tok & 15);
-      } else {
-        row = tok;
-      }
-      const bf16_t* src = lr + row * r + ch * 8;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (l_fast) {
-        if (ch * 8 < r) val = *reinterpret_cast<const uint4*>(src);
-      } else {
-        uint32_t w[4] = {0, 0, 0, 0};
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (ch * 8 + e < r) w[e >> 1] |= static_cast<uint32_t>(src[e]) << ((e & 1) * 16);
-        val = make_uint4(w[0], w[1], w[2], w[3]);
-      }
-      st.l[i] = val;
-    }
-  };
-
-  // ---- registers -> wave-private LDS, swizzled on 16-byte chunks ----
-  auto store_stage = [&](const Stage& st) {
-#pragma unroll
-    for (int i = 0; i < KVL; ++i) {
-      const int f = i * 64 + lane;
-      const int key = f / KCH, ch = f % KCH;
-      lds_write16(ks_lds, key * (D * 2) + ((ch ^ (key & 7)) << 4), st.k[i]);
-      lds_write16(vs_lds, key * (D * 2) + ((ch ^ ((key & 3) << 1)) << 4), st.v[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < LL; ++i) {
-      const int f = i * 64 + lane;
-      const int key = f / RCH, ch = f % RCH;
-      lds_write16(ls_lds, key * (RP * 2) + ((ch ^ ((key >> LSW_SHIFT) & (RCH - 1))) << 4), st.l[i]);
-    }
-  };
-
-  Stage st0, st1;
-  const bool has_keys = jw0 < jw1;
-  if (has_keys) load_stage(st0, jw0);
-  if (PF == 2 && jw0 + 32 < jw1) load_stage(st1, jw0 + 32);
-
-  // ---- prologue: Q rows as MFMA operands, Qt = Q B_K^T through LDS ----
-  bf16x8 qb[RT][KS];   // B operand of S^T: lane (row ln, k = 32ks + 8lg + e)
-  bf16x8 qtb[RT][RKS];
-  const bf16_t* qg = static_cast<const bf16_t*>(p.q);
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int R = row0 + rt * 16 + ln;
-    const int slot = R / GP, gg = R - slot * GP;
-    const bool valid = slot < n_q && gg < G;
-    const bf16_t* qrow = qg + (static_cast<int64_t>(q_begin + slot) * p.n_q_heads + h * G + gg) * D;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (valid) v = *reinterpret_cast<const uint4*>(qrow + ks * 32 + lg * 8);
-      qb[rt][ks] = as_bf16x8(v);
-    }
-  }
+  // ===================== per-lane constants of the tile traffic =====================
+  // global -> LDS: lane l of load i lands at LDS row i*ROWS + l/CH, physical chunk l%CH,
+  // and therefore fetches logical chunk (l%CH) ^ swizzle(row).
+  uint32_t k_voff[2], v_voff, l_voff;
   {
-    const int S = 16 / GP;  // agent slots per 16-row tile
-    const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
-    const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
+    const int rr = lane / KCH, pc = lane % KCH;
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      for (int idx = wave; idx < S * RB; idx += NW) {
-        const int si = idx / RB, cb = idx - si * RB;
-        const int slot = (row0 + rt * 16) / GP + si;
-        const int rho = cb * 16 + ln;
-        const bool live = bkg != nullptr && slot < n_q && rho < r;
-        int a = 0;
-        if (slot < n_q) a = p.query_adapter[q_begin + slot];
-        const bf16_t* brow = bkg + (static_cast<int64_t>(a) * r + rho) * ldb + h * D + lg * 8;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          uint4 v = make_uint4(0, 0, 0, 0);
-          if (live) v = *reinterpret_cast<const uint4*>(brow + ks * 32);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qb[rt][ks], as_bf16x8(v), acc, 0, 0, 0);
-        }
-        // C layout: rows 4lg + j, column rho.  Rows 4lg..4lg+3 belong to slot (4lg)/GP.
-        if ((4 * lg) / GP == si) {
-          bf16_t* dst = reinterpret_cast<bf16_t*>(qt_lds) + (rt * 16 + 4 * lg) * RP + rho;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) dst[j * RP] = f32_to_bf16(acc[j]);
-        }
-      }
+    for (int par = 0; par < 2; ++par) {
+      const int row = par * KROWS + rr;  // the parity of the load index matters only when KROWS == 4
+      k_voff[par] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ (row & 7)) << 4);
     }
+    v_voff = static_cast<uint32_t>(rr) * ts2 + ((pc ^ ((rr & 3) << 1)) << 4);
+    const int lrow = lane / RCH, lpc = lane % RCH;
+    const int lch = lpc ^ ((lrow >> LSW_SHIFT) & (RCH - 1));
+    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * r2 + (lch << 4) : kOob;
   }
-  __syncthreads();
+  // LDS -> MFMA operands (byte offsets inside the tile regions)
+  int k_rd[2];  // K rows as A operand of S^T: [ks & 1], plus (ks >> 1)*128 + tt*16*2D
+  {
+    const int x = (lg ^ (ln & 3)) | (ln & 4);
+    k_rd[0] = ln * (2 * D) + (x << 4);
+    k_rd[1] = k_rd[0] ^ 64;
+  }
+  const int ka = 4 * lg + (ln >> 2);  // row (within a 16-key tile) this lane addresses in transpose reads
+  int v_rd[4];                        // V^T as A operand: [b & 3], plus (b >> 2)*128 + tt*16*2D
+  {
+    const int u = ka & 3, c0 = (ln & 3) >> 1, sub = (ln & 1) * 8;
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
+    for (int q = 0; q < 4; ++q) v_rd[q] = ka * (2 * D) + ((2 * (q ^ u) + c0) << 4) + sub;
+  }
+  int l_rd[RKS][2];  // L rows as A operand of S^T: two 8-byte pieces per k-step
+  int lt_rd[RB];     // L^T as A operand of Olr^T
+  {
+    const int swz_s = (ln >> LSW_SHIFT) & (RCH - 1);
 #pragma unroll
     for (int ks = 0; ks < RKS; ++ks)
-      qtb[rt][ks] = as_bf16x8(lds_read16(qt_lds, ((rt * 16 + ln) * RP + ks * 32 + lg * 8) * 2));
+#pragma unroll
+      for (int pc = 0; pc < 2; ++pc) {
+        const int ch = 4 * ks + 2 * pc + (lg >> 1);
+        l_rd[ks][pc] = ln * (2 * RP) + ((ch ^ swz_s) << 4) + (lg & 1) * 8;
+      }
+    const int swz_t = (ka >> LSW_SHIFT) & (RCH - 1);
+#pragma unroll
+    for (int b = 0; b < RB; ++b) {
+      const int ch = 2 * b + ((ln & 3) >> 1);
+      lt_rd[b] = ka * (2 * RP) + ((ch ^ swz_t) << 4) + (ln & 1) * 8;
+    }
+  }
 
-  // ---- main loop ----
+  // Contiguous cache: one resource per wave covering exactly its keys [jw0, jw1).
+  __amdgpu_buffer_rsrc_t rs_k, rs_v, rs_l;
+  if (!PAGED) {
+    const int nk = jw1 - jw0;
+    const int64_t base = static_cast<int64_t>(h) * p.kv_head_stride + static_cast<int64_t>(jw0) * p.kv_token_stride;
+    const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
+    rs_k = make_rsrc(kb + base, bytes);
+    rs_v = make_rsrc(vb + base, bytes);
+    rs_l = make_rsrc(lr + static_cast<int64_t>(jw0) * r, static_cast<uint32_t>(nk) * r2);
+  }
+  const int32_t* bt = p.block_table + static_cast<int64_t>(t) * p.max_blocks_per_seq;
+
+  // ---- HBM -> LDS for the 32-key step starting at token j ----
+  auto issue_tile = [&](int j) {
+    if (PAGED) {
+      const int nb_last = (n_t - 1) >> 4;
+      const int64_t hoff = static_cast<int64_t>(h) * p.kv_head_stride;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int jb = j + 16 * half;
+        const int blk = bt[min(jb >> 4, nb_last)];
+        const int nv = max(0, min(16, jw1 - jb));  // slots of this block inside the wave's range
+        const uint32_t kv_bytes = nv > 0 ? static_cast<uint32_t>(nv - 1) * ts2 + D * 2 : 0u;
+        const __amdgpu_buffer_rsrc_t pk = make_rsrc(kb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
+        const __amdgpu_buffer_rsrc_t pv = make_rsrc(vb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
+        const __amdgpu_buffer_rsrc_t pl =
+            make_rsrc(lr + static_cast<int64_t>(blk) * 16 * r, static_cast<uint32_t>(nv) * r2);
+#pragma unroll
+        for (int i = 0; i < KVL / 2; ++i) {
+          const int ii = half * (KVL / 2) + i;
+          buf_load16_to_lds(pk, ks_lds + ii * 1024, k_voff[KROWS == 4 ? (ii & 1) : 0], i * KROWS * ts2);
+          buf_load16_to_lds(pv, vs_lds + ii * 1024, v_voff, i * KROWS * ts2);
+        }
+#pragma unroll
+        for (int i = 0; i < LL / 2; ++i) {
+          const int ii = half * (LL / 2) + i;
+          buf_load16_to_lds(pl, ls_lds + ii * 1024, l_voff, i * LROWS * r2);
+        }
+      }
+    } else {
+      const uint32_t s0 = static_cast<uint32_t>(j - jw0);
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) {
+        buf_load16_to_lds(rs_k, ks_lds + i * 1024, k_voff[KROWS == 4 ? (i & 1) : 0], (s0 + i * KROWS) * ts2);
+        buf_load16_to_lds(rs_v, vs_lds + i * 1024, v_voff, (s0 + i * KROWS) * ts2);
+      }
+#pragma unroll
+      for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * r2);
+    }
+  };
+
+  // The first tile is on its way before the prologue touches Q and B_K.
+  if (jw0 < jw1) issue_tile(jw0);
+
+  // ===================== prologue: Q operands and Qt = Q B_K^T =====================
+  // qb[rt][ks]: lane (row ln of tile rt, k = 32ks + 8lg + e), e = 0..7.  Used as the
+  // B operand of S^T and as the B operand of Qt^T = B_K Q^T below.
+  bf16x8 qb[RT][KS];
+  {
+    const __amdgpu_buffer_rsrc_t rs_q =
+        make_rsrc(static_cast<const bf16_t*>(p.q) + static_cast<int64_t>(q_begin) * p.n_q_heads * D,
+                  static_cast<uint32_t>(n_q) * p.n_q_heads * D * 2);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int R = row0 + rt * 16 + ln;
+      const int slot = R / GP, gg = R - slot * GP;
+      const bool valid = slot < n_q && gg < G;
+      const uint32_t off = valid ? static_cast<uint32_t>((slot * p.n_q_heads + h * G + gg) * D * 2 + lg * 16) : kOob;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qb[rt][ks] = as_bf16x8(buf_load16(rs_q, off, ks * 64));
+    }
+  }
+  // Qt^T block (rho block cb, tile rt) = B_K^a[16cb..16cb+15][:] . Q_tile^T : C layout
+  // lane (rho = 16cb + 4lg + j, row ln).  Rows of a tile belong to 16/GP agents; each
+  // agent's product is kept only in its own rows (lanes).  The items are spread over
+  // the waves and exchanged through LDS in operand-ready form: operand (rt, ks') of
+  // lane l is the 16 bytes at ((rt*RKS + ks')*64 + l)*16, elements
+  // e -> rho = 32ks' + 16(e/4) + 4lg + e%4.  The L operand below uses the same order.
+  bf16x8 qtb[RT][RKS];
+  {
+    const int S = 16 / GP;         // agent slots per 16-row tile
+    const int ncb = (r + 15) >> 4;
+    const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
+    const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      for (int idx = wave; idx < S * ncb; idx += NW) {
+        const int si = idx / ncb, cb = idx - si * ncb;
+        const int slot = (row0 + rt * 16) / GP + si;
+        int a = 0;
+        uint32_t bytes = 0;
+        if (bkg != nullptr && slot < n_q) {
+          a = p.query_adapter[q_begin + slot];
+          bytes = static_cast<uint32_t>((r - 1) * ldb + D) * 2u;
+        }
+        const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(bkg + static_cast<int64_t>(a) * r * ldb + h * D, bytes);
+        const uint32_t off = static_cast<uint32_t>((cb * 16 + ln) * ldb * 2 + lg * 16);
+        uint4 bt4[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bt4[ks] = buf_load16(rs_b, off, ks * 64);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bt4[ks]), qb[rt][ks], acc, 0, 0, 0);
+        if (ln / GP == si) {
+          unsigned char* dst = qt_lds + ((rt * RKS + (cb >> 1)) * 64 + lane) * 16;
+          const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
+          if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
+            *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
+          else
+            *reinterpret_cast<uint2*>(dst + (cb & 1) * 8) = pk;
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int ks = 0; ks < RKS; ++ks) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);  // k-steps entirely beyond the rank were never written
+        if (ks * 32 < r) v = lds_read16(qt_lds + ((rt * RKS + ks) * 64 + lane) * 16);
+        qtb[rt][ks] = as_bf16x8(v);
+      }
+  }
+
+  // ===================== main loop =====================
   f32x4 o_acc[RT][DB], lr_acc[RT][RB];
-  float m_run[RT], l_run[RT];
+  float m_run[RT], l_run[RT];  // m_run in base-2 units of the scaled score
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     m_run[rt] = -INFINITY;
@@ -257,127 +359,100 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(Params p) {
 #pragma unroll
     for (int b = 0; b < RB; ++b) lr_acc[rt][b] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  const float sc = p.scale * 1.44269504088896340736f;  // scores in base-2 units
+  const float sc = p.scale * 1.44269504088896340736f;
 
-  auto compute_step = [&](int j) {
-    // S^T for two 16-key tiles
+  for (int j = jw0; j < jw1; j += 32) {
+    // the first LDS read below waits for the whole tile (LDS reads are ordered
+    // after outstanding buffer_load ... lds)
     f32x4 s[2][RT];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int key = tt * 16 + ln;
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) s[tt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = as_bf16x8(lds_read16(ks_lds, key * (D * 2) + (((ks * 4 + lg) ^ (key & 7)) << 4)));
+        const bf16x8 a = as_bf16x8(lds_read16(ks_lds + k_rd[ks & 1] + (ks >> 1) * 128 + tt * 32 * D));
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
           s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[rt][ks], s[tt][rt], 0, 0, 0);
       }
 #pragma unroll
       for (int ks = 0; ks < RKS; ++ks) {
-        const bf16x8 a = as_bf16x8(
-            lds_read16(ls_lds, key * (RP * 2) + (((ks * 4 + lg) ^ ((key >> LSW_SHIFT) & (RCH - 1))) << 4)));
+        const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 32 * RP);
+        const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 32 * RP);
+        const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
           s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qtb[rt][ks], s[tt][rt], 0, 0, 0);
       }
     }
     // online softmax; element (tt, jj) of this lane is key j + 16tt + 4lg + jj of row ln
+    const bool tail = j + 32 > jw1;
     bf16x8 pb[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      float mx = -INFINITY;
+      if (tail) {
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
+        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const int key = j + tt * 16 + lg * 4 + jj;
-          const float v = key < n_t ? s[tt][rt][jj] * sc : -INFINITY;
-          s[tt][rt][jj] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[rt], mx);
-      const float alpha = fast_exp2(m_run[rt] - m_new);
-      m_run[rt] = m_new;
+          for (int jj = 0; jj < 4; ++jj)
+            if (j + tt * 16 + lg * 4 + jj >= jw1) s[tt][rt][jj] = -INFINITY;
+      }
+      float mx = fmaxf(fmaxf(fmaxf(s[0][rt][0], s[0][rt][1]), fmaxf(s[0][rt][2], s[0][rt][3])),
+                       fmaxf(fmaxf(s[1][rt][0], s[1][rt][1]), fmaxf(s[1][rt][2], s[1][rt][3])));
+      mx = max_over_lane_groups(mx) * sc;  // sc > 0
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[rt]) != 0) {
+        const float m_new = fmaxf(m_run[rt], mx);
+        const float alpha = fast_exp2(m_run[rt] - m_new);
+        m_run[rt] = m_new;
+        l_run[rt] *= alpha;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) o_acc[rt][b] *= alpha;
+#pragma unroll
+        for (int b = 0; b < RB; ++b) lr_acc[rt][b] *= alpha;
+      }
+      const float nm = -m_run[rt];
       float pe[8];
       float sum = 0.f;
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-          const float e = fast_exp2(s[tt][rt][jj] - m_new);
+          const float e = fast_exp2(fmaf(s[tt][rt][jj], sc, nm));
           pe[tt * 4 + jj] = e;
           sum += e;
         }
-      l_run[rt] = l_run[rt] * alpha + sum;
-      uint4 pk = make_uint4(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]), pack_bf16x2(pe[4], pe[5]),
-                            pack_bf16x2(pe[6], pe[7]));
-      pb[rt] = as_bf16x8(pk);
-#pragma unroll
-      for (int b = 0; b < DB; ++b) o_acc[rt][b] *= alpha;
-#pragma unroll
-      for (int b = 0; b < RB; ++b) lr_acc[rt][b] *= alpha;
+      l_run[rt] += sum;
+      pb[rt] = as_bf16x8(make_uint4(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]), pack_bf16x2(pe[4], pe[5]),
+                                    pack_bf16x2(pe[6], pe[7])));
     }
     // O^T += V^T P^T ; Olr^T += L^T P^T
-    const int ka = 4 * lg + (ln >> 2);  // key (within a 16-key tile) this lane addresses for the transpose read
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
-      const int ch = 2 * b + ((ln & 3) >> 1);
-      const int sub = (ln & 1) * 8;
-      const s16x4 lo = lds_read_tr16(vs_lds, ka * (D * 2) + ((ch ^ ((ka & 3) << 1)) << 4) + sub);
-      const s16x4 hi = lds_read_tr16(vs_lds, (16 + ka) * (D * 2) + ((ch ^ ((ka & 3) << 1)) << 4) + sub);
-      const bf16x8 a = join_tr(lo, hi);
+      const unsigned char* src = vs_lds + v_rd[b & 3] + (b >> 2) * 128;
+      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 32 * D));
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         o_acc[rt][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rt], o_acc[rt][b], 0, 0, 0);
     }
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
-      const int ch = 2 * b + ((ln & 3) >> 1);
-      const int sub = (ln & 1) * 8;
-      const int k0 = ka, k1 = 16 + ka;
-      const s16x4 lo = lds_read_tr16(ls_lds, k0 * (RP * 2) + ((ch ^ ((k0 >> LSW_SHIFT) & (RCH - 1))) << 4) + sub);
-      const s16x4 hi = lds_read_tr16(ls_lds, k1 * (RP * 2) + ((ch ^ ((k1 >> LSW_SHIFT) & (RCH - 1))) << 4) + sub);
-      const bf16x8 a = join_tr(lo, hi);
+      const unsigned char* src = ls_lds + lt_rd[b];
+      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 32 * RP));
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         lr_acc[rt][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rt], lr_acc[rt][b], 0, 0, 0);
     }
-  };
-
-  if (PF == 2) {
-    for (int j = jw0; j < jw1; j += 64) {
-      store_stage(st0);
-      if (j + 64 < jw1) load_stage(st0, j + 64);
-      __builtin_amdgcn_wave_barrier();
-      compute_step(j);
-      __builtin_amdgcn_wave_barrier();
-      if (j + 32 < jw1) {
-        store_stage(st1);
-        if (j + 96 < jw1) load_stage(st1, j + 96);
-        __builtin_amdgcn_wave_barrier();
-        compute_step(j + 32);
-        __builtin_amdgcn_wave_barrier();
-      }
-    }
-  } else {
-    for (int j = jw0; j < jw1; j += 32) {
-      store_stage(st0);
-      if (j + 32 < jw1) load_stage(st0, j + 32);
-      __builtin_amdgcn_wave_barrier();
-      compute_step(j);
-      __builtin_amdgcn_wave_barrier();
-    }
+    // the next tile overwrites this one: every LDS read above must have returned
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+    if (j + 32 < jw1) issue_tile(j + 32);
   }
 
-  // ---- merge the waves of this workgroup (flash-decoding rule), base-2 units ----
+  // ===================== merge the waves of this workgroup =====================
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    l_run[rt] += __shfl_xor(l_run[rt], 16, 64);
-    l_run[rt] += __shfl_xor(l_run[rt], 32, 64);
+    l_run[rt] = sum_over_lane_groups(l_run[rt]);
     if (lg == 0) m_sh[wave][rt][ln] = m_run[rt];
   }
   __syncthreads();
@@ -434,7 +509,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(Params p) {
     __syncthreads();
   }
 
-  // ---- wave 0 writes the workgroup's partial state ----
+  // ===================== wave 0 writes the workgroup's partial state =====================
   if (wave == 0) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -462,12 +537,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(Params p) {
 }
 
 template <int D, int RT, int RP>
-static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s, int pf) {
-  constexpr int NW = 4;
-  if (pf == 2)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, NW, 2>), grid, dim3(NW * 64), 0, s, p);
+static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s) {
+  const dim3 block(256);
+  if (p.block_size != 0)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true>), grid, block, 0, s, p);
   else
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, NW, 1>), grid, dim3(NW * 64), 0, s, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false>), grid, block, 0, s, p);
   return hipGetLastError();
 }
 
@@ -475,18 +550,19 @@ static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s, int pf) 
 int decode_mfma_row_tiles(int rows_needed) { return rows_needed <= 16 ? 1 : 2; }
 
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s) {
+  (void)prefetch;
   dim3 grid(p.n_splits, p.n_kv_heads, p.n_seqs * p.row_groups);
   const int rp = p.rank <= 32 ? 32 : 64;
   const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (rp == 64 ? 1 : 0);
   switch (key) {
-    case 0: return launch_cfg<64, 1, 32>(p, grid, s, prefetch);
-    case 1: return launch_cfg<64, 1, 64>(p, grid, s, prefetch);
-    case 2: return launch_cfg<64, 2, 32>(p, grid, s, prefetch);
-    case 3: return launch_cfg<64, 2, 64>(p, grid, s, prefetch);
-    case 4: return launch_cfg<128, 1, 32>(p, grid, s, prefetch);
-    case 5: return launch_cfg<128, 1, 64>(p, grid, s, prefetch);
-    case 6: return launch_cfg<128, 2, 32>(p, grid, s, prefetch);
-    default: return launch_cfg<128, 2, 64>(p, grid, s, prefetch);
+    case 0: return launch_cfg<64, 1, 32>(p, grid, s);
+    case 1: return launch_cfg<64, 1, 64>(p, grid, s);
+    case 2: return launch_cfg<64, 2, 32>(p, grid, s);
+    case 3: return launch_cfg<64, 2, 64>(p, grid, s);
+    case 4: return launch_cfg<128, 1, 32>(p, grid, s);
+    case 5: return launch_cfg<128, 1, 64>(p, grid, s);
+    case 6: return launch_cfg<128, 2, 32>(p, grid, s);
+    default: return launch_cfg<128, 2, 64>(p, grid, s);
   }
 }
 

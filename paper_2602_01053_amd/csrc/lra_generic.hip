@@ -105,12 +105,17 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
 // Flash-decoding merge of the per-split states followed by Alg. 1's epilogue:
 //   M = max_s m_s, w_s = exp(m_s - M), l = sum w_s l_s, O = sum w_s O_s,
 //   O_lr = sum w_s O_lr,s ;  out = (O + O_lr B_V) / l.
-// Splits are visited in index order, so the result does not depend on which
-// workgroup finished first.
+// One workgroup of 128 x kMergeGroups threads per query row: thread (c, g) sums
+// column c over the splits s = g, g + kMergeGroups, ...; the groups are then added
+// in a fixed order, so the result does not depend on which workgroup of the first
+// kernel finished first.
+constexpr int kMergeGroups = 8;
+
 template <typename T>
-__global__ __launch_bounds__(128) void merge_kernel(Params p) {
+__global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   const int row = blockIdx.x;
-  const int c = threadIdx.x;
+  const int c = threadIdx.x, gq = threadIdx.y;
+  const int tid = gq * 128 + c;
   const int Hq = p.n_q_heads, d = p.head_dim, r = p.rank;
   const int tok = row / Hq;
   const int g = row - tok * Hq;
@@ -127,33 +132,72 @@ __global__ __launch_bounds__(128) void merge_kernel(Params p) {
   }
   // splits that start at or past this row's last visible key were never written
   const int ns = min(p.n_splits, (n_vis + p.split_keys - 1) / p.split_keys);
-  const float* ml = p.part_ml + static_cast<int64_t>(row) * p.n_splits * 2;
+  const int64_t slot0 = static_cast<int64_t>(row) * p.n_splits;
+  const float2* ml = reinterpret_cast<const float2*>(p.part_ml) + slot0;
+
+  __shared__ float red[2 * kMergeGroups];
+  __shared__ float o_sh[kMergeGroups][128];
+  __shared__ float olr_sh[kMergeGroups][64];
+  __shared__ float ell_sh[kMergeGroups];
 
   float big = -INFINITY;
-  for (int s = 0; s < ns; ++s)
-    if (ml[2 * s + 1] > 0.f) big = fmaxf(big, ml[2 * s]);
-
-  __shared__ float olr_s[64];
-  float ell = 0.f, o = 0.f, olr = 0.f;
-  for (int s = 0; s < ns; ++s) {
-    const float ls = ml[2 * s + 1];
-    if (!(ls > 0.f)) continue;
-    const float w = expf(ml[2 * s] - big);
-    const int64_t slot = static_cast<int64_t>(row) * p.n_splits + s;
-    ell = fmaf(w, ls, ell);
-    if (c < d) o = fmaf(w, p.part_o[slot * d + c], o);
-    if (c < r) olr = fmaf(w, p.part_lr[slot * r + c], olr);
+  for (int s = tid; s < ns; s += 128 * kMergeGroups) {
+    const float2 v = ml[s];
+    if (v.y > 0.f) big = fmaxf(big, v.x);
   }
-  if (c < r) olr_s[c] = olr;
+  big = wave_max(big);
+  if ((tid & 63) == 0) red[tid >> 6] = big;
   __syncthreads();
-  if (c < d) {
-    if (p.b_v != nullptr) {
-      const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * (static_cast<int64_t>(p.n_kv_heads) * d) +
-                    h * d + c;
-      const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * d;
-      for (int rho = 0; rho < r; ++rho) o = fmaf(olr_s[rho], to_f32<T>(bv[rho * ld]), o);
+  big = red[0];
+#pragma unroll
+  for (int i = 1; i < 2 * kMergeGroups; ++i) big = fmaxf(big, red[i]);
+
+  float ell = 0.f, o = 0.f, olr = 0.f;
+  const float* po = p.part_o + slot0 * d + c;
+  const float* pl = p.part_lr + slot0 * r + c;
+  for (int s = gq; s < ns; s += 2 * kMergeGroups) {
+    const int s2 = s + kMergeGroups;
+    const bool has2 = s2 < ns;
+    const float2 v0 = ml[s];
+    const float2 v1 = has2 ? ml[s2] : make_float2(0.f, 0.f);
+    const float x0 = c < d ? po[static_cast<int64_t>(s) * d] : 0.f;
+    const float x1 = (has2 && c < d) ? po[static_cast<int64_t>(s2) * d] : 0.f;
+    const float y0 = c < r ? pl[static_cast<int64_t>(s) * r] : 0.f;
+    const float y1 = (has2 && c < r) ? pl[static_cast<int64_t>(s2) * r] : 0.f;
+    const float w0 = v0.y > 0.f ? expf(v0.x - big) : 0.f;
+    const float w1 = v1.y > 0.f ? expf(v1.x - big) : 0.f;
+    ell = fmaf(w0, v0.y, ell);
+    ell = fmaf(w1, v1.y, ell);
+    o = fmaf(w0, x0, o);
+    o = fmaf(w1, x1, o);
+    olr = fmaf(w0, y0, olr);
+    olr = fmaf(w1, y1, olr);
+  }
+  o_sh[gq][c] = o;
+  if (c < 64) olr_sh[gq][c] = olr;
+  if (c == 0) ell_sh[gq] = ell;
+  __syncthreads();
+  if (gq == 0) {
+    o = o_sh[0][c];
+    ell = ell_sh[0];
+#pragma unroll
+    for (int i = 1; i < kMergeGroups; ++i) {
+      o += o_sh[i][c];
+      ell += ell_sh[i];
     }
-    static_cast<T*>(p.out)[static_cast<int64_t>(row) * d + c] = from_f32<T>(o / ell);
+    if (c < d) {
+      if (p.b_v != nullptr) {
+        const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * d;
+        const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * ld + h * d + c;
+        for (int rho = 0; rho < r; ++rho) {
+          float x = olr_sh[0][rho];
+#pragma unroll
+          for (int i = 1; i < kMergeGroups; ++i) x += olr_sh[i][rho];
+          o = fmaf(x, to_f32<T>(bv[rho * ld]), o);
+        }
+      }
+      static_cast<T*>(p.out)[static_cast<int64_t>(row) * d + c] = from_f32<T>(o / ell);
+    }
   }
 }
 
@@ -167,7 +211,7 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
 }
 
 hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s) {
-  dim3 grid(rows), block(128);
+  dim3 grid(rows), block(128, kMergeGroups);
   if (is_bf16)
     hipLaunchKernelGGL(merge_kernel<bf16_t>, grid, block, 0, s, p);
   else
