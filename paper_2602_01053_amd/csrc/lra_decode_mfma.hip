@@ -138,10 +138,17 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   constexpr int SMEM = STAGE_TOTAL > MERGE_TOTAL ? STAGE_TOTAL : MERGE_TOTAL;
   constexpr int LSW_SHIFT = (RP == 32) ? 1 : 0;
   constexpr int QT_BYTES = RT * RKS * 1024;
+  constexpr int M_BYTES = NW * RT * 16 * 4;
+  // Two workgroups per CU need 2 * LDS <= 160 KB.  Where the tile regions alone
+  // leave no room, the Qt exchange area and the per-wave maxima live inside the
+  // tile regions and the first tile is requested only after the prologue.
+  constexpr bool ALIAS = 2 * (SMEM + QT_BYTES + M_BYTES) > 160 * 1024;
+  constexpr int EXTRA = ALIAS ? 16 : QT_BYTES + M_BYTES;
+  static_assert(QT_BYTES <= WAVE_BYTES && RT * 64 <= WAVE_BYTES, "aliased areas must fit one wave's region");
 
   __shared__ __align__(16) unsigned char smem[SMEM];
-  __shared__ __align__(16) unsigned char qt_lds[QT_BYTES];
-  __shared__ float m_sh[NW][RT][16];
+  __shared__ __align__(16) unsigned char extra_lds[EXTRA];
+  unsigned char* qt_lds = ALIAS ? smem : extra_lds;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -274,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   };
 
   // The first tile is on its way before the prologue touches Q and B_K.
-  if (jw0 < jw1) issue_tile(jw0);
+  if (!ALIAS && jw0 < jw1) issue_tile(jw0);
 
   // ===================== prologue: Q operands and Qt = Q B_K^T =====================
   // qb[rt][ks]: lane (row ln of tile rt, k = 32ks + 8lg + e), e = 0..7.  Used as the
@@ -306,36 +313,54 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     const int ncb = (r + 15) >> 4;
     const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
     const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
+    constexpr int MAXIT = 4;  // at most 4 slots x 4 rho blocks per tile over 4 waves
+    const int n_items = S * ncb;
+    // adapter of every agent slot of every tile: wave-uniform loads, all in flight together
+    int a_slot[RT][4];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      for (int idx = wave; idx < S * ncb; idx += NW) {
-        const int si = idx / ncb, cb = idx - si * ncb;
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int si = 0; si < 4; ++si) {
         const int slot = (row0 + rt * 16) / GP + si;
-        int a = 0;
-        uint32_t bytes = 0;
-        if (bkg != nullptr && slot < n_q) {
-          a = p.query_adapter[q_begin + slot];
-          bytes = static_cast<uint32_t>((r - 1) * ldb + D) * 2u;
-        }
-        const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(bkg + static_cast<int64_t>(a) * r * ldb + h * D, bytes);
+        a_slot[rt][si] = (bkg != nullptr && si < S && slot < n_q) ? p.query_adapter[q_begin + slot] : -1;
+      }
+    // every B_K tile of this wave's items is requested before the first product starts
+    uint4 bt4[RT][MAXIT][KS];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int it = 0; it < MAXIT; ++it) {
+        const int idx = wave + it * NW;
+        const int si = idx / ncb, cb = idx - si * ncb;
+        const int a = si == 0 ? a_slot[rt][0] : (si == 1 ? a_slot[rt][1] : (si == 2 ? a_slot[rt][2] : a_slot[rt][3]));
+        const bool live = idx < n_items && a >= 0;
+        const uint32_t bytes = live ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u;
+        const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(bkg + static_cast<int64_t>(live ? a : 0) * r * ldb + h * D, bytes);
         const uint32_t off = static_cast<uint32_t>((cb * 16 + ln) * ldb * 2 + lg * 16);
-        uint4 bt4[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bt4[ks] = buf_load16(rs_b, off, ks * 64);
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < KS; ++ks) bt4[rt][it][ks] = buf_load16(rs_b, off, ks * 64);
+      }
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bt4[ks]), qb[rt][ks], acc, 0, 0, 0);
-        if (ln / GP == si) {
-          unsigned char* dst = qt_lds + ((rt * RKS + (cb >> 1)) * 64 + lane) * 16;
-          const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
-          if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
-            *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
-          else
-            *reinterpret_cast<uint2*>(dst + (cb & 1) * 8) = pk;
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int it = 0; it < MAXIT; ++it) {
+        const int idx = wave + it * NW;
+        if (idx < n_items) {
+          const int si = idx / ncb, cb = idx - si * ncb;
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bt4[rt][it][ks]), qb[rt][ks], acc, 0, 0, 0);
+          if (ln / GP == si) {
+            unsigned char* dst = qt_lds + ((rt * RKS + (cb >> 1)) * 64 + lane) * 16;
+            const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
+            if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
+              *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
+            else
+              *reinterpret_cast<uint2*>(dst + (cb & 1) * 8) = pk;
+          }
         }
       }
-    }
     __syncthreads();
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
@@ -345,6 +370,10 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
         if (ks * 32 < r) v = lds_read16(qt_lds + ((rt * RKS + ks) * 64 + lane) * 16);
         qtb[rt][ks] = as_bf16x8(v);
       }
+  }
+  if (ALIAS) {
+    __syncthreads();  // the exchange area is about to be overwritten by tiles
+    if (jw0 < jw1) issue_tile(jw0);
   }
 
   // ===================== main loop =====================
@@ -450,18 +479,24 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   }
 
   // ===================== merge the waves of this workgroup =====================
+  // per-wave maxima: in a wave's own tile region when aliased (nobody else touches it
+  // before the barrier), else in their own area
+  float* m_mine = reinterpret_cast<float*>(ALIAS ? smem + wave * WAVE_BYTES : extra_lds + QT_BYTES + wave * RT * 64);
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     l_run[rt] = sum_over_lane_groups(l_run[rt]);
-    if (lg == 0) m_sh[wave][rt][ln] = m_run[rt];
+    if (lg == 0) m_mine[rt * 16 + ln] = m_run[rt];
   }
   __syncthreads();
   float m_all[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    float mm = m_sh[0][rt][ln];
+    float mm = -INFINITY;
 #pragma unroll
-    for (int w = 1; w < NW; ++w) mm = fmaxf(mm, m_sh[w][rt][ln]);
+    for (int w = 0; w < NW; ++w) {
+      const float* m_w = reinterpret_cast<const float*>(ALIAS ? smem + w * WAVE_BYTES : extra_lds + QT_BYTES + w * RT * 64);
+      mm = fmaxf(mm, m_w[rt * 16 + ln]);
+    }
     m_all[rt] = mm;  // finite: wave 0 always owns at least one key
     const float wgt = fast_exp2(m_run[rt] - mm);
     l_run[rt] *= wgt;
@@ -470,6 +505,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 #pragma unroll
     for (int b = 0; b < RB; ++b) lr_acc[rt][b] *= wgt;
   }
+  if (ALIAS) __syncthreads();  // the maxima are about to be overwritten by merge slots
   float* mslots = reinterpret_cast<float*>(smem);
 #pragma unroll
   for (int stride = NW / 2; stride >= 1; stride >>= 1) {

@@ -105,11 +105,15 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
 // Flash-decoding merge of the per-split states followed by Alg. 1's epilogue:
 //   M = max_s m_s, w_s = exp(m_s - M), l = sum w_s l_s, O = sum w_s O_s,
 //   O_lr = sum w_s O_lr,s ;  out = (O + O_lr B_V) / l.
-// One workgroup of 128 x kMergeGroups threads per query row: thread (c, g) sums
-// column c over the splits s = g, g + kMergeGroups, ...; the groups are then added
-// in a fixed order, so the result does not depend on which workgroup of the first
-// kernel finished first.
+// One workgroup of 128 x kMergeGroups threads per query row.  Thread (c, g) owns
+// column c of the splits s = g, g + kMergeGroups, ... and, for the epilogue, the
+// B_V rows rho = g, g + kMergeGroups, ...  All of a thread's global loads (split
+// statistics, partial rows, B_V) are issued before the first one is consumed, so
+// the kernel costs about two memory round trips.  Groups are added in a fixed
+// order: the result does not depend on which workgroup of the first kernel
+// finished first.
 constexpr int kMergeGroups = 8;
+constexpr int kMergeUnroll = 8;  // splits per thread and pass
 
 template <typename T>
 __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
@@ -134,17 +138,42 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   const int ns = min(p.n_splits, (n_vis + p.split_keys - 1) / p.split_keys);
   const int64_t slot0 = static_cast<int64_t>(row) * p.n_splits;
   const float2* ml = reinterpret_cast<const float2*>(p.part_ml) + slot0;
+  const float* po = p.part_o + slot0 * d + c;
+  const float* pl = p.part_lr + slot0 * r + c;
+  const bool col_o = c < d, col_l = c < r;
 
   __shared__ float red[2 * kMergeGroups];
   __shared__ float o_sh[kMergeGroups][128];
   __shared__ float olr_sh[kMergeGroups][64];
   __shared__ float ell_sh[kMergeGroups];
 
+  // ---- issue: statistics for the row maximum, first pass of partial rows, B_V rows ----
   float big = -INFINITY;
   for (int s = tid; s < ns; s += 128 * kMergeGroups) {
     const float2 v = ml[s];
     if (v.y > 0.f) big = fmaxf(big, v.x);
   }
+  float2 st[kMergeUnroll];
+  float xo[kMergeUnroll], xl[kMergeUnroll];
+#pragma unroll
+  for (int i = 0; i < kMergeUnroll; ++i) {
+    const int s = i * kMergeGroups + gq;
+    const bool ok = s < ns;
+    st[i] = ok ? ml[s] : make_float2(0.f, 0.f);
+    xo[i] = (ok && col_o) ? po[static_cast<int64_t>(s) * d] : 0.f;
+    xl[i] = (ok && col_l) ? pl[static_cast<int64_t>(s) * r] : 0.f;
+  }
+  float bvv[64 / kMergeGroups];
+  {
+    const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * d;
+    const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * ld + h * d + c;
+#pragma unroll
+    for (int i = 0; i < 64 / kMergeGroups; ++i) {
+      const int rho = i * kMergeGroups + gq;
+      bvv[i] = (p.b_v != nullptr && col_o && rho < r) ? to_f32<T>(bv[rho * ld]) : 0.f;
+    }
+  }
+
   big = wave_max(big);
   if ((tid & 63) == 0) red[tid >> 6] = big;
   __syncthreads();
@@ -153,51 +182,48 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   for (int i = 1; i < 2 * kMergeGroups; ++i) big = fmaxf(big, red[i]);
 
   float ell = 0.f, o = 0.f, olr = 0.f;
-  const float* po = p.part_o + slot0 * d + c;
-  const float* pl = p.part_lr + slot0 * r + c;
-  for (int s = gq; s < ns; s += 2 * kMergeGroups) {
-    const int s2 = s + kMergeGroups;
-    const bool has2 = s2 < ns;
-    const float2 v0 = ml[s];
-    const float2 v1 = has2 ? ml[s2] : make_float2(0.f, 0.f);
-    const float x0 = c < d ? po[static_cast<int64_t>(s) * d] : 0.f;
-    const float x1 = (has2 && c < d) ? po[static_cast<int64_t>(s2) * d] : 0.f;
-    const float y0 = c < r ? pl[static_cast<int64_t>(s) * r] : 0.f;
-    const float y1 = (has2 && c < r) ? pl[static_cast<int64_t>(s2) * r] : 0.f;
-    const float w0 = v0.y > 0.f ? expf(v0.x - big) : 0.f;
-    const float w1 = v1.y > 0.f ? expf(v1.x - big) : 0.f;
-    ell = fmaf(w0, v0.y, ell);
-    ell = fmaf(w1, v1.y, ell);
-    o = fmaf(w0, x0, o);
-    o = fmaf(w1, x1, o);
-    olr = fmaf(w0, y0, olr);
-    olr = fmaf(w1, y1, olr);
+#pragma unroll
+  for (int i = 0; i < kMergeUnroll; ++i) {
+    const float w = st[i].y > 0.f ? expf(st[i].x - big) : 0.f;
+    ell = fmaf(w, st[i].y, ell);
+    o = fmaf(w, xo[i], o);
+    olr = fmaf(w, xl[i], olr);
   }
-  o_sh[gq][c] = o;
+  // further passes, only for more than kMergeGroups * kMergeUnroll splits
+  for (int s = kMergeGroups * kMergeUnroll + gq; s < ns; s += kMergeGroups) {
+    const float2 v = ml[s];
+    const float x = col_o ? po[static_cast<int64_t>(s) * d] : 0.f;
+    const float y = col_l ? pl[static_cast<int64_t>(s) * r] : 0.f;
+    const float w = v.y > 0.f ? expf(v.x - big) : 0.f;
+    ell = fmaf(w, v.y, ell);
+    o = fmaf(w, x, o);
+    olr = fmaf(w, y, olr);
+  }
   if (c < 64) olr_sh[gq][c] = olr;
   if (c == 0) ell_sh[gq] = ell;
   __syncthreads();
-  if (gq == 0) {
+  // epilogue O += O_lr B_V: group g contributes its rows rho = g, g + kMergeGroups, ...
+#pragma unroll
+  for (int i = 0; i < 64 / kMergeGroups; ++i) {
+    const int rho = i * kMergeGroups + gq;
+    if (rho < r) {
+      float x = olr_sh[0][rho];
+#pragma unroll
+      for (int k = 1; k < kMergeGroups; ++k) x += olr_sh[k][rho];
+      o = fmaf(x, bvv[i], o);
+    }
+  }
+  o_sh[gq][c] = o;
+  __syncthreads();
+  if (gq == 0 && col_o) {
     o = o_sh[0][c];
     ell = ell_sh[0];
 #pragma unroll
-    for (int i = 1; i < kMergeGroups; ++i) {
-      o += o_sh[i][c];
-      ell += ell_sh[i];
+    for (int k = 1; k < kMergeGroups; ++k) {
+      o += o_sh[k][c];
+      ell += ell_sh[k];
     }
-    if (c < d) {
-      if (p.b_v != nullptr) {
-        const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * d;
-        const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * ld + h * d + c;
-        for (int rho = 0; rho < r; ++rho) {
-          float x = olr_sh[0][rho];
-#pragma unroll
-          for (int i = 1; i < kMergeGroups; ++i) x += olr_sh[i][rho];
-          o = fmaf(x, to_f32<T>(bv[rho * ld]), o);
-        }
-      }
-      static_cast<T*>(p.out)[static_cast<int64_t>(row) * d + c] = from_f32<T>(o / ell);
-    }
+    static_cast<T*>(p.out)[static_cast<int64_t>(row) * d + c] = from_f32<T>(o / ell);
   }
 }
 
