@@ -61,7 +61,15 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   const int G = sh->n_q_heads / sh->n_kv_heads;
   // The MFMA decode kernel moves L in 16-byte pieces: ranks that are not a
   // multiple of 8 take the vector-ALU kernels.
-  pl.mfma = !prefill && sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
+  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
+  if (prefill && pl.mfma) {  // one kernel, no split over keys, no workspace
+    pl.rows = tokens * sh->n_q_heads;
+    pl.group_pad = pl.row_tiles = pl.row_groups = 1;
+    pl.split_keys = c->max_seq_len;
+    pl.n_splits = 1;
+    pl.bytes = 0;
+    return pl;
+  }
   pl.rows = tokens * sh->n_q_heads;
   pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
   pl.row_tiles = 1;
@@ -230,6 +238,11 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   const bool bf16 = shape->dtype == LRA_BF16;
   hipEvent_t ev0 = static_cast<hipEvent_t>(g_ev_start.load()), ev1 = static_cast<hipEvent_t>(g_ev_stop.load());
   if (ev0) (void)hipEventRecord(ev0, s);
+  if (pl.mfma) {
+    if (launch_prefill_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
+    if (ev1) (void)hipEventRecord(ev1, s);
+    return LRA_OK;
+  }
   if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   if (ev1) (void)hipEventRecord(ev1, s);
   if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;

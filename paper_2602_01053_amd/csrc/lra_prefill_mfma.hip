@@ -1,0 +1,421 @@
+// MFMA causal prefill kernel of the Flash-LoRA-Attention library (bf16, gfx950).
+//
+// Alg. 1 of LRAgent (Sec. 3.3) for L_c new tokens of one agent after L_p cached
+// ones, with the key side reordered as in App. D.1: per 64-key tile
+//   S^T[key][row]  = K_base[key][:] . Q[row][:] + L[key][:] . Qt[row][:]   (MFMA, k = d + r)
+//   online softmax along keys, causal mask aligned to the end of the sequence
+//   O^T[d][row]   += V_base^T[d][key] . P^T[key][row]                      (MFMA)
+//   Olr^T[p][row] += L^T[p][key]      . P^T[key][row]                      (MFMA)
+// and after the last tile O^T += B_V^T . Olr^T (one more MFMA k-step per 16 ranks),
+// O /= l.  Qt = Q B_K^T is formed once per wave before the loop (MFMA).
+//
+// A workgroup owns 128 query rows of one q head (4 waves x 32 rows) and walks the
+// key tiles up to its causal limit.  v_mfma_f32_32x32x16_bf16 throughout; the
+// transposed score tile leaves P^T in the lanes that need it as the B operand of
+// the second product.  K_base / V_base / L tiles are shared by the four waves:
+// global loads one tile ahead into registers, swizzled stores into a double
+// buffered LDS tile, one barrier per tile.  ds_read_b128 feeds the K operand,
+// ds_read_b64_tr_b16 the transposed V and L operands.  Workgroups are numbered so
+// that all q heads of a kv head run on the same XCD and share its L2.
+#include "lra_common.h"
+
+namespace lra {
+
+typedef __bf16 pf_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 pf_bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 pf_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float pf_f32x16 __attribute__((ext_vector_type(16)));
+typedef float pf_f32x4 __attribute__((ext_vector_type(4)));
+typedef float pf_f32x2 __attribute__((ext_vector_type(2)));
+typedef short pf_s16x4 __attribute__((ext_vector_type(4)));
+typedef short pf_s16x8 __attribute__((ext_vector_type(8)));
+
+#define PF_LDS_AS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+__device__ __forceinline__ pf_bf16x8 pf_as_bf16x8(uint4 v) { return __builtin_bit_cast(pf_bf16x8, v); }
+
+__device__ __forceinline__ pf_s16x4 pf_read_tr16(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(PF_LDS_AS(pf_s16x4, p));
+}
+
+__device__ __forceinline__ pf_bf16x8 pf_join(pf_s16x4 lo, pf_s16x4 hi) {
+  pf_s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(pf_bf16x8, v);
+}
+
+__device__ __forceinline__ uint32_t pf_pack2(float a, float b) {  // one v_cvt_pk_bf16_f32
+  const pf_f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, pf_bf16x2));
+}
+
+// value of the partner lane l ^ 32 (inline assembly: the compiler's builtin for
+// v_permlane32_swap treats its two results as one value)
+__device__ __forceinline__ float pf_partner32(float v) {
+  float x = v, y = v;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+  // lanes 0-31: x = own, y = partner ; lanes 32-63: x = partner, y = own
+  return (threadIdx.x & 32) ? x : y;
+}
+
+template <int D, int RP, bool PAGED>
+__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
+  constexpr int BM = 128, BN = 64;
+  constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
+  constexpr int RKS = RP / 16; // k-steps over the padded rank
+  constexpr int DB = D / 32;   // 32-row blocks of O^T
+  constexpr int RB = (RP + 31) / 32;  // 32-row blocks of Olr^T
+  constexpr int KCH = D / 8;   // 16-byte chunks per K/V row
+  constexpr int KV_LOADS = BN * KCH / 256;  // per-thread 16-byte loads per K (or V) tile
+  constexpr int LCH = RP / 8;               // 16-byte chunks per L row
+  constexpr int L_LOADS = (BN * LCH + 255) / 256;
+  constexpr int LS = RP * 2 + 8;            // L row stride in LDS (bytes): odd multiple of 8 spreads banks
+  constexpr int K_BYTES = BN * D * 2;
+  constexpr int L_BYTES = (BN * LS + 15) / 16 * 16;
+  constexpr int STAGE = 2 * K_BYTES + L_BYTES;
+
+  __shared__ __align__(16) unsigned char smem[2 * STAGE];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const int Hq = p.n_q_heads, Hkv = p.n_kv_heads, G = p.group, r = p.rank;
+
+  // workgroup -> (kv head, q head in group, q tile); consecutive ids go to consecutive XCDs
+  const int lin = blockIdx.x;
+  const int hk = lin % Hkv;
+  const int rest = lin / Hkv;
+  const int gq = rest % G;
+  const int qt = rest / G;
+  const int head = hk * G + gq;
+  const int t = p.seq_index;
+  const int n_t = min(p.seq_lens[t], p.max_seq_len);
+  const int n_new = p.n_new;
+  const int q0 = qt * BM;
+  if (q0 >= n_new) return;
+  const int base_vis = n_t - n_new;  // new token i sees keys 0 .. base_vis + i
+  const int row = q0 + wave * 32 + l32;           // this lane's query row (new-token index)
+  const int row_c = min(row, n_new - 1);          // clamped for loads; rows past the end are never stored
+  const int limit = base_vis + row_c;             // last visible key of this lane's row
+  const int wg_last = base_vis + min(q0 + BM, n_new) - 1;  // last key any row of the workgroup sees
+  const int n_tiles = wg_last / BN + 1;
+
+  const bf16_t* kb = static_cast<const bf16_t*>(p.k_base);
+  const bf16_t* vb = static_cast<const bf16_t*>(p.v_base);
+  const bf16_t* lr = static_cast<const bf16_t*>(p.l);
+  const int32_t* bt = p.block_table + static_cast<int64_t>(t) * p.max_blocks_per_seq;
+
+  // ---------------- tile staging: global -> registers -> LDS ----------------
+  struct Stage {
+    uint4 k[KV_LOADS], v[KV_LOADS], l[L_LOADS];
+  };
+  auto load_tile = [&](Stage& st, int j) {
+#pragma unroll
+    for (int i = 0; i < KV_LOADS; ++i) {
+      const int f = i * 256 + tid;
+      const int key = f / KCH, ch = f % KCH;
+      const int tok = min(j + key, n_t - 1);  // clamped: masked later, never out of the sequence
+      int64_t off;
+      if (PAGED) {
+        const int blk = bt[tok >> 4];
+        off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(tok & 15) * p.kv_token_stride;
+      } else {
+        off = static_cast<int64_t>(tok) * p.kv_token_stride;
+      }
+      off += static_cast<int64_t>(hk) * p.kv_head_stride + ch * 8;
+      st.k[i] = *reinterpret_cast<const uint4*>(kb + off);
+      st.v[i] = *reinterpret_cast<const uint4*>(vb + off);
+    }
+#pragma unroll
+    for (int i = 0; i < L_LOADS; ++i) {
+      const int f = i * 256 + tid;
+      const int key = f / LCH, ch = f % LCH;
+      uint4 val = make_uint4(0u, 0u, 0u, 0u);
+      if (f < BN * LCH && ch * 8 < r) {
+        const int tok = min(j + key, n_t - 1);
+        int64_t lrow;
+        if (PAGED)
+          lrow = static_cast<int64_t>(bt[tok >> 4]) * 16 + (tok & 15);
+        else
+          lrow = tok;
+        val = *reinterpret_cast<const uint4*>(lr + lrow * r + ch * 8);
+      }
+      st.l[i] = val;
+    }
+  };
+  auto store_tile = [&](const Stage& st, unsigned char* buf) {
+    unsigned char* ks = buf;
+    unsigned char* vs = buf + K_BYTES;
+    unsigned char* ls = buf + 2 * K_BYTES;
+#pragma unroll
+    for (int i = 0; i < KV_LOADS; ++i) {
+      const int f = i * 256 + tid;
+      const int key = f / KCH, ch = f % KCH;
+      *reinterpret_cast<uint4*>(ks + key * (D * 2) + ((ch ^ (key & 7)) << 4)) = st.k[i];
+      *reinterpret_cast<uint4*>(vs + key * (D * 2) + ((ch ^ ((key & 3) << 1)) << 4)) = st.v[i];
+    }
+#pragma unroll
+    for (int i = 0; i < L_LOADS; ++i) {
+      const int f = i * 256 + tid;
+      const int key = f / LCH, ch = f % LCH;
+      if (f < BN * LCH) {
+        unsigned char* dst = ls + key * LS + ch * 16;  // rows are 8-byte aligned only
+        *reinterpret_cast<uint2*>(dst) = make_uint2(st.l[i].x, st.l[i].y);
+        *reinterpret_cast<uint2*>(dst + 8) = make_uint2(st.l[i].z, st.l[i].w);
+      }
+    }
+  };
+
+  Stage st;
+  load_tile(st, 0);
+
+  // ---------------- prologue: Q operands, Qt = Q B_K^T ----------------
+  // qb[ks]: B operand of S^T: lane (row l32, k = 16ks + 8g2 + e)
+  pf_bf16x8 qb[KS];
+  {
+    const bf16_t* qrow = static_cast<const bf16_t*>(p.q) + (static_cast<int64_t>(row_c) * Hq + head) * D + g2 * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qb[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(qrow + ks * 16));
+  }
+  // Qt^T[rho][row] = B_K[rho][:] . Q[row][:]: C layout lane (row l32; reg i <-> rho = 32b + 8(i/4) + 4g2 + i%4).
+  // As B operand of the rank k-steps of S^T, k-step ks' takes registers 8ks'..8ks'+7 of
+  // block b = ks'/2, i.e. element e <-> rho = 16ks' + 8(e/4) + 4g2 + e%4; the L operand
+  // below is read in the same order.
+  pf_bf16x8 qtb[RKS];
+  {
+    const int64_t ldb = static_cast<int64_t>(Hkv) * D;
+    const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
+#pragma unroll
+    for (int b = 0; b < RB; ++b) {
+      pf_f32x16 acc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+      const int rho = b * 32 + l32;
+      const bool live = bkg != nullptr && rho < r;
+      const bf16_t* brow = bkg + (static_cast<int64_t>(p.adapter_index) * r + (live ? rho : 0)) * ldb + hk * D + g2 * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (live) v = *reinterpret_cast<const uint4*>(brow + ks * 16);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(v), qb[ks], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int ks2 = b * 2 + half;
+        if (ks2 < RKS) {
+          const int o = half * 8;
+          qtb[ks2] = pf_as_bf16x8(make_uint4(pf_pack2(acc[o + 0], acc[o + 1]), pf_pack2(acc[o + 2], acc[o + 3]),
+                                             pf_pack2(acc[o + 4], acc[o + 5]), pf_pack2(acc[o + 6], acc[o + 7])));
+        }
+      }
+    }
+  }
+
+  // ---------------- per-lane LDS read offsets ----------------
+  // K rows as A operand of S^T (ds_read_b128): key = 32kt + l32, logical chunk 2ks + g2
+  int k_rd[4];  // index (2ks + g2) & 7 pattern: the swizzle touches chunk bits 0..2 only
+  {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) k_rd[q] = l32 * (D * 2) + ((((2 * q + g2) ^ (l32 & 7)) & 7) << 4);
+  }
+  // V^T as A operand of O^T (ds_read_b64_tr_b16): lane a of a 16-lane group addresses
+  // row 4*g2 + a/4 (+ 8 for the second read) of the 16-key k-step, 8 bytes at d = dbase + 4(a%4)
+  const int a16 = lane & 15;
+  const int dsel = (lane >> 4) & 1;   // which 16 of the 32 output rows this 16-lane group produces
+  const int vrow = 4 * g2 + (a16 >> 2);
+  // byte offset in the row: 64b + 32dsel + 8(a16 & 3), i.e. chunk 4b + 2dsel + c0, half sub;
+  // the swizzle (row & 3) << 1 flips chunk bits 1..2, so the pattern depends on b & 1 only
+  int v_rd[2];
+  {
+    const int u = vrow & 3, c0 = (a16 & 3) >> 1, sub = (a16 & 1) * 8;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) v_rd[q] = vrow * (D * 2) + ((2 * ((2 * q + dsel) ^ u) + c0) << 4) + sub;
+  }
+  // L rows as A operand of S^T: two 8-byte pieces per k-step; L^T as A operand of Olr^T
+  const int l_rd = l32 * LS + g2 * 8;           // + ks'*32 (+16 for the second piece) + kt*32*LS
+  const int lt_rd = vrow * LS + dsel * 32 + (a16 & 3) * 8;  // + b*64 ; + 16s... rows
+
+  // ---------------- main loop ----------------
+  pf_f32x16 o_acc[DB], lr_acc[RB];
+#pragma unroll
+  for (int b = 0; b < DB; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[b][i] = 0.f;
+#pragma unroll
+  for (int b = 0; b < RB; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lr_acc[b][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = p.scale * 1.44269504088896340736f;
+
+  store_tile(st, smem);
+  __syncthreads();
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int j = tile * BN;
+    unsigned char* buf = smem + (tile & 1) * STAGE;
+    const unsigned char* ks_l = buf;
+    const unsigned char* vs_l = buf + K_BYTES;
+    const unsigned char* ls_l = buf + 2 * K_BYTES;
+    const bool more = tile + 1 < n_tiles;
+    if (more) load_tile(st, j + BN);
+
+    // S^T for the two 32-key halves of the tile
+    pf_f32x16 s[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[kt][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        // chunk 2ks + g2: bits 0..2 go through the swizzle pattern, bit 3 is an offset of 128 bytes
+        const pf_bf16x8 a = pf_as_bf16x8(
+            *reinterpret_cast<const uint4*>(ks_l + k_rd[ks & 3] + (ks >> 2) * 128 + kt * 32 * D * 2));
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[ks], s[kt], 0, 0, 0);
+      }
+#pragma unroll
+      for (int ks = 0; ks < RKS; ++ks) {
+        const unsigned char* src = ls_l + l_rd + ks * 32 + kt * 32 * LS;
+        const uint2 lo = *reinterpret_cast<const uint2*>(src);
+        const uint2 hi = *reinterpret_cast<const uint2*>(src + 16);
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y)), qtb[ks],
+                                                        s[kt], 0, 0, 0);
+      }
+    }
+    // causal mask + online softmax.  Element (kt, i) of this lane is key
+    // j + 32kt + 8(i/4) + 4g2 + i%4 of row l32.
+    if (j + BN - 1 > base_vis + q0 + wave * 32) {  // some row of this wave does not see the whole tile
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = j + 32 * kt + 8 * (i >> 2) + 4 * g2 + (i & 3);
+          if (key > limit) s[kt][i] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kt][i]);
+    mx = fmaxf(mx, pf_partner32(mx)) * sc;
+    if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int b = 0; b < DB; ++b) o_acc[b] *= alpha;
+#pragma unroll
+      for (int b = 0; b < RB; ++b) lr_acc[b] *= alpha;
+    }
+    const float nm = -m_run;  // finite from the first tile on: key 0 is visible to every row
+    pf_bf16x8 pb[2][2];       // [kt][16-key k-step]
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      float e[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        e[i] = __builtin_amdgcn_exp2f(fmaf(s[kt][i], sc, nm));
+        l_run += e[i];
+      }
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2)
+        pb[kt][h2] = pf_as_bf16x8(make_uint4(pf_pack2(e[8 * h2 + 0], e[8 * h2 + 1]), pf_pack2(e[8 * h2 + 2], e[8 * h2 + 3]),
+                                             pf_pack2(e[8 * h2 + 4], e[8 * h2 + 5]), pf_pack2(e[8 * h2 + 6], e[8 * h2 + 7])));
+    }
+    // O^T += V^T P^T ; Olr^T += L^T P^T, one 16-key k-step at a time.
+    // k-step (kt, h2), element e <-> key 32kt + 16h2 + 8(e/4) + 4g2 + e%4.
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const int rowoff = (32 * kt + 16 * h2) * (D * 2);
+#pragma unroll
+        for (int b = 0; b < DB; ++b) {
+          const unsigned char* src = vs_l + v_rd[b & 1] + (b >> 1) * 128 + rowoff;
+          const pf_bf16x8 a = pf_join(pf_read_tr16(src), pf_read_tr16(src + 8 * (D * 2)));
+          o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][h2], o_acc[b], 0, 0, 0);
+        }
+#pragma unroll
+        for (int b = 0; b < RB; ++b) {
+          // rows rho = 32b + 16dsel + a16 of L^T; lanes whose rho lies beyond the padded rank
+          // re-read block 0 (their output rows are never used)
+          const int boff = (b * 64 + dsel * 32 < RP * 2) ? b * 64 : -dsel * 32;
+          const unsigned char* src = ls_l + lt_rd + boff + (32 * kt + 16 * h2) * LS;
+          const pf_bf16x8 a = pf_join(pf_read_tr16(src), pf_read_tr16(src + 8 * LS));
+          lr_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][h2], lr_acc[b], 0, 0, 0);
+        }
+      }
+
+    if (more) store_tile(st, smem + ((tile + 1) & 1) * STAGE);
+    __syncthreads();
+  }
+
+  // ---------------- epilogue: O^T += B_V^T Olr^T, O /= l, store ----------------
+  l_run += pf_partner32(l_run);
+  if (p.b_v != nullptr) {
+    const int64_t ldb = static_cast<int64_t>(Hkv) * D;
+    const bf16_t* bv = static_cast<const bf16_t*>(p.b_v) + static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D;
+#pragma unroll
+    for (int ks = 0; ks < RKS; ++ks) {
+      // B operand: Olr^T registers 8(ks&1)..+7 of block ks/2: element e <-> rho = 16ks + 8(e/4) + 4g2 + e%4
+      const int o = (ks & 1) * 8;
+      const pf_f32x16& src = lr_acc[ks >> 1];
+      const pf_bf16x8 bop =
+          pf_as_bf16x8(make_uint4(pf_pack2(src[o + 0], src[o + 1]), pf_pack2(src[o + 2], src[o + 3]),
+                                  pf_pack2(src[o + 4], src[o + 5]), pf_pack2(src[o + 6], src[o + 7])));
+#pragma unroll
+      for (int b = 0; b < DB; ++b) {
+        // A operand: B_V^T: lane (d = 32b + l32, element e <-> rho as above)
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int rho = 16 * ks + 8 * (e >> 2) + 4 * g2 + (e & 3);
+          const uint32_t val = rho < r ? static_cast<uint32_t>(bv[rho * ldb + 32 * b + l32]) : 0u;
+          w[e >> 1] |= val << ((e & 1) * 16);
+        }
+        o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])), bop,
+                                                           o_acc[b], 0, 0, 0);
+      }
+    }
+  }
+  if (row < n_new) {
+    const float inv = 1.0f / l_run;
+    bf16_t* orow = static_cast<bf16_t*>(p.out) + (static_cast<int64_t>(row) * Hq + head) * D;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        // registers 4q..4q+3 are d = 32b + 8q + 4g2 + 0..3
+        const uint2 pk = make_uint2(pf_pack2(o_acc[b][4 * q + 0] * inv, o_acc[b][4 * q + 1] * inv),
+                                    pf_pack2(o_acc[b][4 * q + 2] * inv, o_acc[b][4 * q + 3] * inv));
+        *reinterpret_cast<uint2*>(orow + 32 * b + 8 * q + 4 * g2) = pk;
+      }
+  }
+}
+
+template <int D, int RP>
+static hipError_t launch_pf(const Params& p, dim3 grid, hipStream_t s) {
+  if (p.block_size != 0)
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true>), grid, dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false>), grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill_mfma(const Params& p, hipStream_t s) {
+  const int q_tiles = (p.n_new + 127) / 128;
+  dim3 grid(q_tiles * p.n_q_heads);
+  const int rp = p.rank <= 16 ? 16 : (p.rank <= 32 ? 32 : 64);
+  if (p.head_dim == 128) {
+    if (rp == 16) return launch_pf<128, 16>(p, grid, s);
+    if (rp == 32) return launch_pf<128, 32>(p, grid, s);
+    return launch_pf<128, 64>(p, grid, s);
+  }
+  if (rp == 16) return launch_pf<64, 16>(p, grid, s);
+  if (rp == 32) return launch_pf<64, 32>(p, grid, s);
+  return launch_pf<64, 64>(p, grid, s);
+}
+
+}  // namespace lra

@@ -107,7 +107,9 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _prefill(lib, sh, c, ad, n_new=8193) == SHAPE
     assert _prefill(lib, sh, c, ad, q=None) == NULL
     bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 0)
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) > 0
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) == 0      # bf16 prefill: one kernel
+    sh32 = mutated(dtype=1)[0]
+    assert 0 < lib.lra_workspace_bytes(ctypes.byref(sh32), ctypes.byref(c), 0, 0, 16) < (1 << 40)
     assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 5, 0) == ctypes.c_size_t(-1).value
     assert bad == ctypes.c_size_t(-1).value
 
