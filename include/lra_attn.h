@@ -204,13 +204,13 @@ int32_t lra_set_decode_split_keys(int32_t keys);
 int32_t lra_set_decode_prefetch(int32_t steps);
 
 /*
- * Measurement hook.  While both are non-NULL, every later call records
- * start_event (a hipEvent_t) on its stream right before its dominant kernel (the
- * key-streaming kernel, not the merge/epilogue) and stop_event right after it,
- * so a benchmark can time that kernel alone with HIP events.  The events belong
- * to the caller.  Pass NULL, NULL to switch off (the default).
+ * Measurement hook.  mode 1: later calls enqueue only their dominant kernel (the
+ * key-streaming kernel) and skip the split merge / epilogue, so a benchmark can
+ * time that kernel alone with HIP events around a batch of launches; `out` is NOT
+ * produced in this mode.  mode 0 (the default) restores normal operation.
+ * Returns the previous mode.
  */
-void lra_set_profile_events(void* start_event, void* stop_event);
+int32_t lra_set_profile_mode(int32_t mode);
 
 #ifdef __cplusplus
 }

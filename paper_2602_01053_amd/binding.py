@@ -19,7 +19,7 @@ LRA_BF16, LRA_F32 = 0, 1
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
            "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch",
-           "lra_set_profile_events")
+           "lra_set_profile_mode")
 
 
 class LraShape(ctypes.Structure):
@@ -77,8 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.lra_set_decode_split_keys.argtypes = [i32]
     lib.lra_set_decode_prefetch.restype = i32
     lib.lra_set_decode_prefetch.argtypes = [i32]
-    lib.lra_set_profile_events.restype = None
-    lib.lra_set_profile_events.argtypes = [vp, vp]
+    lib.lra_set_profile_mode.restype = i32
+    lib.lra_set_profile_mode.argtypes = [i32]
     _lib = lib
     return lib
 
@@ -99,8 +99,8 @@ def lra_set_decode_prefetch(steps: int) -> int:
     return int(load_library().lra_set_decode_prefetch(int(steps)))
 
 
-def lra_set_profile_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
-    load_library().lra_set_profile_events(start_event, stop_event)
+def lra_set_profile_mode(mode: int) -> int:
+    return int(load_library().lra_set_profile_mode(int(mode)))
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:

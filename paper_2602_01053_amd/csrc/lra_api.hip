@@ -13,7 +13,7 @@ std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
 std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
 
-std::atomic<void*> g_ev_start{nullptr}, g_ev_stop{nullptr};
+std::atomic<int32_t> g_profile_mode{0};
 
 constexpr int kCUs = 256;  // MI355X
 
@@ -195,14 +195,12 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   p.is_prefill = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
-  hipEvent_t ev0 = static_cast<hipEvent_t>(g_ev_start.load()), ev1 = static_cast<hipEvent_t>(g_ev_stop.load());
-  if (ev0) (void)hipEventRecord(ev0, s);
   if (pl.mfma) {
     if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
   } else {
     if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   }
-  if (ev1) (void)hipEventRecord(ev1, s);
+  if (g_profile_mode.load() == 1) return LRA_OK;  // measurement: key-streaming kernel alone
   if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
 }
@@ -236,15 +234,12 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   p.adapter_index = adapter_index;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
-  hipEvent_t ev0 = static_cast<hipEvent_t>(g_ev_start.load()), ev1 = static_cast<hipEvent_t>(g_ev_stop.load());
-  if (ev0) (void)hipEventRecord(ev0, s);
   if (pl.mfma) {
     if (launch_prefill_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
-    if (ev1) (void)hipEventRecord(ev1, s);
     return LRA_OK;
   }
   if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
-  if (ev1) (void)hipEventRecord(ev1, s);
+  if (g_profile_mode.load() == 1) return LRA_OK;
   if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
 }
@@ -268,9 +263,6 @@ int32_t lra_set_decode_split_keys(int32_t keys) { return g_split_keys.exchange(k
 
 int32_t lra_set_decode_prefetch(int32_t steps) { return g_prefetch.exchange(steps >= 2 ? 2 : 1); }
 
-void lra_set_profile_events(void* start_event, void* stop_event) {
-  g_ev_start.store(start_event);
-  g_ev_stop.store(stop_event);
-}
+int32_t lra_set_profile_mode(int32_t mode) { return g_profile_mode.exchange(mode == 1 ? 1 : 0); }
 
 }  // extern "C"

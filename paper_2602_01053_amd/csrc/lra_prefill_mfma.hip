@@ -29,6 +29,8 @@ typedef float pf_f32x4 __attribute__((ext_vector_type(4)));
 typedef float pf_f32x2 __attribute__((ext_vector_type(2)));
 typedef short pf_s16x4 __attribute__((ext_vector_type(4)));
 typedef short pf_s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int pf_u32x4 __attribute__((ext_vector_type(4)));  // native vector: stays in registers
+typedef unsigned int pf_u32x2 __attribute__((ext_vector_type(2)));
 
 #define PF_LDS_AS(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -106,10 +108,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int32_t* bt = p.block_table + static_cast<int64_t>(t) * p.max_blocks_per_seq;
 
   // ---------------- tile staging: global -> registers -> LDS ----------------
-  struct Stage {
-    uint4 k[KV_LOADS], v[KV_LOADS], l[L_LOADS];
-  };
-  auto load_tile = [&](Stage& st, int j) {
+  pf_u32x4 st_k[KV_LOADS], st_v[KV_LOADS], st_l[L_LOADS];  // one tile ahead, in registers
+  auto load_tile = [&](int j) {
 #pragma unroll
     for (int i = 0; i < KV_LOADS; ++i) {
       const int f = i * 256 + tid;
@@ -123,27 +123,27 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         off = static_cast<int64_t>(tok) * p.kv_token_stride;
       }
       off += static_cast<int64_t>(hk) * p.kv_head_stride + ch * 8;
-      st.k[i] = *reinterpret_cast<const uint4*>(kb + off);
-      st.v[i] = *reinterpret_cast<const uint4*>(vb + off);
+      st_k[i] = *reinterpret_cast<const pf_u32x4*>(kb + off);
+      st_v[i] = *reinterpret_cast<const pf_u32x4*>(vb + off);
     }
 #pragma unroll
     for (int i = 0; i < L_LOADS; ++i) {
-      const int f = i * 256 + tid;
-      const int key = f / LCH, ch = f % LCH;
-      uint4 val = make_uint4(0u, 0u, 0u, 0u);
-      if (f < BN * LCH && ch * 8 < r) {
-        const int tok = min(j + key, n_t - 1);
-        int64_t lrow;
-        if (PAGED)
-          lrow = static_cast<int64_t>(bt[tok >> 4]) * 16 + (tok & 15);
-        else
-          lrow = tok;
-        val = *reinterpret_cast<const uint4*>(lr + lrow * r + ch * 8);
-      }
-      st.l[i] = val;
+      // every thread loads something valid (no branch around a load: a conditional load
+      // would force the compiler to wait for it on the spot); store_tile drops or zeroes
+      // what lies outside the tile or beyond the rank
+      const int f = min(i * 256 + tid, BN * LCH - 1);
+      const int key = f / LCH;
+      const int ch = min(f % LCH, (r - 1) >> 3);
+      const int tok = min(j + key, n_t - 1);
+      int64_t lrow;
+      if (PAGED)
+        lrow = static_cast<int64_t>(bt[tok >> 4]) * 16 + (tok & 15);
+      else
+        lrow = tok;
+      st_l[i] = *reinterpret_cast<const pf_u32x4*>(lr + lrow * r + ch * 8);
     }
   };
-  auto store_tile = [&](const Stage& st, unsigned char* buf) {
+  auto store_tile = [&](unsigned char* buf) {
     unsigned char* ks = buf;
     unsigned char* vs = buf + K_BYTES;
     unsigned char* ls = buf + 2 * K_BYTES;
@@ -151,23 +151,24 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     for (int i = 0; i < KV_LOADS; ++i) {
       const int f = i * 256 + tid;
       const int key = f / KCH, ch = f % KCH;
-      *reinterpret_cast<uint4*>(ks + key * (D * 2) + ((ch ^ (key & 7)) << 4)) = st.k[i];
-      *reinterpret_cast<uint4*>(vs + key * (D * 2) + ((ch ^ ((key & 3) << 1)) << 4)) = st.v[i];
+      *reinterpret_cast<pf_u32x4*>(ks + key * (D * 2) + ((ch ^ (key & 7)) << 4)) = st_k[i];
+      *reinterpret_cast<pf_u32x4*>(vs + key * (D * 2) + ((ch ^ ((key & 3) << 1)) << 4)) = st_v[i];
     }
 #pragma unroll
     for (int i = 0; i < L_LOADS; ++i) {
       const int f = i * 256 + tid;
       const int key = f / LCH, ch = f % LCH;
       if (f < BN * LCH) {
+        const bool live = ch * 8 < r;  // chunks beyond the rank are zero
         unsigned char* dst = ls + key * LS + ch * 16;  // rows are 8-byte aligned only
-        *reinterpret_cast<uint2*>(dst) = make_uint2(st.l[i].x, st.l[i].y);
-        *reinterpret_cast<uint2*>(dst + 8) = make_uint2(st.l[i].z, st.l[i].w);
+        const pf_u32x4 v = live ? st_l[i] : pf_u32x4{0u, 0u, 0u, 0u};
+        *reinterpret_cast<pf_u32x2*>(dst) = pf_u32x2{v[0], v[1]};
+        *reinterpret_cast<pf_u32x2*>(dst + 8) = pf_u32x2{v[2], v[3]};
       }
     }
   };
 
-  Stage st;
-  load_tile(st, 0);
+  load_tile(0);
 
   // ---------------- prologue: Q operands, Qt = Q B_K^T ----------------
   // qb[ks]: B operand of S^T: lane (row l32, k = 16ks + 8g2 + e)
@@ -248,9 +249,16 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = p.scale * 1.44269504088896340736f;
 
-  store_tile(st, smem);
+  store_tile(smem);
   __syncthreads();
 
+#ifdef LRA_PF_TIMING
+  long long tph[6] = {0, 0, 0, 0, 0, 0};
+  long long tprev = __builtin_readcyclecounter();
+#define PF_MARK(i) { const long long tn = __builtin_readcyclecounter(); tph[i] += tn - tprev; tprev = tn; }
+#else
+#define PF_MARK(i)
+#endif
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int j = tile * BN;
     unsigned char* buf = smem + (tile & 1) * STAGE;
@@ -258,7 +266,10 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     const unsigned char* vs_l = buf + K_BYTES;
     const unsigned char* ls_l = buf + 2 * K_BYTES;
     const bool more = tile + 1 < n_tiles;
-    if (more) load_tile(st, j + BN);
+    // unconditional: after the last tile this re-reads it (a conditional load would be
+    // waited for right where it is issued)
+    load_tile(more ? j + BN : j);
+    PF_MARK(0)
 
     // S^T for the two 32-key halves of the tile
     pf_f32x16 s[2];
@@ -282,6 +293,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
                                                         s[kt], 0, 0, 0);
       }
     }
+    PF_MARK(1)
     // causal mask + online softmax.  Element (kt, i) of this lane is key
     // j + 32kt + 8(i/4) + 4g2 + i%4 of row l32.
     if (j + BN - 1 > base_vis + q0 + wave * 32) {  // some row of this wave does not see the whole tile
@@ -324,6 +336,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         pb[kt][h2] = pf_as_bf16x8(make_uint4(pf_pack2(e[8 * h2 + 0], e[8 * h2 + 1]), pf_pack2(e[8 * h2 + 2], e[8 * h2 + 3]),
                                              pf_pack2(e[8 * h2 + 4], e[8 * h2 + 5]), pf_pack2(e[8 * h2 + 6], e[8 * h2 + 7])));
     }
+    PF_MARK(2)
     // O^T += V^T P^T ; Olr^T += L^T P^T, one 16-key k-step at a time.
     // k-step (kt, h2), element e <-> key 32kt + 16h2 + 8(e/4) + 4g2 + e%4.
 #pragma unroll
@@ -348,9 +361,18 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         }
       }
 
-    if (more) store_tile(st, smem + ((tile + 1) & 1) * STAGE);
+    PF_MARK(3)
+    if (more) store_tile(smem + ((tile + 1) & 1) * STAGE);
+    PF_MARK(4)
     __syncthreads();
+    PF_MARK(5)
   }
+#ifdef LRA_PF_TIMING
+  if (blockIdx.x == 300 && lane == 0) {
+    for (int i = 0; i < 6; ++i) p.part_ml[wave * 8 + i] = static_cast<float>(tph[i]);
+    p.part_ml[wave * 8 + 6] = static_cast<float>(n_tiles);
+  }
+#endif
 
   // ---------------- epilogue: O^T += B_V^T Olr^T, O /= l, store ----------------
   l_run += pf_partner32(l_run);
