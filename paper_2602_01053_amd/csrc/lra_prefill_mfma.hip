@@ -59,6 +59,15 @@ __device__ __forceinline__ float pf_partner32(float v) {
   return (threadIdx.x & 32) ? x : y;
 }
 
+// LDS swizzles (XOR on the 16-byte chunk index of a row).  The LDS of this chip serves
+// 256 bytes per clock (64 banks): a ds_read_b128 is conflict-free when 16 consecutive
+// lanes cover 16 different chunk positions of that 256-byte window, a ds_read_b64_tr_b16
+// when the eight 32-byte pieces of 32 consecutive lanes do.
+template <int D> __device__ __forceinline__ int pf_swz_k(int key) { return D == 128 ? (key & 15) : ((key >> 1) & 7); }
+template <int D> __device__ __forceinline__ int pf_swz_v(int key) {
+  return D == 128 ? ((key & 3) << 2) : (((key >> 1) & 1) << 2);
+}
+
 template <int D, int RP, bool PAGED>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   constexpr int BM = 128, BN = 64;
@@ -151,8 +160,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     for (int i = 0; i < KV_LOADS; ++i) {
       const int f = i * 256 + tid;
       const int key = f / KCH, ch = f % KCH;
-      *reinterpret_cast<pf_u32x4*>(ks + key * (D * 2) + ((ch ^ (key & 7)) << 4)) = st_k[i];
-      *reinterpret_cast<pf_u32x4*>(vs + key * (D * 2) + ((ch ^ ((key & 3) << 1)) << 4)) = st_v[i];
+      *reinterpret_cast<pf_u32x4*>(ks + key * (D * 2) + ((ch ^ pf_swz_k<D>(key)) << 4)) = st_k[i];
+      *reinterpret_cast<pf_u32x4*>(vs + key * (D * 2) + ((ch ^ pf_swz_v<D>(key)) << 4)) = st_v[i];
     }
 #pragma unroll
     for (int i = 0; i < L_LOADS; ++i) {
@@ -213,25 +222,18 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   }
 
   // ---------------- per-lane LDS read offsets ----------------
-  // K rows as A operand of S^T (ds_read_b128): key = 32kt + l32, logical chunk 2ks + g2
-  int k_rd[4];  // index (2ks + g2) & 7 pattern: the swizzle touches chunk bits 0..2 only
-  {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) k_rd[q] = l32 * (D * 2) + ((((2 * q + g2) ^ (l32 & 7)) & 7) << 4);
-  }
+  // K rows as A operand of S^T (ds_read_b128): key = 32kt + l32, logical chunk c = 2ks + g2
+  // lives at chunk c ^ swizzle(key); row offset and swizzle occupy disjoint address bits,
+  // so the address is k_pre ^ (c << 4) (+ kt * 32 rows)
+  const int k_pre = l32 * (D * 2) + (pf_swz_k<D>(l32) << 4);
   // V^T as A operand of O^T (ds_read_b64_tr_b16): lane a of a 16-lane group addresses
-  // row 4*g2 + a/4 (+ 8 for the second read) of the 16-key k-step, 8 bytes at d = dbase + 4(a%4)
+  // row 4*g2 + a/4 (+ 8 for the second read) of the 16-key k-step, 8 bytes at
+  // d = 32b + 16dsel + 4(a%4): chunk 4b + 2dsel + c0, half sub; the swizzle flips chunk
+  // bits 2..3, so the address is v_pre ^ (b << 6) (+ row offsets)
   const int a16 = lane & 15;
   const int dsel = (lane >> 4) & 1;   // which 16 of the 32 output rows this 16-lane group produces
   const int vrow = 4 * g2 + (a16 >> 2);
-  // byte offset in the row: 64b + 32dsel + 8(a16 & 3), i.e. chunk 4b + 2dsel + c0, half sub;
-  // the swizzle (row & 3) << 1 flips chunk bits 1..2, so the pattern depends on b & 1 only
-  int v_rd[2];
-  {
-    const int u = vrow & 3, c0 = (a16 & 3) >> 1, sub = (a16 & 1) * 8;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) v_rd[q] = vrow * (D * 2) + ((2 * ((2 * q + dsel) ^ u) + c0) << 4) + sub;
-  }
+  const int v_pre = vrow * (D * 2) + ((((a16 & 3) >> 1) + 2 * dsel + pf_swz_v<D>(vrow)) << 4) + (a16 & 1) * 8;
   // L rows as A operand of S^T: two 8-byte pieces per k-step; L^T as A operand of Olr^T
   const int l_rd = l32 * LS + g2 * 8;           // + ks'*32 (+16 for the second piece) + kt*32*LS
   const int lt_rd = vrow * LS + dsel * 32 + (a16 & 3) * 8;  // + b*64 ; + 16s... rows
@@ -279,9 +281,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       for (int i = 0; i < 16; ++i) s[kt][i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        // chunk 2ks + g2: bits 0..2 go through the swizzle pattern, bit 3 is an offset of 128 bytes
         const pf_bf16x8 a = pf_as_bf16x8(
-            *reinterpret_cast<const uint4*>(ks_l + k_rd[ks & 3] + (ks >> 2) * 128 + kt * 32 * D * 2));
+            *reinterpret_cast<const uint4*>(ks_l + (k_pre ^ ((2 * ks + g2) << 4)) + kt * 32 * D * 2));
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[ks], s[kt], 0, 0, 0);
       }
 #pragma unroll
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         const int rowoff = (32 * kt + 16 * h2) * (D * 2);
 #pragma unroll
         for (int b = 0; b < DB; ++b) {
-          const unsigned char* src = vs_l + v_rd[b & 1] + (b >> 1) * 128 + rowoff;
+          const unsigned char* src = vs_l + (v_pre ^ (b << 6)) + rowoff;
           const pf_bf16x8 a = pf_join(pf_read_tr16(src), pf_read_tr16(src + 8 * (D * 2)));
           o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][h2], o_acc[b], 0, 0, 0);
         }
