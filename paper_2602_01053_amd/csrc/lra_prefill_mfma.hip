@@ -83,6 +83,10 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   constexpr int K_BYTES = BN * D * 2;
   constexpr int L_BYTES = (BN * LS + 15) / 16 * 16;
   constexpr int STAGE = 2 * K_BYTES + L_BYTES;
+  // With a half-empty last 32-row block of Olr^T (rank 16 or 48 after padding), one of its
+  // idle rows carries a column of ones appended to the L tile, so the matrix core also
+  // accumulates the softmax row sums.
+  constexpr bool ONES_ROW = (RP % 32) != 0;
 
   __shared__ __align__(16) unsigned char smem[2 * STAGE];
 
@@ -118,20 +122,52 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 
   // ---------------- tile staging: global -> registers -> LDS ----------------
   pf_u32x4 st_k[KV_LOADS], st_v[KV_LOADS], st_l[L_LOADS];  // one tile ahead, in registers
+  // Contiguous cache: raw buffer resources over this kv head's rows; the per-thread byte
+  // offsets are loop invariant and the tile offset travels in a scalar register, so a
+  // tile costs no address arithmetic.  Rows past the sequence read as zero (they are
+  // masked anyway).
+  __amdgpu_buffer_rsrc_t rs_k, rs_v, rs_l;
+  uint32_t kv_voff[KV_LOADS], l_voff[L_LOADS];
+  const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u, r2 = static_cast<uint32_t>(r) * 2u;
+  if (!PAGED) {
+    const uint32_t kv_bytes = static_cast<uint32_t>(n_t - 1) * ts2 + D * 2;
+    rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kb) + static_cast<int64_t>(hk) * p.kv_head_stride, 0,
+                                            static_cast<int>(kv_bytes), 0x00020000);
+    rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vb) + static_cast<int64_t>(hk) * p.kv_head_stride, 0,
+                                            static_cast<int>(kv_bytes), 0x00020000);
+    rs_l = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(lr), 0, static_cast<int>(static_cast<uint32_t>(n_t) * r2),
+                                            0x00020000);
+#pragma unroll
+    for (int i = 0; i < KV_LOADS; ++i) {
+      const int f = i * 256 + tid;
+      kv_voff[i] = static_cast<uint32_t>(f / KCH) * ts2 + (f % KCH) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < L_LOADS; ++i) {
+      const int f = min(i * 256 + tid, BN * LCH - 1);
+      l_voff[i] = static_cast<uint32_t>(f / LCH) * r2 + min(f % LCH, (r - 1) >> 3) * 16;
+    }
+  }
   auto load_tile = [&](int j) {
+    if (!PAGED) {
+#pragma unroll
+      for (int i = 0; i < KV_LOADS; ++i) {
+        st_k[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_k, kv_voff[i], static_cast<uint32_t>(j) * ts2, 0);
+        st_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_v, kv_voff[i], static_cast<uint32_t>(j) * ts2, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < L_LOADS; ++i)
+        st_l[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_l, l_voff[i], static_cast<uint32_t>(j) * r2, 0);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < KV_LOADS; ++i) {
       const int f = i * 256 + tid;
       const int key = f / KCH, ch = f % KCH;
       const int tok = min(j + key, n_t - 1);  // clamped: masked later, never out of the sequence
-      int64_t off;
-      if (PAGED) {
-        const int blk = bt[tok >> 4];
-        off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(tok & 15) * p.kv_token_stride;
-      } else {
-        off = static_cast<int64_t>(tok) * p.kv_token_stride;
-      }
-      off += static_cast<int64_t>(hk) * p.kv_head_stride + ch * 8;
+      const int blk = bt[tok >> 4];
+      const int64_t off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(tok & 15) * p.kv_token_stride +
+                          static_cast<int64_t>(hk) * p.kv_head_stride + ch * 8;
       st_k[i] = *reinterpret_cast<const pf_u32x4*>(kb + off);
       st_v[i] = *reinterpret_cast<const pf_u32x4*>(vb + off);
     }
@@ -144,11 +180,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       const int key = f / LCH;
       const int ch = min(f % LCH, (r - 1) >> 3);
       const int tok = min(j + key, n_t - 1);
-      int64_t lrow;
-      if (PAGED)
-        lrow = static_cast<int64_t>(bt[tok >> 4]) * 16 + (tok & 15);
-      else
-        lrow = tok;
+      const int64_t lrow = static_cast<int64_t>(bt[tok >> 4]) * 16 + (tok & 15);
       st_l[i] = *reinterpret_cast<const pf_u32x4*>(lr + lrow * r + ch * 8);
     }
   };
@@ -236,7 +268,6 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int v_pre = vrow * (D * 2) + ((((a16 & 3) >> 1) + 2 * dsel + pf_swz_v<D>(vrow)) << 4) + (a16 & 1) * 8;
   // L rows as A operand of S^T: two 8-byte pieces per k-step; L^T as A operand of Olr^T
   const int l_rd = l32 * LS + g2 * 8;           // + ks'*32 (+16 for the second piece) + kt*32*LS
-  const int lt_rd = vrow * LS + dsel * 32 + (a16 & 3) * 8;  // + b*64 ; + 16s... rows
 
   // ---------------- main loop ----------------
   pf_f32x16 o_acc[DB], lr_acc[RB];
@@ -251,6 +282,10 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = p.scale * 1.44269504088896340736f;
 
+  if (ONES_ROW && tid < 2 * BN) {  // pad of every L row of both buffers: bf16 [1, 0, 0, 0]
+    unsigned char* dst = smem + (tid / BN) * STAGE + 2 * K_BYTES + (tid % BN) * LS + RP * 2;
+    *reinterpret_cast<pf_u32x2*>(dst) = pf_u32x2{0x00003f80u, 0u};
+  }
   store_tile(smem);
   __syncthreads();
 
@@ -330,7 +365,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         e[i] = __builtin_amdgcn_exp2f(fmaf(s[kt][i], sc, nm));
-        l_run += e[i];
+        if (!ONES_ROW) l_run += e[i];
       }
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2)
@@ -353,10 +388,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         }
 #pragma unroll
         for (int b = 0; b < RB; ++b) {
-          // rows rho = 32b + 16dsel + a16 of L^T; lanes whose rho lies beyond the padded rank
-          // re-read block 0 (their output rows are never used)
-          const int boff = (b * 64 + dsel * 32 < RP * 2) ? b * 64 : -dsel * 32;
-          const unsigned char* src = ls_l + lt_rd + boff + (32 * kt + 16 * h2) * LS;
+          // rows rho = 32b + 16dsel + a16 of L^T.  In a half-empty last block the upper 16
+          // lanes read the pad of the row instead ([1, 0, 0, 0]): output row 32b + 16 then
+          // accumulates the row sums; the rows after it are never used.
+          const bool upper_idle = ONES_ROW && b == RB - 1;
+          const int col = (upper_idle && dsel) ? RP * 2 : b * 64 + dsel * 32 + (a16 & 3) * 8;
+          const unsigned char* src = ls_l + vrow * LS + col + (32 * kt + 16 * h2) * LS;
           const pf_bf16x8 a = pf_join(pf_read_tr16(src), pf_read_tr16(src + 8 * LS));
           lr_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][h2], lr_acc[b], 0, 0, 0);
         }
@@ -376,7 +413,14 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 #endif
 
   // ---------------- epilogue: O^T += B_V^T Olr^T, O /= l, store ----------------
-  l_run += pf_partner32(l_run);
+  if (ONES_ROW) {
+    // row sums sit in register 8 (rho = 32(RB-1) + 16) of the lanes with g2 == 0
+    const float mine = lr_acc[RB - 1][8];
+    const float other = pf_partner32(mine);
+    l_run = g2 == 0 ? mine : other;
+  } else {
+    l_run += pf_partner32(l_run);
+  }
   if (p.b_v != nullptr) {
     const int64_t ldb = static_cast<int64_t>(Hkv) * D;
     const bf16_t* bv = static_cast<const bf16_t*>(p.b_v) + static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D;
