@@ -148,16 +148,25 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       l_voff[i] = static_cast<uint32_t>(f / LCH) * r2 + min(f % LCH, (r - 1) >> 3) * 16;
     }
   }
-  auto load_tile = [&](int j) {
-    if (!PAGED) {
+  // part q of 4 of the next tile's loads (contiguous cache): spread over the tile's
+  // phases so that the eight waves of a CU do not hit the vector memory queue together
+  auto load_part = [&](int j, int q) {
 #pragma unroll
-      for (int i = 0; i < KV_LOADS; ++i) {
+    for (int i = 0; i < KV_LOADS; ++i)
+      if (i * 4 / KV_LOADS == q) {
         st_k[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_k, kv_voff[i], static_cast<uint32_t>(j) * ts2, 0);
         st_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_v, kv_voff[i], static_cast<uint32_t>(j) * ts2, 0);
       }
+    if (q == 3) {
 #pragma unroll
       for (int i = 0; i < L_LOADS; ++i)
         st_l[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_l, l_voff[i], static_cast<uint32_t>(j) * r2, 0);
+    }
+  };
+  auto load_tile = [&](int j) {
+    if (!PAGED) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) load_part(j, q);
       return;
     }
 #pragma unroll
@@ -305,7 +314,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     const bool more = tile + 1 < n_tiles;
     // unconditional: after the last tile this re-reads it (a conditional load would be
     // waited for right where it is issued)
-    load_tile(more ? j + BN : j);
+    const int jn = more ? j + BN : j;
+    if (PAGED) load_tile(jn); else load_part(jn, 0);
     PF_MARK(0)
 
     // S^T for the two 32-key halves of the tile
@@ -329,6 +339,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
                                                         s[kt], 0, 0, 0);
       }
     }
+    if (!PAGED) load_part(jn, 1);
     PF_MARK(1)
     // causal mask + online softmax.  Element (kt, i) of this lane is key
     // j + 32kt + 8(i/4) + 4g2 + i%4 of row l32.
@@ -372,6 +383,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         pb[kt][h2] = pf_as_bf16x8(make_uint4(pf_pack2(e[8 * h2 + 0], e[8 * h2 + 1]), pf_pack2(e[8 * h2 + 2], e[8 * h2 + 3]),
                                              pf_pack2(e[8 * h2 + 4], e[8 * h2 + 5]), pf_pack2(e[8 * h2 + 6], e[8 * h2 + 7])));
     }
+    if (!PAGED) load_part(jn, 2);
     PF_MARK(2)
     // O^T += V^T P^T ; Olr^T += L^T P^T, one 16-key k-step at a time.
     // k-step (kt, h2), element e <-> key 32kt + 16h2 + 8(e/4) + 4g2 + e%4.
@@ -379,6 +391,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
+        if (!PAGED && kt == 1 && h2 == 0) load_part(jn, 3);
         const int rowoff = (32 * kt + 16 * h2) * (D * 2);
 #pragma unroll
         for (int b = 0; b < DB; ++b) {
