@@ -153,7 +153,9 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ln = lane & 15, lg = lane >> 4;
-  const int split = blockIdx.x, h = blockIdx.y;
+  // kv head is the fastest grid index: workgroups go round-robin over the XCDs, so with 8 kv
+  // heads all workgroups of a head run on one XCD and share Q and B_K in its L2
+  const int h = blockIdx.x, split = blockIdx.y;
   const int t = blockIdx.z / p.row_groups;
   const int rg = blockIdx.z - t * p.row_groups;
   const int n_t = min(p.seq_lens[t], p.max_seq_len);
@@ -587,7 +589,7 @@ int decode_mfma_row_tiles(int rows_needed) { return rows_needed <= 16 ? 1 : 2; }
 
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s) {
   (void)prefetch;
-  dim3 grid(p.n_splits, p.n_kv_heads, p.n_seqs * p.row_groups);
+  dim3 grid(p.n_kv_heads, p.n_splits, p.n_seqs * p.row_groups);
   const int rp = p.rank <= 32 ? 32 : 64;
   const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (rp == 64 ? 1 : 0);
   switch (key) {

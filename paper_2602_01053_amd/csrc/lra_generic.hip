@@ -117,13 +117,16 @@ constexpr int kMergeUnroll = 8;  // splits per thread and pass
 
 template <typename T>
 __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
-  const int row = blockIdx.x;
+  // Workgroups go round-robin over the XCDs; numbering them kv head first puts the rows of
+  // kv head h on the XCD(s) where the streaming kernel wrote that head's partial states.
+  const int Hq = p.n_q_heads, d = p.head_dim, r = p.rank;
+  const int h = blockIdx.x % p.n_kv_heads;
+  const int rest = blockIdx.x / p.n_kv_heads;
+  const int tok = rest / p.group;
+  const int g = h * p.group + rest % p.group;
+  const int row = tok * Hq + g;
   const int c = threadIdx.x, gq = threadIdx.y;
   const int tid = gq * 128 + c;
-  const int Hq = p.n_q_heads, d = p.head_dim, r = p.rank;
-  const int tok = row / Hq;
-  const int g = row - tok * Hq;
-  const int h = g / p.group;
   int a, n_vis;
   if (p.is_prefill) {
     a = p.adapter_index;
