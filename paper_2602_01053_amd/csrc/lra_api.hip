@@ -83,13 +83,23 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     pl.row_groups = (rows_needed + 16 * pl.row_tiles - 1) / (16 * pl.row_tiles);
     tile = 128;        // 4 waves x 32 keys
     work = static_cast<int64_t>(c->n_seqs) * sh->n_kv_heads * pl.row_groups;
-    want = kCUs * 2;
+    want = kCUs;
   } else {
     work = pl.rows;
     want = kCUs * 8;
   }
   int split_keys = g_split_keys.load();
-  if (split_keys <= 0) {
+  if (split_keys <= 0 && pl.mfma) {
+    // Measured on MI355X: one sequence runs best with about one workgroup per CU (the
+    // per-workgroup prologue is not amortised otherwise); a ragged batch wants about four
+    // times as many, equal-sized pieces so the CUs stay balanced.  A batch is assumed to be
+    // half as long on average as its longest sequence.
+    const bool batch = c->n_seqs > 1;
+    const int64_t key_heads = work * c->max_seq_len / (batch ? 2 : 1);
+    const int64_t wgs = batch ? kCUs * 4 : kCUs;
+    split_keys = static_cast<int>((key_heads + wgs - 1) / wgs);
+    if (split_keys > c->max_seq_len) split_keys = c->max_seq_len;
+  } else if (split_keys <= 0) {
     int64_t ns = (want + work - 1) / work;
     const int64_t max_ns = (c->max_seq_len + tile - 1) / tile;
     ns = ns < 1 ? 1 : (ns > max_ns ? max_ns : ns);

@@ -183,35 +183,39 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
 
   // ===================== per-lane constants of the tile traffic =====================
+  // The LDS of this chip serves 256 bytes per clock (64 banks): a ds_read_b128 is free of
+  // conflicts when 16 consecutive lanes hit 16 different 16-byte positions of that window,
+  // a ds_read_b64_tr_b16 when the eight 32-byte pieces of 32 consecutive lanes do.  Rows of
+  // 256 bytes (d = 128) all start at position 0, rows of 128 bytes alternate halves; the XOR
+  // swizzles below (on the 16-byte chunk index of a row) spread them accordingly:
+  //   K (b128, 16 rows per clock)      chunk ^ (row & 15)            | chunk ^ ((row >> 1) & 7)
+  //   V (tr_b64, 8 rows per clock)     chunk ^ ((row & 7) << 1)      | chunk ^ (((row >> 1) & 3) << 1)
+  auto swz_k = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
+  auto swz_v = [](int row) { return D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1); };
   // global -> LDS: lane l of load i lands at LDS row i*ROWS + l/CH, physical chunk l%CH,
-  // and therefore fetches logical chunk (l%CH) ^ swizzle(row).
-  uint32_t k_voff[2], v_voff, l_voff;
+  // and therefore fetches logical chunk (l%CH) ^ swizzle(row).  The swizzle of row
+  // i*ROWS + l/CH repeats with period 16/KROWS (K) and 8/KROWS (V) in i.
+  constexpr int KPER = KROWS == 4 ? 4 : 2, VPER = KROWS == 4 ? 2 : 1;
+  uint32_t k_voff[KPER], v_voff[VPER], l_voff;
   {
     const int rr = lane / KCH, pc = lane % KCH;
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      const int row = par * KROWS + rr;  // the parity of the load index matters only when KROWS == 4
-      k_voff[par] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ (row & 7)) << 4);
-    }
-    v_voff = static_cast<uint32_t>(rr) * ts2 + ((pc ^ ((rr & 3) << 1)) << 4);
+    for (int q = 0; q < KPER; ++q) k_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_k(q * KROWS + rr)) << 4);
+#pragma unroll
+    for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
     const int lrow = lane / RCH, lpc = lane % RCH;
     const int lch = lpc ^ ((lrow >> LSW_SHIFT) & (RCH - 1));
     l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * r2 + (lch << 4) : kOob;
   }
-  // LDS -> MFMA operands (byte offsets inside the tile regions)
-  int k_rd[2];  // K rows as A operand of S^T: [ks & 1], plus (ks >> 1)*128 + tt*16*2D
-  {
-    const int x = (lg ^ (ln & 3)) | (ln & 4);
-    k_rd[0] = ln * (2 * D) + (x << 4);
-    k_rd[1] = k_rd[0] ^ 64;
-  }
+  // LDS -> MFMA operands (byte offsets inside the tile regions).
+  // K rows as A operand of S^T: key = 16tt + ln, logical chunk 4ks + lg at chunk ^ swz_k(key):
+  // row offset, swizzle and lg sit in disjoint address bits, so the address is
+  // k_pre ^ (ks << 6) + tt * 16 rows.
+  const int k_pre = ln * (2 * D) + ((swz_k(ln) ^ lg) << 4);
+  // V^T as A operand of O^T: this lane addresses row ka (+16tt) of the tile, logical chunk
+  // 2b + c0 (+ half sub): address v_pre ^ (b << 5) + tt * 16 rows.
   const int ka = 4 * lg + (ln >> 2);  // row (within a 16-key tile) this lane addresses in transpose reads
-  int v_rd[4];                        // V^T as A operand: [b & 3], plus (b >> 2)*128 + tt*16*2D
-  {
-    const int u = ka & 3, c0 = (ln & 3) >> 1, sub = (ln & 1) * 8;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) v_rd[q] = ka * (2 * D) + ((2 * (q ^ u) + c0) << 4) + sub;
-  }
+  const int v_pre = ka * (2 * D) + ((swz_v(ka) + ((ln & 3) >> 1)) << 4) + (ln & 1) * 8;
   int l_rd[RKS][2];  // L rows as A operand of S^T: two 8-byte pieces per k-step
   int lt_rd[RB];     // L^T as A operand of Olr^T
   {
@@ -243,15 +247,28 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   }
   const int32_t* bt = p.block_table + static_cast<int64_t>(t) * p.max_blocks_per_seq;
 
+  // Paged cache: the two physical block ids of a step are fetched one step ahead (scalar
+  // loads), so the table lookup is off the path that requests the tile.
+  int blk_next[2] = {0, 0};
+  auto fetch_block_ids = [&](int j) {
+    if (PAGED) {
+      const int nb_last = (n_t - 1) >> 4;
+      blk_next[0] = bt[min(j >> 4, nb_last)];
+      blk_next[1] = bt[min((j >> 4) + 1, nb_last)];
+    }
+  };
+  fetch_block_ids(jw0);
+
   // ---- HBM -> LDS for the 32-key step starting at token j ----
   auto issue_tile = [&](int j) {
     if (PAGED) {
-      const int nb_last = (n_t - 1) >> 4;
       const int64_t hoff = static_cast<int64_t>(h) * p.kv_head_stride;
+      const int blk_cur[2] = {blk_next[0], blk_next[1]};
+      fetch_block_ids(j + 32);
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         const int jb = j + 16 * half;
-        const int blk = bt[min(jb >> 4, nb_last)];
+        const int blk = blk_cur[half];
         const int nv = max(0, min(16, jw1 - jb));  // slots of this block inside the wave's range
         const uint32_t kv_bytes = nv > 0 ? static_cast<uint32_t>(nv - 1) * ts2 + D * 2 : 0u;
         const __amdgpu_buffer_rsrc_t pk = make_rsrc(kb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
@@ -261,8 +278,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 #pragma unroll
         for (int i = 0; i < KVL / 2; ++i) {
           const int ii = half * (KVL / 2) + i;
-          buf_load16_to_lds(pk, ks_lds + ii * 1024, k_voff[KROWS == 4 ? (ii & 1) : 0], i * KROWS * ts2);
-          buf_load16_to_lds(pv, vs_lds + ii * 1024, v_voff, i * KROWS * ts2);
+          buf_load16_to_lds(pk, ks_lds + ii * 1024, k_voff[ii % KPER], i * KROWS * ts2);
+          buf_load16_to_lds(pv, vs_lds + ii * 1024, v_voff[ii % VPER], i * KROWS * ts2);
         }
 #pragma unroll
         for (int i = 0; i < LL / 2; ++i) {
@@ -274,8 +291,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
       const uint32_t s0 = static_cast<uint32_t>(j - jw0);
 #pragma unroll
       for (int i = 0; i < KVL; ++i) {
-        buf_load16_to_lds(rs_k, ks_lds + i * 1024, k_voff[KROWS == 4 ? (i & 1) : 0], (s0 + i * KROWS) * ts2);
-        buf_load16_to_lds(rs_v, vs_lds + i * 1024, v_voff, (s0 + i * KROWS) * ts2);
+        buf_load16_to_lds(rs_k, ks_lds + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
+        buf_load16_to_lds(rs_v, vs_lds + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
       }
 #pragma unroll
       for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * r2);
@@ -402,7 +419,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
       for (int rt = 0; rt < RT; ++rt) s[tt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = as_bf16x8(lds_read16(ks_lds + k_rd[ks & 1] + (ks >> 1) * 128 + tt * 32 * D));
+        const bf16x8 a = as_bf16x8(lds_read16(ks_lds + (k_pre ^ (ks << 6)) + tt * 32 * D));
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
           s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[rt][ks], s[tt][rt], 0, 0, 0);
@@ -460,7 +477,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     // O^T += V^T P^T ; Olr^T += L^T P^T
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
-      const unsigned char* src = vs_lds + v_rd[b & 3] + (b >> 2) * 128;
+      const unsigned char* src = vs_lds + (v_pre ^ (b << 5));
       const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 32 * D));
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)

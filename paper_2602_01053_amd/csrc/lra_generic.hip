@@ -112,10 +112,9 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
 // the kernel costs about two memory round trips.  Groups are added in a fixed
 // order: the result does not depend on which workgroup of the first kernel
 // finished first.
-constexpr int kMergeGroups = 8;
 constexpr int kMergeUnroll = 8;  // splits per thread and pass
 
-template <typename T>
+template <typename T, int kMergeGroups>
 __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   // Workgroups go round-robin over the XCDs; numbering them kv head first puts the rows of
   // kv head h on the XCD(s) where the streaming kernel wrote that head's partial states.
@@ -132,10 +131,18 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
     a = p.adapter_index;
     n_vis = min(p.seq_lens[p.seq_index], p.max_seq_len) - p.n_new + tok + 1;
   } else {
-    int t = 0;
-    while (t + 1 < p.n_seqs && p.seq_query_start[t + 1] <= tok) ++t;
+    // the sequence that owns this query: every thread tests some sequences at once (one
+    // memory round trip instead of a dependent walk along seq_query_start)
+    __shared__ int seq_of_row;
+    if (p.n_seqs == 1) {
+      if (tid == 0) seq_of_row = 0;
+    } else {
+      for (int t = tid; t < p.n_seqs; t += 128 * kMergeGroups)
+        if (p.seq_query_start[t] <= tok && tok < p.seq_query_start[t + 1]) seq_of_row = t;
+    }
+    __syncthreads();
     a = p.query_adapter[tok];
-    n_vis = min(p.seq_lens[t], p.max_seq_len);
+    n_vis = min(p.seq_lens[seq_of_row], p.max_seq_len);
   }
   // splits that start at or past this row's last visible key were never written
   const int ns = min(p.n_splits, (n_vis + p.split_keys - 1) / p.split_keys);
@@ -239,12 +246,26 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
   return hipGetLastError();
 }
 
-hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s) {
-  dim3 grid(rows), block(128, kMergeGroups);
-  if (is_bf16)
-    hipLaunchKernelGGL(merge_kernel<bf16_t>, grid, block, 0, s, p);
+template <typename T>
+static void launch_merge_t(const Params& p, int rows, hipStream_t s) {
+  // enough 128-thread groups that one pass of kMergeUnroll splits per thread covers the splits
+  const int groups = (p.n_splits + kMergeUnroll - 1) / kMergeUnroll;
+  dim3 grid(rows);
+  if (groups <= 1)
+    hipLaunchKernelGGL((merge_kernel<T, 1>), grid, dim3(128, 1), 0, s, p);
+  else if (groups <= 2)
+    hipLaunchKernelGGL((merge_kernel<T, 2>), grid, dim3(128, 2), 0, s, p);
+  else if (groups <= 4)
+    hipLaunchKernelGGL((merge_kernel<T, 4>), grid, dim3(128, 4), 0, s, p);
   else
-    hipLaunchKernelGGL(merge_kernel<float>, grid, block, 0, s, p);
+    hipLaunchKernelGGL((merge_kernel<T, 8>), grid, dim3(128, 8), 0, s, p);
+}
+
+hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s) {
+  if (is_bf16)
+    launch_merge_t<bf16_t>(p, rows, s);
+  else
+    launch_merge_t<float>(p, rows, s);
   return hipGetLastError();
 }
 
