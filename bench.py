@@ -85,13 +85,17 @@ def _load_traffic(name):
         return None
 
 
-def bench_decode(args, torch, lra, workloads):
+def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None):
+    """Times one decode configuration.  Caches smaller than COLD_BYTES are rotated over
+    enough copies that every step streams from HBM."""
     from paper_2602_01053_amd.runner import DeviceWorkload
+    steps = steps or args.steps
+    warmup = warmup or args.warmup
     dev = torch.device("cuda:0")
-    w = workloads.config(2)
+    w = workloads.config(index)
     alg_bytes = w.algorithmic_bytes()
-    cache_bytes = 2 * w.k_base.numel() * 2 + w.l.numel() * 2
-    n_copies = int(math.ceil(COLD_BYTES / cache_bytes)) + 1
+    cache_bytes = (2 * w.k_base.numel() + w.l.numel()) * w.k_base.element_size()
+    n_copies = 1 if cache_bytes >= COLD_BYTES else int(math.ceil(COLD_BYTES / cache_bytes)) + 1
     base = DeviceWorkload(w, dev)
     base.alloc_workspace()
     copies = [base]
@@ -99,7 +103,7 @@ def bench_decode(args, torch, lra, workloads):
         c = DeviceWorkload.__new__(DeviceWorkload)
         c.__dict__.update(base.__dict__)
         c.k_base, c.v_base, c.l = base.k_base.clone(), base.v_base.clone(), base.l.clone()
-        c.cache = lra.make_cache(c.k_base, c.v_base, c.l, c.seq_lens, max(w.seq_lens), None)
+        c.cache = lra.make_cache(c.k_base, c.v_base, c.l, c.seq_lens, max(w.seq_lens), c.block_table)
         copies.append(c)
 
     def run(n_steps, cold):
@@ -107,18 +111,36 @@ def bench_decode(args, torch, lra, workloads):
             copies[i % n_copies if cold else 0].decode()
 
     def timed(n_steps, cold):
-        run(args.warmup, cold)
+        run(warmup, cold)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         run(n_steps, cold)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / n_steps
 
-    sec_cold = timed(args.steps, True)
-    sec_hot = timed(args.steps, False)
-    out = {"cold": kernel_seconds(lra, torch, lambda i: copies[i % n_copies].decode(), args.steps),
-           "hot": kernel_seconds(lra, torch, lambda i: copies[0].decode(), args.steps)}
+    sec_cold = timed(steps, True)
+    sec_hot = timed(steps, False)
+    out = {"cold": kernel_seconds(lra, torch, lambda i: copies[i % n_copies].decode(), steps),
+           "hot": kernel_seconds(lra, torch, lambda i: copies[0].decode(), steps)}
     return w, alg_bytes, sec_cold, sec_hot, out, n_copies
+
+
+def other_decode_workloads(args, torch, lra, workloads):
+    """The two larger decode configurations (8 agents x 32768 tokens, r = 64; ragged paged
+    batch of 16 x 4 queries), reported next to the headline workload."""
+    rows = []
+    for index in (4, 5):
+        w, alg, sec_cold, _, ksec, n_copies = bench_decode(args, torch, lra, workloads, index,
+                                                           steps=max(20, args.steps // 10),
+                                                           warmup=max(5, args.warmup // 10))
+        rows.append({"workload": w.name, "algorithmic_bytes": alg, "cache_copies": n_copies,
+                     "value": round(alg / sec_cold / 1e9, 1), "unit": "GB/s",
+                     "ms_per_step": round(sec_cold * 1e3, 5),
+                     "kernel_us": round(ksec["cold"] * 1e6, 2),
+                     "kernel_GBps": round(alg / ksec["cold"] / 1e9, 1),
+                     "kernel_frac_of_hbm_peak": round(alg / ksec["cold"] / 1e9 / HBM_PEAK_GBS, 4)})
+        torch.cuda.empty_cache()
+    return rows
 
 
 def bench_prefill(args, torch, lra, workloads):
@@ -172,6 +194,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-other-decode", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -216,6 +239,8 @@ def main():
             "roofline": {"bound": "mfma", "achieved": round(ktf, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(ktf / MFMA_BF16_PEAK_TFLOPS, 4),
                          "kernel_ms": round(pksec * 1e3, 4), "traffic": _load_traffic("prefill_cfg3")}}
+    if not args.no_other_decode:
+        line["other_decode_workloads"] = other_decode_workloads(args, torch, lra, workloads)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(workloads)
     print(json.dumps(line), flush=True)
