@@ -102,6 +102,9 @@ PREFILL_CASES = [
     (200, 129, 4, 4, 64, 8),
     (513, 257, 14, 2, 128, 32),
     (1500, 300, 8, 1, 128, 64),
+    (700, 200, 8, 2, 128, 24),     # rank padded to 32 inside the MFMA kernel
+    (391, 150, 6, 2, 64, 48),      # rank padded to 64, half-empty last block
+    (260, 131, 4, 4, 128, 20),     # rank not a multiple of 8: vector-ALU kernels
 ]
 
 
@@ -113,6 +116,34 @@ def test_prefill_small_shapes(variant, case, dtype):
                           n_kv_heads=hkv, head_dim=d, rank=r, n=n, n_new=n_new, d_model=None,
                           b_std=0.05)
     _gate(run_prefill(w, DEV), oracle_prefill(w), fp32=dtype == torch.float32, label=str(case))
+
+
+@pytest.mark.parametrize("seq,n_new", [(0, 1), (1, 77), (2, 300), (3, 1027)])
+def test_prefill_on_paged_cache(variant, seq, n_new):
+    """Causal prefill of the last n_new tokens of one sequence of a paged, ragged cache
+    (block table lookups, a last block that is partly filled, NaN in the free slots)."""
+    w = W.make_paged("paged_prefill", seed=91, seq_lens=[1, 130, 300, 1027], agents_per_seq=1, n_adapters=3,
+                     n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, d_model=None, b_std=0.05)
+    gen = torch.Generator().manual_seed(500 + seq)
+    q = torch.randn(n_new, 8, 128, generator=gen).to(torch.bfloat16)
+    adapter = (seq + 1) % 3
+    dw = DeviceWorkload(w, DEV)
+    dw.alloc_workspace()
+    qd = q.to(DEV)
+    out = torch.full_like(qd, float("nan"))
+    ws_bytes = lra.lra_workspace_bytes(dw.shape, dw.cache, 1, 1, n_new)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    lra.lra_attn_prefill(dw.shape, dw.cache, dw.b_k, dw.b_v, w.n_adapters, qd, seq, adapter, out, ws)
+    torch.cuda.synchronize()
+    import oracle
+    f = lambda t: t.to(torch.float64).numpy()
+    n_t = w.seq_lens[seq]
+    ids = w.block_table[seq].numpy()
+    kb = oracle.gather_paged(f(w.k_base), ids, n_t)
+    vb = oracle.gather_paged(f(w.v_base), ids, n_t)
+    lr = oracle.lra_oracle.gather_paged_l(f(w.l), ids, n_t)
+    ref = oracle.prefill(f(q), kb, vb, lr, f(w.b_k[adapter]), f(w.b_v[adapter]), n=n_t, scale=w.scale)
+    _gate(out.to(torch.float64).cpu().numpy(), ref, label=f"paged prefill seq {seq} n_new {n_new}")
 
 
 def test_paged_small_ragged_distinct_adapters(variant):
