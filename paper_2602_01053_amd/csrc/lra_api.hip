@@ -145,6 +145,7 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.rank = sh->rank;
   p.block_size = c->block_size;
   p.max_blocks_per_seq = c->max_blocks_per_seq;
+  p.num_blocks = c->num_blocks;
   p.n_seqs = c->n_seqs;
   p.max_seq_len = c->max_seq_len;
   p.group_pad = pl.group_pad;

@@ -31,7 +31,7 @@ struct Params {
   int32_t n_q_heads, n_kv_heads, group, head_dim, rank;
   int32_t group_pad;   // rows reserved per agent in the MFMA row tiles: 4, 8 or 16 (>= group)
   int32_t row_groups;  // workgroups along the query-row axis per (sequence, kv head)
-  int32_t block_size, max_blocks_per_seq, n_seqs, max_seq_len;
+  int32_t block_size, max_blocks_per_seq, num_blocks, n_seqs, max_seq_len;
   int32_t n_queries, max_queries_per_seq;
   int32_t n_new;          // query tokens of the prefill call, 1 in decode
   int32_t is_prefill;     // 0: decode (rows = queries x Hq), 1: prefill (rows = new tokens x Hq)

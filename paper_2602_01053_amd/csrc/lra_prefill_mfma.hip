@@ -17,6 +17,8 @@
 // buffered LDS tile, one barrier per tile.  ds_read_b128 feeds the K operand,
 // ds_read_b64_tr_b16 the transposed V and L operands.  Workgroups are numbered so
 // that all q heads of a kv head run on the same XCD and share its L2.
+#include <type_traits>
+
 #include "lra_common.h"
 
 namespace lra {
@@ -59,6 +61,36 @@ __device__ __forceinline__ float pf_partner32(float v) {
   return (threadIdx.x & 32) ? x : y;
 }
 
+// Raw buffer resource over [base, base + bytes) as four scalar words: loads past the end
+// return zero and touch no memory.  The words are wave-uniform by construction;
+// readfirstlane pins them to scalar registers.
+__device__ __forceinline__ pf_u32x4 pf_rsrc(const void* base, uint32_t bytes) {
+  auto uni = [](uint32_t v) { return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v))); };
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  return pf_u32x4{uni(static_cast<uint32_t>(a)), uni(static_cast<uint32_t>(a >> 32) & 0xffffu), uni(bytes), 0x00020000u};
+}
+
+// buffer_load_dwordx4 ... lds: 16 bytes per lane from the buffer straight into LDS at
+// lds_addr + lane*16 (the LDS base travels in M0; one wait state between the write of M0
+// and the load).  Inline assembly on purpose: the compiler does not track these loads, so
+// it neither parks their data in registers nor drains them before unrelated LDS reads.
+// The waits are placed by hand (pf_wait_vm0) and LDS ordering comes from the barriers.
+__device__ __forceinline__ void pf_load16_to_lds(pf_u32x4 rs, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
+               : "m0");
+}
+__device__ __forceinline__ void pf_wait_vm0() { asm volatile("s_waitcnt vmcnt(0)"); }
+
+// Read-only int32 tables addressed as constant memory, so that wave-uniform reads stay
+// scalar loads although the kernel contains assembly statements the compiler cannot see
+// through.
+typedef const __attribute__((address_space(4))) int32_t* pf_const_i32;
+#define PF_CONST_I32(p) ((pf_const_i32)(p))
+
+constexpr uint32_t kPfOob = 0x80000000u;  // beyond any resource this kernel builds
+
 // LDS swizzles (XOR on the 16-byte chunk index of a row).  The LDS of this chip serves
 // 256 bytes per clock (64 banks): a ds_read_b128 is conflict-free when 16 consecutive
 // lanes cover 16 different chunk positions of that 256-byte window, a ds_read_b64_tr_b16
@@ -66,6 +98,11 @@ __device__ __forceinline__ float pf_partner32(float v) {
 template <int D> __device__ __forceinline__ int pf_swz_k(int key) { return D == 128 ? (key & 15) : ((key >> 1) & 7); }
 template <int D> __device__ __forceinline__ int pf_swz_v(int key) {
   return D == 128 ? ((key & 3) << 2) : (((key >> 1) & 1) << 2);
+}
+// L rows are dense (2, 4 or 8 chunks): as many consecutive rows as fill 256 bytes share a
+// swizzle value, the next group takes the next one.
+template <int LCH> __device__ __forceinline__ int pf_swz_l(int key) {
+  return LCH == 2 ? ((key >> 3) & 1) : (LCH == 4 ? ((key >> 2) & 3) : ((key >> 1) & 7));
 }
 
 template <int D, int RP, bool PAGED>
@@ -75,20 +112,22 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   constexpr int RKS = RP / 16; // k-steps over the padded rank
   constexpr int DB = D / 32;   // 32-row blocks of O^T
   constexpr int RB = (RP + 31) / 32;  // 32-row blocks of Olr^T
-  constexpr int KCH = D / 8;   // 16-byte chunks per K/V row
-  constexpr int KV_LOADS = BN * KCH / 256;  // per-thread 16-byte loads per K (or V) tile
-  constexpr int LCH = RP / 8;               // 16-byte chunks per L row
-  constexpr int L_LOADS = (BN * LCH + 255) / 256;
-  constexpr int LS = RP * 2 + 8;            // L row stride in LDS (bytes): odd multiple of 8 spreads banks
+  constexpr int KCH = D / 8;          // 16-byte chunks per K/V row
+  constexpr int KROWS = 64 / KCH;     // K/V rows one wave-wide load moves (4 or 8)
+  constexpr int KV_DMA = BN / KROWS / 4;  // wave-wide loads per wave and K (or V) tile (4 or 2)
+  constexpr int LCH = RP / 8;         // 16-byte chunks per L row (2, 4 or 8)
+  constexpr int LROWS = 64 / LCH;     // L rows one wave-wide load moves (32, 16 or 8)
+  constexpr int L_DMA = (LCH + 3) / 4;    // the tile takes LCH wave-wide loads; wave w issues i = w + 4q < LCH
   constexpr int K_BYTES = BN * D * 2;
-  constexpr int L_BYTES = (BN * LS + 15) / 16 * 16;
+  constexpr int L_BYTES = BN * RP * 2;
   constexpr int STAGE = 2 * K_BYTES + L_BYTES;
-  // With a half-empty last 32-row block of Olr^T (rank 16 or 48 after padding), one of its
-  // idle rows carries a column of ones appended to the L tile, so the matrix core also
+  // With a half-empty last 32-row block of Olr^T (rank 16 or 48 after padding), its idle
+  // upper lanes read a constant [1, 0, 0, 0] instead of L, so the matrix core also
   // accumulates the softmax row sums.
   constexpr bool ONES_ROW = (RP % 32) != 0;
+  constexpr int ONES_AT = 2 * STAGE;
 
-  __shared__ __align__(16) unsigned char smem[2 * STAGE];
+  __shared__ __align__(16) unsigned char smem[2 * STAGE + (ONES_ROW ? 16 : 0)];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -104,7 +143,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int qt = rest / G;
   const int head = hk * G + gq;
   const int t = p.seq_index;
-  const int n_t = min(p.seq_lens[t], p.max_seq_len);
+  const int n_t = min(PF_CONST_I32(p.seq_lens)[t], p.max_seq_len);
   const int n_new = p.n_new;
   const int q0 = qt * BM;
   if (q0 >= n_new) return;
@@ -118,107 +157,98 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const bf16_t* kb = static_cast<const bf16_t*>(p.k_base);
   const bf16_t* vb = static_cast<const bf16_t*>(p.v_base);
   const bf16_t* lr = static_cast<const bf16_t*>(p.l);
-  const int32_t* bt = p.block_table + static_cast<int64_t>(t) * p.max_blocks_per_seq;
+  const pf_const_i32 bt = PF_CONST_I32(p.block_table) + static_cast<int64_t>(t) * p.max_blocks_per_seq;
 
-  // ---------------- tile staging: global -> registers -> LDS ----------------
-  pf_u32x4 st_k[KV_LOADS], st_v[KV_LOADS], st_l[L_LOADS];  // one tile ahead, in registers
-  // Contiguous cache: raw buffer resources over this kv head's rows; the per-thread byte
-  // offsets are loop invariant and the tile offset travels in a scalar register, so a
-  // tile costs no address arithmetic.  Rows past the sequence read as zero (they are
-  // masked anyway).
-  __amdgpu_buffer_rsrc_t rs_k, rs_v, rs_l;
-  uint32_t kv_voff[KV_LOADS], l_voff[L_LOADS];
+  // ---------------- tile traffic: HBM -> LDS, no registers in between ----------------
+  // A wave-wide load moves 1 KB: KROWS rows of K or V, LROWS rows of L.  Load i of a tile
+  // fills LDS rows i*ROWS ..; lane l lands at row i*ROWS + l/CH, physical chunk l%CH, and
+  // therefore fetches logical chunk (l%CH) ^ swizzle(row).  Wave w issues loads i = w + 4q,
+  // for which the swizzle of its rows does not depend on q: one K, one V offset per lane.
+  // Rows past the sequence (and chunks past the rank) lie outside the resource: they read
+  // as zero and touch no memory; such keys are masked anyway.
   const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u, r2 = static_cast<uint32_t>(r) * 2u;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(PF_LDS_AS(unsigned char, smem)));
+  uint32_t k_voff, v_voff, l_voff[L_DMA];
+  {
+    const int rr = lane / KCH, pc = lane % KCH;
+    const int krow = wave * KROWS + rr;  // LDS row of load i = w (loads w + 4q: + 4q*KROWS, same swizzle)
+    k_voff = static_cast<uint32_t>(rr) * ts2 + ((pc ^ pf_swz_k<D>(krow)) << 4);
+    v_voff = static_cast<uint32_t>(rr) * ts2 + ((pc ^ pf_swz_v<D>(krow)) << 4);
+  }
+  pf_u32x4 rs_k = {0u, 0u, 0u, 0u}, rs_v = rs_k, rs_l = rs_k;
   if (!PAGED) {
     const uint32_t kv_bytes = static_cast<uint32_t>(n_t - 1) * ts2 + D * 2;
-    rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(kb) + static_cast<int64_t>(hk) * p.kv_head_stride, 0,
-                                            static_cast<int>(kv_bytes), 0x00020000);
-    rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(vb) + static_cast<int64_t>(hk) * p.kv_head_stride, 0,
-                                            static_cast<int>(kv_bytes), 0x00020000);
-    rs_l = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(lr), 0, static_cast<int>(static_cast<uint32_t>(n_t) * r2),
-                                            0x00020000);
+    rs_k = pf_rsrc(kb + static_cast<int64_t>(hk) * p.kv_head_stride, kv_bytes);
+    rs_v = pf_rsrc(vb + static_cast<int64_t>(hk) * p.kv_head_stride, kv_bytes);
+    rs_l = pf_rsrc(lr, static_cast<uint32_t>(n_t) * r2);
 #pragma unroll
-    for (int i = 0; i < KV_LOADS; ++i) {
-      const int f = i * 256 + tid;
-      kv_voff[i] = static_cast<uint32_t>(f / KCH) * ts2 + (f % KCH) * 16;
+    for (int q = 0; q < L_DMA; ++q) {
+      const int lrow = (wave + 4 * q) * LROWS + lane / LCH;
+      const int lch = (lane % LCH) ^ pf_swz_l<LCH>(lrow);
+      l_voff[q] = (lch * 8 < r) ? static_cast<uint32_t>(lane / LCH) * r2 + (lch << 4) : kPfOob;
     }
-#pragma unroll
-    for (int i = 0; i < L_LOADS; ++i) {
-      const int f = min(i * 256 + tid, BN * LCH - 1);
-      l_voff[i] = static_cast<uint32_t>(f / LCH) * r2 + min(f % LCH, (r - 1) >> 3) * 16;
-    }
+  } else {
+    // paged L: one resource over the whole array; the lane's physical row is chosen per tile
+    rs_l = pf_rsrc(lr, static_cast<uint32_t>(p.num_blocks) * 16u * r2);
   }
-  // part q of 4 of the next tile's loads (contiguous cache): spread over the tile's
-  // phases so that the eight waves of a CU do not hit the vector memory queue together
-  auto load_part = [&](int j, int q) {
-#pragma unroll
-    for (int i = 0; i < KV_LOADS; ++i)
-      if (i * 4 / KV_LOADS == q) {
-        st_k[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_k, kv_voff[i], static_cast<uint32_t>(j) * ts2, 0);
-        st_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_v, kv_voff[i], static_cast<uint32_t>(j) * ts2, 0);
-      }
-    if (q == 3) {
-#pragma unroll
-      for (int i = 0; i < L_LOADS; ++i)
-        st_l[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_l, l_voff[i], static_cast<uint32_t>(j) * r2, 0);
-    }
-  };
-  auto load_tile = [&](int j) {
+  const int nb_last = (n_t - 1) >> 4;
+
+  // K and V loads number q (of KV_DMA) of this wave for the tile starting at key j
+  auto issue_kv = [&](int j, int st, int q) {
+    const int i = wave + 4 * q;
+    const uint32_t dst = lds0 + st * STAGE + i * 1024;
     if (!PAGED) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) load_part(j, q);
-      return;
-    }
-#pragma unroll
-    for (int i = 0; i < KV_LOADS; ++i) {
-      const int f = i * 256 + tid;
-      const int key = f / KCH, ch = f % KCH;
-      const int tok = min(j + key, n_t - 1);  // clamped: masked later, never out of the sequence
-      const int blk = bt[tok >> 4];
-      const int64_t off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(tok & 15) * p.kv_token_stride +
-                          static_cast<int64_t>(hk) * p.kv_head_stride + ch * 8;
-      st_k[i] = *reinterpret_cast<const pf_u32x4*>(kb + off);
-      st_v[i] = *reinterpret_cast<const pf_u32x4*>(vb + off);
-    }
-#pragma unroll
-    for (int i = 0; i < L_LOADS; ++i) {
-      // every thread loads something valid (no branch around a load: a conditional load
-      // would force the compiler to wait for it on the spot); store_tile drops or zeroes
-      // what lies outside the tile or beyond the rank
-      const int f = min(i * 256 + tid, BN * LCH - 1);
-      const int key = f / LCH;
-      const int ch = min(f % LCH, (r - 1) >> 3);
-      const int tok = min(j + key, n_t - 1);
-      const int64_t lrow = static_cast<int64_t>(bt[tok >> 4]) * 16 + (tok & 15);
-      st_l[i] = *reinterpret_cast<const pf_u32x4*>(lr + lrow * r + ch * 8);
+      const uint32_t soff = static_cast<uint32_t>(j + i * KROWS) * ts2;
+      pf_load16_to_lds(rs_k, dst, k_voff, soff);
+      pf_load16_to_lds(rs_v, dst + K_BYTES, v_voff, soff);
+    } else {
+      // the KROWS rows of one load lie in one 16-token block
+      const int tok = j + i * KROWS;
+      const int blk = bt[min(tok >> 4, nb_last)];
+      const int nv = max(0, min(KROWS, n_t - tok));  // rows of this load inside the sequence
+      const uint32_t bytes = nv > 0 ? static_cast<uint32_t>(nv - 1) * ts2 + D * 2 : 0u;
+      const int64_t off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(hk) * p.kv_head_stride +
+                          static_cast<int64_t>(tok & 15) * p.kv_token_stride;
+      pf_load16_to_lds(pf_rsrc(kb + off, bytes), dst, k_voff, 0);
+      pf_load16_to_lds(pf_rsrc(vb + off, bytes), dst + K_BYTES, v_voff, 0);
     }
   };
-  auto store_tile = [&](unsigned char* buf) {
-    unsigned char* ks = buf;
-    unsigned char* vs = buf + K_BYTES;
-    unsigned char* ls = buf + 2 * K_BYTES;
+  auto issue_l = [&](int j, int st) {
 #pragma unroll
-    for (int i = 0; i < KV_LOADS; ++i) {
-      const int f = i * 256 + tid;
-      const int key = f / KCH, ch = f % KCH;
-      *reinterpret_cast<pf_u32x4*>(ks + key * (D * 2) + ((ch ^ pf_swz_k<D>(key)) << 4)) = st_k[i];
-      *reinterpret_cast<pf_u32x4*>(vs + key * (D * 2) + ((ch ^ pf_swz_v<D>(key)) << 4)) = st_v[i];
-    }
-#pragma unroll
-    for (int i = 0; i < L_LOADS; ++i) {
-      const int f = i * 256 + tid;
-      const int key = f / LCH, ch = f % LCH;
-      if (f < BN * LCH) {
-        const bool live = ch * 8 < r;  // chunks beyond the rank are zero
-        unsigned char* dst = ls + key * LS + ch * 16;  // rows are 8-byte aligned only
-        const pf_u32x4 v = live ? st_l[i] : pf_u32x4{0u, 0u, 0u, 0u};
-        *reinterpret_cast<pf_u32x2*>(dst) = pf_u32x2{v[0], v[1]};
-        *reinterpret_cast<pf_u32x2*>(dst + 8) = pf_u32x2{v[2], v[3]};
+    for (int q = 0; q < L_DMA; ++q) {
+      const int i = wave + 4 * q;
+      if (i < LCH) {
+        const uint32_t dst = lds0 + st * STAGE + 2 * K_BYTES + i * 1024;
+        if (!PAGED) {
+          pf_load16_to_lds(rs_l, dst, l_voff[q], static_cast<uint32_t>(j + i * LROWS) * r2);
+        } else {
+          // LROWS rows span at most two blocks; their ids are wave-uniform (scalar loads)
+          const int tok0 = j + i * LROWS;
+          const int blk_a = bt[min(tok0 >> 4, nb_last)];
+          const int blk_b = bt[min((tok0 >> 4) + 1, nb_last)];
+          const int lrow = i * LROWS + lane / LCH;
+          const int tok = tok0 + lane / LCH;
+          const int blk = ((tok >> 4) == (tok0 >> 4)) ? blk_a : blk_b;
+          const int lch = (lane % LCH) ^ pf_swz_l<LCH>(lrow);
+          const uint32_t voff = (tok < n_t && lch * 8 < r)
+                                    ? (static_cast<uint32_t>(blk) * 16u + static_cast<uint32_t>(tok & 15)) * r2 + (lch << 4)
+                                    : kPfOob;
+          pf_load16_to_lds(rs_l, dst, voff, 0);
+        }
       }
     }
+  };
+  // part q of 4 of a tile's loads: spread over the phases of the previous tile so that the
+  // eight waves of a CU do not hit the vector memory queue together
+  auto issue_part = [&](int j, int st, int q) {
+    if (KV_DMA == 4) issue_kv(j, st, q);
+    if (KV_DMA == 2 && q < 2) issue_kv(j, st, q);
+    if (q == 3) issue_l(j, st);
   };
 
-  load_tile(0);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) issue_part(0, 0, q);
+  if (ONES_ROW && tid == 0) *reinterpret_cast<pf_u32x4*>(smem + ONES_AT) = pf_u32x4{0x00003f80u, 0u, 0u, 0u};
 
   // ---------------- prologue: Q operands, Qt = Q B_K^T ----------------
   // qb[ks]: B operand of S^T: lane (row l32, k = 16ks + 8g2 + e)
@@ -236,20 +266,24 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   {
     const int64_t ldb = static_cast<int64_t>(Hkv) * D;
     const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
+    // rows of this adapter's B_K for kv head hk; rows past the rank (and everything when
+    // there is no B_K) lie outside the resource and read as zero
+    const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(bkg) + (bkg != nullptr ? static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D : 0), 0,
+        bkg != nullptr ? static_cast<int>((static_cast<int64_t>(r - 1) * ldb + D) * 2) : 0, 0x00020000);
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
       pf_f32x16 acc;
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[i] = 0.f;
       const int rho = b * 32 + l32;
-      const bool live = bkg != nullptr && rho < r;
-      const bf16_t* brow = bkg + (static_cast<int64_t>(p.adapter_index) * r + (live ? rho : 0)) * ldb + hk * D + g2 * 8;
+      const uint32_t boff = rho < r ? static_cast<uint32_t>(rho * ldb * 2 + g2 * 16) : kPfOob;
+      pf_u32x4 bk[KS];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (live) v = *reinterpret_cast<const uint4*>(brow + ks * 16);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(v), qb[ks], acc, 0, 0, 0);
-      }
+      for (int ks = 0; ks < KS; ++ks) bk[ks] = __builtin_amdgcn_raw_buffer_load_b128(rs_b, boff, ks * 32, 0);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pf_bf16x8, bk[ks]), qb[ks], acc, 0, 0, 0);
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         const int ks2 = b * 2 + half;
@@ -262,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     }
   }
 
-  // ---------------- per-lane LDS read offsets ----------------
+  // ---------------- per-lane LDS read offsets (stage 0; stage 1 is STAGE further) ----------------
   // K rows as A operand of S^T (ds_read_b128): key = 32kt + l32, logical chunk c = 2ks + g2
   // lives at chunk c ^ swizzle(key); row offset and swizzle occupy disjoint address bits,
   // so the address is k_pre ^ (c << 4) (+ kt * 32 rows)
@@ -274,9 +308,29 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int a16 = lane & 15;
   const int dsel = (lane >> 4) & 1;   // which 16 of the 32 output rows this 16-lane group produces
   const int vrow = 4 * g2 + (a16 >> 2);
-  const int v_pre = vrow * (D * 2) + ((((a16 & 3) >> 1) + 2 * dsel + pf_swz_v<D>(vrow)) << 4) + (a16 & 1) * 8;
-  // L rows as A operand of S^T: two 8-byte pieces per k-step; L^T as A operand of Olr^T
-  const int l_rd = l32 * LS + g2 * 8;           // + ks'*32 (+16 for the second piece) + kt*32*LS
+  const int v_pre = K_BYTES + vrow * (D * 2) + ((((a16 & 3) >> 1) + 2 * dsel + pf_swz_v<D>(vrow)) << 4) + (a16 & 1) * 8;
+  // L rows as A operand of S^T: two 8-byte pieces per k-step (chunks 2ks' and 2ks' + 1, half
+  // g2); the swizzle of row 32kt + l32 does not depend on kt
+  int l_rd[RKS][2];
+#pragma unroll
+  for (int ks = 0; ks < RKS; ++ks)
+#pragma unroll
+    for (int pc = 0; pc < 2; ++pc)
+      l_rd[ks][pc] = 2 * K_BYTES + l32 * (RP * 2) + (((2 * ks + pc) ^ pf_swz_l<LCH>(l32)) << 4) + g2 * 8;
+  // L^T as A operand of Olr^T: rows rho = 32b + 16dsel + 4(a%4) .. +3 of key vrow (+8 for the
+  // second read; +16 per k-step does not change the swizzle).  In a half-empty last block
+  // the upper 16 lanes read the constant [1, 0, 0, 0] instead: output row 32b + 16 then
+  // accumulates the row sums; the rows after it are never used.
+  int lt_rd[RB][2];
+#pragma unroll
+  for (int b = 0; b < RB; ++b)
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int key = vrow + 8 * hh;
+      const int ch = 4 * b + 2 * dsel + ((a16 & 3) >> 1);
+      lt_rd[b][hh] = 2 * K_BYTES + key * (RP * 2) + (((ch & (LCH - 1)) ^ pf_swz_l<LCH>(key)) << 4) + (a16 & 1) * 8;
+    }
+  const bool ones_lane = ONES_ROW && dsel == 1;  // in block RB - 1
 
   // ---------------- main loop ----------------
   pf_f32x16 o_acc[DB], lr_acc[RB];
@@ -290,33 +344,22 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     for (int i = 0; i < 16; ++i) lr_acc[b][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = p.scale * 1.44269504088896340736f;
+  // The running maximum is only raised when some row's tile maximum exceeds it by more than
+  // kSlack (base-2 units): until then probabilities up to 2^kSlack are accumulated, which
+  // fp32 sums and bf16 probabilities hold without loss, and the final division by the row
+  // sum (taken with the same reference) cancels the factor exactly.
+  constexpr float kSlack = 8.0f;
 
-  if (ONES_ROW && tid < 2 * BN) {  // pad of every L row of both buffers: bf16 [1, 0, 0, 0]
-    unsigned char* dst = smem + (tid / BN) * STAGE + 2 * K_BYTES + (tid % BN) * LS + RP * 2;
-    *reinterpret_cast<pf_u32x2*>(dst) = pf_u32x2{0x00003f80u, 0u};
-  }
-  store_tile(smem);
+  pf_wait_vm0();
   __syncthreads();
 
-#ifdef LRA_PF_TIMING
-  long long tph[6] = {0, 0, 0, 0, 0, 0};
-  long long tprev = __builtin_readcyclecounter();
-#define PF_MARK(i) { const long long tn = __builtin_readcyclecounter(); tph[i] += tn - tprev; tprev = tn; }
-#else
-#define PF_MARK(i)
-#endif
-  for (int tile = 0; tile < n_tiles; ++tile) {
+  auto tile_step = [&](int tile, auto st_c) {
+    constexpr int ST = decltype(st_c)::value;
     const int j = tile * BN;
-    unsigned char* buf = smem + (tile & 1) * STAGE;
-    const unsigned char* ks_l = buf;
-    const unsigned char* vs_l = buf + K_BYTES;
-    const unsigned char* ls_l = buf + 2 * K_BYTES;
+    const unsigned char* ks_l = smem + ST * STAGE;  // K region; the V and L offsets are part of v_pre, l_rd, lt_rd
     const bool more = tile + 1 < n_tiles;
-    // unconditional: after the last tile this re-reads it (a conditional load would be
-    // waited for right where it is issued)
-    const int jn = more ? j + BN : j;
-    if (PAGED) load_tile(jn); else load_part(jn, 0);
-    PF_MARK(0)
+    // the other stage was last read before the barrier that ended the previous tile
+    if (more) issue_part(j + BN, ST ^ 1, 0);
 
     // S^T for the two 32-key halves of the tile
     pf_f32x16 s[2];
@@ -332,15 +375,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       }
 #pragma unroll
       for (int ks = 0; ks < RKS; ++ks) {
-        const unsigned char* src = ls_l + l_rd + ks * 32 + kt * 32 * LS;
-        const uint2 lo = *reinterpret_cast<const uint2*>(src);
-        const uint2 hi = *reinterpret_cast<const uint2*>(src + 16);
+        const uint2 lo = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][0] + kt * 32 * RP * 2);
+        const uint2 hi = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][1] + kt * 32 * RP * 2);
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y)), qtb[ks],
                                                         s[kt], 0, 0, 0);
       }
     }
-    if (!PAGED) load_part(jn, 1);
-    PF_MARK(1)
+    if (more) issue_part(j + BN, ST ^ 1, 1);
     // causal mask + online softmax.  Element (kt, i) of this lane is key
     // j + 32kt + 8(i/4) + 4g2 + i%4 of row l32.
     if (j + BN - 1 > base_vis + q0 + wave * 32) {  // some row of this wave does not see the whole tile
@@ -358,7 +399,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kt][i]);
     mx = fmaxf(mx, pf_partner32(mx)) * sc;
-    if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + kSlack) != 0) {  // always on the first tile (m_run = -inf)
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
       m_run = m_new;
@@ -383,47 +424,42 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         pb[kt][h2] = pf_as_bf16x8(make_uint4(pf_pack2(e[8 * h2 + 0], e[8 * h2 + 1]), pf_pack2(e[8 * h2 + 2], e[8 * h2 + 3]),
                                              pf_pack2(e[8 * h2 + 4], e[8 * h2 + 5]), pf_pack2(e[8 * h2 + 6], e[8 * h2 + 7])));
     }
-    if (!PAGED) load_part(jn, 2);
-    PF_MARK(2)
+    if (more) issue_part(j + BN, ST ^ 1, 2);
     // O^T += V^T P^T ; Olr^T += L^T P^T, one 16-key k-step at a time.
     // k-step (kt, h2), element e <-> key 32kt + 16h2 + 8(e/4) + 4g2 + e%4.
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
-        if (!PAGED && kt == 1 && h2 == 0) load_part(jn, 3);
+        if (kt == 1 && h2 == 0 && more) issue_part(j + BN, ST ^ 1, 3);
         const int rowoff = (32 * kt + 16 * h2) * (D * 2);
 #pragma unroll
         for (int b = 0; b < DB; ++b) {
-          const unsigned char* src = vs_l + (v_pre ^ (b << 6)) + rowoff;
+          const unsigned char* src = ks_l + (v_pre ^ (b << 6)) + rowoff;
           const pf_bf16x8 a = pf_join(pf_read_tr16(src), pf_read_tr16(src + 8 * (D * 2)));
           o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][h2], o_acc[b], 0, 0, 0);
         }
 #pragma unroll
         for (int b = 0; b < RB; ++b) {
-          // rows rho = 32b + 16dsel + a16 of L^T.  In a half-empty last block the upper 16
-          // lanes read the pad of the row instead ([1, 0, 0, 0]): output row 32b + 16 then
-          // accumulates the row sums; the rows after it are never used.
-          const bool upper_idle = ONES_ROW && b == RB - 1;
-          const int col = (upper_idle && dsel) ? RP * 2 : b * 64 + dsel * 32 + (a16 & 3) * 8;
-          const unsigned char* src = ls_l + vrow * LS + col + (32 * kt + 16 * h2) * LS;
-          const pf_bf16x8 a = pf_join(pf_read_tr16(src), pf_read_tr16(src + 8 * LS));
+          const int koff = (32 * kt + 16 * h2) * (RP * 2);
+          const unsigned char* src0 = ks_l + lt_rd[b][0] + koff;
+          const unsigned char* src1 = ks_l + lt_rd[b][1] + koff;
+          if (ONES_ROW && b == RB - 1) {
+            src0 = ones_lane ? smem + ONES_AT : src0;
+            src1 = ones_lane ? smem + ONES_AT : src1;
+          }
+          const pf_bf16x8 a = pf_join(pf_read_tr16(src0), pf_read_tr16(src1));
           lr_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][h2], lr_acc[b], 0, 0, 0);
         }
       }
-
-    PF_MARK(3)
-    if (more) store_tile(smem + ((tile + 1) & 1) * STAGE);
-    PF_MARK(4)
+    // the next tile has landed (this wave's share) and everybody is done reading this one
+    pf_wait_vm0();
     __syncthreads();
-    PF_MARK(5)
+  };
+  for (int tile = 0; tile < n_tiles; tile += 2) {
+    tile_step(tile, std::integral_constant<int, 0>{});
+    if (tile + 1 < n_tiles) tile_step(tile + 1, std::integral_constant<int, 1>{});
   }
-#ifdef LRA_PF_TIMING
-  if (blockIdx.x == 300 && lane == 0) {
-    for (int i = 0; i < 6; ++i) p.part_ml[wave * 8 + i] = static_cast<float>(tph[i]);
-    p.part_ml[wave * 8 + 6] = static_cast<float>(n_tiles);
-  }
-#endif
 
   // ---------------- epilogue: O^T += B_V^T Olr^T, O /= l, store ----------------
   if (ONES_ROW) {
