@@ -238,16 +238,14 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       }
     }
   };
-  // part q of 4 of a tile's loads: spread over the phases of the previous tile so that the
-  // eight waves of a CU do not hit the vector memory queue together
-  auto issue_part = [&](int j, int st, int q) {
-    if (KV_DMA == 4) issue_kv(j, st, q);
-    if (KV_DMA == 2 && q < 2) issue_kv(j, st, q);
-    if (q == 3) issue_l(j, st);
+  // this wave's share of the tile starting at key j
+  auto issue_tile = [&](int j, int st) {
+#pragma unroll
+    for (int q = 0; q < KV_DMA; ++q) issue_kv(j, st, q);
+    issue_l(j, st);
   };
 
-#pragma unroll
-  for (int q = 0; q < 4; ++q) issue_part(0, 0, q);
+  issue_tile(0, 0);
   if (ONES_ROW && tid == 0) *reinterpret_cast<pf_u32x4*>(smem + ONES_AT) = pf_u32x4{0x00003f80u, 0u, 0u, 0u};
 
   // ---------------- prologue: Q operands, Qt = Q B_K^T ----------------
@@ -349,6 +347,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   // fp32 sums and bf16 probabilities hold without loss, and the final division by the row
   // sum (taken with the same reference) cancels the factor exactly.
   constexpr float kSlack = 8.0f;
+  constexpr int kReadAheadS = 8, kReadAheadPV = 6;
 
   pf_wait_vm0();
   __syncthreads();
@@ -358,30 +357,47 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     const int j = tile * BN;
     const unsigned char* ks_l = smem + ST * STAGE;  // K region; the V and L offsets are part of v_pre, l_rd, lt_rd
     const bool more = tile + 1 < n_tiles;
-    // the other stage was last read before the barrier that ended the previous tile
-    if (more) issue_part(j + BN, ST ^ 1, 0);
+    // the other stage was last read before the barrier that ended the previous tile; where
+    // in the tile the requests are placed makes no measurable difference
+    if (more) issue_tile(j + BN, ST ^ 1);
 
-    // S^T for the two 32-key halves of the tile
+    // S^T for the two 32-key halves of the tile.  The halves alternate, so consecutive
+    // matrix instructions never wait for each other's result, and the LDS reads run
+    // kReadAheadS operands ahead of the products that consume them.
     pf_f32x16 s[2];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[kt][i] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
         const pf_bf16x8 a = pf_as_bf16x8(
             *reinterpret_cast<const uint4*>(ks_l + (k_pre ^ ((2 * ks + g2) << 4)) + kt * 32 * D * 2));
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[ks], s[kt], 0, 0, 0);
       }
 #pragma unroll
-      for (int ks = 0; ks < RKS; ++ks) {
+    for (int ks = 0; ks < RKS; ++ks)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
         const uint2 lo = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][0] + kt * 32 * RP * 2);
         const uint2 hi = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][1] + kt * 32 * RP * 2);
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y)), qtb[ks],
                                                         s[kt], 0, 0, 0);
       }
+    // instruction order for the scheduler: kReadAheadS LDS reads, then one product per read
+    __builtin_amdgcn_sched_group_barrier(0x100, kReadAheadS, 0);
+#pragma unroll
+    for (int i = 0; i < 2 * KS; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    if (more) issue_part(j + BN, ST ^ 1, 1);
+#pragma unroll
+    for (int i = 0; i < 2 * RKS; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
     // causal mask + online softmax.  Element (kt, i) of this lane is key
     // j + 32kt + 8(i/4) + 4g2 + i%4 of row l32.
     if (j + BN - 1 > base_vis + q0 + wave * 32) {  // some row of this wave does not see the whole tile
@@ -424,14 +440,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         pb[kt][h2] = pf_as_bf16x8(make_uint4(pf_pack2(e[8 * h2 + 0], e[8 * h2 + 1]), pf_pack2(e[8 * h2 + 2], e[8 * h2 + 3]),
                                              pf_pack2(e[8 * h2 + 4], e[8 * h2 + 5]), pf_pack2(e[8 * h2 + 6], e[8 * h2 + 7])));
     }
-    if (more) issue_part(j + BN, ST ^ 1, 2);
     // O^T += V^T P^T ; Olr^T += L^T P^T, one 16-key k-step at a time.
     // k-step (kt, h2), element e <-> key 32kt + 16h2 + 8(e/4) + 4g2 + e%4.
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
-        if (kt == 1 && h2 == 0 && more) issue_part(j + BN, ST ^ 1, 3);
         const int rowoff = (32 * kt + 16 * h2) * (D * 2);
 #pragma unroll
         for (int b = 0; b < DB; ++b) {
@@ -452,6 +466,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
           lr_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kt][h2], lr_acc[b], 0, 0, 0);
         }
       }
+    // the transposed reads (two per operand) run kReadAheadPV operands ahead
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kReadAheadPV, 0);
+#pragma unroll
+    for (int i = 0; i < 4 * (DB + RB); ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
     // the next tile has landed (this wave's share) and everybody is done reading this one
     pf_wait_vm0();
     __syncthreads();
