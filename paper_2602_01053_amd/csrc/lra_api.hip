@@ -268,7 +268,7 @@ const char* lra_status_string(lra_status status) {
   return "unknown status";
 }
 
-int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant); }
+int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant == 1 ? 1 : 0); }
 
 int32_t lra_set_decode_split_keys(int32_t keys) { return g_split_keys.exchange(keys < 0 ? 0 : keys); }
 
