@@ -158,14 +158,31 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   const int h = blockIdx.x, split = blockIdx.y;
   const int t = blockIdx.z / p.row_groups;
   const int rg = blockIdx.z - t * p.row_groups;
-  const int n_t = min(p.seq_lens[t], p.max_seq_len);
+  // The first and the last entry of seq_query_start are fixed by the contract (0 and
+  // n_queries): a single sequence needs no table read at all, and the adapter ids can be
+  // requested at once instead of one memory round trip later.
+  const int32_t len_t = p.seq_lens[t];
+  int q_begin = 0, q_end = p.n_queries;
+  if (t > 0) q_begin = p.seq_query_start[t];
+  if (t + 1 < p.n_seqs) q_end = p.seq_query_start[t + 1];
+  const int n_t = min(len_t, p.max_seq_len);
   const int j0 = split * p.split_keys;
   if (j0 >= n_t) return;
-  const int q_begin = p.seq_query_start[t];
-  const int n_q = p.seq_query_start[t + 1] - q_begin;
+  const int n_q = q_end - q_begin;
   const int GP = p.group_pad, G = p.group, r = p.rank;
   const int row0 = rg * RT * 16;
   if (row0 >= n_q * GP) return;
+
+  // adapter of every agent slot of every row tile: wave-uniform loads, requested before
+  // anything else so that the B_K rows they select can follow one round trip earlier
+  int a_slot[RT][4];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int si = 0; si < 4; ++si) {
+      const int slot = (row0 + rt * 16) / GP + si;
+      a_slot[rt][si] = (p.b_k != nullptr && si < 16 / GP && slot < n_q) ? p.query_adapter[q_begin + slot] : -1;
+    }
 
   const int j1 = min(j0 + p.split_keys, n_t);
   const int kpw = p.split_keys / NW;  // multiple of 32
@@ -334,15 +351,6 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
     constexpr int MAXIT = 4;  // at most 4 slots x 4 rho blocks per tile over 4 waves
     const int n_items = S * ncb;
-    // adapter of every agent slot of every tile: wave-uniform loads, all in flight together
-    int a_slot[RT][4];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-      for (int si = 0; si < 4; ++si) {
-        const int slot = (row0 + rt * 16) / GP + si;
-        a_slot[rt][si] = (bkg != nullptr && si < S && slot < n_q) ? p.query_adapter[q_begin + slot] : -1;
-      }
     // every B_K tile of this wave's items is requested before the first product starts
     uint4 bt4[RT][MAXIT][KS];
 #pragma unroll
@@ -526,6 +534,66 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   }
   if (ALIAS) __syncthreads();  // the maxima are about to be overwritten by merge slots
   float* mslots = reinterpret_cast<float*>(smem);
+  constexpr int PER_RT = (DB + RB) * 4 + 1;  // floats per lane and row tile: O^T, Olr^T, l
+  // Where four slots fit, every wave deposits its state once and then sums and stores a
+  // quarter of it (one barrier, four waves writing); otherwise a two-level tree through two
+  // slots with wave 0 writing.
+  constexpr bool FLAT = NW * MERGE_SLOT <= SMEM;
+  if (FLAT) {
+    float* dst = mslots + wave * (NACC * 64) + lane;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) dst[(rt * PER_RT + b * 4 + jj) * 64] = o_acc[rt][b][jj];
+#pragma unroll
+      for (int b = 0; b < RB; ++b)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) dst[(rt * PER_RT + (DB + b) * 4 + jj) * 64] = lr_acc[rt][b][jj];
+      dst[(rt * PER_RT + (DB + RB) * 4) * 64] = l_run[rt];
+    }
+    __syncthreads();
+    auto total = [&](int x) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) v += mslots[w * (NACC * 64) + x * 64 + lane];
+      return v;
+    };
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int R = row0 + rt * 16 + ln;
+      const int slot_q = R / GP, gg = R - slot_q * GP;
+      if (!(slot_q < n_q && gg < G)) continue;
+      const int64_t row = static_cast<int64_t>(q_begin + slot_q) * p.n_q_heads + h * G + gg;
+      const int64_t slot = row * p.n_splits + split;
+      // blocks are dealt round robin: O^T block b to wave b % 4, Olr^T block b to wave
+      // (DB + b) % 4, the row sum to wave 3 (wave-uniform branches)
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+        if ((b & (NW - 1)) == wave) {
+          f32x4 v;
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) v[jj] = total(rt * PER_RT + b * 4 + jj);
+          *reinterpret_cast<f32x4*>(p.part_o + slot * D + b * 16 + lg * 4) = v;
+        }
+#pragma unroll
+      for (int b = 0; b < RB; ++b)
+        if (((DB + b) & (NW - 1)) == wave) {
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const int rho = b * 16 + lg * 4 + jj;
+            const float v = total(rt * PER_RT + (DB + b) * 4 + jj);
+            if (rho < r) p.part_lr[slot * r + rho] = v;
+          }
+        }
+      if (wave == NW - 1 && lg == 0) {
+        p.part_ml[slot * 2 + 0] = m_all[rt] * 0.69314718055994530942f;  // natural-log units
+        p.part_ml[slot * 2 + 1] = total(rt * PER_RT + (DB + RB) * 4);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int stride = NW / 2; stride >= 1; stride >>= 1) {
     if (wave >= stride && wave < 2 * stride) {
