@@ -85,9 +85,10 @@ def _load_traffic(name):
         return None
 
 
-def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None):
+def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None, value_only=False):
     """Times one decode configuration.  Caches smaller than COLD_BYTES are rotated over
-    enough copies that every step streams from HBM."""
+    enough copies that every step streams from HBM.  value_only passes b_k = NULL (keys
+    fully shared, LoRA on the value side only: the paper's main setting)."""
     from paper_2602_01053_amd.runner import DeviceWorkload
     steps = steps or args.steps
     warmup = warmup or args.warmup
@@ -98,6 +99,8 @@ def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None):
     n_copies = 1 if cache_bytes >= COLD_BYTES else int(math.ceil(COLD_BYTES / cache_bytes)) + 1
     base = DeviceWorkload(w, dev)
     base.alloc_workspace()
+    if value_only:
+        base.b_k = None
     copies = [base]
     for _ in range(n_copies - 1):
         c = DeviceWorkload.__new__(DeviceWorkload)
@@ -141,6 +144,17 @@ def other_decode_workloads(args, torch, lra, workloads):
                      "kernel_frac_of_hbm_peak": round(alg / ksec["cold"] / 1e9 / HBM_PEAK_GBS, 4)})
         torch.cuda.empty_cache()
     return rows
+
+
+def value_only_decode(args, torch, lra, workloads):
+    """Config 2 with b_k = NULL, reported next to the headline workload."""
+    w, alg, sec_cold, _, ksec, _ = bench_decode(args, torch, lra, workloads, 2, steps=max(20, args.steps // 4),
+                                                warmup=max(5, args.warmup // 4), value_only=True)
+    torch.cuda.empty_cache()
+    return {"workload": w.name + " with b_k = NULL", "value": round(alg / sec_cold / 1e9, 1), "unit": "GB/s",
+            "ms_per_step": round(sec_cold * 1e3, 5), "kernel_us": round(ksec["cold"] * 1e6, 2),
+            "kernel_GBps": round(alg / ksec["cold"] / 1e9, 1),
+            "kernel_frac_of_hbm_peak": round(alg / ksec["cold"] / 1e9 / HBM_PEAK_GBS, 4)}
 
 
 def bench_prefill(args, torch, lra, workloads):
@@ -241,6 +255,7 @@ def main():
                          "kernel_ms": round(pksec * 1e3, 4), "traffic": _load_traffic("prefill_cfg3")}}
     if not args.no_other_decode:
         line["other_decode_workloads"] = other_decode_workloads(args, torch, lra, workloads)
+        line["value_only_adapters"] = value_only_decode(args, torch, lra, workloads)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(workloads)
     print(json.dumps(line), flush=True)

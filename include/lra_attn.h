@@ -121,7 +121,9 @@ typedef struct {
  * b_k / b_v: DEVICE [n_adapters][rank][Hkv*head_dim], row-major; kv head h owns
  * columns h*d .. (h+1)*d-1 (Eq. 1: B is r x d_out).  Any LoRA scaling alpha/r is
  * folded into B by the caller.  b_k == NULL means B_K = 0 for every adapter (the
- * paper's main setting: keys fully shared); b_v == NULL means B_V = 0.
+ * paper's main setting: keys fully shared); b_v == NULL means B_V = 0.  With b_k == NULL
+ * the bf16 kernels skip the key-side adapter work altogether (no Q B_K^T, no L term in the
+ * scores) instead of computing it with zeros.
  */
 typedef struct {
   const void* b_k;

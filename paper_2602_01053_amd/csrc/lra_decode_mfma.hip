@@ -115,7 +115,9 @@ __device__ __forceinline__ void buf_load16_to_lds(__amdgpu_buffer_rsrc_t rs, uns
 
 constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel builds
 
-template <int D, int RT, int RP, bool PAGED>
+// HAS_BK = false is the value-only setting (b_k == NULL, keys fully shared): no Qt, no
+// adapter lookup on the key side, no L term in the scores; L is still streamed for P.L.
+template <int D, int RT, int RP, bool PAGED, bool HAS_BK>
 __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   constexpr int NW = 4;
   constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 #pragma unroll
     for (int si = 0; si < 4; ++si) {
       const int slot = (row0 + rt * 16) / GP + si;
-      a_slot[rt][si] = (p.b_k != nullptr && si < 16 / GP && slot < n_q) ? p.query_adapter[q_begin + slot] : -1;
+      a_slot[rt][si] = (HAS_BK && si < 16 / GP && slot < n_q) ? p.query_adapter[q_begin + slot] : -1;
     }
 
   const int j1 = min(j0 + p.split_keys, n_t);
@@ -317,7 +319,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   };
 
   // The first tile is on its way before the prologue touches Q and B_K.
-  if (!ALIAS && jw0 < jw1) issue_tile(jw0);
+  if ((!ALIAS || !HAS_BK) && jw0 < jw1) issue_tile(jw0);
 
   // ===================== prologue: Q operands and Qt = Q B_K^T =====================
   // qb[rt][ks]: lane (row ln of tile rt, k = 32ks + 8lg + e), e = 0..7.  Used as the
@@ -344,7 +346,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   // lane l is the 16 bytes at ((rt*RKS + ks')*64 + l)*16, elements
   // e -> rho = 32ks' + 16(e/4) + 4lg + e%4.  The L operand below uses the same order.
   bf16x8 qtb[RT][RKS];
-  {
+  if (HAS_BK) {
     const int S = 16 / GP;         // agent slots per 16-row tile
     const int ncb = (r + 15) >> 4;
     const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
@@ -398,7 +400,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
         qtb[rt][ks] = as_bf16x8(v);
       }
   }
-  if (ALIAS) {
+  if (ALIAS && HAS_BK) {
     __syncthreads();  // the exchange area is about to be overwritten by tiles
     if (jw0 < jw1) issue_tile(jw0);
   }
@@ -432,14 +434,16 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
         for (int rt = 0; rt < RT; ++rt)
           s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[rt][ks], s[tt][rt], 0, 0, 0);
       }
+      if (HAS_BK) {
 #pragma unroll
-      for (int ks = 0; ks < RKS; ++ks) {
-        const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 32 * RP);
-        const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 32 * RP);
-        const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+        for (int ks = 0; ks < RKS; ++ks) {
+          const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 32 * RP);
+          const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 32 * RP);
+          const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-          s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qtb[rt][ks], s[tt][rt], 0, 0, 0);
+          for (int rt = 0; rt < RT; ++rt)
+            s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qtb[rt][ks], s[tt][rt], 0, 0, 0);
+        }
       }
     }
     // online softmax; element (tt, jj) of this lane is key j + 16tt + 4lg + jj of row ln
@@ -662,10 +666,15 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 template <int D, int RT, int RP>
 static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s) {
   const dim3 block(256);
-  if (p.block_size != 0)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true>), grid, block, 0, s, p);
+  const bool paged = p.block_size != 0, has_bk = p.b_k != nullptr;
+  if (paged && has_bk)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true, true>), grid, block, 0, s, p);
+  else if (paged)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true, false>), grid, block, 0, s, p);
+  else if (has_bk)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false, true>), grid, block, 0, s, p);
   else
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false>), grid, block, 0, s, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false, false>), grid, block, 0, s, p);
   return hipGetLastError();
 }
 

@@ -25,7 +25,9 @@
 
 namespace lra {
 
-template <int D, int RP, bool PAGED>
+// HAS_BK = false is the value-only setting (b_k == NULL, keys fully shared): no Qt and no
+// L term in the scores; L is still staged for P.L.
+template <int D, int RP, bool PAGED, bool HAS_BK>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   constexpr int BM = 128, BN = 64;
   constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   // block b = ks'/2, i.e. element e <-> rho = 16ks' + 8(e/4) + 4g2 + e%4; the L operand
   // below is read in the same order.
   pf_bf16x8 qtb[RKS];
-  {
+  if (HAS_BK) {
     const int64_t ldb = static_cast<int64_t>(Hkv) * D;
     const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
     // rows of this adapter's B_K for kv head hk; rows past the rank (and everything when
@@ -206,15 +208,17 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
             *reinterpret_cast<const uint4*>(ks_l + (k_pre ^ ((2 * ks + g2) << 4)) + kt * 32 * D * 2));
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[ks], s[kt], 0, 0, 0);
       }
+    if (HAS_BK) {
 #pragma unroll
-    for (int ks = 0; ks < RKS; ++ks)
+      for (int ks = 0; ks < RKS; ++ks)
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        const uint2 lo = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][0] + kt * 32 * RP * 2);
-        const uint2 hi = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][1] + kt * 32 * RP * 2);
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y)), qtb[ks],
-                                                        s[kt], 0, 0, 0);
-      }
+        for (int kt = 0; kt < 2; ++kt) {
+          const uint2 lo = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][0] + kt * 32 * RP * 2);
+          const uint2 hi = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][1] + kt * 32 * RP * 2);
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y)), qtb[ks],
+                                                          s[kt], 0, 0, 0);
+        }
+    }
     // instruction order for the scheduler: kReadAheadS LDS reads, then one product per read
     __builtin_amdgcn_sched_group_barrier(0x100, kReadAheadS, 0);
 #pragma unroll
@@ -222,10 +226,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
+    if (HAS_BK) {
 #pragma unroll
-    for (int i = 0; i < 2 * RKS; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      for (int i = 0; i < 2 * RKS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
     }
     // causal mask + online softmax.  Element (kt, i) of this lane is key
     // j + 32kt + 8(i/4) + 4g2 + i%4 of row l32.
@@ -363,10 +369,15 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 
 template <int D, int RP>
 static hipError_t launch_pf(const Params& p, dim3 grid, hipStream_t s) {
-  if (p.block_size != 0)
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true>), grid, dim3(256), 0, s, p);
+  const bool paged = p.block_size != 0, has_bk = p.b_k != nullptr;
+  if (paged && has_bk)
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, true>), grid, dim3(256), 0, s, p);
+  else if (paged)
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false>), grid, dim3(256), 0, s, p);
+  else if (has_bk)
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, true>), grid, dim3(256), 0, s, p);
   else
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
 

@@ -177,6 +177,35 @@ def test_null_adapters_reduce_to_plain_attention(variant):
     _gate(dw.out.to(torch.float64).cpu().numpy(), oracle_decode(w), label="null adapters")
 
 
+@pytest.mark.parametrize("kind", ["decode_contiguous", "decode_paged", "prefill_contiguous", "prefill_r64"])
+def test_value_only_adapters(variant, kind):
+    """b_k = NULL with b_v present: the paper's main setting (keys fully shared, LoRA on the
+    value side only, Sec. 3.2).  Equals the oracle with B_K = 0."""
+    if kind == "decode_contiguous":
+        w = W.config(2, shrink=8)
+    elif kind == "decode_paged":
+        w = W.make_paged("value_only_paged", seed=79, seq_lens=[5, 64, 333, 1500], agents_per_seq=3, n_adapters=4,
+                         n_q_heads=14, n_kv_heads=2, head_dim=128, rank=32, d_model=None, b_std=0.05)
+    elif kind == "prefill_contiguous":
+        w = W.make_contiguous("value_only_prefill", "prefill", seed=80, n_agents=1, n_q_heads=8, n_kv_heads=2,
+                              head_dim=128, rank=16, n=700, n_new=300, d_model=None, b_std=0.05)
+    else:
+        w = W.make_contiguous("value_only_prefill_r64", "prefill", seed=81, n_agents=1, n_q_heads=4, n_kv_heads=4,
+                              head_dim=64, rank=64, n=391, n_new=391, d_model=None, b_std=0.05)
+    dw = DeviceWorkload(w, DEV)
+    dw.alloc_workspace()
+    dw.b_k = None
+    dw.out.fill_(float("nan"))
+    if w.kind == "decode":
+        dw.decode()
+    else:
+        dw.prefill()
+    torch.cuda.synchronize()
+    w.b_k.zero_()
+    ref = oracle_decode(w) if w.kind == "decode" else oracle_prefill(w)
+    _gate(dw.out.to(torch.float64).cpu().numpy(), ref, label=kind)
+
+
 def test_deterministic_and_inputs_untouched(variant):
     w = W.config(2, shrink=4)
     dw = DeviceWorkload(w, DEV)
