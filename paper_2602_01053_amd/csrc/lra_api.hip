@@ -23,7 +23,7 @@ struct Plan {
   int split_keys;  // keys per split
   int n_splits;    // splits per sequence at max_seq_len
   int group_pad, row_tiles, row_groups;  // MFMA decode row packing
-  size_t off_ml, off_o, off_lr, bytes;
+  size_t off_ml, off_o, off_lr, off_adapter, bytes;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -118,7 +118,8 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   pl.off_ml = 0;
   pl.off_o = align_up(slots * 2 * sizeof(float), 256);
   pl.off_lr = pl.off_o + align_up(slots * sh->head_dim * sizeof(float), 256);
-  pl.bytes = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
+  pl.off_adapter = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
+  pl.bytes = pl.off_adapter + align_up(static_cast<size_t>(pl.rows) * sizeof(int32_t), 256);
   return pl;
 }
 
@@ -135,6 +136,7 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.part_ml = reinterpret_cast<float*>(ws + pl.off_ml);
   p.part_o = reinterpret_cast<float*>(ws + pl.off_o);
   p.part_lr = reinterpret_cast<float*>(ws + pl.off_lr);
+  p.part_adapter = reinterpret_cast<int32_t*>(ws + pl.off_adapter);
   p.kv_token_stride = c->kv_token_stride;
   p.kv_head_stride = c->kv_head_stride;
   p.kv_block_stride = c->kv_block_stride;

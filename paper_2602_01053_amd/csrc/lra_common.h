@@ -27,6 +27,7 @@ struct Params {
   float* part_ml;  // [rows][n_splits][2]
   float* part_o;   // [rows][n_splits][d]
   float* part_lr;  // [rows][n_splits][r]
+  int32_t* part_adapter;  // [rows]: adapter of the row's query, left by the first kernel for the merge
   int64_t kv_token_stride, kv_head_stride, kv_block_stride;
   int32_t n_q_heads, n_kv_heads, group, head_dim, rank;
   int32_t group_pad;   // rows reserved per agent in the MFMA row tiles: 4, 8 or 16 (>= group)

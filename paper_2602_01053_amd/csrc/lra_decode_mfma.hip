@@ -42,6 +42,11 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_AS(T, p) ((__attribute__((address_space(3))) T*)(p))
+// Read-only int32 tables of a call, addressed as constant memory: wave-uniform reads stay
+// scalar loads also after the hand-issued loads below, which the compiler must treat as
+// statements that may write anywhere.
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+#define CONST_I32(p) ((const_i32_ptr)(p))
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -107,11 +112,32 @@ __device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t rs, uint32_t 
   return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// 16 bytes per lane from the buffer straight into LDS at lds + lane*16.
-__device__ __forceinline__ void buf_load16_to_lds(__amdgpu_buffer_rsrc_t rs, unsigned char* lds, uint32_t voff,
-                                                  uint32_t soff) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LDS_AS(void, lds), 16, voff, soff, 0, 0);
+// The same kind of resource as four plain words, for the hand-issued loads below (the words
+// are wave-uniform by construction; readfirstlane pins them to scalar registers).
+__device__ __forceinline__ u32x4 make_rsrc_words(const void* base, uint32_t bytes) {
+  auto uni = [](uint32_t v) { return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v))); };
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  return u32x4{uni(static_cast<uint32_t>(a)), uni(static_cast<uint32_t>(a >> 32) & 0xffffu), uni(bytes), 0x00020000u};
 }
+
+// 16 bytes per lane from the buffer straight into LDS at lds + lane*16 (the LDS base travels
+// in M0; one wait state between the write of M0 and the load).  Issued as inline assembly
+// and waited for by hand (wait_vm0): the compiler's own bookkeeping of such loads proved
+// fragile - with other vector loads still outstanding it has placed the wait AFTER the
+// first LDS reads of the tile.  Neither statement claims to touch memory (the compiler
+// would then stop using scalar loads for the kernel's read-only tables); the ordering
+// against the LDS reads of the tile comes from lds_fence() on both sides.
+__device__ __forceinline__ void buf_load16_to_lds(u32x4 rs, unsigned char* lds, uint32_t voff, uint32_t soff) {
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_AS(unsigned char, lds)));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
+               : "m0");
+}
+__device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)"); }
+// Compiler-level ordering point for the LDS traffic of one wave: no LDS access moves across
+// it and LDS contents are taken as changed.  Emits no instruction.
+__device__ __forceinline__ void lds_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront"); }
 
 constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel builds
 
@@ -163,29 +189,59 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   // The first and the last entry of seq_query_start are fixed by the contract (0 and
   // n_queries): a single sequence needs no table read at all, and the adapter ids can be
   // requested at once instead of one memory round trip later.
-  const int32_t len_t = p.seq_lens[t];
+  const int32_t len_t = CONST_I32(p.seq_lens)[t];
   int q_begin = 0, q_end = p.n_queries;
-  if (t > 0) q_begin = p.seq_query_start[t];
-  if (t + 1 < p.n_seqs) q_end = p.seq_query_start[t + 1];
+  if (t > 0) q_begin = CONST_I32(p.seq_query_start)[t];
+  if (t + 1 < p.n_seqs) q_end = CONST_I32(p.seq_query_start)[t + 1];
   const int n_t = min(len_t, p.max_seq_len);
   const int j0 = split * p.split_keys;
-  if (j0 >= n_t) return;
   const int n_q = q_end - q_begin;
   const int GP = p.group_pad, G = p.group, r = p.rank;
   const int row0 = rg * RT * 16;
   if (row0 >= n_q * GP) return;
+  // workspace slot of the row this lane stands for in row tile rt (-1: padding row)
+  auto row_slot = [&](int rt) -> int64_t {
+    const int R = row0 + rt * 16 + ln;
+    const int slot_q = R / GP, gg = R - slot_q * GP;
+    if (!(slot_q < n_q && gg < G)) return -1;
+    return (static_cast<int64_t>(q_begin + slot_q) * p.n_q_heads + h * G + gg) * p.n_splits + split;
+  };
+  if (j0 >= n_t) {
+    // a split past the end of this sequence: leave an empty state (zero row sum), which is
+    // all the merge kernel looks at; the O and O_lr rows of the slot stay unwritten
+    if (wave == 0 && lg == 0) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const int64_t slot = row_slot(rt);
+        if (slot >= 0) {
+          p.part_ml[slot * 2 + 0] = -INFINITY;
+          p.part_ml[slot * 2 + 1] = 0.f;
+        }
+      }
+    }
+    return;
+  }
+  // The merge kernel takes each row's adapter from the workspace: the workgroups of split 0
+  // copy it there (requested now, stored with the state at the end).
+  int my_adapter[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int R = row0 + rt * 16 + ln;
+    const int slot_q = min(R / GP, n_q - 1);
+    my_adapter[rt] = split == 0 ? p.query_adapter[q_begin + slot_q] : 0;
+  }
 
   // adapter of every agent slot of every row tile: wave-uniform loads, requested before
   // anything else so that the B_K rows they select can follow one round trip earlier
+  const bool warm_bv = p.b_v != nullptr && split == min(1, p.n_splits - 1);
   int a_slot[RT][4];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int si = 0; si < 4; ++si) {
       const int slot = (row0 + rt * 16) / GP + si;
-      a_slot[rt][si] = (HAS_BK && si < 16 / GP && slot < n_q) ? p.query_adapter[q_begin + slot] : -1;
+      a_slot[rt][si] = ((HAS_BK || warm_bv) && si < 16 / GP && slot < n_q) ? CONST_I32(p.query_adapter)[q_begin + slot] : -1;
     }
-
   const int j1 = min(j0 + p.split_keys, n_t);
   const int kpw = p.split_keys / NW;  // multiple of 32
   const int jw0 = j0 + wave * kpw;
@@ -255,16 +311,16 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   }
 
   // Contiguous cache: one resource per wave covering exactly its keys [jw0, jw1).
-  __amdgpu_buffer_rsrc_t rs_k, rs_v, rs_l;
+  u32x4 rs_k = {0u, 0u, 0u, 0u}, rs_v = rs_k, rs_l = rs_k;
   if (!PAGED) {
     const int nk = jw1 - jw0;
     const int64_t base = static_cast<int64_t>(h) * p.kv_head_stride + static_cast<int64_t>(jw0) * p.kv_token_stride;
     const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
-    rs_k = make_rsrc(kb + base, bytes);
-    rs_v = make_rsrc(vb + base, bytes);
-    rs_l = make_rsrc(lr + static_cast<int64_t>(jw0) * r, static_cast<uint32_t>(nk) * r2);
+    rs_k = make_rsrc_words(kb + base, bytes);
+    rs_v = make_rsrc_words(vb + base, bytes);
+    rs_l = make_rsrc_words(lr + static_cast<int64_t>(jw0) * r, static_cast<uint32_t>(nk) * r2);
   }
-  const int32_t* bt = p.block_table + static_cast<int64_t>(t) * p.max_blocks_per_seq;
+  const const_i32_ptr bt = CONST_I32(p.block_table) + static_cast<int64_t>(t) * p.max_blocks_per_seq;
 
   // Paged cache: the two physical block ids of a step are fetched one step ahead (scalar
   // loads), so the table lookup is off the path that requests the tile.
@@ -290,10 +346,9 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
         const int blk = blk_cur[half];
         const int nv = max(0, min(16, jw1 - jb));  // slots of this block inside the wave's range
         const uint32_t kv_bytes = nv > 0 ? static_cast<uint32_t>(nv - 1) * ts2 + D * 2 : 0u;
-        const __amdgpu_buffer_rsrc_t pk = make_rsrc(kb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
-        const __amdgpu_buffer_rsrc_t pv = make_rsrc(vb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
-        const __amdgpu_buffer_rsrc_t pl =
-            make_rsrc(lr + static_cast<int64_t>(blk) * 16 * r, static_cast<uint32_t>(nv) * r2);
+        const u32x4 pk = make_rsrc_words(kb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
+        const u32x4 pv = make_rsrc_words(vb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
+        const u32x4 pl = make_rsrc_words(lr + static_cast<int64_t>(blk) * 16 * r, static_cast<uint32_t>(nv) * r2);
 #pragma unroll
         for (int i = 0; i < KVL / 2; ++i) {
           const int ii = half * (KVL / 2) + i;
@@ -420,8 +475,9 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   const float sc = p.scale * 1.44269504088896340736f;
 
   for (int j = jw0; j < jw1; j += 32) {
-    // the first LDS read below waits for the whole tile (LDS reads are ordered
-    // after outstanding buffer_load ... lds)
+    // the tile requested one step earlier (or before the prologue) has landed
+    wait_vm0();
+    lds_fence();
     f32x4 s[2][RT];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -505,8 +561,31 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     }
     // the next tile overwrites this one: every LDS read above must have returned
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-    __builtin_amdgcn_wave_barrier();
+    lds_fence();
     if (j + 32 < jw1) issue_tile(j + 32);
+  }
+
+  // One workgroup per (sequence, kv head, row group) touches the B_V rows the merge kernel
+  // will need (one 4-byte read per 128-byte line) once its keys are done, so that they wait
+  // in this XCD's L2 instead of in HBM: wave w takes agent slot w of every row tile.  The
+  // values are only looked at by an empty statement at the very end.
+  int warm[RT][2];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    warm[rt][0] = warm[rt][1] = 0;
+    const int a = wave == 0 ? a_slot[rt][0] : (wave == 1 ? a_slot[rt][1] : (wave == 2 ? a_slot[rt][2] : a_slot[rt][3]));
+    if (warm_bv && a >= 0) {
+      constexpr int LPR = D * 2 / 128;  // 128-byte lines per B_V row of one kv head
+      const int n_lines = r * LPR;      // <= 128
+      const char* bv = static_cast<const char*>(p.b_v) +
+                       (static_cast<int64_t>(a) * r * p.n_kv_heads * D + static_cast<int64_t>(h) * D) * 2;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int li = i * 64 + lane;
+        if (li < n_lines)
+          warm[rt][i] = *reinterpret_cast<const int*>(bv + static_cast<int64_t>(li / LPR) * p.n_kv_heads * D * 2 + (li % LPR) * 128);
+      }
+    }
   }
 
   // ===================== merge the waves of this workgroup =====================
@@ -566,11 +645,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     };
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int R = row0 + rt * 16 + ln;
-      const int slot_q = R / GP, gg = R - slot_q * GP;
-      if (!(slot_q < n_q && gg < G)) continue;
-      const int64_t row = static_cast<int64_t>(q_begin + slot_q) * p.n_q_heads + h * G + gg;
-      const int64_t slot = row * p.n_splits + split;
+      const int64_t slot = row_slot(rt);
+      if (slot < 0) continue;
       // blocks are dealt round robin: O^T block b to wave b % 4, Olr^T block b to wave
       // (DB + b) % 4, the row sum to wave 3 (wave-uniform branches)
 #pragma unroll
@@ -594,8 +670,11 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
       if (wave == NW - 1 && lg == 0) {
         p.part_ml[slot * 2 + 0] = m_all[rt] * 0.69314718055994530942f;  // natural-log units
         p.part_ml[slot * 2 + 1] = total(rt * PER_RT + (DB + RB) * 4);
+        if (split == 0) p.part_adapter[slot / p.n_splits] = my_adapter[rt];
       }
     }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) asm volatile("" ::"v"(warm[rt][0]), "v"(warm[rt][1]));
     return;
   }
 #pragma unroll
@@ -640,14 +719,12 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   if (wave == 0) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int R = row0 + rt * 16 + ln;
-      const int slot_q = R / GP, gg = R - slot_q * GP;
-      if (!(slot_q < n_q && gg < G)) continue;
-      const int64_t row = static_cast<int64_t>(q_begin + slot_q) * p.n_q_heads + h * G + gg;
-      const int64_t slot = row * p.n_splits + split;
+      const int64_t slot = row_slot(rt);
+      if (slot < 0) continue;
       if (lg == 0) {
         p.part_ml[slot * 2 + 0] = m_all[rt] * 0.69314718055994530942f;  // natural-log units
         p.part_ml[slot * 2 + 1] = l_run[rt];
+        if (split == 0) p.part_adapter[slot / p.n_splits] = my_adapter[rt];
       }
 #pragma unroll
       for (int b = 0; b < DB; ++b)
@@ -661,6 +738,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
         }
     }
   }
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) asm volatile("" ::"v"(warm[rt][0]), "v"(warm[rt][1]));
 }
 
 template <int D, int RT, int RP>

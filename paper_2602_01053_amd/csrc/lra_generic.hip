@@ -94,8 +94,9 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
 
   const int64_t slot = static_cast<int64_t>(row) * p.n_splits + split;
   if (lane == 0) {
-    p.part_ml[slot * 2 + 0] = m;
+    p.part_ml[slot * 2 + 0] = m;  // a split past the row's last visible key leaves (-inf, 0)
     p.part_ml[slot * 2 + 1] = ell;
+    if (split == 0) p.part_adapter[row] = a;
   }
   if (lane < d) p.part_o[slot * d + lane] = o0;
   if (lane + kWave < d) p.part_o[slot * d + lane + kWave] = o1;
@@ -126,26 +127,11 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   const int row = tok * Hq + g;
   const int c = threadIdx.x, gq = threadIdx.y;
   const int tid = gq * 128 + c;
-  int a, n_vis;
-  if (p.is_prefill) {
-    a = p.adapter_index;
-    n_vis = min(p.seq_lens[p.seq_index], p.max_seq_len) - p.n_new + tok + 1;
-  } else {
-    // the sequence that owns this query: every thread tests some sequences at once (one
-    // memory round trip instead of a dependent walk along seq_query_start)
-    __shared__ int seq_of_row;
-    if (p.n_seqs == 1) {
-      if (tid == 0) seq_of_row = 0;
-    } else {
-      for (int t = tid; t < p.n_seqs; t += 128 * kMergeGroups)
-        if (p.seq_query_start[t] <= tok && tok < p.seq_query_start[t + 1]) seq_of_row = t;
-    }
-    __syncthreads();
-    a = p.query_adapter[tok];
-    n_vis = min(p.seq_lens[seq_of_row], p.max_seq_len);
-  }
-  // splits that start at or past this row's last visible key were never written
-  const int ns = min(p.n_splits, (n_vis + p.split_keys - 1) / p.split_keys);
+  // Everything this kernel needs was left in the workspace by the first kernel: the row's
+  // adapter, and a zero row sum in every split that had no visible key (its O and O_lr rows
+  // were never written and are ignored below).  No sequence table is read here.
+  const int ns = p.n_splits;
+  const int a = p.part_adapter[row];
   const int64_t slot0 = static_cast<int64_t>(row) * p.n_splits;
   const float2* ml = reinterpret_cast<const float2*>(p.part_ml) + slot0;
   const float* po = p.part_o + slot0 * d + c;
@@ -194,20 +180,22 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   float ell = 0.f, o = 0.f, olr = 0.f;
 #pragma unroll
   for (int i = 0; i < kMergeUnroll; ++i) {
-    const float w = st[i].y > 0.f ? expf(st[i].x - big) : 0.f;
+    const bool live = st[i].y > 0.f;
+    const float w = live ? expf(st[i].x - big) : 0.f;
     ell = fmaf(w, st[i].y, ell);
-    o = fmaf(w, xo[i], o);
-    olr = fmaf(w, xl[i], olr);
+    o = fmaf(w, live ? xo[i] : 0.f, o);
+    olr = fmaf(w, live ? xl[i] : 0.f, olr);
   }
   // further passes, only for more than kMergeGroups * kMergeUnroll splits
   for (int s = kMergeGroups * kMergeUnroll + gq; s < ns; s += kMergeGroups) {
     const float2 v = ml[s];
     const float x = col_o ? po[static_cast<int64_t>(s) * d] : 0.f;
     const float y = col_l ? pl[static_cast<int64_t>(s) * r] : 0.f;
-    const float w = v.y > 0.f ? expf(v.x - big) : 0.f;
+    const bool live = v.y > 0.f;
+    const float w = live ? expf(v.x - big) : 0.f;
     ell = fmaf(w, v.y, ell);
-    o = fmaf(w, x, o);
-    olr = fmaf(w, y, olr);
+    o = fmaf(w, live ? x : 0.f, o);
+    olr = fmaf(w, live ? y : 0.f, olr);
   }
   if (c < 64) olr_sh[gq][c] = olr;
   if (c == 0) ell_sh[gq] = ell;
