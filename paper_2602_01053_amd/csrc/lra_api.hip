@@ -62,6 +62,14 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   // The MFMA decode kernel moves L in 16-byte pieces: ranks that are not a
   // multiple of 8 take the vector-ALU kernels.
   pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
+  if (prefill && pl.mfma) {
+    // the MFMA prefill kernel addresses a contiguous kv head slice, and L as a whole, with
+    // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
+    const int64_t lim = (int64_t{1} << 32) - 4096;
+    const int64_t l_rows = c->block_size == 0 ? c->max_seq_len : static_cast<int64_t>(c->num_blocks) * 16;
+    if (l_rows * sh->rank * 2 > lim) pl.mfma = false;
+    if (c->block_size == 0 && static_cast<int64_t>(c->max_seq_len) * c->kv_token_stride * 2 > lim) pl.mfma = false;
+  }
   if (prefill && pl.mfma) {  // one kernel, no split over keys, no workspace
     pl.rows = tokens * sh->n_q_heads;
     pl.group_pad = pl.row_tiles = pl.row_groups = 1;
