@@ -200,6 +200,15 @@ int32_t lra_set_kernel_variant(int32_t variant);
 int32_t lra_set_decode_split_keys(int32_t keys);
 
 /*
+ * Tuning and test hook: bf16 prefill calls with at most this many new tokens (and a context
+ * at least four times as long) run on the split-KV decode kernels, the new tokens standing
+ * in for the agents, instead of on the tile-walking prefill kernel; they then need a
+ * workspace (ask lra_workspace_bytes after setting this).  0 switches that path off.
+ * Returns the previous value.  Default 64.
+ */
+int32_t lra_set_short_prefill(int32_t tokens);
+
+/*
  * Tuning hook: how many 32-key steps ahead the MFMA decode kernel keeps its global
  * loads in registers (1 or 2; other values are clamped).  Returns the previous value.
  */

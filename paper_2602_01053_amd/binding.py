@@ -18,7 +18,7 @@ LRA_OK = 0
 LRA_BF16, LRA_F32 = 0, 1
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
-           "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch",
+           "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill",
            "lra_set_profile_mode")
 
 
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.lra_set_kernel_variant.argtypes = [i32]
     lib.lra_set_decode_split_keys.restype = i32
     lib.lra_set_decode_split_keys.argtypes = [i32]
+    lib.lra_set_short_prefill.restype = i32
+    lib.lra_set_short_prefill.argtypes = [i32]
     lib.lra_set_decode_prefetch.restype = i32
     lib.lra_set_decode_prefetch.argtypes = [i32]
     lib.lra_set_profile_mode.restype = i32
@@ -93,6 +95,10 @@ def lra_set_kernel_variant(variant: int) -> int:
 
 def lra_set_decode_split_keys(keys: int) -> int:
     return int(load_library().lra_set_decode_split_keys(int(keys)))
+
+
+def lra_set_short_prefill(tokens: int) -> int:
+    return int(load_library().lra_set_short_prefill(int(tokens)))
 
 
 def lra_set_decode_prefetch(steps: int) -> int:

@@ -11,6 +11,7 @@ namespace lra {
 
 std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
+std::atomic<int32_t> g_short_prefill{64};  // kShortPrefill: new tokens up to which prefill takes the split-KV path
 std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
 
 std::atomic<int32_t> g_profile_mode{0};
@@ -19,6 +20,7 @@ constexpr int kCUs = 256;  // MI355X
 
 struct Plan {
   bool mfma;
+  bool short_prefill;  // prefill served by the split-KV decode kernels (few new tokens)
   int rows;        // query rows = (queries | new tokens) x Hq
   int split_keys;  // keys per split
   int n_splits;    // splits per sequence at max_seq_len
@@ -70,7 +72,13 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     if (l_rows * sh->rank * 2 > lim) pl.mfma = false;
     if (c->block_size == 0 && static_cast<int64_t>(c->max_seq_len) * c->kv_token_stride * 2 > lim) pl.mfma = false;
   }
-  if (prefill && pl.mfma) {  // one kernel, no split over keys, no workspace
+  // A handful of new tokens after a long context gives the tile-walking prefill kernel one
+  // workgroup per q head and nothing to split; the split-KV decode kernel, with the new
+  // tokens in the place of the agents and a causal limit per row, spreads the context over
+  // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
+  pl.short_prefill = prefill && pl.mfma && tokens <= g_short_prefill.load() &&
+                     static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
+  if (prefill && pl.mfma && !pl.short_prefill) {  // one kernel, no split over keys, no workspace
     pl.rows = tokens * sh->n_q_heads;
     pl.group_pad = pl.row_tiles = pl.row_groups = 1;
     pl.split_keys = c->max_seq_len;
@@ -85,12 +93,14 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   int tile = 64;       // keys per wave-step of the vector-ALU kernel
   int64_t work;        // units that want a wave (vector-ALU) or a workgroup share (MFMA)
   int want;
+  const int n_seqs_eff = prefill ? 1 : c->n_seqs;
+  if (pl.short_prefill) max_queries_per_seq = tokens;
   if (pl.mfma) {
     const int rows_needed = max_queries_per_seq * pl.group_pad;
     pl.row_tiles = decode_mfma_row_tiles(rows_needed);
     pl.row_groups = (rows_needed + 16 * pl.row_tiles - 1) / (16 * pl.row_tiles);
     tile = 128;        // 4 waves x 32 keys
-    work = static_cast<int64_t>(c->n_seqs) * sh->n_kv_heads * pl.row_groups;
+    work = static_cast<int64_t>(n_seqs_eff) * sh->n_kv_heads * pl.row_groups;
     want = kCUs;
   } else {
     work = pl.rows;
@@ -102,7 +112,7 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     // per-workgroup prologue is not amortised otherwise); a ragged batch wants about four
     // times as many, equal-sized pieces so the CUs stay balanced.  A batch is assumed to be
     // half as long on average as its longest sequence.
-    const bool batch = c->n_seqs > 1;
+    const bool batch = n_seqs_eff > 1;
     const int64_t key_heads = work * c->max_seq_len / (batch ? 2 : 1);
     const int64_t wgs = batch ? kCUs * 4 : kCUs;
     split_keys = static_cast<int>((key_heads + wgs - 1) / wgs);
@@ -120,6 +130,7 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     if (cap < tile) pl.mfma = false;
     else if (split_keys > cap) split_keys = static_cast<int>(cap);
   }
+  if (!pl.mfma) pl.short_prefill = false;
   pl.split_keys = split_keys;
   pl.n_splits = (c->max_seq_len + split_keys - 1) / split_keys;
   const size_t slots = static_cast<size_t>(pl.rows) * pl.n_splits;
@@ -255,6 +266,12 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   p.adapter_index = adapter_index;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
+  if (pl.short_prefill) {
+    if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
+    if (g_profile_mode.load() == 1) return LRA_OK;
+    if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
+    return LRA_OK;
+  }
   if (pl.mfma) {
     if (launch_prefill_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
     return LRA_OK;
@@ -279,6 +296,8 @@ const char* lra_status_string(lra_status status) {
 }
 
 int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant == 1 ? 1 : 0); }
+
+int32_t lra_set_short_prefill(int32_t tokens) { return g_short_prefill.exchange(tokens < 0 ? 0 : tokens); }
 
 int32_t lra_set_decode_split_keys(int32_t keys) { return g_split_keys.exchange(keys < 0 ? 0 : keys); }
 

@@ -143,7 +143,11 @@ constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel build
 
 // HAS_BK = false is the value-only setting (b_k == NULL, keys fully shared): no Qt, no
 // adapter lookup on the key side, no L term in the scores; L is still streamed for P.L.
-template <int D, int RT, int RP, bool PAGED, bool HAS_BK>
+// CAUSAL = true serves lra_attn_prefill with a handful of new tokens: the new tokens of the
+// one sequence take the place of the agents (same adapter for all), and row i only sees the
+// keys up to n - n_new + i (Alg. 1 line 10); a long context is then split over the whole chip
+// like any decode call instead of being walked by one workgroup per q head.
+template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   constexpr int NW = 4;
   constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
@@ -184,15 +188,17 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   // kv head is the fastest grid index: workgroups go round-robin over the XCDs, so with 8 kv
   // heads all workgroups of a head run on one XCD and share Q and B_K in its L2
   const int h = blockIdx.x, split = blockIdx.y;
-  const int t = blockIdx.z / p.row_groups;
-  const int rg = blockIdx.z - t * p.row_groups;
+  const int t = CAUSAL ? p.seq_index : blockIdx.z / p.row_groups;
+  const int rg = CAUSAL ? blockIdx.z : blockIdx.z - t * p.row_groups;
   // The first and the last entry of seq_query_start are fixed by the contract (0 and
   // n_queries): a single sequence needs no table read at all, and the adapter ids can be
   // requested at once instead of one memory round trip later.
   const int32_t len_t = CONST_I32(p.seq_lens)[t];
-  int q_begin = 0, q_end = p.n_queries;
-  if (t > 0) q_begin = CONST_I32(p.seq_query_start)[t];
-  if (t + 1 < p.n_seqs) q_end = CONST_I32(p.seq_query_start)[t + 1];
+  int q_begin = 0, q_end = CAUSAL ? p.n_new : p.n_queries;
+  if (!CAUSAL) {
+    if (t > 0) q_begin = CONST_I32(p.seq_query_start)[t];
+    if (t + 1 < p.n_seqs) q_end = CONST_I32(p.seq_query_start)[t + 1];
+  }
   const int n_t = min(len_t, p.max_seq_len);
   const int j0 = split * p.split_keys;
   const int n_q = q_end - q_begin;
@@ -228,8 +234,13 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   for (int rt = 0; rt < RT; ++rt) {
     const int R = row0 + rt * 16 + ln;
     const int slot_q = min(R / GP, n_q - 1);
-    my_adapter[rt] = split == 0 ? p.query_adapter[q_begin + slot_q] : 0;
+    my_adapter[rt] = CAUSAL ? p.adapter_index : (split == 0 ? p.query_adapter[q_begin + slot_q] : 0);
   }
+  // last key each of this lane's rows may see (causal form only)
+  int lim[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) lim[rt] = n_t - n_q + min((row0 + rt * 16 + ln) / GP, n_q - 1);
+  const int lim_first = n_t - n_q + row0 / GP;  // the smallest of them in this workgroup
 
   // adapter of every agent slot of every row tile: wave-uniform loads, requested before
   // anything else so that the B_K rows they select can follow one round trip earlier
@@ -240,7 +251,10 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 #pragma unroll
     for (int si = 0; si < 4; ++si) {
       const int slot = (row0 + rt * 16) / GP + si;
-      a_slot[rt][si] = ((HAS_BK || warm_bv) && si < 16 / GP && slot < n_q) ? CONST_I32(p.query_adapter)[q_begin + slot] : -1;
+      if (CAUSAL)
+        a_slot[rt][si] = (si < 16 / GP && slot < n_q) ? p.adapter_index : -1;
+      else
+        a_slot[rt][si] = ((HAS_BK || warm_bv) && si < 16 / GP && slot < n_q) ? CONST_I32(p.query_adapter)[q_begin + slot] : -1;
     }
   const int j1 = min(j0 + p.split_keys, n_t);
   const int kpw = p.split_keys / NW;  // multiple of 32
@@ -503,7 +517,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
       }
     }
     // online softmax; element (tt, jj) of this lane is key j + 16tt + 4lg + jj of row ln
-    const bool tail = j + 32 > jw1;
+    const bool tail = j + 32 > jw1 || (CAUSAL && j + 31 > lim_first);
     bf16x8 pb[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -511,15 +525,18 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj)
-            if (j + tt * 16 + lg * 4 + jj >= jw1) s[tt][rt][jj] = -INFINITY;
+          for (int jj = 0; jj < 4; ++jj) {
+            const int key = j + tt * 16 + lg * 4 + jj;
+            if (key >= jw1 || (CAUSAL && key > lim[rt])) s[tt][rt][jj] = -INFINITY;
+          }
       }
       float mx = fmaxf(fmaxf(fmaxf(s[0][rt][0], s[0][rt][1]), fmaxf(s[0][rt][2], s[0][rt][3])),
                        fmaxf(fmaxf(s[1][rt][0], s[1][rt][1]), fmaxf(s[1][rt][2], s[1][rt][3])));
       mx = max_over_lane_groups(mx) * sc;  // sc > 0
       if (__builtin_amdgcn_ballot_w64(mx > m_run[rt]) != 0) {
         const float m_new = fmaxf(m_run[rt], mx);
-        const float alpha = fast_exp2(m_run[rt] - m_new);
+        // causal form: a row may have seen no key yet (both maxima -inf)
+        const float alpha = (CAUSAL && m_new == -INFINITY) ? 1.f : fast_exp2(m_run[rt] - m_new);
         m_run[rt] = m_new;
         l_run[rt] *= alpha;
 #pragma unroll
@@ -527,7 +544,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 #pragma unroll
         for (int b = 0; b < RB; ++b) lr_acc[rt][b] *= alpha;
       }
-      const float nm = -m_run[rt];
+      const float nm = (CAUSAL && m_run[rt] == -INFINITY) ? 0.f : -m_run[rt];
       float pe[8];
       float sum = 0.f;
 #pragma unroll
@@ -607,8 +624,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
       const float* m_w = reinterpret_cast<const float*>(ALIAS ? smem + w * WAVE_BYTES : extra_lds + QT_BYTES + w * RT * 64);
       mm = fmaxf(mm, m_w[rt * 16 + ln]);
     }
-    m_all[rt] = mm;  // finite: wave 0 always owns at least one key
-    const float wgt = fast_exp2(m_run[rt] - mm);
+    m_all[rt] = mm;  // finite (wave 0 always owns a key) unless a causal row sees none of this split
+    const float wgt = (CAUSAL && mm == -INFINITY) ? 0.f : fast_exp2(m_run[rt] - mm);
     l_run[rt] *= wgt;
 #pragma unroll
     for (int b = 0; b < DB; ++b) o_acc[rt][b] *= wgt;
@@ -742,19 +759,24 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   for (int rt = 0; rt < RT; ++rt) asm volatile("" ::"v"(warm[rt][0]), "v"(warm[rt][1]));
 }
 
-template <int D, int RT, int RP>
-static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s) {
+template <int D, int RT, int RP, bool CAUSAL>
+static hipError_t launch_cfg2(const Params& p, dim3 grid, hipStream_t s) {
   const dim3 block(256);
   const bool paged = p.block_size != 0, has_bk = p.b_k != nullptr;
   if (paged && has_bk)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true, true>), grid, block, 0, s, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true, true, CAUSAL>), grid, block, 0, s, p);
   else if (paged)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true, false>), grid, block, 0, s, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true, false, CAUSAL>), grid, block, 0, s, p);
   else if (has_bk)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false, true>), grid, block, 0, s, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false, true, CAUSAL>), grid, block, 0, s, p);
   else
-    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false, false>), grid, block, 0, s, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, false, false, CAUSAL>), grid, block, 0, s, p);
   return hipGetLastError();
+}
+
+template <int D, int RT, int RP>
+static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s) {
+  return p.is_prefill ? launch_cfg2<D, RT, RP, true>(p, grid, s) : launch_cfg2<D, RT, RP, false>(p, grid, s);
 }
 
 // Row tiles per workgroup the kernel is built for.
@@ -762,7 +784,7 @@ int decode_mfma_row_tiles(int rows_needed) { return rows_needed <= 16 ? 1 : 2; }
 
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s) {
   (void)prefetch;
-  dim3 grid(p.n_kv_heads, p.n_splits, p.n_seqs * p.row_groups);
+  dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
   const int rp = p.rank <= 32 ? 32 : 64;
   const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (rp == 64 ? 1 : 0);
   switch (key) {

@@ -107,7 +107,13 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _prefill(lib, sh, c, ad, n_new=8193) == SHAPE
     assert _prefill(lib, sh, c, ad, q=None) == NULL
     bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 0)
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) == 0      # bf16 prefill: one kernel
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 1024) == 0    # bf16 prefill: one kernel
+    short = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16)           # few new tokens: split-KV path
+    assert 0 < short < (1 << 40)
+    lib.lra_set_short_prefill.restype = ctypes.c_int32
+    old = lib.lra_set_short_prefill(0)
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) == 0      # that path switched off
+    assert lib.lra_set_short_prefill(old) == 0 and old > 0
     sh32 = mutated(dtype=1)[0]
     assert 0 < lib.lra_workspace_bytes(ctypes.byref(sh32), ctypes.byref(c), 0, 0, 16) < (1 << 40)
     assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 5, 0) == ctypes.c_size_t(-1).value

@@ -118,6 +118,67 @@ def test_prefill_small_shapes(variant, case, dtype):
     _gate(run_prefill(w, DEV), oracle_prefill(w), fp32=dtype == torch.float32, label=str(case))
 
 
+SHORT_PREFILL_CASES = [
+    # n, n_new, Hq, Hkv, d, r
+    (1000, 1, 8, 2, 128, 16),
+    (1000, 7, 8, 2, 128, 16),
+    (4099, 16, 32, 8, 128, 16),    # two row tiles, several splits
+    (300, 13, 14, 2, 128, 32),     # group of 7: 8 rows per token, several row groups
+    (777, 16, 16, 1, 64, 64),      # group of 16
+    (64, 16, 4, 4, 64, 8),         # context exactly four times the new tokens
+]
+
+
+@pytest.mark.parametrize("case", SHORT_PREFILL_CASES, ids=lambda c: "n%d_new%d_hq%d_hkv%d_d%d_r%d" % c)
+@pytest.mark.parametrize("path", ["split_kv", "tile_walk"])
+def test_short_prefill_both_paths(case, path):
+    """A few new tokens after a longer context: served by the split-KV decode kernels with a
+    causal limit per row (default) or by the tile-walking prefill kernel (path switched off);
+    both must match the oracle."""
+    n, n_new, hq, hkv, d, r = case
+    w = W.make_contiguous("short_prefill", "prefill", seed=3000 + n + n_new, n_agents=1, n_q_heads=hq,
+                          n_kv_heads=hkv, head_dim=d, rank=r, n=n, n_new=n_new, d_model=None, b_std=0.05)
+    old = lra.lra_set_short_prefill(64 if path == "split_kv" else 0)
+    try:
+        dw = DeviceWorkload(w, DEV)
+        nbytes = dw.alloc_workspace()
+        assert (nbytes > 0) == (path == "split_kv")
+        dw.out.fill_(float("nan"))
+        dw.prefill()
+        torch.cuda.synchronize()
+        got = dw.out.to(torch.float64).cpu().numpy()
+    finally:
+        lra.lra_set_short_prefill(old)
+    _gate(got, oracle_prefill(w), label=f"{case} {path}")
+
+
+def test_short_prefill_on_paged_cache_value_only():
+    """Split-KV prefill of 5 new tokens on a paged, ragged cache without B_K."""
+    w = W.make_paged("paged_short_prefill", seed=92, seq_lens=[40, 333, 1500], agents_per_seq=1, n_adapters=3,
+                     n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, d_model=None, b_std=0.05)
+    import oracle
+    f = lambda t: t.to(torch.float64).numpy()
+    for seq, n_new in [(0, 5), (1, 16), (2, 9)]:
+        gen = torch.Generator().manual_seed(600 + seq)
+        q = torch.randn(n_new, 8, 128, generator=gen).to(torch.bfloat16)
+        adapter = seq % 3
+        dw = DeviceWorkload(w, DEV)
+        qd = q.to(DEV)
+        out = torch.full_like(qd, float("nan"))
+        ws_bytes = lra.lra_workspace_bytes(dw.shape, dw.cache, 1, 1, n_new)
+        assert ws_bytes > 0
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+        lra.lra_attn_prefill(dw.shape, dw.cache, None, dw.b_v, w.n_adapters, qd, seq, adapter, out, ws)
+        torch.cuda.synchronize()
+        n_t = w.seq_lens[seq]
+        ids = w.block_table[seq].numpy()
+        kb = oracle.gather_paged(f(w.k_base), ids, n_t)
+        vb = oracle.gather_paged(f(w.v_base), ids, n_t)
+        lr = oracle.lra_oracle.gather_paged_l(f(w.l), ids, n_t)
+        ref = oracle.prefill(f(q), kb, vb, lr, np.zeros_like(f(w.b_k[adapter])), f(w.b_v[adapter]), n=n_t, scale=w.scale)
+        _gate(out.to(torch.float64).cpu().numpy(), ref, label=f"paged short prefill seq {seq} n_new {n_new}")
+
+
 @pytest.mark.parametrize("seq,n_new", [(0, 1), (1, 77), (2, 300), (3, 1027)])
 def test_prefill_on_paged_cache(variant, seq, n_new):
     """Causal prefill of the last n_new tokens of one sequence of a paged, ragged cache
