@@ -209,6 +209,15 @@ int32_t lra_set_decode_split_keys(int32_t keys);
 int32_t lra_set_short_prefill(int32_t tokens);
 
 /*
+ * Tuning and test hook: number of workgroups that share the key tiles of one q tile in the
+ * bf16 tile-walking prefill kernel (clamped to 1..32); more than one needs a workspace and
+ * ends with the merge kernel.  0 restores the automatic choice (enough to give the chip two
+ * workgroups per CU, at least eight 64-key tiles each at max_seq_len).  Returns the previous
+ * value.
+ */
+int32_t lra_set_prefill_splits(int32_t splits);
+
+/*
  * Tuning hook: how many 32-key steps ahead the MFMA decode kernel keeps its global
  * loads in registers (1 or 2; other values are clamped).  Returns the previous value.
  */

@@ -18,7 +18,7 @@ LRA_OK = 0
 LRA_BF16, LRA_F32 = 0, 1
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
-           "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill",
+           "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill", "lra_set_prefill_splits",
            "lra_set_profile_mode")
 
 
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.lra_set_decode_split_keys.argtypes = [i32]
     lib.lra_set_short_prefill.restype = i32
     lib.lra_set_short_prefill.argtypes = [i32]
+    lib.lra_set_prefill_splits.restype = i32
+    lib.lra_set_prefill_splits.argtypes = [i32]
     lib.lra_set_decode_prefetch.restype = i32
     lib.lra_set_decode_prefetch.argtypes = [i32]
     lib.lra_set_profile_mode.restype = i32
@@ -99,6 +101,10 @@ def lra_set_decode_split_keys(keys: int) -> int:
 
 def lra_set_short_prefill(tokens: int) -> int:
     return int(load_library().lra_set_short_prefill(int(tokens)))
+
+
+def lra_set_prefill_splits(splits: int) -> int:
+    return int(load_library().lra_set_prefill_splits(int(splits)))
 
 
 def lra_set_decode_prefetch(steps: int) -> int:

@@ -11,6 +11,7 @@ namespace lra {
 
 std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
+std::atomic<int32_t> g_prefill_splits{0};  // 0 = automatic
 std::atomic<int32_t> g_short_prefill{64};  // kShortPrefill: new tokens up to which prefill takes the split-KV path
 std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
 
@@ -78,12 +79,32 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
   pl.short_prefill = prefill && pl.mfma && tokens <= g_short_prefill.load() &&
                      static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
-  if (prefill && pl.mfma && !pl.short_prefill) {  // one kernel, no split over keys, no workspace
+  if (prefill && pl.mfma && !pl.short_prefill) {
+    // Tile-walking kernel: one workgroup per (128-row q tile, q head).  When that is fewer
+    // than two workgroups per CU, the key tiles of every q tile are divided among several
+    // workgroups (at least eight 64-key tiles each) and the merge kernel finishes the job;
+    // otherwise it is one kernel without a workspace.
     pl.rows = tokens * sh->n_q_heads;
     pl.group_pad = pl.row_tiles = pl.row_groups = 1;
     pl.split_keys = c->max_seq_len;
-    pl.n_splits = 1;
+    const int64_t wgs = static_cast<int64_t>((tokens + 127) / 128) * sh->n_q_heads;
+    int64_t ns = g_prefill_splits.load();
+    if (ns <= 0) {  // automatic: two workgroups per CU, at least eight key tiles per share
+      ns = (2 * kCUs + wgs - 1) / wgs;
+      const int64_t max_ns = c->max_seq_len / (8 * 64);
+      ns = ns > max_ns ? max_ns : ns;
+    }
+    ns = ns > 32 ? 32 : (ns < 1 ? 1 : ns);
+    pl.n_splits = static_cast<int>(ns);
     pl.bytes = 0;
+    if (pl.n_splits > 1) {
+      const size_t slots = static_cast<size_t>(pl.rows) * pl.n_splits;
+      pl.off_ml = 0;
+      pl.off_o = align_up(slots * 2 * sizeof(float), 256);
+      pl.off_lr = pl.off_o + align_up(slots * sh->head_dim * sizeof(float), 256);
+      pl.off_adapter = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
+      pl.bytes = pl.off_adapter + align_up(static_cast<size_t>(pl.rows) * sizeof(int32_t), 256);
+    }
     return pl;
   }
   pl.rows = tokens * sh->n_q_heads;
@@ -149,6 +170,7 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.l = c->l;
   p.b_k = ad->b_k;
   p.b_v = ad->b_v;
+  p.n_adapters = ad->n_adapters;
   p.block_table = c->block_table;
   p.seq_lens = c->seq_lens;
   char* ws = static_cast<char*>(workspace);
@@ -274,6 +296,8 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   }
   if (pl.mfma) {
     if (launch_prefill_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
+    if (pl.n_splits > 1 && g_profile_mode.load() != 1 && launch_merge(p, bf16, pl.rows, s) != hipSuccess)
+      return LRA_ERR_HIP;
     return LRA_OK;
   }
   if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
@@ -296,6 +320,8 @@ const char* lra_status_string(lra_status status) {
 }
 
 int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant == 1 ? 1 : 0); }
+
+int32_t lra_set_prefill_splits(int32_t splits) { return g_prefill_splits.exchange(splits < 0 ? 0 : splits); }
 
 int32_t lra_set_short_prefill(int32_t tokens) { return g_short_prefill.exchange(tokens < 0 ? 0 : tokens); }
 

@@ -34,6 +34,7 @@ struct Params {
   int32_t row_groups;  // workgroups along the query-row axis per (sequence, kv head)
   int32_t block_size, max_blocks_per_seq, num_blocks, n_seqs, max_seq_len;
   int32_t n_queries, max_queries_per_seq;
+  int32_t n_adapters;
   int32_t n_new;          // query tokens of the prefill call, 1 in decode
   int32_t is_prefill;     // 0: decode (rows = queries x Hq), 1: prefill (rows = new tokens x Hq)
   int32_t seq_index, adapter_index;  // prefill only

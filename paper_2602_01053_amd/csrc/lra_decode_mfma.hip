@@ -131,7 +131,8 @@ __device__ __forceinline__ void buf_load16_to_lds(u32x4 rs, unsigned char* lds, 
   const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_AS(unsigned char, lds)));
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
-               : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
+               : "s"(__builtin_amdgcn_readfirstlane(static_cast<int>(lds_addr))), "v"(voff), "s"(rs),
+                 "s"(__builtin_amdgcn_readfirstlane(static_cast<int>(soff)))  // wave-uniform by construction
                : "m0");
 }
 __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)"); }

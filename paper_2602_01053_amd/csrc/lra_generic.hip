@@ -131,7 +131,8 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   // adapter, and a zero row sum in every split that had no visible key (its O and O_lr rows
   // were never written and are ignored below).  No sequence table is read here.
   const int ns = p.n_splits;
-  const int a = p.part_adapter[row];
+  // (clamped: whatever the workspace holds, the B_V rows read below exist)
+  const int a = min(max(p.part_adapter[row], 0), p.n_adapters - 1);
   const int64_t slot0 = static_cast<int64_t>(row) * p.n_splits;
   const float2* ml = reinterpret_cast<const float2*>(p.part_ml) + slot0;
   const float* po = p.part_o + slot0 * d + c;

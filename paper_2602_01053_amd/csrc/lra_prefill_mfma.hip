@@ -27,7 +27,10 @@ namespace lra {
 
 // HAS_BK = false is the value-only setting (b_k == NULL, keys fully shared): no Qt and no
 // L term in the scores; L is still staged for P.L.
-template <int D, int RP, bool PAGED, bool HAS_BK>
+// SPLIT = true: the key tiles of a q tile are shared by gridDim.y workgroups; each leaves its
+// softmax state (m, l, O, O_lr per row) in the workspace and the merge kernel combines
+// them, applies B_V and normalises (for calls with too few q tiles to fill the chip).
+template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   constexpr int BM = 128, BN = 64;
   constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
@@ -71,12 +74,27 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int limit = base_vis + row_c;             // last visible key of this lane's row
   const int wg_last = base_vis + min(q0 + BM, n_new) - 1;  // last key any row of the workgroup sees
   const int n_tiles = wg_last / BN + 1;
+  // this workgroup's share of the q tile's key tiles: [tile_begin, tile_end)
+  const int split = SPLIT ? blockIdx.y : 0;
+  const int tile_begin = SPLIT ? static_cast<int>(static_cast<int64_t>(n_tiles) * split / p.n_splits) : 0;
+  const int tile_end = SPLIT ? static_cast<int>(static_cast<int64_t>(n_tiles) * (split + 1) / p.n_splits) : n_tiles;
+  if (SPLIT && tile_begin >= tile_end) {
+    // more workgroups than key tiles: leave an empty state (zero row sum), all the merge
+    // kernel looks at
+    if (row < n_new && g2 == 0) {
+      const int64_t slot = (static_cast<int64_t>(row) * Hq + head) * p.n_splits + split;
+      p.part_ml[slot * 2 + 0] = -INFINITY;
+      p.part_ml[slot * 2 + 1] = 0.f;
+      if (split == 0) p.part_adapter[static_cast<int64_t>(row) * Hq + head] = p.adapter_index;
+    }
+    return;
+  }
 
   // ---------------- tile traffic: HBM -> LDS, no registers in between ----------------
   const PfTileLoader<D, RP, PAGED> loader(p, smem, wave, lane, hk, t, n_t);
   auto issue_tile = [&](int j, int st) { loader.issue_tile(j, st * STAGE); };
 
-  issue_tile(0, 0);
+  issue_tile(tile_begin * BN, 0);
   if (ONES_ROW && tid == 0) *reinterpret_cast<pf_u32x4*>(smem + ONES_AT) = pf_u32x4{0x00003f80u, 0u, 0u, 0u};
 
   // ---------------- prologue: Q operands, Qt = Q B_K^T ----------------
@@ -187,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     constexpr int ST = decltype(st_c)::value;
     const int j = tile * BN;
     const unsigned char* ks_l = smem + ST * STAGE;  // K region; the V and L offsets are part of v_pre, l_rd, lt_rd
-    const bool more = tile + 1 < n_tiles;
+    const bool more = tile + 1 < tile_end;
     // the other stage was last read before the barrier that ended the previous tile; where
     // in the tile the requests are placed makes no measurable difference
     if (more) issue_tile(j + BN, ST ^ 1);
@@ -252,7 +270,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     mx = fmaxf(mx, pf_partner32(mx)) * sc;
     if (__builtin_amdgcn_ballot_w64(mx > m_run + kSlack) != 0) {  // always on the first tile (m_run = -inf)
       const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      // a share that does not start at key 0 may hold rows that have seen nothing yet
+      const float alpha = (SPLIT && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
       m_run = m_new;
       l_run *= alpha;
 #pragma unroll
@@ -260,7 +279,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 #pragma unroll
       for (int b = 0; b < RB; ++b) lr_acc[b] *= alpha;
     }
-    const float nm = -m_run;  // finite from the first tile on: key 0 is visible to every row
+    // finite from the first tile on (key 0 is visible to every row) unless the share starts later
+    const float nm = (SPLIT && m_run == -INFINITY) ? 0.f : -m_run;
     pf_bf16x8 pb[2][2];       // [kt][16-key k-step]
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -312,9 +332,9 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     pf_wait_vm0();
     __syncthreads();
   };
-  for (int tile = 0; tile < n_tiles; tile += 2) {
+  for (int tile = tile_begin; tile < tile_end; tile += 2) {
     tile_step(tile, std::integral_constant<int, 0>{});
-    if (tile + 1 < n_tiles) tile_step(tile + 1, std::integral_constant<int, 1>{});
+    if (tile + 1 < tile_end) tile_step(tile + 1, std::integral_constant<int, 1>{});
   }
 
   // ---------------- epilogue: O^T += B_V^T Olr^T, O /= l, store ----------------
@@ -325,6 +345,34 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     l_run = g2 == 0 ? mine : other;
   } else {
     l_run += pf_partner32(l_run);
+  }
+  if (SPLIT) {
+    // this share's state for the merge kernel: m in natural-log units, l, O^T and Olr^T as
+    // fp32 rows [slot][d] and [slot][rank]; registers 4q..4q+3 are d (rho) = 32b + 8q + 4g2 + 0..3
+    if (row < n_new) {
+      const int64_t slot = (static_cast<int64_t>(row) * Hq + head) * p.n_splits + split;
+      if (g2 == 0) {
+        p.part_ml[slot * 2 + 0] = m_run * 0.69314718055994530942f;
+        p.part_ml[slot * 2 + 1] = l_run;
+        if (split == 0) p.part_adapter[static_cast<int64_t>(row) * Hq + head] = p.adapter_index;
+      }
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<pf_f32x4*>(p.part_o + slot * D + 32 * b + 8 * q + 4 * g2) =
+              pf_f32x4{o_acc[b][4 * q + 0], o_acc[b][4 * q + 1], o_acc[b][4 * q + 2], o_acc[b][4 * q + 3]};
+#pragma unroll
+      for (int b = 0; b < RB; ++b)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int rho = 32 * b + 8 * q + 4 * g2;  // the rank is a multiple of 8: all four or none
+          if (rho < r)
+            *reinterpret_cast<pf_f32x4*>(p.part_lr + slot * r + rho) =
+                pf_f32x4{lr_acc[b][4 * q + 0], lr_acc[b][4 * q + 1], lr_acc[b][4 * q + 2], lr_acc[b][4 * q + 3]};
+        }
+    }
+    return;
   }
   if (p.b_v != nullptr) {
     const int64_t ldb = static_cast<int64_t>(Hkv) * D;
@@ -367,23 +415,28 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   }
 }
 
-template <int D, int RP>
-static hipError_t launch_pf(const Params& p, dim3 grid, hipStream_t s) {
+template <int D, int RP, bool SPLIT>
+static hipError_t launch_pf2(const Params& p, dim3 grid, hipStream_t s) {
   const bool paged = p.block_size != 0, has_bk = p.b_k != nullptr;
   if (paged && has_bk)
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, true>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, true, SPLIT>), grid, dim3(256), 0, s, p);
   else if (paged)
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false, SPLIT>), grid, dim3(256), 0, s, p);
   else if (has_bk)
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, true>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, true, SPLIT>), grid, dim3(256), 0, s, p);
   else
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, SPLIT>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
+}
+
+template <int D, int RP>
+static hipError_t launch_pf(const Params& p, dim3 grid, hipStream_t s) {
+  return p.n_splits > 1 ? launch_pf2<D, RP, true>(p, grid, s) : launch_pf2<D, RP, false>(p, grid, s);
 }
 
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s) {
   const int q_tiles = (p.n_new + 127) / 128;
-  dim3 grid(q_tiles * p.n_q_heads);
+  dim3 grid(q_tiles * p.n_q_heads, p.n_splits);
   const int rp = p.rank <= 16 ? 16 : (p.rank <= 32 ? 32 : 64);
   if (p.head_dim == 128) {
     if (rp == 16) return launch_pf<128, 16>(p, grid, s);

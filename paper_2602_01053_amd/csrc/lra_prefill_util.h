@@ -63,7 +63,8 @@ __device__ __forceinline__ pf_u32x4 pf_rsrc(const void* base, uint32_t bytes) {
 __device__ __forceinline__ void pf_load16_to_lds(pf_u32x4 rs, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
-               : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
+               : "s"(__builtin_amdgcn_readfirstlane(static_cast<int>(lds_addr))), "v"(voff), "s"(rs),
+                 "s"(__builtin_amdgcn_readfirstlane(static_cast<int>(soff)))  // wave-uniform by construction
                : "m0");
 }
 __device__ __forceinline__ void pf_wait_vm0() { asm volatile("s_waitcnt vmcnt(0)"); }

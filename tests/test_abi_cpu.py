@@ -107,12 +107,17 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _prefill(lib, sh, c, ad, n_new=8193) == SHAPE
     assert _prefill(lib, sh, c, ad, q=None) == NULL
     bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 0)
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 1024) == 0    # bf16 prefill: one kernel
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 2048) == 0    # bf16 prefill, enough q tiles: one kernel
+    assert 0 < lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 1024) < (1 << 40)   # key tiles shared: merge
     short = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16)           # few new tokens: split-KV path
     assert 0 < short < (1 << 40)
     lib.lra_set_short_prefill.restype = ctypes.c_int32
     old = lib.lra_set_short_prefill(0)
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) == 0      # that path switched off
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) > 0       # that path off: key tiles shared instead
+    lib.lra_set_prefill_splits.restype = ctypes.c_int32
+    assert lib.lra_set_prefill_splits(1) == 0
+    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) == 0      # one workgroup per q tile and head
+    assert lib.lra_set_prefill_splits(0) == 1
     assert lib.lra_set_short_prefill(old) == 0 and old > 0
     sh32 = mutated(dtype=1)[0]
     assert 0 < lib.lra_workspace_bytes(ctypes.byref(sh32), ctypes.byref(c), 0, 0, 16) < (1 << 40)

@@ -139,6 +139,7 @@ def test_short_prefill_both_paths(case, path):
     w = W.make_contiguous("short_prefill", "prefill", seed=3000 + n + n_new, n_agents=1, n_q_heads=hq,
                           n_kv_heads=hkv, head_dim=d, rank=r, n=n, n_new=n_new, d_model=None, b_std=0.05)
     old = lra.lra_set_short_prefill(64 if path == "split_kv" else 0)
+    old_s = lra.lra_set_prefill_splits(1)
     try:
         dw = DeviceWorkload(w, DEV)
         nbytes = dw.alloc_workspace()
@@ -149,7 +150,41 @@ def test_short_prefill_both_paths(case, path):
         got = dw.out.to(torch.float64).cpu().numpy()
     finally:
         lra.lra_set_short_prefill(old)
+        lra.lra_set_prefill_splits(old_s)
     _gate(got, oracle_prefill(w), label=f"{case} {path}")
+
+
+SPLIT_PREFILL_CASES = [
+    # n, n_new, Hq, Hkv, d, r, splits (0 = automatic)
+    (3000, 200, 8, 2, 128, 16, 0),     # automatic: few q tiles, several shares
+    (2048, 130, 4, 4, 64, 8, 3),
+    (5000, 700, 14, 2, 128, 32, 4),    # ragged last q tile, group of 7
+    (1100, 1100, 4, 1, 128, 64, 2),    # no old context: later shares hold rows that see nothing of them
+    (700, 300, 8, 2, 64, 48, 32),      # more shares than key tiles: empty shares
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_PREFILL_CASES, ids=lambda c: "n%d_new%d_hq%d_hkv%d_d%d_r%d_s%d" % c)
+def test_prefill_key_tiles_shared_by_workgroups(case):
+    """The tile-walking prefill kernel with the key tiles of each q tile divided among several
+    workgroups plus the merge kernel."""
+    n, n_new, hq, hkv, d, r, splits = case
+    w = W.make_contiguous("split_prefill", "prefill", seed=4000 + n + n_new, n_agents=1, n_q_heads=hq,
+                          n_kv_heads=hkv, head_dim=d, rank=r, n=n, n_new=n_new, d_model=None, b_std=0.05)
+    old_s = lra.lra_set_prefill_splits(splits)
+    old_t = lra.lra_set_short_prefill(0)
+    try:
+        dw = DeviceWorkload(w, DEV)
+        nbytes = dw.alloc_workspace()
+        assert nbytes > 0
+        dw.out.fill_(float("nan"))
+        dw.prefill()
+        torch.cuda.synchronize()
+        got = dw.out.to(torch.float64).cpu().numpy()
+    finally:
+        lra.lra_set_prefill_splits(old_s)
+        lra.lra_set_short_prefill(old_t)
+    _gate(got, oracle_prefill(w), label=str(case))
 
 
 def test_short_prefill_on_paged_cache_value_only():
