@@ -204,7 +204,8 @@ int32_t lra_set_decode_split_keys(int32_t keys);
  * at least four times as long) run on the split-KV decode kernels, the new tokens standing
  * in for the agents, instead of on the tile-walking prefill kernel; they then need a
  * workspace (ask lra_workspace_bytes after setting this).  0 switches that path off.
- * Returns the previous value.  Default 64.
+ * Returns the previous value.  Default 32 (measured crossover against the tile-walking kernel
+ * with shared key tiles).
  */
 int32_t lra_set_short_prefill(int32_t tokens);
 

@@ -12,7 +12,7 @@ namespace lra {
 std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
 std::atomic<int32_t> g_prefill_splits{0};  // 0 = automatic
-std::atomic<int32_t> g_short_prefill{64};  // kShortPrefill: new tokens up to which prefill takes the split-KV path
+std::atomic<int32_t> g_short_prefill{32};  // kShortPrefill: new tokens up to which prefill takes the split-KV path
 std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
 
 std::atomic<int32_t> g_profile_mode{0};

@@ -54,3 +54,16 @@ def test_config5_lengths():
     lens = W.ragged_lengths(W.BASE_SEED + 5, 16, 4096, 65536)
     assert len(lens) == 16 and min(lens) >= 4096 and max(lens) <= 65536
     assert any(n % 16 for n in lens)
+
+
+def test_agent_trace_matches_the_papers_totals():
+    """The 17-step agent-iteration schedule of bench_trace.py (App. C.5, table of prefill and
+    generation lengths): the paper states 17 steps per iteration and total trajectory lengths
+    from 1.9k (L_ctx = 0.25k) to 66.4k (L_ctx = 16k)."""
+    import bench_trace
+    assert len(bench_trace.TRACE) == 17
+    assert [a for a, _, _ in bench_trace.TRACE].count("reflect") == 2
+    def total(l_ctx):
+        return sum((l_ctx if p is None else p) + g for _, p, g in bench_trace.TRACE)
+    assert round(total(256) / 1000, 1) == 1.9
+    assert round(total(16384) / 1000, 1) == 66.4
