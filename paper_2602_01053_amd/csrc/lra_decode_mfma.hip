@@ -131,8 +131,7 @@ __device__ __forceinline__ void buf_load16_to_lds(u32x4 rs, unsigned char* lds, 
   const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_AS(unsigned char, lds)));
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
-               : "s"(__builtin_amdgcn_readfirstlane(static_cast<int>(lds_addr))), "v"(voff), "s"(rs),
-                 "s"(__builtin_amdgcn_readfirstlane(static_cast<int>(soff)))  // wave-uniform by construction
+               : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
                : "m0");
 }
 __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)"); }
@@ -245,7 +244,9 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 
   // adapter of every agent slot of every row tile: wave-uniform loads, requested before
   // anything else so that the B_K rows they select can follow one round trip earlier
-  const bool warm_bv = p.b_v != nullptr && split == min(1, p.n_splits - 1);
+  // (only in the one-row-tile kernels: in the two-tile ones the extra registers and the wait
+  // cost the streaming kernel more than the merge kernel gains)
+  const bool warm_bv = RT == 1 && p.b_v != nullptr && split == min(1, p.n_splits - 1);
   int a_slot[RT][4];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
