@@ -26,7 +26,11 @@ Pins (tests/test_oracle_pins.py): scalar brute force on tiny inputs, the n=1 and
 Q=0 closed forms, the reordering identity of Sec. 3.3 / App. B on both sides,
 the augmented-head identity, a library SDPA in float64 with B=0 and with
 materialised K/V, a block-wise transcription of Alg. 1, softmax rows summing to
-one, convex-hull / shift / permutation invariances.  Every function is pinned.
+one, convex-hull / shift / permutation invariances.  The cache-append producer at the end
+of the file (projection of new tokens, rotary embedding of the keys, paged scatter) is pinned
+by the 2x2 rotation at d = 2, the identity at position 0, norm preservation, additivity of
+positions, the relative-position property of rotated dot products, explicit loops on tiny
+inputs and the scatter / gather round trip.  Every function is pinned.
 """
 from __future__ import annotations
 
@@ -163,3 +167,66 @@ def prefill(q, k_base, v_base, l, b_k_a, b_v_a, n: int, scale: float, rows=None,
     n_visible = n - t_new + idx + 1
     return attend(q[idx], np.asarray(k_base)[:n], np.asarray(v_base)[:n], np.asarray(l)[:n],
                   b_k_a, b_v_a, scale, n_visible, q_to_kv)
+
+
+# --------------------------------------------------------------------------------------
+# Cache-append producer (the step before the attention path; Sec. 3.2 and the caption of
+# the base / LR cache diagram: the base cache comes from the pretrained projections, the
+# LR cache from the shared LoRA down-projection, both for the newly appended tokens only).
+# The paper fixes WHAT is stored - X W_K and X W_V as base cache, X A as LR cache, keys
+# rotated by the model's rotary position embedding before they are cached (App. D.1 speaks
+# of post-rotation keys) - not how; the rotation below is the usual rotate-half form.
+# --------------------------------------------------------------------------------------
+def rope_rotate(x, positions, theta: float) -> np.ndarray:
+    """Rotary position embedding, rotate-half convention, on x [n][H][d] (d even).
+
+    Pair (i, i + d/2) of token t is rotated by the angle positions[t] * theta**(-2i/d):
+        out[i]       = x[i] cos - x[i + d/2] sin
+        out[i + d/2] = x[i + d/2] cos + x[i] sin"""
+    x = _f64(x)
+    n, _, d = x.shape
+    half = d // 2
+    pos = _f64(positions).reshape(n, 1, 1)
+    inv_freq = float(theta) ** (-2.0 * np.arange(half, dtype=np.float64) / d)
+    ang = pos * inv_freq.reshape(1, 1, half)
+    c, s = np.cos(ang), np.sin(ang)
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def project_new_tokens(x, w_cat, n_kv_heads: int, head_dim: int, rank: int, positions, rope_theta: float):
+    """Rows the producer appends for the new tokens x [n_new][d_model].
+
+    w_cat [2*Hkv*d + r][d_model] holds, one output feature per row, W_K (kv head h owns rows
+    h*d .. (h+1)*d-1), then W_V, then the shared down-projection A transposed.  Returns
+    (k_rows [n_new][Hkv][d], v_rows [n_new][Hkv][d], l_rows [n_new][r]); keys are rotated
+    when rope_theta > 0."""
+    x, w_cat = _f64(x), _f64(w_cat)
+    hd = n_kv_heads * head_dim
+    if w_cat.shape != (2 * hd + rank, x.shape[1]):
+        raise ValueError("w_cat must be [2*Hkv*d + r][d_model]")
+    y = x @ w_cat.T
+    n = x.shape[0]
+    k = y[:, :hd].reshape(n, n_kv_heads, head_dim)
+    v = y[:, hd:2 * hd].reshape(n, n_kv_heads, head_dim)
+    l = y[:, 2 * hd:]
+    if rope_theta > 0:
+        k = rope_rotate(k, positions, rope_theta)
+    return k, v, l
+
+
+def scatter_paged(pool_kv: np.ndarray, block_ids: Sequence[int], start: int, rows: np.ndarray) -> None:
+    """Write rows [m][Hkv][d] as tokens start .. start+m-1 of a sequence stored as
+    [num_blocks][Hkv][bs][d] (in place; the inverse of gather_paged on that range)."""
+    bs = pool_kv.shape[2]
+    for i in range(rows.shape[0]):
+        j = start + i
+        pool_kv[block_ids[j // bs], :, j % bs, :] = rows[i]
+
+
+def scatter_paged_l(pool_l: np.ndarray, block_ids: Sequence[int], start: int, rows: np.ndarray) -> None:
+    """The same for the LR cache stored as [num_blocks][bs][r]."""
+    bs = pool_l.shape[1]
+    for i in range(rows.shape[0]):
+        j = start + i
+        pool_l[block_ids[j // bs], j % bs, :] = rows[i]

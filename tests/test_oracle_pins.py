@@ -386,3 +386,89 @@ def test_p10_gate_sees_missing_or_swapped_adapters():
     assert _rel_l2(oracle.decode(*base, f(w.b_v), f(w.b_k), *args), out) > 5e-3 * 4
     swapped = w.query_adapter.numpy()[::-1].copy()
     assert _rel_l2(oracle.decode(*base, f(w.b_k), f(w.b_v), swapped, *args[1:]), out) > 5e-3 * 4
+
+
+# --------------------------------------------------------------------------
+# P11: cache-append producer (projection of the new tokens, rotary embedding
+# of the keys, paged scatter).
+# --------------------------------------------------------------------------
+def test_p11_rope_is_a_plane_rotation_for_d2():
+    """d = 2 has the single pair (0, 1) and frequency theta**0 = 1: the rotation by the
+    position itself, written as a 2x2 matrix."""
+    rng = np.random.default_rng(110)
+    x = rng.standard_normal((5, 3, 2))
+    pos = np.array([0, 1, 2, 7, 100])
+    out = oracle.rope_rotate(x, pos, 10000.0)
+    for t in range(5):
+        c, s = math.cos(pos[t]), math.sin(pos[t])
+        rot = np.array([[c, -s], [s, c]])
+        np.testing.assert_allclose(out[t], x[t] @ rot.T, rtol=0, atol=1e-12)
+
+
+def test_p11_rope_identity_norm_additivity_and_relative_position():
+    rng = np.random.default_rng(111)
+    n, H, d, theta = 6, 2, 16, 500000.0
+    x = rng.standard_normal((n, H, d))
+    y = rng.standard_normal((n, H, d))
+    pos = np.array([0, 3, 17, 100, 4095, 65535])
+    # position 0 changes nothing
+    np.testing.assert_array_equal(oracle.rope_rotate(x, np.zeros(n), theta), x)
+    # every pair keeps its length
+    out = oracle.rope_rotate(x, pos, theta)
+    half = d // 2
+    np.testing.assert_allclose(out[..., :half] ** 2 + out[..., half:] ** 2,
+                               x[..., :half] ** 2 + x[..., half:] ** 2, rtol=1e-12)
+    # rotating by a then by b is rotating by a + b
+    twice = oracle.rope_rotate(oracle.rope_rotate(x, pos, theta), 2 * pos + 1, theta)
+    np.testing.assert_allclose(twice, oracle.rope_rotate(x, 3 * pos + 1, theta), rtol=0, atol=1e-9)
+    # dot products of rotated vectors depend on the position difference only
+    a = np.einsum("thd,thd->th", oracle.rope_rotate(x, pos, theta), oracle.rope_rotate(y, pos + 5, theta))
+    b = np.einsum("thd,thd->th", oracle.rope_rotate(x, pos + 1000, theta), oracle.rope_rotate(y, pos + 1005, theta))
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-9)
+    # the pair index i uses theta**(-2i/d): the slowest pair of token 1 turns by theta**(-(d-2)/d)
+    e = np.zeros((2, 1, d))
+    e[:, 0, half - 1] = 1.0
+    ang = theta ** (-(d - 2) / d)
+    got = oracle.rope_rotate(e, np.array([0, 1]), theta)[1, 0]
+    assert abs(got[half - 1] - math.cos(ang)) < 1e-15 and abs(got[d - 1] - math.sin(ang)) < 1e-15
+
+
+def test_p11_projection_matches_explicit_loops():
+    rng = np.random.default_rng(112)
+    n, dm, Hkv, d, r, theta = 3, 5, 2, 4, 3, 100.0
+    x = rng.standard_normal((n, dm))
+    w = rng.standard_normal((2 * Hkv * d + r, dm))
+    pos = np.array([4, 5, 6])
+    k, v, l = oracle.project_new_tokens(x, w, Hkv, d, r, pos, theta)
+    for t in range(n):
+        y = [sum(x[t, c] * w[o, c] for c in range(dm)) for o in range(w.shape[0])]
+        for h in range(Hkv):
+            kh = y[h * d:(h + 1) * d]
+            for i in range(d // 2):
+                ang = pos[t] * theta ** (-2.0 * i / d)
+                assert abs(k[t, h, i] - (kh[i] * math.cos(ang) - kh[i + d // 2] * math.sin(ang))) < 1e-12
+                assert abs(k[t, h, i + d // 2] - (kh[i + d // 2] * math.cos(ang) + kh[i] * math.sin(ang))) < 1e-12
+            for i in range(d):
+                assert abs(v[t, h, i] - y[Hkv * d + h * d + i]) < 1e-12
+        for i in range(r):
+            assert abs(l[t, i] - y[2 * Hkv * d + i]) < 1e-12
+    # without rotation the keys are the plain projection
+    k0, _, _ = oracle.project_new_tokens(x, w, Hkv, d, r, pos, 0.0)
+    np.testing.assert_allclose(k0.reshape(n, -1), x @ w[:Hkv * d].T, rtol=1e-13)
+
+
+def test_p11_paged_scatter_is_the_inverse_of_gather():
+    rng = np.random.default_rng(113)
+    nb, Hkv, bs, d, r = 7, 2, 16, 4, 3
+    pool = rng.standard_normal((nb, Hkv, bs, d))
+    pool_l = rng.standard_normal((nb, bs, r))
+    ids = [5, 2, 6, 0]
+    before = oracle.gather_paged(pool, ids, 50).copy()
+    rows = rng.standard_normal((20, Hkv, d))
+    rows_l = rng.standard_normal((20, r))
+    oracle.scatter_paged(pool, ids, 30, rows)
+    oracle.scatter_paged_l(pool_l, ids, 30, rows_l)
+    after = oracle.gather_paged(pool, ids, 50)
+    np.testing.assert_array_equal(after[30:50], rows)
+    np.testing.assert_array_equal(after[:30], before[:30])
+    np.testing.assert_array_equal(lra_oracle.gather_paged_l(pool_l, ids, 50)[30:50], rows_l)
