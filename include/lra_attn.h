@@ -181,6 +181,38 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache,
                             int32_t adapter_index, int32_t n_new, void* out, void* workspace,
                             size_t workspace_bytes, void* stream);
 
+/*
+ * Projection weights of one attention layer for lra_cache_append.
+ * w: DEVICE [2*Hkv*head_dim + rank][d_model], row-major, one output feature per row (the
+ * layout of a linear layer's weight): first W_K (kv head h owns rows h*d .. (h+1)*d-1), then
+ * W_V, then the shared LoRA down-projection A (Eq. 1: Delta W = A B, A is d_model x r), one
+ * rank per row.  16-byte aligned; d_model a multiple of 64.
+ * rope_theta > 0 rotates the keys by the rotary position embedding in its rotate-half form
+ * (pair (i, i + d/2) of the token at position j by the angle j * rope_theta^(-2i/d)) before
+ * they are cached - the cached keys are the rotated ones (App. D.1); 0 stores them unrotated.
+ */
+typedef struct {
+  const void* w;
+  int32_t d_model;
+  float rope_theta;
+} lra_projection;
+
+/*
+ * The step before the attention path (Sec. 3.2 and the diagram of base and LR cache
+ * computation): for the LAST n_new tokens of sequence seq_index, whose length seq_lens
+ * already counts them, compute from their hidden states x
+ *     K_base rows = rope(x W_K^T),   V_base rows = x W_V^T,   L rows = x A
+ * (fp32 accumulation, one rounding to bf16) and write them into the caches described by
+ * `cache`, whose k_base / v_base / l are WRITTEN by this call although declared const in
+ * the struct.  Only BaseLRShared needs this once per appended token, for all agents.
+ *
+ *   x  DEVICE [n_new][d_model], dense, 16-byte aligned
+ * bf16 only; head_dim in {64, 128}; rank a multiple of 8.  No workspace.  Asynchronous on
+ * `stream` like the other calls.
+ */
+lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
+                            const void* x, int32_t seq_index, int32_t n_new, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* lra_status_string(lra_status status);
 

@@ -18,7 +18,7 @@ LRA_OK = 0
 LRA_BF16, LRA_F32 = 0, 1
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
-           "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill", "lra_set_prefill_splits",
+           "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill", "lra_set_prefill_splits",
            "lra_set_profile_mode")
 
 
@@ -40,6 +40,10 @@ class LraCache(ctypes.Structure):
 
 class LraAdapters(ctypes.Structure):
     _fields_ = [("b_k", ctypes.c_void_p), ("b_v", ctypes.c_void_p), ("n_adapters", ctypes.c_int32)]
+
+
+class LraProjection(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("d_model", ctypes.c_int32), ("rope_theta", ctypes.c_float)]
 
 
 class LraError(RuntimeError):
@@ -69,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.lra_attn_decode.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
     lib.lra_attn_prefill.restype = ctypes.c_int
     lib.lra_attn_prefill.argtypes = [sp, cp, ap, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.lra_cache_append.restype = ctypes.c_int
+    lib.lra_cache_append.argtypes = [sp, cp, ctypes.POINTER(LraProjection), vp, i32, i32, vp]
     lib.lra_status_string.restype = ctypes.c_char_p
     lib.lra_status_string.argtypes = [ctypes.c_int]
     lib.lra_set_kernel_variant.restype = i32
@@ -89,6 +95,17 @@ def load_library() -> ctypes.CDLL:
 
 def lra_status_string(status: int) -> str:
     return load_library().lra_status_string(int(status)).decode()
+
+
+def lra_cache_append(shape: LraShape, cache: LraCache, w: torch.Tensor, rope_theta: float, x: torch.Tensor,
+                     seq_index: int, stream=None) -> None:
+    """Project the new tokens x [n_new][d_model] with w [2*Hkv*d + r][d_model] and write their
+    K_base / V_base / L rows into the cache (the last n_new rows of sequence seq_index)."""
+    if not (x.is_contiguous() and w.is_contiguous()) or x.shape[1] != w.shape[1]:
+        raise LraError(2, "x and w must be dense and share d_model")
+    proj = LraProjection(_ptr(w), int(w.shape[1]), float(rope_theta))
+    _check(load_library().lra_cache_append(ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(proj), _ptr(x),
+                                           int(seq_index), int(x.shape[0]), _stream_ptr(stream)))
 
 
 def lra_set_kernel_variant(variant: int) -> int:

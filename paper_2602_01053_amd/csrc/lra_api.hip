@@ -306,6 +306,46 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   return LRA_OK;
 }
 
+lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
+                            const void* x, int32_t seq_index, int32_t n_new, void* stream) {
+  lra_status st = check_common(shape, cache);
+  if (st != LRA_OK) return st;
+  if (!proj || !proj->w || !x) return LRA_ERR_NULL;
+  if (seq_index < 0 || seq_index >= cache->n_seqs) return LRA_ERR_SHAPE;
+  if (n_new < 1 || n_new > cache->max_seq_len) return LRA_ERR_SHAPE;
+  if (proj->d_model < 64 || !(proj->rope_theta >= 0.f)) return LRA_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(proj->w)) & 15) return LRA_ERR_SHAPE;
+  if (shape->dtype != LRA_BF16 || shape->rank % 8 != 0 || proj->d_model % 64 != 0) return LRA_ERR_UNSUPPORTED;
+  // x and w are addressed with 32-bit byte offsets inside one buffer resource each
+  const int64_t lim = (int64_t{1} << 32) - 4096;
+  const int64_t n_feat = 2LL * shape->n_kv_heads * shape->head_dim + shape->rank;
+  if (n_feat * proj->d_model * 2 > lim || static_cast<int64_t>(n_new) * proj->d_model * 2 > lim)
+    return LRA_ERR_UNSUPPORTED;
+  AppendParams p{};
+  p.x = x;
+  p.w = proj->w;
+  p.k_base = const_cast<void*>(cache->k_base);
+  p.v_base = const_cast<void*>(cache->v_base);
+  p.l = const_cast<void*>(cache->l);
+  p.block_table = cache->block_table;
+  p.seq_lens = cache->seq_lens;
+  p.kv_token_stride = cache->kv_token_stride;
+  p.kv_head_stride = cache->kv_head_stride;
+  p.kv_block_stride = cache->kv_block_stride;
+  p.d_model = proj->d_model;
+  p.n_kv_heads = shape->n_kv_heads;
+  p.head_dim = shape->head_dim;
+  p.rank = shape->rank;
+  p.n_new = n_new;
+  p.seq_index = seq_index;
+  p.block_size = cache->block_size;
+  p.max_blocks_per_seq = cache->max_blocks_per_seq;
+  p.max_seq_len = cache->max_seq_len;
+  p.rope_theta = proj->rope_theta;
+  if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return LRA_ERR_HIP;
+  return LRA_OK;
+}
+
 const char* lra_status_string(lra_status status) {
   switch (status) {
     case LRA_OK: return "ok";

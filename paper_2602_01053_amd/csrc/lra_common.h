@@ -98,4 +98,20 @@ int decode_mfma_row_tiles(int rows_needed);
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s);
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s);
 
+// Arguments of the cache-append producer kernel.
+struct AppendParams {
+  const void* x;   // [n_new][d_model]
+  const void* w;   // [2*Hkv*d + rank][d_model]
+  void* k_base;
+  void* v_base;
+  void* l;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  int64_t kv_token_stride, kv_head_stride, kv_block_stride;
+  int32_t d_model, n_kv_heads, head_dim, rank, n_new, seq_index;
+  int32_t block_size, max_blocks_per_seq, max_seq_len;
+  float rope_theta;
+};
+hipError_t launch_append(const AppendParams& p, hipStream_t s);
+
 }  // namespace lra

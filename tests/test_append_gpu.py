@@ -1,0 +1,145 @@
+"""Parity of the cache-append producer (lra_cache_append) against the fp64 oracle, through
+the C ABI.  Bar as for the attention calls: relative L2 <= 5e-3 over every written tensor
+and over every token, max-abs <= 2e-2 (outputs are O(1): x ~ N(0,1), w ~ N(0, 1/d_model))."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_01053_amd as lra
+from tests.harness import MAX_ABS_TOL, REL_L2_TOL, errors
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SENTINEL = 7.0   # value of every cache element before the call: rows that are not appended must keep it
+
+
+def _inputs(seed, n_new, d_model, hkv, d, r):
+    gen = torch.Generator().manual_seed(seed)
+    x = torch.randn(n_new, d_model, generator=gen).to(torch.bfloat16)
+    w = (torch.randn(2 * hkv * d + r, d_model, generator=gen) / d_model ** 0.5).to(torch.bfloat16)
+    return x, w
+
+
+def _gate(got, ref, label):
+    rel, mx = errors(got, ref)
+    print(f"{label}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL, (label, rel, mx)
+
+
+CASES = [
+    # n (after the append), n_new, d_model, Hkv, d, r, rope_theta
+    (1, 1, 64, 1, 64, 8, 10000.0),
+    (200, 129, 256, 2, 128, 16, 500000.0),      # ragged token tile
+    (300, 300, 512, 3, 64, 24, 10000.0),        # no old rows; Hkv*d = 192: a partly filled feature tile
+    (70000, 130, 1024, 8, 128, 16, 500000.0),   # positions in the tens of thousands
+    (513, 257, 4096, 8, 128, 64, 0.0),          # Llama-3-8B projection shape, keys stored unrotated
+    (1000, 512, 1024, 4, 128, 32, 500000.0),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
+def test_append_contiguous(case):
+    n, n_new, d_model, hkv, d, r, theta = case
+    x, w = _inputs(5000 + n + n_new, n_new, d_model, hkv, d, r)
+    k_base = torch.full((n, hkv, d), SENTINEL, dtype=torch.bfloat16, device=DEV)
+    v_base = torch.full_like(k_base, SENTINEL)
+    l = torch.full((n, r), SENTINEL, dtype=torch.bfloat16, device=DEV)
+    seq_lens = torch.tensor([n], dtype=torch.int32, device=DEV)
+    q_like = torch.empty(1, hkv, d, dtype=torch.bfloat16, device=DEV)
+    shape = lra.make_shape(q_like, hkv, r, 0.0)
+    cache = lra.make_cache(k_base, v_base, l, seq_lens, n, None)
+    xd, wd = x.to(DEV), w.to(DEV)
+    lra.lra_cache_append(shape, cache, wd, theta, xd, 0)
+    torch.cuda.synchronize()
+    f = lambda t: t.to(torch.float64).cpu().numpy()
+    pos = np.arange(n - n_new, n)
+    k_ref, v_ref, l_ref = oracle.project_new_tokens(f(x), f(w), hkv, d, r, pos, theta)
+    _gate(f(k_base)[n - n_new:], k_ref, "K rows")
+    _gate(f(v_base)[n - n_new:], v_ref, "V rows")
+    _gate(f(l)[n - n_new:], l_ref, "L rows")
+    for t in (k_base, v_base, l):   # older rows untouched
+        assert bool((t[:n - n_new] == SENTINEL).all())
+
+
+def test_append_paged_then_attend():
+    """Appends to two sequences of a paged cache (a last block that is partly filled, blocks in
+    permuted order), checks the written rows and that nothing else moved, then runs the
+    attention prefill on the appended tokens and compares it with the oracle evaluated on
+    the cache the producer wrote."""
+    hkv, hq, d, r, d_model, theta = 2, 8, 128, 16, 512, 500000.0
+    seq_lens = [77, 300]
+    n_new = [30, 130]
+    bs, max_blocks = 16, 20
+    num_blocks = 45
+    gen = torch.Generator().manual_seed(6001)
+    perm = torch.randperm(num_blocks, generator=gen).to(torch.int32)
+    table = torch.stack([perm[:max_blocks], perm[max_blocks:2 * max_blocks]])
+    k_pool = torch.randn(num_blocks, hkv, bs, d, generator=gen).to(torch.bfloat16)
+    v_pool = torch.randn(num_blocks, hkv, bs, d, generator=gen).to(torch.bfloat16)
+    l_pool = torch.randn(num_blocks, bs, r, generator=gen).to(torch.bfloat16)
+    kd, vd, ld = k_pool.to(DEV), v_pool.to(DEV), l_pool.to(DEV)
+    lens_d = torch.tensor(seq_lens, dtype=torch.int32, device=DEV)
+    table_d = table.to(DEV)
+    q_like = torch.empty(1, hq, d, dtype=torch.bfloat16, device=DEV)
+    shape = lra.make_shape(q_like, hkv, r, 0.0)
+    cache = lra.make_cache(kd, vd, ld, lens_d, max(seq_lens), table_d)
+    f = lambda t: t.to(torch.float64).cpu().numpy()
+    k_exp, v_exp, l_exp = f(k_pool).copy(), f(v_pool).copy(), f(l_pool).copy()
+    w = None
+    for s in range(2):
+        x, w = _inputs(6100 + s, n_new[s], d_model, hkv, d, r)
+        lra.lra_cache_append(shape, cache, w.to(DEV), theta, x.to(DEV), s)
+        torch.cuda.synchronize()
+        pos = np.arange(seq_lens[s] - n_new[s], seq_lens[s])
+        k_ref, v_ref, l_ref = oracle.project_new_tokens(f(x), f(w), hkv, d, r, pos, theta)
+        ids = table[s].numpy()
+        got_k = oracle.gather_paged(f(kd), ids, seq_lens[s])[seq_lens[s] - n_new[s]:]
+        got_v = oracle.gather_paged(f(vd), ids, seq_lens[s])[seq_lens[s] - n_new[s]:]
+        got_l = oracle.lra_oracle.gather_paged_l(f(ld), ids, seq_lens[s])[seq_lens[s] - n_new[s]:]
+        _gate(got_k, k_ref, f"paged K rows seq {s}")
+        _gate(got_v, v_ref, f"paged V rows seq {s}")
+        _gate(got_l, l_ref, f"paged L rows seq {s}")
+        # everything except the appended rows is bit-identical to before
+        oracle.scatter_paged(k_exp, ids, seq_lens[s] - n_new[s], got_k)
+        oracle.scatter_paged(v_exp, ids, seq_lens[s] - n_new[s], got_v)
+        oracle.scatter_paged_l(l_exp, ids, seq_lens[s] - n_new[s], got_l)
+        np.testing.assert_array_equal(f(kd), k_exp)
+        np.testing.assert_array_equal(f(vd), v_exp)
+        np.testing.assert_array_equal(f(ld), l_exp)
+    # attention over the cache the producer wrote (sequence 1, its 130 new tokens)
+    s = 1
+    gen = torch.Generator().manual_seed(6200)
+    q = torch.randn(n_new[s], hq, d, generator=gen).to(torch.bfloat16)
+    b_k = (0.05 * torch.randn(2, r, hkv * d, generator=gen)).to(torch.bfloat16)
+    b_v = (0.05 * torch.randn(2, r, hkv * d, generator=gen)).to(torch.bfloat16)
+    qd = q.to(DEV)
+    out = torch.full_like(qd, float("nan"))
+    ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, 1, 1, n_new[s]), 256), dtype=torch.uint8, device=DEV)
+    lra.lra_attn_prefill(shape, cache, b_k.to(DEV), b_v.to(DEV), 2, qd, s, 1, out, ws)
+    torch.cuda.synchronize()
+    ids = table[s].numpy()
+    kb = oracle.gather_paged(f(kd), ids, seq_lens[s])
+    vb = oracle.gather_paged(f(vd), ids, seq_lens[s])
+    lr = oracle.lra_oracle.gather_paged_l(f(ld), ids, seq_lens[s])
+    ref = oracle.prefill(f(q), kb, vb, lr, f(b_k[1]), f(b_v[1]), n=seq_lens[s], scale=1.0 / d ** 0.5)
+    _gate(f(out), ref, "attention over the appended cache")
+
+
+def test_append_rejects_what_it_cannot_do():
+    hkv, d, r = 2, 128, 16
+    k_base = torch.zeros(64, hkv, d, dtype=torch.bfloat16, device=DEV)
+    l = torch.zeros(64, r, dtype=torch.bfloat16, device=DEV)
+    seq_lens = torch.tensor([64], dtype=torch.int32, device=DEV)
+    shape = lra.make_shape(torch.empty(1, hkv, d, dtype=torch.bfloat16, device=DEV), hkv, r, 0.0)
+    cache = lra.make_cache(k_base, k_base.clone(), l, seq_lens, 64, None)
+    w = torch.zeros(2 * hkv * d + r, 96, dtype=torch.bfloat16, device=DEV)   # d_model not a multiple of 64
+    x = torch.zeros(4, 96, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(lra.LraError) as e:
+        lra.lra_cache_append(shape, cache, w, 10000.0, x, 0)
+    assert e.value.status == 4
+    w = torch.zeros(2 * hkv * d + r, 128, dtype=torch.bfloat16, device=DEV)
+    x = torch.zeros(65, 128, dtype=torch.bfloat16, device=DEV)              # more new tokens than the cache holds
+    with pytest.raises(lra.LraError) as e:
+        lra.lra_cache_append(shape, cache, w, 10000.0, x, 0)
+    assert e.value.status == 2
