@@ -232,6 +232,21 @@ int32_t lra_set_kernel_variant(int32_t variant);
 int32_t lra_set_decode_split_keys(int32_t keys);
 
 /*
+ * Tuning and test hook: lra_cache_append calls with at most this many new tokens run the
+ * weight-streaming kernel (16 features per workgroup, d_model split over its waves) instead
+ * of the tiled GEMM; any value is valid, both kernels handle any n_new.  0 switches the
+ * streaming kernel off.  Returns the previous value.  Default 64.
+ */
+int32_t lra_set_append_skinny(int32_t tokens);
+
+/*
+ * Tuning and test hook: number of LDS stages (requests in flight) of lra_cache_append's
+ * tiled GEMM: 2, 3 or 4; anything else restores the default (4 when the grid has at most one
+ * workgroup per compute unit, else 2 with two workgroups per unit).  Returns the previous value.
+ */
+int32_t lra_set_append_stages(int32_t stages);
+
+/*
  * Tuning and test hook: bf16 prefill calls with at most this many new tokens (and a context
  * at least four times as long) run on the split-KV decode kernels, the new tokens standing
  * in for the agents, instead of on the tile-walking prefill kernel; they then need a

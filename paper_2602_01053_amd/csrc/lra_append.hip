@@ -22,14 +22,14 @@
 
 namespace lra {
 
-template <int D, bool PAGED>
-__global__ __launch_bounds__(256, 2) void append_kernel(AppendParams p) {
+template <int D, bool PAGED, int NS>
+__global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendParams p) {
   constexpr int BF = 128, BT = 128, BK = 64;  // features, tokens, d_model step
   constexpr int TILE_BYTES = BF * BK * 2;      // one operand tile: 128 rows of 128 bytes
   constexpr int STAGE = 2 * TILE_BYTES;        // [W tile][X tile]
   constexpr int HALF = D / 2;
 
-  __shared__ __align__(16) unsigned char smem[2 * STAGE];
+  __shared__ __align__(16) unsigned char smem[NS * STAGE];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -70,17 +70,25 @@ __global__ __launch_bounds__(256, 2) void append_kernel(AppendParams p) {
       pf_load16_to_lds(rs_x, dst + TILE_BYTES, voff, static_cast<uint32_t>(tok0 + 8 * i) * ldw2 + k0 * 2);
     }
   };
-  issue_step(0, 0);
+  const int n_steps = p.d_model / BK;
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+    if (st < n_steps) issue_step(st * BK, st);
 
   // ---------------- operands ----------------
   // A operand: W rows (features), B operand: X rows (tokens); lane (row l32 of a 32-row block,
   // k = 16ks + 8g2 + e): the 16-byte chunk 2ks + g2 of its row, at chunk ^ ((row >> 1) & 7).
   const int pre = l32 * (BK * 2) + (((l32 >> 1) & 7) << 4);
   // the wave's two feature blocks are half a head apart: rotary pairs meet in one lane
-  const int fb0 = D == 128 ? wr : 2 * wr;
-  const int fb1 = D == 128 ? wr + 2 : 2 * wr + 1;
+  // The L tile holds at most 64 features (blocks 0 and 1): there every wave takes both and
+  // one token block, half the matrix work of a K or V tile.
+  const bool lr_tile = kind == 2;
+  const int fb0 = lr_tile ? 0 : (D == 128 ? wr : 2 * wr);
+  const int fb1 = lr_tile ? 1 : (D == 128 ? wr + 2 : 2 * wr + 1);
+  const int tb0 = lr_tile ? wave : 2 * wc;
+  const int tb1 = 2 * wc + 1;  // unused by the L tile
 
-  pf_f32x16 acc[2][2];  // [feature block 0/1][token block 2wc / 2wc+1]
+  pf_f32x16 acc[2][2];  // [feature block fb0 / fb1][token block tb0 / tb1]
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -88,44 +96,70 @@ __global__ __launch_bounds__(256, 2) void append_kernel(AppendParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  pf_wait_vm0();
-  __syncthreads();
-  const int n_steps = p.d_model / BK;
-  auto k_step = [&](int step, auto st_c) {
+  // Step s computes on stage s % NS while the tiles of the next NS - 2 steps are in flight and
+  // the one after them is requested: a wave waits until only the loads younger than step s
+  // (8 per step and wave) are outstanding, the barrier makes every wave's share visible and
+  // retires stage (s - 1) % NS, which the new request then overwrites.
+  // The 16 operand reads of a step are issued together, ahead of its 16 MFMAs: the matrix
+  // pipe starts on the first operands while the rest are still on their way.
+  auto k_step = [&](int step, auto st_c, auto lr_c) {
     constexpr int ST = decltype(st_c)::value;
-    if (step + 1 < n_steps) issue_step((step + 1) * BK, ST ^ 1);
+    constexpr bool LR = decltype(lr_c)::value;
+    if (step + NS - 2 < n_steps) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (NS - 2)));
+    else pf_wait_vm0();
+    __syncthreads();
+    if (step + NS - 1 < n_steps) issue_step((step + NS - 1) * BK, (ST + NS - 1) % NS);
     const unsigned char* wt = smem + ST * STAGE;
     const unsigned char* xt = wt + TILE_BYTES;
+    pf_bf16x8 a0[BK / 16], a1[BK / 16], b0[BK / 16], b1[BK / 16];
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       const int off = pre ^ ((2 * ks + g2) << 4);
-      const pf_bf16x8 a0 = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb0 * 32 * (BK * 2)));
-      const pf_bf16x8 a1 = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb1 * 32 * (BK * 2)));
-      const pf_bf16x8 b0 = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + (2 * wc) * 32 * (BK * 2)));
-      const pf_bf16x8 b1 = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + (2 * wc + 1) * 32 * (BK * 2)));
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+      a0[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb0 * 32 * (BK * 2)));
+      b0[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb0 * 32 * (BK * 2)));
+      a1[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb1 * 32 * (BK * 2)));
+      if (!LR) b1[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb1 * 32 * (BK * 2)));
     }
-    // the next step's tiles have landed (this wave's share) and everybody is done with these
-    pf_wait_vm0();
-    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[ks], b0[ks], acc[0][0], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[ks], b0[ks], acc[1][0], 0, 0, 0);
+      if (!LR) {
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[ks], b1[ks], acc[0][1], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[ks], b1[ks], acc[1][1], 0, 0, 0);
+      }
+    }
+    // order for the scheduler: the reads of two k-slices, then one read per MFMA, then the rest
+    constexpr int READS = LR ? 12 : 16, MFMAS = LR ? 8 : 16, AHEAD = READS / 2;
+    __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+    for (int i = 0; i < READS - AHEAD; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - (READS - AHEAD), 0);
   };
-  for (int step = 0; step < n_steps; step += 2) {
-    k_step(step, std::integral_constant<int, 0>{});
-    if (step + 1 < n_steps) k_step(step + 1, std::integral_constant<int, 1>{});
-  }
+  auto k_loop = [&](auto lr_c) {
+    for (int step = 0; step < n_steps; step += NS) {
+      k_step(step, std::integral_constant<int, 0>{}, lr_c);
+      if (step + 1 < n_steps) k_step(step + 1, std::integral_constant<int, 1>{}, lr_c);
+      if (NS > 2 && step + 2 < n_steps) k_step(step + 2, std::integral_constant<int, 2 % NS>{}, lr_c);
+      if (NS > 3 && step + 3 < n_steps) k_step(step + 3, std::integral_constant<int, 3 % NS>{}, lr_c);
+    }
+  };
+  if (lr_tile) k_loop(std::true_type{});
+  else k_loop(std::false_type{});
 
   // ---------------- epilogue: rotate the keys, cast, store into the cache rows ----------------
   // acc[a][b], register i, lane (l32, g2): feature 32*fb_a + 8(i/4) + 4g2 + i%4 of the tile,
-  // token 32*(2wc + b) + l32 of the tile.
+  // token 32*tb_b + l32 of the tile.
   bf16_t* kcache = static_cast<bf16_t*>(kind == 0 ? p.k_base : p.v_base);
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
-    const int tok = tok0 + 32 * (2 * wc + b) + l32;
-    if (tok >= n_new) continue;
+    if (b == 1 && lr_tile) continue;
+    const int tok = tok0 + 32 * (b == 0 ? tb0 : tb1) + l32;
     const int j = pos0 + tok;  // cache row of this token, and its position
+    if (tok >= n_new || j < 0) continue;  // (a sequence length below n_new breaks the contract: nothing is written)
     int64_t row_off;           // element offset of (token j, kv head 0) in K_base / V_base, or of row j in L
     if (PAGED) {
       const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
@@ -178,17 +212,311 @@ __global__ __launch_bounds__(256, 2) void append_kernel(AppendParams p) {
   (void)HALF;
 }
 
+// ---------------------------------------------------------------------------------------
+// Few new tokens (a decode step appends one): the projection is one pass over the weights,
+// bound by HBM, and a 128 x 128 tile grid would put a handful of workgroups on the chip.
+// Here a workgroup owns 16 output features and 16 * NT tokens; its 8 waves split d_model
+// (wave w takes the 32-wide steps w, w+8, ...), feed v_mfma_f32_16x16x32_bf16 straight from
+// global loads (every weight element is used once: nothing to stage) and add their partial
+// tiles through LDS.  The 16 features are 8 + the 8 half a head further on, so the rotary
+// pairs meet in one thread of the epilogue.  blockIdx.y walks chunks of 16 * NT tokens.
+// ---------------------------------------------------------------------------------------
+template <int D, int NT, bool PAGED>
+__global__ __launch_bounds__(512) void append_skinny_kernel(AppendParams p) {
+  constexpr int NW = 8;
+  __shared__ __align__(16) float red[NW][NT][256];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, g4 = lane >> 4;
+  const int HD = p.n_kv_heads * D;
+  const int groups_kv = HD / 16;  // feature groups of the K (and of the V) region
+  const int fg = blockIdx.x;
+  const int kind = fg < groups_kv ? 0 : (fg < 2 * groups_kv ? 1 : 2);
+  const int fg_in = kind == 0 ? fg : (kind == 1 ? fg - groups_kv : fg - 2 * groups_kv);
+  const int head = fg_in / (D / 16), sub = fg_in - head * (D / 16);
+  // feature (inside its region) of tile row i: K/V  head*D + 8 sub + i  (i < 8),  + d/2 - 8 beyond;  L  16 fg_in + i
+  auto feature_of = [&](int i) {
+    return kind == 2 ? 16 * fg_in + i : head * D + 8 * sub + (i < 8 ? i : i - 8 + D / 2);
+  };
+  const int n_new = p.n_new;
+  const int tok0 = blockIdx.y * (16 * NT);
+  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int pos0 = n_t - n_new;
+
+  // operand rows of this lane (clamped into the tensors; what a clamped row produces is never stored)
+  const int w_row = (kind == 0 ? 0 : (kind == 1 ? HD : 2 * HD)) +
+                    (kind == 2 ? min(feature_of(l16), p.rank - 1) : feature_of(l16));
+  const int64_t ld = p.d_model;
+  const bf16_t* wp = static_cast<const bf16_t*>(p.w) + static_cast<int64_t>(w_row) * ld + 8 * g4;
+  const bf16_t* xp[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+    xp[t] = static_cast<const bf16_t*>(p.x) + static_cast<int64_t>(min(tok0 + 16 * t + l16, n_new - 1)) * ld + 8 * g4;
+
+  pf_f32x4 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) acc[t] = pf_f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // lane (l16, g4) of step s holds k = 32 s + 8 g4 .. + 8 of its W row (A) and of its token (B)
+  const int n_steps = p.d_model / 32;
+  constexpr int U = 16 / NT;  // steps in flight per wave (64 operand registers of x)
+  int s = wave;
+  for (; s + (U - 1) * NW < n_steps; s += U * NW) {
+    uint4 a[U], b[U][NT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      a[u] = *reinterpret_cast<const uint4*>(wp + (s + u * NW) * 32);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) b[u][t] = *reinterpret_cast<const uint4*>(xp[t] + (s + u * NW) * 32);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_as_bf16x8(a[u]), pf_as_bf16x8(b[u][t]), acc[t], 0, 0, 0);
+  }
+  for (; s < n_steps; s += NW) {
+    const uint4 a = *reinterpret_cast<const uint4*>(wp + s * 32);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const uint4 b = *reinterpret_cast<const uint4*>(xp[t] + s * 32);
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_as_bf16x8(a), pf_as_bf16x8(b), acc[t], 0, 0, 0);
+    }
+  }
+  // acc[t], register e, lane (l16, g4): tile row (feature) 4 g4 + e, token 16 t + l16
+#pragma unroll
+  for (int t = 0; t < NT; ++t) *reinterpret_cast<pf_f32x4*>(&red[wave][t][lane * 4]) = acc[t];
+  __syncthreads();
+
+  // thread (t, i < 8, token): sums the 8 partial tiles for rows i and i + 8, rotates, stores
+  if (tid >= NT * 128) return;
+  const int t = tid >> 7, i = (tid >> 4) & 7, tk = tid & 15;
+  const int tok = tok0 + 16 * t + tk;
+  if (tok >= n_new || pos0 + tok < 0) return;
+  const int at_lo = (tk + 16 * (i >> 2)) * 4 + (i & 3);  // row i      -> lane tk + 16 (i/4), register i%4
+  const int at_hi = at_lo + 128;                         // row i + 8  -> two lane groups further
+  float lo = 0.f, hi = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    lo += red[w][t][at_lo];
+    hi += red[w][t][at_hi];
+  }
+  const int j = pos0 + tok;
+  if (kind == 2) {
+    int64_t row_off;
+    if (PAGED) {
+      const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
+      row_off = (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank;
+    } else {
+      row_off = static_cast<int64_t>(j) * p.rank;
+    }
+    bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
+    const int f = 16 * fg_in + i;
+    if (f < p.rank) lrow[f] = f32_to_bf16(lo);
+    if (f + 8 < p.rank) lrow[f + 8] = f32_to_bf16(hi);
+    return;
+  }
+  const int dd = 8 * sub + i;  // < d/2
+  if (kind == 0 && p.rope_theta > 0.f) {
+    const double inv_freq = exp2(-2.0 * dd / D * log2(static_cast<double>(p.rope_theta)));
+    double ang = static_cast<double>(j) * inv_freq;
+    ang -= 6.283185307179586476925 * floor(ang * 0.15915494309189533577);
+    float sn, cs;
+    sincosf(static_cast<float>(ang), &sn, &cs);
+    const float a = lo, b = hi;
+    lo = a * cs - b * sn;
+    hi = b * cs + a * sn;
+  }
+  int64_t row_off;
+  if (PAGED) {
+    const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
+    row_off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(j & 15) * p.kv_token_stride;
+  } else {
+    row_off = static_cast<int64_t>(j) * p.kv_token_stride;
+  }
+  bf16_t* dst = static_cast<bf16_t*>(kind == 0 ? p.k_base : p.v_base) + row_off + static_cast<int64_t>(head) * p.kv_head_stride + dd;
+  dst[0] = f32_to_bf16(lo);
+  dst[D / 2] = f32_to_bf16(hi);
+}
+
+// ---------------------------------------------------------------------------------------
+// One to four new tokens (every decode step appends one): a matrix-vector product.  One wave
+// per weight row reads it in fully coalesced 1 KB pieces, all in flight at once, and forms
+// the dot products with v_dot2c_f32_bf16; the 2 * Hkv * d + r rows make several hundred
+// workgroups, enough outstanding loads to run at HBM speed.  A workgroup's four rows are two
+// rotary pairs (features f, f+1 and f + d/2, f+1 + d/2).
+// ---------------------------------------------------------------------------------------
+typedef __bf16 ap_bf16x2 __attribute__((ext_vector_type(2)));
+
+template <int D, int NT, bool PAGED>
+__global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
+  __shared__ float red[4][NT];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int HD = p.n_kv_heads * D;
+  const int groups_kv = HD / 4;
+  const int fg = blockIdx.x;
+  const int kind = fg < groups_kv ? 0 : (fg < 2 * groups_kv ? 1 : 2);
+  const int fg_in = kind == 0 ? fg : (kind == 1 ? fg - groups_kv : fg - 2 * groups_kv);
+  const int head = fg_in / (D / 4), sub = fg_in - head * (D / 4);  // K, V: pairs 2 sub, 2 sub + 1 of this head
+  const int pr = wave & 1, half = wave >> 1;
+  // row of this wave: K/V  head*D + 2 sub + pr (+ d/2 for the second half);  L  4 fg_in + pr + 2 half
+  const int feat = kind == 2 ? 4 * fg_in + pr + 2 * half : head * D + 2 * sub + pr + half * (D / 2);
+  const int w_row = kind == 2 ? 2 * HD + min(feat, p.rank - 1) : (kind == 1 ? HD : 0) + feat;
+  const int n_new = p.n_new;
+  const int64_t ld = p.d_model;
+  const uint4* wp = reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(p.w) + static_cast<int64_t>(w_row) * ld);
+  const uint4* xp[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+    xp[t] = reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(p.x) + static_cast<int64_t>(min(t, n_new - 1)) * ld);
+
+  float acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) acc[t] = 0.f;
+  const int n_chunks = p.d_model / 8;  // 16-byte pieces of a row; lane l takes l, l + 64, ...
+  constexpr int U = 8;
+  for (int c0 = lane; c0 < n_chunks; c0 += 64 * U) {
+    uint4 wv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int c = c0 + 64 * u;
+      wv[u] = c < n_chunks ? wp[c] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int c = c0 + 64 * u;
+        const uint4 xv = xp[t][c < n_chunks ? c : 0];  // (the weight piece is zero there)
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].x), __builtin_bit_cast(ap_bf16x2, xv.x), acc[t], false);
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].y), __builtin_bit_cast(ap_bf16x2, xv.y), acc[t], false);
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].z), __builtin_bit_cast(ap_bf16x2, xv.z), acc[t], false);
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].w), __builtin_bit_cast(ap_bf16x2, xv.w), acc[t], false);
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    float v = acc[t];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0) red[wave][t] = v;
+  }
+  __syncthreads();
+
+  // thread (pair, token): both halves of a rotary pair (K), two independent features (V, L)
+  if (tid >= 2 * NT) return;
+  const int q = tid & 1, t = tid >> 1;
+  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int j = n_t - n_new + t;
+  if (t >= n_new || j < 0) return;
+  float lo = red[q][t], hi = red[2 + q][t];
+  if (kind == 2) {
+    int64_t row_off;
+    if (PAGED) {
+      const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
+      row_off = (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank;
+    } else {
+      row_off = static_cast<int64_t>(j) * p.rank;
+    }
+    bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
+    const int f = 4 * fg_in + q;
+    if (f < p.rank) lrow[f] = f32_to_bf16(lo);
+    if (f + 2 < p.rank) lrow[f + 2] = f32_to_bf16(hi);
+    return;
+  }
+  const int dd = 2 * sub + q;  // < d/2
+  if (kind == 0 && p.rope_theta > 0.f) {
+    const double inv_freq = exp2(-2.0 * dd / D * log2(static_cast<double>(p.rope_theta)));
+    double ang = static_cast<double>(j) * inv_freq;
+    ang -= 6.283185307179586476925 * floor(ang * 0.15915494309189533577);
+    float sn, cs;
+    sincosf(static_cast<float>(ang), &sn, &cs);
+    const float a = lo, b = hi;
+    lo = a * cs - b * sn;
+    hi = b * cs + a * sn;
+  }
+  int64_t row_off;
+  if (PAGED) {
+    const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
+    row_off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(j & 15) * p.kv_token_stride;
+  } else {
+    row_off = static_cast<int64_t>(j) * p.kv_token_stride;
+  }
+  bf16_t* dst = static_cast<bf16_t*>(kind == 0 ? p.k_base : p.v_base) + row_off + static_cast<int64_t>(head) * p.kv_head_stride + dd;
+  dst[0] = f32_to_bf16(lo);
+  dst[D / 2] = f32_to_bf16(hi);
+}
+
+template <int D, int NT>
+static void launch_gemv(const AppendParams& p, hipStream_t s) {
+  const int hd = p.n_kv_heads * p.head_dim;
+  dim3 grid(2 * (hd / 4) + (p.rank + 3) / 4);
+  if (p.block_size != 0) hipLaunchKernelGGL((append_gemv_kernel<D, NT, true>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((append_gemv_kernel<D, NT, false>), grid, dim3(256), 0, s, p);
+}
+
+template <int D, int NT>
+static void launch_skinny(const AppendParams& p, hipStream_t s) {
+  const int hd = p.n_kv_heads * p.head_dim;
+  dim3 grid(2 * (hd / 16) + (p.rank + 15) / 16, (p.n_new + 16 * NT - 1) / (16 * NT));
+  if (p.block_size != 0) hipLaunchKernelGGL((append_skinny_kernel<D, NT, true>), grid, dim3(512), 0, s, p);
+  else hipLaunchKernelGGL((append_skinny_kernel<D, NT, false>), grid, dim3(512), 0, s, p);
+}
+
 hipError_t launch_append(const AppendParams& p, hipStream_t s) {
   const int hd = p.n_kv_heads * p.head_dim;
+  if (p.n_new <= 4 && p.n_new <= p.skinny_max) {
+    if (p.head_dim == 128) {
+      if (p.n_new == 1) launch_gemv<128, 1>(p, s);
+      else if (p.n_new == 2) launch_gemv<128, 2>(p, s);
+      else launch_gemv<128, 4>(p, s);
+    } else {
+      if (p.n_new == 1) launch_gemv<64, 1>(p, s);
+      else if (p.n_new == 2) launch_gemv<64, 2>(p, s);
+      else launch_gemv<64, 4>(p, s);
+    }
+    return hipGetLastError();
+  }
+  if (p.n_new <= p.skinny_max) {
+    const int nt = p.n_new <= 16 ? 1 : (p.n_new <= 32 ? 2 : 4);
+    if (p.head_dim == 128) {
+      if (nt == 1) launch_skinny<128, 1>(p, s);
+      else if (nt == 2) launch_skinny<128, 2>(p, s);
+      else launch_skinny<128, 4>(p, s);
+    } else {
+      if (nt == 1) launch_skinny<64, 1>(p, s);
+      else if (nt == 2) launch_skinny<64, 2>(p, s);
+      else launch_skinny<64, 4>(p, s);
+    }
+    return hipGetLastError();
+  }
   dim3 grid((p.n_new + 127) / 128, 2 * ((hd + 127) / 128) + 1);
   const bool paged = p.block_size != 0;
+  // One workgroup per compute unit or fewer: nothing shares the LDS, so a deeper ring of
+  // stages (more requests in flight per workgroup) is free; beyond that two workgroups per
+  // unit with two stages each hide each other's waits.
+  const int stages = p.stages != 0 ? p.stages : (static_cast<int>(grid.x * grid.y) <= 256 ? 4 : 2);
+#define LRA_APPEND_LAUNCH(DD, PG, NS_) hipLaunchKernelGGL((append_kernel<DD, PG, NS_>), grid, dim3(256), 0, s, p)
+#define LRA_APPEND_STAGES(DD, PG)            \
+  do {                                       \
+    if (stages == 2) LRA_APPEND_LAUNCH(DD, PG, 2);      \
+    else if (stages == 3) LRA_APPEND_LAUNCH(DD, PG, 3); \
+    else LRA_APPEND_LAUNCH(DD, PG, 4);                  \
+  } while (0)
   if (p.head_dim == 128) {
-    if (paged) hipLaunchKernelGGL((append_kernel<128, true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((append_kernel<128, false>), grid, dim3(256), 0, s, p);
+    if (paged) LRA_APPEND_STAGES(128, true);
+    else LRA_APPEND_STAGES(128, false);
   } else {
-    if (paged) hipLaunchKernelGGL((append_kernel<64, true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((append_kernel<64, false>), grid, dim3(256), 0, s, p);
+    if (paged) LRA_APPEND_STAGES(64, true);
+    else LRA_APPEND_STAGES(64, false);
   }
+#undef LRA_APPEND_STAGES
+#undef LRA_APPEND_LAUNCH
   return hipGetLastError();
 }
 

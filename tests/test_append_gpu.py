@@ -38,6 +38,45 @@ CASES = [
 ]
 
 
+# few new tokens: the weight-streaming kernel (and, with it switched off, the tiled one on the same inputs)
+SMALL = [
+    (1, 1, 64, 1, 64, 8, 10000.0),
+    (4097, 1, 4096, 8, 128, 16, 500000.0),     # a decode step at the Llama-3-8B shape
+    (9, 2, 192, 2, 64, 8, 10000.0),            # matrix-vector kernel, d_model/8 = 24 pieces: lanes without one
+    (31, 3, 1088, 2, 128, 24, 500000.0),       # three tokens on the four-token instantiation; 136 pieces: a ragged second round
+    (40000, 4, 4096, 8, 128, 16, 500000.0),
+    (50, 7, 320, 2, 64, 24, 10000.0),          # d_model/32 = 10 steps over 8 waves; rank 24: a partly filled L group
+    (100, 16, 512, 2, 128, 16, 500000.0),
+    (100, 17, 512, 2, 128, 40, 500000.0),
+    (65000, 33, 1024, 4, 128, 16, 500000.0),
+    (64, 64, 768, 3, 64, 64, 10000.0),
+    (300, 150, 512, 2, 128, 16, 500000.0),     # beyond the default limit: runs streamed only when the limit is raised
+]
+
+
+@pytest.mark.parametrize("skinny", [0, 64, 1 << 30], ids=["tiled", "default", "streamed"])
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
+def test_append_few_tokens(case, skinny):
+    prev = lra.lra_set_append_skinny(skinny)
+    try:
+        test_append_contiguous(case)
+    finally:
+        lra.lra_set_append_skinny(prev)
+
+
+@pytest.mark.parametrize("stages", [2, 3, 4])
+@pytest.mark.parametrize("case", [SMALL[0], (200, 129, 256, 2, 128, 16, 500000.0), (700, 300, 704, 3, 64, 24, 10000.0)],
+                         ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
+def test_append_tiled_stage_counts(case, stages):
+    """The tiled GEMM with 2, 3 and 4 LDS stages (d_model of 1, 4 and 11 steps: shorter than the ring, and ragged against it)."""
+    prev_s, prev_k = lra.lra_set_append_stages(stages), lra.lra_set_append_skinny(0)
+    try:
+        test_append_contiguous(case)
+    finally:
+        lra.lra_set_append_stages(prev_s)
+        lra.lra_set_append_skinny(prev_k)
+
+
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
 def test_append_contiguous(case):
     n, n_new, d_model, hkv, d, r, theta = case
@@ -62,7 +101,16 @@ def test_append_contiguous(case):
         assert bool((t[:n - n_new] == SENTINEL).all())
 
 
-def test_append_paged_then_attend():
+@pytest.mark.parametrize("skinny", [0, 1 << 30], ids=["tiled", "streamed"])
+def test_append_paged_then_attend(skinny):
+    prev = lra.lra_set_append_skinny(skinny)
+    try:
+        _paged_then_attend()
+    finally:
+        lra.lra_set_append_skinny(prev)
+
+
+def _paged_then_attend():
     """Appends to two sequences of a paged cache (a last block that is partly filled, blocks in
     permuted order), checks the written rows and that nothing else moved, then runs the
     attention prefill on the appended tokens and compares it with the oracle evaluated on
