@@ -15,6 +15,7 @@ The JSON line also carries
   roofline      the key-streaming kernel alone (no merge), HIP events on its stream
                 around the same number of back-to-back launches,
   prefill       the causal prefill workload (2048 new tokens after 16384), TFLOP/s,
+  cache_append  the producer of the caches (lra_cache_append) at the Llama-3-8B projection shape,
   cpu_baseline  the fp64 oracle timed on this machine's host cores.
 """
 from __future__ import annotations
@@ -177,6 +178,85 @@ def bench_prefill(args, torch, lra, workloads):
     return w, flops, sec, ksec, steps
 
 
+def bench_append(args, torch, lra, with_cpu, sizes=(16384, 2048, 1)):
+    """lra_cache_append at the Llama-3-8B projection shape (d_model 4096 -> 8 kv heads x 128 keys
+    and values + rank 16, rotary base 500000): the chunk sizes of the prefill workload and of
+    the longest trace step (MFMA-bound, TFLOP/s) and one decode step (one pass over the
+    weights, HBM-bound, GB/s).  HIP events around replays of a HIP graph of back-to-back calls;
+    one call is one kernel."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    hkv, d, r, dm, theta = 8, 128, 16, 4096, 500000.0
+    gen = torch.Generator(device="cpu").manual_seed(20260203)
+    w_host = (torch.randn(2 * hkv * d + r, dm, generator=gen) / dm ** 0.5).to(torch.bfloat16)
+    w = w_host.to(dev)
+    shape = lra.make_shape(torch.empty(1, hkv, d, dtype=torch.bfloat16, device=dev), hkv, r, 0.0)
+    hip = _hip()
+    stream = torch.cuda.current_stream().cuda_stream or None
+    rows = []
+    for n_new in sizes:
+        x = torch.randn(n_new, dm, generator=gen).to(torch.bfloat16).to(dev)
+        k = torch.empty(n_new, hkv, d, dtype=torch.bfloat16, device=dev)
+        v = torch.empty_like(k)
+        l = torch.empty(n_new, r, dtype=torch.bfloat16, device=dev)
+        lens = torch.tensor([n_new], dtype=torch.int32, device=dev)
+        cache = lra.make_cache(k, v, l, lens, n_new, None)
+        # the calls are captured into a HIP graph and the graph is replayed: a decode-step call
+        # is shorter than the Python call overhead, which would otherwise be what is timed
+        per_graph, replays = (10, 5) if n_new > 64 else (100, 5)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                lra.lra_cache_append(shape, cache, w, theta, x, 0, side)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(per_graph):
+                lra.lra_cache_append(shape, cache, w, theta, x, 0, side)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+        assert hip.hipEventRecord(e0, stream) == 0
+        for _ in range(replays):
+            graph.replay()
+        assert hip.hipEventRecord(e1, stream) == 0
+        hip.hipEventSynchronize(e1)
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+        hip.hipEventDestroy(e0)
+        hip.hipEventDestroy(e1)
+        del graph
+        sec = ms.value * 1e-3 / (per_graph * replays)
+        flops = 2.0 * n_new * dm * (2 * hkv * d + r)
+        nbytes = 2.0 * ((2 * hkv * d + r) * dm + n_new * dm + n_new * (2 * hkv * d + r))
+        row = {"n_new": n_new, "us_per_call": round(sec * 1e6, 2), "algorithmic_flops": flops,
+               "algorithmic_bytes": nbytes}
+        if n_new > 64:
+            tf = flops / sec / 1e12
+            row["roofline"] = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                               "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+        else:
+            gbs = nbytes / sec / 1e9
+            row["roofline"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": round(gbs / HBM_PEAK_GBS, 4),
+                               "note": "back-to-back calls re-read the same 17 MB of weights: served partly by the memory-side cache"}
+        rows.append(row)
+    out = {"call": "lra_cache_append", "workload": "Llama-3-8B key/value/LoRA-down projection, d_model 4096, bf16, rotary keys",
+           "rows": rows}
+    if with_cpu:
+        import oracle
+        n_s = 256
+        xs = torch.randn(n_s, dm, generator=gen).to(torch.bfloat16).to(torch.float64).numpy()
+        ws = w_host.to(torch.float64).numpy()
+        t0 = time.perf_counter()
+        oracle.project_new_tokens(xs, ws, hkv, d, r, np.arange(1000, 1000 + n_s), theta)
+        sec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * n_s * dm * (2 * hkv * d + r) / sec / 1e12, 5), "unit": "TFLOP/s",
+                               "kind": "oracle", "seconds": round(sec, 4), "sample": f"{n_s} new tokens, fp64 numpy oracle, one run"}
+    return out
+
+
 def cpu_baseline(workloads):
     """The oracle as it stands, on the host cores, on the decode workload."""
     import numpy as np  # noqa: F401
@@ -209,6 +289,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-other-decode", action="store_true")
+    ap.add_argument("--no-append", action="store_true")
+    ap.add_argument("--append-only", action="store_true",
+                    help="only the lra_cache_append sweep over chunk sizes (its own JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -222,6 +305,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     lra.load_library()
+
+    if args.append_only:
+        print(json.dumps(bench_append(args, torch, lra, False,
+                                      sizes=(1, 2, 4, 8, 16, 32, 64, 128, 512, 1024, 2048, 8192, 16384))), flush=True)
+        return
 
     w, alg_bytes, sec_cold, sec_hot, ksec, n_copies = bench_decode(args, torch, lra, workloads)
     gbs = alg_bytes / sec_cold / 1e9
@@ -256,6 +344,8 @@ def main():
     if not args.no_other_decode:
         line["other_decode_workloads"] = other_decode_workloads(args, torch, lra, workloads)
         line["value_only_adapters"] = value_only_decode(args, torch, lra, workloads)
+    if not args.no_append:
+        line["cache_append"] = bench_append(args, torch, lra, not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(workloads)
     print(json.dumps(line), flush=True)

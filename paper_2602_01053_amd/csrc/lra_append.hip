@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
 // Few new tokens (a decode step appends one): the projection is one pass over the weights,
 // bound by HBM, and a 128 x 128 tile grid would put a handful of workgroups on the chip.
 // Here a workgroup owns 16 output features and 16 * NT tokens; its 8 waves split d_model
-// (wave w takes the 32-wide steps w, w+8, ...), feed v_mfma_f32_16x16x32_bf16 straight from
+// (wave w takes the 64-wide steps w, w+8, ...), feed v_mfma_f32_16x16x32_bf16 straight from
 // global loads (every weight element is used once: nothing to stage) and add their partial
 // tiles through LDS.  The 16 features are 8 + the 8 half a head further on, so the rotary
 // pairs meet in one thread of the epilogue.  blockIdx.y walks chunks of 16 * NT tokens.
@@ -259,30 +259,46 @@ __global__ __launch_bounds__(512) void append_skinny_kernel(AppendParams p) {
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = pf_f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // lane (l16, g4) of step s holds k = 32 s + 8 g4 .. + 8 of its W row (A) and of its token (B)
-  const int n_steps = p.d_model / 32;
-  constexpr int U = 16 / NT;  // steps in flight per wave (64 operand registers of x)
+  // A step covers 64 values of d_model with two MFMAs: lane (l16, g4) holds k = 64 s + 16 g4 .. + 16
+  // of its W row (A) and of its token (B), the first eight for one MFMA, the rest for the other
+  // (any assignment of k to lanes is right as long as A and B share it); four lanes read one
+  // 128-byte line of a row.
+  const int n_steps = p.d_model / 64;
+  constexpr int U = 8 / NT;  // steps in flight per wave (64 operand registers of x)
+  const bf16_t* wq = wp + 8 * g4;  // wp and xp already carry 8 g4
   int s = wave;
   for (; s + (U - 1) * NW < n_steps; s += U * NW) {
-    uint4 a[U], b[U][NT];
+    pf_u32x4 a[U][2], b[U][NT][2];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      a[u] = *reinterpret_cast<const uint4*>(wp + (s + u * NW) * 32);
+      a[u][0] = *reinterpret_cast<const pf_u32x4*>(wq + (s + u * NW) * 64);
+      a[u][1] = *reinterpret_cast<const pf_u32x4*>(wq + (s + u * NW) * 64 + 8);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) b[u][t] = *reinterpret_cast<const uint4*>(xp[t] + (s + u * NW) * 32);
+      for (int t = 0; t < NT; ++t) {
+        b[u][t][0] = *reinterpret_cast<const pf_u32x4*>(xp[t] + 8 * g4 + (s + u * NW) * 64);
+        b[u][t][1] = *reinterpret_cast<const pf_u32x4*>(xp[t] + 8 * g4 + (s + u * NW) * 64 + 8);
+      }
     }
+    // every request of the batch is out before the first result is used (left alone the
+    // compiler recycles a few registers and the loads trickle out a handful at a time)
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int t = 0; t < NT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_as_bf16x8(a[u]), pf_as_bf16x8(b[u][t]), acc[t], 0, 0, 0);
+      for (int t = 0; t < NT; ++t) {
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(pf_bf16x8, a[u][0]), __builtin_bit_cast(pf_bf16x8, b[u][t][0]), acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(pf_bf16x8, a[u][1]), __builtin_bit_cast(pf_bf16x8, b[u][t][1]), acc[t], 0, 0, 0);
+      }
   }
   for (; s < n_steps; s += NW) {
-    const uint4 a = *reinterpret_cast<const uint4*>(wp + s * 32);
+    const uint4 a0 = *reinterpret_cast<const uint4*>(wq + s * 64);
+    const uint4 a1 = *reinterpret_cast<const uint4*>(wq + s * 64 + 8);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const uint4 b = *reinterpret_cast<const uint4*>(xp[t] + s * 32);
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_as_bf16x8(a), pf_as_bf16x8(b), acc[t], 0, 0, 0);
+      const uint4 b0 = *reinterpret_cast<const uint4*>(xp[t] + 8 * g4 + s * 64);
+      const uint4 b1 = *reinterpret_cast<const uint4*>(xp[t] + 8 * g4 + s * 64 + 8);
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_as_bf16x8(a0), pf_as_bf16x8(b0), acc[t], 0, 0, 0);
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_as_bf16x8(a1), pf_as_bf16x8(b1), acc[t], 0, 0, 0);
     }
   }
   // acc[t], register e, lane (l16, g4): tile row (feature) 4 g4 + e, token 16 t + l16
@@ -386,6 +402,9 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
       const int c = c0 + 64 * u;
       wv[u] = c < n_chunks ? wp[c] : make_uint4(0u, 0u, 0u, 0u);
     }
+    // all requests out before the first use.  (The operands stay HIP's uint4 structs on purpose: with
+    // native 4-vectors this compiler selected element 0 for all four dot products.)
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
 #pragma unroll
