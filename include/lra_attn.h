@@ -247,6 +247,13 @@ int32_t lra_set_append_skinny(int32_t tokens);
 int32_t lra_set_append_stages(int32_t stages);
 
 /*
+ * Tuning and test hook: output tile of lra_cache_append's GEMM kernels, 128 (128 features x
+ * 128 tokens per workgroup, the default) or 256 (256 x 256); anything else restores the
+ * default.  Both handle any n_new.  Returns the previous value.
+ */
+int32_t lra_set_append_tile(int32_t tile);
+
+/*
  * Tuning and test hook: bf16 prefill calls with at most this many new tokens (and a context
  * at least four times as long) run on the split-KV decode kernels, the new tokens standing
  * in for the agents, instead of on the tile-walking prefill kernel; they then need a

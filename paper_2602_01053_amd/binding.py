@@ -18,7 +18,7 @@ LRA_OK = 0
 LRA_BF16, LRA_F32 = 0, 1
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
-           "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill", "lra_set_prefill_splits", "lra_set_append_skinny", "lra_set_append_stages",
+           "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill", "lra_set_prefill_splits", "lra_set_append_skinny", "lra_set_append_stages", "lra_set_append_tile",
            "lra_set_profile_mode")
 
 
@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.lra_set_kernel_variant.argtypes = [i32]
     lib.lra_set_decode_split_keys.restype = i32
     lib.lra_set_decode_split_keys.argtypes = [i32]
+    lib.lra_set_append_tile.restype = i32
+    lib.lra_set_append_tile.argtypes = [i32]
     lib.lra_set_append_stages.restype = i32
     lib.lra_set_append_stages.argtypes = [i32]
     lib.lra_set_append_skinny.restype = i32
@@ -118,6 +120,10 @@ def lra_set_kernel_variant(variant: int) -> int:
 
 def lra_set_decode_split_keys(keys: int) -> int:
     return int(load_library().lra_set_decode_split_keys(int(keys)))
+
+
+def lra_set_append_tile(tile: int) -> int:
+    return int(load_library().lra_set_append_tile(int(tile)))
 
 
 def lra_set_append_stages(stages: int) -> int:

@@ -13,6 +13,7 @@ std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
 std::atomic<int32_t> g_prefill_splits{0};  // 0 = automatic
 std::atomic<int32_t> g_append_stages{0};   // LDS stages of the tiled append GEMM (0: chosen from the grid)
+std::atomic<int32_t> g_append_tile{0};     // output tile of the append GEMM (0: chosen from the grid, 128, 256)
 std::atomic<int32_t> g_append_skinny{64};  // new tokens up to which lra_cache_append streams the weights instead of tiling
 std::atomic<int32_t> g_short_prefill{32};  // kShortPrefill: new tokens up to which prefill takes the split-KV path
 std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
@@ -346,6 +347,7 @@ lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, cons
   p.rope_theta = proj->rope_theta;
   p.skinny_max = g_append_skinny.load();
   p.stages = g_append_stages.load();
+  p.tile = g_append_tile.load();
   if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
 }
@@ -370,6 +372,8 @@ int32_t lra_set_prefill_splits(int32_t splits) { return g_prefill_splits.exchang
 int32_t lra_set_append_stages(int32_t stages) {
   return g_append_stages.exchange(stages < 2 || stages > 4 ? 0 : stages);
 }
+
+int32_t lra_set_append_tile(int32_t tile) { return g_append_tile.exchange(tile == 128 || tile == 256 ? tile : 0); }
 
 int32_t lra_set_append_skinny(int32_t tokens) { return g_append_skinny.exchange(tokens < 0 ? 0 : tokens); }
 

@@ -15,12 +15,28 @@
 // (buffer_load ... lds, swizzled by choosing which chunk a lane fetches).  The four waves
 // form a 2 x 2 grid; a wave's two 32-feature blocks are chosen d/2 apart, so the two halves
 // of every rotary pair sit in the same lane and register of its two accumulators and the
-// rotation needs no data movement.  Angles are formed in double precision and reduced
-// before the single-precision sine and cosine, so positions in the tens of thousands lose
-// nothing.
+// rotation needs no data movement.  The rotation rate of every pair is tabulated once per
+// workgroup in double precision (revolutions per position); angle = fractional part of
+// position * rate, so positions in the tens of thousands lose nothing.
 #include "lra_prefill_util.h"
 
 namespace lra {
+
+// Rotary angles.  Pair dd of a head turns by pos * theta^(-2 dd / d) radians; the kernels keep
+// that rate in revolutions (divided by 2 pi) in double precision, so that the product with a
+// position in the tens of thousands can be reduced to its fractional part without loss, and
+// take sine and cosine of the fraction with v_sin_f32 / v_cos_f32 (argument in revolutions,
+// absolute error around 1e-6: far below the bf16 rounding of the result).
+__device__ __forceinline__ double rope_rate_rev(int dd, int head_dim, float theta) {
+  return exp2(-2.0 * dd / head_dim * log2(static_cast<double>(theta))) * 0.15915494309189533577;
+}
+__device__ __forceinline__ void rope_sincos(double rate_rev, int pos, float& sn, float& cs) {
+  double rev = static_cast<double>(pos) * rate_rev;
+  rev -= floor(rev);
+  const float fr = static_cast<float>(rev);
+  sn = __builtin_amdgcn_sinf(fr);
+  cs = __builtin_amdgcn_cosf(fr);
+}
 
 template <int D, bool PAGED, int NS>
 __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendParams p) {
@@ -30,6 +46,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   constexpr int HALF = D / 2;
 
   __shared__ __align__(16) unsigned char smem[NS * STAGE];
+  __shared__ double rope_rate[D / 2];  // revolutions per position of every rotary pair
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -61,19 +78,22 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(PF_LDS_AS(unsigned char, smem)));
   const uint32_t voff = static_cast<uint32_t>(lane >> 3) * ldw2 +
                         (((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) << 4);
-  auto issue_step = [&](int k0, int st) {
+  // request number part (0..7) of this wave for the step at k0: W and X alternate
+  auto issue_part = [&](int k0, int st, int part) __attribute__((always_inline)) {
+    const int i = wave + 4 * (part >> 1);
+    const uint32_t dst = lds0 + st * STAGE + i * 1024;
+    if ((part & 1) == 0) pf_load16_to_lds(rs_w, dst, voff, static_cast<uint32_t>(w_row0 + 8 * i) * ldw2 + k0 * 2);
+    else pf_load16_to_lds(rs_x, dst + TILE_BYTES, voff, static_cast<uint32_t>(tok0 + 8 * i) * ldw2 + k0 * 2);
+  };
+  auto issue_step = [&](int k0, int st) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int i = wave + 4 * q;
-      const uint32_t dst = lds0 + st * STAGE + i * 1024;
-      pf_load16_to_lds(rs_w, dst, voff, static_cast<uint32_t>(w_row0 + 8 * i) * ldw2 + k0 * 2);
-      pf_load16_to_lds(rs_x, dst + TILE_BYTES, voff, static_cast<uint32_t>(tok0 + 8 * i) * ldw2 + k0 * 2);
-    }
+    for (int part = 0; part < 8; ++part) issue_part(k0, st, part);
   };
   const int n_steps = p.d_model / BK;
 #pragma unroll
   for (int st = 0; st < NS - 1; ++st)
     if (st < n_steps) issue_step(st * BK, st);
+  if (tid < D / 2 && p.rope_theta > 0.f) rope_rate[tid] = rope_rate_rev(tid, D, p.rope_theta);  // read after the loop's barriers
 
   // ---------------- operands ----------------
   // A operand: W rows (features), B operand: X rows (tokens); lane (row l32 of a 32-row block,
@@ -99,47 +119,85 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   // Step s computes on stage s % NS while the tiles of the next NS - 2 steps are in flight and
   // the one after them is requested: a wave waits until only the loads younger than step s
   // (8 per step and wave) are outstanding, the barrier makes every wave's share visible and
-  // retires stage (s - 1) % NS, which the new request then overwrites.
-  // The 16 operand reads of a step are issued together, ahead of its 16 MFMAs: the matrix
-  // pipe starts on the first operands while the rest are still on their way.
-  auto k_step = [&](int step, auto st_c, auto lr_c) {
+  // retires stage (s - 1) % NS, which the new requests then overwrite.
+  // A wave issues in order and a wave-wide request holds it for as long as the memory pipe of
+  // the compute unit (shared by the four waves) needs to take it.  With one workgroup per
+  // compute unit the eight requests therefore go out two per k-slice between the MFMAs, next
+  // to the LDS reads of the following slice (operand registers double-buffered; sched_barrier
+  // keeps the compiler from regrouping them).
+  auto k_step = [&](int step, auto st_c, auto lr_c) __attribute__((always_inline)) {
     constexpr int ST = decltype(st_c)::value;
     constexpr bool LR = decltype(lr_c)::value;
+    constexpr int KS = BK / 16;
     if (step + NS - 2 < n_steps) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (NS - 2)));
     else pf_wait_vm0();
     __syncthreads();
-    if (step + NS - 1 < n_steps) issue_step((step + NS - 1) * BK, (ST + NS - 1) % NS);
+    const bool more = step + NS - 1 < n_steps;
+    const int k_next = (step + NS - 1) * BK;
     const unsigned char* wt = smem + ST * STAGE;
     const unsigned char* xt = wt + TILE_BYTES;
-    pf_bf16x8 a0[BK / 16], a1[BK / 16], b0[BK / 16], b1[BK / 16];
+    if (NS == 2) {
+      // Two workgroups per compute unit: the other one's MFMAs cover this one's requests, and
+      // what pays is reading far ahead.  All requests first, then the sixteen operand reads of
+      // the step ordered against its sixteen MFMAs: two k-slices of reads, one read per MFMA.
+      if (more) issue_step(k_next, (ST + NS - 1) % NS);
+      pf_bf16x8 a0[KS], a1[KS], b0[KS], b1[KS];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int off = pre ^ ((2 * ks + g2) << 4);
-      a0[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb0 * 32 * (BK * 2)));
-      b0[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb0 * 32 * (BK * 2)));
-      a1[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb1 * 32 * (BK * 2)));
-      if (!LR) b1[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb1 * 32 * (BK * 2)));
+      for (int ks = 0; ks < KS; ++ks) {
+        const int off = pre ^ ((2 * ks + g2) << 4);
+        a0[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb0 * 32 * (BK * 2)));
+        b0[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb0 * 32 * (BK * 2)));
+        a1[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb1 * 32 * (BK * 2)));
+        if (!LR) b1[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb1 * 32 * (BK * 2)));
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[ks], b0[ks], acc[0][0], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[ks], b0[ks], acc[1][0], 0, 0, 0);
+        if (!LR) {
+          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[ks], b1[ks], acc[0][1], 0, 0, 0);
+          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[ks], b1[ks], acc[1][1], 0, 0, 0);
+        }
+      }
+      constexpr int READS = LR ? 12 : 16, MFMAS = LR ? 8 : 16, AHEAD = READS / 2;
+      __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+      for (int i = 0; i < READS - AHEAD; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - (READS - AHEAD), 0);
+      return;
     }
+    // One workgroup per compute unit (the deeper rings): nothing else covers the requests.
+    pf_bf16x8 a0[2], a1[2], b0[2], b1[2];
+    auto read_slice = [&](int ks, int buf) __attribute__((always_inline)) {
+      const int off = pre ^ ((2 * ks + g2) << 4);
+      a0[buf] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb0 * 32 * (BK * 2)));
+      b0[buf] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb0 * 32 * (BK * 2)));
+      a1[buf] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + fb1 * 32 * (BK * 2)));
+      if (!LR) b1[buf] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + tb1 * 32 * (BK * 2)));
+    };
+    read_slice(0, 0);
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[ks], b0[ks], acc[0][0], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[ks], b0[ks], acc[1][0], 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cur = ks & 1;
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) {
+        issue_part(k_next, (ST + NS - 1) % NS, 2 * ks);
+        issue_part(k_next, (ST + NS - 1) % NS, 2 * ks + 1);
+      }
+      if (ks + 1 < KS) read_slice(ks + 1, cur ^ 1);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[cur], b0[cur], acc[0][0], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[cur], b0[cur], acc[1][0], 0, 0, 0);
       if (!LR) {
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[ks], b1[ks], acc[0][1], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[ks], b1[ks], acc[1][1], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[cur], b1[cur], acc[0][1], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[cur], b1[cur], acc[1][1], 0, 0, 0);
       }
     }
-    // order for the scheduler: the reads of two k-slices, then one read per MFMA, then the rest
-    constexpr int READS = LR ? 12 : 16, MFMAS = LR ? 8 : 16, AHEAD = READS / 2;
-    __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
-#pragma unroll
-    for (int i = 0; i < READS - AHEAD; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - (READS - AHEAD), 0);
+    __builtin_amdgcn_sched_barrier(0);
   };
-  auto k_loop = [&](auto lr_c) {
+  auto k_loop = [&](auto lr_c) __attribute__((always_inline)) {
     for (int step = 0; step < n_steps; step += NS) {
       k_step(step, std::integral_constant<int, 0>{}, lr_c);
       if (step + 1 < n_steps) k_step(step + 1, std::integral_constant<int, 1>{}, lr_c);
@@ -183,15 +241,11 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
     }
     if (kind == 0 && p.rope_theta > 0.f) {
       // pair (feature dd, dd + d/2) of a head: acc[0] holds the first half, acc[1] the second
-      const double log2_theta = log2(static_cast<double>(p.rope_theta));
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int dd = (32 * fb0 + 8 * (i >> 2) + 4 * g2 + (i & 3)) % D;  // < d/2 by construction
-        const double inv_freq = exp2(-2.0 * dd / D * log2_theta);
-        double ang = static_cast<double>(j) * inv_freq;
-        ang -= 6.283185307179586476925 * floor(ang * 0.15915494309189533577);
         float sn, cs;
-        sincosf(static_cast<float>(ang), &sn, &cs);
+        rope_sincos(rope_rate[dd], j, sn, cs);
         const float lo = acc[0][b][i], hi = acc[1][b][i];
         acc[0][b][i] = lo * cs - hi * sn;
         acc[1][b][i] = hi * cs + lo * sn;
@@ -210,6 +264,222 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
       }
   }
   (void)HALF;
+}
+
+// ---------------------------------------------------------------------------------------
+// 256 features x 256 tokens per workgroup (selected by lra_set_append_tile(256) only).  At
+// 128 x 128 a step moves 32 KB into LDS for 2.1 MFLOP and every MFMA costs one 1 KB LDS read:
+// with two workgroups per compute unit the LDS is busier than the matrix pipes.  Here a wave
+// owns 128 x 128 of the output (sixteen 32 x 32 accumulators, kept in the accumulation
+// registers), reads eight operands for sixteen MFMAs, and a step moves 64 KB for 8.4 MFLOP.
+// Same LDS layout, DMA and epilogue as append_kernel; two stages of 64 KB, one workgroup per
+// compute unit.  The wave's four feature blocks are one head (d = 128: pairs (0,2), (1,3)) or
+// two (d = 64: pairs (0,1), (2,3)).  Measured: 1.45 us per step against 0.9 us of MFMA work,
+// level with append_kernel at 16384 tokens and behind it at 8192 (the grid of 256-wide tiles
+// quantises worse), so it is not the default.
+// ---------------------------------------------------------------------------------------
+template <int D, bool PAGED>
+__global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
+  constexpr int BF = 256, BT = 256, BK = 64;
+  constexpr int TILE_BYTES = BF * BK * 2;  // 256 rows of 128 bytes
+  constexpr int STAGE = 2 * TILE_BYTES;    // [W tile][X tile]
+  __shared__ __align__(16) unsigned char smem[2 * STAGE];
+  __shared__ double rope_rate[D / 2];  // revolutions per position of every rotary pair
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const int wr = wave >> 1, wc = wave & 1;
+  const int HD = p.n_kv_heads * D;
+  const int n_ct_kv = (HD + BF - 1) / BF;
+  const int ct = blockIdx.y;
+  const int kind = ct < n_ct_kv ? 0 : (ct < 2 * n_ct_kv ? 1 : 2);  // 0 K, 1 V, 2 L
+  const int ct_in = kind == 0 ? ct : (kind == 1 ? ct - n_ct_kv : 0);
+  const int feat0 = ct_in * BF;
+  const int w_row0 = (kind == 0 ? 0 : (kind == 1 ? HD : 2 * HD)) + feat0;
+  const int tok0 = blockIdx.x * BT;
+  const int n_new = p.n_new;
+  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int pos0 = n_t - n_new;
+
+  // tile traffic: as in append_kernel, 32 wave-wide loads per tile, wave w issues i = w + 4q
+  const uint32_t ldw2 = static_cast<uint32_t>(p.d_model) * 2u;
+  const uint32_t n_w_rows = static_cast<uint32_t>(2 * HD + p.rank);
+  const pf_u32x4 rs_w = pf_rsrc(p.w, (n_w_rows - 1) * ldw2 + ldw2);
+  const pf_u32x4 rs_x = pf_rsrc(p.x, static_cast<uint32_t>(n_new - 1) * ldw2 + ldw2);
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(PF_LDS_AS(unsigned char, smem)));
+  const uint32_t voff = static_cast<uint32_t>(lane >> 3) * ldw2 +
+                        (((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) << 4);
+  // request number part (0..15) of this wave for the step at k0: W loads first, then X
+  auto issue_part = [&](int k0, int st, int part) __attribute__((always_inline)) {
+    const int i = wave + 4 * (part & 7);
+    const uint32_t dst = lds0 + st * STAGE + i * 1024;
+    if (part < 8) pf_load16_to_lds(rs_w, dst, voff, static_cast<uint32_t>(w_row0 + 8 * i) * ldw2 + k0 * 2);
+    else pf_load16_to_lds(rs_x, dst + TILE_BYTES, voff, static_cast<uint32_t>(tok0 + 8 * i) * ldw2 + k0 * 2);
+  };
+  auto issue_step = [&](int k0, int st) __attribute__((always_inline)) {
+#pragma unroll
+    for (int part = 0; part < 16; ++part) issue_part(k0, st, part);
+  };
+  const int n_steps = p.d_model / BK;
+  issue_step(0, 0);
+  if (tid < D / 2 && p.rope_theta > 0.f) rope_rate[tid] = rope_rate_rev(tid, D, p.rope_theta);  // read after the loop's barriers
+
+  const int pre = l32 * (BK * 2) + (((l32 >> 1) & 7) << 4);
+  const bool lr_tile = kind == 2;
+  // K, V tiles: feature blocks 4 wr + i, token blocks 4 wc + j (i, j < 4).
+  // L tile (at most 64 features): feature blocks 0, 1 and token blocks 2 wave + j (j < 2).
+  const int fbase = lr_tile ? 0 : 4 * wr;
+  const int tbase = lr_tile ? 2 * wave : 4 * wc;
+
+  pf_f32x16 acc[4][4];  // [feature block][token block]
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  // One step.  A wave issues instructions in order, and a wave-wide request occupies the
+  // memory pipe of the compute unit for some sixteen cycles (all four waves share it): sixteen
+  // requests issued in a row keep the wave off the matrix pipe for as long as the pipe needs
+  // to take them, and the two times add up.  So the requests for the next step go out two at a
+  // time between the groups of four MFMAs of the first half of the step, next to the LDS reads of the next k-slice
+  // (registers double-buffered); sched_barrier keeps the compiler from regrouping them.
+  auto k_step = [&](int step, auto st_c, auto lr_c, auto more_c) __attribute__((always_inline)) {
+    constexpr int ST = decltype(st_c)::value;
+    constexpr bool LR = decltype(lr_c)::value;
+    constexpr bool MORE = decltype(more_c)::value;  // another step follows: request its tiles
+    constexpr int NA = LR ? 2 : 4, NB = LR ? 2 : 4;
+    constexpr int KS = BK / 16;
+    constexpr int GROUPS = KS * NA;          // groups of NB MFMAs in a step
+    constexpr int PARTS = 2 * 16 / GROUPS;   // requests per group: all sixteen go out in the first half of the
+                                             // step, so that the last one has the other half to land
+    pf_wait_vm0();
+    __syncthreads();
+    const unsigned char* wt = smem + ST * STAGE + fbase * 32 * (BK * 2);
+    const unsigned char* xt = smem + ST * STAGE + TILE_BYTES + tbase * 32 * (BK * 2);
+    pf_bf16x8 a[2][NA], b[2][NB];
+    {
+      const int off = pre ^ (g2 << 4);
+#pragma unroll
+      for (int i = 0; i < NA; ++i) a[0][i] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + i * 32 * (BK * 2)));
+#pragma unroll
+      for (int j = 0; j < NB; ++j) b[0][j] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + j * 32 * (BK * 2)));
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      const int off = pre ^ ((2 * (ks + 1) + g2) << 4);
+#pragma unroll
+      for (int i = 0; i < NA; ++i) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (MORE && (ks * NA + i) * PARTS < 16) {
+#pragma unroll
+          for (int q = 0; q < PARTS; ++q) issue_part((step + 1) * BK, ST ^ 1, (ks * NA + i) * PARTS + q);
+        }
+        if (ks + 1 < KS) {
+          // two operands of the next k-slice per group, in the order its groups need them: its
+          // first group takes every b and a[0], so the b's go first (NA == NB)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int o = 2 * i + q;  // 0 .. NA + NB - 1
+            if (o < NB) b[nxt][o] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(xt + off + o * 32 * (BK * 2)));
+            else a[nxt][o - NB] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(wt + off + (o - NB) * 32 * (BK * 2)));
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto k_loop = [&](auto lr_c) __attribute__((always_inline)) {
+    int step = 0;
+    for (; step + 2 < n_steps; step += 2) {
+      k_step(step, std::integral_constant<int, 0>{}, lr_c, std::true_type{});
+      k_step(step + 1, std::integral_constant<int, 1>{}, lr_c, std::true_type{});
+    }
+    if (step + 1 < n_steps) {
+      k_step(step, std::integral_constant<int, 0>{}, lr_c, std::true_type{});
+      k_step(step + 1, std::integral_constant<int, 1>{}, lr_c, std::false_type{});
+    } else {
+      k_step(step, std::integral_constant<int, 0>{}, lr_c, std::false_type{});
+    }
+  };
+  if (lr_tile) k_loop(std::true_type{});
+  else k_loop(std::false_type{});
+  pf_wait_vm0();
+
+  // epilogue.  acc[a][b], register i, lane (l32, g2): feature 32 (fbase + a) + 8 (i/4) + 4 g2 + i%4
+  // of the tile, token 32 (tbase + b) + l32 of the tile.
+  bf16_t* kcache = static_cast<bf16_t*>(kind == 0 ? p.k_base : p.v_base);
+  auto store_block = [&](auto b_c) __attribute__((always_inline)) {
+    constexpr int b = decltype(b_c)::value;
+    if (b >= 2 && lr_tile) return;
+    const int tok = tok0 + 32 * (tbase + b) + l32;
+    const int j = pos0 + tok;
+    if (tok >= n_new || j < 0) return;
+    int64_t row_off;
+    if (PAGED) {
+      const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
+      row_off = kind == 2 ? (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank
+                          : static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(j & 15) * p.kv_token_stride;
+    } else {
+      row_off = kind == 2 ? static_cast<int64_t>(j) * p.rank : static_cast<int64_t>(j) * p.kv_token_stride;
+    }
+    if (kind == 2) {
+      bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int f = 32 * a + 8 * q + 4 * g2;
+          if (f < p.rank)
+            *reinterpret_cast<uint2*>(lrow + f) =
+                make_uint2(pf_pack2(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]), pf_pack2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]));
+        }
+      return;
+    }
+    if (kind == 0 && p.rope_theta > 0.f) {
+      // rotates the pair of blocks (lo, hi); block_lo = position of lo among the wave's four
+      auto rotate = [&](pf_f32x16& lo_v, pf_f32x16& hi_v, int block_lo) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int dd = (32 * block_lo + 8 * (i >> 2) + 4 * g2 + (i & 3)) % D;  // < d/2 by construction
+          float sn, cs;
+          rope_sincos(rope_rate[dd], j, sn, cs);
+          const float lo = lo_v[i], hi = hi_v[i];
+          lo_v[i] = lo * cs - hi * sn;
+          hi_v[i] = hi * cs + lo * sn;
+        }
+      };
+      if (D == 128) {
+        rotate(acc[0][b], acc[2][b], 0);
+        rotate(acc[1][b], acc[3][b], 1);
+      } else {
+        rotate(acc[0][b], acc[1][b], 0);
+        rotate(acc[2][b], acc[3][b], 2);
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int f = feat0 + 32 * (fbase + a) + 8 * q + 4 * g2;
+        if (f < HD) {
+          const int head = f / D, dd = f - head * D;
+          *reinterpret_cast<uint2*>(kcache + row_off + static_cast<int64_t>(head) * p.kv_head_stride + dd) =
+              make_uint2(pf_pack2(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]), pf_pack2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]));
+        }
+      }
+  };
+  store_block(std::integral_constant<int, 0>{});
+  store_block(std::integral_constant<int, 1>{});
+  store_block(std::integral_constant<int, 2>{});
+  store_block(std::integral_constant<int, 3>{});
 }
 
 // ---------------------------------------------------------------------------------------
@@ -237,7 +507,7 @@ __global__ __launch_bounds__(512) void append_skinny_kernel(AppendParams p) {
   const int fg_in = kind == 0 ? fg : (kind == 1 ? fg - groups_kv : fg - 2 * groups_kv);
   const int head = fg_in / (D / 16), sub = fg_in - head * (D / 16);
   // feature (inside its region) of tile row i: K/V  head*D + 8 sub + i  (i < 8),  + d/2 - 8 beyond;  L  16 fg_in + i
-  auto feature_of = [&](int i) {
+  auto feature_of = [&](int i) __attribute__((always_inline)) {
     return kind == 2 ? 16 * fg_in + i : head * D + 8 * sub + (i < 8 ? i : i - 8 + D / 2);
   };
   const int n_new = p.n_new;
@@ -336,11 +606,8 @@ __global__ __launch_bounds__(512) void append_skinny_kernel(AppendParams p) {
   }
   const int dd = 8 * sub + i;  // < d/2
   if (kind == 0 && p.rope_theta > 0.f) {
-    const double inv_freq = exp2(-2.0 * dd / D * log2(static_cast<double>(p.rope_theta)));
-    double ang = static_cast<double>(j) * inv_freq;
-    ang -= 6.283185307179586476925 * floor(ang * 0.15915494309189533577);
     float sn, cs;
-    sincosf(static_cast<float>(ang), &sn, &cs);
+    rope_sincos(rope_rate_rev(dd, D, p.rope_theta), j, sn, cs);
     const float a = lo, b = hi;
     lo = a * cs - b * sn;
     hi = b * cs + a * sn;
@@ -450,11 +717,8 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
   }
   const int dd = 2 * sub + q;  // < d/2
   if (kind == 0 && p.rope_theta > 0.f) {
-    const double inv_freq = exp2(-2.0 * dd / D * log2(static_cast<double>(p.rope_theta)));
-    double ang = static_cast<double>(j) * inv_freq;
-    ang -= 6.283185307179586476925 * floor(ang * 0.15915494309189533577);
     float sn, cs;
-    sincosf(static_cast<float>(ang), &sn, &cs);
+    rope_sincos(rope_rate_rev(dd, D, p.rope_theta), j, sn, cs);
     const float a = lo, b = hi;
     lo = a * cs - b * sn;
     hi = b * cs + a * sn;
@@ -514,8 +778,21 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s) {
     }
     return hipGetLastError();
   }
-  dim3 grid((p.n_new + 127) / 128, 2 * ((hd + 127) / 128) + 1);
   const bool paged = p.block_size != 0;
+  if (p.tile == 256) {
+    // 256 x 256 tiles: measured equal to the 128 x 128 kernel at 16384 new tokens and slower below
+    // (Llama-3-8B projection), so only on request
+    dim3 wgrid((p.n_new + 255) / 256, 2 * ((hd + 255) / 256) + 1);
+    if (p.head_dim == 128) {
+      if (paged) hipLaunchKernelGGL((append_wide_kernel<128, true>), wgrid, dim3(256), 0, s, p);
+      else hipLaunchKernelGGL((append_wide_kernel<128, false>), wgrid, dim3(256), 0, s, p);
+    } else {
+      if (paged) hipLaunchKernelGGL((append_wide_kernel<64, true>), wgrid, dim3(256), 0, s, p);
+      else hipLaunchKernelGGL((append_wide_kernel<64, false>), wgrid, dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+  }
+  dim3 grid((p.n_new + 127) / 128, 2 * ((hd + 127) / 128) + 1);
   // One workgroup per compute unit or fewer: nothing shares the LDS, so a deeper ring of
   // stages (more requests in flight per workgroup) is free; beyond that two workgroups per
   // unit with two stages each hide each other's waits.

@@ -112,6 +112,7 @@ struct AppendParams {
   int32_t block_size, max_blocks_per_seq, max_seq_len;
   float rope_theta;
   int stages;      // LDS stages of the tiled GEMM: 0 = chosen from the grid, else 2, 3 or 4
+  int tile;        // output tile of the GEMM kernels: 0 = chosen from the grid, 128 or 256
   int skinny_max;  // up to this many new tokens the weight-streaming kernel runs instead of the tiled GEMM
 };
 hipError_t launch_append(const AppendParams& p, hipStream_t s);

@@ -77,6 +77,21 @@ def test_append_tiled_stage_counts(case, stages):
         lra.lra_set_append_skinny(prev_k)
 
 
+@pytest.mark.parametrize("case", [SMALL[0], (200, 129, 256, 2, 128, 16, 500000.0), (700, 300, 704, 3, 64, 24, 10000.0),
+                                  (66000, 515, 1024, 8, 128, 64, 500000.0), (520, 520, 512, 1, 64, 8, 10000.0),
+                                  (1000, 257, 4096, 8, 128, 16, 0.0)],
+                         ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
+def test_append_wide_tile(case):
+    """The 256 x 256 tile kernel, forced: ragged token tiles, feature regions of 64, 192 and 1024
+    (a tile that is partly filled, one that straddles the K and V rows of w), rank 8 to 64."""
+    prev_t, prev_k = lra.lra_set_append_tile(256), lra.lra_set_append_skinny(0)
+    try:
+        test_append_contiguous(case)
+    finally:
+        lra.lra_set_append_tile(prev_t)
+        lra.lra_set_append_skinny(prev_k)
+
+
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
 def test_append_contiguous(case):
     n, n_new, d_model, hkv, d, r, theta = case
@@ -101,13 +116,14 @@ def test_append_contiguous(case):
         assert bool((t[:n - n_new] == SENTINEL).all())
 
 
-@pytest.mark.parametrize("skinny", [0, 1 << 30], ids=["tiled", "streamed"])
-def test_append_paged_then_attend(skinny):
-    prev = lra.lra_set_append_skinny(skinny)
+@pytest.mark.parametrize("skinny,tile", [(0, 128), (0, 256), (1 << 30, 0)], ids=["tiled", "wide", "streamed"])
+def test_append_paged_then_attend(skinny, tile):
+    prev, prev_t = lra.lra_set_append_skinny(skinny), lra.lra_set_append_tile(tile)
     try:
         _paged_then_attend()
     finally:
         lra.lra_set_append_skinny(prev)
+        lra.lra_set_append_tile(prev_t)
 
 
 def _paged_then_attend():
