@@ -6,6 +6,8 @@ through lra_attn_prefill / lra_attn_decode at the Llama-3-8B attention shape.
 One iteration is 17 agent steps (five plan-plan-action cycles, two reflect steps).  Step k
 appends P_k context tokens (one causal prefill call by that step's agent) and then
 generates G_k tokens (G_k single-query decode calls, the context growing by one each).
+The producer of the caches (lra_cache_append: one call per prefill chunk and per generated
+token, Llama-3-8B projection shape) is timed as a separate leg over the same schedule.
 The retrieved-context length L_ctx sets four of the P_k.  Only attention is timed - this
 library holds no projections or MLPs - so the figures are the attention share of one layer
 for one iteration, not the paper's end-to-end throughput; shapes only, random data.
@@ -26,6 +28,7 @@ for _ in range(4):
 TRACE += [("reflect", 32, 32), ("reflect", 8, 8)]
 ADAPTER = {"plan": 0, "action": 1, "reflect": 2}
 HQ, HKV, D, R, LAYERS = 32, 8, 128, 16, 32
+D_MODEL, ROPE_THETA = 4096, 500000.0
 
 
 def run_trace(torch, lra, l_ctx, replays):
@@ -42,6 +45,9 @@ def run_trace(torch, lra, l_ctx, replays):
     max_p = max(p for _, p, _ in steps)
     q = torch.randn(max_p, HQ, D, generator=gen).to(bf).to(dev)
     out = torch.empty_like(q)
+    # the producer of the caches: hidden states of the new tokens and [W_K; W_V; A]
+    x = torch.randn(max_p, D_MODEL, generator=gen).to(bf).to(dev)
+    w_cat = (torch.randn(2 * HKV * D + R, D_MODEL, generator=gen) / D_MODEL ** 0.5).to(bf).to(dev)
     # one device int per call holds the sequence length of that call
     calls = []  # (kind, n_after, n_new, adapter)
     n = 0
@@ -68,6 +74,9 @@ def run_trace(torch, lra, l_ctx, replays):
 
     def iteration(stream, only=None):
         for kind, cache, n_new, a in prepared:
+            if only == "append":
+                lra.lra_cache_append(shape, cache, w_cat, ROPE_THETA, x[:n_new], 0, stream)
+                continue
             if only is not None and kind != only:
                 continue
             if kind == "prefill":
@@ -77,7 +86,7 @@ def run_trace(torch, lra, l_ctx, replays):
 
     side = torch.cuda.Stream()
     res = {}
-    for label, only in (("all", None), ("prefill", "prefill"), ("decode", "decode")):
+    for label, only in (("all", None), ("prefill", "prefill"), ("decode", "decode"), ("append", "append")):
         with torch.cuda.stream(side):
             iteration(side, only)  # warm-up outside the graph
         side.synchronize()
@@ -99,6 +108,7 @@ def run_trace(torch, lra, l_ctx, replays):
             "calls": len(calls), "attention_ms_per_layer": round(res["all"], 4),
             "prefill_ms_per_layer": round(res["prefill"], 4), "decode_ms_per_layer": round(res["decode"], 4),
             "attention_ms_32_layers": round(res["all"] * LAYERS, 3),
+            "cache_append_ms_per_layer": round(res["append"], 4),
             "decode_us_per_token_per_layer": round(res["decode"] * 1e3 / n_gen, 2)}
 
 

@@ -125,7 +125,46 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert bad == ctypes.c_size_t(-1).value
 
 
+def test_cache_append_rejects_bad_arguments_before_launch(lib):
+    from paper_2602_01053_amd.binding import LraProjection
+    NULL, SHAPE, UNSUP = 1, 2, 4
+
+    def call(sh=None, c=None, proj=None, x=FAKE, seq=0, n_new=16, w=FAKE, d_model=4096, theta=500000.0, no_proj=False):
+        s0, c0, _ = _good()
+        sh = sh or s0
+        c = c or c0
+        pr = LraProjection(w, d_model, theta)
+        return lib.lra_cache_append(ctypes.byref(sh), ctypes.byref(c), None if no_proj else ctypes.byref(pr), x, seq,
+                                    n_new, None)
+
+    assert call(no_proj=True) == NULL
+    assert call(w=None) == NULL
+    assert call(x=None) == NULL
+    assert call(seq=1) == SHAPE                       # one (contiguous) sequence
+    assert call(n_new=0) == SHAPE
+    assert call(n_new=8193) == SHAPE                  # more new tokens than the cache can hold
+    assert call(d_model=0) == SHAPE
+    assert call(theta=-1.0) == SHAPE
+    assert call(theta=float("nan")) == SHAPE
+    assert call(x=FAKE + 8) == SHAPE                  # misaligned
+    assert call(d_model=4000) == UNSUP                # not a multiple of 64
+    assert call(d_model=1 << 22) == UNSUP             # weights beyond 32-bit byte offsets
+    sh, c, _ = _good()
+    sh.dtype = 1
+    assert call(sh=sh) == UNSUP                       # fp32 caches
+    sh, c, _ = _good()
+    sh.rank = 12
+    assert call(sh=sh) == UNSUP                       # rank not a multiple of 8
+    sh, c, _ = _good()
+    c.k_base = None
+    assert call(c=c) == NULL
+
+
 def test_tuning_hooks_round_trip(lib):
+    old = lra.lra_set_append_skinny(7)
+    assert lra.lra_set_append_skinny(old) == 7 and old == 64
+    assert lra.lra_set_append_stages(3) == 0 and lra.lra_set_append_stages(9) == 3 and lra.lra_set_append_stages(0) == 0
+    assert lra.lra_set_append_tile(256) == 0 and lra.lra_set_append_tile(100) == 256 and lra.lra_set_append_tile(0) == 0
     old = lra.lra_set_decode_split_keys(512)
     assert lra.lra_set_decode_split_keys(old) == 512
     old = lra.lra_set_kernel_variant(1)
