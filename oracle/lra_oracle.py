@@ -30,7 +30,9 @@ one, convex-hull / shift / permutation invariances.  The cache-append producer a
 of the file (projection of new tokens, rotary embedding of the keys, paged scatter) is pinned
 by the 2x2 rotation at d = 2, the identity at position 0, norm preservation, additivity of
 positions, the relative-position property of rotated dot products, explicit loops on tiny
-inputs and the scatter / gather round trip.  Every function is pinned.
+inputs and the scatter / gather round trip.  The rotary key side (key_rope_theta) is pinned
+against attention over keys rotated as a whole, RoPE(K'_base + L B_K), by a scalar loop, and
+by its two degenerate cases (B_K = 0, a single token at position 0).  Every function is pinned.
 """
 from __future__ import annotations
 
@@ -67,13 +69,22 @@ def gather_paged_l(pool_l: np.ndarray, block_ids: Sequence[int], n: int) -> np.n
     return pool_l[ids].reshape(nb * bs, pool_l.shape[2])[:n]
 
 
-def materialise_kv(k_base_h, v_base_h, l, b_k_h, b_v_h):
+def materialise_kv(k_base_h, v_base_h, l, b_k_h, b_v_h, key_rope_theta: float = 0.0):
     """Per-agent keys and values of one kv head (Eq. 3 applied to the cache:
     base output plus LR cache times the agent's up-projection).
 
-    k_base_h, v_base_h [n][d]; l [n][r]; b_k_h, b_v_h [r][d]  ->  K, V [n][d]"""
+    k_base_h, v_base_h [n][d]; l [n][r]; b_k_h, b_v_h [r][d]  ->  K, V [n][d]
+
+    key_rope_theta > 0 is the rotary setting of App. D.1 (LoRA on the key projection of a
+    model with rotary embeddings): the cached base keys are the rotated ones, the adapter
+    contribution is reconstructed in the head dimension and rotated by its token's position
+    (= its cache row) before it is added,  K_j = K_base,j + RoPE_j(L_j B_K)."""
     l = _f64(l)
-    k = _f64(k_base_h) + l @ _f64(b_k_h)
+    k_lr = l @ _f64(b_k_h)
+    if key_rope_theta > 0.0:
+        n = k_lr.shape[0]
+        k_lr = rope_rotate(k_lr[:, None, :], np.arange(n), key_rope_theta)[:, 0, :]
+    k = _f64(k_base_h) + k_lr
     v = _f64(v_base_h) + l @ _f64(b_v_h)
     return k, v
 
@@ -95,7 +106,7 @@ def softmax_weights(q_rows, k, scale: float, n_visible) -> np.ndarray:
 
 
 def attend(q_tok, k_base, v_base, l, b_k, b_v, scale: float, n_visible,
-           q_to_kv: Optional[Sequence[int]] = None) -> np.ndarray:
+           q_to_kv: Optional[Sequence[int]] = None, key_rope_theta: float = 0.0) -> np.ndarray:
     """One agent on one sequence.
 
     q_tok [T][Hq][d] (T query tokens), k_base/v_base [n][Hkv][d], l [n][r],
@@ -112,7 +123,7 @@ def attend(q_tok, k_base, v_base, l, b_k, b_v, scale: float, n_visible,
     for h in range(hkv):
         cols = slice(h * d, (h + 1) * d)
         k, v = materialise_kv(np.asarray(k_base)[:, h, :], np.asarray(v_base)[:, h, :], l,
-                              np.asarray(b_k)[:, cols], np.asarray(b_v)[:, cols])
+                              np.asarray(b_k)[:, cols], np.asarray(b_v)[:, cols], key_rope_theta)
         for g in range(hq):
             if q_to_kv[g] != h:
                 continue
@@ -133,7 +144,8 @@ def _sequence_views(k_base, v_base, l, seq_lens, block_size, block_table, t):
 
 
 def decode(q, k_base, v_base, l, b_k, b_v, query_adapter, seq_query_start, seq_lens,
-           scale: float, block_size: int = 0, block_table=None, q_to_kv=None) -> np.ndarray:
+           scale: float, block_size: int = 0, block_table=None, q_to_kv=None,
+           key_rope_theta: float = 0.0) -> np.ndarray:
     """Every query is one new token that sees all n_t cached tokens of its
     sequence (the cache already holds that token's own K/V/L row).
 
@@ -149,12 +161,12 @@ def decode(q, k_base, v_base, l, b_k, b_v, query_adapter, seq_query_start, seq_l
         for qi in range(start[t], start[t + 1]):
             a = int(np.asarray(query_adapter)[qi])
             out[qi] = attend(q[qi][None], kb, vb, lr, np.asarray(b_k)[a], np.asarray(b_v)[a],
-                             scale, [n_t], q_to_kv)[0]
+                             scale, [n_t], q_to_kv, key_rope_theta)[0]
     return out
 
 
 def prefill(q, k_base, v_base, l, b_k_a, b_v_a, n: int, scale: float, rows=None,
-            q_to_kv=None) -> np.ndarray:
+            q_to_kv=None, key_rope_theta: float = 0.0) -> np.ndarray:
     """One agent appends T = len(q) tokens at the end of a sequence of n cached
     tokens (n includes them, L = L_p + L_c in Alg. 1).  Causal mask aligned to
     the end: new token i sees keys 0 .. n - T + i.
@@ -166,7 +178,7 @@ def prefill(q, k_base, v_base, l, b_k_a, b_v_a, n: int, scale: float, rows=None,
     idx = np.arange(t_new) if rows is None else np.asarray(rows, dtype=np.int64)
     n_visible = n - t_new + idx + 1
     return attend(q[idx], np.asarray(k_base)[:n], np.asarray(v_base)[:n], np.asarray(l)[:n],
-                  b_k_a, b_v_a, scale, n_visible, q_to_kv)
+                  b_k_a, b_v_a, scale, n_visible, q_to_kv, key_rope_theta)
 
 
 # --------------------------------------------------------------------------------------

@@ -472,3 +472,75 @@ def test_p11_paged_scatter_is_the_inverse_of_gather():
     np.testing.assert_array_equal(after[30:50], rows)
     np.testing.assert_array_equal(after[:30], before[:30])
     np.testing.assert_array_equal(lra_oracle.gather_paged_l(pool_l, ids, 50)[30:50], rows_l)
+
+
+# --------------------------------------------------------------------------
+# P12: the rotary key side (App. D.1: the adapter's key contribution is reconstructed in the
+# head dimension and rotated before the score).
+# --------------------------------------------------------------------------
+def test_p12_rotary_key_side_equals_attention_over_keys_rotated_as_a_whole():
+    """K = RoPE(K'_base + L B_K) by the definition of the model; the cache holds
+    RoPE(K'_base), so by linearity of the rotation the oracle's K_base + RoPE(L B_K) must
+    give the same attention as textbook attention over the fully rotated keys."""
+    rng = np.random.default_rng(120)
+    n, hq, hkv, d, r, theta = 37, 4, 2, 8, 3, 10000.0
+    k_pre = rng.standard_normal((n, hkv, d))
+    v = rng.standard_normal((n, hkv, d))
+    l = rng.standard_normal((n, r))
+    b_k = 0.7 * rng.standard_normal((2, r, hkv * d))
+    b_v = 0.7 * rng.standard_normal((2, r, hkv * d))
+    q = rng.standard_normal((2, hq, d))
+    k_cache = oracle.rope_rotate(k_pre, np.arange(n), theta)
+    got = oracle.decode(q, k_cache, v, l, b_k, b_v, np.array([0, 1]), np.array([0, 2]), [n], 0.3,
+                        key_rope_theta=theta)
+    for a in range(2):
+        k_full = oracle.rope_rotate(k_pre + (l @ b_k[a]).reshape(n, hkv, d), np.arange(n), theta)
+        v_full = v + (l @ b_v[a]).reshape(n, hkv, d)
+        for g in range(hq):
+            h = g // (hq // hkv)
+            s = 0.3 * (k_full[:, h, :] @ q[a, g])
+            p = np.exp(s - s.max())
+            np.testing.assert_allclose(got[a, g], (p / p.sum()) @ v_full[:, h, :], rtol=0, atol=1e-12)
+
+
+def test_p12_rotary_key_side_scalar_loop_and_degenerate_cases():
+    rng = np.random.default_rng(121)
+    n, d, r, theta = 9, 4, 2, 100.0
+    w = _tiny(n=n, d=d, r=r, hq=2, hkv=1, agents=1, rng=rng)
+    t_new = 4
+    q = rng.standard_normal((t_new, 2, d))
+    got = oracle.prefill(q, w["k_base"], w["v_base"], w["l"], w["b_k"][0], w["b_v"][0], n=n, scale=0.5,
+                         key_rope_theta=theta)
+    half = d // 2
+    for i in range(t_new):
+        n_vis = n - t_new + i + 1
+        for g in range(2):
+            scores, vals = [], []
+            for j in range(n_vis):
+                delta = [sum(w["l"][j, p] * w["b_k"][0][p, c] for p in range(r)) for c in range(d)]
+                key = []
+                for c in range(d):
+                    ang = j * theta ** (-2.0 * (c % half) / d)
+                    rot = (delta[c] * math.cos(ang) - delta[c + half] * math.sin(ang)) if c < half else \
+                          (delta[c] * math.cos(ang) + delta[c - half] * math.sin(ang))
+                    key.append(w["k_base"][j, 0, c] + rot)
+                scores.append(0.5 * sum(q[i, g, c] * key[c] for c in range(d)))
+                vals.append([w["v_base"][j, 0, c] + sum(w["l"][j, p] * w["b_v"][0][p, c] for p in range(r))
+                             for c in range(d)])
+            m = max(scores)
+            e = [math.exp(x - m) for x in scores]
+            z = sum(e)
+            ref = [sum(e[j] / z * vals[j][c] for j in range(n_vis)) for c in range(d)]
+            np.testing.assert_allclose(got[i, g], ref, rtol=0, atol=1e-12)
+    # B_K = 0: the rotation has nothing to act on
+    zero = np.zeros_like(w["b_k"][0])
+    np.testing.assert_array_equal(
+        oracle.prefill(q, w["k_base"], w["v_base"], w["l"], zero, w["b_v"][0], n=n, scale=0.5, key_rope_theta=theta),
+        oracle.prefill(q, w["k_base"], w["v_base"], w["l"], zero, w["b_v"][0], n=n, scale=0.5))
+    # one cached token at position 0: no rotation
+    np.testing.assert_allclose(
+        oracle.prefill(q[:1], w["k_base"], w["v_base"], w["l"], w["b_k"][0], w["b_v"][0], n=1, scale=0.5, key_rope_theta=theta),
+        oracle.prefill(q[:1], w["k_base"], w["v_base"], w["l"], w["b_k"][0], w["b_v"][0], n=1, scale=0.5), rtol=0, atol=1e-15)
+    # and it does change the result otherwise
+    plain = oracle.prefill(q, w["k_base"], w["v_base"], w["l"], w["b_k"][0], w["b_v"][0], n=n, scale=0.5)
+    assert np.abs(plain - got).max() > 1e-3
