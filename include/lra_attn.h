@@ -76,6 +76,16 @@ typedef struct {
   int32_t dtype;      /* lra_dtype */
   float scale;        /* softmax scale; 0.0f selects 1/sqrt(head_dim) (Alg. 1 line 10).
                          The rank never enters the scale. */
+  float key_rope_theta; /* 0: the key-side adapter is added as it is, K = K_base + L B_K, and
+                         the scores are reordered (App. D.1 without a rotation).
+                         > 0: the rotary setting of App. D.1 (LoRA on the key projection of a
+                         model with rotary embeddings, the qkvo ablation): K_base holds rotated
+                         keys, and the adapter's contribution, reconstructed in the head
+                         dimension, is rotated by its token's position before the score,
+                           K_j = K_base,j + RoPE_j(L_j B_K),
+                         rotate-half pairs (i, i + d/2), angle j * theta^(-2i/d), position j =
+                         the token's index in its sequence.  Q is the caller's (rotated) query.
+                         The value side is unchanged.  Served by the vector-ALU kernels. */
 } lra_shape;
 
 /*

@@ -25,7 +25,7 @@ EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_st
 class LraShape(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("rank", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float), ("key_rope_theta", ctypes.c_float)]
 
 
 class LraCache(ctypes.Structure):
@@ -162,9 +162,10 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise LraError(3, f"unsupported torch dtype {t.dtype}")
 
 
-def make_shape(q: torch.Tensor, n_kv_heads: int, rank: int, scale: float = 0.0) -> LraShape:
+def make_shape(q: torch.Tensor, n_kv_heads: int, rank: int, scale: float = 0.0,
+               key_rope_theta: float = 0.0) -> LraShape:
     return LraShape(int(q.shape[-2]), int(n_kv_heads), int(q.shape[-1]), int(rank), _dtype_code(q),
-                    float(scale))
+                    float(scale), float(key_rope_theta))
 
 
 def make_cache(k_base: torch.Tensor, v_base: torch.Tensor, l: torch.Tensor, seq_lens: torch.Tensor,

@@ -40,6 +40,8 @@ static lra_status check_common(const lra_shape* sh, const lra_cache* c) {
   if (sh->n_q_heads < 1 || sh->n_kv_heads < 1 || sh->head_dim < 1 || sh->rank < 1) return LRA_ERR_SHAPE;
   if (sh->n_q_heads % sh->n_kv_heads) return LRA_ERR_SHAPE;
   if (!(sh->scale >= 0.f) || std::isinf(sh->scale)) return LRA_ERR_SHAPE;
+  if (!(sh->key_rope_theta >= 0.f) || std::isinf(sh->key_rope_theta)) return LRA_ERR_SHAPE;
+  if (sh->key_rope_theta > 0.f && (sh->head_dim & 1)) return LRA_ERR_SHAPE;
   if (sh->head_dim != 64 && sh->head_dim != 128) return LRA_ERR_UNSUPPORTED;
   if (sh->rank > 64) return LRA_ERR_UNSUPPORTED;
   if (sh->n_q_heads / sh->n_kv_heads > 16) return LRA_ERR_UNSUPPORTED;
@@ -67,7 +69,7 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   const int G = sh->n_q_heads / sh->n_kv_heads;
   // The MFMA decode kernel moves L in 16-byte pieces: ranks that are not a
   // multiple of 8 take the vector-ALU kernels.
-  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
+  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0 && !(sh->key_rope_theta > 0.f);
   if (prefill && pl.mfma) {
     // the MFMA prefill kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
@@ -199,6 +201,7 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.split_keys = pl.split_keys;
   p.n_splits = pl.n_splits;
   p.scale = sh->scale > 0.f ? sh->scale : 1.0f / std::sqrt(static_cast<float>(sh->head_dim));
+  p.key_rope_theta = sh->key_rope_theta;
 }
 
 static lra_status check_workspace(const Plan& pl, void* workspace, size_t workspace_bytes) {

@@ -40,6 +40,7 @@ struct Params {
   int32_t seq_index, adapter_index;  // prefill only
   int32_t split_keys, n_splits;
   float scale;
+  float key_rope_theta;  // > 0: the key-side adapter contribution is rotated by its token's position
 };
 
 typedef uint16_t bf16_t;

@@ -103,6 +103,126 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
   if (lane < r) p.part_lr[slot * r + lane] = olr;
 }
 
+// The same for the rotary key side (App. D.1 with the rotation in place: LoRA on the key
+// projection of a model with rotary embeddings).  K_j = K_base,j + RoPE_j(L_j B_K): the
+// rotation sits between L_j B_K and the score, so (q B_K^T) . L_j no longer applies.  With
+// rotate-half pairs (i, i + h), h = d/2, and c_i, s_i the cosine and sine of j * theta^(-2i/d),
+//     q . RoPE_j(L_j B) = sum_i  c_i (L_j . U_i) + s_i (L_j . W_i),
+//     U_i[rho] = q_i B[rho][i] + q_{i+h} B[rho][i+h],   W_i[rho] = q_{i+h} B[rho][i] - q_i B[rho][i+h],
+// r-vectors per pair that depend on the query row only.  The wave forms U and W once in LDS,
+// stages the L rows of its 64 keys there as well, and every lane (one key) sums over the
+// pairs.  r * d multiply-adds per (row, key) instead of d + r: the price of the rotation
+// without materialising the keys.  Angles as in the cache-append producer: rates in double
+// precision and revolutions, fractional part, v_sin_f32 / v_cos_f32.
+template <typename T>
+__global__ __launch_bounds__(kWave) void generic_partial_rope_kernel(Params p) {
+  const int row = blockIdx.x;
+  const int split = blockIdx.y;
+  const int lane = threadIdx.x;
+  const int Hq = p.n_q_heads, d = p.head_dim, r = p.rank, half = d / 2;
+  const int tok = row / Hq;
+  const int g = row - tok * Hq;
+  const int h = g / p.group;
+
+  int t, a, n_vis;
+  if (p.is_prefill) {
+    t = p.seq_index;
+    a = p.adapter_index;
+    const int n_t = min(p.seq_lens[t], p.max_seq_len);
+    n_vis = n_t - p.n_new + tok + 1;
+  } else {
+    t = 0;
+    while (t + 1 < p.n_seqs && p.seq_query_start[t + 1] <= tok) ++t;
+    a = p.query_adapter[tok];
+    n_vis = min(p.seq_lens[t], p.max_seq_len);
+  }
+  const int j0 = split * p.split_keys;
+  const int j1 = min(j0 + p.split_keys, n_vis);
+
+  __shared__ float q_s[128];
+  __shared__ float u_s[64 * 64];   // [rho][i], i < d/2
+  __shared__ float w_s[64 * 64];
+  __shared__ float l_s[64 * 65];   // [key of the step][rho], rows padded to 65 floats
+  __shared__ double rate_s[64];    // revolutions per position of pair i
+  const T* q = static_cast<const T*>(p.q) + static_cast<int64_t>(row) * d;
+  for (int c = lane; c < d; c += kWave) q_s[c] = to_f32<T>(q[c]);
+  if (lane < half)
+    rate_s[lane] = exp2(-2.0 * lane / d * log2(static_cast<double>(p.key_rope_theta))) * 0.15915494309189533577;
+  __syncthreads();
+  {
+    const T* bk = static_cast<const T*>(p.b_k) + static_cast<int64_t>(a) * r * (static_cast<int64_t>(p.n_kv_heads) * d) + h * d;
+    for (int e = lane; e < r * half; e += kWave) {
+      const int rho = e / half, i = e - rho * half;
+      const float b_lo = to_f32<T>(bk[static_cast<int64_t>(rho) * p.n_kv_heads * d + i]);
+      const float b_hi = to_f32<T>(bk[static_cast<int64_t>(rho) * p.n_kv_heads * d + i + half]);
+      u_s[rho * 64 + i] = q_s[i] * b_lo + q_s[i + half] * b_hi;
+      w_s[rho * 64 + i] = q_s[i + half] * b_lo - q_s[i] * b_hi;
+    }
+  }
+  __syncthreads();
+
+  const T* kb = static_cast<const T*>(p.k_base);
+  const T* vb = static_cast<const T*>(p.v_base);
+  const T* lr = static_cast<const T*>(p.l);
+
+  float m = -INFINITY, ell = 0.f, o0 = 0.f, o1 = 0.f, olr = 0.f;
+  for (int jb = j0; jb < j1; jb += kWave) {
+    const int j = jb + lane;
+    const bool valid = j < j1;
+    // this lane's L row, as floats, where the lane can index it with a loop variable
+    if (valid) {
+      const T* lrow = lr + l_offset(p, t, j);
+      for (int rho = 0; rho < r; ++rho) l_s[lane * 65 + rho] = to_f32<T>(lrow[rho]);
+    }
+    __syncthreads();  // one wave: orders the staging against the other lanes' reads below
+    float s = -INFINITY;
+    if (valid) {
+      const float sk = dot_row<T>(kb + kv_offset(p, t, j, h), q_s, d);
+      float sl = 0.f;
+      for (int i = 0; i < half; ++i) {
+        float u = 0.f, w = 0.f;
+        for (int rho = 0; rho < r; ++rho) {
+          const float lv = l_s[lane * 65 + rho];
+          u = fmaf(lv, u_s[rho * 64 + i], u);
+          w = fmaf(lv, w_s[rho * 64 + i], w);
+        }
+        double rev = static_cast<double>(j) * rate_s[i];
+        rev -= floor(rev);
+        const float fr = static_cast<float>(rev);
+        sl = fmaf(__builtin_amdgcn_cosf(fr), u, fmaf(__builtin_amdgcn_sinf(fr), w, sl));
+      }
+      s = p.scale * (sk + sl);
+    }
+    const float m_new = fmaxf(m, wave_max(s));  // finite: lane 0 is always valid here
+    const float alpha = (m == -INFINITY) ? 0.f : expf(m - m_new);
+    const float pj = valid ? expf(s - m_new) : 0.f;
+    ell = alpha * ell + wave_sum(pj);
+    o0 *= alpha;
+    o1 *= alpha;
+    olr *= alpha;
+    const int cnt = min(kWave, j1 - jb);
+    for (int jj = 0; jj < cnt; ++jj) {
+      const float pjj = __shfl(pj, jj, kWave);
+      const T* v = vb + kv_offset(p, t, jb + jj, h);
+      if (lane < d) o0 = fmaf(pjj, to_f32<T>(v[lane]), o0);
+      if (lane + kWave < d) o1 = fmaf(pjj, to_f32<T>(v[lane + kWave]), o1);
+      if (lane < r) olr = fmaf(pjj, l_s[jj * 65 + lane], olr);
+    }
+    m = m_new;
+    __syncthreads();  // before the next step overwrites the staged rows
+  }
+
+  const int64_t slot = static_cast<int64_t>(row) * p.n_splits + split;
+  if (lane == 0) {
+    p.part_ml[slot * 2 + 0] = m;  // a split past the row's last visible key leaves (-inf, 0)
+    p.part_ml[slot * 2 + 1] = ell;
+    if (split == 0) p.part_adapter[row] = a;
+  }
+  if (lane < d) p.part_o[slot * d + lane] = o0;
+  if (lane + kWave < d) p.part_o[slot * d + lane + kWave] = o1;
+  if (lane < r) p.part_lr[slot * r + lane] = olr;
+}
+
 // Flash-decoding merge of the per-split states followed by Alg. 1's epilogue:
 //   M = max_s m_s, w_s = exp(m_s - M), l = sum w_s l_s, O = sum w_s O_s,
 //   O_lr = sum w_s O_lr,s ;  out = (O + O_lr B_V) / l.
@@ -228,6 +348,11 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
 
 hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipStream_t s) {
   dim3 grid(rows, p.n_splits), block(kWave);
+  if (p.key_rope_theta > 0.f && p.b_k != nullptr) {
+    if (is_bf16) hipLaunchKernelGGL(generic_partial_rope_kernel<bf16_t>, grid, block, 0, s, p);
+    else hipLaunchKernelGGL(generic_partial_rope_kernel<float>, grid, block, 0, s, p);
+    return hipGetLastError();
+  }
   if (is_bf16)
     hipLaunchKernelGGL(generic_partial_kernel<bf16_t>, grid, block, 0, s, p);
   else

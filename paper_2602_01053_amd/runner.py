@@ -11,7 +11,7 @@ from .workloads import Workload
 class DeviceWorkload:
     """Device copies of a Workload plus the C structs that describe them."""
 
-    def __init__(self, w: Workload, dev, head_major: bool = False):
+    def __init__(self, w: Workload, dev, head_major: bool = False, key_rope_theta: float = 0.0):
         self.w = w
         self.q = w.q.to(dev)
         if w.block_size == 0 and head_major:
@@ -30,7 +30,7 @@ class DeviceWorkload:
         self.seq_query_start = w.seq_query_start.to(dev)
         s = w.seq_query_start.tolist()
         self.max_queries_per_seq = max(b - a for a, b in zip(s[:-1], s[1:]))
-        self.shape = lra.make_shape(self.q, w.n_kv_heads, w.rank, w.scale)
+        self.shape = lra.make_shape(self.q, w.n_kv_heads, w.rank, w.scale, key_rope_theta)
         self.cache = lra.make_cache(self.k_base, self.v_base, self.l, self.seq_lens,
                                     max(w.seq_lens), self.block_table)
         self.out = torch.empty_like(self.q)
