@@ -207,3 +207,29 @@ def test_append_rejects_what_it_cannot_do():
     with pytest.raises(lra.LraError) as e:
         lra.lra_cache_append(shape, cache, w, 10000.0, x, 0)
     assert e.value.status == 2
+
+
+@pytest.mark.parametrize("n_new,prior", [(2048, 16384), (16384, 0), (1, 40000)], ids=["2048_after_16384", "16384_from_empty", "decode_step"])
+def test_append_llama3_8b_full_size_sampled_rows(n_new, prior):
+    """The benchmark's configuration (d_model 4096 -> 8 kv heads x 128 + rank 16, rotary base 500000) in the
+    launch shape bench.py times; the oracle evaluates a sample of the new tokens (rows are independent)."""
+    hkv, d, r, dm, theta = 8, 128, 16, 4096, 500000.0
+    n = prior + n_new
+    x, w = _inputs(7000 + n_new, n_new, dm, hkv, d, r)
+    k_base = torch.full((n, hkv, d), SENTINEL, dtype=torch.bfloat16, device=DEV)
+    v_base = torch.full_like(k_base, SENTINEL)
+    l = torch.full((n, r), SENTINEL, dtype=torch.bfloat16, device=DEV)
+    seq_lens = torch.tensor([n], dtype=torch.int32, device=DEV)
+    shape = lra.make_shape(torch.empty(1, hkv, d, dtype=torch.bfloat16, device=DEV), hkv, r, 0.0)
+    cache = lra.make_cache(k_base, v_base, l, seq_lens, n, None)
+    lra.lra_cache_append(shape, cache, w.to(DEV), theta, x.to(DEV), 0)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(n_new)
+    rows = np.unique(np.concatenate([[0, n_new - 1], rng.integers(0, n_new, size=min(96, n_new))]))
+    f = lambda t: t.to(torch.float64).cpu().numpy()
+    k_ref, v_ref, l_ref = oracle.project_new_tokens(f(x[rows]), f(w), hkv, d, r, prior + rows, theta)
+    _gate(f(k_base[prior + rows]), k_ref, "K rows")
+    _gate(f(v_base[prior + rows]), v_ref, "V rows")
+    _gate(f(l[prior + rows]), l_ref, "L rows")
+    if prior:
+        assert bool((k_base[:prior] == SENTINEL).all()) and bool((l[:prior] == SENTINEL).all())
