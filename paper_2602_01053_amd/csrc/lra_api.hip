@@ -69,7 +69,11 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   const int G = sh->n_q_heads / sh->n_kv_heads;
   // The MFMA decode kernel moves L in 16-byte pieces: ranks that are not a
   // multiple of 8 take the vector-ALU kernels.
-  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0 && !(sh->key_rope_theta > 0.f);
+  // The rotary key side has an MFMA kernel for prefill only (the tile-walking one: a key tile
+  // is completed in LDS for its single adapter); decode, where every agent would need its own
+  // completed tile, takes the vector-ALU kernels.
+  const bool rope = sh->key_rope_theta > 0.f;
+  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0 && (!rope || prefill);
   if (prefill && pl.mfma) {
     // the MFMA prefill kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
@@ -82,7 +86,7 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   // workgroup per q head and nothing to split; the split-KV decode kernel, with the new
   // tokens in the place of the agents and a causal limit per row, spreads the context over
   // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
-  pl.short_prefill = prefill && pl.mfma && tokens <= g_short_prefill.load() &&
+  pl.short_prefill = prefill && pl.mfma && !rope && tokens <= g_short_prefill.load() &&
                      static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
   if (prefill && pl.mfma && !pl.short_prefill) {
     // Tile-walking kernel: one workgroup per (128-row q tile, q head).  When that is fewer

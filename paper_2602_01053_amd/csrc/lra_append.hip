@@ -22,22 +22,6 @@
 
 namespace lra {
 
-// Rotary angles.  Pair dd of a head turns by pos * theta^(-2 dd / d) radians; the kernels keep
-// that rate in revolutions (divided by 2 pi) in double precision, so that the product with a
-// position in the tens of thousands can be reduced to its fractional part without loss, and
-// take sine and cosine of the fraction with v_sin_f32 / v_cos_f32 (argument in revolutions,
-// absolute error around 1e-6: far below the bf16 rounding of the result).
-__device__ __forceinline__ double rope_rate_rev(int dd, int head_dim, float theta) {
-  return exp2(-2.0 * dd / head_dim * log2(static_cast<double>(theta))) * 0.15915494309189533577;
-}
-__device__ __forceinline__ void rope_sincos(double rate_rev, int pos, float& sn, float& cs) {
-  double rev = static_cast<double>(pos) * rate_rev;
-  rev -= floor(rev);
-  const float fr = static_cast<float>(rev);
-  sn = __builtin_amdgcn_sinf(fr);
-  cs = __builtin_amdgcn_cosf(fr);
-}
-
 template <int D, bool PAGED, int NS>
 __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendParams p) {
   constexpr int BF = 128, BT = 128, BK = 64;  // features, tokens, d_model step

@@ -30,8 +30,17 @@ namespace lra {
 // SPLIT = true: the key tiles of a q tile are shared by gridDim.y workgroups; each leaves its
 // softmax state (m, l, O, O_lr per row) in the workspace and the merge kernel combines
 // them, applies B_V and normalises (for calls with too few q tiles to fill the chip).
-template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT>
+// ROPE_K = true (with HAS_BK = false) is the rotary key side of App. D.1: the cached keys are
+// rotated ones and the adapter's contribution has to be rotated by its key's position before
+// the score, so it cannot ride on Qt.  Instead every key tile is completed in LDS before the
+// scores are taken: E^T = B_K^T . L^T for the tile's 64 keys (two MFMAs per wave and 16
+// ranks: a wave owns 32 keys and the two 32-feature blocks that hold the halves of its rotary
+// pairs, so both halves of a pair sit in the same lane and register), rotated, and added to
+// the K_base rows of the tile (8-byte read-modify-writes in bf16).  One more barrier per
+// tile; the score loop is the value-only one.
+template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
+  static_assert(!(ROPE_K && HAS_BK), "the rotary key side replaces the Qt term");
   constexpr int BM = 128, BN = 64;
   constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
   constexpr int RKS = RP / 16; // k-steps over the padded rank
@@ -49,6 +58,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   constexpr int ONES_AT = 2 * STAGE;
 
   __shared__ __align__(16) unsigned char smem[2 * STAGE + (ONES_ROW ? 16 : 0)];
+  __shared__ double rope_rate[ROPE_K ? D / 2 : 1];  // revolutions per position of every rotary pair
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -96,6 +106,42 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 
   issue_tile(tile_begin * BN, 0);
   if (ONES_ROW && tid == 0) *reinterpret_cast<pf_u32x4*>(smem + ONES_AT) = pf_u32x4{0x00003f80u, 0u, 0u, 0u};
+
+  // ---------------- rotary key side: B_K^T operands of E^T, rotation rates ----------------
+  // Wave (pair set ps = wave / 2, key half kt_e = wave % 2); d = 128: feature blocks ps and ps + 2,
+  // d = 64: blocks 0 and 1 (waves 2, 3 have nothing to do).  A operand of E^T = B_K^T . L^T: lane
+  // (feature l32 of the block, half g2), element e <-> rho = 16ks + 8(e/4) + 4g2 + e%4, the order in
+  // which the L operand is read below.
+  constexpr int E_WAVES = ROPE_K ? 2 * (D / 64) : 0;
+  const int fb_lo = D == 128 ? (wave >> 1) : 0, fb_hi = D == 128 ? (wave >> 1) + 2 : 1;
+  const int kt_e = wave & 1;
+  pf_bf16x8 bkt[2][ROPE_K ? RKS : 1];
+  if (ROPE_K) {
+    if (tid < D / 2) rope_rate[tid] = rope_rate_rev(tid, D, p.key_rope_theta);  // read after the loop's first barrier
+    if (wave < E_WAVES) {
+      const int64_t ldb = static_cast<int64_t>(Hkv) * D;
+      const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k) + static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D;
+#pragma unroll
+      for (int sel = 0; sel < 2; ++sel)
+#pragma unroll
+        for (int ks = 0; ks < RKS; ++ks) {
+          uint32_t w4[4];
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            uint32_t pair = 0;
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+              const int e = 2 * e2 + x;
+              const int rho = 16 * ks + 8 * (e >> 2) + 4 * g2 + (e & 3);
+              const uint32_t v = rho < r ? bkg[rho * ldb + 32 * (sel == 0 ? fb_lo : fb_hi) + l32] : 0u;
+              pair |= v << (16 * x);
+            }
+            w4[e2] = pair;
+          }
+          bkt[sel][ks] = pf_as_bf16x8(make_uint4(w4[0], w4[1], w4[2], w4[3]));
+        }
+    }
+  }
 
   // ---------------- prologue: Q operands, Qt = Q B_K^T ----------------
   // qb[ks]: B operand of S^T: lane (row l32, k = 16ks + 8g2 + e)
@@ -209,6 +255,49 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     // the other stage was last read before the barrier that ended the previous tile; where
     // in the tile the requests are placed makes no measurable difference
     if (more) issue_tile(j + BN, ST ^ 1);
+
+    if (ROPE_K) {
+      if (wave < E_WAVES) {
+        pf_f32x16 e_lo, e_hi;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) e_lo[i] = e_hi[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < RKS; ++ks) {
+          const uint2 lo = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][0] + kt_e * 32 * RP * 2);
+          const uint2 hi = *reinterpret_cast<const uint2*>(ks_l + l_rd[ks][1] + kt_e * 32 * RP * 2);
+          const pf_bf16x8 lop = pf_as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+          e_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bkt[0][ks], lop, e_lo, 0, 0, 0);
+          e_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bkt[1][ks], lop, e_hi, 0, 0, 0);
+        }
+        // register i of this lane: key 32 kt_e + l32 of the tile (position j + that), features
+        // 32 fb + 8 (i/4) + 4 g2 + i%4 of blocks fb_lo, fb_hi: pair index = the fb_lo feature
+        const int key = 32 * kt_e + l32;
+        const int pos = j + key;
+        unsigned char* krow = smem + ST * STAGE + key * (D * 2) + 8 * g2;
+        const int swz = pf_swz_k<D>(key);
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float lo4[4], hi4[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * q4 + e;
+            float sn, cs;
+            rope_sincos(rope_rate[32 * fb_lo + 8 * q4 + 4 * g2 + e], pos, sn, cs);
+            lo4[e] = e_lo[i] * cs - e_hi[i] * sn;
+            hi4[e] = e_hi[i] * cs + e_lo[i] * sn;
+          }
+#pragma unroll
+          for (int sel = 0; sel < 2; ++sel) {
+            const float* add = sel == 0 ? lo4 : hi4;
+            uint2* at = reinterpret_cast<uint2*>(krow + (((4 * (sel == 0 ? fb_lo : fb_hi) + q4) ^ swz) << 4));
+            const uint2 old = *at;
+            *at = make_uint2(pf_pack2(__uint_as_float(old.x << 16) + add[0], __uint_as_float(old.x & 0xffff0000u) + add[1]),
+                             pf_pack2(__uint_as_float(old.y << 16) + add[2], __uint_as_float(old.y & 0xffff0000u) + add[3]));
+          }
+        }
+      }
+      __syncthreads();  // the completed keys are visible to the score loop of every wave
+    }
 
     // S^T for the two 32-key halves of the tile.  The halves alternate, so consecutive
     // matrix instructions never wait for each other's result, and the LDS reads run
@@ -418,6 +507,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
 template <int D, int RP, bool SPLIT>
 static hipError_t launch_pf2(const Params& p, dim3 grid, hipStream_t s) {
   const bool paged = p.block_size != 0, has_bk = p.b_k != nullptr;
+  if (has_bk && p.key_rope_theta > 0.f) {
+    if (paged) hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false, SPLIT, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, SPLIT, true>), grid, dim3(256), 0, s, p);
+    return hipGetLastError();
+  }
   if (paged && has_bk)
     hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, true, SPLIT>), grid, dim3(256), 0, s, p);
   else if (paged)

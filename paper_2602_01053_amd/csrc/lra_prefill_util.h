@@ -77,6 +77,22 @@ typedef const __attribute__((address_space(4))) int32_t* pf_const_i32;
 
 constexpr uint32_t kPfOob = 0x80000000u;  // beyond any resource this kernel builds
 
+// Rotary angles.  Pair dd of a head turns by pos * theta^(-2 dd / d) radians; the kernels keep
+// that rate in revolutions (divided by 2 pi) in double precision, so that the product with a
+// position in the tens of thousands can be reduced to its fractional part without loss, and
+// take sine and cosine of the fraction with v_sin_f32 / v_cos_f32 (argument in revolutions,
+// absolute error around 1e-6: far below the bf16 rounding of the result).
+__device__ __forceinline__ double rope_rate_rev(int dd, int head_dim, float theta) {
+  return exp2(-2.0 * dd / head_dim * log2(static_cast<double>(theta))) * 0.15915494309189533577;
+}
+__device__ __forceinline__ void rope_sincos(double rate_rev, int pos, float& sn, float& cs) {
+  double rev = static_cast<double>(pos) * rate_rev;
+  rev -= floor(rev);
+  const float fr = static_cast<float>(rev);
+  sn = __builtin_amdgcn_sinf(fr);
+  cs = __builtin_amdgcn_cosf(fr);
+}
+
 // LDS swizzles (XOR on the 16-byte chunk index of a row).  The LDS of this chip serves
 // 256 bytes per clock (64 banks): a ds_read_b128 is conflict-free when 16 consecutive
 // lanes cover 16 different chunk positions of that 256-byte window, a ds_read_b64_tr_b16

@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import oracle
+import paper_2602_01053_amd as lra
 from paper_2602_01053_amd import workloads as W
 from paper_2602_01053_amd.runner import DeviceWorkload
 from tests.harness import MAX_ABS_TOL, REL_L2_TOL, _f64, errors
@@ -83,3 +84,86 @@ def test_rotary_key_side_without_key_adapter_is_the_plain_path():
     assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
     rel, mx = errors(outs[0], outs[1])
     assert rel <= REL_L2_TOL
+
+
+def _prefill_cases():
+    mk = W.make_contiguous
+    yield "d128_r16_ragged", mk("rp1", "prefill", seed=311, n_agents=1, n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16,
+                                n=700, n_new=300, d_model=None, b_std=0.1), 500000.0
+    yield "d64_r24", mk("rp2", "prefill", seed=312, n_agents=1, n_q_heads=6, n_kv_heads=3, head_dim=64, rank=24,
+                        n=391, n_new=391, d_model=None, b_std=0.1), 10000.0
+    yield "d128_r64", mk("rp3", "prefill", seed=313, n_agents=1, n_q_heads=4, n_kv_heads=4, head_dim=128, rank=64,
+                         n=260, n_new=129, d_model=None, b_std=0.05), 500000.0
+    yield "positions_beyond_40000", mk("rp4", "prefill", seed=314, n_agents=1, n_q_heads=4, n_kv_heads=1, head_dim=128, rank=16,
+                                       n=41000, n_new=70, d_model=None, b_std=0.1), 500000.0
+    yield "paged_second_sequence", None, 500000.0
+
+
+@pytest.mark.parametrize("variant", [0, 1], ids=["mfma", "vector_alu"])
+@pytest.mark.parametrize("name,w,theta", list(_prefill_cases()), ids=[c[0] for c in _prefill_cases()])
+def test_rotary_key_side_prefill(name, w, theta, variant):
+    """The MFMA prefill kernel completes every key tile in LDS (E = L B_K rotated and added to the K_base rows)
+    before the scores; the vector-ALU kernels serve the same call when asked to (kernel variant 1)."""
+    if variant == 1 and name == "positions_beyond_40000":
+        pytest.skip("one wave per row over 41000 keys: covered by the shorter cases")
+    prev = lra.lra_set_kernel_variant(variant)
+    try:
+        if w is None:
+            _paged_prefill(theta)
+            return
+        got = _run(w, theta)
+    finally:
+        lra.lra_set_kernel_variant(prev)
+    ref = _oracle(w, theta)
+    rel, mx = errors(got, ref)
+    moved = np.linalg.norm(ref - _oracle(w, 0.0)) / np.linalg.norm(ref)
+    print(f"{name}: relL2={rel:.3e} maxabs={mx:.3e}; the rotation moves the output by {moved:.3e}", flush=True)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+    assert moved > 4 * REL_L2_TOL
+
+
+def _paged_prefill(theta):
+    """130 new tokens at the end of the second sequence of a paged cache (blocks in permuted order)."""
+    hkv, hq, d, r = 2, 8, 128, 16
+    seq_lens, n_new, s = [77, 500], 130, 1
+    bs, max_blocks, num_blocks = 16, 32, 70
+    gen = torch.Generator().manual_seed(315)
+    perm = torch.randperm(num_blocks, generator=gen).to(torch.int32)
+    table = torch.stack([perm[:max_blocks], perm[max_blocks:2 * max_blocks]])
+    rn = lambda *sh, std=1.0: (std * torch.randn(*sh, generator=gen)).to(torch.bfloat16)
+    k_pool, v_pool, l_pool = rn(num_blocks, hkv, bs, d), rn(num_blocks, hkv, bs, d), rn(num_blocks, bs, r)
+    q, b_k, b_v = rn(n_new, hq, d), rn(2, r, hkv * d, std=0.1), rn(2, r, hkv * d, std=0.1)
+    dev = lambda t: t.to(DEV)
+    lens_d = torch.tensor(seq_lens, dtype=torch.int32, device=DEV)
+    qd, kd, vd, ld, td, bkd, bvd = dev(q), dev(k_pool), dev(v_pool), dev(l_pool), dev(table), dev(b_k), dev(b_v)
+    shape = lra.make_shape(qd, hkv, r, 0.0, theta)
+    cache = lra.make_cache(kd, vd, ld, lens_d, max(seq_lens), td)   # holds raw pointers: the tensors stay alive above
+    out = torch.full_like(qd, float("nan"))
+    ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, 1, 1, n_new), 256), dtype=torch.uint8, device=DEV)
+    lra.lra_attn_prefill(shape, cache, bkd, bvd, 2, qd, s, 1, out, ws)
+    torch.cuda.synchronize()
+    f = lambda t: t.to(torch.float64).cpu().numpy()
+    ids = table[s].numpy()
+    kb, vb = oracle.gather_paged(f(k_pool), ids, seq_lens[s]), oracle.gather_paged(f(v_pool), ids, seq_lens[s])
+    lr = oracle.lra_oracle.gather_paged_l(f(l_pool), ids, seq_lens[s])
+    ref = oracle.prefill(f(q), kb, vb, lr, f(b_k[1]), f(b_v[1]), n=seq_lens[s], scale=1.0 / d ** 0.5, key_rope_theta=theta)
+    rel, mx = errors(f(out), ref)
+    print(f"paged prefill: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
+def test_rotary_key_side_prefill_with_shared_key_tiles():
+    """Few q tiles: the key tiles of a q tile are shared by several workgroups (forced to 5, then 32 with empty
+    shares) and merged; every share completes its own tiles."""
+    w = W.make_contiguous("rp5", "prefill", seed=316, n_agents=1, n_q_heads=4, n_kv_heads=2, head_dim=128, rank=16,
+                          n=2000, n_new=40, d_model=None, b_std=0.1)
+    ref = _oracle(w, 500000.0)
+    for splits in (5, 32):
+        prev = lra.lra_set_prefill_splits(splits)
+        try:
+            got = _run(w, 500000.0)
+        finally:
+            lra.lra_set_prefill_splits(prev)
+        rel, mx = errors(got, ref)
+        print(f"splits {splits}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+        assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
