@@ -15,6 +15,7 @@ The JSON line also carries
   roofline      the key-streaming kernel alone (no merge), HIP events on its stream
                 around the same number of back-to-back launches,
   prefill       the causal prefill workload (2048 new tokens after 16384), TFLOP/s,
+  rotary_key_prefill  the prefill workload with the rotary key side (key_rope_theta),
   cache_append  the producer of the caches (lra_cache_append) at the Llama-3-8B projection shape,
   cpu_baseline  the fp64 oracle timed on this machine's host cores.
 """
@@ -176,6 +177,23 @@ def bench_prefill(args, torch, lra, workloads):
     sec = (time.perf_counter() - t0) / steps
     ksec = kernel_seconds(lra, torch, lambda i: dw.prefill(), steps)
     return w, flops, sec, ksec, steps
+
+
+def bench_rotary_prefill(args, torch, lra, workloads):
+    """The prefill workload with the rotary key side (lra_shape.key_rope_theta: the adapter's key
+    contribution is rotated by its token's position, App. D.1): same algorithmic flops as the plain
+    call plus 2 * keys * rank * d per kv head and q tile for completing the key tiles."""
+    from paper_2602_01053_amd.runner import DeviceWorkload
+    w = workloads.config(3)
+    dw = DeviceWorkload(w, torch.device("cuda:0"), key_rope_theta=500000.0)
+    dw.alloc_workspace()
+    steps = max(3, min(args.steps // 10, 100))
+    ksec = kernel_seconds(lra, torch, lambda i: dw.prefill(), steps)
+    tf = w.algorithmic_flops() / ksec / 1e12
+    return {"workload": w.name + " with key_rope_theta = 500000", "call": "lra_attn_prefill", "kernel_ms": round(ksec * 1e3, 4),
+            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "note": "flops of the plain call; the completion of the key tiles in LDS is overhead"}}
 
 
 def bench_append(args, torch, lra, with_cpu, sizes=(16384, 2048, 1)):
@@ -341,6 +359,8 @@ def main():
             "roofline": {"bound": "mfma", "achieved": round(ktf, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(ktf / MFMA_BF16_PEAK_TFLOPS, 4),
                          "kernel_ms": round(pksec * 1e3, 4), "traffic": _load_traffic("prefill_cfg3")}}
+    if not args.no_prefill:
+        line["rotary_key_prefill"] = bench_rotary_prefill(args, torch, lra, workloads)
     if not args.no_other_decode:
         line["other_decode_workloads"] = other_decode_workloads(args, torch, lra, workloads)
         line["value_only_adapters"] = value_only_decode(args, torch, lra, workloads)

@@ -58,7 +58,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   constexpr int ONES_AT = 2 * STAGE;
 
   __shared__ __align__(16) unsigned char smem[2 * STAGE + (ONES_ROW ? 16 : 0)];
-  __shared__ double rope_rate[ROPE_K ? D / 2 : 1];  // revolutions per position of every rotary pair
+  // rotary key side: revolutions per position of every rotary pair (double, and rounded to float for
+  // the offsets inside a tile), and the angle of the first key of a tile (fraction of a revolution),
+  // double-buffered like the stages
+  __shared__ double rope_rate[ROPE_K ? D / 2 : 1];
+  __shared__ __align__(16) float rope_rate_f[ROPE_K ? D / 2 : 4];
+  __shared__ __align__(16) float rope_fr0[2][ROPE_K ? D / 2 : 4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -117,7 +122,14 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int kt_e = wave & 1;
   pf_bf16x8 bkt[2][ROPE_K ? RKS : 1];
   if (ROPE_K) {
-    if (tid < D / 2) rope_rate[tid] = rope_rate_rev(tid, D, p.key_rope_theta);  // read after the loop's first barrier
+    if (tid < D / 2) {  // read after the barrier that precedes the loop
+      const double rate = rope_rate_rev(tid, D, p.key_rope_theta);
+      rope_rate[tid] = rate;
+      rope_rate_f[tid] = static_cast<float>(rate);
+      double rev = static_cast<double>(tile_begin * BN) * rate;
+      rev -= floor(rev);
+      rope_fr0[0][tid] = static_cast<float>(rev);
+    }
     if (wave < E_WAVES) {
       const int64_t ldb = static_cast<int64_t>(Hkv) * D;
       const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k) + static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D;
@@ -271,18 +283,24 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         }
         // register i of this lane: key 32 kt_e + l32 of the tile (position j + that), features
         // 32 fb + 8 (i/4) + 4 g2 + i%4 of blocks fb_lo, fb_hi: pair index = the fb_lo feature
+        // Angle of (key, pair) in revolutions: that of the tile's first key, kept in double precision
+        // by the table threads, plus the key's offset in the tile times the rate (at most 63 x 0.16
+        // revolutions: single precision holds it to 1e-6).
         const int key = 32 * kt_e + l32;
-        const int pos = j + key;
+        const float key_f = static_cast<float>(key);
         unsigned char* krow = smem + ST * STAGE + key * (D * 2) + 8 * g2;
         const int swz = pf_swz_k<D>(key);
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
+          const int dd0 = 32 * fb_lo + 8 * q4 + 4 * g2;
+          const pf_f32x4 fr0 = *reinterpret_cast<const pf_f32x4*>(&rope_fr0[ST][dd0]);
+          const pf_f32x4 rt = *reinterpret_cast<const pf_f32x4*>(&rope_rate_f[dd0]);
           float lo4[4], hi4[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * q4 + e;
-            float sn, cs;
-            rope_sincos(rope_rate[32 * fb_lo + 8 * q4 + 4 * g2 + e], pos, sn, cs);
+            const float fr = fmaf(key_f, rt[e], fr0[e]);
+            const float sn = __builtin_amdgcn_sinf(fr), cs = __builtin_amdgcn_cosf(fr);
             lo4[e] = e_lo[i] * cs - e_hi[i] * sn;
             hi4[e] = e_hi[i] * cs + e_lo[i] * sn;
           }
@@ -297,6 +315,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
         }
       }
       __syncthreads();  // the completed keys are visible to the score loop of every wave
+      if (more && tid < D / 2) {  // the next tile's first angle, for the expansion after the barrier that ends this tile
+        double rev = static_cast<double>(j + BN) * rope_rate[tid];
+        rev -= floor(rev);
+        rope_fr0[ST ^ 1][tid] = static_cast<float>(rev);
+      }
     }
 
     // S^T for the two 32-key halves of the tile.  The halves alternate, so consecutive
