@@ -89,6 +89,10 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _decode(lib, *mutated(n_seqs=2)) == SHAPE              # contiguous holds one sequence
     assert _decode(lib, *mutated(n_adapters=0)) == SHAPE
     assert _decode(lib, *mutated(scale=float("nan"))) == SHAPE
+    assert _decode(lib, *mutated(key_rope_theta=-1.0)) == SHAPE
+    assert _decode(lib, *mutated(key_rope_theta=float("nan"))) == SHAPE
+    assert _decode(lib, *mutated(key_rope_theta=float("inf"))) == SHAPE
+    assert _decode(lib, *mutated(key_rope_theta=500000.0)) == WS     # valid: stops at the missing workspace
     assert _decode(lib, *mutated(block_size=16, n_seqs=2)) == NULL   # paged without a block table
     assert _decode(lib, *mutated(block_size=16, block_table=FAKE, num_blocks=600, kv_block_stride=16384,
                                  max_blocks_per_seq=8)) == SHAPE  # table row shorter than max_seq_len
