@@ -25,6 +25,7 @@ constexpr int kCUs = 256;  // MI355X
 struct Plan {
   bool mfma;
   bool short_prefill;  // prefill served by the split-KV decode kernels (few new tokens)
+  bool rope_decode;    // decode with the rotary key side, served by the tile-walking prefill kernel per query
   int rows;        // query rows = (queries | new tokens) x Hq
   int split_keys;  // keys per split
   int n_splits;    // splits per sequence at max_seq_len
@@ -67,36 +68,40 @@ static lra_status check_common(const lra_shape* sh, const lra_cache* c) {
 static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_queries_per_seq, bool prefill) {
   Plan pl{};
   const int G = sh->n_q_heads / sh->n_kv_heads;
-  // The MFMA decode kernel moves L in 16-byte pieces: ranks that are not a
-  // multiple of 8 take the vector-ALU kernels.
-  // The rotary key side has an MFMA kernel for prefill only (the tile-walking one: a key tile
-  // is completed in LDS for its single adapter); decode, where every agent would need its own
-  // completed tile, takes the vector-ALU kernels.
+  // The MFMA kernels move L in 16-byte pieces: ranks that are not a multiple of 8 take the
+  // vector-ALU kernels.
+  // The rotary key side runs on the tile-walking MFMA kernel, which completes a key tile in LDS
+  // for one adapter: prefill as it is, decode with one column of workgroups per query (every
+  // agent needs its own completed tiles).  The split-KV decode kernel has no rotary path.
   const bool rope = sh->key_rope_theta > 0.f;
-  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0 && (!rope || prefill);
-  if (prefill && pl.mfma) {
-    // the MFMA prefill kernel addresses a contiguous kv head slice, and L as a whole, with
+  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
+  bool rope_decode = rope && !prefill && pl.mfma;
+  if ((prefill || rope_decode) && pl.mfma) {
+    // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
     const int64_t lim = (int64_t{1} << 32) - 4096;
     const int64_t l_rows = c->block_size == 0 ? c->max_seq_len : static_cast<int64_t>(c->num_blocks) * 16;
     if (l_rows * sh->rank * 2 > lim) pl.mfma = false;
     if (c->block_size == 0 && static_cast<int64_t>(c->max_seq_len) * c->kv_token_stride * 2 > lim) pl.mfma = false;
   }
+  rope_decode = rope_decode && pl.mfma;
+  if (rope && !prefill && !rope_decode) pl.mfma = false;
+  pl.rope_decode = rope_decode;
   // A handful of new tokens after a long context gives the tile-walking prefill kernel one
   // workgroup per q head and nothing to split; the split-KV decode kernel, with the new
   // tokens in the place of the agents and a causal limit per row, spreads the context over
   // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
   pl.short_prefill = prefill && pl.mfma && !rope && tokens <= g_short_prefill.load() &&
                      static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
-  if (prefill && pl.mfma && !pl.short_prefill) {
-    // Tile-walking kernel: one workgroup per (128-row q tile, q head).  When that is fewer
-    // than two workgroups per CU, the key tiles of every q tile are divided among several
-    // workgroups (at least eight 64-key tiles each) and the merge kernel finishes the job;
-    // otherwise it is one kernel without a workspace.
+  if ((prefill && pl.mfma && !pl.short_prefill) || rope_decode) {
+    // Tile-walking kernel: one workgroup per (128-row q tile, q head) - per (query, q head) for
+    // the rotary decode.  When that is fewer than two workgroups per CU, the key tiles of
+    // every q tile are divided among several workgroups (at least eight 64-key tiles each)
+    // and the merge kernel finishes the job; otherwise it is one kernel without a workspace.
     pl.rows = tokens * sh->n_q_heads;
     pl.group_pad = pl.row_tiles = pl.row_groups = 1;
     pl.split_keys = c->max_seq_len;
-    const int64_t wgs = static_cast<int64_t>((tokens + 127) / 128) * sh->n_q_heads;
+    const int64_t wgs = static_cast<int64_t>(rope_decode ? tokens : (tokens + 127) / 128) * sh->n_q_heads;
     int64_t ns = g_prefill_splits.load();
     if (ns <= 0) {  // automatic: two workgroups per CU, at least eight key tiles per share
       ns = (2 * kCUs + wgs - 1) / wgs;
@@ -259,6 +264,12 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   p.is_prefill = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
+  if (pl.rope_decode) {
+    if (launch_decode_rope_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
+    if (pl.n_splits > 1 && g_profile_mode.load() != 1 && launch_merge(p, bf16, pl.rows, s) != hipSuccess)
+      return LRA_ERR_HIP;
+    return LRA_OK;
+  }
   if (pl.mfma) {
     if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
   } else {

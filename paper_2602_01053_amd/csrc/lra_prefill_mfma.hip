@@ -38,9 +38,15 @@ namespace lra {
 // pairs, so both halves of a pair sit in the same lane and register), rotated, and added to
 // the K_base rows of the tile (8-byte read-modify-writes in bf16).  One more barrier per
 // tile; the score loop is the value-only one.
-template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false>
+// PERQ = true serves decode with the rotary key side on the same kernel: blockIdx.z is a query
+// of the decode call (sequence and adapter come from the call's device tables), treated as a
+// prefill of one new token that sees its whole sequence.  Only row 0 of the q tile is live, so
+// the matrix work is mostly idle, but the keys of a sequence are streamed and completed by the
+// same code, shared over gridDim.y workgroups and merged.
+template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false, bool PERQ = false>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   static_assert(!(ROPE_K && HAS_BK), "the rotary key side replaces the Qt term");
+  static_assert(!PERQ || ROPE_K, "decode without the rotary key side has its own kernel");
   constexpr int BM = 128, BN = 64;
   constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
   constexpr int RKS = RP / 16; // k-steps over the padded rank
@@ -78,14 +84,23 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int gq = rest % G;
   const int qt = rest / G;
   const int head = hk * G + gq;
-  const int t = p.seq_index;
+  // PERQ: the query this workgroup serves, its sequence (queries are grouped by sequence) and adapter
+  const int zq = PERQ ? static_cast<int>(blockIdx.z) : 0;
+  int t = p.seq_index;
+  int a_idx = p.adapter_index;
+  if (PERQ) {
+    t = 0;
+    while (t + 1 < p.n_seqs && PF_CONST_I32(p.seq_query_start)[t + 1] <= zq) ++t;
+    a_idx = min(max(PF_CONST_I32(p.query_adapter)[zq], 0), p.n_adapters - 1);
+  }
   const int n_t = min(PF_CONST_I32(p.seq_lens)[t], p.max_seq_len);
-  const int n_new = p.n_new;
+  const int n_new = PERQ ? 1 : p.n_new;
   const int q0 = qt * BM;
   if (q0 >= n_new) return;
   const int base_vis = n_t - n_new;  // new token i sees keys 0 .. base_vis + i
   const int row = q0 + wave * 32 + l32;           // this lane's query row (new-token index)
   const int row_c = min(row, n_new - 1);          // clamped for loads; rows past the end are never stored
+  const int grow = zq + row, grow_c = zq + row_c; // row of q, out and the workspace (PERQ: the query; else the new token)
   const int limit = base_vis + row_c;             // last visible key of this lane's row
   const int wg_last = base_vis + min(q0 + BM, n_new) - 1;  // last key any row of the workgroup sees
   const int n_tiles = wg_last / BN + 1;
@@ -97,10 +112,10 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     // more workgroups than key tiles: leave an empty state (zero row sum), all the merge
     // kernel looks at
     if (row < n_new && g2 == 0) {
-      const int64_t slot = (static_cast<int64_t>(row) * Hq + head) * p.n_splits + split;
+      const int64_t slot = (static_cast<int64_t>(grow) * Hq + head) * p.n_splits + split;
       p.part_ml[slot * 2 + 0] = -INFINITY;
       p.part_ml[slot * 2 + 1] = 0.f;
-      if (split == 0) p.part_adapter[static_cast<int64_t>(row) * Hq + head] = p.adapter_index;
+      if (split == 0) p.part_adapter[static_cast<int64_t>(grow) * Hq + head] = a_idx;
     }
     return;
   }
@@ -132,7 +147,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     }
     if (wave < E_WAVES) {
       const int64_t ldb = static_cast<int64_t>(Hkv) * D;
-      const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k) + static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D;
+      const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k) + static_cast<int64_t>(a_idx) * r * ldb + hk * D;
+      const bool has_b = p.b_k != nullptr;  // (a decode call may come without key-side adapters: nothing to add)
 #pragma unroll
       for (int sel = 0; sel < 2; ++sel)
 #pragma unroll
@@ -145,7 +161,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
             for (int x = 0; x < 2; ++x) {
               const int e = 2 * e2 + x;
               const int rho = 16 * ks + 8 * (e >> 2) + 4 * g2 + (e & 3);
-              const uint32_t v = rho < r ? bkg[rho * ldb + 32 * (sel == 0 ? fb_lo : fb_hi) + l32] : 0u;
+              const uint32_t v = (has_b && rho < r) ? bkg[rho * ldb + 32 * (sel == 0 ? fb_lo : fb_hi) + l32] : 0u;
               pair |= v << (16 * x);
             }
             w4[e2] = pair;
@@ -159,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   // qb[ks]: B operand of S^T: lane (row l32, k = 16ks + 8g2 + e)
   pf_bf16x8 qb[KS];
   {
-    const bf16_t* qrow = static_cast<const bf16_t*>(p.q) + (static_cast<int64_t>(row_c) * Hq + head) * D + g2 * 8;
+    const bf16_t* qrow = static_cast<const bf16_t*>(p.q) + (static_cast<int64_t>(grow_c) * Hq + head) * D + g2 * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qb[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(qrow + ks * 16));
   }
@@ -174,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     // rows of this adapter's B_K for kv head hk; rows past the rank (and everything when
     // there is no B_K) lie outside the resource and read as zero
     const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t*>(bkg) + (bkg != nullptr ? static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D : 0), 0,
+        const_cast<bf16_t*>(bkg) + (bkg != nullptr ? static_cast<int64_t>(a_idx) * r * ldb + hk * D : 0), 0,
         bkg != nullptr ? static_cast<int>((static_cast<int64_t>(r - 1) * ldb + D) * 2) : 0, 0x00020000);
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
@@ -462,11 +478,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     // this share's state for the merge kernel: m in natural-log units, l, O^T and Olr^T as
     // fp32 rows [slot][d] and [slot][rank]; registers 4q..4q+3 are d (rho) = 32b + 8q + 4g2 + 0..3
     if (row < n_new) {
-      const int64_t slot = (static_cast<int64_t>(row) * Hq + head) * p.n_splits + split;
+      const int64_t slot = (static_cast<int64_t>(grow) * Hq + head) * p.n_splits + split;
       if (g2 == 0) {
         p.part_ml[slot * 2 + 0] = m_run * 0.69314718055994530942f;
         p.part_ml[slot * 2 + 1] = l_run;
-        if (split == 0) p.part_adapter[static_cast<int64_t>(row) * Hq + head] = p.adapter_index;
+        if (split == 0) p.part_adapter[static_cast<int64_t>(grow) * Hq + head] = a_idx;
       }
 #pragma unroll
       for (int b = 0; b < DB; ++b)
@@ -488,7 +504,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   }
   if (p.b_v != nullptr) {
     const int64_t ldb = static_cast<int64_t>(Hkv) * D;
-    const bf16_t* bv = static_cast<const bf16_t*>(p.b_v) + static_cast<int64_t>(p.adapter_index) * r * ldb + hk * D;
+    const bf16_t* bv = static_cast<const bf16_t*>(p.b_v) + static_cast<int64_t>(a_idx) * r * ldb + hk * D;
 #pragma unroll
     for (int ks = 0; ks < RKS; ++ks) {
       // B operand: Olr^T registers 8(ks&1)..+7 of block ks/2: element e <-> rho = 16ks + 8(e/4) + 4g2 + e%4
@@ -514,7 +530,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   }
   if (row < n_new) {
     const float inv = 1.0f / l_run;
-    bf16_t* orow = static_cast<bf16_t*>(p.out) + (static_cast<int64_t>(row) * Hq + head) * D;
+    bf16_t* orow = static_cast<bf16_t*>(p.out) + (static_cast<int64_t>(grow) * Hq + head) * D;
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -563,6 +579,33 @@ hipError_t launch_prefill_mfma(const Params& p, hipStream_t s) {
   if (rp == 16) return launch_pf<64, 16>(p, grid, s);
   if (rp == 32) return launch_pf<64, 32>(p, grid, s);
   return launch_pf<64, 64>(p, grid, s);
+}
+
+// Decode with the rotary key side: one workgroup per (q head, share of the keys, query).
+template <int D, int RP>
+static hipError_t launch_rope_dec(const Params& p, dim3 grid, hipStream_t s) {
+  const bool paged = p.block_size != 0;
+  if (p.n_splits > 1) {
+    if (paged) hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false, true, true, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, true, true, true>), grid, dim3(256), 0, s, p);
+  } else {
+    if (paged) hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false, false, true, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, false, true, true>), grid, dim3(256), 0, s, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_rope_mfma(const Params& p, hipStream_t s) {
+  dim3 grid(p.n_q_heads, p.n_splits, p.n_queries);
+  const int rp = p.rank <= 16 ? 16 : (p.rank <= 32 ? 32 : 64);
+  if (p.head_dim == 128) {
+    if (rp == 16) return launch_rope_dec<128, 16>(p, grid, s);
+    if (rp == 32) return launch_rope_dec<128, 32>(p, grid, s);
+    return launch_rope_dec<128, 64>(p, grid, s);
+  }
+  if (rp == 16) return launch_rope_dec<64, 16>(p, grid, s);
+  if (rp == 32) return launch_rope_dec<64, 32>(p, grid, s);
+  return launch_rope_dec<64, 64>(p, grid, s);
 }
 
 }  // namespace lra

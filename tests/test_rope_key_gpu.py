@@ -47,15 +47,25 @@ def _cases():
                                               head_dim=64, rank=24, n=333, n_new=1, d_model=None, b_std=0.1), 10000.0, None
     yield "decode_paged", W.make_paged("rope_paged", seed=303, seq_lens=[5, 64, 700], agents_per_seq=2, n_adapters=3,
                                        n_q_heads=8, n_kv_heads=2, head_dim=128, rank=8, d_model=None, b_std=0.1), 500000.0, None
+    yield "decode_paged_batch", W.make_paged("rope_paged2", seed=307, seq_lens=[1, 63, 64, 65, 1000, 2500], agents_per_seq=4,
+                                             n_adapters=4, n_q_heads=28, n_kv_heads=4, head_dim=128, rank=32, d_model=None,
+                                             b_std=0.1), 500000.0, None
     yield "prefill", W.make_contiguous("rope_pre", "prefill", seed=304, n_agents=1, n_q_heads=8, n_kv_heads=2,
                                        head_dim=128, rank=16, n=400, n_new=150, d_model=None, b_std=0.1), 500000.0, None
     yield "decode_fp32", W.make_contiguous("rope_f32", "decode", seed=305, dtype=torch.float32, n_agents=2, n_q_heads=4,
                                            n_kv_heads=2, head_dim=64, rank=5, n=200, n_new=1, d_model=None, b_std=0.1), 10000.0, 1e-4
 
 
+@pytest.mark.parametrize("variant", [0, 1], ids=["mfma", "vector_alu"])
 @pytest.mark.parametrize("name,w,theta,tight", list(_cases()), ids=[c[0] for c in _cases()])
-def test_rotary_key_side(name, w, theta, tight):
-    got = _run(w, theta)
+def test_rotary_key_side(name, w, theta, tight, variant):
+    """bf16 decode runs on the tile-walking MFMA kernel, one column of workgroups per query (variant 0), or on
+    the vector-ALU kernels (variant 1, and fp32 always)."""
+    prev = lra.lra_set_kernel_variant(variant)
+    try:
+        got = _run(w, theta)
+    finally:
+        lra.lra_set_kernel_variant(prev)
     ref = _oracle(w, theta)
     rel, mx = errors(got, ref)
     plain = _oracle(w, 0.0)
