@@ -94,14 +94,15 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   pl.short_prefill = prefill && pl.mfma && !rope && tokens <= g_short_prefill.load() &&
                      static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
   if ((prefill && pl.mfma && !pl.short_prefill) || rope_decode) {
-    // Tile-walking kernel: one workgroup per (128-row q tile, q head) - per (query, q head) for
+    // Tile-walking kernel: one workgroup per (128-row q tile, q head) - per (query, kv head) for
     // the rotary decode.  When that is fewer than two workgroups per CU, the key tiles of
     // every q tile are divided among several workgroups (at least eight 64-key tiles each)
     // and the merge kernel finishes the job; otherwise it is one kernel without a workspace.
     pl.rows = tokens * sh->n_q_heads;
     pl.group_pad = pl.row_tiles = pl.row_groups = 1;
     pl.split_keys = c->max_seq_len;
-    const int64_t wgs = static_cast<int64_t>(rope_decode ? tokens : (tokens + 127) / 128) * sh->n_q_heads;
+    const int64_t wgs = rope_decode ? static_cast<int64_t>(tokens) * sh->n_kv_heads
+                                    : static_cast<int64_t>((tokens + 127) / 128) * sh->n_q_heads;
     int64_t ns = g_prefill_splits.load();
     if (ns <= 0) {  // automatic: two workgroups per CU, at least eight key tiles per share
       ns = (2 * kCUs + wgs - 1) / wgs;

@@ -39,10 +39,10 @@ namespace lra {
 // the K_base rows of the tile (8-byte read-modify-writes in bf16).  One more barrier per
 // tile; the score loop is the value-only one.
 // PERQ = true serves decode with the rotary key side on the same kernel: blockIdx.z is a query
-// of the decode call (sequence and adapter come from the call's device tables), treated as a
-// prefill of one new token that sees its whole sequence.  Only row 0 of the q tile is live, so
-// the matrix work is mostly idle, but the keys of a sequence are streamed and completed by the
-// same code, shared over gridDim.y workgroups and merged.
+// of the decode call (sequence and adapter come from the call's device tables) and blockIdx.x
+// a kv head, whose G q heads are rows 0 .. G-1 of the q tile; every row sees the whole
+// sequence.  The matrix work is mostly idle, but the keys of a sequence are streamed once per
+// (query, kv head) and completed by the same code, shared over gridDim.y workgroups and merged.
 template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false, bool PERQ = false>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   static_assert(!(ROPE_K && HAS_BK), "the rotary key side replaces the Qt term");
@@ -78,12 +78,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int Hq = p.n_q_heads, Hkv = p.n_kv_heads, G = p.group, r = p.rank;
 
   // workgroup -> (kv head, q head in group, q tile); consecutive ids go to consecutive XCDs
+  // (PERQ: blockIdx.x is the kv head; rows 0 .. G-1 of the tile are its q heads)
   const int lin = blockIdx.x;
   const int hk = lin % Hkv;
   const int rest = lin / Hkv;
   const int gq = rest % G;
   const int qt = rest / G;
-  const int head = hk * G + gq;
   // PERQ: the query this workgroup serves, its sequence (queries are grouped by sequence) and adapter
   const int zq = PERQ ? static_cast<int>(blockIdx.z) : 0;
   int t = p.seq_index;
@@ -99,9 +99,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   if (q0 >= n_new) return;
   const int base_vis = n_t - n_new;  // new token i sees keys 0 .. base_vis + i
   const int row = q0 + wave * 32 + l32;           // this lane's query row (new-token index)
-  const int row_c = min(row, n_new - 1);          // clamped for loads; rows past the end are never stored
-  const int grow = zq + row, grow_c = zq + row_c; // row of q, out and the workspace (PERQ: the query; else the new token)
-  const int limit = base_vis + row_c;             // last visible key of this lane's row
+  const int n_live = PERQ ? G : n_new;            // live rows of the tile: new tokens, or (PERQ) the q heads of the kv head
+  const int row_c = min(row, n_live - 1);         // clamped for loads; rows past the end are never stored
+  // token (PERQ: query) and q head of this lane's row: where its q, out and workspace rows are
+  const int grow = PERQ ? zq : row, grow_c = PERQ ? zq : row_c;
+  const int head = PERQ ? hk * G + row_c : hk * G + gq;
+  const int limit = base_vis + (PERQ ? 0 : row_c);  // last visible key of this lane's row
   const int wg_last = base_vis + min(q0 + BM, n_new) - 1;  // last key any row of the workgroup sees
   const int n_tiles = wg_last / BN + 1;
   // this workgroup's share of the q tile's key tiles: [tile_begin, tile_end)
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   if (SPLIT && tile_begin >= tile_end) {
     // more workgroups than key tiles: leave an empty state (zero row sum), all the merge
     // kernel looks at
-    if (row < n_new && g2 == 0) {
+    if (row < n_live && g2 == 0) {
       const int64_t slot = (static_cast<int64_t>(grow) * Hq + head) * p.n_splits + split;
       p.part_ml[slot * 2 + 0] = -INFINITY;
       p.part_ml[slot * 2 + 1] = 0.f;
@@ -477,7 +480,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   if (SPLIT) {
     // this share's state for the merge kernel: m in natural-log units, l, O^T and Olr^T as
     // fp32 rows [slot][d] and [slot][rank]; registers 4q..4q+3 are d (rho) = 32b + 8q + 4g2 + 0..3
-    if (row < n_new) {
+    if (row < n_live) {
       const int64_t slot = (static_cast<int64_t>(grow) * Hq + head) * p.n_splits + split;
       if (g2 == 0) {
         p.part_ml[slot * 2 + 0] = m_run * 0.69314718055994530942f;
@@ -528,7 +531,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       }
     }
   }
-  if (row < n_new) {
+  if (row < n_live) {
     const float inv = 1.0f / l_run;
     bf16_t* orow = static_cast<bf16_t*>(p.out) + (static_cast<int64_t>(grow) * Hq + head) * D;
 #pragma unroll
@@ -581,7 +584,7 @@ hipError_t launch_prefill_mfma(const Params& p, hipStream_t s) {
   return launch_pf<64, 64>(p, grid, s);
 }
 
-// Decode with the rotary key side: one workgroup per (q head, share of the keys, query).
+// Decode with the rotary key side: one workgroup per (kv head, share of the keys, query).
 template <int D, int RP>
 static hipError_t launch_rope_dec(const Params& p, dim3 grid, hipStream_t s) {
   const bool paged = p.block_size != 0;
@@ -596,7 +599,7 @@ static hipError_t launch_rope_dec(const Params& p, dim3 grid, hipStream_t s) {
 }
 
 hipError_t launch_decode_rope_mfma(const Params& p, hipStream_t s) {
-  dim3 grid(p.n_q_heads, p.n_splits, p.n_queries);
+  dim3 grid(p.n_kv_heads, p.n_splits, p.n_queries);
   const int rp = p.rank <= 16 ? 16 : (p.rank <= 32 ? 32 : 64);
   if (p.head_dim == 128) {
     if (rp == 16) return launch_rope_dec<128, 16>(p, grid, s);
