@@ -259,9 +259,10 @@ int32_t lra_set_append_skinny(int32_t tokens);
 int32_t lra_set_append_stages(int32_t stages);
 
 /*
- * Tuning and test hook: output tile of lra_cache_append's GEMM kernels, 128 (128 features x
- * 128 tokens per workgroup, the default) or 256 (256 x 256); anything else restores the
- * default.  Both handle any n_new.  Returns the previous value.
+ * Tuning and test hook: output tile of lra_cache_append's GEMM kernels: 64 (128 features x 64
+ * tokens per workgroup), 128 (128 x 128) or 256 (256 x 256); anything else restores the
+ * default (64 while 128-token tiles would occupy fewer than about 100 CUs, else 128).
+ * All handle any n_new.  Returns the previous value.
  */
 int32_t lra_set_append_tile(int32_t tile);
 

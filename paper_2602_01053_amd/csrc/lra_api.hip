@@ -392,7 +392,9 @@ int32_t lra_set_append_stages(int32_t stages) {
   return g_append_stages.exchange(stages < 2 || stages > 4 ? 0 : stages);
 }
 
-int32_t lra_set_append_tile(int32_t tile) { return g_append_tile.exchange(tile == 128 || tile == 256 ? tile : 0); }
+int32_t lra_set_append_tile(int32_t tile) {
+  return g_append_tile.exchange(tile == 64 || tile == 128 || tile == 256 ? tile : 0);
+}
 
 int32_t lra_set_append_skinny(int32_t tokens) { return g_append_skinny.exchange(tokens < 0 ? 0 : tokens); }
 

@@ -22,11 +22,15 @@
 
 namespace lra {
 
-template <int D, bool PAGED, int NS>
+// BT = 64 halves the token side of the tile (a wave then owns 64 features x 32 tokens): twice the
+// workgroups and three quarters of the bytes per step for chunks too small to fill the chip.
+template <int D, bool PAGED, int NS, int BT = 128>
 __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendParams p) {
-  constexpr int BF = 128, BT = 128, BK = 64;  // features, tokens, d_model step
-  constexpr int TILE_BYTES = BF * BK * 2;      // one operand tile: 128 rows of 128 bytes
-  constexpr int STAGE = 2 * TILE_BYTES;        // [W tile][X tile]
+  constexpr int BF = 128, BK = 64;  // features, d_model step (BT tokens)
+  constexpr bool ONE_TB = BT == 64;  // one 32-token block per wave
+  constexpr int REQ = ONE_TB ? 6 : 8;  // requests per step and wave
+  constexpr int TILE_BYTES = BF * BK * 2;      // the W tile: 128 rows of 128 bytes
+  constexpr int STAGE = TILE_BYTES + BT * BK * 2;  // [W tile][X tile]
   constexpr int HALF = D / 2;
 
   __shared__ __align__(16) unsigned char smem[NS * STAGE];
@@ -67,7 +71,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
     const int i = wave + 4 * (part >> 1);
     const uint32_t dst = lds0 + st * STAGE + i * 1024;
     if ((part & 1) == 0) pf_load16_to_lds(rs_w, dst, voff, static_cast<uint32_t>(w_row0 + 8 * i) * ldw2 + k0 * 2);
-    else pf_load16_to_lds(rs_x, dst + TILE_BYTES, voff, static_cast<uint32_t>(tok0 + 8 * i) * ldw2 + k0 * 2);
+    else if (8 * i < BT) pf_load16_to_lds(rs_x, dst + TILE_BYTES, voff, static_cast<uint32_t>(tok0 + 8 * i) * ldw2 + k0 * 2);
   };
   auto issue_step = [&](int k0, int st) __attribute__((always_inline)) {
 #pragma unroll
@@ -89,8 +93,10 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   const bool lr_tile = kind == 2;
   const int fb0 = lr_tile ? 0 : (D == 128 ? wr : 2 * wr);
   const int fb1 = lr_tile ? 1 : (D == 128 ? wr + 2 : 2 * wr + 1);
-  const int tb0 = lr_tile ? wave : 2 * wc;
-  const int tb1 = 2 * wc + 1;  // unused by the L tile
+  // (BT = 64: one token block per wave, wc or, in the L tile, wave % 2 with waves 2 and 3 repeating 0 and 1)
+  const int tb0 = ONE_TB ? (lr_tile ? (wave & 1) : wc) : (lr_tile ? wave : 2 * wc);
+  const int tb1 = 2 * wc + 1;  // unused by the L tile and with BT = 64
+  const bool stores = !(ONE_TB && lr_tile && wave >= 2);
 
   pf_f32x16 acc[2][2];  // [feature block fb0 / fb1][token block tb0 / tb1]
 #pragma unroll
@@ -113,7 +119,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
     constexpr int ST = decltype(st_c)::value;
     constexpr bool LR = decltype(lr_c)::value;
     constexpr int KS = BK / 16;
-    if (step + NS - 2 < n_steps) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (NS - 2)));
+    if (step + NS - 2 < n_steps) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(REQ * (NS - 2)));
     else pf_wait_vm0();
     __syncthreads();
     const bool more = step + NS - 1 < n_steps;
@@ -189,7 +195,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
       if (NS > 3 && step + 3 < n_steps) k_step(step + 3, std::integral_constant<int, 3 % NS>{}, lr_c);
     }
   };
-  if (lr_tile) k_loop(std::true_type{});
+  if (lr_tile || ONE_TB) k_loop(std::true_type{});  // one token block per wave
   else k_loop(std::false_type{});
 
   // ---------------- epilogue: rotate the keys, cast, store into the cache rows ----------------
@@ -198,7 +204,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   bf16_t* kcache = static_cast<bf16_t*>(kind == 0 ? p.k_base : p.v_base);
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
-    if (b == 1 && lr_tile) continue;
+    if ((b == 1 && (lr_tile || ONE_TB)) || !stores) continue;
     const int tok = tok0 + 32 * (b == 0 ? tb0 : tb1) + l32;
     const int j = pos0 + tok;  // cache row of this token, and its position
     if (tok >= n_new || j < 0) continue;  // (a sequence length below n_new breaks the contract: nothing is written)
@@ -781,6 +787,19 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s) {
   // stages (more requests in flight per workgroup) is free; beyond that two workgroups per
   // unit with two stages each hide each other's waits.
   const int stages = p.stages != 0 ? p.stages : (static_cast<int>(grid.x * grid.y) <= 256 ? 4 : 2);
+  // half-size token tiles while even those leave CUs idle, or when asked for (Llama-3-8B projection:
+  // 22-24 us against 33-34 us up to 512 new tokens, level at 1024)
+  if (p.tile == 64 || (p.tile == 0 && p.stages == 0 && static_cast<int>(grid.x * grid.y) <= 100)) {
+    dim3 g64((p.n_new + 63) / 64, grid.y);
+    if (p.head_dim == 128) {
+      if (paged) hipLaunchKernelGGL((append_kernel<128, true, 4, 64>), g64, dim3(256), 0, s, p);
+      else hipLaunchKernelGGL((append_kernel<128, false, 4, 64>), g64, dim3(256), 0, s, p);
+    } else {
+      if (paged) hipLaunchKernelGGL((append_kernel<64, true, 4, 64>), g64, dim3(256), 0, s, p);
+      else hipLaunchKernelGGL((append_kernel<64, false, 4, 64>), g64, dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+  }
 #define LRA_APPEND_LAUNCH(DD, PG, NS_) hipLaunchKernelGGL((append_kernel<DD, PG, NS_>), grid, dim3(256), 0, s, p)
 #define LRA_APPEND_STAGES(DD, PG)            \
   do {                                       \

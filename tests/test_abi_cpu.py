@@ -168,7 +168,8 @@ def test_tuning_hooks_round_trip(lib):
     old = lra.lra_set_append_skinny(7)
     assert lra.lra_set_append_skinny(old) == 7 and old == 64
     assert lra.lra_set_append_stages(3) == 0 and lra.lra_set_append_stages(9) == 3 and lra.lra_set_append_stages(0) == 0
-    assert lra.lra_set_append_tile(256) == 0 and lra.lra_set_append_tile(100) == 256 and lra.lra_set_append_tile(0) == 0
+    assert lra.lra_set_append_tile(256) == 0 and lra.lra_set_append_tile(64) == 256 and lra.lra_set_append_tile(100) == 64
+    assert lra.lra_set_append_tile(0) == 0
     old = lra.lra_set_decode_split_keys(512)
     assert lra.lra_set_decode_split_keys(old) == 512
     old = lra.lra_set_kernel_variant(1)

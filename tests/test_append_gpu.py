@@ -81,10 +81,11 @@ def test_append_tiled_stage_counts(case, stages):
                                   (66000, 515, 1024, 8, 128, 64, 500000.0), (520, 520, 512, 1, 64, 8, 10000.0),
                                   (1000, 257, 4096, 8, 128, 16, 0.0)],
                          ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
-def test_append_wide_tile(case):
-    """The 256 x 256 tile kernel, forced: ragged token tiles, feature regions of 64, 192 and 1024
+@pytest.mark.parametrize("tile", [64, 128, 256])
+def test_append_tile_sizes(case, tile):
+    """Every tile size of the GEMM kernels, forced: ragged token tiles, feature regions of 64, 192 and 1024
     (a tile that is partly filled, one that straddles the K and V rows of w), rank 8 to 64."""
-    prev_t, prev_k = lra.lra_set_append_tile(256), lra.lra_set_append_skinny(0)
+    prev_t, prev_k = lra.lra_set_append_tile(tile), lra.lra_set_append_skinny(0)
     try:
         test_append_contiguous(case)
     finally:
@@ -116,7 +117,7 @@ def test_append_contiguous(case):
         assert bool((t[:n - n_new] == SENTINEL).all())
 
 
-@pytest.mark.parametrize("skinny,tile", [(0, 128), (0, 256), (1 << 30, 0)], ids=["tiled", "wide", "streamed"])
+@pytest.mark.parametrize("skinny,tile", [(0, 64), (0, 128), (0, 256), (1 << 30, 0)], ids=["tile64", "tiled", "wide", "streamed"])
 def test_append_paged_then_attend(skinny, tile):
     prev, prev_t = lra.lra_set_append_skinny(skinny), lra.lra_set_append_tile(tile)
     try:
