@@ -190,10 +190,26 @@ def bench_rotary_prefill(args, torch, lra, workloads):
     steps = max(3, min(args.steps // 10, 100))
     ksec = kernel_seconds(lra, torch, lambda i: dw.prefill(), steps)
     tf = w.algorithmic_flops() / ksec / 1e12
-    return {"workload": w.name + " with key_rope_theta = 500000", "call": "lra_attn_prefill", "kernel_ms": round(ksec * 1e3, 4),
-            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                         "note": "flops of the plain call; the completion of the key tiles in LDS is overhead"}}
+    out = {"workload": w.name + " with key_rope_theta = 500000", "call": "lra_attn_prefill", "kernel_ms": round(ksec * 1e3, 4),
+           "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                        "note": "flops of the plain call; the completion of the key tiles in LDS is overhead"}}
+    # the decode workload with the rotary key side: tile-walking kernel per (query, kv head) + merge
+    w2 = workloads.config(2)
+    dw2 = DeviceWorkload(w2, torch.device("cuda:0"), key_rope_theta=500000.0)
+    dw2.alloc_workspace()
+    for _ in range(5):
+        dw2.decode()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(200):
+        dw2.decode()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / 200
+    out["decode"] = {"workload": w2.name + " with key_rope_theta = 500000", "call": "lra_attn_decode",
+                     "us_per_call": round(sec * 1e6, 2), "GBps_of_the_plain_call's_bytes": round(w2.algorithmic_bytes() / sec / 1e9, 1),
+                     "note": "same buffers every call (hot); keys are streamed once per query and kv head"}
+    return out
 
 
 def bench_append(args, torch, lra, with_cpu, sizes=(16384, 2048, 1)):

@@ -38,7 +38,7 @@ namespace lra {
 // pairs, so both halves of a pair sit in the same lane and register), rotated, and added to
 // the K_base rows of the tile (8-byte read-modify-writes in bf16).  One more barrier per
 // tile; the score loop is the value-only one.
-// PERQ = true serves decode with the rotary key side on the same kernel: blockIdx.z is a query
+// PERQ = true serves decode with the rotary key side on the same kernel: blockIdx.y is a query
 // of the decode call (sequence and adapter come from the call's device tables) and blockIdx.x
 // a kv head, whose G q heads are rows 0 .. G-1 of the q tile; every row sees the whole
 // sequence.  The matrix work is mostly idle, but the keys of a sequence are streamed once per
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int gq = rest % G;
   const int qt = rest / G;
   // PERQ: the query this workgroup serves, its sequence (queries are grouped by sequence) and adapter
-  const int zq = PERQ ? static_cast<int>(blockIdx.z) : 0;
+  const int zq = PERQ ? static_cast<int>(blockIdx.y) : 0;
   int t = p.seq_index;
   int a_idx = p.adapter_index;
   if (PERQ) {
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int wg_last = base_vis + min(q0 + BM, n_new) - 1;  // last key any row of the workgroup sees
   const int n_tiles = wg_last / BN + 1;
   // this workgroup's share of the q tile's key tiles: [tile_begin, tile_end)
-  const int split = SPLIT ? blockIdx.y : 0;
+  const int split = SPLIT ? (PERQ ? blockIdx.z : blockIdx.y) : 0;
   const int tile_begin = SPLIT ? static_cast<int>(static_cast<int64_t>(n_tiles) * split / p.n_splits) : 0;
   const int tile_end = SPLIT ? static_cast<int>(static_cast<int64_t>(n_tiles) * (split + 1) / p.n_splits) : n_tiles;
   if (SPLIT && tile_begin >= tile_end) {
@@ -341,6 +341,9 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       }
     }
 
+    // (PERQ: the live rows, the q heads of one kv head, all sit in wave 0; the other waves only
+    // move and complete tiles)
+    if (!PERQ || wave == 0) {
     // S^T for the two 32-key halves of the tile.  The halves alternate, so consecutive
     // matrix instructions never wait for each other's result, and the LDS reads run
     // kReadAheadS operands ahead of the products that consume them.
@@ -458,6 +461,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     for (int i = 0; i < 4 * (DB + RB); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
     }
     // the next tile has landed (this wave's share) and everybody is done reading this one
     pf_wait_vm0();
@@ -599,7 +603,10 @@ static hipError_t launch_rope_dec(const Params& p, dim3 grid, hipStream_t s) {
 }
 
 hipError_t launch_decode_rope_mfma(const Params& p, hipStream_t s) {
-  dim3 grid(p.n_kv_heads, p.n_splits, p.n_queries);
+  // kv head fastest, then the query, then the share of the keys: the workgroups that stream the
+  // same keys for different agents are dispatched together and, with 8 kv heads, to the same XCD,
+  // so all but the first find the tiles in its L2
+  dim3 grid(p.n_kv_heads, p.n_queries, p.n_splits);
   const int rp = p.rank <= 16 ? 16 : (p.rank <= 32 ? 32 : 64);
   if (p.head_dim == 128) {
     if (rp == 16) return launch_rope_dec<128, 16>(p, grid, s);
