@@ -266,6 +266,7 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
   if (pl.rope_decode) {
+    if (n_queries > 65535) return LRA_ERR_UNSUPPORTED;  // one grid row per query
     if (launch_decode_rope_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
     if (pl.n_splits > 1 && g_profile_mode.load() != 1 && launch_merge(p, bf16, pl.rows, s) != hipSuccess)
       return LRA_ERR_HIP;
