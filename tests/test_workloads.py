@@ -78,3 +78,20 @@ def test_agent_trace_matches_the_papers_table_and_totals():
     for l_ctx, thousands in totals.items():
         total = sum((l_ctx if p is None else p) + g for _, p, g in bench_trace.TRACE)
         assert round(total / 1000, 1) == thousands
+
+
+def test_flop_accounting_follows_the_papers_cost_model():
+    """App. B "Compute Overhead": with reordering the low-rank part costs L_c L r + L_c r d_head
+    multiply-adds per head (accumulate P V_lr in rank r, apply B once); without it
+    L r d_head + L_c L d_head.  algorithmic_flops() is the base attention (2 L_c L d_head
+    multiply-adds, which the paper omits) plus the reordered count, taken once for the value
+    side and once for the key side (App. D.1 applies the same decomposition there), two flops
+    per multiply-add - checked on a decode workload, where every row sees all L keys."""
+    w = W.config(2, shrink=16)
+    rows = w.n_queries * w.n_q_heads          # L_c = 1 per (query, head)
+    big_l, d, r = w.seq_lens[0], w.head_dim, w.rank
+    base = 2 * rows * big_l * d
+    reordered = rows * big_l * r + rows * r * d
+    assert w.algorithmic_flops() == 2 * (base + 2 * reordered)
+    not_reordered = big_l * r * d + rows * big_l * d      # per head and agent in the paper; rows already counts both
+    assert reordered < not_reordered                       # r << d_head: the point of the reordering
