@@ -177,3 +177,21 @@ def test_rotary_key_side_prefill_with_shared_key_tiles():
         rel, mx = errors(got, ref)
         print(f"splits {splits}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
         assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
+def test_rotary_decode_with_more_key_shares_than_tiles():
+    """Rotary decode on a ragged paged batch with the key tiles of every query forced onto 32 workgroups:
+    sequences of 1 to 65 tokens leave most shares empty, and every share, empty or not, must leave
+    what the merge kernel reads."""
+    w = W.make_paged("rope_paged3", seed=308, seq_lens=[1, 63, 64, 65, 1000, 2500], agents_per_seq=3, n_adapters=3,
+                     n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, d_model=None, b_std=0.1)
+    ref = _oracle(w, 500000.0)
+    for splits in (32, 3):
+        prev = lra.lra_set_prefill_splits(splits)
+        try:
+            got = _run(w, 500000.0)
+        finally:
+            lra.lra_set_prefill_splits(prev)
+        rel, mx = errors(got, ref)
+        print(f"splits {splits}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+        assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
