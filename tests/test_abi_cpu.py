@@ -181,3 +181,22 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(lra.binding, "LIB_PATH", "/nonexistent/liblra_attn.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         lra.binding.load_library()
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own, with warnings as errors."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "lra_attn.h"\n'
+        "lra_status call(const lra_shape* s, const lra_cache* c, const lra_projection* p, const void* x) {\n"
+        "  return lra_cache_append(s, c, p, x, 0, 1, (void*)0);\n"
+        "}\n"
+        "size_t need(const lra_shape* s, const lra_cache* c) { return lra_workspace_bytes(s, c, 4, 4, 0); }\n")
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                          "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
