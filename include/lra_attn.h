@@ -261,7 +261,8 @@ int32_t lra_set_append_stages(int32_t stages);
 /*
  * Tuning and test hook: output tile of lra_cache_append's GEMM kernels: 64 (128 features x 64
  * tokens per workgroup), 128 (128 x 128) or 256 (256 x 256); anything else restores the
- * default (64 while 128-token tiles would occupy fewer than about 100 CUs, else 128).
+ * default (64 while 128-token tiles would occupy fewer than about 100 CUs; 256 when such tiles
+ * fill whole rounds of the chip, e.g. 16384 new tokens at the Llama-3-8B shape; else 128).
  * All handle any n_new.  Returns the previous value.
  */
 int32_t lra_set_append_tile(int32_t tile);

@@ -43,8 +43,10 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   const int wr = wave >> 1, wc = wave & 1;  // position in the 2 x 2 grid of waves: features, tokens
   const int HD = p.n_kv_heads * D;
   const int n_ct_kv = (HD + BF - 1) / BF;   // feature tiles of the K (and of the V) region
-  const int ct = blockIdx.y;
-  const int kind = ct < n_ct_kv ? 0 : (ct < 2 * n_ct_kv ? 1 : 2);  // 0 K, 1 V, 2 L
+  // The L tiles (little matrix work) come first in the grid, so they run beside the first full
+  // tiles instead of as a round of their own at the end.
+  const int ct = static_cast<int>(blockIdx.y) - 1;
+  const int kind = ct < 0 ? 2 : (ct < n_ct_kv ? 0 : 1);  // 0 K, 1 V, 2 L
   const int ct_in = kind == 0 ? ct : (kind == 1 ? ct - n_ct_kv : 0);
   const int feat0 = ct_in * BF;                                 // first feature of the tile inside its region
   const int w_row0 = (kind == 0 ? 0 : (kind == 1 ? HD : 2 * HD)) + feat0;  // its row of w
@@ -257,16 +259,16 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
 }
 
 // ---------------------------------------------------------------------------------------
-// 256 features x 256 tokens per workgroup (selected by lra_set_append_tile(256) only).  At
+// 256 features x 256 tokens per workgroup (for chunks whose tiles fill whole rounds of the chip).  At
 // 128 x 128 a step moves 32 KB into LDS for 2.1 MFLOP and every MFMA costs one 1 KB LDS read:
 // with two workgroups per compute unit the LDS is busier than the matrix pipes.  Here a wave
 // owns 128 x 128 of the output (sixteen 32 x 32 accumulators, kept in the accumulation
 // registers), reads eight operands for sixteen MFMAs, and a step moves 64 KB for 8.4 MFLOP.
 // Same LDS layout, DMA and epilogue as append_kernel; two stages of 64 KB, one workgroup per
 // compute unit.  The wave's four feature blocks are one head (d = 128: pairs (0,2), (1,3)) or
-// two (d = 64: pairs (0,1), (2,3)).  Measured: 1.45 us per step against 0.9 us of MFMA work,
-// level with append_kernel at 16384 tokens and behind it at 8192 (the grid of 256-wide tiles
-// quantises worse), so it is not the default.
+// two (d = 64: pairs (0,1), (2,3)).  Measured: about 1.45 us per step against 0.9 us of MFMA
+// work; ahead of append_kernel when its tiles fill whole rounds of the chip (16384 tokens:
+// 277 us against 302 us), behind it otherwise (the grid of 256-wide tiles quantises worse).
 // ---------------------------------------------------------------------------------------
 template <int D, bool PAGED>
 __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
@@ -283,8 +285,10 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
   const int wr = wave >> 1, wc = wave & 1;
   const int HD = p.n_kv_heads * D;
   const int n_ct_kv = (HD + BF - 1) / BF;
-  const int ct = blockIdx.y;
-  const int kind = ct < n_ct_kv ? 0 : (ct < 2 * n_ct_kv ? 1 : 2);  // 0 K, 1 V, 2 L
+  // The L tiles (little matrix work) come first in the grid, so they run beside the first full
+  // tiles instead of as a round of their own at the end.
+  const int ct = static_cast<int>(blockIdx.y) - 1;
+  const int kind = ct < 0 ? 2 : (ct < n_ct_kv ? 0 : 1);  // 0 K, 1 V, 2 L
   const int ct_in = kind == 0 ? ct : (kind == 1 ? ct - n_ct_kv : 0);
   const int feat0 = ct_in * BF;
   const int w_row0 = (kind == 0 ? 0 : (kind == 1 ? HD : 2 * HD)) + feat0;
@@ -769,9 +773,14 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s) {
     return hipGetLastError();
   }
   const bool paged = p.block_size != 0;
-  if (p.tile == 256) {
-    // 256 x 256 tiles: measured equal to the 128 x 128 kernel at 16384 new tokens and slower below
-    // (Llama-3-8B projection), so only on request
+  // 256 x 256 tiles, one workgroup per CU: on request, or when their full tiles fill whole rounds of
+  // the chip's 256 CUs (at most a tenth of the last round idle) and there are at least two rounds.
+  // Measured on the Llama-3-8B projection: 277 us against 302 us at 16384 new tokens (512 tiles, two
+  // rounds), but 165 against 158 at 8192 and worse wherever a round stays half empty.
+  const int wide_full = ((p.n_new + 255) / 256) * 2 * (hd / 256);
+  const int wide_rounds = (wide_full + 255) / 256;
+  const bool wide_fits = wide_full >= 448 && wide_rounds * 256 * 10 <= wide_full * 11;
+  if (p.tile == 256 || (p.tile == 0 && p.stages == 0 && wide_fits)) {
     dim3 wgrid((p.n_new + 255) / 256, 2 * ((hd + 255) / 256) + 1);
     if (p.head_dim == 128) {
       if (paged) hipLaunchKernelGGL((append_wide_kernel<128, true>), wgrid, dim3(256), 0, s, p);
