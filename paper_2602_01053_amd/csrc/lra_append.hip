@@ -6,18 +6,23 @@
 // rotates the keys by the model's rotary position embedding (the cached keys are the rotated
 // ones, App. D.1) and writes the rows into K_base, V_base and L, contiguous or paged.
 //
-// One MFMA GEMM with the weights stored one output feature per row (the usual layout of a
-// linear layer), computed transposed, Y^T[feature][token] = W[feature][:] . X[token][:], so
+// Four kernels, chosen by the number of new tokens (launch_append at the end of the file): a
+// matrix-vector kernel (1-4 tokens), a weight-streaming MFMA kernel (up to 64), and two tiled
+// GEMM kernels (128 features x 128 or 64 tokens per workgroup; 256 x 256 for chunks whose tiles
+// fill whole rounds of the chip).
+//
+// The tiled GEMM takes the weights one output feature per row (the usual layout of a linear
+// layer) and computes transposed, Y^T[feature][token] = W[feature][:] . X[token][:], so
 // that both operands are rows of 16-byte chunks along d_model (ds_read_b128, no transposed
 // reads) and every lane ends up with four consecutive features of one token: an 8-byte
-// store into a cache row.  A workgroup owns 128 features x 128 tokens and walks d_model in
-// steps of 64; the W and X tiles go from HBM straight into a double-buffered LDS stage
-// (buffer_load ... lds, swizzled by choosing which chunk a lane fetches).  The four waves
-// form a 2 x 2 grid; a wave's two 32-feature blocks are chosen d/2 apart, so the two halves
-// of every rotary pair sit in the same lane and register of its two accumulators and the
-// rotation needs no data movement.  The rotation rate of every pair is tabulated once per
-// workgroup in double precision (revolutions per position); angle = fractional part of
-// position * rate, so positions in the tens of thousands lose nothing.
+// store into a cache row.  A workgroup walks d_model in steps of 64; the W and X tiles go
+// from HBM straight into a ring of 2 to 4 LDS stages (buffer_load ... lds, swizzled by
+// choosing which chunk a lane fetches).  The four waves form a 2 x 2 grid; a wave's two
+// 32-feature blocks are chosen d/2 apart, so the two halves of every rotary pair sit in the
+// same lane and register of its two accumulators and the rotation needs no data movement.
+// The rotation rate of every pair is tabulated once per workgroup in double precision
+// (revolutions per position); angle = fractional part of position * rate, so positions in
+// the tens of thousands lose nothing.
 #include "lra_prefill_util.h"
 
 namespace lra {
