@@ -74,7 +74,7 @@ typedef struct {
   int32_t head_dim;   /* d = d_head of Alg. 1 */
   int32_t rank;       /* r, columns of the LR cache and rows of every B */
   int32_t dtype;      /* lra_dtype */
-  float scale;        /* softmax scale; 0.0f selects 1/sqrt(head_dim) (Alg. 1 line 10).
+  float scale;        /* softmax scale; 0.0f selects 1/sqrt(head_dim) (the score step of Alg. 1).
                          The rank never enters the scale. */
   float key_rope_theta; /* 0: the key-side adapter is added as it is, K = K_base + L B_K, and
                          the scores are reordered (App. D.1 without a rotation).
@@ -182,7 +182,7 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache,
  * Causal prefill of one agent (Alg. 1 as printed: L_c = n_new query tokens after
  * L_p cached ones).  The n_new query tokens are the LAST n_new tokens of sequence
  * seq_index, whose cache rows are already in place; new token i sees keys
- * 0 .. n_t - n_new + i ("Mask" of Alg. 1 line 10, aligned to the end).
+ * 0 .. n_t - n_new + i ("Mask" in the score step of Alg. 1, aligned to the end).
  *
  *   q    DEVICE [n_new][Hq][d]        out  DEVICE [n_new][Hq][d]
  *   seq_index in [0, n_seqs), adapter_index in [0, n_adapters)

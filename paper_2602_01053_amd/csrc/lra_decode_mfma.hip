@@ -6,7 +6,7 @@
 // v_mfma_f32_16x16x32_bf16, so K_base, V_base and L are read from HBM once for
 // all agents (LRAgent Sec. 3.2: one base cache and one LR cache for the system).
 //
-// Per 32-key step (Alg. 1 lines 9-17 with the App. D.1 key-side reordering):
+// Per 32-key step (the inner loop of Alg. 1 with the App. D.1 key-side reordering):
 //   S^T[key][row]  = K_base[key][:] . Q[row][:]  +  L[key][:] . Qt[row][:]     (MFMA)
 //   online softmax along keys (per row = per lane column)
 //   O^T[d][row]   += V_base^T[d][key] . P^T[key][row]                          (MFMA)
@@ -145,7 +145,7 @@ constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel build
 // adapter lookup on the key side, no L term in the scores; L is still streamed for P.L.
 // CAUSAL = true serves lra_attn_prefill with a handful of new tokens: the new tokens of the
 // one sequence take the place of the agents (same adapter for all), and row i only sees the
-// keys up to n - n_new + i (Alg. 1 line 10); a long context is then split over the whole chip
+// keys up to n - n_new + i (the mask of Alg. 1); a long context is then split over the whole chip
 // like any decode call instead of being walked by one workgroup per q head.
 template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {

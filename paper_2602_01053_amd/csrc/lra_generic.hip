@@ -6,7 +6,7 @@
 // keys, with the key-side reordering of App. D.1:
 //     s_j  = scale * ( q . K_base[j] + (q B_K^T) . L[j] )
 //     m, l = online softmax statistics,  O += p_j V_base[j],  O_lr += p_j L[j]
-// The epilogue O += O_lr B_V and the division by l (Alg. 1 lines 19-20) happen in
+// The epilogue O += O_lr B_V and the division by l (the last two steps of Alg. 1) happen in
 // the merge kernel, after the per-split states are combined.
 #include "lra_common.h"
 
