@@ -129,7 +129,8 @@ typedef struct {
 } lra_cache;
 
 /*
- * Per-agent adapter table (Sec. 3.2: "agent-specific outputs via their B_i").
+ * Per-agent adapter table (Sec. 3.2: every agent turns the shared caches into its own
+ * keys and values through its own up-projection B_i).
  * b_k / b_v: DEVICE [n_adapters][rank][Hkv*head_dim], row-major; kv head h owns
  * columns h*d .. (h+1)*d-1 (Eq. 1: B is r x d_out).  Any LoRA scaling alpha/r is
  * folded into B by the caller.  b_k == NULL means B_K = 0 for every adapter (the
