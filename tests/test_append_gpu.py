@@ -51,6 +51,8 @@ SMALL = [
     (65000, 33, 1024, 4, 128, 16, 500000.0),
     (64, 64, 768, 3, 64, 64, 10000.0),
     (300, 150, 512, 2, 128, 16, 500000.0),     # beyond the default limit: runs streamed only when the limit is raised
+    (20, 3, 128, 2, 64, 8, 0.0),               # unrotated keys on the matrix-vector kernel
+    (40, 12, 256, 2, 128, 16, 0.0),            # and on the weight-streaming one
 ]
 
 
