@@ -106,6 +106,12 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     int64_t ns = g_prefill_splits.load();
     if (ns <= 0) {  // automatic: two workgroups per CU, at least eight key tiles per share
       ns = (2 * kCUs + wgs - 1) / wgs;
+      // a batch of sequences of very different lengths (rotary decode) is only as fast as the
+      // shares of its longest one: at most 32 key tiles per share
+      if (rope_decode && c->n_seqs > 1) {
+        const int64_t by_len = (c->max_seq_len + 64 * 32 - 1) / (64 * 32);
+        ns = ns > by_len ? ns : by_len;
+      }
       const int64_t max_ns = c->max_seq_len / (8 * 64);
       ns = ns > max_ns ? max_ns : ns;
     }
