@@ -75,7 +75,8 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   // agent needs its own completed tiles).  The split-KV decode kernel has no rotary path.
   const bool rope = sh->key_rope_theta > 0.f;
   pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
-  bool rope_decode = rope && !prefill && pl.mfma;
+  const bool rope_split = rope && !prefill && pl.mfma;  // rotary form of the split-KV decode kernel
+  bool rope_decode = false;
   if ((prefill || rope_decode) && pl.mfma) {
     // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
@@ -84,8 +85,6 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     if (l_rows * sh->rank * 2 > lim) pl.mfma = false;
     if (c->block_size == 0 && static_cast<int64_t>(c->max_seq_len) * c->kv_token_stride * 2 > lim) pl.mfma = false;
   }
-  rope_decode = rope_decode && pl.mfma;
-  if (rope && !prefill && !rope_decode) pl.mfma = false;
   pl.rope_decode = rope_decode;
   // A handful of new tokens after a long context gives the tile-walking prefill kernel one
   // workgroup per q head and nothing to split; the split-KV decode kernel, with the new
@@ -138,8 +137,16 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   const int n_seqs_eff = prefill ? 1 : c->n_seqs;
   if (pl.short_prefill) max_queries_per_seq = tokens;
   if (pl.mfma) {
-    const int rows_needed = max_queries_per_seq * pl.group_pad;
+    int rows_needed = max_queries_per_seq * pl.group_pad;
     pl.row_tiles = decode_mfma_row_tiles(rows_needed);
+    if (rope_split) {
+      // one row tile per workgroup, and no more agent slots in it than the kernel keeps B_K^T
+      // operands for
+      const int min_pad = 16 / decode_mfma_rope_slots(sh->rank);
+      pl.group_pad = pl.group_pad > min_pad ? pl.group_pad : min_pad;
+      pl.row_tiles = 1;
+      rows_needed = max_queries_per_seq * pl.group_pad;
+    }
     pl.row_groups = (rows_needed + 16 * pl.row_tiles - 1) / (16 * pl.row_tiles);
     tile = 128;        // 4 waves x 32 keys
     work = static_cast<int64_t>(n_seqs_eff) * sh->n_kv_heads * pl.row_groups;

@@ -29,6 +29,7 @@
 // the end (flash-decoding rule) and one partial (m, l, O, O_lr) per workgroup
 // goes to the workspace.
 #include "lra_common.h"
+#include "lra_prefill_util.h"
 
 namespace lra {
 
@@ -147,9 +148,23 @@ constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel build
 // one sequence take the place of the agents (same adapter for all), and row i only sees the
 // keys up to n - n_new + i (the mask of Alg. 1); a long context is then split over the whole chip
 // like any decode call instead of being walked by one workgroup per q head.
-template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL>
+//
+// RPE > 0 is the rotary key side, K_j = K_base,j + RoPE_j(L_j B_K) (what App. D.1 leaves to the
+// key cache because the rotation stands between L_j and B_K): the L.Qt term of the scores is
+// replaced, per 16-key tile and agent slot, by
+//   E^T[f][key]   = B_K^T[f][:] . L^T[:][key]                 (MFMA, C layout: lane = key)
+//   rotate the pairs (f, f + D/2) of E^T by the key's angle   (registers, sine/cosine shared by the slots)
+//   S^T[key][row] += rot(E)[key][f] . Q[row][f]                (MFMA; the C layout of E^T is the
+//                                                              A layout of this product)
+// with Q masked to the rows of the slot.  The B_K^T operands of NS agent slots stay in
+// registers (RPE = padded rank of that product: 16, 32 or 64, for 4, 2 or 1 slots per tile).
+template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL, int RPE = 0>
 __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   constexpr int NW = 4;
+  constexpr bool ROPE = RPE > 0;
+  constexpr int NS = !ROPE ? 1 : (RPE == 16 ? 4 : (RPE == 32 ? 2 : 1));  // agent slots with operands in registers
+  constexpr int EK = RPE == 64 ? 2 : 1;                                    // 32-wide k-steps of the E product
+  static_assert(!ROPE || (RT == 1 && HAS_BK && !CAUSAL && (RPE == 64) == (RP == 64)), "rotary form: one row tile, decode");
   constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
   constexpr int RKS = RP / 32;     // MFMA k-steps over the (padded) rank
   constexpr int DB = D / 16;       // 16-wide output blocks over d
@@ -174,12 +189,14 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   // Two workgroups per CU need 2 * LDS <= 160 KB.  Where the tile regions alone
   // leave no room, the Qt exchange area and the per-wave maxima live inside the
   // tile regions and the first tile is requested only after the prologue.
-  constexpr bool ALIAS = 2 * (SMEM + QT_BYTES + M_BYTES) > 160 * 1024;
+  constexpr int ROPE_FLOATS = ROPE ? NW * 128 : 4;  // per wave: 64 rates, 64 phases of the current step
+  constexpr bool ALIAS = 2 * (SMEM + QT_BYTES + M_BYTES + (ROPE ? ROPE_FLOATS * 4 : 0)) > 160 * 1024;
   constexpr int EXTRA = ALIAS ? 16 : QT_BYTES + M_BYTES;
   static_assert(QT_BYTES <= WAVE_BYTES && RT * 64 <= WAVE_BYTES, "aliased areas must fit one wave's region");
 
   __shared__ __align__(16) unsigned char smem[SMEM];
   __shared__ __align__(16) unsigned char extra_lds[EXTRA];
+  __shared__ __align__(16) float rope_tab[ROPE_FLOATS];
   unsigned char* qt_lds = ALIAS ? smem : extra_lds;
 
   const int lane = threadIdx.x & 63;
@@ -390,12 +407,15 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   };
 
   // The first tile is on its way before the prologue touches Q and B_K.
-  if ((!ALIAS || !HAS_BK) && jw0 < jw1) issue_tile(jw0);
+  if (!ROPE && (!ALIAS || !HAS_BK) && jw0 < jw1) issue_tile(jw0);
 
   // ===================== prologue: Q operands and Qt = Q B_K^T =====================
   // qb[rt][ks]: lane (row ln of tile rt, k = 32ks + 8lg + e), e = 0..7.  Used as the
   // B operand of S^T and as the B operand of Qt^T = B_K Q^T below.
   bf16x8 qb[RT][KS];
+  // rotary form: the same rows once more in the order the rotated E^T blocks come out of
+  // their product: qp[fb] = Q[row ln][16fb + 4lg + 0..3]
+  s16x4 qp[ROPE ? DB : 1];
   {
     const __amdgpu_buffer_rsrc_t rs_q =
         make_rsrc(static_cast<const bf16_t*>(p.q) + static_cast<int64_t>(q_begin) * p.n_q_heads * D,
@@ -408,6 +428,12 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
       const uint32_t off = valid ? static_cast<uint32_t>((slot * p.n_q_heads + h * G + gg) * D * 2 + lg * 16) : kOob;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) qb[rt][ks] = as_bf16x8(buf_load16(rs_q, off, ks * 64));
+      if constexpr (ROPE) {
+        const uint32_t offp = valid ? off - lg * 8 : kOob;
+#pragma unroll
+        for (int fb = 0; fb < DB; ++fb)
+          qp[fb] = __builtin_bit_cast(s16x4, __builtin_amdgcn_raw_buffer_load_b64(rs_q, offp, fb * 32, 0));
+      }
     }
   }
   // Qt^T block (rho block cb, tile rt) = B_K^a[16cb..16cb+15][:] . Q_tile^T : C layout
@@ -417,7 +443,57 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   // lane l is the 16 bytes at ((rt*RKS + ks')*64 + l)*16, elements
   // e -> rho = 32ks' + 16(e/4) + 4lg + e%4.  The L operand below uses the same order.
   bf16x8 qtb[RT][RKS];
-  if (HAS_BK) {
+  // ===================== rotary form: B_K^T operands and rotation rates =====================
+  using e_op = typename std::conditional<RPE == 16, s16x4, bf16x8>::type;
+  e_op bkt[NS][ROPE ? DB : 1][EK];
+  float* rope_w = rope_tab + (ROPE ? wave * 128 : 0);
+  double rate_d = 0.0;
+  if constexpr (ROPE) {
+    // The slices B_K[a][:, h*D .. h*D+D) of the tile's agents go through this wave's K and V
+    // regions in the layout of a V tile (rows = rank index) and come back transposed, which is
+    // the A operand of E^T.  Rows beyond the rank, and the slices of empty slots, are outside
+    // the resource and arrive as zeros.
+    const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
+    const uint32_t ldb2 = static_cast<uint32_t>(ldb) * 2u;
+    constexpr int SLOT_BYTES = RPE * D * 2;
+    static_assert(NS * SLOT_BYTES <= 2 * KV_BYTES, "the slices must fit the K and V regions");
+    uint32_t bk_voff[VPER];
+    {
+      const int rr = lane / KCH, pc = lane % KCH;
+#pragma unroll
+      for (int q = 0; q < VPER; ++q) bk_voff[q] = static_cast<uint32_t>(rr) * ldb2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
+    }
+    const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
+#pragma unroll
+    for (int si = 0; si < NS; ++si) {
+      const int a = min(a_slot[0][si], p.n_adapters - 1);
+      const uint32_t bytes = a >= 0 ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u;
+      const u32x4 rs_b = make_rsrc_words(bkg + static_cast<int64_t>(a >= 0 ? a : 0) * r * ldb + h * D, bytes);
+#pragma unroll
+      for (int i = 0; i < RPE / KROWS; ++i)
+        buf_load16_to_lds(rs_b, ks_lds + si * SLOT_BYTES + i * 1024, bk_voff[i % VPER], i * KROWS * ldb2);
+    }
+    rate_d = rope_rate_rev(lane & (D / 2 - 1), D, p.key_rope_theta);
+    rope_w[lane] = static_cast<float>(rate_d);
+    wait_vm0();
+    lds_fence();
+#pragma unroll
+    for (int si = 0; si < NS; ++si)
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int ek = 0; ek < EK; ++ek) {
+          const unsigned char* src = ks_lds + si * SLOT_BYTES + ek * (64 * D) + (v_pre ^ (b << 5));
+          if constexpr (RPE == 16)
+            bkt[si][b][ek] = lds_read_tr16(src);
+          else
+            bkt[si][b][ek] = join_tr(lds_read_tr16(src), lds_read_tr16(src + 32 * D));
+        }
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the regions are about to receive tiles
+    lds_fence();
+    if (jw0 < jw1) issue_tile(jw0);
+  }
+  if (HAS_BK && !ROPE) {
     const int S = 16 / GP;         // agent slots per 16-row tile
     const int ncb = (r + 15) >> 4;
     const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
@@ -471,7 +547,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
         qtb[rt][ks] = as_bf16x8(v);
       }
   }
-  if (ALIAS && HAS_BK) {
+  if (ALIAS && HAS_BK && !ROPE) {
     __syncthreads();  // the exchange area is about to be overwritten by tiles
     if (jw0 < jw1) issue_tile(jw0);
   }
@@ -506,7 +582,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
         for (int rt = 0; rt < RT; ++rt)
           s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[rt][ks], s[tt][rt], 0, 0, 0);
       }
-      if (HAS_BK) {
+      if (HAS_BK && !ROPE) {
 #pragma unroll
         for (int ks = 0; ks < RKS; ++ks) {
           const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 32 * RP);
@@ -515,6 +591,78 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
 #pragma unroll
           for (int rt = 0; rt < RT; ++rt)
             s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qtb[rt][ks], s[tt][rt], 0, 0, 0);
+        }
+      }
+    }
+    if constexpr (ROPE) {
+      // phase (in revolutions) of every rotary pair at position j: lane = pair, in double so
+      // that positions in the tens of thousands lose nothing; the lanes below add the key's
+      // own offset in single precision
+      {
+        double rev = static_cast<double>(j) * rate_d;
+        rev -= floor(rev);
+        rope_w[64 + lane] = static_cast<float>(rev);
+      }
+      e_op lop[2][EK];  // L^T as B operand of E^T: the register contents of the L operand of S^T
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int ek = 0; ek < EK; ++ek) {
+          const uint2 lo = lds_read8(ls_lds + l_rd[ek][0] + tt * 32 * RP);
+          if constexpr (RPE == 16) {
+            lop[tt][ek] = __builtin_bit_cast(s16x4, lo);
+          } else {
+            const uint2 hi = lds_read8(ls_lds + l_rd[ek][1] + tt * 32 * RP);
+            lop[tt][ek] = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+          }
+        }
+      const int n_slots = 16 / GP;
+      const int my_slot = ln / GP;
+      const float keyf[2] = {static_cast<float>(ln), static_cast<float>(16 + ln)};
+#pragma unroll
+      for (int fbl = 0; fbl < DB / 2; ++fbl) {
+        const f32x4 rt4 = *reinterpret_cast<const f32x4*>(rope_w + 16 * fbl + 4 * lg);
+        const f32x4 f04 = *reinterpret_cast<const f32x4*>(rope_w + 64 + 16 * fbl + 4 * lg);
+        float cs[2][4], sn[2][4];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const float fr = fmaf(keyf[tt], rt4[jj], f04[jj]);
+            sn[tt][jj] = __builtin_amdgcn_sinf(fr);
+            cs[tt][jj] = __builtin_amdgcn_cosf(fr);
+          }
+#pragma unroll
+        for (int si = 0; si < NS; ++si) {
+          if (si >= n_slots) continue;
+          const bool mine = my_slot == si;
+          const s16x4 zero4 = {0, 0, 0, 0};
+          const s16x4 q_lo = mine ? qp[fbl] : zero4;
+          const s16x4 q_hi = mine ? qp[fbl + DB / 2] : zero4;
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            f32x4 e_lo = {0.f, 0.f, 0.f, 0.f}, e_hi = e_lo;
+            if constexpr (RPE == 16) {
+              e_lo = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(bkt[si][fbl][0], lop[tt][0], e_lo, 0, 0, 0);
+              e_hi = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(bkt[si][fbl + DB / 2][0], lop[tt][0], e_hi, 0, 0, 0);
+            } else {
+#pragma unroll
+              for (int ek = 0; ek < EK; ++ek) {
+                e_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bkt[si][fbl][ek], lop[tt][ek], e_lo, 0, 0, 0);
+                e_hi = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bkt[si][fbl + DB / 2][ek], lop[tt][ek], e_hi, 0, 0, 0);
+              }
+            }
+            float r_lo[4], r_hi[4];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+              r_lo[jj] = e_lo[jj] * cs[tt][jj] - e_hi[jj] * sn[tt][jj];
+              r_hi[jj] = e_hi[jj] * cs[tt][jj] + e_lo[jj] * sn[tt][jj];
+            }
+            const s16x4 a_lo = __builtin_bit_cast(s16x4, make_uint2(pack_bf16x2(r_lo[0], r_lo[1]), pack_bf16x2(r_lo[2], r_lo[3])));
+            const s16x4 a_hi = __builtin_bit_cast(s16x4, make_uint2(pack_bf16x2(r_hi[0], r_hi[1]), pack_bf16x2(r_hi[2], r_hi[3])));
+            s[tt][0] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, q_lo, s[tt][0], 0, 0, 0);
+            s[tt][0] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, q_hi, s[tt][0], 0, 0, 0);
+          }
         }
       }
     }
@@ -784,9 +932,34 @@ static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s) {
 // Row tiles per workgroup the kernel is built for.
 int decode_mfma_row_tiles(int rows_needed) { return rows_needed <= 16 ? 1 : 2; }
 
+template <int D, int RP, int RPE>
+static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
+  if (p.block_size != 0)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, false, RPE>), grid, dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, false, RPE>), grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+// Agent slots a 16-row tile may hold in the rotary form (the B_K^T operands of its slots
+// stay in registers): the row padding per query is at least 16 / this.
+int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 : 1); }
+
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s) {
   (void)prefetch;
   dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
+  if (p.key_rope_theta > 0.f && p.b_k != nullptr && !p.is_prefill) {
+    if (row_tiles != 1 || 16 / p.group_pad > decode_mfma_rope_slots(p.rank)) return hipErrorInvalidValue;
+    const int sel = (p.head_dim == 128 ? 3 : 0) + (p.rank <= 16 ? 0 : (p.rank <= 32 ? 1 : 2));
+    switch (sel) {
+      case 0: return launch_rope<64, 32, 16>(p, grid, s);
+      case 1: return launch_rope<64, 32, 32>(p, grid, s);
+      case 2: return launch_rope<64, 64, 64>(p, grid, s);
+      case 3: return launch_rope<128, 32, 16>(p, grid, s);
+      case 4: return launch_rope<128, 32, 32>(p, grid, s);
+      default: return launch_rope<128, 64, 64>(p, grid, s);
+    }
+  }
   const int rp = p.rank <= 32 ? 32 : 64;
   const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (rp == 64 ? 1 : 0);
   switch (key) {

@@ -50,6 +50,16 @@ def _cases():
     yield "decode_paged_batch", W.make_paged("rope_paged2", seed=307, seq_lens=[1, 63, 64, 65, 1000, 2500], agents_per_seq=4,
                                              n_adapters=4, n_q_heads=28, n_kv_heads=4, head_dim=128, rank=32, d_model=None,
                                              b_std=0.1), 500000.0, None
+    yield "decode_r64_8_agents", W.make_contiguous("rope_dec_r64", "decode", seed=308, n_agents=8, n_q_heads=32, n_kv_heads=8,
+                                                   head_dim=128, rank=64, n=2100, n_new=1, d_model=None, b_std=0.05), 500000.0, None
+    yield "decode_r48_d64", W.make_contiguous("rope_dec_r48", "decode", seed=309, n_agents=2, n_q_heads=16, n_kv_heads=2,
+                                              head_dim=64, rank=48, n=777, n_new=1, d_model=None, b_std=0.05), 10000.0, None
+    yield "decode_9_agents_r16", W.make_contiguous("rope_dec_9", "decode", seed=310, n_agents=9, n_q_heads=16, n_kv_heads=4,
+                                                   head_dim=128, rank=16, n=4100, n_new=1, d_model=None, b_std=0.1), 500000.0, None
+    yield "decode_d64_r8_group1", W.make_contiguous("rope_dec_g1", "decode", seed=311, n_agents=5, n_q_heads=4, n_kv_heads=4,
+                                                    head_dim=64, rank=8, n=129, n_new=1, d_model=None, b_std=0.1), 10000.0, None
+    yield "decode_long_positions", W.make_contiguous("rope_dec_long", "decode", seed=312, n_agents=4, n_q_heads=8, n_kv_heads=2,
+                                                     head_dim=128, rank=16, n=70001, n_new=1, d_model=None, b_std=0.1), 500000.0, None
     yield "prefill", W.make_contiguous("rope_pre", "prefill", seed=304, n_agents=1, n_q_heads=8, n_kv_heads=2,
                                        head_dim=128, rank=16, n=400, n_new=150, d_model=None, b_std=0.1), 500000.0, None
     yield "decode_fp32", W.make_contiguous("rope_f32", "decode", seed=305, dtype=torch.float32, n_agents=2, n_q_heads=4,
@@ -59,8 +69,8 @@ def _cases():
 @pytest.mark.parametrize("variant", [0, 1], ids=["mfma", "vector_alu"])
 @pytest.mark.parametrize("name,w,theta,tight", list(_cases()), ids=[c[0] for c in _cases()])
 def test_rotary_key_side(name, w, theta, tight, variant):
-    """bf16 decode runs on the tile-walking MFMA kernel, one column of workgroups per query (variant 0), or on
-    the vector-ALU kernels (variant 1, and fp32 always)."""
+    """bf16 decode runs on the rotary form of the split-KV MFMA kernel (variant 0: 4, 2 or 1 agent slots per
+    workgroup for ranks up to 16, 32, 64), or on the vector-ALU kernels (variant 1, and fp32 always)."""
     prev = lra.lra_set_kernel_variant(variant)
     try:
         got = _run(w, theta)
