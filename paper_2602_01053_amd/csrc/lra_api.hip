@@ -25,7 +25,6 @@ constexpr int kCUs = 256;  // MI355X
 struct Plan {
   bool mfma;
   bool short_prefill;  // prefill served by the split-KV decode kernels (few new tokens)
-  bool rope_decode;    // decode with the rotary key side, served by the tile-walking prefill kernel per query
   int rows;        // query rows = (queries | new tokens) x Hq
   int split_keys;  // keys per split
   int n_splits;    // splits per sequence at max_seq_len
@@ -70,14 +69,11 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   const int G = sh->n_q_heads / sh->n_kv_heads;
   // The MFMA kernels move L in 16-byte pieces: ranks that are not a multiple of 8 take the
   // vector-ALU kernels.
-  // The rotary key side runs on the tile-walking MFMA kernel, which completes a key tile in LDS
-  // for one adapter: prefill as it is, decode with one column of workgroups per query (every
-  // agent needs its own completed tiles).  The split-KV decode kernel has no rotary path.
+  // The rotary key side: prefill runs on the tile-walking MFMA kernel, which completes a key
+  // tile in LDS for its one adapter; decode on the rotary form of the split-KV kernel.
   const bool rope = sh->key_rope_theta > 0.f;
   pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
-  const bool rope_split = rope && !prefill && pl.mfma;  // rotary form of the split-KV decode kernel
-  bool rope_decode = false;
-  if ((prefill || rope_decode) && pl.mfma) {
+  if (prefill && pl.mfma) {
     // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
     const int64_t lim = (int64_t{1} << 32) - 4096;
@@ -85,32 +81,25 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     if (l_rows * sh->rank * 2 > lim) pl.mfma = false;
     if (c->block_size == 0 && static_cast<int64_t>(c->max_seq_len) * c->kv_token_stride * 2 > lim) pl.mfma = false;
   }
-  pl.rope_decode = rope_decode;
   // A handful of new tokens after a long context gives the tile-walking prefill kernel one
   // workgroup per q head and nothing to split; the split-KV decode kernel, with the new
   // tokens in the place of the agents and a causal limit per row, spreads the context over
   // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
-  pl.short_prefill = prefill && pl.mfma && !rope && tokens <= g_short_prefill.load() &&
+  pl.short_prefill = prefill && pl.mfma && tokens <= g_short_prefill.load() &&
                      static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
-  if ((prefill && pl.mfma && !pl.short_prefill) || rope_decode) {
-    // Tile-walking kernel: one workgroup per (128-row q tile, q head) - per (query, kv head) for
-    // the rotary decode.  When that is fewer than two workgroups per CU, the key tiles of
-    // every q tile are divided among several workgroups (at least eight 64-key tiles each)
-    // and the merge kernel finishes the job; otherwise it is one kernel without a workspace.
+  const bool rope_split = rope && pl.mfma && (!prefill || pl.short_prefill);  // rotary form of the split-KV kernel
+  if (prefill && pl.mfma && !pl.short_prefill) {
+    // Tile-walking kernel: one workgroup per (128-row q tile, q head).  When that is fewer than
+    // two workgroups per CU, the key tiles of every q tile are divided among several workgroups
+    // (at least eight 64-key tiles each) and the merge kernel finishes the job; otherwise it is
+    // one kernel without a workspace.
     pl.rows = tokens * sh->n_q_heads;
     pl.group_pad = pl.row_tiles = pl.row_groups = 1;
     pl.split_keys = c->max_seq_len;
-    const int64_t wgs = rope_decode ? static_cast<int64_t>(tokens) * sh->n_kv_heads
-                                    : static_cast<int64_t>((tokens + 127) / 128) * sh->n_q_heads;
+    const int64_t wgs = static_cast<int64_t>((tokens + 127) / 128) * sh->n_q_heads;
     int64_t ns = g_prefill_splits.load();
     if (ns <= 0) {  // automatic: two workgroups per CU, at least eight key tiles per share
       ns = (2 * kCUs + wgs - 1) / wgs;
-      // a batch of sequences of very different lengths (rotary decode) is only as fast as the
-      // shares of its longest one: at most 32 key tiles per share
-      if (rope_decode && c->n_seqs > 1) {
-        const int64_t by_len = (c->max_seq_len + 64 * 32 - 1) / (64 * 32);
-        ns = ns > by_len ? ns : by_len;
-      }
       const int64_t max_ns = c->max_seq_len / (8 * 64);
       ns = ns > max_ns ? max_ns : ns;
     }
@@ -140,9 +129,9 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
     int rows_needed = max_queries_per_seq * pl.group_pad;
     pl.row_tiles = decode_mfma_row_tiles(rows_needed);
     if (rope_split) {
-      // one row tile per workgroup, and no more agent slots in it than the kernel keeps B_K^T
-      // operands for
-      const int min_pad = 16 / decode_mfma_rope_slots(sh->rank);
+      // one row tile per workgroup, and (decode) no more agent slots in it than the kernel keeps
+      // B_K^T operands for
+      const int min_pad = prefill ? 1 : 16 / decode_mfma_rope_slots(sh->rank);
       pl.group_pad = pl.group_pad > min_pad ? pl.group_pad : min_pad;
       pl.row_tiles = 1;
       rows_needed = max_queries_per_seq * pl.group_pad;
@@ -278,13 +267,6 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   p.is_prefill = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
-  if (pl.rope_decode) {
-    if (n_queries > 65535) return LRA_ERR_UNSUPPORTED;  // one grid row per query
-    if (launch_decode_rope_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
-    if (pl.n_splits > 1 && g_profile_mode.load() != 1 && launch_merge(p, bf16, pl.rows, s) != hipSuccess)
-      return LRA_ERR_HIP;
-    return LRA_OK;
-  }
   if (pl.mfma) {
     if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
   } else {

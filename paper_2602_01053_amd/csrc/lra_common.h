@@ -99,7 +99,6 @@ int decode_mfma_row_tiles(int rows_needed);
 int decode_mfma_rope_slots(int rank);
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s);
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s);
-hipError_t launch_decode_rope_mfma(const Params& p, hipStream_t s);
 
 // Arguments of the cache-append producer kernel.
 struct AppendParams {

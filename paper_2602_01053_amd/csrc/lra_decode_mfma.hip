@@ -157,14 +157,16 @@ constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel build
 //   S^T[key][row] += rot(E)[key][f] . Q[row][f]                (MFMA; the C layout of E^T is the
 //                                                              A layout of this product)
 // with Q masked to the rows of the slot.  The B_K^T operands of NS agent slots stay in
-// registers (RPE = padded rank of that product: 16, 32 or 64, for 4, 2 or 1 slots per tile).
+// registers (RPE = padded rank of that product: 16, 32 or 64, for 4, 2 or 1 slots per tile);
+// in the causal form all rows belong to the one adapter of the call.
 template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL, int RPE = 0>
 __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   constexpr int NW = 4;
   constexpr bool ROPE = RPE > 0;
   constexpr int NS = !ROPE ? 1 : (RPE == 16 ? 4 : (RPE == 32 ? 2 : 1));  // agent slots with operands in registers
   constexpr int EK = RPE == 64 ? 2 : 1;                                    // 32-wide k-steps of the E product
-  static_assert(!ROPE || (RT == 1 && HAS_BK && !CAUSAL && (RPE == 64) == (RP == 64)), "rotary form: one row tile, decode");
+  static_assert(!ROPE || (RT == 1 && HAS_BK && (RPE == 64) == (RP == 64)), "rotary form: one row tile");
+  constexpr int NSL = CAUSAL ? 1 : NS;  // the causal form has one adapter for all rows: one slot
   constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
   constexpr int RKS = RP / 32;     // MFMA k-steps over the (padded) rank
   constexpr int DB = D / 16;       // 16-wide output blocks over d
@@ -445,7 +447,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
   bf16x8 qtb[RT][RKS];
   // ===================== rotary form: B_K^T operands and rotation rates =====================
   using e_op = typename std::conditional<RPE == 16, s16x4, bf16x8>::type;
-  e_op bkt[NS][ROPE ? DB : 1][EK];
+  e_op bkt[NSL][ROPE ? DB : 1][EK];
   float* rope_w = rope_tab + (ROPE ? wave * 128 : 0);
   double rate_d = 0.0;
   if constexpr (ROPE) {
@@ -465,7 +467,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     }
     const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
 #pragma unroll
-    for (int si = 0; si < NS; ++si) {
+    for (int si = 0; si < NSL; ++si) {
       const int a = min(a_slot[0][si], p.n_adapters - 1);
       const uint32_t bytes = a >= 0 ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u;
       const u32x4 rs_b = make_rsrc_words(bkg + static_cast<int64_t>(a >= 0 ? a : 0) * r * ldb + h * D, bytes);
@@ -478,7 +480,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     wait_vm0();
     lds_fence();
 #pragma unroll
-    for (int si = 0; si < NS; ++si)
+    for (int si = 0; si < NSL; ++si)
 #pragma unroll
       for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -616,8 +618,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
             lop[tt][ek] = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
           }
         }
-      const int n_slots = 16 / GP;
-      const int my_slot = ln / GP;
+      const int n_slots = CAUSAL ? 1 : 16 / GP;
+      const int my_slot = CAUSAL ? 0 : ln / GP;
       const float keyf[2] = {static_cast<float>(ln), static_cast<float>(16 + ln)};
 #pragma unroll
       for (int fbl = 0; fbl < DB / 2; ++fbl) {
@@ -633,7 +635,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
             cs[tt][jj] = __builtin_amdgcn_cosf(fr);
           }
 #pragma unroll
-        for (int si = 0; si < NS; ++si) {
+        for (int si = 0; si < NSL; ++si) {
           if (si >= n_slots) continue;
           const bool mine = my_slot == si;
           const s16x4 zero4 = {0, 0, 0, 0};
@@ -934,10 +936,14 @@ int decode_mfma_row_tiles(int rows_needed) { return rows_needed <= 16 ? 1 : 2; }
 
 template <int D, int RP, int RPE>
 static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
-  if (p.block_size != 0)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, false, RPE>), grid, dim3(256), 0, s, p);
-  else
-    hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, false, RPE>), grid, dim3(256), 0, s, p);
+  const bool paged = p.block_size != 0;
+  if (p.is_prefill) {
+    if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, true, RPE>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, true, RPE>), grid, dim3(256), 0, s, p);
+  } else {
+    if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, false, RPE>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, false, RPE>), grid, dim3(256), 0, s, p);
+  }
   return hipGetLastError();
 }
 
@@ -948,8 +954,8 @@ int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 :
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s) {
   (void)prefetch;
   dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
-  if (p.key_rope_theta > 0.f && p.b_k != nullptr && !p.is_prefill) {
-    if (row_tiles != 1 || 16 / p.group_pad > decode_mfma_rope_slots(p.rank)) return hipErrorInvalidValue;
+  if (p.key_rope_theta > 0.f && p.b_k != nullptr) {
+    if (row_tiles != 1 || (!p.is_prefill && 16 / p.group_pad > decode_mfma_rope_slots(p.rank))) return hipErrorInvalidValue;
     const int sel = (p.head_dim == 128 ? 3 : 0) + (p.rank <= 16 ? 0 : (p.rank <= 32 ? 1 : 2));
     switch (sel) {
       case 0: return launch_rope<64, 32, 16>(p, grid, s);

@@ -38,15 +38,9 @@ namespace lra {
 // pairs, so both halves of a pair sit in the same lane and register), rotated, and added to
 // the K_base rows of the tile (8-byte read-modify-writes in bf16).  One more barrier per
 // tile; the score loop is the value-only one.
-// PERQ = true serves decode with the rotary key side on the same kernel: blockIdx.y is a query
-// of the decode call (sequence and adapter come from the call's device tables) and blockIdx.x
-// a kv head, whose G q heads are rows 0 .. G-1 of the q tile; every row sees the whole
-// sequence.  The matrix work is mostly idle, but the keys of a sequence are streamed once per
-// (query, kv head) and completed by the same code, shared over gridDim.y workgroups and merged.
-template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false, bool PERQ = false>
+template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   static_assert(!(ROPE_K && HAS_BK), "the rotary key side replaces the Qt term");
-  static_assert(!PERQ || ROPE_K, "decode without the rotary key side has its own kernel");
   constexpr int BM = 128, BN = 64;
   constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
   constexpr int RKS = RP / 16; // k-steps over the padded rank
@@ -78,37 +72,29 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int Hq = p.n_q_heads, Hkv = p.n_kv_heads, G = p.group, r = p.rank;
 
   // workgroup -> (kv head, q head in group, q tile); consecutive ids go to consecutive XCDs
-  // (PERQ: blockIdx.x is the kv head; rows 0 .. G-1 of the tile are its q heads)
   const int lin = blockIdx.x;
   const int hk = lin % Hkv;
   const int rest = lin / Hkv;
   const int gq = rest % G;
   const int qt = rest / G;
-  // PERQ: the query this workgroup serves, its sequence (queries are grouped by sequence) and adapter
-  const int zq = PERQ ? static_cast<int>(blockIdx.y) : 0;
-  int t = p.seq_index;
-  int a_idx = p.adapter_index;
-  if (PERQ) {
-    t = 0;
-    while (t + 1 < p.n_seqs && PF_CONST_I32(p.seq_query_start)[t + 1] <= zq) ++t;
-    a_idx = min(max(PF_CONST_I32(p.query_adapter)[zq], 0), p.n_adapters - 1);
-  }
+  const int t = p.seq_index;
+  const int a_idx = p.adapter_index;
   const int n_t = min(PF_CONST_I32(p.seq_lens)[t], p.max_seq_len);
-  const int n_new = PERQ ? 1 : p.n_new;
+  const int n_new = p.n_new;
   const int q0 = qt * BM;
   if (q0 >= n_new) return;
   const int base_vis = n_t - n_new;  // new token i sees keys 0 .. base_vis + i
   const int row = q0 + wave * 32 + l32;           // this lane's query row (new-token index)
-  const int n_live = PERQ ? G : n_new;            // live rows of the tile: new tokens, or (PERQ) the q heads of the kv head
+  const int n_live = n_new;                       // live rows of the tile
   const int row_c = min(row, n_live - 1);         // clamped for loads; rows past the end are never stored
-  // token (PERQ: query) and q head of this lane's row: where its q, out and workspace rows are
-  const int grow = PERQ ? zq : row, grow_c = PERQ ? zq : row_c;
-  const int head = PERQ ? hk * G + row_c : hk * G + gq;
-  const int limit = base_vis + (PERQ ? 0 : row_c);  // last visible key of this lane's row
+  // token and q head of this lane's row: where its q, out and workspace rows are
+  const int grow = row, grow_c = row_c;
+  const int head = hk * G + gq;
+  const int limit = base_vis + row_c;             // last visible key of this lane's row
   const int wg_last = base_vis + min(q0 + BM, n_new) - 1;  // last key any row of the workgroup sees
   const int n_tiles = wg_last / BN + 1;
   // this workgroup's share of the q tile's key tiles: [tile_begin, tile_end)
-  const int split = SPLIT ? (PERQ ? blockIdx.z : blockIdx.y) : 0;
+  const int split = SPLIT ? blockIdx.y : 0;
   const int tile_begin = SPLIT ? static_cast<int>(static_cast<int64_t>(n_tiles) * split / p.n_splits) : 0;
   const int tile_end = SPLIT ? static_cast<int>(static_cast<int64_t>(n_tiles) * (split + 1) / p.n_splits) : n_tiles;
   if (SPLIT && tile_begin >= tile_end) {
@@ -341,9 +327,6 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       }
     }
 
-    // (PERQ: the live rows, the q heads of one kv head, all sit in wave 0; the other waves only
-    // move and complete tiles)
-    if (!PERQ || wave == 0) {
     // S^T for the two 32-key halves of the tile.  The halves alternate, so consecutive
     // matrix instructions never wait for each other's result, and the LDS reads run
     // kReadAheadS operands ahead of the products that consume them.
@@ -461,7 +444,6 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     for (int i = 0; i < 4 * (DB + RB); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-    }
     }
     // the next tile has landed (this wave's share) and everybody is done reading this one
     pf_wait_vm0();
@@ -586,36 +568,6 @@ hipError_t launch_prefill_mfma(const Params& p, hipStream_t s) {
   if (rp == 16) return launch_pf<64, 16>(p, grid, s);
   if (rp == 32) return launch_pf<64, 32>(p, grid, s);
   return launch_pf<64, 64>(p, grid, s);
-}
-
-// Decode with the rotary key side: one workgroup per (kv head, share of the keys, query).
-template <int D, int RP>
-static hipError_t launch_rope_dec(const Params& p, dim3 grid, hipStream_t s) {
-  const bool paged = p.block_size != 0;
-  if (p.n_splits > 1) {
-    if (paged) hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false, true, true, true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, true, true, true>), grid, dim3(256), 0, s, p);
-  } else {
-    if (paged) hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false, false, true, true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, false, true, true>), grid, dim3(256), 0, s, p);
-  }
-  return hipGetLastError();
-}
-
-hipError_t launch_decode_rope_mfma(const Params& p, hipStream_t s) {
-  // kv head fastest, then the query, then the share of the keys: the workgroups that stream the
-  // same keys for different agents are dispatched together and, with 8 kv heads, to the same XCD,
-  // so all but the first find the tiles in its L2
-  dim3 grid(p.n_kv_heads, p.n_queries, p.n_splits);
-  const int rp = p.rank <= 16 ? 16 : (p.rank <= 32 ? 32 : 64);
-  if (p.head_dim == 128) {
-    if (rp == 16) return launch_rope_dec<128, 16>(p, grid, s);
-    if (rp == 32) return launch_rope_dec<128, 32>(p, grid, s);
-    return launch_rope_dec<128, 64>(p, grid, s);
-  }
-  if (rp == 16) return launch_rope_dec<64, 16>(p, grid, s);
-  if (rp == 32) return launch_rope_dec<64, 32>(p, grid, s);
-  return launch_rope_dec<64, 64>(p, grid, s);
 }
 
 }  // namespace lra

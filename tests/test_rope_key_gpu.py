@@ -117,19 +117,28 @@ def _prefill_cases():
     yield "positions_beyond_40000", mk("rp4", "prefill", seed=314, n_agents=1, n_q_heads=4, n_kv_heads=1, head_dim=128, rank=16,
                                        n=41000, n_new=70, d_model=None, b_std=0.1), 500000.0
     yield "paged_second_sequence", None, 500000.0
+    # few new tokens after a long context: the causal form of the split-KV kernel
+    yield "short_7_tokens_r16", mk("rp6", "prefill", seed=317, n_agents=1, n_q_heads=32, n_kv_heads=8, head_dim=128, rank=16,
+                                   n=3000, n_new=7, d_model=None, b_std=0.1), 500000.0
+    yield "short_1_token_r32_g7", mk("rp7", "prefill", seed=318, n_agents=1, n_q_heads=28, n_kv_heads=4, head_dim=128, rank=32,
+                                     n=1234, n_new=1, d_model=None, b_std=0.1), 500000.0
+    yield "short_32_tokens_r64_d64", mk("rp8", "prefill", seed=319, n_agents=1, n_q_heads=4, n_kv_heads=2, head_dim=64, rank=64,
+                                        n=900, n_new=32, d_model=None, b_std=0.05), 10000.0
+    yield "paged_short", None, 500000.0
 
 
 @pytest.mark.parametrize("variant", [0, 1], ids=["mfma", "vector_alu"])
 @pytest.mark.parametrize("name,w,theta", list(_prefill_cases()), ids=[c[0] for c in _prefill_cases()])
 def test_rotary_key_side_prefill(name, w, theta, variant):
     """The MFMA prefill kernel completes every key tile in LDS (E = L B_K rotated and added to the K_base rows)
-    before the scores; the vector-ALU kernels serve the same call when asked to (kernel variant 1)."""
+    before the scores; a handful of new tokens after a long context takes the causal rotary form of the
+    split-KV kernel; the vector-ALU kernels serve the same calls when asked to (kernel variant 1)."""
     if variant == 1 and name == "positions_beyond_40000":
         pytest.skip("one wave per row over 41000 keys: covered by the shorter cases")
     prev = lra.lra_set_kernel_variant(variant)
     try:
         if w is None:
-            _paged_prefill(theta)
+            _paged_prefill(theta, 9 if name == "paged_short" else 130)
             return
         got = _run(w, theta)
     finally:
@@ -142,10 +151,10 @@ def test_rotary_key_side_prefill(name, w, theta, variant):
     assert moved > 4 * REL_L2_TOL
 
 
-def _paged_prefill(theta):
-    """130 new tokens at the end of the second sequence of a paged cache (blocks in permuted order)."""
+def _paged_prefill(theta, n_new):
+    """New tokens at the end of the second sequence of a paged cache (blocks in permuted order)."""
     hkv, hq, d, r = 2, 8, 128, 16
-    seq_lens, n_new, s = [77, 500], 130, 1
+    seq_lens, s = [77, 500], 1
     bs, max_blocks, num_blocks = 16, 32, 70
     gen = torch.Generator().manual_seed(315)
     perm = torch.randperm(num_blocks, generator=gen).to(torch.int32)
@@ -190,18 +199,18 @@ def test_rotary_key_side_prefill_with_shared_key_tiles():
 
 
 def test_rotary_decode_with_more_key_shares_than_tiles():
-    """Rotary decode on a ragged paged batch with the key tiles of every query forced onto 32 workgroups:
-    sequences of 1 to 65 tokens leave most shares empty, and every share, empty or not, must leave
-    what the merge kernel reads."""
+    """Rotary decode on a ragged paged batch with 128 keys per share (sequences of 1 to 65 tokens leave
+    most shares of the batch empty, and every share, empty or not, must leave what the merge kernel reads),
+    then with one share per sequence."""
     w = W.make_paged("rope_paged3", seed=308, seq_lens=[1, 63, 64, 65, 1000, 2500], agents_per_seq=3, n_adapters=3,
                      n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, d_model=None, b_std=0.1)
     ref = _oracle(w, 500000.0)
-    for splits in (32, 3):
-        prev = lra.lra_set_prefill_splits(splits)
+    for keys in (128, 4096):
+        prev = lra.lra_set_decode_split_keys(keys)
         try:
             got = _run(w, 500000.0)
         finally:
-            lra.lra_set_prefill_splits(prev)
+            lra.lra_set_decode_split_keys(prev)
         rel, mx = errors(got, ref)
-        print(f"splits {splits}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+        print(f"{keys} keys per share: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
         assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
