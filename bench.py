@@ -194,7 +194,7 @@ def bench_rotary_prefill(args, torch, lra, workloads):
            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                         "note": "flops of the plain call; the completion of the key tiles in LDS is overhead"}}
-    # the decode workload with the rotary key side: tile-walking kernel per (query, kv head) + merge
+    # the decode workload with the rotary key side: rotary form of the split-KV kernel + merge
     w2 = workloads.config(2)
     dw2 = DeviceWorkload(w2, torch.device("cuda:0"), key_rope_theta=500000.0)
     dw2.alloc_workspace()
@@ -208,7 +208,7 @@ def bench_rotary_prefill(args, torch, lra, workloads):
     sec = (time.perf_counter() - t0) / 200
     out["decode"] = {"workload": w2.name + " with key_rope_theta = 500000", "call": "lra_attn_decode",
                      "us_per_call": round(sec * 1e6, 2), "GBps_of_the_plain_call's_bytes": round(w2.algorithmic_bytes() / sec / 1e9, 1),
-                     "note": "same buffers every call (hot); keys are streamed once per query and kv head"}
+                     "note": "same buffers every call (hot); keys are streamed once, L B_K is rotated per tile and agent in registers"}
     return out
 
 

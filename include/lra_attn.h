@@ -85,9 +85,11 @@ typedef struct {
                            K_j = K_base,j + RoPE_j(L_j B_K),
                          rotate-half pairs (i, i + d/2), angle j * theta^(-2i/d), position j =
                          the token's index in its sequence.  Q is the caller's (rotated) query.
-                         The value side is unchanged.  bf16 with rank % 8 == 0 runs on the
-                         tile-walking MFMA kernel (decode: one column of workgroups per query),
-                         everything else on the vector-ALU kernels. */
+                         The value side is unchanged.  bf16 with rank % 8 == 0 runs on MFMA
+                         kernels (decode and prefills of a few tokens: the split-KV kernel
+                         rotates L B_K per key tile in registers, once for every agent of the
+                         tile; other prefills complete each key tile in LDS), everything else
+                         on the vector-ALU kernels. */
 } lra_shape;
 
 /*
