@@ -87,6 +87,18 @@ def test_rotary_key_side(name, w, theta, tight, variant):
     assert moved > 4 * REL_L2_TOL      # the gate would see a missing rotation
 
 
+@pytest.mark.parametrize("cfg", [2, 4, 5])
+def test_rotary_decode_at_the_named_configurations(cfg):
+    """The decode configurations at full size (4 slots per tile at rank 16, one at rank 64, two at rank 32 on a
+    ragged paged batch), in the launch configuration the benchmark's rotary leg times."""
+    w = W.config(cfg)
+    got = _run(w, 500000.0)
+    ref = _oracle(w, 500000.0)
+    rel, mx = errors(got, ref)
+    print(f"{w.name}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
 def test_rotary_key_side_without_key_adapter_is_the_plain_path():
     """b_k = NULL: nothing to rotate; the result agrees with key_rope_theta = 0 (which runs on the MFMA kernels)."""
     w = W.make_contiguous("rope_nobk", "decode", seed=306, n_agents=2, n_q_heads=8, n_kv_heads=2, head_dim=128,
