@@ -290,12 +290,6 @@ int32_t lra_set_short_prefill(int32_t tokens);
 int32_t lra_set_prefill_splits(int32_t splits);
 
 /*
- * Tuning hook: how many 32-key steps ahead the MFMA decode kernel keeps its global
- * loads in registers (1 or 2; other values are clamped).  Returns the previous value.
- */
-int32_t lra_set_decode_prefetch(int32_t steps);
-
-/*
  * Measurement hook.  mode 1: later calls enqueue only their dominant kernel (the
  * key-streaming kernel) and skip the split merge / epilogue, so a benchmark can
  * time that kernel alone with HIP events around a batch of launches; `out` is NOT

@@ -18,7 +18,8 @@ LRA_OK = 0
 LRA_BF16, LRA_F32 = 0, 1
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
-           "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_decode_prefetch", "lra_set_short_prefill", "lra_set_prefill_splits", "lra_set_append_skinny", "lra_set_append_stages", "lra_set_append_tile",
+           "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_short_prefill",
+           "lra_set_prefill_splits", "lra_set_append_skinny", "lra_set_append_stages", "lra_set_append_tile",
            "lra_set_profile_mode")
 
 
@@ -91,8 +92,6 @@ def load_library() -> ctypes.CDLL:
     lib.lra_set_short_prefill.argtypes = [i32]
     lib.lra_set_prefill_splits.restype = i32
     lib.lra_set_prefill_splits.argtypes = [i32]
-    lib.lra_set_decode_prefetch.restype = i32
-    lib.lra_set_decode_prefetch.argtypes = [i32]
     lib.lra_set_profile_mode.restype = i32
     lib.lra_set_profile_mode.argtypes = [i32]
     _lib = lib
@@ -140,10 +139,6 @@ def lra_set_short_prefill(tokens: int) -> int:
 
 def lra_set_prefill_splits(splits: int) -> int:
     return int(load_library().lra_set_prefill_splits(int(splits)))
-
-
-def lra_set_decode_prefetch(steps: int) -> int:
-    return int(load_library().lra_set_decode_prefetch(int(steps)))
 
 
 def lra_set_profile_mode(mode: int) -> int:

@@ -16,7 +16,6 @@ std::atomic<int32_t> g_append_stages{0};   // LDS stages of the tiled append GEM
 std::atomic<int32_t> g_append_tile{0};     // output tile of the append GEMM (0: chosen from the grid, 128, 256)
 std::atomic<int32_t> g_append_skinny{64};  // new tokens up to which lra_cache_append streams the weights instead of tiling
 std::atomic<int32_t> g_short_prefill{32};  // kShortPrefill: new tokens up to which prefill takes the split-KV path
-std::atomic<int32_t> g_prefetch{2};  // register prefetch depth of the MFMA decode kernel (1 or 2 steps)
 
 std::atomic<int32_t> g_profile_mode{0};
 
@@ -268,7 +267,7 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
   if (pl.mfma) {
-    if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
+    if (launch_decode_mfma(p, pl.row_tiles, s) != hipSuccess) return LRA_ERR_HIP;
   } else {
     if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   }
@@ -307,7 +306,7 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
   if (pl.short_prefill) {
-    if (launch_decode_mfma(p, pl.row_tiles, g_prefetch.load(), s) != hipSuccess) return LRA_ERR_HIP;
+    if (launch_decode_mfma(p, pl.row_tiles, s) != hipSuccess) return LRA_ERR_HIP;
     if (g_profile_mode.load() == 1) return LRA_OK;
     if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
     return LRA_OK;
@@ -398,7 +397,6 @@ int32_t lra_set_short_prefill(int32_t tokens) { return g_short_prefill.exchange(
 
 int32_t lra_set_decode_split_keys(int32_t keys) { return g_split_keys.exchange(keys < 0 ? 0 : keys); }
 
-int32_t lra_set_decode_prefetch(int32_t steps) { return g_prefetch.exchange(steps >= 2 ? 2 : 1); }
 
 int32_t lra_set_profile_mode(int32_t mode) { return g_profile_mode.exchange(mode == 1 ? 1 : 0); }
 

@@ -97,7 +97,7 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
 hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s);
 int decode_mfma_row_tiles(int rows_needed);
 int decode_mfma_rope_slots(int rank);
-hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s);
+hipError_t launch_decode_mfma(const Params& p, int row_tiles, hipStream_t s);
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s);
 
 // Arguments of the cache-append producer kernel.

@@ -951,8 +951,7 @@ static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
 // stay in registers): the row padding per query is at least 16 / this.
 int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 : 1); }
 
-hipError_t launch_decode_mfma(const Params& p, int row_tiles, int prefetch, hipStream_t s) {
-  (void)prefetch;
+hipError_t launch_decode_mfma(const Params& p, int row_tiles, hipStream_t s) {
   dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
   if (p.key_rope_theta > 0.f && p.b_k != nullptr) {
     if (row_tiles != 1 || (!p.is_prefill && 16 / p.group_pad > decode_mfma_rope_slots(p.rank))) return hipErrorInvalidValue;
