@@ -15,7 +15,7 @@ for one iteration, not the paper's end-to-end throughput; shapes only, random da
 All calls of an iteration are captured once into a HIP graph on a side stream and replayed,
 so the time is GPU time without the Python call overhead between the ~300 launches.
 
-Prints ONE JSON line.  `python bench_trace.py [--replays N] [--lctx 256,1024,...]`
+Prints ONE JSON line.  `python bench_trace.py [--replays N] [--lctx 256,1024,...] [--key-rope-theta 500000]`
 """
 import argparse
 import json
@@ -31,7 +31,7 @@ HQ, HKV, D, R, LAYERS = 32, 8, 128, 16, 32
 D_MODEL, ROPE_THETA = 4096, 500000.0
 
 
-def run_trace(torch, lra, l_ctx, replays):
+def run_trace(torch, lra, l_ctx, replays, key_rope_theta=0.0):
     dev = torch.device("cuda:0")
     steps = [(a, l_ctx if p is None else p, g) for a, p, g in TRACE]
     total = sum(p + g for _, p, g in steps)
@@ -60,7 +60,7 @@ def run_trace(torch, lra, l_ctx, replays):
     lens = torch.tensor([c[1] for c in calls], dtype=torch.int32, device=dev)
     adapters_dev = torch.tensor([0, 1, 2], dtype=torch.int32, device=dev)
     qstart = torch.tensor([0, 1], dtype=torch.int32, device=dev)
-    shape = lra.make_shape(q, HKV, R, 0.0)
+    shape = lra.make_shape(q, HKV, R, 0.0, key_rope_theta)
     ws_bytes = 256
     prepared = []
     for i, (kind, n_after, n_new, a) in enumerate(calls):
@@ -116,6 +116,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--replays", type=int, default=5)
     ap.add_argument("--lctx", type=str, default="256,1024,4096,16384")
+    ap.add_argument("--key-rope-theta", type=float, default=0.0,
+                    help="> 0: the rotary key side (LoRA on the key projection, App. D.1) with this base")
     args = ap.parse_args()
     import torch
     import paper_2602_01053_amd as lra
@@ -123,10 +125,10 @@ def main():
         print("bench_trace.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     lra.load_library()
-    rows = [run_trace(torch, lra, int(x), args.replays) for x in args.lctx.split(",")]
+    rows = [run_trace(torch, lra, int(x), args.replays, args.key_rope_theta) for x in args.lctx.split(",")]
     print(json.dumps({"workload": "LRAgent emulated agent-iteration trace (17 steps), attention only, "
                                   "Llama-3-8B attention shape (32 q / 8 kv heads, d=128, r=16), bf16, one sequence, 3 adapters",
-                      "data": "synthetic", "timing": "HIP graph replay of all calls of one iteration",
+                      "key_rope_theta": args.key_rope_theta, "data": "synthetic", "timing": "HIP graph replay of all calls of one iteration",
                       "rows": rows}), flush=True)
 
 
