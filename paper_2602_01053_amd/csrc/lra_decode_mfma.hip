@@ -141,6 +141,9 @@ __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)");
 __device__ __forceinline__ void lds_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront"); }
 
 constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel builds
+// Agent slots per tile of the rotary form at ranks above 32: that kernel has a CU to itself
+// (its LDS leaves no room for a second workgroup), hence 512 registers per wave.
+constexpr int kRopeSlots64 = 4;
 
 // HAS_BK = false is the value-only setting (b_k == NULL, keys fully shared): no Qt, no
 // adapter lookup on the key side, no L term in the scores; L is still streamed for P.L.
@@ -157,13 +160,14 @@ constexpr uint32_t kOob = 0x80000000u;  // beyond any resource this kernel build
 //   S^T[key][row] += rot(E)[key][f] . Q[row][f]                (MFMA; the C layout of E^T is the
 //                                                              A layout of this product)
 // with Q masked to the rows of the slot.  The B_K^T operands of NS agent slots stay in
-// registers (RPE = padded rank of that product: 16, 32 or 64, for 4, 2 or 1 slots per tile);
+// registers (RPE = padded rank of that product: 16, 32 or 64, for 4, 2 or 4 slots per tile - at
+// 64 the LDS leaves room for one workgroup per CU only, whose waves then have 512 registers);
 // in the causal form all rows belong to the one adapter of the call.
 template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL, int RPE = 0>
-__global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
+__global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Params p) {
   constexpr int NW = 4;
   constexpr bool ROPE = RPE > 0;
-  constexpr int NS = !ROPE ? 1 : (RPE == 16 ? 4 : (RPE == 32 ? 2 : 1));  // agent slots with operands in registers
+  constexpr int NS = !ROPE ? 1 : (RPE == 16 ? 4 : (RPE == 32 ? 2 : kRopeSlots64));  // agent slots with operands in registers
   constexpr int EK = RPE == 64 ? 2 : 1;                                    // 32-wide k-steps of the E product
   static_assert(!ROPE || (RT == 1 && HAS_BK && (RPE == 64) == (RP == 64)), "rotary form: one row tile");
   constexpr int NSL = CAUSAL ? 1 : NS;  // the causal form has one adapter for all rows: one slot
@@ -458,7 +462,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
     const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
     const uint32_t ldb2 = static_cast<uint32_t>(ldb) * 2u;
     constexpr int SLOT_BYTES = RPE * D * 2;
-    static_assert(NS * SLOT_BYTES <= 2 * KV_BYTES, "the slices must fit the K and V regions");
+    constexpr int SPP = NSL * SLOT_BYTES <= 2 * KV_BYTES ? NSL : 2 * KV_BYTES / SLOT_BYTES;  // slots per pass through the regions
+    static_assert(SPP >= 1 && NSL % SPP == 0, "a slice must fit the K and V regions");
     uint32_t bk_voff[VPER];
     {
       const int rr = lane / KCH, pc = lane % KCH;
@@ -466,33 +471,36 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(Params p) {
       for (int q = 0; q < VPER; ++q) bk_voff[q] = static_cast<uint32_t>(rr) * ldb2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
     }
     const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
-#pragma unroll
-    for (int si = 0; si < NSL; ++si) {
-      const int a = min(a_slot[0][si], p.n_adapters - 1);
-      const uint32_t bytes = a >= 0 ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u;
-      const u32x4 rs_b = make_rsrc_words(bkg + static_cast<int64_t>(a >= 0 ? a : 0) * r * ldb + h * D, bytes);
-#pragma unroll
-      for (int i = 0; i < RPE / KROWS; ++i)
-        buf_load16_to_lds(rs_b, ks_lds + si * SLOT_BYTES + i * 1024, bk_voff[i % VPER], i * KROWS * ldb2);
-    }
     rate_d = rope_rate_rev(lane & (D / 2 - 1), D, p.key_rope_theta);
     rope_w[lane] = static_cast<float>(rate_d);
-    wait_vm0();
-    lds_fence();
 #pragma unroll
-    for (int si = 0; si < NSL; ++si)
+    for (int s0 = 0; s0 < NSL; s0 += SPP) {
 #pragma unroll
-      for (int b = 0; b < DB; ++b)
+      for (int sp = 0; sp < SPP; ++sp) {
+        const int a = min(a_slot[0][s0 + sp], p.n_adapters - 1);
+        const uint32_t bytes = a >= 0 ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u;
+        const u32x4 rs_b = make_rsrc_words(bkg + static_cast<int64_t>(a >= 0 ? a : 0) * r * ldb + h * D, bytes);
 #pragma unroll
-        for (int ek = 0; ek < EK; ++ek) {
-          const unsigned char* src = ks_lds + si * SLOT_BYTES + ek * (64 * D) + (v_pre ^ (b << 5));
-          if constexpr (RPE == 16)
-            bkt[si][b][ek] = lds_read_tr16(src);
-          else
-            bkt[si][b][ek] = join_tr(lds_read_tr16(src), lds_read_tr16(src + 32 * D));
-        }
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the regions are about to receive tiles
-    lds_fence();
+        for (int i = 0; i < RPE / KROWS; ++i)
+          buf_load16_to_lds(rs_b, ks_lds + sp * SLOT_BYTES + i * 1024, bk_voff[i % VPER], i * KROWS * ldb2);
+      }
+      wait_vm0();
+      lds_fence();
+#pragma unroll
+      for (int sp = 0; sp < SPP; ++sp)
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+          for (int ek = 0; ek < EK; ++ek) {
+            const unsigned char* src = ks_lds + sp * SLOT_BYTES + ek * (64 * D) + (v_pre ^ (b << 5));
+            if constexpr (RPE == 16)
+              bkt[s0 + sp][b][ek] = lds_read_tr16(src);
+            else
+              bkt[s0 + sp][b][ek] = join_tr(lds_read_tr16(src), lds_read_tr16(src + 32 * D));
+          }
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the regions are about to be written again
+      lds_fence();
+    }
     if (jw0 < jw1) issue_tile(jw0);
   }
   if (HAS_BK && !ROPE) {
@@ -949,7 +957,7 @@ static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
 
 // Agent slots a 16-row tile may hold in the rotary form (the B_K^T operands of its slots
 // stay in registers): the row padding per query is at least 16 / this.
-int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 : 1); }
+int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 : kRopeSlots64); }
 
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, hipStream_t s) {
   dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
