@@ -99,6 +99,39 @@ def test_rotary_decode_at_the_named_configurations(cfg):
     assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
 
 
+def _random_decode_cases(count=28, seed=2026):
+    """Seeded draws over the shapes the rotary decode kernel distinguishes: head dimension, rank class (16 / 32 /
+    64 and ranks inside a class), group size (row padding 4, 8, 16), more agents than slots of a tile, lengths
+    around the 32-key step and the share boundaries, contiguous and paged."""
+    rng = np.random.default_rng(seed)
+    for i in range(count):
+        d = int(rng.choice([64, 128]))
+        rank = int(rng.choice([8, 16, 24, 32, 40, 64]))
+        group = int(rng.choice([1, 2, 4, 7, 8, 16]))
+        hkv = int(rng.choice([1, 2, 4]))
+        agents = int(rng.integers(1, 10))
+        theta = float(rng.choice([10000.0, 500000.0]))
+        if i % 2 == 0:
+            n = int(rng.choice([1, 31, 32, 33, 127, 128, 129, 500, 1025, 2600]))
+            w = W.make_contiguous(f"rnd{i}", "decode", seed=1000 + i, n_agents=agents, n_q_heads=group * hkv, n_kv_heads=hkv,
+                                  head_dim=d, rank=rank, n=n, n_new=1, d_model=None, b_std=0.1)
+        else:
+            lens = [int(x) for x in rng.choice([1, 15, 16, 17, 100, 129, 700, 1500], size=int(rng.integers(1, 5)))]
+            w = W.make_paged(f"rnd{i}", seed=1000 + i, seq_lens=lens, agents_per_seq=agents, n_adapters=3,
+                             n_q_heads=group * hkv, n_kv_heads=hkv, head_dim=d, rank=rank, d_model=None, b_std=0.1)
+        yield f"{i}_d{d}_r{rank}_g{group}_kv{hkv}_a{agents}_{'paged' if i % 2 else 'contig'}", w, theta
+
+
+@pytest.mark.parametrize("name,w,theta", list(_random_decode_cases()), ids=[c[0] for c in _random_decode_cases()])
+def test_rotary_decode_random_shapes(name, w, theta):
+    got = _run(w, theta)
+    ref = _oracle(w, theta)
+    rel, mx = errors(got, ref)
+    print(f"{name}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
 def test_rotary_key_side_without_key_adapter_is_the_plain_path():
     """b_k = NULL: nothing to rotate; the result agrees with key_rope_theta = 0 (which runs on the MFMA kernels)."""
     w = W.make_contiguous("rope_nobk", "decode", seed=306, n_agents=2, n_q_heads=8, n_kv_heads=2, head_dim=128,
