@@ -77,6 +77,44 @@ def kernel_seconds(lra, torch, launch, n):
     return ms.value * 1e-3 / n
 
 
+def machine_ceilings(torch, lra):
+    """What this GPU gives a plain streaming read (1.5 GB, far beyond the memory-side cache) and a
+    register-resident bf16 MFMA loop (about half a second of sustained matrix work, so the clock settles
+    where it does under such load): the library's two probe kernels, HIP events on their stream."""
+    dev = torch.device("cuda:0")
+    hip = _hip()
+    stream = torch.cuda.current_stream().cuda_stream or None
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+
+    def timed(launch, n):
+        launch()
+        torch.cuda.synchronize()
+        assert hip.hipEventRecord(e0, stream) == 0
+        for _ in range(n):
+            launch()
+        assert hip.hipEventRecord(e1, stream) == 0
+        hip.hipEventSynchronize(e1)
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+        return ms.value * 1e-3 / n
+
+    buf = torch.empty(1536 << 20, dtype=torch.uint8, device=dev)
+    buf.fill_(1)
+    read_s = timed(lambda: lra.lra_probe_stream_read(buf, sink), 20)
+    hbm = buf.numel() / read_s / 1e9
+    del buf
+    flops = []
+    mfma_s = timed(lambda: flops.append(lra.lra_probe_mfma_bf16(200000, sink)), 20)
+    hip.hipEventDestroy(e0)
+    hip.hipEventDestroy(e1)
+    return {"hbm_stream_read_GBps": round(hbm, 1), "hbm_frac_of_peak": round(hbm / HBM_PEAK_GBS, 4),
+            "mfma_bf16_TFLOPs": round(flops[-1] / mfma_s / 1e12, 1),
+            "mfma_frac_of_peak": round(flops[-1] / mfma_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "note": "lra_probe_stream_read over 1.5 GB and lra_probe_mfma_bf16 (operands in registers), measured in this run"}
+
+
 def _load_traffic(name):
     """HBM bytes per launch from committed rocprofv3 --pmc summaries, if any."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
@@ -382,6 +420,12 @@ def main():
         line["value_only_adapters"] = value_only_decode(args, torch, lra, workloads)
     if not args.no_append:
         line["cache_append"] = bench_append(args, torch, lra, not args.no_cpu_baseline)
+    ceil = machine_ceilings(torch, lra)
+    line["machine_ceilings"] = ceil
+    line["roofline"]["frac_of_measured_ceiling"] = round(k_gbs / ceil["hbm_stream_read_GBps"], 4)
+    if "prefill" in line:
+        line["prefill"]["roofline"]["frac_of_measured_ceiling"] = round(
+            line["prefill"]["roofline"]["achieved"] / ceil["mfma_bf16_TFLOPs"], 4)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(workloads)
     print(json.dumps(line), flush=True)

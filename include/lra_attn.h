@@ -298,6 +298,26 @@ int32_t lra_set_prefill_splits(int32_t splits);
  */
 int32_t lra_set_profile_mode(int32_t mode);
 
+/*
+ * Machine probes for the benchmark (not part of the attention path): what the GPU at hand
+ * gives a plain streaming read and a register-resident bf16 MFMA loop, to be timed by the
+ * caller with events around the call.
+ *
+ * lra_probe_stream_read: one kernel reads `bytes` (a multiple of 16 is read; >= 16) from the
+ * device buffer src (16-byte aligned) once, coalesced, 16 bytes per lane and request.  Use a
+ * buffer larger than the 256 MB memory-side cache for an HBM figure.  sink: 4 writable device
+ * bytes (written only for one improbable value of the checksum).
+ *
+ * lra_probe_mfma_bf16: one kernel of two workgroups per CU, every wave issuing
+ * iters x 4 independent v_mfma_f32_32x32x16_bf16 on register operands (1 <= iters <= 2^24);
+ * *flops (host, may be NULL) receives the floating-point operations of the launch.  sink: 4
+ * writable device bytes.
+ *
+ * Both are asynchronous on `stream`; LRA_ERR_NULL / LRA_ERR_SHAPE on bad arguments.
+ */
+lra_status lra_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+lra_status lra_probe_mfma_bf16(int32_t iters, int64_t* flops, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ LRA_BF16, LRA_F32 = 0, 1
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
            "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_short_prefill",
            "lra_set_prefill_splits", "lra_set_append_skinny", "lra_set_append_stages", "lra_set_append_tile",
-           "lra_set_profile_mode")
+           "lra_set_profile_mode", "lra_probe_stream_read", "lra_probe_mfma_bf16")
 
 
 class LraShape(ctypes.Structure):
@@ -94,6 +94,10 @@ def load_library() -> ctypes.CDLL:
     lib.lra_set_prefill_splits.argtypes = [i32]
     lib.lra_set_profile_mode.restype = i32
     lib.lra_set_profile_mode.argtypes = [i32]
+    lib.lra_probe_stream_read.restype = ctypes.c_int
+    lib.lra_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.lra_probe_mfma_bf16.restype = ctypes.c_int
+    lib.lra_probe_mfma_bf16.argtypes = [i32, ctypes.POINTER(ctypes.c_int64), vp, vp]
     _lib = lib
     return lib
 
@@ -143,6 +147,19 @@ def lra_set_prefill_splits(splits: int) -> int:
 
 def lra_set_profile_mode(mode: int) -> int:
     return int(load_library().lra_set_profile_mode(int(mode)))
+
+
+def lra_probe_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """One streaming read of the whole of src (a machine probe for the benchmark)."""
+    _check(load_library().lra_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                                                _stream_ptr(stream)))
+
+
+def lra_probe_mfma_bf16(iters: int, sink: torch.Tensor, stream=None) -> int:
+    """One launch of the register-resident bf16 MFMA loop; returns its floating-point operations."""
+    flops = ctypes.c_int64(0)
+    _check(load_library().lra_probe_mfma_bf16(int(iters), ctypes.byref(flops), _ptr(sink), _stream_ptr(stream)))
+    return int(flops.value)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:

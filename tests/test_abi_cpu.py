@@ -23,7 +23,7 @@ def lib():
 def test_header_symbols_are_exported(lib):
     text = open(os.path.join(ROOT, "include", "lra_attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(lra_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(lra_[a-z0-9_]+)\s*\(", text))
     assert {"lra_attn_decode", "lra_attn_prefill", "lra_workspace_bytes"} <= declared
     for name in declared:
         assert hasattr(lib, name), f"{name} declared in lra_attn.h but not exported"
@@ -200,3 +200,14 @@ def test_header_is_plain_c(tmp_path):
     res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                           "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
+
+
+def test_probes_reject_bad_arguments(lib):
+    """The two machine probes validate on the host before any launch."""
+    import ctypes
+    flops = ctypes.c_int64(0)
+    assert lib.lra_probe_stream_read(None, 1024, None, None) != 0
+    assert lib.lra_probe_stream_read(ctypes.c_void_p(4096), 8, ctypes.c_void_p(4096), None) != 0      # fewer than 16 bytes
+    assert lib.lra_probe_stream_read(ctypes.c_void_p(4100), 1024, ctypes.c_void_p(4096), None) != 0   # misaligned
+    assert lib.lra_probe_mfma_bf16(0, ctypes.byref(flops), ctypes.c_void_p(4096), None) != 0
+    assert lib.lra_probe_mfma_bf16(10, ctypes.byref(flops), None, None) != 0

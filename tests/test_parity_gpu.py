@@ -339,3 +339,15 @@ def test_runs_on_a_side_stream():
         dw.decode(s)
     s.synchronize()
     _gate(dw.out.to(torch.float64).cpu().numpy(), oracle_decode(w), label="side stream")
+
+
+def test_machine_probes_run():
+    """The benchmark's two probe kernels complete, leave their sink alone and report their work."""
+    sink = torch.zeros(4, dtype=torch.int32, device=DEV)
+    buf = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    lra.lra_probe_stream_read(buf, sink)
+    lra.lra_probe_stream_read(buf[:1000], sink)       # a length that leaves a remainder pass
+    flops = lra.lra_probe_mfma_bf16(100, sink)
+    torch.cuda.synchronize()
+    assert flops == 512 * 4 * 4 * 100 * 2 * 32 * 32 * 16
+    assert int(sink.abs().sum()) == 0
