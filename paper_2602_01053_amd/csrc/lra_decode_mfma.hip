@@ -128,12 +128,21 @@ __device__ __forceinline__ u32x4 make_rsrc_words(const void* base, uint32_t byte
 // first LDS reads of the tile.  Neither statement claims to touch memory (the compiler
 // would then stop using scalar loads for the kernel's read-only tables); the ordering
 // against the LDS reads of the tile comes from lds_fence() on both sides.
+// STREAM = true marks the request non-temporal: K_base and V_base rows are read once per call, by
+// one workgroup, and should not displace what other workgroups share (L, B_K, the partial states).
+template <bool STREAM = false>
 __device__ __forceinline__ void buf_load16_to_lds(u32x4 rs, unsigned char* lds, uint32_t voff, uint32_t soff) {
   const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_AS(unsigned char, lds)));
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
-               : "m0");
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
+                 : "m0");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff)
+                 : "m0");
 }
 __device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)"); }
 // Compiler-level ordering point for the LDS traffic of one wave: no LDS access moves across
@@ -391,8 +400,8 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
 #pragma unroll
         for (int i = 0; i < KVL / 2; ++i) {
           const int ii = half * (KVL / 2) + i;
-          buf_load16_to_lds(pk, ks_lds + ii * 1024, k_voff[ii % KPER], i * KROWS * ts2);
-          buf_load16_to_lds(pv, vs_lds + ii * 1024, v_voff[ii % VPER], i * KROWS * ts2);
+          buf_load16_to_lds<true>(pk, ks_lds + ii * 1024, k_voff[ii % KPER], i * KROWS * ts2);
+          buf_load16_to_lds<true>(pv, vs_lds + ii * 1024, v_voff[ii % VPER], i * KROWS * ts2);
         }
 #pragma unroll
         for (int i = 0; i < LL / 2; ++i) {
@@ -404,8 +413,8 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
       const uint32_t s0 = static_cast<uint32_t>(j - jw0);
 #pragma unroll
       for (int i = 0; i < KVL; ++i) {
-        buf_load16_to_lds(rs_k, ks_lds + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
-        buf_load16_to_lds(rs_v, vs_lds + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
+        buf_load16_to_lds<true>(rs_k, ks_lds + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
+        buf_load16_to_lds<true>(rs_v, vs_lds + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
       }
 #pragma unroll
       for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * r2);
