@@ -17,7 +17,8 @@
 // between lanes.
 //
 // Data path: buffer_load ... lds (16 bytes per lane, straight from HBM into
-// wave-private LDS, no staging registers).  Each lane fetches the 16-byte chunk
+// wave-private LDS, no staging registers; K_base and V_base non-temporal, since
+// nobody reads them twice, L cached for the workgroups of the other kv heads).  Each lane fetches the 16-byte chunk
 // that belongs at ITS LDS slot under an XOR swizzle, so the later ds_read_b128
 // (K operand), ds_read_b64 (L operand) and ds_read_b64_tr_b16 (transposed V and
 // L operands) avoid bank conflicts.  Keys past the end of a wave's range are
