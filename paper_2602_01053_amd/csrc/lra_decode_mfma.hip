@@ -383,6 +383,13 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   };
   fetch_block_ids(jw0);
 
+  // K_base / V_base requests: non-temporal when this workgroup is the only reader of its keys; with
+  // several row groups per (sequence, kv head) the others find the tiles in L2
+  const bool stream_kv = p.row_groups == 1;
+  auto kv_load = [&](u32x4 rs, unsigned char* lds, uint32_t voff, uint32_t soff) __attribute__((always_inline)) {
+    if (stream_kv) buf_load16_to_lds<true>(rs, lds, voff, soff);
+    else buf_load16_to_lds<false>(rs, lds, voff, soff);
+  };
   // ---- HBM -> LDS for the 32-key step starting at token j ----
   auto issue_tile = [&](int j) {
     if (PAGED) {
@@ -401,8 +408,8 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
 #pragma unroll
         for (int i = 0; i < KVL / 2; ++i) {
           const int ii = half * (KVL / 2) + i;
-          buf_load16_to_lds<true>(pk, ks_lds + ii * 1024, k_voff[ii % KPER], i * KROWS * ts2);
-          buf_load16_to_lds<true>(pv, vs_lds + ii * 1024, v_voff[ii % VPER], i * KROWS * ts2);
+          kv_load(pk, ks_lds + ii * 1024, k_voff[ii % KPER], i * KROWS * ts2);
+          kv_load(pv, vs_lds + ii * 1024, v_voff[ii % VPER], i * KROWS * ts2);
         }
 #pragma unroll
         for (int i = 0; i < LL / 2; ++i) {
@@ -414,8 +421,8 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
       const uint32_t s0 = static_cast<uint32_t>(j - jw0);
 #pragma unroll
       for (int i = 0; i < KVL; ++i) {
-        buf_load16_to_lds<true>(rs_k, ks_lds + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
-        buf_load16_to_lds<true>(rs_v, vs_lds + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
+        kv_load(rs_k, ks_lds + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
+        kv_load(rs_v, vs_lds + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
       }
 #pragma unroll
       for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * r2);
