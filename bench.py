@@ -353,6 +353,23 @@ def cpu_baseline(workloads):
                       f"fp64 numpy oracle, best of {reps} runs"}
 
 
+def cpu_baseline_prefill(workloads):
+    """The oracle on a sample of the prefill workload's new-token rows (rows are independent): every eighth
+    row of the block, all 32 heads each, timed once; flops counted as for the GPU (visible pairs of those rows)."""
+    from tests.harness import oracle_prefill
+    w = workloads.config(3)
+    rows = list(range(3, w.n_new, 8))
+    t0 = time.perf_counter()
+    oracle_prefill(w, rows=rows)
+    sec = time.perf_counter() - t0
+    n = int(w.seq_lens[0])
+    d, r, hq = int(w.q.shape[-1]), int(w.l.shape[-1]), int(w.q.shape[-2])
+    pairs = sum(n - w.n_new + i + 1 for i in rows) * hq
+    flops = 4.0 * (d + r) * pairs + 4.0 * len(rows) * hq * d * r
+    return {"value": round(flops / sec / 1e12, 5), "unit": "TFLOP/s", "kind": "oracle", "seconds": round(sec, 3),
+            "sample": f"{len(rows)} of the {w.n_new} new-token rows of {w.name}, all heads, fp64 numpy oracle, one run"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -427,6 +444,8 @@ def main():
         line["prefill"]["roofline"]["frac_of_measured_ceiling"] = round(
             line["prefill"]["roofline"]["achieved"] / ceil["mfma_bf16_TFLOPs"], 4)
     if not args.no_cpu_baseline:
+        if "prefill" in line:
+            line["prefill"]["cpu_baseline"] = cpu_baseline_prefill(workloads)
         line["cpu_baseline"] = cpu_baseline(workloads)
     print(json.dumps(line), flush=True)
 
