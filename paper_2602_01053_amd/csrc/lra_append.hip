@@ -7,7 +7,7 @@
 // ones, App. D.1) and writes the rows into K_base, V_base and L, contiguous or paged.
 //
 // Four kernels, chosen by the number of new tokens (launch_append at the end of the file): a
-// matrix-vector kernel (1-4 tokens), a weight-streaming MFMA kernel (up to 64), and two tiled
+// matrix-vector kernel (1-2 tokens), a weight-streaming MFMA kernel (up to 64), and two tiled
 // GEMM kernels (128 features x 128 or 64 tokens per workgroup; 256 x 256 for chunks whose tiles
 // fill whole rounds of the chip).
 //
@@ -666,7 +666,13 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int c = c0 + 64 * u;
-      wv[u] = c < n_chunks ? wp[c] : make_uint4(0u, 0u, 0u, 0u);
+      // (non-temporal: a weight row is read once per call, by this wave)
+      if (c < n_chunks) {
+        const pf_u32x4 t4 = __builtin_nontemporal_load(reinterpret_cast<const pf_u32x4*>(wp + c));
+        wv[u] = make_uint4(t4[0], t4[1], t4[2], t4[3]);
+      } else {
+        wv[u] = make_uint4(0u, 0u, 0u, 0u);
+      }
     }
     // all requests out before the first use.  (The operands stay HIP's uint4 structs on purpose: with
     // native 4-vectors this compiler selected element 0 for all four dot products.)
@@ -752,15 +758,13 @@ static void launch_skinny(const AppendParams& p, hipStream_t s) {
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s) {
   const int hd = p.n_kv_heads * p.head_dim;
-  if (p.n_new <= 4 && p.n_new <= p.skinny_max) {
+  if (p.n_new <= 2 && p.n_new <= p.skinny_max) {
     if (p.head_dim == 128) {
       if (p.n_new == 1) launch_gemv<128, 1>(p, s);
-      else if (p.n_new == 2) launch_gemv<128, 2>(p, s);
-      else launch_gemv<128, 4>(p, s);
+      else launch_gemv<128, 2>(p, s);
     } else {
       if (p.n_new == 1) launch_gemv<64, 1>(p, s);
-      else if (p.n_new == 2) launch_gemv<64, 2>(p, s);
-      else launch_gemv<64, 4>(p, s);
+      else launch_gemv<64, 2>(p, s);
     }
     return hipGetLastError();
   }
