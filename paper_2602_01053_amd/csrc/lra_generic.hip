@@ -234,6 +234,9 @@ __global__ __launch_bounds__(kWave) void generic_partial_rope_kernel(Params p) {
 // order: the result does not depend on which workgroup of the first kernel
 // finished first.
 constexpr int kMergeUnroll = 8;  // splits per thread and pass
+// Rows from which the wave-per-row form of the merge runs (measured on MI355X: 1792 rows of config
+// 5 take 12.7 us against 20.5 us; 256 rows of config 4 take 10.4 us against 9.3 us).
+constexpr int kMergeWaveRows = 1024;
 
 template <typename T, int kMergeGroups>
 __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
@@ -346,6 +349,103 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   }
 }
 
+// The same merge for calls with many rows: one wave per row (four rows, q heads of one kv
+// head, per workgroup), no LDS and no barrier, so that a CU holds twenty rows' worth of loads
+// in flight instead of four.  Lane = split for the statistics (at most 64 splits), lane =
+// column (pair of columns at d = 128) for the rows; the weight of a split and the entries of
+// O_lr travel by v_readlane.  Splits are added in index order.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_wave_kernel(Params p) {
+  constexpr int CPL = D / 64;  // columns per lane: c = CPL * lane + k
+  const int Hq = p.n_q_heads, r = p.rank, G = p.group;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int GC = (G + 3) >> 2;
+  const int h = blockIdx.x % p.n_kv_heads;
+  const int rest = blockIdx.x / p.n_kv_heads;
+  const int gc = rest % GC, tok = rest / GC;
+  const int gq = gc * 4 + wave;
+  if (gq >= G) return;
+  const int row = tok * Hq + h * G + gq;
+  const int ns = p.n_splits;
+  const int64_t slot0 = static_cast<int64_t>(row) * ns;
+  const int a = __builtin_amdgcn_readfirstlane(min(max(p.part_adapter[row], 0), p.n_adapters - 1));
+
+  const float2 st = lane < ns ? reinterpret_cast<const float2*>(p.part_ml)[slot0 + lane] : make_float2(0.f, 0.f);
+  const bool live = st.y > 0.f;  // a share without a visible key left a zero row sum; its rows were never written
+  const float big = wave_max(live ? st.x : -INFINITY);
+  const float w = live ? expf(st.x - big) : 0.f;
+  const float ell = wave_sum(w * st.y);
+
+  const float* po = p.part_o + slot0 * D + CPL * lane;
+  const float* pl = p.part_lr + slot0 * r + lane;
+  const bool col_l = lane < r;
+  float o[CPL], olr = 0.f;
+#pragma unroll
+  for (int k = 0; k < CPL; ++k) o[k] = 0.f;
+  constexpr int U = 8;
+  for (int s0 = 0; s0 < ns; s0 += U) {
+    float x[U][CPL], y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int sidx = min(s0 + u, ns - 1);
+      if (CPL == 2) {
+        const float2 v = *reinterpret_cast<const float2*>(po + static_cast<int64_t>(sidx) * D);
+        x[u][0] = v.x;
+        x[u][CPL - 1] = v.y;
+      } else {
+        x[u][0] = po[static_cast<int64_t>(sidx) * D];
+      }
+      y[u] = col_l ? pl[static_cast<int64_t>(sidx) * r] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float wu = (s0 + u < ns) ? __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), (s0 + u) & 63)) : 0.f;
+      if (wu > 0.f) {  // wave-uniform; also keeps whatever an unwritten row holds out of the sums
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) o[k] = fmaf(wu, x[u][k], o[k]);
+        olr = fmaf(wu, y[u], olr);
+      }
+    }
+  }
+  // epilogue O += O_lr B_V, sixteen B_V rows requested at a time
+  if (p.b_v != nullptr) {
+    const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * D;
+    const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * ld + h * D + CPL * lane;
+    for (int r0 = 0; r0 < r; r0 += 16) {
+      float b[16][CPL];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int rho = min(r0 + i, r - 1);
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) b[i][k] = to_f32<T>(bv[rho * ld + k]);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (r0 + i < r) {
+          const float xr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, olr), (r0 + i) & 63));
+#pragma unroll
+          for (int k = 0; k < CPL; ++k) o[k] = fmaf(xr, b[i][k], o[k]);
+        }
+      }
+    }
+  }
+  T* out = static_cast<T*>(p.out) + static_cast<int64_t>(row) * D + CPL * lane;
+#pragma unroll
+  for (int k = 0; k < CPL; ++k) out[k] = from_f32<T>(o[k] / ell);
+}
+
+template <typename T>
+static bool launch_merge_wave(const Params& p, int rows, hipStream_t s) {
+  // worth it from a few hundred rows on; the statistics need one lane per split
+  if (rows < kMergeWaveRows || p.n_splits > 64 || (p.head_dim != 64 && p.head_dim != 128)) return false;
+  const int tokens = rows / p.n_q_heads;
+  dim3 grid(static_cast<unsigned>(tokens) * p.n_kv_heads * ((p.group + 3) / 4));
+  if (p.head_dim == 128) hipLaunchKernelGGL((merge_wave_kernel<T, 128>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((merge_wave_kernel<T, 64>), grid, dim3(256), 0, s, p);
+  return true;
+}
+
 hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipStream_t s) {
   dim3 grid(rows, p.n_splits), block(kWave);
   if (p.key_rope_theta > 0.f && p.b_k != nullptr) {
@@ -362,6 +462,7 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
 
 template <typename T>
 static void launch_merge_t(const Params& p, int rows, hipStream_t s) {
+  if (launch_merge_wave<T>(p, rows, s)) return;
   // enough 128-thread groups that one pass of kMergeUnroll splits per thread covers the splits
   const int groups = (p.n_splits + kMergeUnroll - 1) / kMergeUnroll;
   dim3 grid(rows);

@@ -351,3 +351,41 @@ def test_machine_probes_run():
     torch.cuda.synchronize()
     assert flops == 512 * 4 * 4 * 100 * 2 * 32 * 32 * 16
     assert int(sink.abs().sum()) == 0
+
+
+@pytest.mark.parametrize("case", [
+    # sequences, agents per sequence, Hq, Hkv, d, r  -> rows = sequences x agents x Hq
+    (40, 8, 4, 1, 128, 16),     # 1280 rows, group of 4
+    (30, 5, 14, 2, 64, 24),     # 2100 rows, group of 7 (two workgroups of four waves per kv head, one wave idle)
+    (20, 4, 16, 1, 128, 64),    # 1280 rows, group of 16
+    (70, 3, 5, 5, 64, 8),       # 1050 rows, group of 1 (three of four waves idle)
+], ids=lambda c: "s%d_a%d_hq%d_hkv%d_d%d_r%d" % c)
+def test_many_rows_take_the_wave_per_row_merge(case):
+    """Calls with 1024 rows or more end with the wave-per-row form of the merge kernel: ragged paged batches
+    with many short sequences (so that most key shares of most rows are empty), every group size class."""
+    n_seqs, agents, hq, hkv, d, r = case
+    rng = np.random.default_rng(sum(case))
+    lens = [int(x) for x in rng.integers(1, 700, size=n_seqs)]
+    w = W.make_paged("many_rows", seed=4000 + sum(case), seq_lens=lens, agents_per_seq=agents, n_adapters=3,
+                     n_q_heads=hq, n_kv_heads=hkv, head_dim=d, rank=r, d_model=None, b_std=0.05)
+    assert w.q.shape[0] * hq >= 1024
+    prev = lra.lra_set_decode_split_keys(128)   # up to six shares per sequence
+    try:
+        got = run_decode(w, DEV)
+    finally:
+        lra.lra_set_decode_split_keys(prev)
+    _gate(got, oracle_decode(w), label=w.name)
+
+
+def test_prefill_with_shared_key_tiles_and_many_rows():
+    """64 new tokens x 16 q heads = 1024 rows, key tiles shared by 4 workgroups: the wave-per-row merge after the
+    tile-walking prefill kernel."""
+    w = W.make_contiguous("pf_many_rows", "prefill", seed=4100, n_agents=1, n_q_heads=16, n_kv_heads=4, head_dim=128,
+                          rank=16, n=1500, n_new=64, d_model=None, b_std=0.05)
+    prev_s, prev_p = lra.lra_set_short_prefill(0), lra.lra_set_prefill_splits(4)
+    try:
+        got = run_prefill(w, DEV)
+    finally:
+        lra.lra_set_short_prefill(prev_s)
+        lra.lra_set_prefill_splits(prev_p)
+    _gate(got, oracle_prefill(w), label=w.name)
