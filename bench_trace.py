@@ -7,7 +7,9 @@ One iteration is 17 agent steps (five plan-plan-action cycles, two reflect steps
 appends P_k context tokens (one causal prefill call by that step's agent) and then
 generates G_k tokens (G_k single-query decode calls, the context growing by one each).
 The producer of the caches (lra_cache_append: one call per prefill chunk and per generated
-token, Llama-3-8B projection shape) is timed as a separate leg over the same schedule.
+token, Llama-3-8B projection shape) is timed as a separate leg over the same schedule, with
+40 copies of the projection weights taken in turn so that every call reads them from HBM, as
+a layer of a model does (its other layers' weights pass through the caches in between).
 The retrieved-context length L_ctx sets four of the P_k.  Only attention is timed - this
 library holds no projections or MLPs - so the figures are the attention share of one layer
 for one iteration, not the paper's end-to-end throughput; shapes only, random data.
@@ -48,6 +50,9 @@ def run_trace(torch, lra, l_ctx, replays, key_rope_theta=0.0):
     # the producer of the caches: hidden states of the new tokens and [W_K; W_V; A]
     x = torch.randn(max_p, D_MODEL, generator=gen).to(bf).to(dev)
     w_cat = (torch.randn(2 * HKV * D + R, D_MODEL, generator=gen) / D_MODEL ** 0.5).to(bf).to(dev)
+    # 40 copies taken in turn (680 MB, beyond the caches): between two appends of one layer a model reads the
+    # weights of all its other layers, so a layer's projection weights come from HBM every time
+    w_copies = [w_cat] + [w_cat.clone() for _ in range(39)]
     # one device int per call holds the sequence length of that call
     calls = []  # (kind, n_after, n_new, adapter)
     n = 0
@@ -73,9 +78,9 @@ def run_trace(torch, lra, l_ctx, replays, key_rope_theta=0.0):
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def iteration(stream, only=None):
-        for kind, cache, n_new, a in prepared:
+        for i, (kind, cache, n_new, a) in enumerate(prepared):
             if only == "append":
-                lra.lra_cache_append(shape, cache, w_cat, ROPE_THETA, x[:n_new], 0, stream)
+                lra.lra_cache_append(shape, cache, w_copies[i % len(w_copies)], ROPE_THETA, x[:n_new], 0, stream)
                 continue
             if only is not None and kind != only:
                 continue
