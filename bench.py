@@ -107,12 +107,15 @@ def machine_ceilings(torch, lra):
     del buf
     flops = []
     mfma_s = timed(lambda: flops.append(lra.lra_probe_mfma_bf16(200000, sink)), 20)
+    mfma_rand_s = timed(lambda: lra.lra_probe_mfma_bf16(200000, sink, random_operands=True), 20)
     hip.hipEventDestroy(e0)
     hip.hipEventDestroy(e1)
     return {"hbm_stream_read_GBps": round(hbm, 1), "hbm_frac_of_peak": round(hbm / HBM_PEAK_GBS, 4),
             "mfma_bf16_TFLOPs": round(flops[-1] / mfma_s / 1e12, 1),
             "mfma_frac_of_peak": round(flops[-1] / mfma_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "note": "lra_probe_stream_read over 1.5 GB and lra_probe_mfma_bf16 (operands in registers), measured in this run"}
+            "mfma_bf16_random_operands_TFLOPs": round(flops[-1] / mfma_rand_s / 1e12, 1),
+            "note": "lra_probe_stream_read over 1.5 GB; lra_probe_mfma_bf16 with operands in registers, two smooth values "
+                    "throughout and four pseudo-random registers in rotation; measured in this run"}
 
 
 def _load_traffic(name):
@@ -457,6 +460,8 @@ def main():
     if "prefill" in line:
         line["prefill"]["roofline"]["frac_of_measured_ceiling"] = round(
             line["prefill"]["roofline"]["achieved"] / ceil["mfma_bf16_TFLOPs"], 4)
+        line["prefill"]["roofline"]["frac_of_ceiling_with_random_operands"] = round(
+            line["prefill"]["roofline"]["achieved"] / ceil["mfma_bf16_random_operands_TFLOPs"], 4)
     if not args.no_cpu_baseline:
         if "prefill" in line:
             line["prefill"]["cpu_baseline"] = cpu_baseline_prefill(workloads)

@@ -309,14 +309,16 @@ int32_t lra_set_profile_mode(int32_t mode);
  * bytes (written only for one improbable value of the checksum).
  *
  * lra_probe_mfma_bf16: one kernel of two workgroups per CU, every wave issuing
- * iters x 4 independent v_mfma_f32_32x32x16_bf16 on register operands (1 <= iters <= 2^24);
- * *flops (host, may be NULL) receives the floating-point operations of the launch.  sink: 4
- * writable device bytes.
+ * iters x 4 independent v_mfma_f32_32x32x16_bf16 on register operands (1 <= iters <= 2^24).
+ * random_operands == 0: two smooth operand values throughout; != 0: four registers of
+ * pseudo-random values in rotation, so that consecutive products see unrelated bits as in a real
+ * kernel (the clock the chip holds under matrix load depends on the data).  *flops (host, may
+ * be NULL) receives the floating-point operations of the launch.  sink: 4 writable device bytes.
  *
  * Both are asynchronous on `stream`; LRA_ERR_NULL / LRA_ERR_SHAPE on bad arguments.
  */
 lra_status lra_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
-lra_status lra_probe_mfma_bf16(int32_t iters, int64_t* flops, void* sink, void* stream);
+lra_status lra_probe_mfma_bf16(int32_t iters, int32_t random_operands, int64_t* flops, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

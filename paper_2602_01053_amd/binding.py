@@ -97,7 +97,7 @@ def load_library() -> ctypes.CDLL:
     lib.lra_probe_stream_read.restype = ctypes.c_int
     lib.lra_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.lra_probe_mfma_bf16.restype = ctypes.c_int
-    lib.lra_probe_mfma_bf16.argtypes = [i32, ctypes.POINTER(ctypes.c_int64), vp, vp]
+    lib.lra_probe_mfma_bf16.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_int64), vp, vp]
     _lib = lib
     return lib
 
@@ -155,10 +155,11 @@ def lra_probe_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) ->
                                                 _stream_ptr(stream)))
 
 
-def lra_probe_mfma_bf16(iters: int, sink: torch.Tensor, stream=None) -> int:
+def lra_probe_mfma_bf16(iters: int, sink: torch.Tensor, random_operands: bool = False, stream=None) -> int:
     """One launch of the register-resident bf16 MFMA loop; returns its floating-point operations."""
     flops = ctypes.c_int64(0)
-    _check(load_library().lra_probe_mfma_bf16(int(iters), ctypes.byref(flops), _ptr(sink), _stream_ptr(stream)))
+    _check(load_library().lra_probe_mfma_bf16(int(iters), int(bool(random_operands)), ctypes.byref(flops), _ptr(sink),
+                                              _stream_ptr(stream)))
     return int(flops.value)
 
 

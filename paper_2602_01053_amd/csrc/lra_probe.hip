@@ -33,23 +33,41 @@ __global__ __launch_bounds__(256) void probe_stream_read_kernel(const pr_u32x4* 
 }
 
 // Four independent 32x32 accumulators per wave, operands in registers, no memory traffic:
-// iters x 4 v_mfma_f32_32x32x16_bf16 per wave (32768 flop each).
+// iters x 4 v_mfma_f32_32x32x16_bf16 per wave (32768 flop each).  RANDOM = false: two smooth
+// operand values, the same for every product; RANDOM = true: four operand registers of
+// pseudo-random bf16 values in [-1, 1) taken in rotation, so that consecutive products see
+// unrelated bits, as the products of a real kernel do (the clock under matrix load depends on it).
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void probe_mfma_bf16_kernel(int iters, float* sink) {
   const float seed = static_cast<float>(threadIdx.x & 7) * 0.125f;
-  pr_bf16x8 a, b;
+  pr_bf16x8 a, b, a2, b2;
+  uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    a[e] = static_cast<__bf16>(seed + e * 0.015625f);
-    b[e] = static_cast<__bf16>(0.5f - seed);
+    if (RANDOM) {
+      float v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        h = h * 1664525u + 1013904223u;
+        v[k] = static_cast<float>(static_cast<int>(h >> 8) - (1 << 23)) * (1.0f / (1 << 23));
+      }
+      a[e] = static_cast<__bf16>(v[0]);
+      b[e] = static_cast<__bf16>(v[1]);
+      a2[e] = static_cast<__bf16>(v[2]);
+      b2[e] = static_cast<__bf16>(v[3]);
+    } else {
+      a[e] = a2[e] = static_cast<__bf16>(seed + e * 0.015625f);
+      b[e] = b2[e] = static_cast<__bf16>(0.5f - seed);
+    }
   }
   pr_f32x16 c0, c1, c2, c3;
 #pragma unroll
   for (int e = 0; e < 16; ++e) c0[e] = c1[e] = c2[e] = c3[e] = 0.f;
   for (int it = 0; it < iters; ++it) {
     c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
-    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c1, 0, 0, 0);
-    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, c2, 0, 0, 0);
-    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, b, c3, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b2, a2, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, a, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, b2, c3, 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
@@ -72,12 +90,16 @@ lra_status lra_probe_stream_read(const void* src, size_t bytes, void* sink, void
   return hipGetLastError() == hipSuccess ? LRA_OK : LRA_ERR_HIP;
 }
 
-lra_status lra_probe_mfma_bf16(int32_t iters, int64_t* flops, void* sink, void* stream) {
+lra_status lra_probe_mfma_bf16(int32_t iters, int32_t random_operands, int64_t* flops, void* sink, void* stream) {
   if (!sink) return LRA_ERR_NULL;
   if (iters < 1 || iters > (1 << 24)) return LRA_ERR_SHAPE;
   constexpr int kGroups = 256 * 2;  // two workgroups of four waves per CU: two waves per SIMD
-  hipLaunchKernelGGL(probe_mfma_bf16_kernel, dim3(kGroups), dim3(256), 0, static_cast<hipStream_t>(stream), iters,
-                     static_cast<float*>(sink));
+  if (random_operands)
+    hipLaunchKernelGGL(probe_mfma_bf16_kernel<true>, dim3(kGroups), dim3(256), 0, static_cast<hipStream_t>(stream), iters,
+                       static_cast<float*>(sink));
+  else
+    hipLaunchKernelGGL(probe_mfma_bf16_kernel<false>, dim3(kGroups), dim3(256), 0, static_cast<hipStream_t>(stream), iters,
+                       static_cast<float*>(sink));
   if (flops) *flops = static_cast<int64_t>(kGroups) * 4 /*waves*/ * 4 /*accumulators*/ * iters * (2LL * 32 * 32 * 16);
   return hipGetLastError() == hipSuccess ? LRA_OK : LRA_ERR_HIP;
 }

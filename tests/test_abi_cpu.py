@@ -209,5 +209,5 @@ def test_probes_reject_bad_arguments(lib):
     assert lib.lra_probe_stream_read(None, 1024, None, None) != 0
     assert lib.lra_probe_stream_read(ctypes.c_void_p(4096), 8, ctypes.c_void_p(4096), None) != 0      # fewer than 16 bytes
     assert lib.lra_probe_stream_read(ctypes.c_void_p(4100), 1024, ctypes.c_void_p(4096), None) != 0   # misaligned
-    assert lib.lra_probe_mfma_bf16(0, ctypes.byref(flops), ctypes.c_void_p(4096), None) != 0
-    assert lib.lra_probe_mfma_bf16(10, ctypes.byref(flops), None, None) != 0
+    assert lib.lra_probe_mfma_bf16(0, 0, ctypes.byref(flops), ctypes.c_void_p(4096), None) != 0
+    assert lib.lra_probe_mfma_bf16(10, 1, ctypes.byref(flops), None, None) != 0

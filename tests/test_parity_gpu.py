@@ -348,6 +348,7 @@ def test_machine_probes_run():
     lra.lra_probe_stream_read(buf, sink)
     lra.lra_probe_stream_read(buf[:1000], sink)       # a length that leaves a remainder pass
     flops = lra.lra_probe_mfma_bf16(100, sink)
+    assert lra.lra_probe_mfma_bf16(100, sink, random_operands=True) == flops
     torch.cuda.synchronize()
     assert flops == 512 * 4 * 4 * 100 * 2 * 32 * 32 * 16
     assert int(sink.abs().sum()) == 0
