@@ -462,6 +462,10 @@ def main():
             line["prefill"]["roofline"]["achieved"] / ceil["mfma_bf16_TFLOPs"], 4)
         line["prefill"]["roofline"]["frac_of_ceiling_with_random_operands"] = round(
             line["prefill"]["roofline"]["achieved"] / ceil["mfma_bf16_random_operands_TFLOPs"], 4)
+    for row in line.get("cache_append", {}).get("rows", []):
+        if row["roofline"]["bound"] == "mfma":
+            row["roofline"]["frac_of_ceiling_with_random_operands"] = round(
+                row["roofline"]["achieved"] / ceil["mfma_bf16_random_operands_TFLOPs"], 4)
     if not args.no_cpu_baseline:
         if "prefill" in line:
             line["prefill"]["cpu_baseline"] = cpu_baseline_prefill(workloads)
