@@ -248,9 +248,10 @@ int32_t lra_set_decode_split_keys(int32_t keys);
 
 /*
  * Tuning and test hook: lra_cache_append calls with at most this many new tokens run the
- * weight-streaming kernel (16 features per workgroup, d_model split over its waves) instead
- * of the tiled GEMM; any value is valid, both kernels handle any n_new.  0 switches the
- * streaming kernel off.  Returns the previous value.  Default 64.
+ * weight-streaming kernels (one or two tokens: one wave per weight row; more: 16 features per
+ * workgroup, d_model split over its waves) instead of the tiled GEMM; any value is valid, all
+ * kernels handle any n_new.  0 switches the streaming kernels off.  Returns the previous
+ * value.  Default 64.
  */
 int32_t lra_set_append_skinny(int32_t tokens);
 
