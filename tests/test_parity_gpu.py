@@ -378,6 +378,22 @@ def test_many_rows_take_the_wave_per_row_merge(case):
     _gate(got, oracle_decode(w), label=w.name)
 
 
+def test_many_rows_fp32_and_vector_alu_partials():
+    """The wave-per-row merge behind the vector-ALU partial kernels: fp32 (held to 2e-5), and bf16 with the
+    vector-ALU kernels forced."""
+    lens = [int(x) for x in np.random.default_rng(77).integers(1, 400, size=36)]
+    for dtype, variant, fp32 in ((torch.float32, 0, True), (torch.bfloat16, 1, False)):
+        w = W.make_paged("many_rows_valu", seed=4200, dtype=dtype, seq_lens=lens, agents_per_seq=4, n_adapters=3,
+                         n_q_heads=8, n_kv_heads=2, head_dim=64, rank=12, d_model=None, b_std=0.05)
+        assert w.q.shape[0] * 8 >= 1024
+        prev = lra.lra_set_kernel_variant(variant)
+        try:
+            got = run_decode(w, DEV)
+        finally:
+            lra.lra_set_kernel_variant(prev)
+        _gate(got, oracle_decode(w), fp32=fp32, label=f"{w.name} {dtype}")
+
+
 def test_prefill_with_shared_key_tiles_and_many_rows():
     """64 new tokens x 16 q heads = 1024 rows, key tiles shared by 4 workgroups: the wave-per-row merge after the
     tile-walking prefill kernel."""
