@@ -51,6 +51,19 @@ def oracle_prefill(w: Workload, rows=None) -> np.ndarray:
                           _f64(w.b_v[a]), n=w.seq_lens[0], scale=w.scale, rows=rows)
 
 
+def oracle_prefill_by_blocks(w: Workload, key_rope_theta: float = 0.0, block: int = 256) -> np.ndarray:
+    """Every new-token row of a prefill workload from the oracle, evaluated in blocks of rows (rows are
+    independent) so that the fp64 score matrix of one call stays small; prints a line per block."""
+    a = int(w.query_adapter[0])
+    args = (_f64(w.q), _f64(w.k_base), _f64(w.v_base), _f64(w.l), _f64(w.b_k[a]), _f64(w.b_v[a]))
+    parts = []
+    for r0 in range(0, w.n_new, block):
+        rows = np.arange(r0, min(r0 + block, w.n_new))
+        parts.append(oracle.prefill(*args, n=w.seq_lens[0], scale=w.scale, rows=rows, key_rope_theta=key_rope_theta))
+        print(f"oracle rows {r0}..{rows[-1]} done", flush=True)
+    return np.concatenate(parts)
+
+
 def errors(got: np.ndarray, ref: np.ndarray) -> Tuple[float, float]:
     """(worst relative L2 over the whole tensor and over each leading-index slice,
     max abs error).  Non-finite outputs count as infinite error."""

@@ -88,6 +88,39 @@ def test_p1_brute_force_prefill_causal():
             np.testing.assert_allclose(out[i, g], ref, rtol=1e-12, atol=1e-13)
 
 
+def test_p1_prefill_row_subset_brute_force_and_selection():
+    """prefill(rows=R) - what the full-size prefill parity checks and the benchmark's CPU
+    baseline call - against the scalar brute force directly, row by row (each row with its
+    own causal limit n - T + i + 1 and its own query), for an unsorted R with a repeat; and
+    equal (to the last bits) to the same rows taken out of the full result, with and without the
+    rotary key side."""
+    t_new, n, hq, hkv, d = 6, 11, 4, 2, 4
+    x = _tiny(n=n, t_new=t_new, agents=1, hq=hq, hkv=hkv, d=d)
+    scale = 0.41
+    rows = [4, 0, 5, 4, 2]
+    args = (x["q"], x["k_base"], x["v_base"], x["l"], x["b_k"][0], x["b_v"][0])
+    sub = oracle.prefill(*args, n=n, scale=scale, rows=rows)
+    assert sub.shape == (len(rows), hq, d)
+    for k, i in enumerate(rows):
+        for g in range(hq):
+            ref = _brute_one_row(x["q"][i, g], x["k_base"], x["v_base"], x["l"],
+                                 x["b_k"][0], x["b_v"][0], g // (hq // hkv), scale, n - t_new + i + 1)
+            np.testing.assert_allclose(sub[k, g], ref, rtol=1e-12, atol=1e-13)
+    # a different causal limit or a different query row must show: neighbouring rows differ
+    assert np.abs(sub[0] - sub[2]).max() > 1e-3 and np.abs(sub[1] - sub[4]).max() > 1e-3
+    for theta in (0.0, 100.0):
+        full = oracle.prefill(*args, n=n, scale=scale, key_rope_theta=theta)
+        part = oracle.prefill(*args, n=n, scale=scale, rows=rows, key_rope_theta=theta)
+        np.testing.assert_allclose(part, full[rows], rtol=1e-13, atol=1e-14)  # same rows, up to BLAS blocking
+    # a numpy index array and a sequence shorter than the cache arrays behave the same
+    longer = dict(x)
+    for name in ("k_base", "v_base", "l"):
+        longer[name] = np.concatenate([x[name], 9.0 + x[name][:3]])
+    part = oracle.prefill(x["q"], longer["k_base"], longer["v_base"], longer["l"], x["b_k"][0], x["b_v"][0],
+                          n=n, scale=scale, rows=np.asarray(rows))
+    np.testing.assert_allclose(part, sub, rtol=1e-13, atol=1e-14)
+
+
 # --------------------------------------------------------------------------
 # P2 / P3: closed forms.
 # --------------------------------------------------------------------------

@@ -10,7 +10,7 @@ import oracle
 import paper_2602_01053_amd as lra
 from paper_2602_01053_amd import workloads as W
 from paper_2602_01053_amd.runner import DeviceWorkload
-from tests.harness import MAX_ABS_TOL, REL_L2_TOL, _f64, errors
+from tests.harness import MAX_ABS_TOL, REL_L2_TOL, _f64, errors, oracle_prefill_by_blocks
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -99,6 +99,17 @@ def test_rotary_decode_at_the_named_configurations(cfg):
     assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
 
 
+def test_rotary_prefill_at_configuration_3_every_row():
+    """The full-size causal prefill with the rotary key side, in the launch configuration the benchmark's rotary
+    leg times, compared with the oracle on every output row."""
+    w = W.config(3)
+    got = _run(w, 500000.0)
+    ref = oracle_prefill_by_blocks(w, key_rope_theta=500000.0)
+    rel, mx = errors(got, ref)
+    print(f"{w.name} rotary: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
 def _random_decode_cases(count=28, seed=2026):
     """Seeded draws over the shapes the rotary decode kernel distinguishes: head dimension, rank class (16 / 32 /
     64 and ranks inside a class), group size (row padding 4, 8, 16), more agents than slots of a tile, lengths
@@ -161,6 +172,10 @@ def _prefill_cases():
                          n=260, n_new=129, d_model=None, b_std=0.05), 500000.0
     yield "positions_beyond_40000", mk("rp4", "prefill", seed=314, n_agents=1, n_q_heads=4, n_kv_heads=1, head_dim=128, rank=16,
                                        n=41000, n_new=70, d_model=None, b_std=0.1), 500000.0
+    # the same positions with a handful of rows, so that the vector-ALU kernels (one wave per row and key
+    # share) finish it quickly as well
+    yield "positions_beyond_40000_few_rows", mk("rp4b", "prefill", seed=320, n_agents=1, n_q_heads=2, n_kv_heads=1, head_dim=128,
+                                                rank=16, n=41000, n_new=3, d_model=None, b_std=0.1), 500000.0
     yield "paged_second_sequence", None, 500000.0
     # few new tokens after a long context: the causal form of the split-KV kernel
     yield "short_7_tokens_r16", mk("rp6", "prefill", seed=317, n_agents=1, n_q_heads=32, n_kv_heads=8, head_dim=128, rank=16,
@@ -172,14 +187,21 @@ def _prefill_cases():
     yield "paged_short", None, 500000.0
 
 
-@pytest.mark.parametrize("variant", [0, 1], ids=["mfma", "vector_alu"])
-@pytest.mark.parametrize("name,w,theta", list(_prefill_cases()), ids=[c[0] for c in _prefill_cases()])
+def _prefill_params():
+    """Every case on both kernel families, except the 70-token case at 41000 positions on the vector-ALU
+    kernels (280 rows walking 41000 keys each): its few-row sibling covers those positions there."""
+    for variant, vid in ((0, "mfma"), (1, "vector_alu")):
+        for name, w, theta in _prefill_cases():
+            if variant == 1 and name == "positions_beyond_40000":
+                continue
+            yield pytest.param(name, w, theta, variant, id=f"{name}-{vid}")
+
+
+@pytest.mark.parametrize("name,w,theta,variant", list(_prefill_params()))
 def test_rotary_key_side_prefill(name, w, theta, variant):
     """The MFMA prefill kernel completes every key tile in LDS (E = L B_K rotated and added to the K_base rows)
     before the scores; a handful of new tokens after a long context takes the causal rotary form of the
     split-KV kernel; the vector-ALU kernels serve the same calls when asked to (kernel variant 1)."""
-    if variant == 1 and name == "positions_beyond_40000":
-        pytest.skip("one wave per row over 41000 keys: covered by the shorter cases")
     prev = lra.lra_set_kernel_variant(variant)
     try:
         if w is None:
