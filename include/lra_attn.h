@@ -182,6 +182,27 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lra_attn_decode for callers that cannot allocate or size a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit for bit the same output as lra_attn_decode, but the split-KV partial states go to
+ * a buffer of LRA_STATIC_WORKSPACE_BYTES that is part of the library's device image (every GPU
+ * the library runs on holds one copy until the process ends).  The call allocates and frees
+ * nothing.  The first call on a device looks up that device's copy of the buffer (one HIP
+ * query, no allocation); make that first call outside graph capture.
+ *   - LRA_ERR_WORKSPACE, with nothing enqueued, when the call would need more than
+ *     LRA_STATIC_WORKSPACE_BYTES (lra_workspace_bytes gives the need).
+ *   - All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU
+ *     (different streams, or threads) race on it and must be serialised by the caller.
+ *     Nothing in the buffer has to survive from one call to the next.
+ */
+#define LRA_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+lra_status lra_attn_decode_static(const lra_shape* shape, const lra_cache* cache,
+                                  const lra_adapters* adapters, const void* q,
+                                  const int32_t* query_adapter, const int32_t* seq_query_start,
+                                  int32_t n_queries, int32_t max_queries_per_seq, void* out,
+                                  void* stream);
+
+/*
  * Causal prefill of one agent (Alg. 1 as printed: L_c = n_new query tokens after
  * L_p cached ones).  The n_new query tokens are the LAST n_new tokens of sequence
  * seq_index, whose cache rows are already in place; new token i sees keys

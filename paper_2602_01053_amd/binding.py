@@ -17,7 +17,9 @@ from .build import LIB_PATH
 LRA_OK = 0
 LRA_BF16, LRA_F32 = 0, 1
 
-EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_prefill", "lra_status_string",
+STATIC_WORKSPACE_BYTES = 64 << 20   # LRA_STATIC_WORKSPACE_BYTES of the header
+
+EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_decode_static", "lra_attn_prefill", "lra_status_string",
            "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_short_prefill",
            "lra_set_prefill_splits", "lra_set_append_skinny", "lra_set_append_stages", "lra_set_append_tile",
            "lra_set_profile_mode", "lra_probe_stream_read", "lra_probe_mfma_bf16")
@@ -72,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.lra_workspace_bytes.argtypes = [sp, cp, i32, i32, i32]
     lib.lra_attn_decode.restype = ctypes.c_int
     lib.lra_attn_decode.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.lra_attn_decode_static.restype = ctypes.c_int
+    lib.lra_attn_decode_static.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, vp]
     lib.lra_attn_prefill.restype = ctypes.c_int
     lib.lra_attn_prefill.argtypes = [sp, cp, ap, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, vp]
     lib.lra_cache_append.restype = ctypes.c_int
@@ -234,6 +238,17 @@ def lra_attn_decode(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor
         ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(ad), _ptr(q), _ptr(query_adapter),
         _ptr(seq_query_start), int(q.shape[0]), int(max_queries_per_seq), _ptr(out), ws_ptr,
         ws_bytes, _stream_ptr(stream)))
+
+
+def lra_attn_decode_static(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor],
+                           b_v: Optional[torch.Tensor], n_adapters: int, q: torch.Tensor,
+                           query_adapter: torch.Tensor, seq_query_start: torch.Tensor,
+                           max_queries_per_seq: int, out: torch.Tensor, stream=None) -> None:
+    """lra_attn_decode with the library's own per-device workspace (no allocation anywhere)."""
+    ad = LraAdapters(_ptr(b_k), _ptr(b_v), int(n_adapters))
+    _check(load_library().lra_attn_decode_static(
+        ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(ad), _ptr(q), _ptr(query_adapter),
+        _ptr(seq_query_start), int(q.shape[0]), int(max_queries_per_seq), _ptr(out), _stream_ptr(stream)))
 
 
 def lra_attn_prefill(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor],

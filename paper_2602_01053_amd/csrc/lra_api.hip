@@ -3,6 +3,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 
 #include "lra_attn.h"
 #include "lra_common.h"
@@ -222,6 +223,27 @@ static lra_status check_workspace(const Plan& pl, void* workspace, size_t worksp
   return LRA_OK;
 }
 
+// Workspace of lra_attn_decode_static: part of the device image, one copy per GPU.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the address a kernel may use
+// is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[LRA_STATIC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static lra_status scratch_of_current_device(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LRA_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* found = nullptr;
+    if (hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)) != hipSuccess || found == nullptr) return LRA_ERR_HIP;
+    g_scratch_ptr[dev] = found;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return LRA_OK;
+}
+
 }  // namespace lra
 
 using namespace lra;
@@ -238,10 +260,12 @@ size_t lra_workspace_bytes(const lra_shape* shape, const lra_cache* cache, int32
   return make_plan(shape, cache, prefill ? n_new : n_queries, prefill ? 1 : max_queries_per_seq, prefill).bytes;
 }
 
-lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,
-                           const void* q, const int32_t* query_adapter, const int32_t* seq_query_start,
-                           int32_t n_queries, int32_t max_queries_per_seq, void* out, void* workspace,
-                           size_t workspace_bytes, void* stream) {
+// Both decode entry points: checks, plan, then the workspace from the caller or, with
+// `use_static`, the library's own per-device buffer.
+static lra_status decode_call(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,
+                              const void* q, const int32_t* query_adapter, const int32_t* seq_query_start,
+                              int32_t n_queries, int32_t max_queries_per_seq, void* out, void* workspace,
+                              size_t workspace_bytes, bool use_static, void* stream) {
   lra_status st = check_common(shape, cache);
   if (st != LRA_OK) return st;
   if (!adapters || !q || !query_adapter || !seq_query_start || !out) return LRA_ERR_NULL;
@@ -251,6 +275,12 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
        reinterpret_cast<uintptr_t>(adapters->b_k) | reinterpret_cast<uintptr_t>(adapters->b_v)) & 15)
     return LRA_ERR_SHAPE;
   const Plan pl = make_plan(shape, cache, n_queries, max_queries_per_seq, false);
+  if (use_static) {
+    if (pl.bytes > LRA_STATIC_WORKSPACE_BYTES) return LRA_ERR_WORKSPACE;
+    st = scratch_of_current_device(&workspace);
+    if (st != LRA_OK) return st;
+    workspace_bytes = LRA_STATIC_WORKSPACE_BYTES;
+  }
   st = check_workspace(pl, workspace, workspace_bytes);
   if (st != LRA_OK) return st;
 
@@ -274,6 +304,21 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const
   if (g_profile_mode.load() == 1) return LRA_OK;  // measurement: key-streaming kernel alone
   if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
+}
+
+lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,
+                           const void* q, const int32_t* query_adapter, const int32_t* seq_query_start,
+                           int32_t n_queries, int32_t max_queries_per_seq, void* out, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  return decode_call(shape, cache, adapters, q, query_adapter, seq_query_start, n_queries, max_queries_per_seq, out,
+                     workspace, workspace_bytes, false, stream);
+}
+
+lra_status lra_attn_decode_static(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,
+                                  const void* q, const int32_t* query_adapter, const int32_t* seq_query_start,
+                                  int32_t n_queries, int32_t max_queries_per_seq, void* out, void* stream) {
+  return decode_call(shape, cache, adapters, q, query_adapter, seq_query_start, n_queries, max_queries_per_seq, out,
+                     nullptr, 0, true, stream);
 }
 
 lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, const lra_adapters* adapters,

@@ -56,6 +56,25 @@ def _prefill(lib, sh, c, ad, q=FAKE, seq=0, a=0, n_new=16, out=FAKE, ws=None, ws
                                 out, ws, ws_bytes, None)
 
 
+def test_static_workspace_entry_point_rejects_before_any_gpu_call(lib):
+    """lra_attn_decode_static runs the same checks, and refuses a call whose partial states would not fit
+    its fixed buffer, before it touches the GPU (there is none here)."""
+    sh, c, ad = _good()
+    call = lambda s, cc, a, nq=4, mq=4, q=FAKE: lib.lra_attn_decode_static(
+        ctypes.byref(s), ctypes.byref(cc), ctypes.byref(a), q, FAKE, FAKE, nq, mq, FAKE, None)
+    assert call(sh, c, ad, q=None) == 1
+    assert call(sh, c, ad, nq=0) == 2
+    sh.rank = 65
+    assert call(sh, c, ad) == 4
+    sh, c, ad = _good()
+    need = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4096, 4096, 0)
+    assert need > lra.binding.STATIC_WORKSPACE_BYTES
+    assert call(sh, c, ad, nq=4096, mq=4096) == 5
+    text = open(os.path.join(ROOT, "include", "lra_attn.h")).read()
+    assert re.search(r"#define LRA_STATIC_WORKSPACE_BYTES \(\(size_t\)(\d+) << 20\)", text).group(1) == str(
+        lra.binding.STATIC_WORKSPACE_BYTES >> 20)
+
+
 def test_rejects_bad_arguments_before_launch(lib):
     NULL, SHAPE, DTYPE, UNSUP, WS = 1, 2, 3, 4, 5
     sh, c, ad = _good()
