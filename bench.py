@@ -48,33 +48,64 @@ def _hip():
     return lib
 
 
-def kernel_seconds(lra, torch, launch, n):
-    """Average duration of the library's dominant kernel: n back-to-back launches of
-    that kernel alone (lra_set_profile_mode(1)) between two HIP events recorded on the
-    stream the kernel runs on.  A HIP event pair costs about 6 us on this platform,
-    which is why the events bracket the batch and not each launch; the figure
-    includes the dispatch gap between consecutive launches."""
+MIN_KERNEL_LAUNCHES = 200     # launches between one pair of events when a kernel is timed alone
+MIN_TIMED_SECONDS = 0.02      # a timed region is repeated until it is at least this long
+
+
+def graph_seconds(torch, launch, n, min_seconds=MIN_TIMED_SECONDS, max_replays=2000):
+    """Seconds per launch of `launch(i, stream)`, i = 0..n-1, enqueued back to back: the n calls are
+    captured into a HIP graph (so that no Python or ctypes time sits between two launches; a decode
+    step is shorter than that overhead) and the graph is replayed between two HIP events on the
+    stream it runs on, as often as it takes to fill min_seconds.  Returns (seconds per launch,
+    launches timed).  A HIP event pair costs about 6 us here, which is why events bracket whole
+    replays and never a single launch."""
     hip = _hip()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for i in range(min(n, 3)):
+            launch(i, side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for i in range(n):
+            launch(i, side)
+    graph.replay()
+    torch.cuda.synchronize()
     stream = torch.cuda.current_stream().cuda_stream or None
     e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
     assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
-    old = lra.lra_set_profile_mode(1)
+    ms = ctypes.c_float()
+    replays, total, done = 1, 0.0, 0
     try:
-        for i in range(min(n, 50)):
-            launch(i)
-        torch.cuda.synchronize()
-        assert hip.hipEventRecord(e0, stream) == 0
-        for i in range(n):
-            launch(i)
-        assert hip.hipEventRecord(e1, stream) == 0
-        hip.hipEventSynchronize(e1)
-        ms = ctypes.c_float()
-        assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+        while True:
+            assert hip.hipEventRecord(e0, stream) == 0
+            for _ in range(replays):
+                graph.replay()
+            assert hip.hipEventRecord(e1, stream) == 0
+            hip.hipEventSynchronize(e1)
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+            total, done = ms.value * 1e-3, replays
+            if total >= min_seconds or replays >= max_replays:
+                break
+            replays = min(max_replays, max(replays * 2, int(replays * min_seconds / max(total, 1e-6)) + 1))
     finally:
-        lra.lra_set_profile_mode(old)
         hip.hipEventDestroy(e0)
         hip.hipEventDestroy(e1)
-    return ms.value * 1e-3 / n
+        del graph
+    return total / (done * n), done * n
+
+
+def kernel_seconds(lra, torch, launch, n=MIN_KERNEL_LAUNCHES):
+    """Average duration of the library's dominant kernel: at least MIN_KERNEL_LAUNCHES back-to-back
+    launches of that kernel alone (lra_set_profile_mode(1): the call enqueues nothing else), timed by
+    graph_seconds.  The figure includes the dispatch gap between consecutive launches."""
+    n = max(n, MIN_KERNEL_LAUNCHES)
+    old = lra.lra_set_profile_mode(1)
+    try:
+        sec, _ = graph_seconds(torch, launch, n)
+    finally:
+        lra.lra_set_profile_mode(old)
+    return sec
 
 
 def machine_ceilings(torch, lra):
@@ -118,6 +149,23 @@ def machine_ceilings(torch, lra):
                     "throughout and four pseudo-random registers in rotation; measured in this run"}
 
 
+def stream_read_at_size(torch, lra, nbytes):
+    """What the plain streaming-read probe reaches on a buffer of the workload's own size, launch
+    for launch, taken in turn from enough distinct buffers that every launch reads from HBM: the
+    ceiling a call that moves this many bytes can be held against (launch, ramp-up and drain
+    included), unlike the 1.5 GB figure."""
+    dev = torch.device("cuda:0")
+    nbytes = (int(nbytes) + 255) // 256 * 256
+    k = int(math.ceil(COLD_BYTES / nbytes)) + 1
+    pool = torch.empty(k * nbytes, dtype=torch.uint8, device=dev)
+    pool.fill_(1)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    bufs = [pool[i * nbytes:(i + 1) * nbytes] for i in range(k)]
+    sec, _ = graph_seconds(torch, lambda i, st: lra.lra_probe_stream_read(bufs[i % k], sink, st), max(MIN_KERNEL_LAUNCHES, 4 * k))
+    del bufs, pool
+    return sec
+
+
 def _load_traffic(name):
     """HBM bytes per launch from committed rocprofv3 --pmc summaries, if any."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
@@ -156,7 +204,9 @@ def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None, 
         for i in range(n_steps):
             copies[i % n_copies if cold else 0].decode()
 
-    def timed(n_steps, cold):
+    def timed_loop(n_steps, cold):
+        """Exactly n_steps calls from a Python loop between two synchronisations (includes the
+        interpreter's and the binding's time per call)."""
         run(warmup, cold)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -164,10 +214,19 @@ def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None, 
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / n_steps
 
-    sec_cold = timed(steps, True)
-    sec_hot = timed(steps, False)
-    out = {"cold": kernel_seconds(lra, torch, lambda i: copies[i % n_copies].decode(), steps),
-           "hot": kernel_seconds(lra, torch, lambda i: copies[0].decode(), steps)}
+    def timed_graph(n_steps, cold):
+        """The same n_steps calls captured once into a HIP graph (what a serving loop does with a
+        decode step that is shorter than a host-side launch) and replayed until the timed region
+        is at least MIN_TIMED_SECONDS long."""
+        run(warmup, cold)
+        return graph_seconds(torch, lambda i, st: copies[i % n_copies if cold else 0].decode(st), n_steps)
+
+    loop_cold = timed_loop(steps, True)
+    sec_cold, timed_steps = timed_graph(steps, True)
+    sec_hot, _ = timed_graph(steps, False)
+    out = {"cold": kernel_seconds(lra, torch, lambda i, st: copies[i % n_copies].decode(st), steps),
+           "hot": kernel_seconds(lra, torch, lambda i, st: copies[0].decode(st), steps),
+           "loop_cold": loop_cold, "timed_steps": timed_steps}
     return w, alg_bytes, sec_cold, sec_hot, out, n_copies
 
 
@@ -200,24 +259,33 @@ def value_only_decode(args, torch, lra, workloads):
             "kernel_frac_of_hbm_peak": round(alg / ksec["cold"] / 1e9 / HBM_PEAK_GBS, 4)}
 
 
+MIN_PREFILL_LAUNCHES = 50
+
+
 def bench_prefill(args, torch, lra, workloads):
+    """Config 3: at least MIN_PREFILL_LAUNCHES timed launches after at least 10 warm-up launches, whatever
+    --steps says (a call is one kernel of 0.6 ms; a handful of launches would time the clock ramp)."""
     from paper_2602_01053_amd.runner import DeviceWorkload
     dev = torch.device("cuda:0")
     w = workloads.config(3)
     flops = w.algorithmic_flops()
     dw = DeviceWorkload(w, dev)
     dw.alloc_workspace()
-    steps = max(3, min(args.steps // 10, 200))
-    for _ in range(max(2, min(args.warmup // 10, 20))):
+    launches = max(MIN_PREFILL_LAUNCHES, min(args.steps // 10, 200))
+    for _ in range(max(10, min(args.warmup // 10, 20))):
         dw.prefill()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for _ in range(launches):
         dw.prefill()
     torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / steps
-    ksec = kernel_seconds(lra, torch, lambda i: dw.prefill(), steps)
-    return w, flops, sec, ksec, steps
+    sec = (time.perf_counter() - t0) / launches
+    old = lra.lra_set_profile_mode(1)
+    try:
+        ksec, k_launches = graph_seconds(torch, lambda i, st: dw.prefill(st), 10, min_seconds=0.03)
+    finally:
+        lra.lra_set_profile_mode(old)
+    return w, flops, sec, ksec, launches, k_launches
 
 
 def bench_rotary_prefill(args, torch, lra, workloads):
@@ -228,8 +296,11 @@ def bench_rotary_prefill(args, torch, lra, workloads):
     w = workloads.config(3)
     dw = DeviceWorkload(w, torch.device("cuda:0"), key_rope_theta=500000.0)
     dw.alloc_workspace()
-    steps = max(3, min(args.steps // 10, 100))
-    ksec = kernel_seconds(lra, torch, lambda i: dw.prefill(), steps)
+    old = lra.lra_set_profile_mode(1)
+    try:
+        ksec, _ = graph_seconds(torch, lambda i, st: dw.prefill(st), 10, min_seconds=0.03)
+    finally:
+        lra.lra_set_profile_mode(old)
     tf = w.algorithmic_flops() / ksec / 1e12
     out = {"workload": w.name + " with key_rope_theta = 500000", "call": "lra_attn_prefill", "kernel_ms": round(ksec * 1e3, 4),
            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -241,12 +312,7 @@ def bench_rotary_prefill(args, torch, lra, workloads):
     dw2.alloc_workspace()
     for _ in range(5):
         dw2.decode()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(200):
-        dw2.decode()
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / 200
+    sec, _ = graph_seconds(torch, lambda i, st: dw2.decode(st), 100)
     out["decode"] = {"workload": w2.name + " with key_rope_theta = 500000", "call": "lra_attn_decode",
                      "us_per_call": round(sec * 1e6, 2), "GBps_of_the_plain_call's_bytes": round(w2.algorithmic_bytes() / sec / 1e9, 1),
                      "note": "same buffers every call (hot); keys are streamed once, L B_K is rotated per tile and agent in registers"}
@@ -429,6 +495,12 @@ def main():
                    "kv_heads": 8, "head_dim": 128, "rank": 16, "algorithmic_bytes": alg_bytes,
                    "cache_protocol": f"cold: {n_copies} rotating copies of K_base/V_base/L"},
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+        "timing": {"method": "the K calls captured once into a HIP graph, replays timed with HIP events until the "
+                             "timed region is at least 20 ms", "timed_steps": ksec["timed_steps"],
+                   "python_loop_ms_per_step": round(ksec["loop_cold"] * 1e3, 6),
+                   "python_loop_GBps": round(alg_bytes / ksec["loop_cold"] / 1e9, 1),
+                   "python_loop_note": "exactly K calls issued one by one from Python between two synchronisations: "
+                                       "includes the interpreter and ctypes time per call"},
         "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": round(k_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(k_gbs / HBM_PEAK_GBS, 4),
                      "kernel_us": round(ksec["cold"] * 1e6, 3), "traffic": _load_traffic("decode_cfg2")},
@@ -437,11 +509,11 @@ def main():
                       "note": "same buffers every step: served largely by the memory-side cache"},
     }
     if not args.no_prefill:
-        wp, flops, psec, pksec, psteps = bench_prefill(args, torch, lra, workloads)
+        wp, flops, psec, pksec, psteps, pk_launches = bench_prefill(args, torch, lra, workloads)
         tf = flops / psec / 1e12
         ktf = flops / pksec / 1e12
         line["prefill"] = {
-            "workload": wp.name, "call": "lra_attn_prefill", "steps": psteps,
+            "workload": wp.name, "call": "lra_attn_prefill", "launches": psteps, "kernel_launches": pk_launches,
             "value": round(tf, 2), "unit": "TFLOP/s", "ms_per_step": round(psec * 1e3, 4),
             "algorithmic_flops": flops, "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
             "roofline": {"bound": "mfma", "achieved": round(ktf, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -457,6 +529,12 @@ def main():
     ceil = machine_ceilings(torch, lra)
     line["machine_ceilings"] = ceil
     line["roofline"]["frac_of_measured_ceiling"] = round(k_gbs / ceil["hbm_stream_read_GBps"], 4)
+    probe_s = stream_read_at_size(torch, lra, alg_bytes)
+    line["roofline"]["ceiling_at_this_size"] = {
+        "GBps": round(alg_bytes / probe_s / 1e9, 1), "us": round(probe_s * 1e6, 3),
+        "frac_of_it": round(probe_s / ksec["cold"], 4),
+        "note": "lra_probe_stream_read on buffers of the call's algorithmic bytes, rotating copies, same timing "
+                "method as kernel_us: a plain read of this size, launch included"}
     if "prefill" in line:
         line["prefill"]["roofline"]["frac_of_measured_ceiling"] = round(
             line["prefill"]["roofline"]["achieved"] / ceil["mfma_bf16_TFLOPs"], 4)

@@ -254,9 +254,11 @@ const char* lra_status_string(lra_status status);
 
 /*
  * Tuning and test hook: choose the kernel family for later calls from this
- * process.  0 = automatic (MFMA kernels for bf16, vector-ALU kernels for fp32),
- * 1 = force the vector-ALU kernels for every dtype.  Returns the previous value.
- * Does not affect results beyond rounding.
+ * process.  0 = automatic (MFMA kernels for bf16, vector-ALU kernels for fp32; among the
+ * MFMA kernels, decode calls on a contiguous cache with rank <= 32 that give every compute
+ * unit at most one workgroup take the form with two tile stages per wave and separate
+ * prologue waves), 1 = force the vector-ALU kernels for every dtype, 2 = automatic without
+ * that form.  Returns the previous value.  Does not affect results beyond rounding.
  */
 int32_t lra_set_kernel_variant(int32_t variant);
 

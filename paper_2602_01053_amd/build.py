@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblra_attn.so")
 
-SOURCES = ["lra_api.hip", "lra_generic.hip", "lra_decode_mfma.hip", "lra_prefill_mfma.hip", "lra_append.hip", "lra_probe.hip"]
+SOURCES = ["lra_api.hip", "lra_generic.hip", "lra_decode_mfma.hip", "lra_decode_stream.hip", "lra_prefill_mfma.hip", "lra_append.hip", "lra_probe.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",

@@ -10,6 +10,10 @@
 
 namespace lra {
 
+#ifdef LRA_TIMING
+static unsigned long long* g_timing = nullptr;  // instrumented test build only
+#endif
+
 std::atomic<int32_t> g_variant{0};
 std::atomic<int32_t> g_split_keys{0};
 std::atomic<int32_t> g_prefill_splits{0};  // 0 = automatic
@@ -72,7 +76,7 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   // The rotary key side: prefill runs on the tile-walking MFMA kernel, which completes a key
   // tile in LDS for its one adapter; decode on the rotary form of the split-KV kernel.
   const bool rope = sh->key_rope_theta > 0.f;
-  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() == 0 && sh->rank % 8 == 0;
+  pl.mfma = sh->dtype == LRA_BF16 && g_variant.load() != 1 && sh->rank % 8 == 0;
   if (prefill && pl.mfma) {
     // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
@@ -214,6 +218,9 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.n_splits = pl.n_splits;
   p.scale = sh->scale > 0.f ? sh->scale : 1.0f / std::sqrt(static_cast<float>(sh->head_dim));
   p.key_rope_theta = sh->key_rope_theta;
+#ifdef LRA_TIMING
+  p.timing = g_timing;
+#endif
 }
 
 static lra_status check_workspace(const Plan& pl, void* workspace, size_t workspace_bytes) {
@@ -297,7 +304,7 @@ static lra_status decode_call(const lra_shape* shape, const lra_cache* cache, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
   if (pl.mfma) {
-    if (launch_decode_mfma(p, pl.row_tiles, s) != hipSuccess) return LRA_ERR_HIP;
+    if (launch_decode_mfma(p, pl.row_tiles, g_variant.load() != 2, s) != hipSuccess) return LRA_ERR_HIP;
   } else {
     if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   }
@@ -351,7 +358,7 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
   if (pl.short_prefill) {
-    if (launch_decode_mfma(p, pl.row_tiles, s) != hipSuccess) return LRA_ERR_HIP;
+    if (launch_decode_mfma(p, pl.row_tiles, g_variant.load() != 2, s) != hipSuccess) return LRA_ERR_HIP;
     if (g_profile_mode.load() == 1) return LRA_OK;
     if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
     return LRA_OK;
@@ -424,7 +431,7 @@ const char* lra_status_string(lra_status status) {
   return "unknown status";
 }
 
-int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant == 1 ? 1 : 0); }
+int32_t lra_set_kernel_variant(int32_t variant) { return g_variant.exchange(variant == 1 || variant == 2 ? variant : 0); }
 
 int32_t lra_set_prefill_splits(int32_t splits) { return g_prefill_splits.exchange(splits < 0 ? 0 : splits); }
 
@@ -444,5 +451,13 @@ int32_t lra_set_decode_split_keys(int32_t keys) { return g_split_keys.exchange(k
 
 
 int32_t lra_set_profile_mode(int32_t mode) { return g_profile_mode.exchange(mode == 1 ? 1 : 0); }
+
+#ifdef LRA_TIMING
+// instrumented test build only
+lra_status lra_debug_set_timing(void* buffer) {
+  lra::g_timing = static_cast<unsigned long long*>(buffer);
+  return LRA_OK;
+}
+#endif
 
 }  // extern "C"

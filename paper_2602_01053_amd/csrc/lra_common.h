@@ -41,6 +41,9 @@ struct Params {
   int32_t split_keys, n_splits;
   float scale;
   float key_rope_theta;  // > 0: the key-side adapter contribution is rotated by its token's position
+#ifdef LRA_TIMING
+  unsigned long long* timing;  // instrumented test build only: per-wave phase stamps
+#endif
 };
 
 typedef uint16_t bf16_t;
@@ -97,7 +100,9 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
 hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s);
 int decode_mfma_row_tiles(int rows_needed);
 int decode_mfma_rope_slots(int rank);
-hipError_t launch_decode_mfma(const Params& p, int row_tiles, hipStream_t s);
+hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, hipStream_t s);
+bool decode_stream_applies(const Params& p, int row_tiles, int n_cus);
+hipError_t launch_decode_stream(const Params& p, int row_tiles, hipStream_t s);
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s);
 
 // Arguments of the cache-append producer kernel.

@@ -1,0 +1,591 @@
+// Split-KV decode kernel for calls that give every compute unit at most one workgroup
+// (bf16, gfx950): one sequence in a contiguous cache, rank <= 32, no rotary key side.
+//
+// Same arithmetic and data layout as decode_mfma_kernel (the inner loop of Alg. 1 with the
+// App. D.1 key-side reordering, scores computed transposed, all agents x GQA rows of a kv
+// head in the N dimension of v_mfma_f32_16x16x32_bf16); what differs is the schedule.  A call
+// of this size (tens of MB) is a chain of latencies, not a stream, so the kernel is built
+// around one rule: every byte of K_base / V_base / L is requested as early as the LDS can
+// take it, and nothing stands between the kernel's first instruction and its first request
+// that the request does not need.
+//   - A workgroup owns the whole LDS of its CU.  Waves 0-3 stream: each has TWO tile stages
+//     (2 x 32 keys) and requests both before it does anything else; the requests are
+//     hand-issued buffer_load ... lds, retire in order, and are waited for by hand-placed
+//     s_waitcnt vmcnt(N) with the number of younger requests - K and L of a tile before its V,
+//     so the scores and the softmax of a tile run while its V rows are still on their way.
+//   - Waves 4-7 are the prologue: they load Q and the B_K rows of the workgroup's agents
+//     into registers with ordinary loads (their own request counters: nothing of theirs
+//     queues in front of a tile), form Qt = Q B_K^T by MFMA and leave Q and Qt in LDS in
+//     operand-ready order.  One barrier later the streaming waves pick both up; by then their
+//     first tile has not landed yet.  The prologue waves then touch the B_V rows the merge
+//     kernel will need and wait at the final barrier.
+//   - All divisions by the row padding (a power of two) are shifts; the addresses of the
+//     LDS reads are formed after the requests have left.
+//   - The four streaming waves merge their states with one barrier (each deposits its
+//     unscaled state and its maxima, then sums a quarter of the blocks with the
+//     flash-decoding weights, in wave order).
+#include "lra_common.h"
+#include "lra_decode_util.h"
+
+namespace lra {
+
+#ifdef LRA_TIMING
+#define LRA_STAMP(k) do { unsigned long long t_; asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t_)); tt[k] = t_; } while (0)
+#define LRA_STAMP_DECL unsigned long long tt[12] = {0,0,0,0,0,0,0,0,0,0,0,0}
+#define LRA_STAMP_FLUSH() do { if (p.timing && lane == 0) { \
+    unsigned long long* o_ = p.timing + ((static_cast<size_t>(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 128 + wave * 16; \
+    for (int i_ = 0; i_ < 12; ++i_) o_[i_] = tt[i_]; \
+    o_[12] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | ((4 - 1) << 11)); \
+    o_[13] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | ((32 - 1) << 11)); } } while (0)
+#else
+#define LRA_STAMP(k)
+#define LRA_STAMP_DECL
+#define LRA_STAMP_FLUSH()
+#endif
+
+// LDS bytes of one workgroup of decode_stream_kernel<D, RT>.
+constexpr int decode_stream_lds_bytes(int D, int RT) {
+  return 4 * 2 * (2 * 32 * D * 2 + 32 * 32 * 2) + RT * 16 * D * 2 + RT * 1024;
+}
+
+template <int D, int RT, bool HAS_BK, bool CAUSAL>
+__global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
+  constexpr int NW = 4;            // streaming waves; waves NW .. 2 NW - 1 are the prologue waves
+  constexpr int RP = 32;           // padded rank
+  constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
+  constexpr int DB = D / 16;       // 16-wide output blocks over d
+  constexpr int RB = RP / 16;      // 16-wide output blocks over the rank
+  constexpr int KCH = D / 8;       // 16-byte chunks per K/V row
+  constexpr int RCH = RP / 8;      // 16-byte chunks per L row in LDS
+  constexpr int KROWS = 64 / KCH;  // K/V rows one wave-wide request moves
+  constexpr int KVL = 32 / KROWS;  // requests per 32-key K (or V) tile
+  constexpr int LROWS = 64 / RCH;
+  constexpr int LL = 32 / LROWS;
+  constexpr int TL = 2 * KVL + LL; // requests of one tile, in the order K, L, V
+  constexpr int KV_BYTES = 32 * D * 2;
+  constexpr int L_BYTES = 32 * RP * 2;
+  constexpr int STAGE_BYTES = 2 * KV_BYTES + L_BYTES;
+  constexpr int WAVE_BYTES = 2 * STAGE_BYTES;
+  constexpr int ROW_BYTES = D * 2;
+  constexpr int MAXIT = 2;                     // Qt items per prologue wave and row tile: 4 slots x 2 rho blocks over 4 waves
+  constexpr int Q_BYTES = RT * KS * 1024;      // Q as B operands: 16 bytes per lane, k-step and row tile
+  constexpr int QT_BYTES = RT * 1024;
+  constexpr int NBLK = DB + RB;                                // f32x4 blocks per lane and row tile
+  constexpr int SLOT_BYTES = RT * (NBLK * 1024 + 512);         // merge slot of a wave: blocks, then (m, l) pairs
+  static_assert(SLOT_BYTES <= WAVE_BYTES, "a wave's merge slot lives in its own tile region");
+  static_assert(NW * WAVE_BYTES + Q_BYTES + QT_BYTES == decode_stream_lds_bytes(D, RT), "LDS accounting");
+  static_assert(NW * WAVE_BYTES + Q_BYTES + QT_BYTES <= 160 * 1024, "LDS of one CU");
+
+  __shared__ __align__(16) unsigned char smem[NW * WAVE_BYTES];
+  __shared__ __align__(16) unsigned char q_lds[Q_BYTES];
+  __shared__ __align__(16) unsigned char qt_lds[QT_BYTES];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ln = lane & 15, lg = lane >> 4;
+  const bool helper = wave >= NW;
+  LRA_STAMP_DECL;
+  LRA_STAMP(0);
+  // kv head is the fastest grid index: workgroups go round-robin over the XCDs, so with 8 kv
+  // heads all workgroups of a head run on one XCD and share Q, B_K and L in its L2
+  const int h = blockIdx.x, split = blockIdx.y, rg = blockIdx.z;
+  const int t = CAUSAL ? p.seq_index : 0;                      // contiguous caches hold one sequence
+  const int32_t len_t = CONST_I32(p.seq_lens)[t];
+  const int n_q = CAUSAL ? p.n_new : p.n_queries;
+  const int GP = p.group_pad, G = p.group, r = p.rank;
+  const int gps = __builtin_ctz(GP);                           // GP is 4, 8 or 16
+  const int row0 = rg * RT * 16;
+  if (row0 >= (n_q << gps)) return;
+  // adapters of the agent slots of the row tiles (wave-uniform), -1 for an empty slot
+  int a_slot[RT][4];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int si = 0; si < 4; ++si) {
+      const int slot = ((row0 + rt * 16) >> gps) + si;
+      const bool live = si < (16 >> gps) && slot < n_q;
+      int a = -1;
+      if (live) a = CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[slot];
+      a_slot[rt][si] = (a >= 0 && a < p.n_adapters) ? a : -1;  // an id outside the table counts as no adapter
+    }
+  auto slot_adapter = [&](int rt, int si) {
+    return si == 0 ? a_slot[rt][0] : (si == 1 ? a_slot[rt][1] : (si == 2 ? a_slot[rt][2] : a_slot[rt][3]));
+  };
+  const int n_t = min(len_t, p.max_seq_len);
+  const int j0 = split * p.split_keys;
+  // output row (query x Hq + q head) this lane stands for in row tile rt (-1: padding row);
+  // its workspace slot is row * n_splits + split
+  auto row_index = [&](int rt) -> int {
+    const int R = row0 + rt * 16 + ln;
+    const int slot_q = R >> gps, gg = R & (GP - 1);
+    if (!(slot_q < n_q && gg < G)) return -1;
+    return slot_q * p.n_q_heads + h * G + gg;
+  };
+  if (j0 >= n_t) {
+    // a split past the end of the sequence: leave an empty state (zero row sum), which is
+    // all the merge kernel looks at; the O and O_lr rows of the slot stay unwritten
+    if (wave == 0 && lg == 0) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const int row = row_index(rt);
+        if (row >= 0) {
+          const int64_t slot = static_cast<int64_t>(row) * p.n_splits + split;
+          p.part_ml[slot * 2 + 0] = -INFINITY;
+          p.part_ml[slot * 2 + 1] = 0.f;
+        }
+      }
+    }
+    return;
+  }
+  LRA_STAMP(1);
+
+  if (helper) {
+    // ===================== prologue waves: Q operands and Qt = Q B_K^T =====================
+    const int hw = wave - NW;
+    // qb[rt][ks]: lane (row ln of tile rt, k = 32ks + 8lg + e), e = 0..7: the B operand of S^T
+    // and of Qt^T = B_K Q^T
+    bf16x8 qb[RT][KS];
+    {
+      const __amdgpu_buffer_rsrc_t rs_q = make_rsrc(p.q, static_cast<uint32_t>(n_q) * p.n_q_heads * D * 2);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const int R = row0 + rt * 16 + ln;
+        const int slot = R >> gps, gg = R & (GP - 1);
+        const bool valid = slot < n_q && gg < G;
+        const uint32_t off = valid ? static_cast<uint32_t>((slot * p.n_q_heads + h * G + gg) * ROW_BYTES + lg * 16) : kOob;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qb[rt][ks] = as_bf16x8(buf_load16(rs_q, off, ks * 64));
+      }
+    }
+    if constexpr (HAS_BK) {
+      // Item idx = hw + it*NW of row tile rt is (agent slot si, rho block cb); this lane holds row
+      // rho = 16cb + ln of B_K^a, columns h*D + 32ks + 8lg ..: the A operand of Qt^T.  Rows beyond
+      // the rank and the rows of empty slots lie outside the resource and arrive as zeros.
+      const int S = 16 >> gps;         // agent slots per 16-row tile
+      const int ncb = (r + 15) >> 4;   // rho blocks: 1 or 2
+      const int n_items = S * ncb;
+      const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
+      const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
+      uint4 bt4[RT][MAXIT][KS];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int it = 0; it < MAXIT; ++it) {
+          const int idx = hw + it * NW;
+          const int si = ncb == 1 ? idx : idx >> 1, cb = ncb == 1 ? 0 : idx & 1;
+          const int a = slot_adapter(rt, si);
+          const bool live = idx < n_items && a >= 0;
+          const uint32_t bytes = live ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u;
+          const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(bkg + static_cast<int64_t>(live ? a : 0) * r * ldb + h * D, bytes);
+          const uint32_t off = static_cast<uint32_t>((cb * 16 + ln) * ldb * 2 + lg * 16);
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) bt4[rt][it][ks] = buf_load16(rs_b, off, ks * 64);
+        }
+      // The streaming waves hold their requests back until these loads have left: the memory
+      // path of a CU takes requests in order, and behind 144 KB of tile requests Q and B_K would
+      // arrive last.  (A bare barrier: nothing is exchanged yet, it only orders the issue.)
+      __builtin_amdgcn_s_barrier();
+      // Qt^T block (rho block cb, tile rt) in C layout: lane (rho = 16cb + 4lg + j, row ln).  Rows
+      // of a tile belong to 16/GP agents; each agent's product is kept only in its own rows
+      // (lanes).  Left in LDS in operand-ready form: the operand of lane l and tile rt is the 16
+      // bytes at (rt*64 + l)*16, elements e -> rho = 16(e/4) + 4lg + e%4 (the L operand of the
+      // loop uses the same order).  Every lane is written: every row belongs to some slot.
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int it = 0; it < MAXIT; ++it) {
+          const int idx = hw + it * NW;
+          if (idx < n_items) {
+            const int si = ncb == 1 ? idx : idx >> 1, cb = ncb == 1 ? 0 : idx & 1;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bt4[rt][it][ks]), qb[rt][ks], acc, 0, 0, 0);
+            if ((ln >> gps) == si) {
+              unsigned char* dst = qt_lds + (rt * 64 + lane) * 16;
+              const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
+              if (ncb == 1)  // the second rho block lies beyond the rank: zeros
+                *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
+              else
+                *reinterpret_cast<uint2*>(dst + cb * 8) = pk;
+            }
+          }
+        }
+    }
+    if constexpr (!HAS_BK) __builtin_amdgcn_s_barrier();  // the Q loads have left (see above)
+    if (hw == 0) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          *reinterpret_cast<uint4*>(q_lds + ((rt * KS + ks) * 64 + lane) * 16) = __builtin_bit_cast(uint4, qb[rt][ks]);
+    }
+    LRA_STAMP(2);
+    __syncthreads();  // Q and Qt are in LDS
+    // One workgroup per (kv head, row group) touches the B_V rows the merge kernel will need
+    // (one 4-byte read per 128-byte line), so that they wait in this XCD's L2 instead of in
+    // HBM: prologue wave w takes agent slot w of every row tile.
+    int warm[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      warm[rt] = 0;
+      const int a = slot_adapter(rt, hw);
+      if (p.b_v != nullptr && split == min(1, p.n_splits - 1) && a >= 0) {
+        constexpr int LPR = D * 2 / 128;  // 128-byte lines per B_V row of one kv head
+        const int n_lines = r * LPR;      // <= 64
+        const char* bv = static_cast<const char*>(p.b_v) +
+                         (static_cast<int64_t>(a) * r * p.n_kv_heads * D + static_cast<int64_t>(h) * D) * 2;
+        if (lane < n_lines)
+          warm[rt] = *reinterpret_cast<const int*>(bv + static_cast<int64_t>(lane / LPR) * p.n_kv_heads * D * 2 + (lane % LPR) * 128);
+      }
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) asm volatile("" ::"v"(warm[rt]));
+    __syncthreads();  // the streaming waves' merge barrier
+    LRA_STAMP(11);
+    LRA_STAMP_FLUSH();
+    return;
+  }
+
+  // ===================== streaming waves =====================
+  const int j1 = min(j0 + p.split_keys, n_t);
+  const int kpw = p.split_keys / NW;  // multiple of 32
+  const int jw0 = j0 + wave * kpw;
+  const int jw1 = max(jw0, min(jw0 + kpw, j1));  // == jw0 for a wave without keys
+
+  unsigned char* wave_lds = smem + wave * WAVE_BYTES;
+  const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
+  const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
+
+  // ---- requests: per-lane offsets and buffer resources ----
+  // LDS swizzles (XOR on the 16-byte chunk index of a row; the LDS serves 256 bytes per clock):
+  //   K (ds_read_b128, 16 rows per clock)           chunk ^ (row & 15)        | chunk ^ ((row >> 1) & 7)
+  //   V (ds_read_b64_tr_b16, 8 rows per clock)      chunk ^ ((row & 7) << 1)  | chunk ^ (((row >> 1) & 3) << 1)
+  // Lane l of request i lands at LDS row i*KROWS + l/KCH, physical chunk l%KCH, and therefore
+  // fetches the logical chunk (l%KCH) ^ swizzle(row); the swizzle repeats with period
+  // 16/KROWS (K) and 8/KROWS (V) in i.
+  auto swz_k = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
+  auto swz_v = [](int row) { return D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1); };
+  constexpr int KPER = KROWS == 4 ? 4 : 2, VPER = KROWS == 4 ? 2 : 1;
+  const int rr = lane / KCH, pc = lane % KCH;
+  uint32_t k_voff[KPER], v_voff[VPER], l_voff;
+#pragma unroll
+  for (int q = 0; q < KPER; ++q) k_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_k(q * KROWS + rr)) << 4);
+#pragma unroll
+  for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
+  {
+    const int lrow = lane / RCH, lpc = lane % RCH;
+    const int lch = lpc ^ ((lrow >> 1) & (RCH - 1));
+    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * r2 + (lch << 4) : kOob;
+  }
+  // one resource per wave covering exactly its keys [jw0, jw1)
+  u32x4 rs_k, rs_v, rs_l;
+  {
+    const int nk = jw1 - jw0;
+    const int64_t base = static_cast<int64_t>(h) * p.kv_head_stride + static_cast<int64_t>(jw0) * p.kv_token_stride;
+    const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
+    rs_k = make_rsrc_words(static_cast<const bf16_t*>(p.k_base) + base, bytes);
+    rs_v = make_rsrc_words(static_cast<const bf16_t*>(p.v_base) + base, bytes);
+    rs_l = make_rsrc_words(static_cast<const bf16_t*>(p.l) + static_cast<int64_t>(jw0) * r, static_cast<uint32_t>(nk) * r2);
+  }
+  // K_base / V_base requests are non-temporal when this workgroup is the only reader of its
+  // keys; with several row groups per kv head the others find the tiles in L2
+  const bool stream_kv = p.row_groups == 1;
+  // HBM -> LDS for the 32-key step starting at token j of the sequence, into stage st of this
+  // wave: K rows, then L rows, then V rows
+  auto issue_tile = [&](int j, int st) __attribute__((always_inline)) {
+    unsigned char* ks = wave_lds + st * STAGE_BYTES;
+    unsigned char* vs = ks + KV_BYTES;
+    unsigned char* ls = vs + KV_BYTES;
+    const uint32_t s0 = static_cast<uint32_t>(j - jw0);
+    if (stream_kv) {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<true>(rs_k, ks + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
+    } else {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<false>(rs_k, ks + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
+    }
+#pragma unroll
+    for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls + i * 1024, l_voff, (s0 + i * LROWS) * r2);
+    if (stream_kv) {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<true>(rs_v, vs + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
+    } else {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<false>(rs_v, vs + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
+    }
+  };
+  __builtin_amdgcn_s_barrier();  // the prologue waves' loads have left: theirs go first
+  if (jw0 < jw1) issue_tile(jw0, 0);
+  if (jw0 + 32 < jw1) issue_tile(jw0 + 32, 1);
+  LRA_STAMP(2);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- addresses of the LDS reads ----
+  // K rows as A operand of S^T: key = 16tt + ln, logical chunk 4ks + lg at chunk ^ swz_k(key):
+  // row offset, swizzle and lg sit in disjoint address bits: k_pre ^ (ks << 6) + tt * 16 rows.
+  const int k_pre = ln * ROW_BYTES + ((swz_k(ln) ^ lg) << 4);
+  // V^T as A operand of O^T: this lane addresses row ka (+16tt) of the tile, logical chunk
+  // 2b + c0 (+ half sub): address v_pre ^ (b << 5) + tt * 16 rows.
+  const int ka = 4 * lg + (ln >> 2);
+  const int v_pre = ka * ROW_BYTES + ((swz_v(ka) + ((ln & 3) >> 1)) << 4) + (ln & 1) * 8;
+  int l_rd[2];   // L rows as A operand of S^T: two 8-byte pieces
+  int lt_rd[RB]; // L^T as A operand of Olr^T
+  {
+    const int swz_s = (ln >> 1) & (RCH - 1);
+#pragma unroll
+    for (int pcs = 0; pcs < 2; ++pcs) {
+      const int ch = 2 * pcs + (lg >> 1);
+      l_rd[pcs] = ln * (2 * RP) + ((ch ^ swz_s) << 4) + (lg & 1) * 8;
+    }
+    const int swz_t = (ka >> 1) & (RCH - 1);
+#pragma unroll
+    for (int b = 0; b < RB; ++b) {
+      const int ch = 2 * b + ((ln & 3) >> 1);
+      lt_rd[b] = ka * (2 * RP) + ((ch ^ swz_t) << 4) + (ln & 1) * 8;
+    }
+  }
+  // last key each of this lane's rows may see (causal form only)
+  int lim[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) lim[rt] = n_t - n_q + min((row0 + rt * 16 + ln) >> gps, n_q - 1);
+  const int lim_first = n_t - n_q + (row0 >> gps);  // the smallest of them in this workgroup
+  int out_row[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) out_row[rt] = row_index(rt);
+
+  f32x4 o_acc[RT][DB], lr_acc[RT][RB];
+  float m_run[RT], l_run[RT];  // m_run in base-2 units of the scaled score
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    m_run[rt] = -INFINITY;
+    l_run[rt] = 0.f;
+#pragma unroll
+    for (int b = 0; b < DB; ++b) o_acc[rt][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int b = 0; b < RB; ++b) lr_acc[rt][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const float sc = p.scale * 1.44269504088896340736f;
+
+  __syncthreads();  // the prologue waves have left Q and Qt in LDS
+  bf16x8 qb[RT][KS], qtb[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qb[rt][ks] = as_bf16x8(lds_read16(q_lds + ((rt * KS + ks) * 64 + lane) * 16));
+    qtb[rt] = as_bf16x8(HAS_BK ? lds_read16(qt_lds + (rt * 64 + lane) * 16) : make_uint4(0u, 0u, 0u, 0u));
+  }
+  LRA_STAMP(3);
+
+  // ===================== main loop =====================
+  // One 32-key step on the tile in stage st.  `younger` = the tile of the other stage has been
+  // requested after this one (TL requests that may stay outstanding).
+  auto step = [&](int j, int st, bool younger) __attribute__((always_inline)) {
+    const unsigned char* ks_lds = wave_lds + st * STAGE_BYTES;
+    const unsigned char* vs_lds = ks_lds + KV_BYTES;
+    const unsigned char* ls_lds = vs_lds + KV_BYTES;
+    // K and L rows of the tile have landed when only its V requests (and the younger tile's) are out
+    if (younger) wait_vm<TL + KVL>(); else wait_vm<KVL>();
+    lds_fence();
+    f32x4 s[2][RT];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) s[tt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a = as_bf16x8(lds_read16(ks_lds + (k_pre ^ (ks << 6)) + tt * 16 * ROW_BYTES));
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+          s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[rt][ks], s[tt][rt], 0, 0, 0);
+      }
+      if constexpr (HAS_BK) {
+        const uint2 lo = lds_read8(ls_lds + l_rd[0] + tt * 16 * (2 * RP));
+        const uint2 hi = lds_read8(ls_lds + l_rd[1] + tt * 16 * (2 * RP));
+        const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+          s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qtb[rt], s[tt][rt], 0, 0, 0);
+      }
+    }
+    // online softmax; element (tt, jj) of this lane is key j + 16tt + 4lg + jj of row ln
+    const bool tail = j + 32 > jw1 || (CAUSAL && j + 31 > lim_first);
+    bf16x8 pb[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      if (tail) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const int key = j + tt * 16 + lg * 4 + jj;
+            if (key >= jw1 || (CAUSAL && key > lim[rt])) s[tt][rt][jj] = -INFINITY;
+          }
+      }
+      float mx = fmaxf(fmaxf(fmaxf(s[0][rt][0], s[0][rt][1]), fmaxf(s[0][rt][2], s[0][rt][3])),
+                       fmaxf(fmaxf(s[1][rt][0], s[1][rt][1]), fmaxf(s[1][rt][2], s[1][rt][3])));
+      mx = max_over_lane_groups(mx) * sc;  // sc > 0
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[rt]) != 0) {
+        const float m_new = fmaxf(m_run[rt], mx);
+        // causal form: a row may have seen no key yet (both maxima -inf)
+        const float alpha = (CAUSAL && m_new == -INFINITY) ? 1.f : fast_exp2(m_run[rt] - m_new);
+        m_run[rt] = m_new;
+        l_run[rt] *= alpha;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) o_acc[rt][b] *= alpha;
+#pragma unroll
+        for (int b = 0; b < RB; ++b) lr_acc[rt][b] *= alpha;
+      }
+      const float nm = (CAUSAL && m_run[rt] == -INFINITY) ? 0.f : -m_run[rt];
+      float pe[8];
+      float sum = 0.f;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const float e = fast_exp2(fmaf(s[tt][rt][jj], sc, nm));
+          pe[tt * 4 + jj] = e;
+          sum += e;
+        }
+      l_run[rt] += sum;
+      pb[rt] = as_bf16x8(make_uint4(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]), pack_bf16x2(pe[4], pe[5]),
+                                    pack_bf16x2(pe[6], pe[7])));
+    }
+    // Olr^T += L^T P^T (L has landed with K), then the V rows: O^T += V^T P^T
+#pragma unroll
+    for (int b = 0; b < RB; ++b) {
+      const unsigned char* src = ls_lds + lt_rd[b];
+      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 16 * (2 * RP)));
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        lr_acc[rt][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rt], lr_acc[rt][b], 0, 0, 0);
+    }
+    if (younger) wait_vm<TL>(); else wait_vm0();
+    lds_fence();
+#pragma unroll
+    for (int b = 0; b < DB; ++b) {
+      const unsigned char* src = vs_lds + (v_pre ^ (b << 5));
+      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 16 * ROW_BYTES));
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        o_acc[rt][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rt], o_acc[rt][b], 0, 0, 0);
+    }
+    // the next tile of this stage overwrites this one: every LDS read above must have returned
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    lds_fence();
+  };
+
+  // Stage 0 holds tile j, stage 1 tile j + 32 (where the wave has that many keys); after a step
+  // the tile two steps ahead, if there is one, is requested into the stage it frees.
+  if (jw0 < jw1) {
+    int j = jw0;
+    while (true) {
+      const bool has1 = j + 32 < jw1;
+      step(j, 0, has1);
+      if (j == jw0) LRA_STAMP(4);
+      const bool has2 = j + 64 < jw1;
+      if (has2) issue_tile(j + 64, 0);
+      if (!has1) break;
+      step(j + 32, 1, has2);
+      if (j + 96 < jw1) issue_tile(j + 96, 1);
+      if (!has2) break;
+      j += 64;
+    }
+  }
+  LRA_STAMP(5);
+
+  // ===================== merge the streaming waves (one barrier) =====================
+  // Every wave deposits its state as it stands - blocks as 16 bytes per lane, then (m, l) per
+  // lane - in its own tile region (nothing of its own is outstanding any more); after the
+  // barrier wave w sums blocks w, w + 4, ... of all four states with the weights
+  // 2^(m_w' - max m), in wave order, and stores them.
+  {
+    unsigned char* mine = wave_lds;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      unsigned char* base = mine + rt * (NBLK * 1024 + 512);
+#pragma unroll
+      for (int b = 0; b < DB; ++b) *reinterpret_cast<f32x4*>(base + b * 1024 + lane * 16) = o_acc[rt][b];
+#pragma unroll
+      for (int b = 0; b < RB; ++b) *reinterpret_cast<f32x4*>(base + (DB + b) * 1024 + lane * 16) = lr_acc[rt][b];
+      const float lsum = sum_over_lane_groups(l_run[rt]);
+      *reinterpret_cast<f32x2*>(base + NBLK * 1024 + lane * 8) = f32x2{m_run[rt], lsum};
+    }
+  }
+  __syncthreads();
+  LRA_STAMP(6);
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    float wgt[NW], m_all = -INFINITY, l_all = 0.f;
+    f32x2 ml[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      ml[w] = *reinterpret_cast<const f32x2*>(smem + w * WAVE_BYTES + rt * (NBLK * 1024 + 512) + NBLK * 1024 + lane * 8);
+      m_all = fmaxf(m_all, ml[w][0]);
+    }
+    // m_all is finite (wave 0 always owns a key) unless a causal row sees none of this split
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      wgt[w] = ml[w][0] == -INFINITY ? 0.f : fast_exp2(ml[w][0] - m_all);
+      l_all = fmaf(wgt[w], ml[w][1], l_all);
+    }
+    if (out_row[rt] < 0) continue;
+    const int64_t slot = static_cast<int64_t>(out_row[rt]) * p.n_splits + split;
+#pragma unroll
+    for (int x = 0; x < NBLK; ++x) {
+      if ((x & (NW - 1)) != wave) continue;  // wave-uniform
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const f32x4 part = *reinterpret_cast<const f32x4*>(smem + w * WAVE_BYTES + rt * (NBLK * 1024 + 512) + x * 1024 + lane * 16);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) v[jj] = fmaf(wgt[w], part[jj], v[jj]);
+      }
+      if (x < DB) {
+        *reinterpret_cast<f32x4*>(p.part_o + slot * D + x * 16 + lg * 4) = v;
+      } else {
+        const int rho = (x - DB) * 16 + lg * 4;  // the rank is a multiple of 8: four entries are inside or outside together
+        if (rho < r) *reinterpret_cast<f32x4*>(p.part_lr + slot * r + rho) = v;
+      }
+    }
+    if (wave == NW - 1 && lg == 0) {
+      p.part_ml[slot * 2 + 0] = m_all * 0.69314718055994530942f;  // natural-log units
+      p.part_ml[slot * 2 + 1] = l_all;
+      if (split == 0) p.part_adapter[out_row[rt]] = max(slot_adapter(rt, ln >> gps), 0);
+    }
+  }
+  LRA_STAMP(11);
+  LRA_STAMP_FLUSH();
+}
+
+// Whether a decode launch can take decode_stream_kernel: contiguous cache, rank <= 32, no
+// rotary key side, at most one workgroup per compute unit.
+bool decode_stream_applies(const Params& p, int row_tiles, int n_cus) {
+  if (p.block_size != 0 || p.rank > 32 || (p.key_rope_theta > 0.f && p.b_k != nullptr)) return false;
+  if (row_tiles < 1 || row_tiles > 2) return false;
+  if (decode_stream_lds_bytes(p.head_dim, row_tiles) > 160 * 1024) return false;
+  const int64_t wgs = static_cast<int64_t>(p.n_kv_heads) * p.n_splits * p.row_groups;
+  return wgs <= n_cus;
+}
+
+template <int D, int RT>
+static hipError_t launch_stream2(const Params& p, dim3 grid, hipStream_t s) {
+  const dim3 block(512);
+  const bool has_bk = p.b_k != nullptr;
+  if (p.is_prefill) {
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, true, true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, false, true>), grid, block, 0, s, p);
+  } else {
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, true, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, false, false>), grid, block, 0, s, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_stream(const Params& p, int row_tiles, hipStream_t s) {
+  const dim3 grid(p.n_kv_heads, p.n_splits, p.row_groups);
+  if (p.head_dim == 128) return row_tiles == 1 ? launch_stream2<128, 1>(p, grid, s) : launch_stream2<128, 2>(p, grid, s);
+  return row_tiles == 1 ? launch_stream2<64, 1>(p, grid, s) : launch_stream2<64, 2>(p, grid, s);
+}
+
+}  // namespace lra

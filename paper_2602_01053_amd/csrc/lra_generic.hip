@@ -238,8 +238,18 @@ constexpr int kMergeUnroll = 8;  // splits per thread and pass
 // 5 take 12.7 us against 20.5 us; 256 rows of config 4 take 10.4 us against 9.3 us).
 constexpr int kMergeWaveRows = 1024;
 
+#ifdef LRA_TIMING
+#define LRA_MSTAMP(k) do { unsigned long long t_; asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t_)); mt[k] = t_; } while (0)
+#else
+#define LRA_MSTAMP(k)
+#endif
+
 template <typename T, int kMergeGroups>
 __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
+#ifdef LRA_TIMING
+  unsigned long long mt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+  LRA_MSTAMP(0);
   // Workgroups go round-robin over the XCDs; numbering them kv head first puts the rows of
   // kv head h on the XCD(s) where the streaming kernel wrote that head's partial states.
   const int Hq = p.n_q_heads, d = p.head_dim, r = p.rank;
@@ -256,6 +266,10 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   const int ns = p.n_splits;
   // (clamped: whatever the workspace holds, the B_V rows read below exist)
   const int a = min(max(p.part_adapter[row], 0), p.n_adapters - 1);
+#ifdef LRA_TIMING
+  asm volatile("" ::"v"(a));
+#endif
+  LRA_MSTAMP(1);
   const int64_t slot0 = static_cast<int64_t>(row) * p.n_splits;
   const float2* ml = reinterpret_cast<const float2*>(p.part_ml) + slot0;
   const float* po = p.part_o + slot0 * d + c;
@@ -294,9 +308,11 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
     }
   }
 
+  LRA_MSTAMP(2);
   big = wave_max(big);
   if ((tid & 63) == 0) red[tid >> 6] = big;
   __syncthreads();
+  LRA_MSTAMP(3);
   big = red[0];
 #pragma unroll
   for (int i = 1; i < 2 * kMergeGroups; ++i) big = fmaxf(big, red[i]);
@@ -323,6 +339,7 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
   }
   if (c < 64) olr_sh[gq][c] = olr;
   if (c == 0) ell_sh[gq] = ell;
+  LRA_MSTAMP(4);
   __syncthreads();
   // epilogue O += O_lr B_V: group g contributes its rows rho = g, g + kMergeGroups, ...
 #pragma unroll
@@ -347,6 +364,13 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
     }
     static_cast<T*>(p.out)[static_cast<int64_t>(row) * d + c] = from_f32<T>(o / ell);
   }
+  LRA_MSTAMP(5);
+#ifdef LRA_TIMING
+  if (p.timing && (tid & 63) == 0) {
+    unsigned long long* o_ = p.timing + 4096 * 128 + static_cast<size_t>(blockIdx.x) * 64 + (tid >> 6) * 8;
+    for (int i_ = 0; i_ < 6; ++i_) o_[i_] = mt[i_];
+  }
+#endif
 }
 
 // The same merge for calls with many rows: one wave per row (four rows, q heads of one kv

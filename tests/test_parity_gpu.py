@@ -17,7 +17,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.fixture(params=[0, 1], ids=["auto", "valu"])
+# 0: automatic choice (bf16: MFMA kernels, and among them the one-workgroup-per-CU streaming form of the
+# split-KV kernel wherever a call qualifies); 1: vector-ALU kernels; 2: MFMA kernels without the streaming form
+@pytest.fixture(params=[0, 1, 2], ids=["auto", "valu", "mfma_no_stream_form"])
 def variant(request):
     old = lra.lra_set_kernel_variant(request.param)
     yield request.param
