@@ -33,7 +33,7 @@ struct Plan {
   int split_keys;  // keys per split
   int n_splits;    // splits per sequence at max_seq_len
   int group_pad, row_tiles, row_groups;  // MFMA decode row packing
-  size_t off_ml, off_o, off_lr, off_adapter, bytes;
+  size_t off_ml, off_o, off_lr, off_adapter, off_qt, qt_bytes, bytes;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -181,6 +181,13 @@ static Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int m
   pl.off_lr = pl.off_o + align_up(slots * sh->head_dim * sizeof(float), 256);
   pl.off_adapter = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
   pl.bytes = pl.off_adapter + align_up(static_cast<size_t>(pl.rows) * sizeof(int32_t), 256);
+  // room for Qt of the whole call where the streaming form of the split-KV kernel would
+  // otherwise reload many B_K rows per workgroup (reserved whether or not the call has a B_K)
+  pl.off_qt = pl.bytes;
+  pl.qt_bytes = 0;
+  if (pl.mfma && c->block_size == 0 && !rope_split && g_variant.load() != 2)
+    pl.qt_bytes = decode_stream_qt_bytes(pl.group_pad, sh->rank, pl.row_tiles, pl.row_groups, sh->n_kv_heads);
+  pl.bytes += align_up(pl.qt_bytes, 256);
   return pl;
 }
 
@@ -199,6 +206,7 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.part_o = reinterpret_cast<float*>(ws + pl.off_o);
   p.part_lr = reinterpret_cast<float*>(ws + pl.off_lr);
   p.part_adapter = reinterpret_cast<int32_t*>(ws + pl.off_adapter);
+  p.qt_ws = (pl.qt_bytes > 0 && ad->b_k != nullptr) ? ws + pl.off_qt : nullptr;
   p.kv_token_stride = c->kv_token_stride;
   p.kv_head_stride = c->kv_head_stride;
   p.kv_block_stride = c->kv_block_stride;
@@ -304,7 +312,7 @@ static lra_status decode_call(const lra_shape* shape, const lra_cache* cache, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
   if (pl.mfma) {
-    if (launch_decode_mfma(p, pl.row_tiles, g_variant.load() != 2, s) != hipSuccess) return LRA_ERR_HIP;
+    if (launch_decode_mfma(p, pl.row_tiles, g_variant.load() != 2, g_profile_mode.load() == 1, s) != hipSuccess) return LRA_ERR_HIP;
   } else {
     if (launch_generic_partials(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
   }
@@ -358,7 +366,7 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = shape->dtype == LRA_BF16;
   if (pl.short_prefill) {
-    if (launch_decode_mfma(p, pl.row_tiles, g_variant.load() != 2, s) != hipSuccess) return LRA_ERR_HIP;
+    if (launch_decode_mfma(p, pl.row_tiles, g_variant.load() != 2, g_profile_mode.load() == 1, s) != hipSuccess) return LRA_ERR_HIP;
     if (g_profile_mode.load() == 1) return LRA_OK;
     if (launch_merge(p, bf16, pl.rows, s) != hipSuccess) return LRA_ERR_HIP;
     return LRA_OK;

@@ -28,6 +28,7 @@ struct Params {
   float* part_o;   // [rows][n_splits][d]
   float* part_lr;  // [rows][n_splits][r]
   int32_t* part_adapter;  // [rows]: adapter of the row's query, left by the first kernel for the merge
+  void* qt_ws;            // Qt = Q B_K^T of the whole call in MFMA operand order, or null (formed per workgroup)
   int64_t kv_token_stride, kv_head_stride, kv_block_stride;
   int32_t n_q_heads, n_kv_heads, group, head_dim, rank;
   int32_t group_pad;   // rows reserved per agent in the MFMA row tiles: 4, 8 or 16 (>= group)
@@ -100,9 +101,10 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
 hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s);
 int decode_mfma_row_tiles(int rows_needed);
 int decode_mfma_rope_slots(int rank);
-hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, hipStream_t s);
+hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, bool main_kernel_only, hipStream_t s);
 bool decode_stream_applies(const Params& p, int row_tiles, int n_cus);
-hipError_t launch_decode_stream(const Params& p, int row_tiles, hipStream_t s);
+hipError_t launch_decode_stream(const Params& p, int row_tiles, bool main_kernel_only, hipStream_t s);
+size_t decode_stream_qt_bytes(int group_pad, int rank, int row_tiles, int row_groups, int n_kv_heads);
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s);
 
 // Arguments of the cache-append producer kernel.

@@ -809,6 +809,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
     __syncthreads();
   }
 
+  LRA_STAMP(7);
   // ===================== wave 0 writes the workgroup's partial state =====================
   if (wave == 0) {
 #pragma unroll
@@ -834,6 +835,8 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   }
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) asm volatile("" ::"v"(warm[rt][0]), "v"(warm[rt][1]));
+  LRA_STAMP(8);
+  LRA_STAMP_FLUSH();
 }
 
 template <int D, int RT, int RP, bool CAUSAL>
@@ -876,9 +879,9 @@ static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
 // stay in registers): the row padding per query is at least 16 / this.
 int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 : kRopeSlots64); }
 
-hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, hipStream_t s) {
+hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, bool main_kernel_only, hipStream_t s) {
   // calls that give a compute unit at most one workgroup: the form with two tile stages per wave
-  if (allow_stream_form && decode_stream_applies(p, row_tiles, 256)) return launch_decode_stream(p, row_tiles, s);
+  if (allow_stream_form && decode_stream_applies(p, row_tiles, 256)) return launch_decode_stream(p, row_tiles, main_kernel_only, s);
   dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
   if (p.key_rope_theta > 0.f && p.b_k != nullptr) {
     if (row_tiles != 1 || (!p.is_prefill && 16 / p.group_pad > decode_mfma_rope_slots(p.rank))) return hipErrorInvalidValue;

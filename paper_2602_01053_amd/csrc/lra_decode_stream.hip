@@ -1,5 +1,5 @@
 // Split-KV decode kernel for calls that give every compute unit at most one workgroup
-// (bf16, gfx950): one sequence in a contiguous cache, rank <= 32, no rotary key side.
+// (bf16, gfx950): one sequence in a contiguous cache, no rotary key side.
 //
 // Same arithmetic and data layout as decode_mfma_kernel (the inner loop of Alg. 1 with the
 // App. D.1 key-side reordering, scores computed transposed, all agents x GQA rows of a kv
@@ -16,9 +16,11 @@
 //   - Waves 4-7 are the prologue: they load Q and the B_K rows of the workgroup's agents
 //     into registers with ordinary loads (their own request counters: nothing of theirs
 //     queues in front of a tile), form Qt = Q B_K^T by MFMA and leave Q and Qt in LDS in
-//     operand-ready order.  One barrier later the streaming waves pick both up; by then their
-//     first tile has not landed yet.  The prologue waves then touch the B_V rows the merge
-//     kernel will need and wait at the final barrier.
+//     operand-ready order - in the second stage of the last streaming wave, which that wave
+//     fills only after everybody has picked them up, so the tile stages can take the whole
+//     LDS.  The streaming waves request their first tile, pick up Q and Qt (long before that
+//     tile lands), then request their second tile.  The prologue waves then touch the B_V
+//     rows the merge kernel will need and wait at the final barrier.
 //   - All divisions by the row padding (a power of two) are shifts; the addresses of the
 //     LDS reads are formed after the requests have left.
 //   - The four streaming waves merge their states with one barrier (each deposits its
@@ -43,16 +45,14 @@ namespace lra {
 #define LRA_STAMP_FLUSH()
 #endif
 
-// LDS bytes of one workgroup of decode_stream_kernel<D, RT>.
-constexpr int decode_stream_lds_bytes(int D, int RT) {
-  return 4 * 2 * (2 * 32 * D * 2 + 32 * 32 * 2) + RT * 16 * D * 2 + RT * 1024;
-}
+// LDS bytes of one workgroup of decode_stream_kernel<D, RT, RP>: the tile stages and nothing else.
+constexpr int decode_stream_lds_bytes(int D, int RP) { return 4 * 2 * (2 * 32 * D * 2 + 32 * RP * 2); }
 
-template <int D, int RT, bool HAS_BK, bool CAUSAL>
+template <int D, int RT, int RP, bool HAS_BK, bool CAUSAL>
 __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   constexpr int NW = 4;            // streaming waves; waves NW .. 2 NW - 1 are the prologue waves
-  constexpr int RP = 32;           // padded rank
   constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
+  constexpr int RKS = RP / 32;     // MFMA k-steps over the (padded) rank
   constexpr int DB = D / 16;       // 16-wide output blocks over d
   constexpr int RB = RP / 16;      // 16-wide output blocks over the rank
   constexpr int KCH = D / 8;       // 16-byte chunks per K/V row
@@ -67,18 +67,21 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   constexpr int STAGE_BYTES = 2 * KV_BYTES + L_BYTES;
   constexpr int WAVE_BYTES = 2 * STAGE_BYTES;
   constexpr int ROW_BYTES = D * 2;
-  constexpr int MAXIT = 2;                     // Qt items per prologue wave and row tile: 4 slots x 2 rho blocks over 4 waves
+  constexpr int LSW_SHIFT = (RP == 32) ? 1 : 0;  // L rows of 64 bytes share a swizzle value in pairs
+  constexpr int MAXIT = RP / 16;               // Qt items per prologue wave and row tile: 4 slots x RP/16 rho blocks over 4 waves
   constexpr int Q_BYTES = RT * KS * 1024;      // Q as B operands: 16 bytes per lane, k-step and row tile
-  constexpr int QT_BYTES = RT * 1024;
+  constexpr int QT_BYTES = RT * RKS * 1024;
   constexpr int NBLK = DB + RB;                                // f32x4 blocks per lane and row tile
   constexpr int SLOT_BYTES = RT * (NBLK * 1024 + 512);         // merge slot of a wave: blocks, then (m, l) pairs
   static_assert(SLOT_BYTES <= WAVE_BYTES, "a wave's merge slot lives in its own tile region");
-  static_assert(NW * WAVE_BYTES + Q_BYTES + QT_BYTES == decode_stream_lds_bytes(D, RT), "LDS accounting");
-  static_assert(NW * WAVE_BYTES + Q_BYTES + QT_BYTES <= 160 * 1024, "LDS of one CU");
+  static_assert(Q_BYTES + QT_BYTES <= STAGE_BYTES, "Q and Qt are handed over in one tile stage");
+  static_assert(NW * WAVE_BYTES == decode_stream_lds_bytes(D, RP), "LDS accounting");
+  static_assert(NW * WAVE_BYTES <= 160 * 1024, "LDS of one CU");
 
   __shared__ __align__(16) unsigned char smem[NW * WAVE_BYTES];
-  __shared__ __align__(16) unsigned char q_lds[Q_BYTES];
-  __shared__ __align__(16) unsigned char qt_lds[QT_BYTES];
+  // hand-over area of Q and Qt: the second stage of the last streaming wave
+  unsigned char* q_lds = smem + (NW - 1) * WAVE_BYTES + STAGE_BYTES;
+  unsigned char* qt_lds = q_lds + Q_BYTES;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -157,13 +160,33 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
         for (int ks = 0; ks < KS; ++ks) qb[rt][ks] = as_bf16x8(buf_load16(rs_q, off, ks * 64));
       }
     }
-    if constexpr (HAS_BK) {
+    const bool qt_ready = HAS_BK && p.qt_ws != nullptr;  // a pre-pass has formed Qt for the whole call
+    if (qt_ready) {
+      // operand-ready Qt of this (kv head, row group): RT*RKS pieces of 1 KB; prologue wave hw copies
+      // pieces hw, hw + NW, ...
+      const uint4* src = reinterpret_cast<const uint4*>(p.qt_ws) + (static_cast<size_t>(rg) * p.n_kv_heads + h) * (RT * RKS * 64);
+      uint4 piece[(RT * RKS + NW - 1) / NW];
+#pragma unroll
+      for (int i = 0; i < (RT * RKS + NW - 1) / NW; ++i) {
+        const int idx = hw + i * NW;
+        piece[i] = idx < RT * RKS ? src[idx * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+      }
+      __builtin_amdgcn_s_barrier();  // these loads have left (see below)
+#pragma unroll
+      for (int i = 0; i < (RT * RKS + NW - 1) / NW; ++i) {
+        const int idx = hw + i * NW;
+        if (idx < RT * RKS) *reinterpret_cast<uint4*>(qt_lds + (idx * 64 + lane) * 16) = piece[i];
+      }
+    }
+    if (HAS_BK && !qt_ready) {
       // Item idx = hw + it*NW of row tile rt is (agent slot si, rho block cb); this lane holds row
       // rho = 16cb + ln of B_K^a, columns h*D + 32ks + 8lg ..: the A operand of Qt^T.  Rows beyond
       // the rank and the rows of empty slots lie outside the resource and arrive as zeros.
       const int S = 16 >> gps;         // agent slots per 16-row tile
-      const int ncb = (r + 15) >> 4;   // rho blocks: 1 or 2
+      const int ncb = (r + 15) >> 4;   // rho blocks: 1 .. RP/16
       const int n_items = S * ncb;
+      // idx -> (slot, rho block): idx / ncb without a division (idx < 16, ncb <= 4)
+      auto item_slot = [&](int idx) { return (idx * (256 / ncb + 1)) >> 8; };
       const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
       const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
       uint4 bt4[RT][MAXIT][KS];
@@ -172,7 +195,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
 #pragma unroll
         for (int it = 0; it < MAXIT; ++it) {
           const int idx = hw + it * NW;
-          const int si = ncb == 1 ? idx : idx >> 1, cb = ncb == 1 ? 0 : idx & 1;
+          const int si = item_slot(idx), cb = idx - si * ncb;
           const int a = slot_adapter(rt, si);
           const bool live = idx < n_items && a >= 0;
           const uint32_t bytes = live ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u;
@@ -187,27 +210,28 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       __builtin_amdgcn_s_barrier();
       // Qt^T block (rho block cb, tile rt) in C layout: lane (rho = 16cb + 4lg + j, row ln).  Rows
       // of a tile belong to 16/GP agents; each agent's product is kept only in its own rows
-      // (lanes).  Left in LDS in operand-ready form: the operand of lane l and tile rt is the 16
-      // bytes at (rt*64 + l)*16, elements e -> rho = 16(e/4) + 4lg + e%4 (the L operand of the
-      // loop uses the same order).  Every lane is written: every row belongs to some slot.
+      // (lanes).  Left in LDS in operand-ready form: operand (rt, ks') of lane l is the 16 bytes
+      // at ((rt*RKS + ks')*64 + l)*16, elements e -> rho = 32ks' + 16(e/4) + 4lg + e%4 (the L
+      // operand of the loop uses the same order).  Every lane of every k-step below the rank is
+      // written: every row belongs to some slot.
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int it = 0; it < MAXIT; ++it) {
           const int idx = hw + it * NW;
           if (idx < n_items) {
-            const int si = ncb == 1 ? idx : idx >> 1, cb = ncb == 1 ? 0 : idx & 1;
+            const int si = item_slot(idx), cb = idx - si * ncb;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
               acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bt4[rt][it][ks]), qb[rt][ks], acc, 0, 0, 0);
             if ((ln >> gps) == si) {
-              unsigned char* dst = qt_lds + (rt * 64 + lane) * 16;
+              unsigned char* dst = qt_lds + ((rt * RKS + (cb >> 1)) * 64 + lane) * 16;
               const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
-              if (ncb == 1)  // the second rho block lies beyond the rank: zeros
+              if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
                 *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
               else
-                *reinterpret_cast<uint2*>(dst + cb * 8) = pk;
+                *reinterpret_cast<uint2*>(dst + (cb & 1) * 8) = pk;
             }
           }
         }
@@ -222,6 +246,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
     }
     LRA_STAMP(2);
     __syncthreads();  // Q and Qt are in LDS
+    __syncthreads();  // ... and have been picked up
     // One workgroup per (kv head, row group) touches the B_V rows the merge kernel will need
     // (one 4-byte read per 128-byte line), so that they wait in this XCD's L2 instead of in
     // HBM: prologue wave w takes agent slot w of every row tile.
@@ -232,11 +257,15 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       const int a = slot_adapter(rt, hw);
       if (p.b_v != nullptr && split == min(1, p.n_splits - 1) && a >= 0) {
         constexpr int LPR = D * 2 / 128;  // 128-byte lines per B_V row of one kv head
-        const int n_lines = r * LPR;      // <= 64
+        const int n_lines = r * LPR;      // <= 128
         const char* bv = static_cast<const char*>(p.b_v) +
                          (static_cast<int64_t>(a) * r * p.n_kv_heads * D + static_cast<int64_t>(h) * D) * 2;
-        if (lane < n_lines)
-          warm[rt] = *reinterpret_cast<const int*>(bv + static_cast<int64_t>(lane / LPR) * p.n_kv_heads * D * 2 + (lane % LPR) * 128);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int li = i * 64 + lane;
+          if (li < n_lines)
+            warm[rt] += *reinterpret_cast<const int*>(bv + static_cast<int64_t>(li / LPR) * p.n_kv_heads * D * 2 + (li % LPR) * 128);
+        }
       }
     }
 #pragma unroll
@@ -275,7 +304,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
   {
     const int lrow = lane / RCH, lpc = lane % RCH;
-    const int lch = lpc ^ ((lrow >> 1) & (RCH - 1));
+    const int lch = lpc ^ ((lrow >> LSW_SHIFT) & (RCH - 1));
     l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * r2 + (lch << 4) : kOob;
   }
   // one resource per wave covering exactly its keys [jw0, jw1)
@@ -317,7 +346,6 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   };
   __builtin_amdgcn_s_barrier();  // the prologue waves' loads have left: theirs go first
   if (jw0 < jw1) issue_tile(jw0, 0);
-  if (jw0 + 32 < jw1) issue_tile(jw0 + 32, 1);
   LRA_STAMP(2);
   __builtin_amdgcn_sched_barrier(0);
 
@@ -329,16 +357,18 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   // 2b + c0 (+ half sub): address v_pre ^ (b << 5) + tt * 16 rows.
   const int ka = 4 * lg + (ln >> 2);
   const int v_pre = ka * ROW_BYTES + ((swz_v(ka) + ((ln & 3) >> 1)) << 4) + (ln & 1) * 8;
-  int l_rd[2];   // L rows as A operand of S^T: two 8-byte pieces
-  int lt_rd[RB]; // L^T as A operand of Olr^T
+  int l_rd[RKS][2];  // L rows as A operand of S^T: two 8-byte pieces per k-step
+  int lt_rd[RB];     // L^T as A operand of Olr^T
   {
-    const int swz_s = (ln >> 1) & (RCH - 1);
+    const int swz_s = (ln >> LSW_SHIFT) & (RCH - 1);
 #pragma unroll
-    for (int pcs = 0; pcs < 2; ++pcs) {
-      const int ch = 2 * pcs + (lg >> 1);
-      l_rd[pcs] = ln * (2 * RP) + ((ch ^ swz_s) << 4) + (lg & 1) * 8;
-    }
-    const int swz_t = (ka >> 1) & (RCH - 1);
+    for (int ks = 0; ks < RKS; ++ks)
+#pragma unroll
+      for (int pcs = 0; pcs < 2; ++pcs) {
+        const int ch = 4 * ks + 2 * pcs + (lg >> 1);
+        l_rd[ks][pcs] = ln * (2 * RP) + ((ch ^ swz_s) << 4) + (lg & 1) * 8;
+      }
+    const int swz_t = (ka >> LSW_SHIFT) & (RCH - 1);
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
       const int ch = 2 * b + ((ln & 3) >> 1);
@@ -368,13 +398,22 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   const float sc = p.scale * 1.44269504088896340736f;
 
   __syncthreads();  // the prologue waves have left Q and Qt in LDS
-  bf16x8 qb[RT][KS], qtb[RT];
+  bf16x8 qb[RT][KS], qtb[RT][RKS];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qb[rt][ks] = as_bf16x8(lds_read16(q_lds + ((rt * KS + ks) * 64 + lane) * 16));
-    qtb[rt] = as_bf16x8(HAS_BK ? lds_read16(qt_lds + (rt * 64 + lane) * 16) : make_uint4(0u, 0u, 0u, 0u));
+#pragma unroll
+    for (int ks = 0; ks < RKS; ++ks) {
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);  // k-steps entirely beyond the rank were never written
+      if (HAS_BK && ks * 32 < r) v = lds_read16(qt_lds + ((rt * RKS + ks) * 64 + lane) * 16);
+      qtb[rt][ks] = as_bf16x8(v);
+    }
   }
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the reads have returned
+  lds_fence();
+  __syncthreads();  // everybody has picked them up: the hand-over area is a tile stage again
+  if (jw0 + 32 < jw1) issue_tile(jw0 + 32, 1);
   LRA_STAMP(3);
 
   // ===================== main loop =====================
@@ -400,12 +439,15 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
           s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[rt][ks], s[tt][rt], 0, 0, 0);
       }
       if constexpr (HAS_BK) {
-        const uint2 lo = lds_read8(ls_lds + l_rd[0] + tt * 16 * (2 * RP));
-        const uint2 hi = lds_read8(ls_lds + l_rd[1] + tt * 16 * (2 * RP));
-        const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-          s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qtb[rt], s[tt][rt], 0, 0, 0);
+        for (int ks = 0; ks < RKS; ++ks) {
+          const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 16 * (2 * RP));
+          const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 16 * (2 * RP));
+          const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt)
+            s[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qtb[rt][ks], s[tt][rt], 0, 0, 0);
+        }
       }
     }
     // online softmax; element (tt, jj) of this lane is key j + 16tt + 4lg + jj of row ln
@@ -558,34 +600,119 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   LRA_STAMP_FLUSH();
 }
 
-// Whether a decode launch can take decode_stream_kernel: contiguous cache, rank <= 32, no
-// rotary key side, at most one workgroup per compute unit.
+// Qt = Q B_K^T for every row of a decode call, once per call instead of once per workgroup of
+// the streaming kernel (App. D.1: the query-side projection of the key-side reordering).  With
+// many agents and a large rank every key share of a kv head would otherwise reload the B_K rows of
+// all its agents (config "8 agents, r = 64": 128 KB per workgroup, 32 workgroups per head).
+// One workgroup per (kv head, row tile, agent slot); wave = rho block.  Output: the operand-ready
+// layout the streaming kernel keeps in LDS, [row group][kv head][row tile][k-step][lane] 16 bytes,
+// elements e -> rho = 32ks' + 16(e/4) + 4lg + e%4.
+template <int D, int RP, bool CAUSAL>
+__global__ __launch_bounds__(256) void decode_qt_prepass_kernel(Params p, int row_tiles) {
+  constexpr int KS = D / 32, RKS = RP / 32, ROW_BYTES = D * 2;
+  const int lane = threadIdx.x & 63;
+  const int cb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // rho block of this wave
+  const int ln = lane & 15, lg = lane >> 4;
+  const int h = blockIdx.x, si = blockIdx.z;
+  const int rg = blockIdx.y / row_tiles, rt = blockIdx.y - rg * row_tiles;
+  const int n_q = CAUSAL ? p.n_new : p.n_queries;
+  const int GP = p.group_pad, G = p.group, r = p.rank;
+  const int gps = __builtin_ctz(GP);
+  const int ncb = (r + 15) >> 4;
+  const int tile_row0 = (rg * row_tiles + rt) * 16;
+  const int slot = (tile_row0 >> gps) + si;
+  if (si >= (16 >> gps) || cb >= ncb) return;
+  int a = -1;
+  if (slot < n_q) a = CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[slot];
+  const bool live = a >= 0 && a < p.n_adapters;
+  const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
+  const __amdgpu_buffer_rsrc_t rs_q = make_rsrc(p.q, static_cast<uint32_t>(n_q) * p.n_q_heads * D * 2);
+  const __amdgpu_buffer_rsrc_t rs_b =
+      make_rsrc(static_cast<const bf16_t*>(p.b_k) + static_cast<int64_t>(live ? a : 0) * r * ldb + h * D,
+                live ? static_cast<uint32_t>((r - 1) * ldb + D) * 2u : 0u);
+  const int R = tile_row0 + ln;
+  const int sq = R >> gps, gg = R & (GP - 1);
+  const uint32_t qoff = (sq < n_q && gg < G) ? static_cast<uint32_t>((sq * p.n_q_heads + h * G + gg) * ROW_BYTES + lg * 16) : kOob;
+  const uint32_t boff = static_cast<uint32_t>((cb * 16 + ln) * ldb * 2 + lg * 16);
+  bf16x8 qv[KS], bv[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    qv[ks] = as_bf16x8(buf_load16(rs_q, qoff, ks * 64));
+    bv[ks] = as_bf16x8(buf_load16(rs_b, boff, ks * 64));
+  }
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv[ks], qv[ks], acc, 0, 0, 0);
+  if ((ln >> gps) == si) {
+    unsigned char* dst = static_cast<unsigned char*>(p.qt_ws) +
+                         ((((static_cast<size_t>(rg) * p.n_kv_heads + h) * row_tiles + rt) * RKS + (cb >> 1)) * 64 + lane) * 16;
+    const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
+    if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
+      *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
+    else
+      *reinterpret_cast<uint2*>(dst + (cb & 1) * 8) = pk;
+  }
+}
+
+// Bytes of workspace the pre-pass output takes, 0 where the streaming kernel forms Qt itself: the
+// pre-pass pays (one more launch) once a workgroup of the streaming kernel would have to load more
+// than eight 16-row blocks of B_K.
+size_t decode_stream_qt_bytes(int group_pad, int rank, int row_tiles, int row_groups, int n_kv_heads) {
+  const int slots = 16 / group_pad, ncb = (rank + 15) / 16;
+  if (slots * ncb * row_tiles <= 8) return 0;
+  const int rks = rank > 32 ? 2 : 1;
+  return static_cast<size_t>(row_groups) * n_kv_heads * row_tiles * rks * 1024;
+}
+
+template <int D, int RP>
+static void launch_prepass2(const Params& p, int row_tiles, hipStream_t s) {
+  const dim3 grid(p.n_kv_heads, p.row_groups * row_tiles, 16 / p.group_pad), block(256);
+  if (p.is_prefill) hipLaunchKernelGGL((decode_qt_prepass_kernel<D, RP, true>), grid, block, 0, s, p, row_tiles);
+  else hipLaunchKernelGGL((decode_qt_prepass_kernel<D, RP, false>), grid, block, 0, s, p, row_tiles);
+}
+
+// Whether a decode launch can take decode_stream_kernel: contiguous cache, no rotary key side, at
+// most one workgroup per compute unit.
 bool decode_stream_applies(const Params& p, int row_tiles, int n_cus) {
-  if (p.block_size != 0 || p.rank > 32 || (p.key_rope_theta > 0.f && p.b_k != nullptr)) return false;
+  if (p.block_size != 0 || (p.key_rope_theta > 0.f && p.b_k != nullptr)) return false;
   if (row_tiles < 1 || row_tiles > 2) return false;
-  if (decode_stream_lds_bytes(p.head_dim, row_tiles) > 160 * 1024) return false;
   const int64_t wgs = static_cast<int64_t>(p.n_kv_heads) * p.n_splits * p.row_groups;
   return wgs <= n_cus;
 }
 
-template <int D, int RT>
+template <int D, int RT, int RP>
 static hipError_t launch_stream2(const Params& p, dim3 grid, hipStream_t s) {
   const dim3 block(512);
   const bool has_bk = p.b_k != nullptr;
   if (p.is_prefill) {
-    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, true, true>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, false, true>), grid, block, 0, s, p);
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, true>), grid, block, 0, s, p);
   } else {
-    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, true, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, false, false>), grid, block, 0, s, p);
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, false>), grid, block, 0, s, p);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_decode_stream(const Params& p, int row_tiles, hipStream_t s) {
+// main_kernel_only (measurement): the streaming kernel alone, on whatever Qt an earlier call left
+hipError_t launch_decode_stream(const Params& p, int row_tiles, bool main_kernel_only, hipStream_t s) {
   const dim3 grid(p.n_kv_heads, p.n_splits, p.row_groups);
-  if (p.head_dim == 128) return row_tiles == 1 ? launch_stream2<128, 1>(p, grid, s) : launch_stream2<128, 2>(p, grid, s);
-  return row_tiles == 1 ? launch_stream2<64, 1>(p, grid, s) : launch_stream2<64, 2>(p, grid, s);
+  if (p.qt_ws != nullptr && !main_kernel_only) {
+    if (p.head_dim == 128) { if (p.rank > 32) launch_prepass2<128, 64>(p, row_tiles, s); else launch_prepass2<128, 32>(p, row_tiles, s); }
+    else { if (p.rank > 32) launch_prepass2<64, 64>(p, row_tiles, s); else launch_prepass2<64, 32>(p, row_tiles, s); }
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  }
+  const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (p.rank > 32 ? 1 : 0);
+  switch (key) {
+    case 0: return launch_stream2<64, 1, 32>(p, grid, s);
+    case 1: return launch_stream2<64, 1, 64>(p, grid, s);
+    case 2: return launch_stream2<64, 2, 32>(p, grid, s);
+    case 3: return launch_stream2<64, 2, 64>(p, grid, s);
+    case 4: return launch_stream2<128, 1, 32>(p, grid, s);
+    case 5: return launch_stream2<128, 1, 64>(p, grid, s);
+    case 6: return launch_stream2<128, 2, 32>(p, grid, s);
+    default: return launch_stream2<128, 2, 64>(p, grid, s);
+  }
 }
 
 }  // namespace lra

@@ -123,6 +123,8 @@ SHORT_PREFILL_CASES = [
     (300, 13, 14, 2, 128, 32),     # group of 7: 8 rows per token, several row groups
     (777, 16, 16, 1, 64, 64),      # group of 16
     (64, 16, 4, 4, 64, 8),         # context exactly four times the new tokens
+    (2000, 8, 8, 2, 128, 64),      # 4 token slots x 4 rank blocks x 2 row tiles: Qt comes from the pre-pass kernel
+    (1500, 6, 16, 4, 64, 40),      # the same at d = 64, rank 40 (3 rank blocks), a ragged last row tile
 ]
 
 
