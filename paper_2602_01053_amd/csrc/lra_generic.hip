@@ -373,6 +373,121 @@ __global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(Params p) {
 #endif
 }
 
+// The same merge with wide loads, for the common case (head dimension 64 or 128, rank a multiple of
+// 4, at most 64 splits): one workgroup of 256 threads per query row.
+//   - lane = split for the statistics: every wave forms the flash-decoding weights w_s on its own
+//     (one 8-byte load per lane), so no barrier stands before the partial rows can be weighted;
+//   - O rows as float4: thread (split group sg, column quad cq) sums splits sg, sg + SG, ...;
+//   - O_lr rows as float4: thread (split group of 16, quad q < r/4);
+//   - the B_V slice of the row's adapter and kv head ([r][d] elements) travels to LDS in 16-byte
+//     pieces; the epilogue O += O_lr B_V reads it from there.
+// Three barriers; every sum runs in a fixed order (splits ascending inside a thread, groups
+// ascending across threads), so the result does not depend on which workgroup of the first
+// kernel finished first.  All loads of a thread are issued before the first is consumed.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_rows_kernel(Params p) {
+  constexpr int CQ = D / 4;        // column quads of an O row
+  constexpr int SG = 256 / CQ;     // split groups for the O rows
+  constexpr int OP = 64 / SG;      // passes over at most 64 splits
+  constexpr int BV_PIECES = 64 * D * static_cast<int>(sizeof(T)) / 16 / 256;  // 16-byte pieces of B_V per thread at r = 64
+  const int Hq = p.n_q_heads, r = p.rank, ns = p.n_splits;
+  const int h = blockIdx.x % p.n_kv_heads;
+  const int rest = blockIdx.x / p.n_kv_heads;
+  const int tok = rest / p.group;
+  const int g = h * p.group + rest % p.group;
+  const int row = tok * Hq + g;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int64_t slot0 = static_cast<int64_t>(row) * ns;
+
+  __shared__ __align__(16) float o_sh[SG][D];
+  __shared__ __align__(16) float lr_sh[16][64];
+  __shared__ __align__(16) float olr_tot[64];
+  __shared__ __align__(16) unsigned char bv_sh[64 * D * sizeof(T)];
+
+  // (clamped: whatever the workspace holds, the B_V rows read below exist)
+  const int a = min(max(((const __attribute__((address_space(4))) int32_t*)(p.part_adapter))[row], 0), p.n_adapters - 1);
+
+  // ---- issue everything ----
+  const float2 st = lane < ns ? reinterpret_cast<const float2*>(p.part_ml)[slot0 + lane] : make_float2(0.f, 0.f);
+  const int sg = tid / CQ, cq = tid % CQ;
+  float4 xo[OP];
+#pragma unroll
+  for (int k = 0; k < OP; ++k) {
+    const int s = sg + SG * k;
+    xo[k] = s < ns ? *reinterpret_cast<const float4*>(p.part_o + (slot0 + s) * D + cq * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const int lg16 = tid >> 4, q = tid & 15;
+  const bool q_live = q * 4 < r;
+  float4 xl[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int s = lg16 + 16 * k;
+    xl[k] = (s < ns && q_live) ? *reinterpret_cast<const float4*>(p.part_lr + (slot0 + s) * r + q * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  constexpr int ROW_PIECES = D * static_cast<int>(sizeof(T)) / 16;  // 16-byte pieces per B_V row of one kv head
+  uint4 bvp[BV_PIECES];
+  {
+    const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * D;
+    const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * ld + h * D;
+#pragma unroll
+    for (int k = 0; k < BV_PIECES; ++k) {
+      const int e = tid + 256 * k;
+      const int rho = e / ROW_PIECES, pc = e % ROW_PIECES;
+      bvp[k] = (p.b_v != nullptr && rho < r) ? *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(bv + rho * ld) + pc * 16)
+                                              : make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+
+  // ---- weights (per wave, lane = split) ----
+  const bool live = st.y > 0.f;  // a share without a visible key left a zero row sum; its rows were never written
+  const float big = wave_max(live ? st.x : -INFINITY);
+  const float w = live ? expf(st.x - big) : 0.f;
+  const float ell = wave_sum(w * st.y);
+
+  // ---- weighted sums of this thread's splits ----
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f), olr = o;
+#pragma unroll
+  for (int k = 0; k < OP; ++k) {
+    const float wk = __shfl(w, min(sg + SG * k, 63), kWave);
+    if (sg + SG * k < ns && wk > 0.f) {  // also keeps whatever an unwritten row holds out of the sums
+      o.x = fmaf(wk, xo[k].x, o.x);
+      o.y = fmaf(wk, xo[k].y, o.y);
+      o.z = fmaf(wk, xo[k].z, o.z);
+      o.w = fmaf(wk, xo[k].w, o.w);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const float wk = __shfl(w, lg16 + 16 * k, kWave);
+    if (lg16 + 16 * k < ns && wk > 0.f) {
+      olr.x = fmaf(wk, xl[k].x, olr.x);
+      olr.y = fmaf(wk, xl[k].y, olr.y);
+      olr.z = fmaf(wk, xl[k].z, olr.z);
+      olr.w = fmaf(wk, xl[k].w, olr.w);
+    }
+  }
+  *reinterpret_cast<float4*>(&o_sh[sg][cq * 4]) = o;
+  *reinterpret_cast<float4*>(&lr_sh[lg16][q * 4]) = olr;
+#pragma unroll
+  for (int k = 0; k < BV_PIECES; ++k) *reinterpret_cast<uint4*>(bv_sh + (tid + 256 * k) * 16) = bvp[k];
+  __syncthreads();
+  if (tid < 64) {
+    float x = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) x += lr_sh[k][tid];
+    olr_tot[tid] = x;
+  }
+  __syncthreads();
+  if (tid < D) {
+    float x = 0.f;
+#pragma unroll
+    for (int k = 0; k < SG; ++k) x += o_sh[k][tid];
+    const T* bcol = reinterpret_cast<const T*>(bv_sh) + tid;
+    for (int rho = 0; rho < r; ++rho) x = fmaf(olr_tot[rho], to_f32<T>(bcol[rho * D]), x);
+    static_cast<T*>(p.out)[static_cast<int64_t>(row) * D + tid] = from_f32<T>(x / ell);
+  }
+}
+
 // The same merge for calls with many rows: one wave per row (four rows, q heads of one kv
 // head, per workgroup), no LDS and no barrier, so that a CU holds twenty rows' worth of loads
 // in flight instead of four.  Lane = split for the statistics (at most 64 splits), lane =
@@ -487,6 +602,11 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
 template <typename T>
 static void launch_merge_t(const Params& p, int rows, hipStream_t s) {
   if (launch_merge_wave<T>(p, rows, s)) return;
+  if (p.rank % 4 == 0 && p.n_splits <= 64 && (p.head_dim == 64 || p.head_dim == 128)) {
+    if (p.head_dim == 128) hipLaunchKernelGGL((merge_rows_kernel<T, 128>), dim3(rows), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((merge_rows_kernel<T, 64>), dim3(rows), dim3(256), 0, s, p);
+    return;
+  }
   // enough 128-thread groups that one pass of kMergeUnroll splits per thread covers the splits
   const int groups = (p.n_splits + kMergeUnroll - 1) / kMergeUnroll;
   dim3 grid(rows);
