@@ -412,6 +412,23 @@ def bench_append(args, torch, lra, with_cpu, sizes=(16384, 2048, 1)):
     return out
 
 
+def bench_trace_leg(torch, lra):
+    """The second workload: the 17-step agent-iteration trace of App. C.5 (bench_trace.py) at its four
+    retrieved-context lengths; attention calls of one layer for one iteration, plus the producer's leg."""
+    import bench_trace
+    rows = []
+    for l_ctx in (256, 1024, 4096, 16384):
+        r = bench_trace.run_trace(torch, lra, l_ctx, replays=3)
+        rows.append({"l_ctx": l_ctx, "tokens": r["trajectory_tokens"], "calls": r["calls"],
+                     "attention_ms": r["attention_ms_per_layer"], "prefill_ms": r["prefill_ms_per_layer"],
+                     "decode_ms": r["decode_ms_per_layer"], "decode_us_per_token": r["decode_us_per_token_per_layer"],
+                     "append_ms": r["cache_append_ms_per_layer"]})
+        torch.cuda.empty_cache()
+    return {"workload": "emulated agent-iteration trace (17 steps: prefill P_k then G_k generated tokens per step, 3 adapters), "
+                        "Llama-3-8B attention shape, one layer, one iteration", "timing": "HIP graph replay of all calls of one iteration",
+            "rows": rows}
+
+
 def cpu_baseline(workloads):
     """The oracle as it stands, on the host cores, on the decode workload."""
     import numpy as np  # noqa: F401
@@ -462,6 +479,7 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-other-decode", action="store_true")
     ap.add_argument("--no-append", action="store_true")
+    ap.add_argument("--no-trace", action="store_true")
     ap.add_argument("--append-only", action="store_true",
                     help="only the lra_cache_append sweep over chunk sizes (its own JSON line)")
     args = ap.parse_args()
@@ -526,6 +544,8 @@ def main():
         line["value_only_adapters"] = value_only_decode(args, torch, lra, workloads)
     if not args.no_append:
         line["cache_append"] = bench_append(args, torch, lra, not args.no_cpu_baseline)
+    if not args.no_trace:
+        line["trace"] = bench_trace_leg(torch, lra)
     ceil = machine_ceilings(torch, lra)
     line["machine_ceilings"] = ceil
     line["roofline"]["frac_of_measured_ceiling"] = round(k_gbs / ceil["hbm_stream_read_GBps"], 4)
