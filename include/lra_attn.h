@@ -33,6 +33,8 @@
  *     LRA_OK (except LRA_ERR_HIP) means nothing was enqueued.  Inputs are never
  *     written.
  *   - Deterministic: equal arguments give bitwise equal outputs.
+ *   - Re-entrant: the library holds no mutable state apart from the one-time, per-device
+ *     lookup of lra_attn_decode_static's buffer; calls from several threads need no lock.
  *   - The caches already contain the rows of the new query tokens: a sequence of
  *     n tokens holds L_p old and L_c new ones, n = L_p + L_c (Alg. 1, first line).
  *   - Element type `dtype` applies to Q, K_base, V_base, L, B_K, B_V and the
@@ -43,7 +45,11 @@
  * Supported: head_dim in {64, 128}; 1 <= rank <= 64; n_q_heads a multiple of
  * n_kv_heads with a group of at most 16; q head g reads kv head g / (Hq/Hkv);
  * block_size 0 (contiguous) or 16; dtype bf16 (MFMA kernels) or fp32 (vector-ALU
- * kernels).  Anything else returns LRA_ERR_UNSUPPORTED.
+ * kernels).  Size caps: n_q_heads <= 4096, n_seqs <= 2^20, max_seq_len <= 2^30,
+ * query rows (queries or new tokens times n_q_heads) <= 2^30, kv_token_stride <= 2^31,
+ * kv_head_stride and kv_block_stride <= 2^40 elements, num_blocks * kv_block_stride <= 2^60,
+ * at most 65535 key shares per sequence and 65535 (sequence, row group) pairs per call.
+ * Anything else returns LRA_ERR_UNSUPPORTED.
  */
 #ifndef LRA_ATTN_H
 #define LRA_ATTN_H
@@ -147,14 +153,52 @@ typedef struct {
 } lra_adapters;
 
 /*
+ * Optional per-call tuning, passed by pointer to every entry point (NULL, or a zero-filled
+ * struct, selects the automatic choice everywhere).  The library keeps no tuning state of
+ * its own: the same struct must be given to lra_workspace_bytes and to the call it sizes.
+ * None of the fields changes a result beyond rounding.
+ *   kernel_variant     0 automatic (MFMA kernels for bf16, vector-ALU kernels for fp32; among the
+ *                      MFMA kernels, decode calls on a contiguous cache that give every compute
+ *                      unit at most one workgroup take the form with two tile stages per wave and
+ *                      separate prologue waves); 1 vector-ALU kernels for every dtype; 2 automatic
+ *                      without that form
+ *   decode_split_keys  keys per workgroup in decode (the flash-decoding split size), rounded up
+ *                      to the kernel's key tile; 0 automatic
+ *   short_prefill      bf16 prefill calls with at most this many new tokens (and a context at
+ *                      least four times as long) run on the split-KV decode kernels, the new
+ *                      tokens standing in for the agents; 0 automatic (32, the measured
+ *                      crossover), negative: never
+ *   prefill_splits     workgroups that share the key tiles of one q tile in the tile-walking
+ *                      prefill kernel (1..32; more than one ends with the merge kernel);
+ *                      0 automatic (two workgroups per CU, at least eight 64-key tiles each)
+ *   append_skinny      lra_cache_append calls with at most this many new tokens stream the
+ *                      weights instead of tiling; 0 automatic (64), negative: never
+ *   append_stages      LDS stages of lra_cache_append's tiled GEMM: 2, 3 or 4; 0 automatic
+ *   append_tile        output tile of that GEMM: 64, 128 or 256; 0 automatic
+ *   measure_main_kernel_only  1: the call enqueues only its dominant kernel (the key-streaming
+ *                      kernel) so that a benchmark can time it alone; `out` is NOT produced.
+ *                      For measurement only (see lra_attn_measure.h).
+ */
+typedef struct {
+  int32_t kernel_variant;
+  int32_t decode_split_keys;
+  int32_t short_prefill;
+  int32_t prefill_splits;
+  int32_t append_skinny;
+  int32_t append_stages;
+  int32_t append_tile;
+  int32_t measure_main_kernel_only;
+} lra_tuning;
+
+/*
  * Bytes of DEVICE workspace a call needs; 0 is a valid answer.
  *   n_new == 0 : for lra_attn_decode with these n_queries / max_queries_per_seq
  *   n_new >= 1 : for lra_attn_prefill with this n_new (the two query counts are ignored)
  * Returns (size_t)-1 when the arguments themselves would be rejected.  The answer
- * depends on the tuning hooks below: set them before asking.
+ * depends on `tuning`: pass the struct the call itself will get.
  */
 size_t lra_workspace_bytes(const lra_shape* shape, const lra_cache* cache, int32_t n_queries,
-                           int32_t max_queries_per_seq, int32_t n_new);
+                           int32_t max_queries_per_seq, int32_t n_new, const lra_tuning* tuning);
 
 /*
  * Decode step for many agents at once (Alg. 1 with L_c = 1 per query, the
@@ -179,7 +223,8 @@ lra_status lra_attn_decode(const lra_shape* shape, const lra_cache* cache,
                            const lra_adapters* adapters, const void* q,
                            const int32_t* query_adapter, const int32_t* seq_query_start,
                            int32_t n_queries, int32_t max_queries_per_seq, void* out,
-                           void* workspace, size_t workspace_bytes, void* stream);
+                           void* workspace, size_t workspace_bytes, const lra_tuning* tuning,
+                           void* stream);
 
 /*
  * lra_attn_decode for callers that cannot allocate or size a workspace: code under HIP graph
@@ -200,7 +245,7 @@ lra_status lra_attn_decode_static(const lra_shape* shape, const lra_cache* cache
                                   const lra_adapters* adapters, const void* q,
                                   const int32_t* query_adapter, const int32_t* seq_query_start,
                                   int32_t n_queries, int32_t max_queries_per_seq, void* out,
-                                  void* stream);
+                                  const lra_tuning* tuning, void* stream);
 
 /*
  * Causal prefill of one agent (Alg. 1 as printed: L_c = n_new query tokens after
@@ -215,7 +260,7 @@ lra_status lra_attn_decode_static(const lra_shape* shape, const lra_cache* cache
 lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache,
                             const lra_adapters* adapters, const void* q, int32_t seq_index,
                             int32_t adapter_index, int32_t n_new, void* out, void* workspace,
-                            size_t workspace_bytes, void* stream);
+                            size_t workspace_bytes, const lra_tuning* tuning, void* stream);
 
 /*
  * Projection weights of one attention layer for lra_cache_append.
@@ -247,102 +292,11 @@ typedef struct {
  * `stream` like the other calls.
  */
 lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
-                            const void* x, int32_t seq_index, int32_t n_new, void* stream);
+                            const void* x, int32_t seq_index, int32_t n_new, const lra_tuning* tuning,
+                            void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* lra_status_string(lra_status status);
-
-/*
- * Tuning and test hook: choose the kernel family for later calls from this
- * process.  0 = automatic (MFMA kernels for bf16, vector-ALU kernels for fp32; among the
- * MFMA kernels, decode calls on a contiguous cache with rank <= 32 that give every compute
- * unit at most one workgroup take the form with two tile stages per wave and separate
- * prologue waves), 1 = force the vector-ALU kernels for every dtype, 2 = automatic without
- * that form.  Returns the previous value.  Does not affect results beyond rounding.
- */
-int32_t lra_set_kernel_variant(int32_t variant);
-
-/*
- * Tuning hook: keys handled per workgroup in decode (the flash-decoding split
- * size).  0 restores the automatic choice.  Values are rounded up to a multiple
- * of the kernel's key tile.  Returns the previous value.
- */
-int32_t lra_set_decode_split_keys(int32_t keys);
-
-/*
- * Tuning and test hook: lra_cache_append calls with at most this many new tokens run the
- * weight-streaming kernels (one or two tokens: one wave per weight row; more: 16 features per
- * workgroup, d_model split over its waves) instead of the tiled GEMM; any value is valid, all
- * kernels handle any n_new.  0 switches the streaming kernels off.  Returns the previous
- * value.  Default 64.
- */
-int32_t lra_set_append_skinny(int32_t tokens);
-
-/*
- * Tuning and test hook: number of LDS stages (requests in flight) of lra_cache_append's
- * tiled GEMM: 2, 3 or 4; anything else restores the default (4 when the grid has at most one
- * workgroup per compute unit, else 2 with two workgroups per unit).  Returns the previous value.
- */
-int32_t lra_set_append_stages(int32_t stages);
-
-/*
- * Tuning and test hook: output tile of lra_cache_append's GEMM kernels: 64 (128 features x 64
- * tokens per workgroup), 128 (128 x 128) or 256 (256 x 256); anything else restores the
- * default (64 while 128-token tiles would occupy fewer than about 100 CUs; 256 when such tiles
- * fill whole rounds of the chip, e.g. 16384 new tokens at the Llama-3-8B shape; else 128).
- * All handle any n_new.  Returns the previous value.
- */
-int32_t lra_set_append_tile(int32_t tile);
-
-/*
- * Tuning and test hook: bf16 prefill calls with at most this many new tokens (and a context
- * at least four times as long) run on the split-KV decode kernels, the new tokens standing
- * in for the agents, instead of on the tile-walking prefill kernel; they then need a
- * workspace (ask lra_workspace_bytes after setting this).  0 switches that path off.
- * Returns the previous value.  Default 32 (measured crossover against the tile-walking kernel
- * with shared key tiles).
- */
-int32_t lra_set_short_prefill(int32_t tokens);
-
-/*
- * Tuning and test hook: number of workgroups that share the key tiles of one q tile in the
- * bf16 tile-walking prefill kernel (clamped to 1..32); more than one needs a workspace and
- * ends with the merge kernel.  0 restores the automatic choice (enough to give the chip two
- * workgroups per CU, at least eight 64-key tiles each at max_seq_len).  Returns the previous
- * value.
- */
-int32_t lra_set_prefill_splits(int32_t splits);
-
-/*
- * Measurement hook.  mode 1: later calls enqueue only their dominant kernel (the
- * key-streaming kernel) and skip the split merge / epilogue, so a benchmark can
- * time that kernel alone with HIP events around a batch of launches; `out` is NOT
- * produced in this mode.  mode 0 (the default) restores normal operation.
- * Returns the previous mode.
- */
-int32_t lra_set_profile_mode(int32_t mode);
-
-/*
- * Machine probes for the benchmark (not part of the attention path): what the GPU at hand
- * gives a plain streaming read and a register-resident bf16 MFMA loop, to be timed by the
- * caller with events around the call.
- *
- * lra_probe_stream_read: one kernel reads `bytes` (a multiple of 16 is read; >= 16) from the
- * device buffer src (16-byte aligned) once, coalesced, 16 bytes per lane and request.  Use a
- * buffer larger than the 256 MB memory-side cache for an HBM figure.  sink: 4 writable device
- * bytes (written only for one improbable value of the checksum).
- *
- * lra_probe_mfma_bf16: one kernel of two workgroups per CU, every wave issuing
- * iters x 4 independent v_mfma_f32_32x32x16_bf16 on register operands (1 <= iters <= 2^24).
- * random_operands == 0: two smooth operand values throughout; != 0: four registers of
- * pseudo-random values in rotation, so that consecutive products see unrelated bits as in a real
- * kernel (the clock the chip holds under matrix load depends on the data).  *flops (host, may
- * be NULL) receives the floating-point operations of the launch.  sink: 4 writable device bytes.
- *
- * Both are asynchronous on `stream`; LRA_ERR_NULL / LRA_ERR_SHAPE on bad arguments.
- */
-lra_status lra_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
-lra_status lra_probe_mfma_bf16(int32_t iters, int32_t random_operands, int64_t* flops, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

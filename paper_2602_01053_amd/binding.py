@@ -20,9 +20,7 @@ LRA_BF16, LRA_F32 = 0, 1
 STATIC_WORKSPACE_BYTES = 64 << 20   # LRA_STATIC_WORKSPACE_BYTES of the header
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_decode_static", "lra_attn_prefill", "lra_status_string",
-           "lra_cache_append", "lra_set_kernel_variant", "lra_set_decode_split_keys", "lra_set_short_prefill",
-           "lra_set_prefill_splits", "lra_set_append_skinny", "lra_set_append_stages", "lra_set_append_tile",
-           "lra_set_profile_mode", "lra_probe_stream_read", "lra_probe_mfma_bf16")
+           "lra_cache_append", "lra_probe_stream_read", "lra_probe_mfma_bf16")
 
 
 class LraShape(ctypes.Structure):
@@ -49,6 +47,20 @@ class LraProjection(ctypes.Structure):
     _fields_ = [("w", ctypes.c_void_p), ("d_model", ctypes.c_int32), ("rope_theta", ctypes.c_float)]
 
 
+class LraTuning(ctypes.Structure):
+    """lra_tuning of the header: all zero = automatic everywhere."""
+    _fields_ = [("kernel_variant", ctypes.c_int32), ("decode_split_keys", ctypes.c_int32),
+                ("short_prefill", ctypes.c_int32), ("prefill_splits", ctypes.c_int32),
+                ("append_skinny", ctypes.c_int32), ("append_stages", ctypes.c_int32),
+                ("append_tile", ctypes.c_int32), ("measure_main_kernel_only", ctypes.c_int32)]
+
+
+# The tuning struct this binding hands to every call.  The C library keeps no tuning state; the
+# lra_set_* helpers below are conveniences for tests and benchmarks that edit this one struct
+# (process-wide on the Python side only) and return the previous value.
+_tuning = LraTuning()
+
+
 class LraError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"lra_attn status {status}: {message}")
@@ -71,33 +83,18 @@ def load_library() -> ctypes.CDLL:
     sp, cp, ap = ctypes.POINTER(LraShape), ctypes.POINTER(LraCache), ctypes.POINTER(LraAdapters)
     vp, i32 = ctypes.c_void_p, ctypes.c_int32
     lib.lra_workspace_bytes.restype = ctypes.c_size_t
-    lib.lra_workspace_bytes.argtypes = [sp, cp, i32, i32, i32]
+    tp = ctypes.POINTER(LraTuning)
+    lib.lra_workspace_bytes.argtypes = [sp, cp, i32, i32, i32, tp]
     lib.lra_attn_decode.restype = ctypes.c_int
-    lib.lra_attn_decode.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.lra_attn_decode.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, tp, vp]
     lib.lra_attn_decode_static.restype = ctypes.c_int
-    lib.lra_attn_decode_static.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, vp]
+    lib.lra_attn_decode_static.argtypes = [sp, cp, ap, vp, vp, vp, i32, i32, vp, tp, vp]
     lib.lra_attn_prefill.restype = ctypes.c_int
-    lib.lra_attn_prefill.argtypes = [sp, cp, ap, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.lra_attn_prefill.argtypes = [sp, cp, ap, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, tp, vp]
     lib.lra_cache_append.restype = ctypes.c_int
-    lib.lra_cache_append.argtypes = [sp, cp, ctypes.POINTER(LraProjection), vp, i32, i32, vp]
+    lib.lra_cache_append.argtypes = [sp, cp, ctypes.POINTER(LraProjection), vp, i32, i32, tp, vp]
     lib.lra_status_string.restype = ctypes.c_char_p
     lib.lra_status_string.argtypes = [ctypes.c_int]
-    lib.lra_set_kernel_variant.restype = i32
-    lib.lra_set_kernel_variant.argtypes = [i32]
-    lib.lra_set_decode_split_keys.restype = i32
-    lib.lra_set_decode_split_keys.argtypes = [i32]
-    lib.lra_set_append_tile.restype = i32
-    lib.lra_set_append_tile.argtypes = [i32]
-    lib.lra_set_append_stages.restype = i32
-    lib.lra_set_append_stages.argtypes = [i32]
-    lib.lra_set_append_skinny.restype = i32
-    lib.lra_set_append_skinny.argtypes = [i32]
-    lib.lra_set_short_prefill.restype = i32
-    lib.lra_set_short_prefill.argtypes = [i32]
-    lib.lra_set_prefill_splits.restype = i32
-    lib.lra_set_prefill_splits.argtypes = [i32]
-    lib.lra_set_profile_mode.restype = i32
-    lib.lra_set_profile_mode.argtypes = [i32]
     lib.lra_probe_stream_read.restype = ctypes.c_int
     lib.lra_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.lra_probe_mfma_bf16.restype = ctypes.c_int
@@ -118,39 +115,57 @@ def lra_cache_append(shape: LraShape, cache: LraCache, w: torch.Tensor, rope_the
         raise LraError(2, "x and w must be dense and share d_model")
     proj = LraProjection(_ptr(w), int(w.shape[1]), float(rope_theta))
     _check(load_library().lra_cache_append(ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(proj), _ptr(x),
-                                           int(seq_index), int(x.shape[0]), _stream_ptr(stream)))
+                                           int(seq_index), int(x.shape[0]), ctypes.byref(_tuning), _stream_ptr(stream)))
+
+
+def _swap(field: str, value: int) -> int:
+    old = getattr(_tuning, field)
+    setattr(_tuning, field, int(value))
+    return int(old)
 
 
 def lra_set_kernel_variant(variant: int) -> int:
-    return int(load_library().lra_set_kernel_variant(int(variant)))
+    """0 automatic, 1 vector-ALU kernels, 2 MFMA kernels without the streaming form of the split-KV kernel."""
+    return _swap("kernel_variant", variant)
 
 
 def lra_set_decode_split_keys(keys: int) -> int:
-    return int(load_library().lra_set_decode_split_keys(int(keys)))
+    return _swap("decode_split_keys", keys)
 
 
 def lra_set_append_tile(tile: int) -> int:
-    return int(load_library().lra_set_append_tile(int(tile)))
+    return _swap("append_tile", tile)
 
 
 def lra_set_append_stages(stages: int) -> int:
-    return int(load_library().lra_set_append_stages(int(stages)))
+    return _swap("append_stages", stages)
+
+
+def _swap_default(field: str, tokens: int, default: int) -> int:
+    """Fields where 0 means "automatic" in the struct but callers say 0 for "off": stored as -1."""
+    raw = getattr(_tuning, field)
+    old = default if raw == 0 else max(raw, 0)
+    setattr(_tuning, field, -1 if tokens <= 0 else int(tokens))
+    return int(old)
 
 
 def lra_set_append_skinny(tokens: int) -> int:
-    return int(load_library().lra_set_append_skinny(int(tokens)))
+    """New tokens up to which lra_cache_append streams the weights; 0 switches that off (default 64)."""
+    return _swap_default("append_skinny", tokens, 64)
 
 
 def lra_set_short_prefill(tokens: int) -> int:
-    return int(load_library().lra_set_short_prefill(int(tokens)))
+    """New tokens up to which a prefill takes the split-KV path; 0 switches that off (default 32)."""
+    return _swap_default("short_prefill", tokens, 32)
 
 
 def lra_set_prefill_splits(splits: int) -> int:
-    return int(load_library().lra_set_prefill_splits(int(splits)))
+    return _swap("prefill_splits", splits)
 
 
 def lra_set_profile_mode(mode: int) -> int:
-    return int(load_library().lra_set_profile_mode(int(mode)))
+    """1: later calls enqueue only their dominant kernel (measurement; `out` is not produced)."""
+    return _swap("measure_main_kernel_only", 1 if mode == 1 else 0)
 
 
 def lra_probe_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
@@ -209,7 +224,7 @@ def lra_workspace_bytes(shape: LraShape, cache: LraCache, n_queries: int,
                         max_queries_per_seq: int = 1, n_new: int = 0) -> int:
     """n_new = 0: workspace of a decode call; n_new >= 1: of a prefill call."""
     n = load_library().lra_workspace_bytes(ctypes.byref(shape), ctypes.byref(cache), int(n_queries),
-                                           int(max_queries_per_seq), int(n_new))
+                                           int(max_queries_per_seq), int(n_new), ctypes.byref(_tuning))
     if n == ctypes.c_size_t(-1).value:
         raise LraError(2, "lra_workspace_bytes rejected the arguments")
     return int(n)
@@ -237,7 +252,7 @@ def lra_attn_decode(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor
     _check(load_library().lra_attn_decode(
         ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(ad), _ptr(q), _ptr(query_adapter),
         _ptr(seq_query_start), int(q.shape[0]), int(max_queries_per_seq), _ptr(out), ws_ptr,
-        ws_bytes, _stream_ptr(stream)))
+        ws_bytes, ctypes.byref(_tuning), _stream_ptr(stream)))
 
 
 def lra_attn_decode_static(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor],
@@ -248,7 +263,8 @@ def lra_attn_decode_static(shape: LraShape, cache: LraCache, b_k: Optional[torch
     ad = LraAdapters(_ptr(b_k), _ptr(b_v), int(n_adapters))
     _check(load_library().lra_attn_decode_static(
         ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(ad), _ptr(q), _ptr(query_adapter),
-        _ptr(seq_query_start), int(q.shape[0]), int(max_queries_per_seq), _ptr(out), _stream_ptr(stream)))
+        _ptr(seq_query_start), int(q.shape[0]), int(max_queries_per_seq), _ptr(out), ctypes.byref(_tuning),
+        _stream_ptr(stream)))
 
 
 def lra_attn_prefill(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tensor],
@@ -260,4 +276,4 @@ def lra_attn_prefill(shape: LraShape, cache: LraCache, b_k: Optional[torch.Tenso
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().lra_attn_prefill(
         ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(ad), _ptr(q), int(seq_index),
-        int(adapter_index), int(q.shape[0]), _ptr(out), ws_ptr, ws_bytes, _stream_ptr(stream)))
+        int(adapter_index), int(q.shape[0]), _ptr(out), ws_ptr, ws_bytes, ctypes.byref(_tuning), _stream_ptr(stream)))

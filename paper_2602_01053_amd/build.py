@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblra_attn.so")
 
-SOURCES = ["lra_api.hip", "lra_generic.hip", "lra_decode_mfma.hip", "lra_decode_stream.hip", "lra_prefill_mfma.hip", "lra_append.hip", "lra_probe.hip"]
+SOURCES = ["lra_plan.cpp", "lra_api.hip", "lra_generic.hip", "lra_decode_mfma.hip", "lra_decode_stream.hip", "lra_prefill_mfma.hip", "lra_append.hip", "lra_probe.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
@@ -45,8 +45,11 @@ def build_library(verbose: bool = False) -> str:
         path = os.path.join(CSRC, src)
         if not os.path.exists(path):
             raise FileNotFoundError(path)
-        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
-        jobs.append(([hipcc, *HIPCC_FLAGS, *inc, "-c", path, "-o", obj], obj))
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        if src.endswith(".cpp"):   # host-only C++ (launch planning): no device pass
+            jobs.append(([hipcc, "-O2", "-std=c++17", "-fPIC", *inc, "-c", path, "-o", obj], obj))
+        else:
+            jobs.append(([hipcc, *HIPCC_FLAGS, *inc, "-c", path, "-o", obj], obj))
     with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1)) as pool:
         list(pool.map(lambda j: _run(j[0], verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[o for _, o in jobs], "-o", LIB_PATH], verbose)

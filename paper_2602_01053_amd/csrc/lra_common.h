@@ -99,12 +99,9 @@ __device__ __forceinline__ int64_t l_offset(const Params& p, int t, int j) {
 // Launchers (defined next to their kernels).
 hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipStream_t s);
 hipError_t launch_merge(const Params& p, bool is_bf16, int rows, hipStream_t s);
-int decode_mfma_row_tiles(int rows_needed);
-int decode_mfma_rope_slots(int rank);
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, bool main_kernel_only, hipStream_t s);
 bool decode_stream_applies(const Params& p, int row_tiles, int n_cus);
 hipError_t launch_decode_stream(const Params& p, int row_tiles, bool main_kernel_only, hipStream_t s);
-size_t decode_stream_qt_bytes(int group_pad, int rank, int row_tiles, int row_groups, int n_kv_heads);
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s);
 
 // Arguments of the cache-append producer kernel.

@@ -31,6 +31,7 @@
 // goes to the workspace.
 #include "lra_common.h"
 #include "lra_decode_util.h"
+#include "lra_plan.h"
 #include "lra_prefill_util.h"
 
 namespace lra {
@@ -859,9 +860,6 @@ static hipError_t launch_cfg(const Params& p, dim3 grid, hipStream_t s) {
   return p.is_prefill ? launch_cfg2<D, RT, RP, true>(p, grid, s) : launch_cfg2<D, RT, RP, false>(p, grid, s);
 }
 
-// Row tiles per workgroup the kernel is built for.
-int decode_mfma_row_tiles(int rows_needed) { return rows_needed <= 16 ? 1 : 2; }
-
 template <int D, int RP, int RPE>
 static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
   const bool paged = p.block_size != 0;
@@ -874,10 +872,6 @@ static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
   }
   return hipGetLastError();
 }
-
-// Agent slots a 16-row tile may hold in the rotary form (the B_K^T operands of its slots
-// stay in registers): the row padding per query is at least 16 / this.
-int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 : kRopeSlots64); }
 
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, bool main_kernel_only, hipStream_t s) {
   // calls that give a compute unit at most one workgroup: the form with two tile stages per wave

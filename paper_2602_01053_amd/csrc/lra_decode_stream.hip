@@ -654,16 +654,6 @@ __global__ __launch_bounds__(256) void decode_qt_prepass_kernel(Params p, int ro
   }
 }
 
-// Bytes of workspace the pre-pass output takes, 0 where the streaming kernel forms Qt itself: the
-// pre-pass pays (one more launch) once a workgroup of the streaming kernel would have to load more
-// than eight 16-row blocks of B_K.
-size_t decode_stream_qt_bytes(int group_pad, int rank, int row_tiles, int row_groups, int n_kv_heads) {
-  const int slots = 16 / group_pad, ncb = (rank + 15) / 16;
-  if (slots * ncb * row_tiles <= 8) return 0;
-  const int rks = rank > 32 ? 2 : 1;
-  return static_cast<size_t>(row_groups) * n_kv_heads * row_tiles * rks * 1024;
-}
-
 template <int D, int RP>
 static void launch_prepass2(const Params& p, int row_tiles, hipStream_t s) {
   const dim3 grid(p.n_kv_heads, p.row_groups * row_tiles, 16 / p.group_pad), block(256);

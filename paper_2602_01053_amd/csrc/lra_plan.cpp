@@ -1,0 +1,219 @@
+// Launch planning (host only; see lra_plan.h).
+#include "lra_plan.h"
+
+#include <cmath>
+
+namespace lra {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+Tuning resolve_tuning(const lra_tuning* t) {
+  Tuning r;
+  if (!t) return r;
+  r.variant = (t->kernel_variant == 1 || t->kernel_variant == 2) ? t->kernel_variant : 0;
+  r.split_keys = t->decode_split_keys > 0 ? t->decode_split_keys : 0;
+  if (t->short_prefill != 0) r.short_prefill = t->short_prefill < 0 ? 0 : t->short_prefill;
+  r.prefill_splits = t->prefill_splits > 0 ? t->prefill_splits : 0;
+  if (t->append_skinny != 0) r.append_skinny = t->append_skinny < 0 ? 0 : t->append_skinny;
+  r.append_stages = (t->append_stages >= 2 && t->append_stages <= 4) ? t->append_stages : 0;
+  r.append_tile = (t->append_tile == 64 || t->append_tile == 128 || t->append_tile == 256) ? t->append_tile : 0;
+  r.main_kernel_only = t->measure_main_kernel_only == 1;
+  return r;
+}
+
+// Caps that keep the planner's and the kernels' 32-bit arithmetic in range: query rows
+// (tokens x Hq) and the padded rows of one sequence (queries x 16) below 2^30.
+bool plan_sizes_fit(const lra_shape* sh, const lra_cache* c, int32_t tokens, int32_t max_queries_per_seq) {
+  (void)c;
+  if (tokens < 1 || max_queries_per_seq < 1) return false;
+  if (static_cast<int64_t>(tokens) * sh->n_q_heads > (int64_t{1} << 30)) return false;
+  if (static_cast<int64_t>(max_queries_per_seq) * 16 > (int64_t{1} << 30)) return false;
+  return true;
+}
+
+int decode_mfma_row_tiles(int rows_needed) { return rows_needed <= 16 ? 1 : 2; }
+
+// (the B_K^T operands of a tile's slots stay in registers: 4 slots at ranks up to 16, 2 up to 32, 4
+// again above, where the kernel has a compute unit to itself)
+int decode_mfma_rope_slots(int rank) { return rank <= 16 ? 4 : (rank <= 32 ? 2 : 4); }
+
+// The pre-pass pays (one more launch) once a workgroup of the streaming kernel would have to load
+// more than eight 16-row blocks of B_K.
+size_t decode_stream_qt_bytes(int group_pad, int rank, int row_tiles, int row_groups, int n_kv_heads) {
+  const int slots = 16 / group_pad, ncb = (rank + 15) / 16;
+  if (slots * ncb * row_tiles <= 8) return 0;
+  const int rks = rank > 32 ? 2 : 1;
+  return static_cast<size_t>(row_groups) * n_kv_heads * row_tiles * rks * 1024;
+}
+
+lra_status check_common(const lra_shape* sh, const lra_cache* c) {
+  if (!sh || !c) return LRA_ERR_NULL;
+  if (sh->dtype != LRA_BF16 && sh->dtype != LRA_F32) return LRA_ERR_DTYPE;
+  if (sh->n_q_heads < 1 || sh->n_kv_heads < 1 || sh->head_dim < 1 || sh->rank < 1) return LRA_ERR_SHAPE;
+  if (sh->n_q_heads % sh->n_kv_heads) return LRA_ERR_SHAPE;
+  if (!(sh->scale >= 0.f) || std::isinf(sh->scale)) return LRA_ERR_SHAPE;
+  if (!(sh->key_rope_theta >= 0.f) || std::isinf(sh->key_rope_theta)) return LRA_ERR_SHAPE;
+  if (sh->key_rope_theta > 0.f && (sh->head_dim & 1)) return LRA_ERR_SHAPE;
+  if (sh->head_dim != 64 && sh->head_dim != 128) return LRA_ERR_UNSUPPORTED;
+  if (sh->rank > 64) return LRA_ERR_UNSUPPORTED;
+  if (sh->n_q_heads / sh->n_kv_heads > 16) return LRA_ERR_UNSUPPORTED;
+  if (sh->n_q_heads > 4096) return LRA_ERR_UNSUPPORTED;
+  if (!c->k_base || !c->v_base || !c->l || !c->seq_lens) return LRA_ERR_NULL;
+  if (c->n_seqs < 1 || c->max_seq_len < 1) return LRA_ERR_SHAPE;
+  if (c->n_seqs > (1 << 20) || c->max_seq_len > (1 << 30)) return LRA_ERR_UNSUPPORTED;
+  if (c->block_size != 0 && c->block_size != 16) return LRA_ERR_UNSUPPORTED;
+  if (c->kv_token_stride < sh->head_dim || c->kv_head_stride < sh->head_dim) return LRA_ERR_SHAPE;
+  if ((c->kv_token_stride | c->kv_head_stride) & 7) return LRA_ERR_SHAPE;
+  // extents stay far inside 64-bit element offsets (and the planner's products inside int64)
+  if (c->kv_token_stride > (int64_t{1} << 31) || c->kv_head_stride > (int64_t{1} << 40)) return LRA_ERR_UNSUPPORTED;
+  if (c->block_size == 0) {
+    if (c->n_seqs != 1) return LRA_ERR_SHAPE;
+  } else {
+    if (!c->block_table) return LRA_ERR_NULL;
+    if (c->num_blocks < 1 || c->max_blocks_per_seq < 1) return LRA_ERR_SHAPE;
+    if (c->kv_block_stride < 16 * sh->head_dim || (c->kv_block_stride & 7)) return LRA_ERR_SHAPE;
+    if (c->kv_block_stride > (int64_t{1} << 40) || c->num_blocks > (int64_t{1} << 60) / c->kv_block_stride)
+      return LRA_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(c->max_blocks_per_seq) * 16 < c->max_seq_len) return LRA_ERR_SHAPE;
+  }
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(c->k_base) | reinterpret_cast<uintptr_t>(c->v_base) |
+                         reinterpret_cast<uintptr_t>(c->l);
+  if (bits & 15) return LRA_ERR_SHAPE;
+  return LRA_OK;
+}
+
+Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_queries_per_seq, bool prefill,
+               const Tuning& tune) {
+  Plan pl{};
+  const int G = sh->n_q_heads / sh->n_kv_heads;
+  // The MFMA kernels move L in 16-byte pieces: ranks that are not a multiple of 8 take the
+  // vector-ALU kernels.
+  // The rotary key side: prefill runs on the tile-walking MFMA kernel, which completes a key
+  // tile in LDS for its one adapter; decode on the rotary form of the split-KV kernel.
+  const bool rope = sh->key_rope_theta > 0.f;
+  pl.mfma = sh->dtype == LRA_BF16 && tune.variant != 1 && sh->rank % 8 == 0;
+  if (prefill && pl.mfma) {
+    // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
+    // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
+    const int64_t lim = (int64_t{1} << 32) - 4096;
+    const int64_t l_rows = c->block_size == 0 ? c->max_seq_len : static_cast<int64_t>(c->num_blocks) * 16;
+    if (l_rows * sh->rank * 2 > lim) pl.mfma = false;
+    if (c->block_size == 0 && static_cast<int64_t>(c->max_seq_len) * c->kv_token_stride * 2 > lim) pl.mfma = false;
+  }
+  // A handful of new tokens after a long context gives the tile-walking prefill kernel one
+  // workgroup per q head and nothing to split; the split-KV decode kernel, with the new
+  // tokens in the place of the agents and a causal limit per row, spreads the context over
+  // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
+  pl.short_prefill = prefill && pl.mfma && tokens <= tune.short_prefill &&
+                     static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
+  const bool rope_split = rope && pl.mfma && (!prefill || pl.short_prefill);  // rotary form of the split-KV kernel
+  if (prefill && pl.mfma && !pl.short_prefill) {
+    // Tile-walking kernel: one workgroup per (128-row q tile, q head).  When that is fewer than
+    // two workgroups per CU, the key tiles of every q tile are divided among several workgroups
+    // (at least eight 64-key tiles each) and the merge kernel finishes the job; otherwise it is
+    // one kernel without a workspace.
+    pl.rows = tokens * sh->n_q_heads;
+    pl.group_pad = pl.row_tiles = pl.row_groups = 1;
+    pl.split_keys = c->max_seq_len;
+    const int64_t wgs = static_cast<int64_t>((tokens + 127) / 128) * sh->n_q_heads;
+    int64_t ns = tune.prefill_splits;
+    if (ns <= 0) {  // automatic: two workgroups per CU, at least eight key tiles per share
+      ns = (2 * kCUs + wgs - 1) / wgs;
+      const int64_t max_ns = c->max_seq_len / (8 * 64);
+      ns = ns > max_ns ? max_ns : ns;
+    }
+    ns = ns > 32 ? 32 : (ns < 1 ? 1 : ns);
+    pl.n_splits = static_cast<int>(ns);
+    pl.bytes = 0;
+    if (pl.n_splits > 1) {
+      const size_t slots = static_cast<size_t>(pl.rows) * pl.n_splits;
+      pl.off_ml = 0;
+      pl.off_o = align_up(slots * 2 * sizeof(float), 256);
+      pl.off_lr = pl.off_o + align_up(slots * sh->head_dim * sizeof(float), 256);
+      pl.off_adapter = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
+      pl.bytes = pl.off_adapter + align_up(static_cast<size_t>(pl.rows) * sizeof(int32_t), 256);
+    }
+    pl.off_qt = pl.bytes;
+    pl.launchable = true;  // at most 32 shares in y
+    return pl;
+  }
+  pl.rows = tokens * sh->n_q_heads;
+  pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
+  pl.row_tiles = 1;
+  pl.row_groups = 1;
+  int tile = 64;       // keys per wave-step of the vector-ALU kernel
+  int64_t work;        // units that want a wave (vector-ALU) or a workgroup share (MFMA)
+  int want;
+  const int n_seqs_eff = prefill ? 1 : c->n_seqs;
+  if (pl.short_prefill) max_queries_per_seq = tokens;
+  if (pl.mfma) {
+    int rows_needed = max_queries_per_seq * pl.group_pad;
+    pl.row_tiles = decode_mfma_row_tiles(rows_needed);
+    if (rope_split) {
+      // one row tile per workgroup, and (decode) no more agent slots in it than the kernel keeps
+      // B_K^T operands for
+      const int min_pad = prefill ? 1 : 16 / decode_mfma_rope_slots(sh->rank);
+      pl.group_pad = pl.group_pad > min_pad ? pl.group_pad : min_pad;
+      pl.row_tiles = 1;
+      rows_needed = max_queries_per_seq * pl.group_pad;
+    }
+    pl.row_groups = (rows_needed + 16 * pl.row_tiles - 1) / (16 * pl.row_tiles);
+    tile = 128;        // 4 waves x 32 keys
+    work = static_cast<int64_t>(n_seqs_eff) * sh->n_kv_heads * pl.row_groups;
+    want = kCUs;
+  } else {
+    work = pl.rows;
+    want = kCUs * 8;
+  }
+  int split_keys = tune.split_keys;
+  if (split_keys <= 0 && pl.mfma) {
+    // Measured on MI355X: one sequence runs best with about one workgroup per CU (the
+    // per-workgroup prologue is not amortised otherwise); a ragged batch wants about four
+    // times as many, equal-sized pieces so the CUs stay balanced.  A batch is assumed to be
+    // half as long on average as its longest sequence.
+    const bool batch = n_seqs_eff > 1;
+    const int64_t wgs = batch ? kCUs * 4 : kCUs;
+    if (work >= 2 * wgs) {
+      split_keys = c->max_seq_len;  // more units than workgroups wanted: one share per sequence
+    } else {
+      const int64_t key_heads = work * c->max_seq_len / (batch ? 2 : 1);
+      const int64_t sk = (key_heads + wgs - 1) / wgs;
+      split_keys = sk > c->max_seq_len ? c->max_seq_len : static_cast<int>(sk);
+    }
+  } else if (split_keys <= 0) {
+    int64_t ns = (want + work - 1) / work;
+    const int64_t max_ns = (c->max_seq_len + tile - 1) / tile;
+    ns = ns < 1 ? 1 : (ns > max_ns ? max_ns : ns);
+    split_keys = static_cast<int>((c->max_seq_len + ns - 1) / ns);
+  }
+  if (split_keys > (1 << 30)) split_keys = 1 << 30;  // (a tuning value; max_seq_len itself is capped there)
+  split_keys = (split_keys + tile - 1) / tile * tile;
+  if (pl.mfma && c->block_size == 0) {
+    // the kernel addresses one split of a contiguous cache with 32-bit byte offsets
+    const int64_t cap = ((int64_t{1} << 31) - 4096) / (c->kv_token_stride * 2) / tile * tile;
+    if (cap < tile) pl.mfma = false;
+    else if (split_keys > cap) split_keys = static_cast<int>(cap);
+  }
+  if (!pl.mfma) pl.short_prefill = false;
+  pl.split_keys = split_keys;
+  pl.n_splits = static_cast<int>((static_cast<int64_t>(c->max_seq_len) + split_keys - 1) / split_keys);
+  // grids: (kv head, share, sequence x row group) for the MFMA kernels, (row, share) otherwise
+  pl.launchable = pl.n_splits <= 65535 &&
+                  (!pl.mfma || static_cast<int64_t>(n_seqs_eff) * pl.row_groups <= 65535);
+  const size_t slots = static_cast<size_t>(pl.rows) * pl.n_splits;
+  pl.off_ml = 0;
+  pl.off_o = align_up(slots * 2 * sizeof(float), 256);
+  pl.off_lr = pl.off_o + align_up(slots * sh->head_dim * sizeof(float), 256);
+  pl.off_adapter = pl.off_lr + align_up(slots * sh->rank * sizeof(float), 256);
+  pl.bytes = pl.off_adapter + align_up(static_cast<size_t>(pl.rows) * sizeof(int32_t), 256);
+  // room for Qt of the whole call where the streaming form of the split-KV kernel would
+  // otherwise reload many B_K rows per workgroup (reserved whether or not the call has a B_K)
+  pl.off_qt = pl.bytes;
+  pl.qt_bytes = 0;
+  if (pl.mfma && c->block_size == 0 && !rope_split && tune.variant != 2)
+    pl.qt_bytes = decode_stream_qt_bytes(pl.group_pad, sh->rank, pl.row_tiles, pl.row_groups, sh->n_kv_heads);
+  pl.bytes += align_up(pl.qt_bytes, 256);
+  return pl;
+}
+
+}  // namespace lra

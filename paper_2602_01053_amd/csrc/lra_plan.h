@@ -1,0 +1,53 @@
+// Host-side launch planning of the Flash-LoRA-Attention library: argument checks and the choice
+// of kernel family, key shares, row packing and workspace layout.  Plain C++ with no HIP
+// dependency, so that the arithmetic (32-bit offset caps, workspace sizes) can also be compiled
+// for the CPU alone and run under the address and undefined-behaviour sanitizers.
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lra_attn.h"
+
+namespace lra {
+
+constexpr int kCUs = 256;  // MI355X
+
+// lra_tuning with every "0 = automatic" resolved.
+struct Tuning {
+  int variant = 0;          // 0 automatic, 1 vector-ALU kernels, 2 MFMA kernels without the streaming form
+  int split_keys = 0;       // keys per workgroup in decode, 0 = automatic
+  int short_prefill = 32;   // new tokens up to which a prefill takes the split-KV path (0 = never)
+  int prefill_splits = 0;   // workgroups sharing the key tiles of a q tile, 0 = automatic
+  int append_skinny = 64;   // new tokens up to which lra_cache_append streams the weights (0 = never)
+  int append_stages = 0;    // LDS stages of the tiled append GEMM, 0 = chosen from the grid
+  int append_tile = 0;      // output tile of the append GEMM, 0 = chosen from the grid
+  bool main_kernel_only = false;  // measurement: enqueue only the dominant kernel of a call
+};
+Tuning resolve_tuning(const lra_tuning* t);
+
+struct Plan {
+  bool mfma;
+  bool short_prefill;  // prefill served by the split-KV decode kernels (few new tokens)
+  int rows;        // query rows = (queries | new tokens) x Hq
+  int split_keys;  // keys per split
+  int n_splits;    // splits per sequence at max_seq_len
+  int group_pad, row_tiles, row_groups;  // MFMA decode row packing
+  bool launchable;  // false: a grid dimension would exceed the limit of 65535 in y or z (LRA_ERR_UNSUPPORTED)
+  size_t off_ml, off_o, off_lr, off_adapter, off_qt, qt_bytes, bytes;
+};
+
+lra_status check_common(const lra_shape* sh, const lra_cache* c);
+// false: the call is too large for the planner's 32-bit row arithmetic (LRA_ERR_UNSUPPORTED)
+bool plan_sizes_fit(const lra_shape* sh, const lra_cache* c, int32_t tokens, int32_t max_queries_per_seq);
+Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_queries_per_seq, bool prefill,
+               const Tuning& tune);
+
+// Row tiles per workgroup the split-KV MFMA kernels are built for.
+int decode_mfma_row_tiles(int rows_needed);
+// Agent slots a 16-row tile may hold in the rotary form of the split-KV kernel.
+int decode_mfma_rope_slots(int rank);
+// Bytes of workspace the Qt pre-pass of the streaming form takes (0: Qt is formed per workgroup).
+size_t decode_stream_qt_bytes(int group_pad, int rank, int row_tiles, int row_groups, int n_kv_heads);
+
+}  // namespace lra

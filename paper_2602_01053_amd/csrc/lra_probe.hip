@@ -2,7 +2,7 @@
 // bf16 MFMA loop reach on the GPU at hand, so that a kernel's fraction of the published
 // peaks (8 TB/s, 2.5 PFLOP/s) can be read beside its fraction of what the machine gives.
 // Neither is part of the attention path.
-#include "lra_attn.h"
+#include "lra_attn_measure.h"
 #include "lra_common.h"
 
 namespace lra {

@@ -7,7 +7,7 @@ import re
 import pytest
 
 import paper_2602_01053_amd as lra
-from paper_2602_01053_amd.binding import LraAdapters, LraCache, LraShape
+from paper_2602_01053_amd.binding import LraAdapters, LraCache, LraShape, LraTuning
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -21,12 +21,12 @@ def lib():
 
 
 def test_header_symbols_are_exported(lib):
-    text = open(os.path.join(ROOT, "include", "lra_attn.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(lra_[a-z0-9_]+)\s*\(", text))
     assert {"lra_attn_decode", "lra_attn_prefill", "lra_workspace_bytes"} <= declared
     for name in declared:
-        assert hasattr(lib, name), f"{name} declared in lra_attn.h but not exported"
+        assert hasattr(lib, name), f"{name} declared in include/ but not exported"
     assert declared == set(lra.binding.EXPORTS)
 
 
@@ -48,12 +48,12 @@ def _good():
 
 def _decode(lib, sh, c, ad, q=FAKE, qa=FAKE, sqs=FAKE, n_queries=4, mq=4, out=FAKE, ws=None, ws_bytes=0):
     return lib.lra_attn_decode(ctypes.byref(sh), ctypes.byref(c), ctypes.byref(ad), q, qa, sqs,
-                               n_queries, mq, out, ws, ws_bytes, None)
+                               n_queries, mq, out, ws, ws_bytes, None, None)
 
 
 def _prefill(lib, sh, c, ad, q=FAKE, seq=0, a=0, n_new=16, out=FAKE, ws=None, ws_bytes=0):
     return lib.lra_attn_prefill(ctypes.byref(sh), ctypes.byref(c), ctypes.byref(ad), q, seq, a, n_new,
-                                out, ws, ws_bytes, None)
+                                out, ws, ws_bytes, None, None)
 
 
 def test_static_workspace_entry_point_rejects_before_any_gpu_call(lib):
@@ -61,13 +61,13 @@ def test_static_workspace_entry_point_rejects_before_any_gpu_call(lib):
     its fixed buffer, before it touches the GPU (there is none here)."""
     sh, c, ad = _good()
     call = lambda s, cc, a, nq=4, mq=4, q=FAKE: lib.lra_attn_decode_static(
-        ctypes.byref(s), ctypes.byref(cc), ctypes.byref(a), q, FAKE, FAKE, nq, mq, FAKE, None)
+        ctypes.byref(s), ctypes.byref(cc), ctypes.byref(a), q, FAKE, FAKE, nq, mq, FAKE, None, None)
     assert call(sh, c, ad, q=None) == 1
     assert call(sh, c, ad, nq=0) == 2
     sh.rank = 65
     assert call(sh, c, ad) == 4
     sh, c, ad = _good()
-    need = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4096, 4096, 0)
+    need = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4096, 4096, 0, None)
     assert need > lra.binding.STATIC_WORKSPACE_BYTES
     assert call(sh, c, ad, nq=4096, mq=4096) == 5
     text = open(os.path.join(ROOT, "include", "lra_attn.h")).read()
@@ -79,7 +79,7 @@ def test_rejects_bad_arguments_before_launch(lib):
     NULL, SHAPE, DTYPE, UNSUP, WS = 1, 2, 3, 4, 5
     sh, c, ad = _good()
     assert lib.lra_attn_decode(None, ctypes.byref(c), ctypes.byref(ad), FAKE, FAKE, FAKE, 4, 4, FAKE,
-                               None, 0, None) == NULL
+                               None, 0, None, None) == NULL
     assert _decode(lib, sh, c, ad, q=None) == NULL
     assert _decode(lib, sh, c, ad, out=None) == NULL
     assert _decode(lib, sh, c, ad, qa=None) == NULL
@@ -119,7 +119,9 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _decode(lib, sh, c, ad, mq=5) == SHAPE
     # good arguments but no / small / misaligned workspace: refused, nothing launched
     assert _decode(lib, sh, c, ad) == WS
-    need = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 4, 0)
+    wsb = lambda s_, n_q, mq, n_new, tune=None: lib.lra_workspace_bytes(
+        ctypes.byref(s_), ctypes.byref(c), n_q, mq, n_new, None if tune is None else ctypes.byref(tune))
+    need = wsb(sh, 4, 4, 0)
     assert 0 < need < (1 << 40)
     assert _decode(lib, sh, c, ad, ws=0x10000, ws_bytes=need - 1) == WS
     assert _decode(lib, sh, c, ad, ws=0x10010, ws_bytes=need) == WS
@@ -129,22 +131,20 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _prefill(lib, sh, c, ad, n_new=0) == SHAPE
     assert _prefill(lib, sh, c, ad, n_new=8193) == SHAPE
     assert _prefill(lib, sh, c, ad, q=None) == NULL
-    bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 0)
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 2048) == 0    # bf16 prefill, enough q tiles: one kernel
-    assert 0 < lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 1024) < (1 << 40)   # key tiles shared: merge
-    short = lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16)           # few new tokens: split-KV path
-    assert 0 < short < (1 << 40)
-    lib.lra_set_short_prefill.restype = ctypes.c_int32
-    old = lib.lra_set_short_prefill(0)
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) > 0       # that path off: key tiles shared instead
-    lib.lra_set_prefill_splits.restype = ctypes.c_int32
-    assert lib.lra_set_prefill_splits(1) == 0
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 0, 0, 16) == 0      # one workgroup per q tile and head
-    assert lib.lra_set_prefill_splits(0) == 1
-    assert lib.lra_set_short_prefill(old) == 0 and old > 0
+    bad = lib.lra_workspace_bytes(ctypes.byref(mutated(head_dim=96)[0]), ctypes.byref(c), 4, 4, 0, None)
+    assert wsb(sh, 0, 0, 2048) == 0                  # bf16 prefill, enough q tiles: one kernel
+    assert 0 < wsb(sh, 0, 0, 1024) < (1 << 40)       # key tiles shared: merge
+    assert 0 < wsb(sh, 0, 0, 16) < (1 << 40)         # few new tokens: split-KV path
+    # the tuning struct travels with the call: the library keeps none of it
+    assert wsb(sh, 0, 0, 16, LraTuning()) == wsb(sh, 0, 0, 16)             # all zero = automatic
+    no_short = LraTuning(short_prefill=-1)
+    assert wsb(sh, 0, 0, 16, no_short) > 0           # that path off: key tiles shared instead
+    assert wsb(sh, 0, 0, 16, LraTuning(short_prefill=-1, prefill_splits=1)) == 0   # one workgroup per q tile and head
+    assert wsb(sh, 0, 0, 16) == wsb(sh, 0, 0, 16, LraTuning(short_prefill=32))     # nothing stuck from the calls above
+    assert wsb(sh, 4, 4, 0, LraTuning(decode_split_keys=4096)) < need              # fewer key shares, fewer partial states
     sh32 = mutated(dtype=1)[0]
-    assert 0 < lib.lra_workspace_bytes(ctypes.byref(sh32), ctypes.byref(c), 0, 0, 16) < (1 << 40)
-    assert lib.lra_workspace_bytes(ctypes.byref(sh), ctypes.byref(c), 4, 5, 0) == ctypes.c_size_t(-1).value
+    assert 0 < wsb(sh32, 0, 0, 16) < (1 << 40)
+    assert wsb(sh, 4, 5, 0) == ctypes.c_size_t(-1).value
     assert bad == ctypes.c_size_t(-1).value
 
 
@@ -158,7 +158,7 @@ def test_cache_append_rejects_bad_arguments_before_launch(lib):
         c = c or c0
         pr = LraProjection(w, d_model, theta)
         return lib.lra_cache_append(ctypes.byref(sh), ctypes.byref(c), None if no_proj else ctypes.byref(pr), x, seq,
-                                    n_new, None)
+                                    n_new, None, None)
 
     assert call(no_proj=True) == NULL
     assert call(w=None) == NULL
@@ -169,6 +169,7 @@ def test_cache_append_rejects_bad_arguments_before_launch(lib):
     assert call(d_model=0) == SHAPE
     assert call(theta=-1.0) == SHAPE
     assert call(theta=float("nan")) == SHAPE
+    assert call(theta=float("inf")) == SHAPE
     assert call(x=FAKE + 8) == SHAPE                  # misaligned
     assert call(d_model=4000) == UNSUP                # not a multiple of 64
     assert call(d_model=1 << 22) == UNSUP             # weights beyond 32-bit byte offsets
@@ -183,16 +184,33 @@ def test_cache_append_rejects_bad_arguments_before_launch(lib):
     assert call(c=c) == NULL
 
 
-def test_tuning_hooks_round_trip(lib):
+def test_tuning_helpers_of_the_binding_round_trip(lib):
+    """The lra_set_* helpers edit the one struct the binding passes to every call and return the previous value."""
     old = lra.lra_set_append_skinny(7)
     assert lra.lra_set_append_skinny(old) == 7 and old == 64
-    assert lra.lra_set_append_stages(3) == 0 and lra.lra_set_append_stages(9) == 3 and lra.lra_set_append_stages(0) == 0
-    assert lra.lra_set_append_tile(256) == 0 and lra.lra_set_append_tile(64) == 256 and lra.lra_set_append_tile(100) == 64
-    assert lra.lra_set_append_tile(0) == 0
+    assert lra.lra_set_append_skinny(0) == 64 and lra.binding._tuning.append_skinny == -1     # 0 = off
+    assert lra.lra_set_append_skinny(64) == 0
+    assert lra.lra_set_append_stages(3) == 0 and lra.lra_set_append_stages(0) == 3
+    assert lra.lra_set_append_tile(256) == 0 and lra.lra_set_append_tile(0) == 256
     old = lra.lra_set_decode_split_keys(512)
     assert lra.lra_set_decode_split_keys(old) == 512
     old = lra.lra_set_kernel_variant(1)
     assert lra.lra_set_kernel_variant(old) == 1
+    old = lra.lra_set_short_prefill(0)
+    assert old == 32 and lra.lra_set_short_prefill(old) == 0
+    assert lra.lra_set_profile_mode(1) == 0 and lra.lra_set_profile_mode(0) == 1
+    t = lra.binding._tuning
+    assert (t.kernel_variant, t.decode_split_keys, t.prefill_splits, t.append_stages, t.append_tile,
+            t.measure_main_kernel_only) == (0, 0, 0, 0, 0, 0)
+
+
+def test_library_exports_no_setters(lib):
+    """No process-wide tuning state in the C library: nothing but the entry points of the headers is exported
+    under the lra_ prefix."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", lra.binding.LIB_PATH], capture_output=True, text=True).stdout
+    exported = {ln.split()[-1] for ln in out.splitlines() if " T " in ln and ln.split()[-1].startswith("lra_")}
+    assert exported == set(lra.binding.EXPORTS), exported ^ set(lra.binding.EXPORTS)
 
 
 def test_binding_fails_loudly_without_library(monkeypatch):
@@ -211,11 +229,12 @@ def test_header_is_plain_c(tmp_path):
         pytest.skip("no C compiler")
     src = tmp_path / "use_header.c"
     src.write_text(
-        '#include "lra_attn.h"\n'
+        '#include "lra_attn.h"\n#include "lra_attn_measure.h"\n'
         "lra_status call(const lra_shape* s, const lra_cache* c, const lra_projection* p, const void* x) {\n"
-        "  return lra_cache_append(s, c, p, x, 0, 1, (void*)0);\n"
+        "  lra_tuning t = {0, 0, 0, 0, 0, 0, 0, 0};\n"
+        "  return lra_cache_append(s, c, p, x, 0, 1, &t, (void*)0);\n"
         "}\n"
-        "size_t need(const lra_shape* s, const lra_cache* c) { return lra_workspace_bytes(s, c, 4, 4, 0); }\n")
+        "size_t need(const lra_shape* s, const lra_cache* c) { return lra_workspace_bytes(s, c, 4, 4, 0, (const lra_tuning*)0); }\n")
     res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                           "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
