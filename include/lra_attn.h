@@ -133,12 +133,18 @@ typedef struct {
   const int32_t* block_table;  /* DEVICE int32 [n_seqs][max_blocks_per_seq]; NULL when contiguous */
   const int32_t* seq_lens;     /* DEVICE int32 [n_seqs]: cached tokens n_t of each sequence, >= 1 */
   int32_t max_seq_len;         /* HOST-known upper bound of every seq_lens[t]; sizes the launch.
-                                  Sequences longer than this are truncated to it. */
+                                  The attention calls treat a longer sequence as if it ended
+                                  there (decode: its first max_seq_len tokens; prefill: the new
+                                  tokens are taken to be the last of those).  lra_cache_append
+                                  writes nothing for a sequence whose device-side length
+                                  exceeds it. */
 } lra_cache;
 
 /*
  * Per-agent adapter table (Sec. 3.2: every agent turns the shared caches into its own
  * keys and values through its own up-projection B_i).
+ * Adapter ids (query_adapter) are device data the host cannot check: the kernels clamp them
+ * into [0, n_adapters), so a bad id selects a wrong adapter but never reads outside the tables.
  * b_k / b_v: DEVICE [n_adapters][rank][Hkv*head_dim], row-major; kv head h owns
  * columns h*d .. (h+1)*d-1 (Eq. 1: B is r x d_out).  Any LoRA scaling alpha/r is
  * folded into B by the caller.  b_k == NULL means B_K = 0 for every adapter (the

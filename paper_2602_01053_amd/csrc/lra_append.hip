@@ -27,6 +27,12 @@
 
 namespace lra {
 
+// Length of the sequence the new rows are appended to.  max_seq_len is exact for this call: it
+// sizes the caches, so a device-side length beyond it cannot be honoured - such a call writes
+// nothing (every row index comes out negative and is skipped) rather than overwrite live rows.
+__device__ __forceinline__ int append_length(int len, int max_seq_len) { return len <= max_seq_len ? len : 0; }
+
+
 // BT = 64 halves the token side of the tile (a wave then owns 64 features x 32 tokens): twice the
 // workgroups and three quarters of the bytes per step for chunks too small to fill the chip.
 template <int D, bool PAGED, int NS, int BT = 128>
@@ -57,7 +63,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   const int w_row0 = (kind == 0 ? 0 : (kind == 1 ? HD : 2 * HD)) + feat0;  // its row of w
   const int tok0 = blockIdx.x * BT;
   const int n_new = p.n_new;
-  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int n_t = append_length(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
   const int pos0 = n_t - n_new;  // cache row (= position) of new token 0
 
   // ---------------- tile traffic ----------------
@@ -299,7 +305,7 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
   const int w_row0 = (kind == 0 ? 0 : (kind == 1 ? HD : 2 * HD)) + feat0;
   const int tok0 = blockIdx.x * BT;
   const int n_new = p.n_new;
-  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int n_t = append_length(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
   const int pos0 = n_t - n_new;
 
   // tile traffic: as in append_kernel, 32 wave-wide loads per tile, wave w issues i = w + 4q
@@ -511,7 +517,7 @@ __global__ __launch_bounds__(512) void append_skinny_kernel(AppendParams p) {
   };
   const int n_new = p.n_new;
   const int tok0 = blockIdx.y * (16 * NT);
-  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int n_t = append_length(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
   const int pos0 = n_t - n_new;
 
   // operand rows of this lane (clamped into the tensors; what a clamped row produces is never stored)
@@ -702,7 +708,7 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
   // thread (pair, token): both halves of a rotary pair (K), two independent features (V, L)
   if (tid >= 2 * NT) return;
   const int q = tid & 1, t = tid >> 1;
-  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int n_t = append_length(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
   const int j = n_t - n_new + t;
   if (t >= n_new || j < 0) return;
   float lo = red[q][t], hi = red[2 + q][t];

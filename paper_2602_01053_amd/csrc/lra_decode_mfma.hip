@@ -178,7 +178,9 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
       if (CAUSAL)
         a_slot[rt][si] = (si < 16 / GP && slot < n_q) ? p.adapter_index : -1;
       else
-        a_slot[rt][si] = ((HAS_BK || warm_bv) && si < 16 / GP && slot < n_q) ? CONST_I32(p.query_adapter)[q_begin + slot] : -1;
+        a_slot[rt][si] = ((HAS_BK || warm_bv) && si < 16 / GP && slot < n_q)
+                             ? min(max(CONST_I32(p.query_adapter)[q_begin + slot], 0), p.n_adapters - 1)  // device data: kept inside the table
+                             : -1;
     }
   const int j1 = min(j0 + p.split_keys, n_t);
   const int kpw = p.split_keys / NW;  // multiple of 32

@@ -108,8 +108,8 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       const int slot = ((row0 + rt * 16) >> gps) + si;
       const bool live = si < (16 >> gps) && slot < n_q;
       int a = -1;
-      if (live) a = CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[slot];
-      a_slot[rt][si] = (a >= 0 && a < p.n_adapters) ? a : -1;  // an id outside the table counts as no adapter
+      if (live) a = min(max(CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[slot], 0), p.n_adapters - 1);
+      a_slot[rt][si] = a;  // (ids are device data: kept inside the table, as the merge kernel does)
     }
   auto slot_adapter = [&](int rt, int si) {
     return si == 0 ? a_slot[rt][0] : (si == 1 ? a_slot[rt][1] : (si == 2 ? a_slot[rt][2] : a_slot[rt][3]));
@@ -623,8 +623,8 @@ __global__ __launch_bounds__(256) void decode_qt_prepass_kernel(Params p, int ro
   const int slot = (tile_row0 >> gps) + si;
   if (si >= (16 >> gps) || cb >= ncb) return;
   int a = -1;
-  if (slot < n_q) a = CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[slot];
-  const bool live = a >= 0 && a < p.n_adapters;
+  if (slot < n_q) a = min(max(CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[slot], 0), p.n_adapters - 1);
+  const bool live = a >= 0;
   const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
   const __amdgpu_buffer_rsrc_t rs_q = make_rsrc(p.q, static_cast<uint32_t>(n_q) * p.n_q_heads * D * 2);
   const __amdgpu_buffer_rsrc_t rs_b =

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
   } else {
     t = 0;
     while (t + 1 < p.n_seqs && p.seq_query_start[t + 1] <= tok) ++t;
-    a = p.query_adapter[tok];
+    a = min(max(p.query_adapter[tok], 0), p.n_adapters - 1);  // ids are device data: kept inside the table
     n_vis = min(p.seq_lens[t], p.max_seq_len);
   }
   const int j0 = split * p.split_keys;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kWave) void generic_partial_rope_kernel(Params p) {
   } else {
     t = 0;
     while (t + 1 < p.n_seqs && p.seq_query_start[t + 1] <= tok) ++t;
-    a = p.query_adapter[tok];
+    a = min(max(p.query_adapter[tok], 0), p.n_adapters - 1);  // ids are device data: kept inside the table
     n_vis = min(p.seq_lens[t], p.max_seq_len);
   }
   const int j0 = split * p.split_keys;

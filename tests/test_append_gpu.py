@@ -236,3 +236,20 @@ def test_append_llama3_8b_full_size_sampled_rows(n_new, prior):
     _gate(f(l[prior + rows]), l_ref, "L rows")
     if prior:
         assert bool((k_base[:prior] == SENTINEL).all()) and bool((l[:prior] == SENTINEL).all())
+
+
+@pytest.mark.parametrize("n_new", [1, 5, 200, 2048], ids=lambda n: f"new{n}")
+def test_append_writes_nothing_when_the_device_length_exceeds_the_bound(n_new):
+    """max_seq_len sizes the caches: a device-side sequence length beyond it cannot be honoured, and the call must
+    leave every cache row as it was (all four kernels: matrix-vector, weight-streaming, tiled, wide tile)."""
+    hkv, d, r, d_model, rows = 2, 128, 16, 256, 2100
+    x, w = _inputs(900 + n_new, n_new, d_model, hkv, d, r)
+    k = torch.full((rows, hkv, d), SENTINEL, dtype=torch.bfloat16, device=DEV)
+    v = torch.full_like(k, SENTINEL)
+    l = torch.full((rows, r), SENTINEL, dtype=torch.bfloat16, device=DEV)
+    lens = torch.tensor([rows + 50], dtype=torch.int32, device=DEV)       # longer than the cache can hold
+    shape = lra.make_shape(torch.empty(1, hkv, d, dtype=torch.bfloat16, device=DEV), hkv, r, 0.0)
+    lra.lra_cache_append(shape, lra.make_cache(k, v, l, lens, rows, None), w.to(DEV), 500000.0, x.to(DEV), 0)
+    torch.cuda.synchronize()
+    for name, t in (("K", k), ("V", v), ("L", l)):
+        assert bool((t == SENTINEL).all()), f"{name} rows were overwritten"

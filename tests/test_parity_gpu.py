@@ -405,3 +405,18 @@ def test_prefill_with_shared_key_tiles_and_many_rows():
         lra.lra_set_short_prefill(prev_s)
         lra.lra_set_prefill_splits(prev_p)
     _gate(got, oracle_prefill(w), label=w.name)
+
+
+def test_adapter_ids_outside_the_table_are_clamped(variant):
+    """query_adapter is device data the host cannot check: every kernel keeps an id inside [0, n_adapters) by
+    clamping, so a bad id gives the result of the nearest valid adapter and no read outside B_K / B_V."""
+    w = W.make_contiguous("bad_ids", "decode", seed=88, n_agents=5, n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16,
+                          n=700, d_model=None, b_std=0.05)
+    good = w.query_adapter.clone()
+    bad = good.clone()
+    bad[1], bad[3] = 99, -7                       # clamp to the last and to the first adapter
+    good[1], good[3] = w.n_adapters - 1, 0
+    w.query_adapter = bad
+    got = run_decode(w, DEV)
+    w.query_adapter = good
+    _gate(got, oracle_decode(w), label="clamped adapter ids")
