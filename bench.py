@@ -262,6 +262,44 @@ def value_only_decode(args, torch, lra, workloads):
 MIN_PREFILL_LAUNCHES = 50
 
 
+def base_shared_decode(args, torch, lra, workloads):
+    """The headline decode workload under BaseShared (Sec. 3.2): every agent has its OWN low-rank cache
+    L_a [n][r] (stored [n][A][r]), so a call streams A*r instead of r low-rank elements per token.
+    Algorithmic bytes: K_base + V_base + A caches L_a + B_K + B_V + Q + out."""
+    from paper_2602_01053_amd.runner import DeviceWorkload
+    dev = torch.device("cuda:0")
+    w = workloads.config(2)
+    agents, n, r = w.n_queries, w.seq_lens[0], w.rank
+    gen = torch.Generator().manual_seed(20260299)
+    l_all = torch.randn(n, agents, r, generator=gen).to(torch.bfloat16)
+    alg = w.algorithmic_bytes() + (agents - 1) * n * r * 2
+    cache_bytes = (2 * w.k_base.numel() + l_all.numel()) * 2
+    n_copies = int(math.ceil(COLD_BYTES / cache_bytes)) + 1
+    base = DeviceWorkload(w, dev)
+    copies = []
+    for _ in range(n_copies):
+        c = DeviceWorkload.__new__(DeviceWorkload)
+        c.__dict__.update(base.__dict__)
+        c.k_base, c.v_base = base.k_base.clone(), base.v_base.clone()
+        c.l = l_all.to(dev).permute(1, 0, 2)      # view [adapter][token][r] over [n][A][r] storage
+        c.cache = lra.make_cache(c.k_base, c.v_base, c.l, c.seq_lens, n, None, l_per_adapter=True)
+        copies.append(c)
+    nbytes = lra.lra_workspace_bytes(copies[0].shape, copies[0].cache, w.n_queries, copies[0].max_queries_per_seq, 0)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    for c in copies:
+        c.workspace = ws
+    steps = max(20, args.steps // 4)
+    for i in range(10):
+        copies[i % n_copies].decode()
+    sec, _ = graph_seconds(torch, lambda i, st: copies[i % n_copies].decode(st), steps)
+    ksec = kernel_seconds(lra, torch, lambda i, st: copies[i % n_copies].decode(st), steps)
+    torch.cuda.empty_cache()
+    return {"workload": w.name + " with one low-rank cache per agent (BaseShared)", "algorithmic_bytes": alg,
+            "value": round(alg / sec / 1e9, 1), "unit": "GB/s", "ms_per_step": round(sec * 1e3, 5),
+            "kernel_us": round(ksec * 1e6, 2), "kernel_GBps": round(alg / ksec / 1e9, 1),
+            "kernel_frac_of_hbm_peak": round(alg / ksec / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def bench_prefill(args, torch, lra, workloads):
     """Config 3: at least MIN_PREFILL_LAUNCHES timed launches after at least 10 warm-up launches, whatever
     --steps says (a call is one kernel of 0.6 ms; a handful of launches would time the clock ramp)."""
@@ -542,6 +580,7 @@ def main():
     if not args.no_other_decode:
         line["other_decode_workloads"] = other_decode_workloads(args, torch, lra, workloads)
         line["value_only_adapters"] = value_only_decode(args, torch, lra, workloads)
+        line["base_shared"] = base_shared_decode(args, torch, lra, workloads)
     if not args.no_append:
         line["cache_append"] = bench_append(args, torch, lra, not args.no_cpu_baseline)
     if not args.no_trace:

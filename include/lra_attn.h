@@ -118,6 +118,24 @@ typedef struct {
  *   Slots past seq_lens[t] inside the last block may hold anything, NaN included.
  *
  * v_base uses the same strides as k_base.
+ *
+ * Low-rank cache.  Row (token j) of adapter a is the `rank` elements at
+ *       l + a*l_adapter_stride + row_index*l_row_stride
+ *   with row_index = j (contiguous) or b*16 + j%16 (paged), l_row_stride = 0 meaning rank.
+ *   l_adapter_stride = 0 is the paper's final scheme, BaseLRShared: one L for every agent
+ *   (the shared down-projection), all agents' keys and values are K_base + L B_K^a,
+ *   V_base + L B_V^a.  l_adapter_stride > 0 is BaseShared: agent a attends over
+ *   K_base + L_a B_K^a, V_base + L_a B_V^a with its own L_a; [n][A][r] storage is
+ *   row stride A*r, adapter stride r; [A][n][r] storage is row stride r, adapter stride n*r.
+ *   Both strides are multiples of 8 elements (a row stride equal to the rank is always accepted).
+ *   The byte model changes with it: a decode call
+ *   streams the L rows of every agent on the sequence (A*r instead of r elements per token).
+ *   Kernels: bf16 with rank % 8 == 0 runs on the MFMA kernels for a contiguous cache without
+ *   the rotary key side (decode: the agents of a row tile each bring their own column block
+ *   of the L tile, so a tile holds 4 agents at rank <= 16, 2 at rank <= 32, 1 above; prefill:
+ *   the one agent's rows are read with their stride); everything else on the vector-ALU
+ *   kernels.  lra_cache_append fills adapter 0's rows only (BaseLRShared is the scheme with
+ *   one producer call per token).
  */
 typedef struct {
   const void* k_base;          /* DEVICE */
@@ -130,6 +148,12 @@ typedef struct {
   int32_t max_blocks_per_seq;  /* paged only: row length of block_table */
   int32_t num_blocks;          /* paged only */
   int32_t n_seqs;              /* 1 when contiguous */
+  int64_t l_row_stride;        /* elements between consecutive L rows; 0 = dense (rank) */
+  int64_t l_adapter_stride;    /* 0: ONE low-rank cache for all agents (BaseLRShared).
+                                  > 0: BaseShared (Sec. 3.2) - every adapter a has its own
+                                  low-rank cache L_a = X A_a, whose row of a token starts
+                                  a * l_adapter_stride elements after that token's row of
+                                  adapter 0 (see below) */
   const int32_t* block_table;  /* DEVICE int32 [n_seqs][max_blocks_per_seq]; NULL when contiguous */
   const int32_t* seq_lens;     /* DEVICE int32 [n_seqs]: cached tokens n_t of each sequence, >= 1 */
   int32_t max_seq_len;         /* HOST-known upper bound of every seq_lens[t]; sizes the launch.

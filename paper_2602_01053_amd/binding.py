@@ -35,6 +35,7 @@ class LraCache(ctypes.Structure):
                 ("kv_block_stride", ctypes.c_int64),
                 ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
                 ("num_blocks", ctypes.c_int32), ("n_seqs", ctypes.c_int32),
+                ("l_row_stride", ctypes.c_int64), ("l_adapter_stride", ctypes.c_int64),
                 ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
                 ("max_seq_len", ctypes.c_int32)]
 
@@ -201,22 +202,32 @@ def make_shape(q: torch.Tensor, n_kv_heads: int, rank: int, scale: float = 0.0,
 
 
 def make_cache(k_base: torch.Tensor, v_base: torch.Tensor, l: torch.Tensor, seq_lens: torch.Tensor,
-               max_seq_len: int, block_table: Optional[torch.Tensor] = None) -> LraCache:
+               max_seq_len: int, block_table: Optional[torch.Tensor] = None, l_per_adapter: bool = False) -> LraCache:
     """Describe a cache held in torch tensors.
 
     contiguous: k_base/v_base any strided view indexed [token][kv head][d] with a
     unit stride on d; paged: k_base/v_base [num_blocks][Hkv][16][d] (strided view
-    allowed), block_table int32 [n_seqs][max_blocks]."""
+    allowed), block_table int32 [n_seqs][max_blocks].
+    l: one low-rank cache for all adapters, [tokens][r] / [num_blocks][16][r] (rows may be strided);
+    with l_per_adapter (BaseShared) a view indexed [adapter][tokens][r] / [adapter][num_blocks][16][r]
+    in any storage order with a unit stride on r, e.g. [n][A][r] storage permuted."""
     if k_base.stride() != v_base.stride() or k_base.stride(-1) != 1:
         raise LraError(2, "k_base and v_base must share strides, innermost stride 1")
-    if not l.is_contiguous():
-        raise LraError(2, "l must be dense")
+    l_adapter_stride = 0
+    if l_per_adapter:
+        l_adapter_stride, l = l.stride(0), l[0]
+    if l.stride(-1) != 1:
+        raise LraError(2, "l must have a unit stride on the rank")
     if block_table is None:
+        if l.dim() != 2:
+            raise LraError(2, "contiguous l must be [tokens][r]")
         return LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(0), k_base.stride(1), 0,
-                        0, 0, 0, 1, None, _ptr(seq_lens), int(max_seq_len))
+                        0, 0, 0, 1, l.stride(0), l_adapter_stride, None, _ptr(seq_lens), int(max_seq_len))
+    if l.dim() != 3 or l.stride(0) != 16 * l.stride(1):
+        raise LraError(2, "paged l must be [num_blocks][16][r] with the 16 rows of a block one row stride apart")
     return LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(2), k_base.stride(1),
                     k_base.stride(0), int(k_base.shape[2]), int(block_table.shape[1]),
-                    int(k_base.shape[0]), int(block_table.shape[0]), _ptr(block_table),
+                    int(k_base.shape[0]), int(block_table.shape[0]), l.stride(1), l_adapter_stride, _ptr(block_table),
                     _ptr(seq_lens), int(max_seq_len))
 
 

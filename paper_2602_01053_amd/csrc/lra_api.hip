@@ -34,6 +34,9 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.kv_token_stride = c->kv_token_stride;
   p.kv_head_stride = c->kv_head_stride;
   p.kv_block_stride = c->kv_block_stride;
+  p.l_row_stride = c->l_row_stride ? c->l_row_stride : sh->rank;
+  p.l_adapter_stride = c->l_adapter_stride;
+  p.l_block = pl.l_block;
   p.n_q_heads = sh->n_q_heads;
   p.n_kv_heads = sh->n_kv_heads;
   p.group = sh->n_q_heads / sh->n_kv_heads;
@@ -246,6 +249,7 @@ lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, cons
   p.kv_token_stride = cache->kv_token_stride;
   p.kv_head_stride = cache->kv_head_stride;
   p.kv_block_stride = cache->kv_block_stride;
+  p.l_row_stride = cache->l_row_stride ? cache->l_row_stride : shape->rank;
   p.d_model = proj->d_model;
   p.n_kv_heads = shape->n_kv_heads;
   p.head_dim = shape->head_dim;

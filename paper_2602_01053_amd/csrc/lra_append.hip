@@ -224,10 +224,10 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
     int64_t row_off;           // element offset of (token j, kv head 0) in K_base / V_base, or of row j in L
     if (PAGED) {
       const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
-      row_off = kind == 2 ? (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank
+      row_off = kind == 2 ? (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.l_row_stride
                           : static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(j & 15) * p.kv_token_stride;
     } else {
-      row_off = kind == 2 ? static_cast<int64_t>(j) * p.rank : static_cast<int64_t>(j) * p.kv_token_stride;
+      row_off = kind == 2 ? static_cast<int64_t>(j) * p.l_row_stride : static_cast<int64_t>(j) * p.kv_token_stride;
     }
     if (kind == 2) {
       bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
@@ -430,10 +430,10 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
     int64_t row_off;
     if (PAGED) {
       const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
-      row_off = kind == 2 ? (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank
+      row_off = kind == 2 ? (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.l_row_stride
                           : static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(j & 15) * p.kv_token_stride;
     } else {
-      row_off = kind == 2 ? static_cast<int64_t>(j) * p.rank : static_cast<int64_t>(j) * p.kv_token_stride;
+      row_off = kind == 2 ? static_cast<int64_t>(j) * p.l_row_stride : static_cast<int64_t>(j) * p.kv_token_stride;
     }
     if (kind == 2) {
       bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
@@ -599,9 +599,9 @@ __global__ __launch_bounds__(512) void append_skinny_kernel(AppendParams p) {
     int64_t row_off;
     if (PAGED) {
       const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
-      row_off = (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank;
+      row_off = (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.l_row_stride;
     } else {
-      row_off = static_cast<int64_t>(j) * p.rank;
+      row_off = static_cast<int64_t>(j) * p.l_row_stride;
     }
     bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
     const int f = 16 * fg_in + i;
@@ -716,9 +716,9 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
     int64_t row_off;
     if (PAGED) {
       const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
-      row_off = (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank;
+      row_off = (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.l_row_stride;
     } else {
-      row_off = static_cast<int64_t>(j) * p.rank;
+      row_off = static_cast<int64_t>(j) * p.l_row_stride;
     }
     bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
     const int f = 4 * fg_in + q;

@@ -30,6 +30,9 @@ struct Params {
   int32_t* part_adapter;  // [rows]: adapter of the row's query, left by the first kernel for the merge
   void* qt_ws;            // Qt = Q B_K^T of the whole call in MFMA operand order, or null (formed per workgroup)
   int64_t kv_token_stride, kv_head_stride, kv_block_stride;
+  int64_t l_row_stride;      // elements between L rows (>= rank)
+  int64_t l_adapter_stride;  // elements between the L rows of consecutive adapters; 0: one L for all
+  int32_t l_block;           // split-KV MFMA kernels, per-adapter L: padded rank of one agent slot's column block (16, 32, 64); 0: one L
   int32_t n_q_heads, n_kv_heads, group, head_dim, rank;
   int32_t group_pad;   // rows reserved per agent in the MFMA row tiles: 4, 8 or 16 (>= group)
   int32_t row_groups;  // workgroups along the query-row axis per (sequence, kv head)
@@ -89,11 +92,12 @@ __device__ __forceinline__ int64_t kv_offset(const Params& p, int t, int j, int 
          static_cast<int64_t>(j & 15) * p.kv_token_stride;
 }
 
-// Element offset of (sequence t, token j) in L.
-__device__ __forceinline__ int64_t l_offset(const Params& p, int t, int j) {
-  if (p.block_size == 0) return static_cast<int64_t>(j) * p.rank;
+// Element offset of (sequence t, token j) in the L rows of adapter a.
+__device__ __forceinline__ int64_t l_offset(const Params& p, int t, int j, int a) {
+  const int64_t base = static_cast<int64_t>(a) * p.l_adapter_stride;
+  if (p.block_size == 0) return base + static_cast<int64_t>(j) * p.l_row_stride;
   const int blk = p.block_table[static_cast<int64_t>(t) * p.max_blocks_per_seq + (j >> 4)];
-  return (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.rank;
+  return base + (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.l_row_stride;
 }
 
 // Launchers (defined next to their kernels).
@@ -114,6 +118,7 @@ struct AppendParams {
   const int32_t* block_table;
   const int32_t* seq_lens;
   int64_t kv_token_stride, kv_head_stride, kv_block_stride;
+  int64_t l_row_stride;  // elements between L rows (>= rank); the rows of adapter 0 are written
   int32_t d_model, n_kv_heads, head_dim, rank, n_new, seq_index;
   int32_t block_size, max_blocks_per_seq, max_seq_len;
   float rope_theta;

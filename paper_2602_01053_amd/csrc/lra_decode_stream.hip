@@ -67,7 +67,6 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   constexpr int STAGE_BYTES = 2 * KV_BYTES + L_BYTES;
   constexpr int WAVE_BYTES = 2 * STAGE_BYTES;
   constexpr int ROW_BYTES = D * 2;
-  constexpr int LSW_SHIFT = (RP == 32) ? 1 : 0;  // L rows of 64 bytes share a swizzle value in pairs
   constexpr int MAXIT = RP / 16;               // Qt items per prologue wave and row tile: 4 slots x RP/16 rho blocks over 4 waves
   constexpr int Q_BYTES = RT * KS * 1024;      // Q as B operands: 16 bytes per lane, k-step and row tile
   constexpr int QT_BYTES = RT * RKS * 1024;
@@ -178,7 +177,18 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
         if (idx < RT * RKS) *reinterpret_cast<uint4*>(qt_lds + (idx * 64 + lane) * 16) = piece[i];
       }
     }
+    // Per-adapter low-rank caches (BaseShared): the L tile holds one column block of lb ranks per
+    // agent slot, so Qt of a row lives in the block of its slot and is zero elsewhere.
+    const bool per_agent = !CAUSAL && p.l_block != 0;
+    const int lb16 = per_agent ? p.l_block >> 4 : 0;  // 16-rank blocks per slot
     if (HAS_BK && !qt_ready) {
+      // every lane of the hand-over area starts as zero (blocks beyond the rank, other slots' blocks)
+#pragma unroll
+      for (int i = 0; i < (RT * RKS + NW - 1) / NW; ++i) {
+        const int idx = hw + i * NW;
+        if (idx < RT * RKS) *reinterpret_cast<uint4*>(qt_lds + (idx * 64 + lane) * 16) = make_uint4(0u, 0u, 0u, 0u);
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): written before the barrier below lets the products follow
       // Item idx = hw + it*NW of row tile rt is (agent slot si, rho block cb); this lane holds row
       // rho = 16cb + ln of B_K^a, columns h*D + 32ks + 8lg ..: the A operand of Qt^T.  Rows beyond
       // the rank and the rows of empty slots lie outside the resource and arrive as zeros.
@@ -212,8 +222,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       // of a tile belong to 16/GP agents; each agent's product is kept only in its own rows
       // (lanes).  Left in LDS in operand-ready form: operand (rt, ks') of lane l is the 16 bytes
       // at ((rt*RKS + ks')*64 + l)*16, elements e -> rho = 32ks' + 16(e/4) + 4lg + e%4 (the L
-      // operand of the loop uses the same order).  Every lane of every k-step below the rank is
-      // written: every row belongs to some slot.
+      // operand of the loop uses the same order).
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -226,12 +235,9 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
             for (int ks = 0; ks < KS; ++ks)
               acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bt4[rt][it][ks]), qb[rt][ks], acc, 0, 0, 0);
             if ((ln >> gps) == si) {
-              unsigned char* dst = qt_lds + ((rt * RKS + (cb >> 1)) * 64 + lane) * 16;
-              const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
-              if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
-                *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
-              else
-                *reinterpret_cast<uint2*>(dst + (cb & 1) * 8) = pk;
+              const int kb = si * lb16 + cb;  // 16-rank block along the L tile's columns
+              unsigned char* dst = qt_lds + ((rt * RKS + (kb >> 1)) * 64 + lane) * 16;
+              *reinterpret_cast<uint2*>(dst + (kb & 1) * 8) = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
             }
           }
         }
@@ -285,6 +291,16 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   unsigned char* wave_lds = smem + wave * WAVE_BYTES;
   const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
   const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
+  const uint32_t lp2 = static_cast<uint32_t>(p.l_row_stride) * 2u;       // bytes between L rows
+  // The L tile in LDS is a row of column blocks, [block][32 keys][lb ranks]: one block of RP ranks
+  // with one low-rank cache for all agents, one block of l_block ranks per agent slot with
+  // per-adapter caches (BaseShared).  A block takes lb/16 requests of 1 KB.
+  const bool per_agent = !CAUSAL && p.l_block != 0;
+  const int lb = per_agent ? p.l_block : RP;   // ranks per block: 16, 32 or 64
+  const int lcpr = lb >> 3;                    // 16-byte chunks per row of a block: 2, 4 or 8
+  const int lb2 = lb * 2;                      // bytes per row of a block
+  // XOR swizzle of the chunk index inside a block row (none for 32-byte rows: 16 rows fill two clocks densely)
+  auto swz_l = [&](int row) { return lcpr == 8 ? (row & 7) : (lcpr == 4 ? ((row >> 1) & 3) : 0); };
 
   // ---- requests: per-lane offsets and buffer resources ----
   // LDS swizzles (XOR on the 16-byte chunk index of a row; the LDS serves 256 bytes per clock):
@@ -303,19 +319,38 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
 #pragma unroll
   for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
   {
-    const int lrow = lane / RCH, lpc = lane % RCH;
-    const int lch = lpc ^ ((lrow >> LSW_SHIFT) & (RCH - 1));
-    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * r2 + (lch << 4) : kOob;
+    const int lrow = lane / lcpr, lpc = lane % lcpr;  // row inside a request: the swizzle repeats from request to request
+    const int lch = lpc ^ swz_l(lrow);
+    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * lp2 + (lch << 4) : kOob;
   }
   // one resource per wave covering exactly its keys [jw0, jw1)
-  u32x4 rs_k, rs_v, rs_l;
+  u32x4 rs_k, rs_v, rs_l[LL];  // one L resource per request: the requests of a block read that block's adapter
+  uint32_t l_soff[LL];        // first row of the request inside its block, in bytes of the source
   {
     const int nk = jw1 - jw0;
     const int64_t base = static_cast<int64_t>(h) * p.kv_head_stride + static_cast<int64_t>(jw0) * p.kv_token_stride;
     const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
     rs_k = make_rsrc_words(static_cast<const bf16_t*>(p.k_base) + base, bytes);
     rs_v = make_rsrc_words(static_cast<const bf16_t*>(p.v_base) + base, bytes);
-    rs_l = make_rsrc_words(static_cast<const bf16_t*>(p.l) + static_cast<int64_t>(jw0) * r, static_cast<uint32_t>(nk) * r2);
+    const int rows_per_req = 512 / lb;  // 1 KB of rows of lb ranks
+    const int req_per_block = lb >> 4;
+    const uint32_t l_bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * lp2 + r2 : 0u;
+#pragma unroll
+    for (int i = 0; i < LL; ++i) {
+      const int blk = i / req_per_block, q = i - blk * req_per_block;
+      // block = agent slot of the row tile (per-adapter caches), or the one cache (of the call's adapter in
+      // the causal form); a block beyond the tile's slots reads nothing
+      int a = CAUSAL ? p.adapter_index : 0;
+      bool live = blk == 0;
+      if (per_agent) {
+        a = slot_adapter(0, blk);
+        live = blk < (16 >> gps) && a >= 0;
+      }
+      rs_l[i] = make_rsrc_words(static_cast<const bf16_t*>(p.l) + static_cast<int64_t>(live ? a : 0) * p.l_adapter_stride +
+                                    static_cast<int64_t>(jw0) * p.l_row_stride,
+                                live ? l_bytes : 0u);
+      l_soff[i] = static_cast<uint32_t>(q * rows_per_req) * lp2;
+    }
   }
   // K_base / V_base requests are non-temporal when this workgroup is the only reader of its
   // keys; with several row groups per kv head the others find the tiles in L2
@@ -335,7 +370,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       for (int i = 0; i < KVL; ++i) buf_load16_to_lds<false>(rs_k, ks + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
     }
 #pragma unroll
-    for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls + i * 1024, l_voff, (s0 + i * LROWS) * r2);
+    for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l[i], ls + i * 1024, l_voff, s0 * lp2 + l_soff[i]);
     if (stream_kv) {
 #pragma unroll
       for (int i = 0; i < KVL; ++i) buf_load16_to_lds<true>(rs_v, vs + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
@@ -360,20 +395,17 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   int l_rd[RKS][2];  // L rows as A operand of S^T: two 8-byte pieces per k-step
   int lt_rd[RB];     // L^T as A operand of Olr^T
   {
-    const int swz_s = (ln >> LSW_SHIFT) & (RCH - 1);
+    // column chunk ch of the tile (8 ranks) lies in block ch / lcpr, chunk ch % lcpr of a row there
+    auto chunk_addr = [&](int ch, int row) {
+      const int blk = ch / lcpr, cc = ch - blk * lcpr;
+      return blk * (32 * lb2) + row * lb2 + ((cc ^ swz_l(row)) << 4);
+    };
 #pragma unroll
     for (int ks = 0; ks < RKS; ++ks)
 #pragma unroll
-      for (int pcs = 0; pcs < 2; ++pcs) {
-        const int ch = 4 * ks + 2 * pcs + (lg >> 1);
-        l_rd[ks][pcs] = ln * (2 * RP) + ((ch ^ swz_s) << 4) + (lg & 1) * 8;
-      }
-    const int swz_t = (ka >> LSW_SHIFT) & (RCH - 1);
+      for (int pcs = 0; pcs < 2; ++pcs) l_rd[ks][pcs] = chunk_addr(4 * ks + 2 * pcs + (lg >> 1), ln) + (lg & 1) * 8;
 #pragma unroll
-    for (int b = 0; b < RB; ++b) {
-      const int ch = 2 * b + ((ln & 3) >> 1);
-      lt_rd[b] = ka * (2 * RP) + ((ch ^ swz_t) << 4) + (ln & 1) * 8;
-    }
+    for (int b = 0; b < RB; ++b) lt_rd[b] = chunk_addr(2 * b + ((ln & 3) >> 1), ka) + (ln & 1) * 8;
   }
   // last key each of this lane's rows may see (causal form only)
   int lim[RT];
@@ -406,7 +438,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
 #pragma unroll
     for (int ks = 0; ks < RKS; ++ks) {
       uint4 v = make_uint4(0u, 0u, 0u, 0u);  // k-steps entirely beyond the rank were never written
-      if (HAS_BK && ks * 32 < r) v = lds_read16(qt_lds + ((rt * RKS + ks) * 64 + lane) * 16);
+      if (HAS_BK && (per_agent || ks * 32 < r)) v = lds_read16(qt_lds + ((rt * RKS + ks) * 64 + lane) * 16);
       qtb[rt][ks] = as_bf16x8(v);
     }
   }
@@ -441,8 +473,8 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       if constexpr (HAS_BK) {
 #pragma unroll
         for (int ks = 0; ks < RKS; ++ks) {
-          const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 16 * (2 * RP));
-          const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 16 * (2 * RP));
+          const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 16 * lb2);
+          const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 16 * lb2);
           const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
 #pragma unroll
           for (int rt = 0; rt < RT; ++rt)
@@ -497,7 +529,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
       const unsigned char* src = ls_lds + lt_rd[b];
-      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 16 * (2 * RP)));
+      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 16 * lb2));
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         lr_acc[rt][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rt], lr_acc[rt][b], 0, 0, 0);
@@ -586,8 +618,16 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       if (x < DB) {
         *reinterpret_cast<f32x4*>(p.part_o + slot * D + x * 16 + lg * 4) = v;
       } else {
-        const int rho = (x - DB) * 16 + lg * 4;  // the rank is a multiple of 8: four entries are inside or outside together
-        if (rho < r) *reinterpret_cast<f32x4*>(p.part_lr + slot * r + rho) = v;
+        // the rank is a multiple of 8: four entries are inside or outside together.  With per-adapter
+        // caches a row keeps the block of its own agent slot only.
+        int rho = (x - DB) * 16 + lg * 4;
+        bool mine = true;
+        if (per_agent) {
+          const int blk = (x - DB) / (lb >> 4);
+          mine = blk == (ln >> gps);
+          rho -= blk * lb;
+        }
+        if (mine && rho < r) *reinterpret_cast<f32x4*>(p.part_lr + slot * r + rho) = v;
       }
     }
     if (wave == NW - 1 && lg == 0) {
@@ -692,7 +732,9 @@ hipError_t launch_decode_stream(const Params& p, int row_tiles, bool main_kernel
     else { if (p.rank > 32) launch_prepass2<64, 64>(p, row_tiles, s); else launch_prepass2<64, 32>(p, row_tiles, s); }
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   }
-  const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (p.rank > 32 ? 1 : 0);
+  // columns of the L tile: the rank, or with per-adapter low-rank caches one block per agent slot of a row tile
+  const int tile_rank = (p.l_block != 0 && !p.is_prefill) ? (16 / p.group_pad) * p.l_block : p.rank;
+  const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (tile_rank > 32 ? 1 : 0);
   switch (key) {
     case 0: return launch_stream2<64, 1, 32>(p, grid, s);
     case 1: return launch_stream2<64, 1, 64>(p, grid, s);

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
     float s = -INFINITY;
     if (valid) {
       const float sk = dot_row<T>(kb + kv_offset(p, t, j, h), q_s, d);
-      const float sl = dot_row<T>(lr + l_offset(p, t, j), qt_s, r);
+      const float sl = dot_row<T>(lr + l_offset(p, t, j, a), qt_s, r);
       s = p.scale * (sk + sl);
     }
     const float m_new = fmaxf(m, wave_max(s));  // finite: lane 0 is always valid here
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
       const T* v = vb + kv_offset(p, t, jb + jj, h);
       if (lane < d) o0 = fmaf(pjj, to_f32<T>(v[lane]), o0);
       if (lane + kWave < d) o1 = fmaf(pjj, to_f32<T>(v[lane + kWave]), o1);
-      if (lane < r) olr = fmaf(pjj, to_f32<T>(lr[l_offset(p, t, jb + jj) + lane]), olr);
+      if (lane < r) olr = fmaf(pjj, to_f32<T>(lr[l_offset(p, t, jb + jj, a) + lane]), olr);
     }
     m = m_new;
   }
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(kWave) void generic_partial_rope_kernel(Params p) {
     const bool valid = j < j1;
     // this lane's L row, as floats, where the lane can index it with a loop variable
     if (valid) {
-      const T* lrow = lr + l_offset(p, t, j);
+      const T* lrow = lr + l_offset(p, t, j, a);
       for (int rho = 0; rho < r; ++rho) l_s[lane * 65 + rho] = to_f32<T>(lrow[rho]);
     }
     __syncthreads();  // one wave: orders the staging against the other lanes' reads below

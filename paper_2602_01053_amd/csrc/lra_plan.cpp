@@ -76,6 +76,13 @@ lra_status check_common(const lra_shape* sh, const lra_cache* c) {
       return LRA_ERR_UNSUPPORTED;
     if (static_cast<int64_t>(c->max_blocks_per_seq) * 16 < c->max_seq_len) return LRA_ERR_SHAPE;
   }
+  if (c->l_row_stride < 0 || c->l_adapter_stride < 0 || (c->l_adapter_stride & 7)) return LRA_ERR_SHAPE;
+  if (c->l_row_stride != sh->rank && (c->l_row_stride & 7)) return LRA_ERR_SHAPE;  // (dense rows of any rank are fine)
+  if (c->l_row_stride != 0 && c->l_row_stride < sh->rank) return LRA_ERR_SHAPE;
+  if (c->l_row_stride > (int64_t{1} << 31) || c->l_adapter_stride > (int64_t{1} << 40)) return LRA_ERR_UNSUPPORTED;
+  if (c->block_size != 0 && c->num_blocks > 0 &&
+      (c->l_row_stride ? c->l_row_stride : sh->rank) > (int64_t{1} << 56) / c->num_blocks)
+    return LRA_ERR_UNSUPPORTED;
   const uintptr_t bits = reinterpret_cast<uintptr_t>(c->k_base) | reinterpret_cast<uintptr_t>(c->v_base) |
                          reinterpret_cast<uintptr_t>(c->l);
   if (bits & 15) return LRA_ERR_SHAPE;
@@ -92,12 +99,19 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   // tile in LDS for its one adapter; decode on the rotary form of the split-KV kernel.
   const bool rope = sh->key_rope_theta > 0.f;
   pl.mfma = sh->dtype == LRA_BF16 && tune.variant != 1 && sh->rank % 8 == 0;
+  // Low-rank rows with a stride of their own, or one low-rank cache per adapter (BaseShared): the
+  // tile-walking prefill kernel and the streaming form of the split-KV kernel read them; that form
+  // needs a contiguous cache and no rotary key side, everything else takes the vector-ALU kernels.
+  const int64_t l_pitch = c->l_row_stride ? c->l_row_stride : sh->rank;
+  const bool custom_l = c->l_adapter_stride > 0 || l_pitch != sh->rank;
+  const bool stream_only = custom_l;
+  const bool stream_ok = c->block_size == 0 && !(sh->key_rope_theta > 0.f) && tune.variant != 2;
   if (prefill && pl.mfma) {
     // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
     const int64_t lim = (int64_t{1} << 32) - 4096;
     const int64_t l_rows = c->block_size == 0 ? c->max_seq_len : static_cast<int64_t>(c->num_blocks) * 16;
-    if (l_rows * sh->rank * 2 > lim) pl.mfma = false;
+    if (l_rows * l_pitch * 2 > lim) pl.mfma = false;
     if (c->block_size == 0 && static_cast<int64_t>(c->max_seq_len) * c->kv_token_stride * 2 > lim) pl.mfma = false;
   }
   // A handful of new tokens after a long context gives the tile-walking prefill kernel one
@@ -105,7 +119,7 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   // tokens in the place of the agents and a causal limit per row, spreads the context over
   // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
   pl.short_prefill = prefill && pl.mfma && tokens <= tune.short_prefill &&
-                     static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
+                     static_cast<int64_t>(tokens) * 4 <= c->max_seq_len && (!stream_only || stream_ok);
   const bool rope_split = rope && pl.mfma && (!prefill || pl.short_prefill);  // rotary form of the split-KV kernel
   if (prefill && pl.mfma && !pl.short_prefill) {
     // Tile-walking kernel: one workgroup per (128-row q tile, q head).  When that is fewer than
@@ -137,8 +151,16 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     pl.launchable = true;  // at most 32 shares in y
     return pl;
   }
+  if (stream_only && !stream_ok) pl.mfma = false;
   pl.rows = tokens * sh->n_q_heads;
   pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
+  pl.l_block = 0;
+  if (pl.mfma && !prefill && c->l_adapter_stride > 0) {
+    // every agent slot of a row tile brings its own column block of the L tile: 64 columns per tile
+    pl.l_block = sh->rank <= 16 ? 16 : (sh->rank <= 32 ? 32 : 64);
+    const int min_pad = 16 / (64 / pl.l_block);
+    pl.group_pad = pl.group_pad > min_pad ? pl.group_pad : min_pad;
+  }
   pl.row_tiles = 1;
   pl.row_groups = 1;
   int tile = 64;       // keys per wave-step of the vector-ALU kernel
@@ -148,7 +170,7 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   if (pl.short_prefill) max_queries_per_seq = tokens;
   if (pl.mfma) {
     int rows_needed = max_queries_per_seq * pl.group_pad;
-    pl.row_tiles = decode_mfma_row_tiles(rows_needed);
+    pl.row_tiles = pl.l_block ? 1 : decode_mfma_row_tiles(rows_needed);  // (an L tile holds the column blocks of one row tile's agents)
     if (rope_split) {
       // one row tile per workgroup, and (decode) no more agent slots in it than the kernel keeps
       // B_K^T operands for
@@ -195,6 +217,23 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     else if (split_keys > cap) split_keys = static_cast<int>(cap);
   }
   if (!pl.mfma) pl.short_prefill = false;
+  if (pl.mfma && stream_only) {
+    // these calls exist only in the streaming form: at most one workgroup per compute unit, and a
+    // wave's L rows inside 32-bit byte offsets
+    const int64_t max_shares = kCUs / work;
+    const int64_t cap_l = ((int64_t{1} << 31) - 4096) / (l_pitch * 2) / tile * tile;
+    if (max_shares < 1 || cap_l < tile) {
+      pl.mfma = false;
+    } else {
+      const int64_t need = ((c->max_seq_len + max_shares - 1) / max_shares + tile - 1) / tile * tile;
+      if (split_keys < need) split_keys = static_cast<int>(need);
+      if (split_keys > cap_l) pl.mfma = false;
+    }
+    if (pl.mfma && c->block_size == 0 &&
+        split_keys > ((int64_t{1} << 31) - 4096) / (c->kv_token_stride * 2) / tile * tile)
+      pl.mfma = false;
+    if (!pl.mfma) pl.l_block = 0;
+  }
   pl.split_keys = split_keys;
   pl.n_splits = static_cast<int>((static_cast<int64_t>(c->max_seq_len) + split_keys - 1) / split_keys);
   // grids: (kv head, share, sequence x row group) for the MFMA kernels, (row, share) otherwise
@@ -210,7 +249,7 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   // otherwise reload many B_K rows per workgroup (reserved whether or not the call has a B_K)
   pl.off_qt = pl.bytes;
   pl.qt_bytes = 0;
-  if (pl.mfma && c->block_size == 0 && !rope_split && tune.variant != 2)
+  if (pl.mfma && c->block_size == 0 && !rope_split && tune.variant != 2 && pl.l_block == 0)
     pl.qt_bytes = decode_stream_qt_bytes(pl.group_pad, sh->rank, pl.row_tiles, pl.row_groups, sh->n_kv_heads);
   pl.bytes += align_up(pl.qt_bytes, 256);
   return pl;

@@ -33,6 +33,7 @@ struct Plan {
   int split_keys;  // keys per split
   int n_splits;    // splits per sequence at max_seq_len
   int group_pad, row_tiles, row_groups;  // MFMA decode row packing
+  int l_block;     // split-KV MFMA kernels with per-adapter low-rank caches: padded rank of one slot's column block, else 0
   bool launchable;  // false: a grid dimension would exceed the limit of 65535 in y or z (LRA_ERR_UNSUPPORTED)
   size_t off_ml, off_o, off_lr, off_adapter, off_qt, qt_bytes, bytes;
 };

@@ -133,7 +133,7 @@ struct PfTileLoader {
   const bf16_t *kb, *vb;
   pf_const_i32 bt;
   pf_u32x4 rs_k, rs_v, rs_l;
-  uint32_t ts2, r2, lds0, k_voff, v_voff, l_voff[L_DMA];
+  uint32_t ts2, r2, lp2, lds0, k_voff, v_voff, l_voff[L_DMA];  // lp2: bytes between L rows
   int wave, lane, hk, n_t, nb_last;
 
   __device__ __forceinline__ PfTileLoader(const Params& p_, unsigned char* smem, int wave_, int lane_, int hk_, int t,
@@ -141,11 +141,13 @@ struct PfTileLoader {
       : p(p_), wave(wave_), lane(lane_), hk(hk_), n_t(n_t_) {
     kb = static_cast<const bf16_t*>(p.k_base);
     vb = static_cast<const bf16_t*>(p.v_base);
-    const bf16_t* lr = static_cast<const bf16_t*>(p.l);
+    // the rows of the call's one adapter (BaseShared: its own low-rank cache), with their own stride
+    const bf16_t* lr = static_cast<const bf16_t*>(p.l) + static_cast<int64_t>(p.adapter_index) * p.l_adapter_stride;
     bt = PF_CONST_I32(p.block_table) + static_cast<int64_t>(t) * p.max_blocks_per_seq;
     const int r = p.rank;
     ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;
     r2 = static_cast<uint32_t>(r) * 2u;
+    lp2 = static_cast<uint32_t>(p.l_row_stride) * 2u;
     lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(PF_LDS_AS(unsigned char, smem)));
     nb_last = (n_t - 1) >> 4;
     const int rr = lane / KCH, pc = lane % KCH;
@@ -159,16 +161,16 @@ struct PfTileLoader {
       const uint32_t kv_bytes = static_cast<uint32_t>(n_t - 1) * ts2 + D * 2;
       rs_k = pf_rsrc(kb + static_cast<int64_t>(hk) * p.kv_head_stride, kv_bytes);
       rs_v = pf_rsrc(vb + static_cast<int64_t>(hk) * p.kv_head_stride, kv_bytes);
-      rs_l = pf_rsrc(lr, static_cast<uint32_t>(n_t) * r2);
+      rs_l = pf_rsrc(lr, static_cast<uint32_t>(n_t - 1) * lp2 + r2);
 #pragma unroll
       for (int q = 0; q < L_DMA; ++q) {
         const int lrow = (wave + 4 * q) * LROWS + lane / LCH;
         const int lch = (lane % LCH) ^ pf_swz_l<LCH>(lrow);
-        l_voff[q] = (lch * 8 < r) ? static_cast<uint32_t>(lane / LCH) * r2 + (lch << 4) : kPfOob;
+        l_voff[q] = (lch * 8 < r) ? static_cast<uint32_t>(lane / LCH) * lp2 + (lch << 4) : kPfOob;
       }
     } else {
       // paged L: one resource over the whole array; the lane's physical row is chosen per tile
-      rs_l = pf_rsrc(lr, static_cast<uint32_t>(p.num_blocks) * 16u * r2);
+      rs_l = pf_rsrc(lr, (static_cast<uint32_t>(p.num_blocks) * 16u - 1u) * lp2 + r2);
     }
   }
 
@@ -201,7 +203,7 @@ struct PfTileLoader {
       if (i < LCH) {
         const uint32_t dst = lds0 + stage_off + 2 * K_BYTES + i * 1024;
         if (!PAGED) {
-          pf_load16_to_lds(rs_l, dst, l_voff[q], static_cast<uint32_t>(j + i * LROWS) * r2);
+          pf_load16_to_lds(rs_l, dst, l_voff[q], static_cast<uint32_t>(j + i * LROWS) * lp2);
         } else {
           // LROWS rows span at most two blocks; their ids are wave-uniform (scalar loads)
           const int tok0 = j + i * LROWS;
@@ -212,7 +214,7 @@ struct PfTileLoader {
           const int blk = ((tok >> 4) == (tok0 >> 4)) ? blk_a : blk_b;
           const int lch = (lane % LCH) ^ pf_swz_l<LCH>(lrow);
           const uint32_t voff = (tok < n_t && lch * 8 < r)
-                                    ? (static_cast<uint32_t>(blk) * 16u + static_cast<uint32_t>(tok & 15)) * r2 + (lch << 4)
+                                    ? (static_cast<uint32_t>(blk) * 16u + static_cast<uint32_t>(tok & 15)) * lp2 + (lch << 4)
                                     : kPfOob;
           pf_load16_to_lds(rs_l, dst, voff, 0);
         }

@@ -61,6 +61,9 @@ int main(int argc, char** argv) {
     c.max_blocks_per_seq = paged ? static_cast<int32_t>(pv({(static_cast<int64_t>(c.max_seq_len > 0 ? c.max_seq_len : 1) + 15) / 16, INT32_MAX}, {1, 4})) : 0;
     c.num_blocks = paged ? static_cast<int32_t>(pv({1, 100, 1 << 20, INT32_MAX}, {0})) : 0;
     c.block_table = paged && rnd() % 16 ? reinterpret_cast<const int32_t*>(dummy) : nullptr;
+    const int64_t rk = sh.rank > 0 ? sh.rank : 8;
+    c.l_row_stride = pv({0, 0, (rk + 7) / 8 * 8, rk * 4 / 8 * 8 + 8, 4096, int64_t{1} << 31}, {rk - 1 > 0 ? (rk - 1) / 8 * 8 : 8, 12, -8, (int64_t{1} << 31) + 8});
+    c.l_adapter_stride = pv({0, 0, 0, 16, 64, int64_t{1} << 30, int64_t{1} << 40}, {-8, 4, (int64_t{1} << 40) + 8});
     lra_tuning t{};
     t.kernel_variant = static_cast<int32_t>(pick({0, 0, 1, 2, 7}));
     t.decode_split_keys = static_cast<int32_t>(pick({0, 0, 1, 64, 100, 1 << 20, INT32_MAX, -5}));
@@ -87,6 +90,11 @@ int main(int argc, char** argv) {
         CHECK(pl.off_o >= slots * 8 && pl.off_lr >= pl.off_o + slots * sh.head_dim * 4);
         CHECK(pl.off_adapter >= pl.off_lr + slots * sh.rank * 4 && pl.off_qt >= pl.off_adapter + static_cast<size_t>(pl.rows) * 4);
         CHECK(pl.bytes >= pl.off_qt + pl.qt_bytes);
+      }
+      if (pl.l_block) {  // per-adapter low-rank caches on the MFMA decode path: streaming form only
+        CHECK(!prefill && pl.mfma && c.block_size == 0 && c.l_adapter_stride > 0 && pl.row_tiles == 1);
+        CHECK(pl.l_block * (16 / pl.group_pad) <= 64 && pl.l_block >= sh.rank && pl.qt_bytes == 0);
+        CHECK(static_cast<int64_t>(sh.n_kv_heads) * pl.n_splits * pl.row_groups <= kCUs);
       }
       const bool split_path = !prefill || pl.short_prefill || !pl.mfma;
       if (split_path && pl.mfma) {

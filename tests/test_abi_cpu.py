@@ -41,7 +41,7 @@ FAKE = 0x1000  # never dereferenced: every case below fails validation first
 
 def _good():
     sh = LraShape(32, 8, 128, 16, 0, 0.0)
-    c = LraCache(FAKE, FAKE, FAKE, 1024, 128, 0, 0, 0, 0, 1, None, FAKE, 8192)
+    c = LraCache(FAKE, FAKE, FAKE, 1024, 128, 0, 0, 0, 0, 1, 0, 0, None, FAKE, 8192)
     ad = LraAdapters(FAKE, FAKE, 4)
     return sh, c, ad
 
@@ -115,6 +115,12 @@ def test_rejects_bad_arguments_before_launch(lib):
     assert _decode(lib, *mutated(block_size=16, n_seqs=2)) == NULL   # paged without a block table
     assert _decode(lib, *mutated(block_size=16, block_table=FAKE, num_blocks=600, kv_block_stride=16384,
                                  max_blocks_per_seq=8)) == SHAPE  # table row shorter than max_seq_len
+    assert _decode(lib, *mutated(l_row_stride=8)) == SHAPE          # rows shorter than the rank
+    assert _decode(lib, *mutated(l_row_stride=20)) == SHAPE         # not a multiple of 8 elements
+    assert _decode(lib, *mutated(l_adapter_stride=-16)) == SHAPE
+    assert _decode(lib, *mutated(l_adapter_stride=12)) == SHAPE
+    assert _decode(lib, *mutated(l_row_stride=1 << 32)) == UNSUP
+    assert _decode(lib, *mutated(l_row_stride=64, l_adapter_stride=16)) == WS     # valid per-adapter caches: only the workspace is missing
     assert _decode(lib, sh, c, ad, n_queries=0) == SHAPE
     assert _decode(lib, sh, c, ad, mq=5) == SHAPE
     # good arguments but no / small / misaligned workspace: refused, nothing launched

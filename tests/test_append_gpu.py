@@ -249,7 +249,8 @@ def test_append_writes_nothing_when_the_device_length_exceeds_the_bound(n_new):
     l = torch.full((rows, r), SENTINEL, dtype=torch.bfloat16, device=DEV)
     lens = torch.tensor([rows + 50], dtype=torch.int32, device=DEV)       # longer than the cache can hold
     shape = lra.make_shape(torch.empty(1, hkv, d, dtype=torch.bfloat16, device=DEV), hkv, r, 0.0)
-    lra.lra_cache_append(shape, lra.make_cache(k, v, l, lens, rows, None), w.to(DEV), 500000.0, x.to(DEV), 0)
+    wd, xd = w.to(DEV), x.to(DEV)   # referenced until the synchronisation: the call only enqueues
+    lra.lra_cache_append(shape, lra.make_cache(k, v, l, lens, rows, None), wd, 500000.0, xd, 0)
     torch.cuda.synchronize()
     for name, t in (("K", k), ("V", v), ("L", l)):
         assert bool((t == SENTINEL).all()), f"{name} rows were overwritten"
