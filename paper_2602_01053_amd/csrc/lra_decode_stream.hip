@@ -48,8 +48,9 @@ namespace lra {
 // LDS bytes of one workgroup of decode_stream_kernel<D, RT, RP>: the tile stages and nothing else.
 constexpr int decode_stream_lds_bytes(int D, int RP) { return 4 * 2 * (2 * 32 * D * 2 + 32 * RP * 2); }
 
-template <int D, int RT, int RP, bool HAS_BK, bool CAUSAL>
+template <int D, int RT, int RP, bool HAS_BK, bool CAUSAL, bool PA>
 __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
+  static_assert(!PA || (!CAUSAL && RT == 1), "per-adapter low-rank caches: decode form, one row tile");
   constexpr int NW = 4;            // streaming waves; waves NW .. 2 NW - 1 are the prologue waves
   constexpr int KS = D / 32;       // MFMA k-steps over the head dimension
   constexpr int RKS = RP / 32;     // MFMA k-steps over the (padded) rank
@@ -73,13 +74,18 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   constexpr int NBLK = DB + RB;                                // f32x4 blocks per lane and row tile
   constexpr int SLOT_BYTES = RT * (NBLK * 1024 + 512);         // merge slot of a wave: blocks, then (m, l) pairs
   static_assert(SLOT_BYTES <= WAVE_BYTES, "a wave's merge slot lives in its own tile region");
-  static_assert(Q_BYTES + QT_BYTES <= STAGE_BYTES, "Q and Qt are handed over in one tile stage");
+  // Q and Qt are handed from the prologue waves to the streaming waves through an area of their own
+  // where the LDS has room for it next to the tile stages; otherwise (head dimension 128 with 64
+  // ranks) through the second stage of the last streaming wave, which then gets its second tile
+  // only after everybody has picked them up.
+  constexpr bool HANDOVER_IN_STAGE = NW * WAVE_BYTES + Q_BYTES + QT_BYTES > 160 * 1024;
+  static_assert(Q_BYTES + QT_BYTES <= STAGE_BYTES, "Q and Qt fit one tile stage");
   static_assert(NW * WAVE_BYTES == decode_stream_lds_bytes(D, RP), "LDS accounting");
   static_assert(NW * WAVE_BYTES <= 160 * 1024, "LDS of one CU");
 
   __shared__ __align__(16) unsigned char smem[NW * WAVE_BYTES];
-  // hand-over area of Q and Qt: the second stage of the last streaming wave
-  unsigned char* q_lds = smem + (NW - 1) * WAVE_BYTES + STAGE_BYTES;
+  __shared__ __align__(16) unsigned char handover[HANDOVER_IN_STAGE ? 16 : Q_BYTES + QT_BYTES];
+  unsigned char* q_lds = HANDOVER_IN_STAGE ? smem + (NW - 1) * WAVE_BYTES + STAGE_BYTES : handover;
   unsigned char* qt_lds = q_lds + Q_BYTES;
 
   const int lane = threadIdx.x & 63;
@@ -88,6 +94,13 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   const bool helper = wave >= NW;
   LRA_STAMP_DECL;
   LRA_STAMP(0);
+  // Everything of the parameter block that stands before the first request is asked for at once:
+  // left to itself the compiler fetches it piece by piece, each piece a round trip of its own
+  // behind the branch that needs it.
+  asm volatile("" ::"s"(p.k_base), "s"(p.v_base), "s"(p.l), "s"(p.seq_lens), "s"(p.query_adapter));
+  asm volatile("" ::"s"(p.kv_token_stride), "s"(p.kv_head_stride), "s"(p.l_row_stride), "s"(p.l_adapter_stride));
+  asm volatile("" ::"s"(p.rank), "s"(p.group_pad), "s"(p.row_groups), "s"(p.max_seq_len), "s"(p.n_queries), "s"(p.n_adapters),
+               "s"(p.split_keys), "s"(p.l_block));
   // kv head is the fastest grid index: workgroups go round-robin over the XCDs, so with 8 kv
   // heads all workgroups of a head run on one XCD and share Q, B_K and L in its L2
   const int h = blockIdx.x, split = blockIdx.y, rg = blockIdx.z;
@@ -97,18 +110,26 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   const int GP = p.group_pad, G = p.group, r = p.rank;
   const int gps = __builtin_ctz(GP);                           // GP is 4, 8 or 16
   const int row0 = rg * RT * 16;
-  if (row0 >= (n_q << gps)) return;
-  // adapters of the agent slots of the row tiles (wave-uniform), -1 for an empty slot
+  // adapters of the agent slots of the row tiles (wave-uniform), -1 for an empty slot.  All ids are
+  // requested before any is looked at (unconditional loads from a clamped index: one round trip
+  // for the lot); being device data, they are then kept inside the table, as the merge kernel does.
   int a_slot[RT][4];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int si = 0; si < 4; ++si) {
       const int slot = ((row0 + rt * 16) >> gps) + si;
+      a_slot[rt][si] = CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[min(slot, n_q - 1)];
+    }
+  asm volatile("" ::"s"(len_t), "s"(a_slot[0][0]), "s"(a_slot[0][1]), "s"(a_slot[0][2]), "s"(a_slot[0][3]));  // one wait for all of them
+  if (row0 >= (n_q << gps)) return;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int si = 0; si < 4; ++si) {
+      const int slot = ((row0 + rt * 16) >> gps) + si;
       const bool live = si < (16 >> gps) && slot < n_q;
-      int a = -1;
-      if (live) a = min(max(CAUSAL ? p.adapter_index : CONST_I32(p.query_adapter)[slot], 0), p.n_adapters - 1);
-      a_slot[rt][si] = a;  // (ids are device data: kept inside the table, as the merge kernel does)
+      a_slot[rt][si] = live ? min(max(a_slot[rt][si], 0), p.n_adapters - 1) : -1;
     }
   auto slot_adapter = [&](int rt, int si) {
     return si == 0 ? a_slot[rt][0] : (si == 1 ? a_slot[rt][1] : (si == 2 ? a_slot[rt][2] : a_slot[rt][3]));
@@ -179,7 +200,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
     }
     // Per-adapter low-rank caches (BaseShared): the L tile holds one column block of lb ranks per
     // agent slot, so Qt of a row lives in the block of its slot and is zero elsewhere.
-    const bool per_agent = !CAUSAL && p.l_block != 0;
+    constexpr bool per_agent = PA;
     const int lb16 = per_agent ? p.l_block >> 4 : 0;  // 16-rank blocks per slot
     if (HAS_BK && !qt_ready) {
       // every lane of the hand-over area starts as zero (blocks beyond the rank, other slots' blocks)
@@ -196,7 +217,8 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       const int ncb = (r + 15) >> 4;   // rho blocks: 1 .. RP/16
       const int n_items = S * ncb;
       // idx -> (slot, rho block): idx / ncb without a division (idx < 16, ncb <= 4)
-      auto item_slot = [&](int idx) { return (idx * (256 / ncb + 1)) >> 8; };
+      const int inv_ncb = ncb == 1 ? 257 : (ncb == 2 ? 129 : (ncb == 3 ? 86 : 65));  // 256 / ncb + 1
+      auto item_slot = [&](int idx) { return (idx * inv_ncb) >> 8; };
       const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
       const bf16_t* bkg = static_cast<const bf16_t*>(p.b_k);
       uint4 bt4[RT][MAXIT][KS];
@@ -252,7 +274,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
     }
     LRA_STAMP(2);
     __syncthreads();  // Q and Qt are in LDS
-    __syncthreads();  // ... and have been picked up
+    if constexpr (HANDOVER_IN_STAGE) __syncthreads();  // ... and have been picked up
     // One workgroup per (kv head, row group) touches the B_V rows the merge kernel will need
     // (one 4-byte read per 128-byte line), so that they wait in this XCD's L2 instead of in
     // HBM: prologue wave w takes agent slot w of every row tile.
@@ -295,9 +317,10 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   // The L tile in LDS is a row of column blocks, [block][32 keys][lb ranks]: one block of RP ranks
   // with one low-rank cache for all agents, one block of l_block ranks per agent slot with
   // per-adapter caches (BaseShared).  A block takes lb/16 requests of 1 KB.
-  const bool per_agent = !CAUSAL && p.l_block != 0;
+  constexpr bool per_agent = PA;
   const int lb = per_agent ? p.l_block : RP;   // ranks per block: 16, 32 or 64
   const int lcpr = lb >> 3;                    // 16-byte chunks per row of a block: 2, 4 or 8
+  const int lcs = __builtin_ctz(lcpr);         // (all powers of two: shifts, no divisions)
   const int lb2 = lb * 2;                      // bytes per row of a block
   // XOR swizzle of the chunk index inside a block row (none for 32-byte rows: 16 rows fill two clocks densely)
   auto swz_l = [&](int row) { return lcpr == 8 ? (row & 7) : (lcpr == 4 ? ((row >> 1) & 3) : 0); };
@@ -319,7 +342,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
 #pragma unroll
   for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
   {
-    const int lrow = lane / lcpr, lpc = lane % lcpr;  // row inside a request: the swizzle repeats from request to request
+    const int lrow = lane >> lcs, lpc = lane & (lcpr - 1);  // row inside a request: the swizzle repeats from request to request
     const int lch = lpc ^ swz_l(lrow);
     l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * lp2 + (lch << 4) : kOob;
   }
@@ -332,12 +355,12 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
     const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
     rs_k = make_rsrc_words(static_cast<const bf16_t*>(p.k_base) + base, bytes);
     rs_v = make_rsrc_words(static_cast<const bf16_t*>(p.v_base) + base, bytes);
-    const int rows_per_req = 512 / lb;  // 1 KB of rows of lb ranks
-    const int req_per_block = lb >> 4;
+    const int rows_per_req = 64 >> lcs;  // 1 KB of rows of lb ranks
+    const int rpb_shift = lcs - 1;       // lb/16 requests per block
     const uint32_t l_bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * lp2 + r2 : 0u;
 #pragma unroll
     for (int i = 0; i < LL; ++i) {
-      const int blk = i / req_per_block, q = i - blk * req_per_block;
+      const int blk = i >> rpb_shift, q = i - (blk << rpb_shift);
       // block = agent slot of the row tile (per-adapter caches), or the one cache (of the call's adapter in
       // the causal form); a block beyond the tile's slots reads nothing
       int a = CAUSAL ? p.adapter_index : 0;
@@ -381,6 +404,8 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   };
   __builtin_amdgcn_s_barrier();  // the prologue waves' loads have left: theirs go first
   if (jw0 < jw1) issue_tile(jw0, 0);
+  if constexpr (!HANDOVER_IN_STAGE)
+    if (jw0 + 32 < jw1) issue_tile(jw0 + 32, 1);
   LRA_STAMP(2);
   __builtin_amdgcn_sched_barrier(0);
 
@@ -397,7 +422,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   {
     // column chunk ch of the tile (8 ranks) lies in block ch / lcpr, chunk ch % lcpr of a row there
     auto chunk_addr = [&](int ch, int row) {
-      const int blk = ch / lcpr, cc = ch - blk * lcpr;
+      const int blk = ch >> lcs, cc = ch & (lcpr - 1);
       return blk * (32 * lb2) + row * lb2 + ((cc ^ swz_l(row)) << 4);
     };
 #pragma unroll
@@ -442,10 +467,12 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       qtb[rt][ks] = as_bf16x8(v);
     }
   }
-  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the reads have returned
-  lds_fence();
-  __syncthreads();  // everybody has picked them up: the hand-over area is a tile stage again
-  if (jw0 + 32 < jw1) issue_tile(jw0 + 32, 1);
+  if constexpr (HANDOVER_IN_STAGE) {
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the reads have returned
+    lds_fence();
+    __syncthreads();  // everybody has picked them up: the hand-over area is a tile stage again
+    if (jw0 + 32 < jw1) issue_tile(jw0 + 32, 1);
+  }
   LRA_STAMP(3);
 
   // ===================== main loop =====================
@@ -623,7 +650,7 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
         int rho = (x - DB) * 16 + lg * 4;
         bool mine = true;
         if (per_agent) {
-          const int blk = (x - DB) / (lb >> 4);
+          const int blk = (x - DB) >> (lcs - 1);
           mine = blk == (ln >> gps);
           rho -= blk * lb;
         }
@@ -715,11 +742,19 @@ static hipError_t launch_stream2(const Params& p, dim3 grid, hipStream_t s) {
   const dim3 block(512);
   const bool has_bk = p.b_k != nullptr;
   if (p.is_prefill) {
-    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, true>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, true>), grid, block, 0, s, p);
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, true, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, true, false>), grid, block, 0, s, p);
+  } else if (p.l_block != 0) {
+    // per-adapter low-rank caches: one column block of the L tile per agent slot (one row tile only)
+    if constexpr (RT == 1) {
+      if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, 1, RP, true, false, true>), grid, block, 0, s, p);
+      else hipLaunchKernelGGL((decode_stream_kernel<D, 1, RP, false, false, true>), grid, block, 0, s, p);
+    } else {
+      return hipErrorInvalidValue;
+    }
   } else {
-    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, false>), grid, block, 0, s, p);
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, false, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, false, false>), grid, block, 0, s, p);
   }
   return hipGetLastError();
 }
