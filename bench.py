@@ -167,16 +167,31 @@ def stream_read_at_size(torch, lra, nbytes):
 
 
 def _load_traffic(name):
-    """HBM bytes per launch from committed rocprofv3 --pmc summaries, if any."""
+    """HBM bytes per launch of the named kernel from the committed rocprofv3 --pmc summary (None if there
+    is none), and whether that summary was taken on kernel sources other than the ones in this tree
+    (profiles/traffic.json records the fingerprint of the sources it was measured on)."""
+    from paper_2602_01053_amd.build import source_fingerprint
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(name)
+            rec = json.load(f)
     except (OSError, ValueError):
-        return None
+        return None, None
+    return rec.get(name), rec.get("source_fingerprint") != source_fingerprint()
 
 
-def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None, value_only=False):
+def _traffic_fields(roof, name, seconds):
+    """Adds the rocprofv3-measured HBM bytes per launch, the rate they give over the kernel time
+    measured in this run, and the staleness flag to a roofline object."""
+    traffic, stale = _load_traffic(name)
+    roof["traffic"] = traffic
+    if traffic is not None:
+        roof["traffic_GBps"] = round(traffic / seconds / 1e9, 1)
+        roof["traffic_measured_on_other_sources"] = bool(stale)
+    return roof
+
+
+def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None, value_only=False, kernel_only=False):
     """Times one decode configuration.  Caches smaller than COLD_BYTES are rotated over
     enough copies that every step streams from HBM.  value_only passes b_k = NULL (keys
     fully shared, LoRA on the value side only: the paper's main setting)."""
@@ -221,6 +236,9 @@ def bench_decode(args, torch, lra, workloads, index=2, steps=None, warmup=None, 
         run(warmup, cold)
         return graph_seconds(torch, lambda i, st: copies[i % n_copies if cold else 0].decode(st), n_steps)
 
+    if kernel_only:  # the roofline leg alone (for a profiler run that should see nothing else)
+        run(warmup, True)
+        return w, alg_bytes, None, None, {"cold": kernel_seconds(lra, torch, lambda i, st: copies[i % n_copies].decode(st), steps)}, n_copies
     loop_cold = timed_loop(steps, True)
     sec_cold, timed_steps = timed_graph(steps, True)
     sec_hot, _ = timed_graph(steps, False)
@@ -262,6 +280,12 @@ def value_only_decode(args, torch, lra, workloads):
 MIN_PREFILL_LAUNCHES = 50
 
 
+def decode_kernel_label(w):
+    """Name of the kernel that streams the keys of a contiguous decode workload without a rotary key
+    side that fits one workgroup per compute unit (what the headline configuration is)."""
+    return f"decode_stream_kernel<{w.head_dim}, 1, {32 if w.rank <= 32 else 64}>"
+
+
 def base_shared_decode(args, torch, lra, workloads):
     """The headline decode workload under BaseShared (Sec. 3.2): every agent has its OWN low-rank cache
     L_a [n][r] (stored [n][A][r]), so a call streams A*r instead of r low-rank elements per token.
@@ -300,7 +324,7 @@ def base_shared_decode(args, torch, lra, workloads):
             "kernel_frac_of_hbm_peak": round(alg / ksec / 1e9 / HBM_PEAK_GBS, 4)}
 
 
-def bench_prefill(args, torch, lra, workloads):
+def bench_prefill(args, torch, lra, workloads, kernel_only=False):
     """Config 3: at least MIN_PREFILL_LAUNCHES timed launches after at least 10 warm-up launches, whatever
     --steps says (a call is one kernel of 0.6 ms; a handful of launches would time the clock ramp)."""
     from paper_2602_01053_amd.runner import DeviceWorkload
@@ -313,11 +337,13 @@ def bench_prefill(args, torch, lra, workloads):
     for _ in range(max(10, min(args.warmup // 10, 20))):
         dw.prefill()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(launches):
-        dw.prefill()
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / launches
+    sec = None
+    if not kernel_only:
+        t0 = time.perf_counter()
+        for _ in range(launches):
+            dw.prefill()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / launches
     old = lra.lra_set_profile_mode(1)
     try:
         ksec, k_launches = graph_seconds(torch, lambda i, st: dw.prefill(st), 10, min_seconds=0.03)
@@ -518,6 +544,10 @@ def main():
     ap.add_argument("--no-other-decode", action="store_true")
     ap.add_argument("--no-append", action="store_true")
     ap.add_argument("--no-trace", action="store_true")
+    ap.add_argument("--profile-leg", choices=["decode_cfg2_kernel", "prefill_cfg3_kernel"],
+                    help="run only the named roofline leg (the dominant kernel alone, launched exactly as in the full "
+                         "run) and print its own JSON line: for a profiler run whose per-kernel average should be "
+                         "that leg's and nothing else's")
     ap.add_argument("--append-only", action="store_true",
                     help="only the lra_cache_append sweep over chunk sizes (its own JSON line)")
     args = ap.parse_args()
@@ -539,6 +569,22 @@ def main():
                                       sizes=(1, 2, 4, 8, 16, 32, 64, 128, 512, 1024, 2048, 8192, 16384))), flush=True)
         return
 
+    if args.profile_leg == "decode_cfg2_kernel":
+        w, alg_bytes, _, _, ksec, n_copies = bench_decode(args, torch, lra, workloads, kernel_only=True)
+        k_gbs = alg_bytes / ksec["cold"] / 1e9
+        print(json.dumps({"leg": args.profile_leg, "workload": w.name, "kernel": decode_kernel_label(w),
+                          "algorithmic_bytes": alg_bytes, "cache_copies": n_copies,
+                          "kernel_us": round(ksec["cold"] * 1e6, 3), "achieved_GBps": round(k_gbs, 1),
+                          "frac": round(k_gbs / HBM_PEAK_GBS, 4)}), flush=True)
+        return
+    if args.profile_leg == "prefill_cfg3_kernel":
+        wp, flops, _, pksec, _, pk_launches = bench_prefill(args, torch, lra, workloads, kernel_only=True)
+        print(json.dumps({"leg": args.profile_leg, "workload": wp.name, "kernel": "prefill_mfma_kernel<128, 16>",
+                          "algorithmic_flops": flops, "kernel_launches": pk_launches,
+                          "kernel_ms": round(pksec * 1e3, 4), "achieved_TFLOPs": round(flops / pksec / 1e12, 2),
+                          "frac": round(flops / pksec / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}), flush=True)
+        return
+
     w, alg_bytes, sec_cold, sec_hot, ksec, n_copies = bench_decode(args, torch, lra, workloads)
     gbs = alg_bytes / sec_cold / 1e9
     k_gbs = alg_bytes / ksec["cold"] / 1e9
@@ -557,9 +603,9 @@ def main():
                    "python_loop_GBps": round(alg_bytes / ksec["loop_cold"] / 1e9, 1),
                    "python_loop_note": "exactly K calls issued one by one from Python between two synchronisations: "
                                        "includes the interpreter and ctypes time per call"},
-        "roofline": {"bound": "hbm", "kernel": "decode_mfma_kernel", "achieved": round(k_gbs, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(k_gbs / HBM_PEAK_GBS, 4),
-                     "kernel_us": round(ksec["cold"] * 1e6, 3), "traffic": _load_traffic("decode_cfg2")},
+        "roofline": _traffic_fields({"bound": "hbm", "kernel": decode_kernel_label(w), "achieved": round(k_gbs, 1),
+                                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(k_gbs / HBM_PEAK_GBS, 4),
+                                     "kernel_us": round(ksec["cold"] * 1e6, 3)}, "decode_cfg2", ksec["cold"]),
         "hot_cache": {"value": round(alg_bytes / sec_hot / 1e9, 1), "unit": "GB/s",
                       "ms_per_step": round(sec_hot * 1e3, 6), "kernel_us": round(ksec["hot"] * 1e6, 3),
                       "note": "same buffers every step: served largely by the memory-side cache"},
@@ -572,9 +618,10 @@ def main():
             "workload": wp.name, "call": "lra_attn_prefill", "launches": psteps, "kernel_launches": pk_launches,
             "value": round(tf, 2), "unit": "TFLOP/s", "ms_per_step": round(psec * 1e3, 4),
             "algorithmic_flops": flops, "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-            "roofline": {"bound": "mfma", "achieved": round(ktf, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                         "unit": "TFLOP/s", "frac": round(ktf / MFMA_BF16_PEAK_TFLOPS, 4),
-                         "kernel_ms": round(pksec * 1e3, 4), "traffic": _load_traffic("prefill_cfg3")}}
+            "roofline": _traffic_fields({"bound": "mfma", "kernel": "prefill_mfma_kernel<128, 16>", "achieved": round(ktf, 2),
+                                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                         "frac": round(ktf / MFMA_BF16_PEAK_TFLOPS, 4),
+                                         "kernel_ms": round(pksec * 1e3, 4)}, "prefill_cfg3", pksec)}
     if not args.no_prefill:
         line["rotary_key_prefill"] = bench_rotary_prefill(args, torch, lra, workloads)
     if not args.no_other_decode:

@@ -21,6 +21,23 @@ HIPCC_FLAGS = [
 ]
 
 
+def source_fingerprint() -> str:
+    """Hash (16 hex digits) of everything the library is compiled from: the sources, the headers
+    beside them and the public headers.  Measurements kept next to the code (HBM traffic per launch
+    from hardware counters) record it, so that a reader can tell whether they were taken on these
+    kernels or on earlier ones."""
+    import hashlib
+    h = hashlib.sha256()
+    inc = os.path.join(ROOT, "include")
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".h", ".cpp"))]
+    files += [os.path.join(inc, f) for f in sorted(os.listdir(inc)) if f.endswith(".h")]
+    for path in files:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
