@@ -16,11 +16,17 @@
 //   - Waves 4-7 are the prologue: they load Q and the B_K rows of the workgroup's agents
 //     into registers with ordinary loads (their own request counters: nothing of theirs
 //     queues in front of a tile), form Qt = Q B_K^T by MFMA and leave Q and Qt in LDS in
-//     operand-ready order - in the second stage of the last streaming wave, which that wave
-//     fills only after everybody has picked them up, so the tile stages can take the whole
-//     LDS.  The streaming waves request their first tile, pick up Q and Qt (long before that
-//     tile lands), then request their second tile.  The prologue waves then touch the B_V
-//     rows the merge kernel will need and wait at the final barrier.
+//     operand-ready order - in a hand-over area of their own where the LDS has room for one
+//     next to the tile stages, else (head dimension 128 with 64 ranks) in the second stage of
+//     the last streaming wave, which that wave fills only after everybody has picked them up.
+//     Their loads are issued before the streaming waves' first requests (a bare barrier orders
+//     the two): the memory path of a compute unit serves requests in order, so a load issued
+//     behind 80 KB of tile requests comes back after them.  With many agent slots and large
+//     ranks Qt comes from a pre-pass kernel instead and is only copied.  The prologue waves
+//     then touch the B_V rows the merge kernel will need and wait at the final barrier.
+//   - With one low-rank cache per adapter (BaseShared) the L tile is a row of column blocks,
+//     one per agent slot of the row tile, each requested from that slot's cache; Qt of a row
+//     is zero outside the block of its slot, so the products are unchanged (template form PA).
 //   - All divisions by the row padding (a power of two) are shifts; the addresses of the
 //     LDS reads are formed after the requests have left.
 //   - The four streaming waves merge their states with one barrier (each deposits its
