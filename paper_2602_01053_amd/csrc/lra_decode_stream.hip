@@ -54,7 +54,7 @@ namespace lra {
 // LDS bytes of one workgroup of decode_stream_kernel<D, RT, RP>: the tile stages and nothing else.
 constexpr int decode_stream_lds_bytes(int D, int RP) { return 4 * 2 * (2 * 32 * D * 2 + 32 * RP * 2); }
 
-template <int D, int RT, int RP, bool HAS_BK, bool CAUSAL, bool PA>
+template <int D, int RT, int RP, bool HAS_BK, bool CAUSAL, bool PA, bool SI = false>
 __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   static_assert(!PA || (!CAUSAL && RT == 1), "per-adapter low-rank caches: decode form, one row tile");
   constexpr int NW = 4;            // streaming waves; waves NW .. 2 NW - 1 are the prologue waves
@@ -86,6 +86,13 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   // only after everybody has picked them up.
   constexpr bool HANDOVER_IN_STAGE = NW * WAVE_BYTES + Q_BYTES + QT_BYTES > 160 * 1024;
   static_assert(Q_BYTES + QT_BYTES <= STAGE_BYTES, "Q and Qt fit one tile stage");
+  // SI ("split issue", for key ranges of at most two tiles per wave): a streaming wave requests its
+  // first tile only; its second tile is requested, and waited for, by the prologue wave of the
+  // same number, which has nothing else left to do.  A wave issues in order, and the memory path
+  // accepts requests only as fast as data returns: a wave that requests both tiles itself sits in
+  // the issue of the second one for microseconds after its first tile has landed, and starts
+  // computing only then.
+  static_assert(!SI || !HANDOVER_IN_STAGE, "split issue needs the second stage from the start");
   static_assert(NW * WAVE_BYTES == decode_stream_lds_bytes(D, RP), "LDS accounting");
   static_assert(NW * WAVE_BYTES <= 160 * 1024, "LDS of one CU");
 
@@ -168,6 +175,107 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   }
   LRA_STAMP(1);
 
+  // ===================== tile requests (of streaming wave sw) =====================
+  const int j1 = min(j0 + p.split_keys, n_t);
+  const int kpw = p.split_keys / NW;  // multiple of 32
+  const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
+  const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
+  const uint32_t lp2 = static_cast<uint32_t>(p.l_row_stride) * 2u;       // bytes between L rows
+  // The L tile in LDS is a row of column blocks, [block][32 keys][lb ranks]: one block of RP ranks
+  // with one low-rank cache for all agents, one block of l_block ranks per agent slot with
+  // per-adapter caches (BaseShared).  A block takes lb/16 requests of 1 KB.
+  constexpr bool per_agent = PA;
+  const int lb = per_agent ? p.l_block : RP;   // ranks per block: 16, 32 or 64
+  const int lcpr = lb >> 3;                    // 16-byte chunks per row of a block: 2, 4 or 8
+  const int lcs = __builtin_ctz(lcpr);         // (all powers of two: shifts, no divisions)
+  const int lb2 = lb * 2;                      // bytes per row of a block
+  // XOR swizzle of the chunk index inside a block row (none for 32-byte rows: 16 rows fill two clocks densely)
+  auto swz_l = [&](int row) { return lcpr == 8 ? (row & 7) : (lcpr == 4 ? ((row >> 1) & 3) : 0); };
+  // LDS swizzles (XOR on the 16-byte chunk index of a row; the LDS serves 256 bytes per clock):
+  //   K (ds_read_b128, 16 rows per clock)           chunk ^ (row & 15)        | chunk ^ ((row >> 1) & 7)
+  //   V (ds_read_b64_tr_b16, 8 rows per clock)      chunk ^ ((row & 7) << 1)  | chunk ^ (((row >> 1) & 3) << 1)
+  // Lane l of request i lands at LDS row i*KROWS + l/KCH, physical chunk l%KCH, and therefore
+  // fetches the logical chunk (l%KCH) ^ swizzle(row); the swizzle repeats with period
+  // 16/KROWS (K) and 8/KROWS (V) in i.
+  auto swz_k = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
+  auto swz_v = [](int row) { return D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1); };
+  constexpr int KPER = KROWS == 4 ? 4 : 2, VPER = KROWS == 4 ? 2 : 1;
+  // K_base / V_base requests are non-temporal when this workgroup is the only reader of its
+  // keys; with several row groups per kv head the others find the tiles in L2
+  const bool stream_kv = p.row_groups == 1;
+  struct TileRequests {
+    int jw0, jw1;               // keys of the wave
+    unsigned char* wave_lds;    // its tile stages
+    uint32_t k_voff[KPER], v_voff[VPER], l_voff;
+    u32x4 rs_k, rs_v, rs_l[LL];  // one resource per wave covering exactly its keys; one L resource per request: the requests of a block read that block's adapter
+    uint32_t l_soff[LL];        // first row of the request inside its block, in bytes of the source
+  };
+  auto tile_requests = [&](int sw) __attribute__((always_inline)) {
+    TileRequests q;
+    q.jw0 = j0 + sw * kpw;
+    q.jw1 = max(q.jw0, min(q.jw0 + kpw, j1));  // == jw0 for a wave without keys
+    q.wave_lds = smem + sw * WAVE_BYTES;
+    const int rr = lane / KCH, pc = lane % KCH;
+#pragma unroll
+    for (int i = 0; i < KPER; ++i) q.k_voff[i] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_k(i * KROWS + rr)) << 4);
+#pragma unroll
+    for (int i = 0; i < VPER; ++i) q.v_voff[i] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(i * KROWS + rr)) << 4);
+    {
+      const int lrow = lane >> lcs, lpc = lane & (lcpr - 1);  // row inside a request: the swizzle repeats from request to request
+      const int lch = lpc ^ swz_l(lrow);
+      q.l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * lp2 + (lch << 4) : kOob;
+    }
+    const int nk = q.jw1 - q.jw0;
+    const int64_t base = static_cast<int64_t>(h) * p.kv_head_stride + static_cast<int64_t>(q.jw0) * p.kv_token_stride;
+    const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
+    q.rs_k = make_rsrc_words(static_cast<const bf16_t*>(p.k_base) + base, bytes);
+    q.rs_v = make_rsrc_words(static_cast<const bf16_t*>(p.v_base) + base, bytes);
+    const int rows_per_req = 64 >> lcs;  // 1 KB of rows of lb ranks
+    const int rpb_shift = lcs - 1;       // lb/16 requests per block
+    const uint32_t l_bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * lp2 + r2 : 0u;
+#pragma unroll
+    for (int i = 0; i < LL; ++i) {
+      const int blk = i >> rpb_shift, qq = i - (blk << rpb_shift);
+      // block = agent slot of the row tile (per-adapter caches), or the one cache (of the call's adapter in
+      // the causal form); a block beyond the tile's slots reads nothing
+      int a = CAUSAL ? p.adapter_index : 0;
+      bool live = blk == 0;
+      if (per_agent) {
+        a = slot_adapter(0, blk);
+        live = blk < (16 >> gps) && a >= 0;
+      }
+      q.rs_l[i] = make_rsrc_words(static_cast<const bf16_t*>(p.l) + static_cast<int64_t>(live ? a : 0) * p.l_adapter_stride +
+                                      static_cast<int64_t>(q.jw0) * p.l_row_stride,
+                                  live ? l_bytes : 0u);
+      q.l_soff[i] = static_cast<uint32_t>(qq * rows_per_req) * lp2;
+    }
+    return q;
+  };
+  // HBM -> LDS for the 32-key step starting at token j of the sequence, into stage st of the
+  // wave: K rows, then L rows, then V rows
+  auto issue_tile_of = [&](const TileRequests& q, int j, int st) __attribute__((always_inline)) {
+    unsigned char* ks = q.wave_lds + st * STAGE_BYTES;
+    unsigned char* vs = ks + KV_BYTES;
+    unsigned char* ls = vs + KV_BYTES;
+    const uint32_t s0 = static_cast<uint32_t>(j - q.jw0);
+    if (stream_kv) {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<true>(q.rs_k, ks + i * 1024, q.k_voff[i % KPER], (s0 + i * KROWS) * ts2);
+    } else {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<false>(q.rs_k, ks + i * 1024, q.k_voff[i % KPER], (s0 + i * KROWS) * ts2);
+    }
+#pragma unroll
+    for (int i = 0; i < LL; ++i) buf_load16_to_lds(q.rs_l[i], ls + i * 1024, q.l_voff, s0 * lp2 + q.l_soff[i]);
+    if (stream_kv) {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<true>(q.rs_v, vs + i * 1024, q.v_voff[i % VPER], (s0 + i * KROWS) * ts2);
+    } else {
+#pragma unroll
+      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<false>(q.rs_v, vs + i * 1024, q.v_voff[i % VPER], (s0 + i * KROWS) * ts2);
+    }
+  };
+
   if (helper) {
     // ===================== prologue waves: Q operands and Qt = Q B_K^T =====================
     const int hw = wave - NW;
@@ -206,7 +314,6 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
     }
     // Per-adapter low-rank caches (BaseShared): the L tile holds one column block of lb ranks per
     // agent slot, so Qt of a row lives in the block of its slot and is zero elsewhere.
-    constexpr bool per_agent = PA;
     const int lb16 = per_agent ? p.l_block >> 4 : 0;  // 16-rank blocks per slot
     if (HAS_BK && !qt_ready) {
       // every lane of the hand-over area starts as zero (blocks beyond the rank, other slots' blocks)
@@ -279,28 +386,49 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
           *reinterpret_cast<uint4*>(q_lds + ((rt * KS + ks) * 64 + lane) * 16) = __builtin_bit_cast(uint4, qb[rt][ks]);
     }
     LRA_STAMP(2);
-    __syncthreads();  // Q and Qt are in LDS
-    if constexpr (HANDOVER_IN_STAGE) __syncthreads();  // ... and have been picked up
     // One workgroup per (kv head, row group) touches the B_V rows the merge kernel will need
     // (one 4-byte read per 128-byte line), so that they wait in this XCD's L2 instead of in
     // HBM: prologue wave w takes agent slot w of every row tile.
     int warm[RT];
+    auto warm_b_v = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      warm[rt] = 0;
-      const int a = slot_adapter(rt, hw);
-      if (p.b_v != nullptr && split == min(1, p.n_splits - 1) && a >= 0) {
-        constexpr int LPR = D * 2 / 128;  // 128-byte lines per B_V row of one kv head
-        const int n_lines = r * LPR;      // <= 128
-        const char* bv = static_cast<const char*>(p.b_v) +
-                         (static_cast<int64_t>(a) * r * p.n_kv_heads * D + static_cast<int64_t>(h) * D) * 2;
+      for (int rt = 0; rt < RT; ++rt) {
+        warm[rt] = 0;
+        const int a = slot_adapter(rt, hw);
+        if (p.b_v != nullptr && split == min(1, p.n_splits - 1) && a >= 0) {
+          constexpr int LPR = D * 2 / 128;  // 128-byte lines per B_V row of one kv head
+          const int n_lines = r * LPR;      // <= 128
+          const char* bv = static_cast<const char*>(p.b_v) +
+                           (static_cast<int64_t>(a) * r * p.n_kv_heads * D + static_cast<int64_t>(h) * D) * 2;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int li = i * 64 + lane;
-          if (li < n_lines)
-            warm[rt] += *reinterpret_cast<const int*>(bv + static_cast<int64_t>(li / LPR) * p.n_kv_heads * D * 2 + (li % LPR) * 128);
+          for (int i = 0; i < 2; ++i) {
+            const int li = i * 64 + lane;
+            if (li < n_lines)
+              warm[rt] += *reinterpret_cast<const int*>(bv + static_cast<int64_t>(li / LPR) * p.n_kv_heads * D * 2 + (li % LPR) * 128);
+          }
         }
       }
+    };
+    if constexpr (SI) {
+      // the second tile of streaming wave hw: requested here, so that wave can start on its first.
+      // (Before the barrier that hands Q and Qt over: the streaming waves arrive there only when
+      // their own requests have been taken, and need Q and Qt only when their tile has landed.)
+      warm_b_v();
+      const TileRequests q = tile_requests(hw);
+      if (q.jw0 + 32 < q.jw1) issue_tile_of(q, q.jw0 + 32, 1);
+      __syncthreads();  // Q and Qt are in LDS
+      // Requests retire in order: with at most the KVL requests of the V rows outstanding (anything
+      // issued after them only makes this later), the K and L rows of the tile have landed.
+      wait_vm<KVL>();
+      lds_fence();
+      __syncthreads();  // the streaming waves may read K and L of their second tile
+      wait_vm0();
+      lds_fence();
+      __syncthreads();  // ... and its V rows
+    } else {
+      __syncthreads();  // Q and Qt are in LDS
+      if constexpr (HANDOVER_IN_STAGE) __syncthreads();  // ... and have been picked up
+      warm_b_v();
     }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) asm volatile("" ::"v"(warm[rt]));
@@ -311,106 +439,13 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   }
 
   // ===================== streaming waves =====================
-  const int j1 = min(j0 + p.split_keys, n_t);
-  const int kpw = p.split_keys / NW;  // multiple of 32
-  const int jw0 = j0 + wave * kpw;
-  const int jw1 = max(jw0, min(jw0 + kpw, j1));  // == jw0 for a wave without keys
-
-  unsigned char* wave_lds = smem + wave * WAVE_BYTES;
-  const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
-  const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
-  const uint32_t lp2 = static_cast<uint32_t>(p.l_row_stride) * 2u;       // bytes between L rows
-  // The L tile in LDS is a row of column blocks, [block][32 keys][lb ranks]: one block of RP ranks
-  // with one low-rank cache for all agents, one block of l_block ranks per agent slot with
-  // per-adapter caches (BaseShared).  A block takes lb/16 requests of 1 KB.
-  constexpr bool per_agent = PA;
-  const int lb = per_agent ? p.l_block : RP;   // ranks per block: 16, 32 or 64
-  const int lcpr = lb >> 3;                    // 16-byte chunks per row of a block: 2, 4 or 8
-  const int lcs = __builtin_ctz(lcpr);         // (all powers of two: shifts, no divisions)
-  const int lb2 = lb * 2;                      // bytes per row of a block
-  // XOR swizzle of the chunk index inside a block row (none for 32-byte rows: 16 rows fill two clocks densely)
-  auto swz_l = [&](int row) { return lcpr == 8 ? (row & 7) : (lcpr == 4 ? ((row >> 1) & 3) : 0); };
-
-  // ---- requests: per-lane offsets and buffer resources ----
-  // LDS swizzles (XOR on the 16-byte chunk index of a row; the LDS serves 256 bytes per clock):
-  //   K (ds_read_b128, 16 rows per clock)           chunk ^ (row & 15)        | chunk ^ ((row >> 1) & 7)
-  //   V (ds_read_b64_tr_b16, 8 rows per clock)      chunk ^ ((row & 7) << 1)  | chunk ^ (((row >> 1) & 3) << 1)
-  // Lane l of request i lands at LDS row i*KROWS + l/KCH, physical chunk l%KCH, and therefore
-  // fetches the logical chunk (l%KCH) ^ swizzle(row); the swizzle repeats with period
-  // 16/KROWS (K) and 8/KROWS (V) in i.
-  auto swz_k = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
-  auto swz_v = [](int row) { return D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1); };
-  constexpr int KPER = KROWS == 4 ? 4 : 2, VPER = KROWS == 4 ? 2 : 1;
-  const int rr = lane / KCH, pc = lane % KCH;
-  uint32_t k_voff[KPER], v_voff[VPER], l_voff;
-#pragma unroll
-  for (int q = 0; q < KPER; ++q) k_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_k(q * KROWS + rr)) << 4);
-#pragma unroll
-  for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
-  {
-    const int lrow = lane >> lcs, lpc = lane & (lcpr - 1);  // row inside a request: the swizzle repeats from request to request
-    const int lch = lpc ^ swz_l(lrow);
-    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * lp2 + (lch << 4) : kOob;
-  }
-  // one resource per wave covering exactly its keys [jw0, jw1)
-  u32x4 rs_k, rs_v, rs_l[LL];  // one L resource per request: the requests of a block read that block's adapter
-  uint32_t l_soff[LL];        // first row of the request inside its block, in bytes of the source
-  {
-    const int nk = jw1 - jw0;
-    const int64_t base = static_cast<int64_t>(h) * p.kv_head_stride + static_cast<int64_t>(jw0) * p.kv_token_stride;
-    const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
-    rs_k = make_rsrc_words(static_cast<const bf16_t*>(p.k_base) + base, bytes);
-    rs_v = make_rsrc_words(static_cast<const bf16_t*>(p.v_base) + base, bytes);
-    const int rows_per_req = 64 >> lcs;  // 1 KB of rows of lb ranks
-    const int rpb_shift = lcs - 1;       // lb/16 requests per block
-    const uint32_t l_bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * lp2 + r2 : 0u;
-#pragma unroll
-    for (int i = 0; i < LL; ++i) {
-      const int blk = i >> rpb_shift, q = i - (blk << rpb_shift);
-      // block = agent slot of the row tile (per-adapter caches), or the one cache (of the call's adapter in
-      // the causal form); a block beyond the tile's slots reads nothing
-      int a = CAUSAL ? p.adapter_index : 0;
-      bool live = blk == 0;
-      if (per_agent) {
-        a = slot_adapter(0, blk);
-        live = blk < (16 >> gps) && a >= 0;
-      }
-      rs_l[i] = make_rsrc_words(static_cast<const bf16_t*>(p.l) + static_cast<int64_t>(live ? a : 0) * p.l_adapter_stride +
-                                    static_cast<int64_t>(jw0) * p.l_row_stride,
-                                live ? l_bytes : 0u);
-      l_soff[i] = static_cast<uint32_t>(q * rows_per_req) * lp2;
-    }
-  }
-  // K_base / V_base requests are non-temporal when this workgroup is the only reader of its
-  // keys; with several row groups per kv head the others find the tiles in L2
-  const bool stream_kv = p.row_groups == 1;
-  // HBM -> LDS for the 32-key step starting at token j of the sequence, into stage st of this
-  // wave: K rows, then L rows, then V rows
-  auto issue_tile = [&](int j, int st) __attribute__((always_inline)) {
-    unsigned char* ks = wave_lds + st * STAGE_BYTES;
-    unsigned char* vs = ks + KV_BYTES;
-    unsigned char* ls = vs + KV_BYTES;
-    const uint32_t s0 = static_cast<uint32_t>(j - jw0);
-    if (stream_kv) {
-#pragma unroll
-      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<true>(rs_k, ks + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
-    } else {
-#pragma unroll
-      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<false>(rs_k, ks + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
-    }
-#pragma unroll
-    for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l[i], ls + i * 1024, l_voff, s0 * lp2 + l_soff[i]);
-    if (stream_kv) {
-#pragma unroll
-      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<true>(rs_v, vs + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
-    } else {
-#pragma unroll
-      for (int i = 0; i < KVL; ++i) buf_load16_to_lds<false>(rs_v, vs + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
-    }
-  };
+  const TileRequests treq = tile_requests(wave);
+  const int jw0 = treq.jw0, jw1 = treq.jw1;
+  unsigned char* wave_lds = treq.wave_lds;
+  auto issue_tile = [&](int j, int st) __attribute__((always_inline)) { issue_tile_of(treq, j, st); };
   __builtin_amdgcn_s_barrier();  // the prologue waves' loads have left: theirs go first
   if (jw0 < jw1) issue_tile(jw0, 0);
-  if constexpr (!HANDOVER_IN_STAGE)
+  if constexpr (!HANDOVER_IN_STAGE && !SI)
     if (jw0 + 32 < jw1) issue_tile(jw0 + 32, 1);
   LRA_STAMP(2);
   __builtin_amdgcn_sched_barrier(0);
@@ -484,12 +519,16 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   // ===================== main loop =====================
   // One 32-key step on the tile in stage st.  `younger` = the tile of the other stage has been
   // requested after this one (TL requests that may stay outstanding).
-  auto step = [&](int j, int st, bool younger) __attribute__((always_inline)) {
+  // `by_barrier` (split issue): the tile was requested by the prologue wave, which announces K and
+  // L, then V, with a workgroup barrier each.
+  auto step = [&](int j, int st, bool younger, bool by_barrier) __attribute__((always_inline)) {
     const unsigned char* ks_lds = wave_lds + st * STAGE_BYTES;
     const unsigned char* vs_lds = ks_lds + KV_BYTES;
     const unsigned char* ls_lds = vs_lds + KV_BYTES;
     // K and L rows of the tile have landed when only its V requests (and the younger tile's) are out
-    if (younger) wait_vm<TL + KVL>(); else wait_vm<KVL>();
+    if (by_barrier) __syncthreads();
+    else if (younger) wait_vm<TL + KVL>();
+    else wait_vm<KVL>();
     lds_fence();
     f32x4 s[2][RT];
 #pragma unroll
@@ -567,7 +606,9 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
       for (int rt = 0; rt < RT; ++rt)
         lr_acc[rt][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rt], lr_acc[rt][b], 0, 0, 0);
     }
-    if (younger) wait_vm<TL>(); else wait_vm0();
+    if (by_barrier) __syncthreads();
+    else if (younger) wait_vm<TL>();
+    else wait_vm0();
     lds_fence();
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
@@ -584,16 +625,26 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
 
   // Stage 0 holds tile j, stage 1 tile j + 32 (where the wave has that many keys); after a step
   // the tile two steps ahead, if there is one, is requested into the stage it frees.
-  if (jw0 < jw1) {
+  if constexpr (SI) {
+    // at most two tiles: the first requested by this wave, the second by its prologue wave
+    if (jw0 < jw1) step(jw0, 0, false, false);
+    LRA_STAMP(4);
+    if (jw0 + 32 < jw1) {
+      step(jw0 + 32, 1, false, true);
+    } else {
+      __syncthreads();  // the two barriers of the second tiles
+      __syncthreads();
+    }
+  } else if (jw0 < jw1) {
     int j = jw0;
     while (true) {
       const bool has1 = j + 32 < jw1;
-      step(j, 0, has1);
+      step(j, 0, has1, false);
       if (j == jw0) LRA_STAMP(4);
       const bool has2 = j + 64 < jw1;
       if (has2) issue_tile(j + 64, 0);
       if (!has1) break;
-      step(j + 32, 1, has2);
+      step(j + 32, 1, has2, false);
       if (j + 96 < jw1) issue_tile(j + 96, 1);
       if (!has2) break;
       j += 64;
@@ -743,26 +794,37 @@ bool decode_stream_applies(const Params& p, int row_tiles, int n_cus) {
   return wgs <= n_cus;
 }
 
-template <int D, int RT, int RP>
-static hipError_t launch_stream2(const Params& p, dim3 grid, hipStream_t s) {
+template <int D, int RT, int RP, bool SI>
+static hipError_t launch_stream3(const Params& p, dim3 grid, hipStream_t s) {
   const dim3 block(512);
   const bool has_bk = p.b_k != nullptr;
   if (p.is_prefill) {
-    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, true, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, true, false>), grid, block, 0, s, p);
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, true, false, SI>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, true, false, SI>), grid, block, 0, s, p);
   } else if (p.l_block != 0) {
     // per-adapter low-rank caches: one column block of the L tile per agent slot (one row tile only)
     if constexpr (RT == 1) {
-      if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, 1, RP, true, false, true>), grid, block, 0, s, p);
-      else hipLaunchKernelGGL((decode_stream_kernel<D, 1, RP, false, false, true>), grid, block, 0, s, p);
+      if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, 1, RP, true, false, true, SI>), grid, block, 0, s, p);
+      else hipLaunchKernelGGL((decode_stream_kernel<D, 1, RP, false, false, true, SI>), grid, block, 0, s, p);
     } else {
       return hipErrorInvalidValue;
     }
   } else {
-    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, false, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, false, false>), grid, block, 0, s, p);
+    if (has_bk) hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, true, false, false, SI>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_stream_kernel<D, RT, RP, false, false, false, SI>), grid, block, 0, s, p);
   }
   return hipGetLastError();
+}
+
+// Key ranges of at most two 32-key tiles per streaming wave take the split-issue form (where the
+// LDS has room for the hand-over area next to the tile stages).
+template <int D, int RT, int RP>
+static hipError_t launch_stream2(const Params& p, dim3 grid, hipStream_t s) {
+  constexpr bool can_split_issue = !(D == 128 && RP == 64);
+  if constexpr (can_split_issue) {
+    if (p.split_keys <= 256) return launch_stream3<D, RT, RP, true>(p, grid, s);
+  }
+  return launch_stream3<D, RT, RP, false>(p, grid, s);
 }
 
 // main_kernel_only (measurement): the streaming kernel alone, on whatever Qt an earlier call left
