@@ -52,7 +52,7 @@ class LraTuning(ctypes.Structure):
     """lra_tuning of the header: all zero = automatic everywhere."""
     _fields_ = [("kernel_variant", ctypes.c_int32), ("decode_split_keys", ctypes.c_int32),
                 ("short_prefill", ctypes.c_int32), ("prefill_splits", ctypes.c_int32),
-                ("append_skinny", ctypes.c_int32), ("append_stages", ctypes.c_int32),
+                ("rope_key_prepass", ctypes.c_int32), ("append_skinny", ctypes.c_int32), ("append_stages", ctypes.c_int32),
                 ("append_tile", ctypes.c_int32), ("measure_main_kernel_only", ctypes.c_int32)]
 
 
@@ -162,6 +162,13 @@ def lra_set_short_prefill(tokens: int) -> int:
 
 def lra_set_prefill_splits(splits: int) -> int:
     return _swap("prefill_splits", splits)
+
+
+def lra_set_rope_key_prepass(on: bool) -> bool:
+    """Rotary prefill on contiguous caches: completed keys by a pre-pass into the workspace (default on)."""
+    old = _tuning.rope_key_prepass >= 0
+    _tuning.rope_key_prepass = 0 if on else -1
+    return old
 
 
 def lra_set_profile_mode(mode: int) -> int:

@@ -186,8 +186,16 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
     return LRA_ERR_SHAPE;
   if (!plan_sizes_fit(shape, cache, n_new, 1)) return LRA_ERR_UNSUPPORTED;
   const Tuning tune = resolve_tuning(tuning);
-  const Plan pl = make_plan(shape, cache, n_new, 1, true, tune);
+  Plan pl = make_plan(shape, cache, n_new, 1, true, tune);
   if (!pl.launchable) return LRA_ERR_UNSUPPORTED;
+  // Rotary key side: the completed keys go to the workspace when the call has a key-side adapter and
+  // the workspace has room for them; otherwise the kernel completes every key tile itself.
+  bool keys_by_prepass = pl.kc_bytes > 0 && adapters->b_k != nullptr;
+  if (pl.kc_bytes > 0 && (!keys_by_prepass || check_workspace(pl, workspace, workspace_bytes) != LRA_OK)) {
+    keys_by_prepass = false;
+    pl.bytes = pl.bytes_without_kc;
+    pl.kc_bytes = 0;
+  }
   st = check_workspace(pl, workspace, workspace_bytes);
   if (st != LRA_OK) return st;
 
@@ -210,6 +218,15 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
     return LRA_OK;
   }
   if (pl.mfma) {
+    if (keys_by_prepass) {
+      // K = K_base + RoPE(L B_K) of the call's adapter, once, then the kernel without a key-side
+      // adapter on those keys (measurement of the main kernel alone: on the keys an earlier call left)
+      void* kc = static_cast<unsigned char*>(workspace) + pl.off_kc;
+      if (!tune.main_kernel_only && launch_complete_rope_keys(p, kc, s) != hipSuccess) return LRA_ERR_HIP;
+      p.k_base = kc;
+      p.b_k = nullptr;
+      p.key_rope_theta = 0.f;
+    }
     if (launch_prefill_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
     if (pl.n_splits > 1 && !tune.main_kernel_only && launch_merge(p, bf16, pl.rows, s) != hipSuccess)
       return LRA_ERR_HIP;

@@ -107,6 +107,8 @@ hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_
 bool decode_stream_applies(const Params& p, int row_tiles, int n_cus);
 hipError_t launch_decode_stream(const Params& p, int row_tiles, bool main_kernel_only, hipStream_t s);
 hipError_t launch_prefill_mfma(const Params& p, hipStream_t s);
+// rotary key side, contiguous cache: the completed keys of the call's adapter, in K_base's layout, into kc
+hipError_t launch_complete_rope_keys(const Params& p, void* kc, hipStream_t s);
 
 // Arguments of the cache-append producer kernel.
 struct AppendParams {

@@ -14,6 +14,7 @@ Tuning resolve_tuning(const lra_tuning* t) {
   r.split_keys = t->decode_split_keys > 0 ? t->decode_split_keys : 0;
   if (t->short_prefill != 0) r.short_prefill = t->short_prefill < 0 ? 0 : t->short_prefill;
   r.prefill_splits = t->prefill_splits > 0 ? t->prefill_splits : 0;
+  r.rope_key_prepass = t->rope_key_prepass >= 0;
   if (t->append_skinny != 0) r.append_skinny = t->append_skinny < 0 ? 0 : t->append_skinny;
   r.append_stages = (t->append_stages >= 2 && t->append_stages <= 4) ? t->append_stages : 0;
   r.append_tile = (t->append_tile == 64 || t->append_tile == 128 || t->append_tile == 256) ? t->append_tile : 0;
@@ -148,6 +149,18 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
       pl.bytes = pl.off_adapter + align_up(static_cast<size_t>(pl.rows) * sizeof(int32_t), 256);
     }
     pl.off_qt = pl.bytes;
+    pl.bytes_without_kc = pl.bytes;
+    if (rope && c->block_size == 0 && tune.rope_key_prepass) {
+      // room for the completed keys of the call's adapter, in the layout of K_base (whether or
+      // not the call has a B_K); caches beyond 4 GB keep completing tiles inside the kernel
+      const int64_t span = (static_cast<int64_t>(c->max_seq_len) - 1) * c->kv_token_stride +
+                           (static_cast<int64_t>(sh->n_kv_heads) - 1) * c->kv_head_stride + sh->head_dim;
+      if (span * 2 <= (int64_t{1} << 32)) {
+        pl.off_kc = pl.bytes;
+        pl.kc_bytes = align_up(static_cast<size_t>(span) * 2, 256);
+        pl.bytes += pl.kc_bytes;
+      }
+    }
     pl.launchable = true;  // at most 32 shares in y
     return pl;
   }
@@ -252,6 +265,7 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   if (pl.mfma && c->block_size == 0 && !rope_split && tune.variant != 2 && pl.l_block == 0)
     pl.qt_bytes = decode_stream_qt_bytes(pl.group_pad, sh->rank, pl.row_tiles, pl.row_groups, sh->n_kv_heads);
   pl.bytes += align_up(pl.qt_bytes, 256);
+  pl.bytes_without_kc = pl.bytes;
   return pl;
 }
 

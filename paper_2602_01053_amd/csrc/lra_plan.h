@@ -19,6 +19,7 @@ struct Tuning {
   int split_keys = 0;       // keys per workgroup in decode, 0 = automatic
   int short_prefill = 32;   // new tokens up to which a prefill takes the split-KV path (0 = never)
   int prefill_splits = 0;   // workgroups sharing the key tiles of a q tile, 0 = automatic
+  bool rope_key_prepass = true;  // rotary prefill on contiguous caches: completed keys by a pre-pass
   int append_skinny = 64;   // new tokens up to which lra_cache_append streams the weights (0 = never)
   int append_stages = 0;    // LDS stages of the tiled append GEMM, 0 = chosen from the grid
   int append_tile = 0;      // output tile of the append GEMM, 0 = chosen from the grid
@@ -36,6 +37,9 @@ struct Plan {
   int l_block;     // split-KV MFMA kernels with per-adapter low-rank caches: padded rank of one slot's column block, else 0
   bool launchable;  // false: a grid dimension would exceed the limit of 65535 in y or z (LRA_ERR_UNSUPPORTED)
   size_t off_ml, off_o, off_lr, off_adapter, off_qt, qt_bytes, bytes;
+  // rotary prefill with the completed keys in the workspace: their offset and size (0: none), and
+  // the size the plan has without them
+  size_t off_kc, kc_bytes, bytes_without_kc;
 };
 
 lra_status check_common(const lra_shape* sh, const lra_cache* c);

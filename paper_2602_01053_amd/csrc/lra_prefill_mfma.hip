@@ -570,4 +570,86 @@ hipError_t launch_prefill_mfma(const Params& p, hipStream_t s) {
   return launch_pf<64, 64>(p, grid, s);
 }
 
+// ---------------------------------------------------------------------------------------
+// Rotary key side, contiguous caches: the keys of the call's one adapter, formed once.
+//   K_j = K_base,j + RoPE_j(L_j B_K^a)             (App. D.1: with LoRA on the key projection the
+//                                                   adapter's part is rebuilt in the head dimension
+//                                                   before the rotation)
+// The tile-walking kernel can complete every key tile in LDS itself, but a call of many q tiles
+// then repeats that work in every workgroup that walks the tile (q tiles x q heads of the kv head:
+// 64 times at 2048 new tokens and a group of 4).  This pre-pass writes the completed keys of all
+// visible tokens into the workspace, in the layout of K_base (same strides), and the call then
+// runs the plain kernel without a key-side adapter on them.  HBM bound: K_base read and written
+// once (+ L); rank x d multiply-adds per key and head on the vector ALU.
+// One workgroup per (16 keys, kv head); lane (key, group g of 16): the pairs (dd, dd + d/2),
+// dd = PPL g .. PPL g + PPL - 1, PPL = d/32.  E in fp32, angle = fractional part of position x rate
+// in double precision, as in the producer of the caches.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void complete_rope_keys_kernel(Params p, unsigned short* kc) {
+  constexpr int PPL = D / 32;              // rotary pairs per lane
+  __shared__ __align__(16) unsigned short b_lds[64 * D];  // B_K^a rows of this kv head, [rho][d]
+  __shared__ double rate[D / 2];
+  const int tid = threadIdx.x;
+  const int h = blockIdx.y;
+  const int r = p.rank;
+  const int n_t = min(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int j = blockIdx.x * 16 + (tid >> 4);
+  if (blockIdx.x * 16 >= n_t) return;
+  const int a = min(max(p.adapter_index, 0), p.n_adapters - 1);
+  const unsigned short* bk = static_cast<const unsigned short*>(p.b_k) +
+                             (static_cast<int64_t>(a) * r * p.n_kv_heads + h) * D;
+  for (int i = tid; i < r * (D / 8); i += 256) {
+    const int rho = i / (D / 8), c = i - rho * (D / 8);
+    *reinterpret_cast<uint4*>(b_lds + rho * D + c * 8) =
+        *reinterpret_cast<const uint4*>(bk + static_cast<int64_t>(rho) * p.n_kv_heads * D + c * 8);
+  }
+  if (tid < D / 2) rate[tid] = rope_rate_rev(tid, D, p.key_rope_theta);
+  __syncthreads();
+  if (j >= n_t) return;
+  const int g = tid & 15;
+  const unsigned short* lrow = static_cast<const unsigned short*>(p.l) + static_cast<int64_t>(a) * p.l_adapter_stride +
+                               static_cast<int64_t>(j) * p.l_row_stride;
+  float lo[PPL], hi[PPL];
+#pragma unroll
+  for (int i = 0; i < PPL; ++i) lo[i] = hi[i] = 0.f;
+  for (int r0 = 0; r0 < r; r0 += 8) {  // the rank is a multiple of 8
+    const uint4 lv = *reinterpret_cast<const uint4*>(lrow + r0);
+    const uint32_t lw[4] = {lv.x, lv.y, lv.z, lv.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float lf = __uint_as_float((e & 1) ? (lw[e >> 1] & 0xffff0000u) : (lw[e >> 1] << 16));
+      const unsigned short* brow = b_lds + (r0 + e) * D + PPL * g;
+#pragma unroll
+      for (int i = 0; i < PPL; ++i) {
+        lo[i] = fmaf(lf, __uint_as_float(static_cast<uint32_t>(brow[i]) << 16), lo[i]);
+        hi[i] = fmaf(lf, __uint_as_float(static_cast<uint32_t>(brow[D / 2 + i]) << 16), hi[i]);
+      }
+    }
+  }
+  const int64_t off = static_cast<int64_t>(j) * p.kv_token_stride + static_cast<int64_t>(h) * p.kv_head_stride + PPL * g;
+  // the lane's PPL consecutive features of either half: one 8-byte (d = 128) or 4-byte (d = 64) piece
+  struct alignas(PPL * 2) Piece { unsigned short v[PPL]; };
+  const unsigned short* ksrc = static_cast<const unsigned short*>(p.k_base) + off;
+  unsigned short* kdst = kc + off;
+  const Piece klo = *reinterpret_cast<const Piece*>(ksrc), khi = *reinterpret_cast<const Piece*>(ksrc + D / 2);
+  Piece olo, ohi;
+#pragma unroll
+  for (int i = 0; i < PPL; ++i) {
+    float sn, cs;
+    rope_sincos(rate[PPL * g + i], j, sn, cs);
+    olo.v[i] = f32_to_bf16(__uint_as_float(static_cast<uint32_t>(klo.v[i]) << 16) + (lo[i] * cs - hi[i] * sn));
+    ohi.v[i] = f32_to_bf16(__uint_as_float(static_cast<uint32_t>(khi.v[i]) << 16) + (hi[i] * cs + lo[i] * sn));
+  }
+  *reinterpret_cast<Piece*>(kdst) = olo;
+  *reinterpret_cast<Piece*>(kdst + D / 2) = ohi;
+}
+
+hipError_t launch_complete_rope_keys(const Params& p, void* kc, hipStream_t s) {
+  const dim3 grid((p.max_seq_len + 15) / 16, p.n_kv_heads);
+  if (p.head_dim == 128) hipLaunchKernelGGL((complete_rope_keys_kernel<128>), grid, dim3(256), 0, s, p, static_cast<unsigned short*>(kc));
+  else hipLaunchKernelGGL((complete_rope_keys_kernel<64>), grid, dim3(256), 0, s, p, static_cast<unsigned short*>(kc));
+  return hipGetLastError();
+}
+
 }  // namespace lra

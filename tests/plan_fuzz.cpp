@@ -69,6 +69,7 @@ int main(int argc, char** argv) {
     t.decode_split_keys = static_cast<int32_t>(pick({0, 0, 1, 64, 100, 1 << 20, INT32_MAX, -5}));
     t.short_prefill = static_cast<int32_t>(pick({0, -1, 1, 64, INT32_MAX}));
     t.prefill_splits = static_cast<int32_t>(pick({0, 1, 5, 32, 1000, -1}));
+    t.rope_key_prepass = static_cast<int32_t>(pick({0, 0, -1, 1}));
     const Tuning tune = resolve_tuning(rnd() % 4 ? &t : nullptr);
     if (check_common(&sh, &c) != LRA_OK) continue;
     ++accepted;
@@ -85,11 +86,19 @@ int main(int argc, char** argv) {
       CHECK(static_cast<int64_t>(pl.n_splits) * pl.split_keys >= c.max_seq_len || (prefill && pl.mfma && !pl.short_prefill));
       CHECK(pl.off_ml % 256 == 0 && pl.off_o % 256 == 0 && pl.off_lr % 256 == 0 && pl.off_adapter % 256 == 0 && pl.off_qt % 256 == 0);
       CHECK(pl.bytes % 256 == 0);
-      if (pl.bytes) {
+      CHECK(pl.bytes == pl.bytes_without_kc + pl.kc_bytes && pl.off_kc % 256 == 0 && pl.kc_bytes % 256 == 0);
+      if (pl.kc_bytes) {  // completed keys of a rotary prefill: a copy of the K_base extent behind everything else
+        CHECK(prefill && pl.mfma && !pl.short_prefill && c.block_size == 0 && sh.key_rope_theta > 0.f);
+        CHECK(pl.off_kc >= pl.bytes_without_kc);
+        const int64_t span = (static_cast<int64_t>(c.max_seq_len) - 1) * c.kv_token_stride +
+                             (static_cast<int64_t>(sh.n_kv_heads) - 1) * c.kv_head_stride + sh.head_dim;
+        CHECK(pl.kc_bytes >= static_cast<size_t>(span) * 2 && pl.kc_bytes <= (size_t{1} << 32) + 256);
+      }
+      if (pl.bytes_without_kc) {
         const size_t slots = static_cast<size_t>(pl.rows) * pl.n_splits;
         CHECK(pl.off_o >= slots * 8 && pl.off_lr >= pl.off_o + slots * sh.head_dim * 4);
         CHECK(pl.off_adapter >= pl.off_lr + slots * sh.rank * 4 && pl.off_qt >= pl.off_adapter + static_cast<size_t>(pl.rows) * 4);
-        CHECK(pl.bytes >= pl.off_qt + pl.qt_bytes);
+        CHECK(pl.bytes_without_kc >= pl.off_qt + pl.qt_bytes);
       }
       if (pl.l_block) {  // per-adapter low-rank caches on the MFMA decode path: streaming form only
         CHECK(!prefill && pl.mfma && c.block_size == 0 && c.l_adapter_stride > 0 && pl.row_tiles == 1);

@@ -237,7 +237,7 @@ def test_header_is_plain_c(tmp_path):
     src.write_text(
         '#include "lra_attn.h"\n#include "lra_attn_measure.h"\n'
         "lra_status call(const lra_shape* s, const lra_cache* c, const lra_projection* p, const void* x) {\n"
-        "  lra_tuning t = {0, 0, 0, 0, 0, 0, 0, 0};\n"
+        "  lra_tuning t = {0, 0, 0, 0, 0, 0, 0, 0, 0};\n"
         "  return lra_cache_append(s, c, p, x, 0, 1, &t, (void*)0);\n"
         "}\n"
         "size_t need(const lra_shape* s, const lra_cache* c) { return lra_workspace_bytes(s, c, 4, 4, 0, (const lra_tuning*)0); }\n")

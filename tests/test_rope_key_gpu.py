@@ -101,12 +101,53 @@ def test_rotary_decode_at_the_named_configurations(cfg):
 
 def test_rotary_prefill_at_configuration_3_every_row():
     """The full-size causal prefill with the rotary key side, in the launch configuration the benchmark's rotary
-    leg times, compared with the oracle on every output row."""
+    leg times (keys completed by the pre-pass) and with the key tiles completed inside the kernel, compared
+    with the oracle on every output row."""
     w = W.config(3)
-    got = _run(w, 500000.0)
     ref = oracle_prefill_by_blocks(w, key_rope_theta=500000.0)
-    rel, mx = errors(got, ref)
-    print(f"{w.name} rotary: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    for prepass in (True, False):
+        prev = lra.lra_set_rope_key_prepass(prepass)
+        try:
+            got = _run(w, 500000.0)
+        finally:
+            lra.lra_set_rope_key_prepass(prev)
+        rel, mx = errors(got, ref)
+        print(f"{w.name} rotary, {'key pre-pass' if prepass else 'tiles completed in the kernel'}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+        assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
+def test_rotary_prefill_key_prepass_layouts_and_small_workspace():
+    """The pre-pass writes the completed keys in the layout of K_base: token-major and head-major caches give
+    the same output; a call whose workspace has no room for them (here: none at all) completes the tiles in the
+    kernel and still matches the oracle."""
+    w = W.make_contiguous("rp_hm", "prefill", seed=321, n_agents=1, n_q_heads=8, n_kv_heads=4, head_dim=128, rank=16,
+                          n=1300, n_new=513, d_model=None, b_std=0.1)
+    ref = _oracle(w, 500000.0)
+    outs = []
+    for head_major in (False, True):
+        dw = DeviceWorkload(w, DEV, head_major, key_rope_theta=500000.0)
+        need = dw.alloc_workspace()
+        assert need >= w.k_base.numel() * 2          # room for a copy of the keys
+        dw.out.fill_(float("nan"))
+        dw.prefill()
+        torch.cuda.synchronize()
+        outs.append(dw.out.to(torch.float64).cpu().numpy())
+        rel, mx = errors(outs[-1], ref)
+        print(f"head_major={head_major}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+        assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+    assert np.array_equal(outs[0], outs[1])
+    dw = DeviceWorkload(w, DEV, key_rope_theta=500000.0)
+    prev = lra.lra_set_rope_key_prepass(False)
+    try:
+        small = dw.alloc_workspace()                  # what the call needs without the completed keys
+    finally:
+        lra.lra_set_rope_key_prepass(prev)
+    assert small < need - w.k_base.numel() * 2 + 4096
+    dw.out.fill_(float("nan"))
+    dw.prefill()                                      # pre-pass allowed, but no room for its keys
+    torch.cuda.synchronize()
+    rel, mx = errors(dw.out.to(torch.float64).cpu().numpy(), ref)
+    print(f"workspace without room for the keys: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
     assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
 
 
@@ -189,20 +230,24 @@ def _prefill_cases():
 
 def _prefill_params():
     """Every case on both kernel families, except the 70-token case at 41000 positions on the vector-ALU
-    kernels (280 rows walking 41000 keys each): its few-row sibling covers those positions there."""
-    for variant, vid in ((0, "mfma"), (1, "vector_alu")):
+    kernels (280 rows walking 41000 keys each): its few-row sibling covers those positions there.  On the MFMA
+    kernels every case runs twice: with the completed keys written to the workspace by the pre-pass (what a
+    contiguous cache gets by default) and with every key tile completed inside the kernel."""
+    for variant, vid, prepass in ((0, "mfma_key_prepass", True), (0, "mfma_in_kernel", False), (1, "vector_alu", True)):
         for name, w, theta in _prefill_cases():
             if variant == 1 and name == "positions_beyond_40000":
                 continue
-            yield pytest.param(name, w, theta, variant, id=f"{name}-{vid}")
+            yield pytest.param(name, w, theta, variant, prepass, id=f"{name}-{vid}")
 
 
-@pytest.mark.parametrize("name,w,theta,variant", list(_prefill_params()))
-def test_rotary_key_side_prefill(name, w, theta, variant):
-    """The MFMA prefill kernel completes every key tile in LDS (E = L B_K rotated and added to the K_base rows)
-    before the scores; a handful of new tokens after a long context takes the causal rotary form of the
-    split-KV kernel; the vector-ALU kernels serve the same calls when asked to (kernel variant 1)."""
+@pytest.mark.parametrize("name,w,theta,variant,prepass", list(_prefill_params()))
+def test_rotary_key_side_prefill(name, w, theta, variant, prepass):
+    """The MFMA prefill kernel runs on keys completed once by a pre-pass (contiguous caches) or completes every
+    key tile in LDS itself (E = L B_K rotated and added to the K_base rows) before the scores; a handful of new
+    tokens after a long context takes the causal rotary form of the split-KV kernel; the vector-ALU kernels
+    serve the same calls when asked to (kernel variant 1)."""
     prev = lra.lra_set_kernel_variant(variant)
+    prev_pp = lra.lra_set_rope_key_prepass(prepass)
     try:
         if w is None:
             _paged_prefill(theta, 9 if name == "paged_short" else 130)
@@ -210,6 +255,7 @@ def test_rotary_key_side_prefill(name, w, theta, variant):
         got = _run(w, theta)
     finally:
         lra.lra_set_kernel_variant(prev)
+        lra.lra_set_rope_key_prepass(prev_pp)
     ref = _oracle(w, theta)
     rel, mx = errors(got, ref)
     moved = np.linalg.norm(ref - _oracle(w, 0.0)) / np.linalg.norm(ref)
