@@ -447,15 +447,22 @@ def bench_append(args, torch, lra, with_cpu, sizes=(16384, 2048, 1)):
         # is shorter than the Python call overhead, which would otherwise be what is timed
         streaming = n_new <= 64
         per_graph, replays = (120, 5) if streaming else (10, 5)
-        sec_same = timed_graph(lambda i, st: lra.lra_cache_append(shape, cache, w, theta, x, 0, st), per_graph, replays)
+        # with the workspace the library asks for, mid-sized chunks divide d_model over the chip
+        ws_bytes = lra.lra_append_workspace_bytes(shape, cache, w, theta, n_new)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+        sec_same = timed_graph(lambda i, st: lra.lra_cache_append(shape, cache, w, theta, x, 0, st, workspace=ws), per_graph, replays)
         sec = sec_same
         if streaming:
-            sec = timed_graph(lambda i, st: lra.lra_cache_append(shape, cache, w_copies[i % len(w_copies)], theta, x, 0, st),
+            sec = timed_graph(lambda i, st: lra.lra_cache_append(shape, cache, w_copies[i % len(w_copies)], theta, x, 0, st, workspace=ws),
                               per_graph, replays)
+        sec_no_ws = timed_graph(lambda i, st: lra.lra_cache_append(shape, cache, w, theta, x, 0, st), per_graph, replays) if ws_bytes else None
         flops = 2.0 * n_new * dm * (2 * hkv * d + r)
         nbytes = 2.0 * ((2 * hkv * d + r) * dm + n_new * dm + n_new * (2 * hkv * d + r))
         row = {"n_new": n_new, "us_per_call": round(sec * 1e6, 2), "algorithmic_flops": flops,
                "algorithmic_bytes": nbytes}
+        if ws_bytes:
+            row["workspace_bytes"] = ws_bytes
+            row["us_per_call_without_workspace"] = round(sec_no_ws * 1e6, 2)
         if n_new > 64:
             tf = flops / sec / 1e12
             row["roofline"] = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,

@@ -67,6 +67,7 @@ def run_trace(torch, lra, l_ctx, replays, key_rope_theta=0.0):
     qstart = torch.tensor([0, 1], dtype=torch.int32, device=dev)
     shape = lra.make_shape(q, HKV, R, 0.0, key_rope_theta)
     ws_bytes = 256
+    aws_bytes = 256   # lra_cache_append's own workspace (mid-sized chunks divide d_model over the chip)
     prepared = []
     for i, (kind, n_after, n_new, a) in enumerate(calls):
         cache = lra.make_cache(k_base, v_base, l, lens[i:i + 1], n_after, None)
@@ -74,13 +75,15 @@ def run_trace(torch, lra, l_ctx, replays, key_rope_theta=0.0):
             ws_bytes = max(ws_bytes, lra.lra_workspace_bytes(shape, cache, 1, 1, n_new))
         else:
             ws_bytes = max(ws_bytes, lra.lra_workspace_bytes(shape, cache, 1, 1, 0))
+        aws_bytes = max(aws_bytes, lra.lra_append_workspace_bytes(shape, cache, w_cat, ROPE_THETA, n_new))
         prepared.append((kind, cache, n_new, a))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    aws = torch.empty(aws_bytes, dtype=torch.uint8, device=dev)
 
     def iteration(stream, only=None):
         for i, (kind, cache, n_new, a) in enumerate(prepared):
             if only == "append":
-                lra.lra_cache_append(shape, cache, w_copies[i % len(w_copies)], ROPE_THETA, x[:n_new], 0, stream)
+                lra.lra_cache_append(shape, cache, w_copies[i % len(w_copies)], ROPE_THETA, x[:n_new], 0, stream, workspace=aws)
                 continue
             if only is not None and kind != only:
                 continue

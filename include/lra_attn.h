@@ -213,6 +213,9 @@ typedef struct {
  *                      weights instead of tiling; 0 automatic (64), negative: never
  *   append_stages      LDS stages of lra_cache_append's tiled GEMM: 2, 3 or 4; 0 automatic
  *   append_tile        output tile of that GEMM: 64, 128 or 256; 0 automatic
+ *   append_k_splits    parts d_model is divided into when lra_cache_append is given a workspace:
+ *                      0 automatic (from the sizes), 1 never, 2..16 that many where d_model / 64
+ *                      is a multiple of it
  *   measure_main_kernel_only  1: the call enqueues only its dominant kernel (the key-streaming
  *                      kernel) so that a benchmark can time it alone; `out` is NOT produced.
  *                      For measurement only (see lra_attn_measure.h).
@@ -226,6 +229,7 @@ typedef struct {
   int32_t append_skinny;
   int32_t append_stages;
   int32_t append_tile;
+  int32_t append_k_splits;
   int32_t measure_main_kernel_only;
 } lra_tuning;
 
@@ -327,12 +331,25 @@ typedef struct {
  * the struct.  Only BaseLRShared needs this once per appended token, for all agents.
  *
  *   x  DEVICE [n_new][d_model], dense, 16-byte aligned
- * bf16 only; head_dim in {64, 128}; rank a multiple of 8.  No workspace.  Asynchronous on
- * `stream` like the other calls.
+ * bf16 only; head_dim in {64, 128}; rank a multiple of 8.  Asynchronous on `stream` like the
+ * other calls.
+ *   workspace  DEVICE, 256-byte aligned, optional (NULL, 0): with at least
+ *              lra_append_workspace_bytes(...) bytes, chunks whose output would occupy a fraction
+ *              of the chip (some tens to about a thousand tokens) divide d_model among several
+ *              workgroups per output tile and finish in a second kernel; without it every size
+ *              runs as one kernel.  Contents undefined afterwards; calls that overlap in time
+ *              need separate workspaces.
  */
 lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
-                            const void* x, int32_t seq_index, int32_t n_new, const lra_tuning* tuning,
-                            void* stream);
+                            const void* x, int32_t seq_index, int32_t n_new, void* workspace,
+                            size_t workspace_bytes, const lra_tuning* tuning, void* stream);
+
+/*
+ * Bytes of DEVICE workspace with which lra_cache_append takes its fastest path for this n_new;
+ * 0 when the call has no use for one.  (size_t)-1 when the arguments would be rejected.
+ */
+size_t lra_append_workspace_bytes(const lra_shape* shape, const lra_cache* cache,
+                                  const lra_projection* proj, int32_t n_new, const lra_tuning* tuning);
 
 /* Static, NUL-terminated description of a status code. */
 const char* lra_status_string(lra_status status);

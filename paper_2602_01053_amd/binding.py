@@ -20,7 +20,7 @@ LRA_BF16, LRA_F32 = 0, 1
 STATIC_WORKSPACE_BYTES = 64 << 20   # LRA_STATIC_WORKSPACE_BYTES of the header
 
 EXPORTS = ("lra_workspace_bytes", "lra_attn_decode", "lra_attn_decode_static", "lra_attn_prefill", "lra_status_string",
-           "lra_cache_append", "lra_probe_stream_read", "lra_probe_mfma_bf16")
+           "lra_cache_append", "lra_append_workspace_bytes", "lra_probe_stream_read", "lra_probe_mfma_bf16")
 
 
 class LraShape(ctypes.Structure):
@@ -53,7 +53,8 @@ class LraTuning(ctypes.Structure):
     _fields_ = [("kernel_variant", ctypes.c_int32), ("decode_split_keys", ctypes.c_int32),
                 ("short_prefill", ctypes.c_int32), ("prefill_splits", ctypes.c_int32),
                 ("rope_key_prepass", ctypes.c_int32), ("append_skinny", ctypes.c_int32), ("append_stages", ctypes.c_int32),
-                ("append_tile", ctypes.c_int32), ("measure_main_kernel_only", ctypes.c_int32)]
+                ("append_tile", ctypes.c_int32), ("append_k_splits", ctypes.c_int32),
+                ("measure_main_kernel_only", ctypes.c_int32)]
 
 
 # The tuning struct this binding hands to every call.  The C library keeps no tuning state; the
@@ -93,7 +94,9 @@ def load_library() -> ctypes.CDLL:
     lib.lra_attn_prefill.restype = ctypes.c_int
     lib.lra_attn_prefill.argtypes = [sp, cp, ap, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, tp, vp]
     lib.lra_cache_append.restype = ctypes.c_int
-    lib.lra_cache_append.argtypes = [sp, cp, ctypes.POINTER(LraProjection), vp, i32, i32, tp, vp]
+    lib.lra_cache_append.argtypes = [sp, cp, ctypes.POINTER(LraProjection), vp, i32, i32, vp, ctypes.c_size_t, tp, vp]
+    lib.lra_append_workspace_bytes.restype = ctypes.c_size_t
+    lib.lra_append_workspace_bytes.argtypes = [sp, cp, ctypes.POINTER(LraProjection), i32, tp]
     lib.lra_status_string.restype = ctypes.c_char_p
     lib.lra_status_string.argtypes = [ctypes.c_int]
     lib.lra_probe_stream_read.restype = ctypes.c_int
@@ -109,14 +112,31 @@ def lra_status_string(status: int) -> str:
 
 
 def lra_cache_append(shape: LraShape, cache: LraCache, w: torch.Tensor, rope_theta: float, x: torch.Tensor,
-                     seq_index: int, stream=None) -> None:
+                     seq_index: int, stream=None, workspace: Optional[torch.Tensor] = None) -> None:
     """Project the new tokens x [n_new][d_model] with w [2*Hkv*d + r][d_model] and write their
-    K_base / V_base / L rows into the cache (the last n_new rows of sequence seq_index)."""
+    K_base / V_base / L rows into the cache (the last n_new rows of sequence seq_index).  `workspace`
+    (optional, lra_append_workspace_bytes bytes) lets mid-sized chunks split d_model over the chip."""
     if not (x.is_contiguous() and w.is_contiguous()) or x.shape[1] != w.shape[1]:
         raise LraError(2, "x and w must be dense and share d_model")
     proj = LraProjection(_ptr(w), int(w.shape[1]), float(rope_theta))
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().lra_cache_append(ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(proj), _ptr(x),
-                                           int(seq_index), int(x.shape[0]), ctypes.byref(_tuning), _stream_ptr(stream)))
+                                           int(seq_index), int(x.shape[0]), _ptr(workspace), ws_bytes,
+                                           ctypes.byref(_tuning), _stream_ptr(stream)))
+
+
+def lra_append_workspace_bytes(shape: LraShape, cache: LraCache, w: torch.Tensor, rope_theta: float, n_new: int) -> int:
+    proj = LraProjection(_ptr(w), int(w.shape[1]), float(rope_theta))
+    n = load_library().lra_append_workspace_bytes(ctypes.byref(shape), ctypes.byref(cache), ctypes.byref(proj),
+                                                  int(n_new), ctypes.byref(_tuning))
+    if n == ctypes.c_size_t(-1).value:
+        raise LraError(2, "lra_append_workspace_bytes: arguments rejected")
+    return int(n)
+
+
+def lra_set_append_k_splits(parts: int) -> int:
+    """Parts of d_model in lra_cache_append when it has a workspace: 0 automatic, 1 never, 2..16 forced."""
+    return _swap("append_k_splits", parts)
 
 
 def _swap(field: str, value: int) -> int:

@@ -238,22 +238,38 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
   return LRA_OK;
 }
 
-lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
-                            const void* x, int32_t seq_index, int32_t n_new, const lra_tuning* tuning,
-                            void* stream) {
+// Argument checks shared by lra_cache_append and lra_append_workspace_bytes (x may be NULL for the latter).
+static lra_status check_append(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
+                               int32_t seq_index, int32_t n_new) {
   lra_status st = check_common(shape, cache);
   if (st != LRA_OK) return st;
-  if (!proj || !proj->w || !x) return LRA_ERR_NULL;
+  if (!proj || !proj->w) return LRA_ERR_NULL;
   if (seq_index < 0 || seq_index >= cache->n_seqs) return LRA_ERR_SHAPE;
   if (n_new < 1 || n_new > cache->max_seq_len) return LRA_ERR_SHAPE;
   if (proj->d_model < 64 || !(proj->rope_theta >= 0.f) || std::isinf(proj->rope_theta)) return LRA_ERR_SHAPE;
-  if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(proj->w)) & 15) return LRA_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(proj->w) & 15) return LRA_ERR_SHAPE;
   if (shape->dtype != LRA_BF16 || shape->rank % 8 != 0 || proj->d_model % 64 != 0) return LRA_ERR_UNSUPPORTED;
   // x and w are addressed with 32-bit byte offsets inside one buffer resource each
   const int64_t lim = (int64_t{1} << 32) - 4096;
   const int64_t n_feat = 2LL * shape->n_kv_heads * shape->head_dim + shape->rank;
   if (n_feat * proj->d_model * 2 > lim || static_cast<int64_t>(n_new) * proj->d_model * 2 > lim)
     return LRA_ERR_UNSUPPORTED;
+  return LRA_OK;
+}
+
+size_t lra_append_workspace_bytes(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
+                                  int32_t n_new, const lra_tuning* tuning) {
+  if (check_append(shape, cache, proj, 0, n_new) != LRA_OK) return static_cast<size_t>(-1);
+  return plan_append_split(n_new, shape->n_kv_heads, shape->head_dim, shape->rank, proj->d_model, resolve_tuning(tuning)).bytes;
+}
+
+lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, const lra_projection* proj,
+                            const void* x, int32_t seq_index, int32_t n_new, void* workspace,
+                            size_t workspace_bytes, const lra_tuning* tuning, void* stream) {
+  lra_status st = check_append(shape, cache, proj, seq_index, n_new);
+  if (st != LRA_OK) return st;
+  if (!x) return LRA_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(x) & 15) return LRA_ERR_SHAPE;
   const Tuning tune = resolve_tuning(tuning);
   AppendParams p{};
   p.x = x;
@@ -280,6 +296,13 @@ lra_status lra_cache_append(const lra_shape* shape, const lra_cache* cache, cons
   p.skinny_max = tune.append_skinny;
   p.stages = tune.append_stages;
   p.tile = tune.append_tile;
+  // the split over d_model, where the sizes ask for it and the caller brought room for its parts
+  const AppendSplit sp = plan_append_split(n_new, shape->n_kv_heads, shape->head_dim, shape->rank, proj->d_model, tune);
+  const bool split = sp.k_splits > 1 && workspace != nullptr && !(reinterpret_cast<uintptr_t>(workspace) & 255) &&
+                     workspace_bytes >= sp.bytes;
+  p.k_splits = split ? sp.k_splits : 1;
+  p.split_bt = sp.bt;
+  p.split_ws = split ? static_cast<float*>(workspace) : nullptr;
   if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return LRA_ERR_HIP;
   return LRA_OK;
 }

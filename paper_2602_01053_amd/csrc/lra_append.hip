@@ -35,7 +35,11 @@ __device__ __forceinline__ int append_length(int len, int max_seq_len) { return 
 
 // BT = 64 halves the token side of the tile (a wave then owns 64 features x 32 tokens): twice the
 // workgroups and three quarters of the bytes per step for chunks too small to fill the chip.
-template <int D, bool PAGED, int NS, int BT = 128>
+// SPLITK: blockIdx.z takes one of p.k_splits equal parts of d_model and leaves its fp32 sums in the
+// workspace, [part][token][feature] (feature = row of w); append_finish_kernel adds the parts,
+// rotates, casts and stores.  For chunks whose output tiles would occupy a fraction of the chip
+// and walk all of d_model one step after the other.
+template <int D, bool PAGED, int NS, int BT = 128, bool SPLITK = false>
 __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendParams p) {
   constexpr int BF = 128, BK = 64;  // features, d_model step (BT tokens)
   constexpr bool ONE_TB = BT == 64;  // one 32-token block per wave
@@ -90,11 +94,13 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
 #pragma unroll
     for (int part = 0; part < 8; ++part) issue_part(k0, st, part);
   };
-  const int n_steps = p.d_model / BK;
+  const int n_steps = SPLITK ? p.d_model / BK / p.k_splits : p.d_model / BK;
+  const int k_first = SPLITK ? static_cast<int>(blockIdx.z) * n_steps * BK : 0;  // first d_model index of this part
 #pragma unroll
   for (int st = 0; st < NS - 1; ++st)
-    if (st < n_steps) issue_step(st * BK, st);
-  if (tid < D / 2 && p.rope_theta > 0.f) rope_rate[tid] = rope_rate_rev(tid, D, p.rope_theta);  // read after the loop's barriers
+    if (st < n_steps) issue_step(k_first + st * BK, st);
+  if constexpr (!SPLITK)  // (the finishing kernel rotates)
+    if (tid < D / 2 && p.rope_theta > 0.f) rope_rate[tid] = rope_rate_rev(tid, D, p.rope_theta);  // read after the loop's barriers
 
   // ---------------- operands ----------------
   // A operand: W rows (features), B operand: X rows (tokens); lane (row l32 of a 32-row block,
@@ -136,7 +142,7 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
     else pf_wait_vm0();
     __syncthreads();
     const bool more = step + NS - 1 < n_steps;
-    const int k_next = (step + NS - 1) * BK;
+    const int k_next = k_first + (step + NS - 1) * BK;
     const unsigned char* wt = smem + ST * STAGE;
     const unsigned char* xt = wt + TILE_BYTES;
     if (NS == 2) {
@@ -214,6 +220,28 @@ __global__ __launch_bounds__(256, NS == 2 ? 2 : 1) void append_kernel(AppendPara
   // ---------------- epilogue: rotate the keys, cast, store into the cache rows ----------------
   // acc[a][b], register i, lane (l32, g2): feature 32*fb_a + 8(i/4) + 4g2 + i%4 of the tile,
   // token 32*tb_b + l32 of the tile.
+  if constexpr (SPLITK) {
+    // the sums of this part of d_model as they are, four consecutive features per 16-byte store
+    const int n_feat = 2 * HD + p.rank;
+    const int region = kind == 2 ? p.rank : HD;   // features of this tile's region
+    float* part = p.split_ws + static_cast<int64_t>(blockIdx.z) * p.n_new * n_feat;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      if ((b == 1 && (lr_tile || ONE_TB)) || !stores) continue;
+      const int tok = tok0 + 32 * (b == 0 ? tb0 : tb1) + l32;
+      if (tok >= n_new) continue;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int f = feat0 + 32 * (a == 0 ? fb0 : fb1) + 8 * q + 4 * g2;  // inside the region: all four or none
+          if (f < region)
+            *reinterpret_cast<float4*>(part + static_cast<int64_t>(tok) * n_feat + (w_row0 - feat0) + f) =
+                make_float4(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+        }
+    }
+    return;
+  }
   bf16_t* kcache = static_cast<bf16_t*>(kind == 0 ? p.k_base : p.v_base);
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
@@ -746,6 +774,88 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
   dst[D / 2] = f32_to_bf16(hi);
 }
 
+// Second half of the split over d_model: adds the parts append_kernel<..., SPLITK> left in the
+// workspace, rotates the keys, casts and writes the cache rows.  Grid (new token, chunk of 256
+// items); a thread takes one item, four consecutive features: of V or L as they are, of K together with their
+// rotary partners half a head further on.
+template <int D, bool PAGED>
+__global__ __launch_bounds__(256) void append_finish_kernel(AppendParams p) {
+  const int tid = threadIdx.x;
+  const int tok = blockIdx.x;
+  const int HD = p.n_kv_heads * D;
+  const int n_feat = 2 * HD + p.rank;
+  const int k_items = HD / 8, v_items = HD / 4, l_items = p.rank / 4;
+  const int it = blockIdx.y * 256 + tid;
+  // rotation rates of the pairs, for the workgroups that hold key items
+  __shared__ double rope_rate[D / 2];
+  if (static_cast<int>(blockIdx.y) * 256 < k_items && p.rope_theta > 0.f) {
+    if (tid < D / 2) rope_rate[tid] = rope_rate_rev(tid, D, p.rope_theta);
+    __syncthreads();
+  }
+  if (it >= k_items + v_items + l_items) return;
+  const int n_t = append_length(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  const int j = n_t - p.n_new + tok;  // cache row of this token, and its position
+  if (j < 0) return;
+  int64_t kv_off, l_off;  // element offsets of (token j, kv head 0) in K_base / V_base and of row j in L
+  if (PAGED) {
+    const int blk = p.block_table[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)];
+    kv_off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(j & 15) * p.kv_token_stride;
+    l_off = (static_cast<int64_t>(blk) * 16 + (j & 15)) * p.l_row_stride;
+  } else {
+    kv_off = static_cast<int64_t>(j) * p.kv_token_stride;
+    l_off = static_cast<int64_t>(j) * p.l_row_stride;
+  }
+  const float* row = p.split_ws + static_cast<int64_t>(tok) * n_feat;
+  const int64_t part_stride = static_cast<int64_t>(p.n_new) * n_feat;
+  // the parts in order (the same sum every run); the part count is a power of two >= 2, or any
+  // forced count: pairs of loads in flight, a last single one for odd counts
+  auto sum4 = [&](int f) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    int z = 0;
+    for (; z + 1 < p.k_splits; z += 2) {
+      const float4 a = *reinterpret_cast<const float4*>(row + z * part_stride + f);
+      const float4 b = *reinterpret_cast<const float4*>(row + (z + 1) * part_stride + f);
+      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+      v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+    }
+    if (z < p.k_splits) {
+      const float4 a = *reinterpret_cast<const float4*>(row + z * part_stride + f);
+      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+    }
+    return v;
+  };
+  auto store4 = [&](bf16_t* dst, float4 v) {
+    *reinterpret_cast<uint2*>(dst) = make_uint2(pf_pack2(v.x, v.y), pf_pack2(v.z, v.w));
+  };
+  if (it < k_items) {
+    // features head*D + dd .. dd+3 (dd < D/2) and their partners at + D/2
+    const int head = it / (D / 8), dd = (it - head * (D / 8)) * 4;
+    float4 lo = sum4(head * D + dd), hi = sum4(head * D + D / 2 + dd);
+    if (p.rope_theta > 0.f) {
+      float l4[4] = {lo.x, lo.y, lo.z, lo.w}, h4[4] = {hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float sn, cs;
+        rope_sincos(rope_rate[dd + e], j, sn, cs);
+        const float a = l4[e], b = h4[e];
+        l4[e] = a * cs - b * sn;
+        h4[e] = b * cs + a * sn;
+      }
+      lo = make_float4(l4[0], l4[1], l4[2], l4[3]);
+      hi = make_float4(h4[0], h4[1], h4[2], h4[3]);
+    }
+    bf16_t* dst = static_cast<bf16_t*>(p.k_base) + kv_off + static_cast<int64_t>(head) * p.kv_head_stride + dd;
+    store4(dst, lo);
+    store4(dst + D / 2, hi);
+  } else if (it < k_items + v_items) {
+    const int f = (it - k_items) * 4, head = f / D, dd = f - head * D;
+    store4(static_cast<bf16_t*>(p.v_base) + kv_off + static_cast<int64_t>(head) * p.kv_head_stride + dd, sum4(HD + f));
+  } else {
+    const int f = (it - k_items - v_items) * 4;
+    store4(static_cast<bf16_t*>(p.l) + l_off + f, sum4(2 * HD + f));
+  }
+}
+
 template <int D, int NT>
 static void launch_gemv(const AppendParams& p, hipStream_t s) {
   const int hd = p.n_kv_heads * p.head_dim;
@@ -764,6 +874,29 @@ static void launch_skinny(const AppendParams& p, hipStream_t s) {
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s) {
   const int hd = p.n_kv_heads * p.head_dim;
+  const bool paged = p.block_size != 0;
+  if (p.k_splits > 1) {
+    // Split over d_model (chosen by the host from the sizes, with a workspace): tiles of 128 features
+    // x 64 or 128 tokens, four LDS stages, p.k_splits parts in z, then the finishing kernel.
+    const int bt = p.split_bt;
+    dim3 grid((p.n_new + bt - 1) / bt, 2 * ((hd + 127) / 128) + 1, p.k_splits);
+#define LRA_APPEND_SPLIT(DD, PG)                                                                                        \
+  do {                                                                                                                  \
+    if (bt == 64) hipLaunchKernelGGL((append_kernel<DD, PG, 4, 64, true>), grid, dim3(256), 0, s, p);                   \
+    else hipLaunchKernelGGL((append_kernel<DD, PG, 4, 128, true>), grid, dim3(256), 0, s, p);                           \
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;                                                   \
+    hipLaunchKernelGGL((append_finish_kernel<DD, PG>), dim3(p.n_new, (hd / 8 + hd / 4 + p.rank / 4 + 255) / 256), dim3(256), 0, s, p);                               \
+  } while (0)
+    if (p.head_dim == 128) {
+      if (paged) LRA_APPEND_SPLIT(128, true);
+      else LRA_APPEND_SPLIT(128, false);
+    } else {
+      if (paged) LRA_APPEND_SPLIT(64, true);
+      else LRA_APPEND_SPLIT(64, false);
+    }
+#undef LRA_APPEND_SPLIT
+    return hipGetLastError();
+  }
   if (p.n_new <= 2 && p.n_new <= p.skinny_max) {
     if (p.head_dim == 128) {
       if (p.n_new == 1) launch_gemv<128, 1>(p, s);
@@ -787,7 +920,6 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s) {
     }
     return hipGetLastError();
   }
-  const bool paged = p.block_size != 0;
   // 256 x 256 tiles, one workgroup per CU: on request, or when their full tiles fill whole rounds of
   // the chip's 256 CUs (at most a tenth of the last round idle) and there are at least two rounds.
   // Measured on the Llama-3-8B projection: 277 us against 302 us at 16384 new tokens (512 tiles, two

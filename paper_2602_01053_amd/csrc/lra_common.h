@@ -127,6 +127,9 @@ struct AppendParams {
   int stages;      // LDS stages of the tiled GEMM: 0 = chosen from the grid, else 2, 3 or 4
   int tile;        // output tile of the GEMM kernels: 0 = chosen from the grid, 128 or 256
   int skinny_max;  // up to this many new tokens the weight-streaming kernel runs instead of the tiled GEMM
+  // split over d_model: parts (1 = none), token side of the tile (64 or 128), fp32 partial sums [part][token][feature]
+  int k_splits, split_bt;
+  float* split_ws;
 };
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 

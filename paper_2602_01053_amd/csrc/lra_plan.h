@@ -23,6 +23,7 @@ struct Tuning {
   int append_skinny = 64;   // new tokens up to which lra_cache_append streams the weights (0 = never)
   int append_stages = 0;    // LDS stages of the tiled append GEMM, 0 = chosen from the grid
   int append_tile = 0;      // output tile of the append GEMM, 0 = chosen from the grid
+  int append_k_splits = 0;  // parts of d_model in the append GEMM: 0 = chosen from the grid, 1 = never split
   bool main_kernel_only = false;  // measurement: enqueue only the dominant kernel of a call
 };
 Tuning resolve_tuning(const lra_tuning* t);
@@ -47,6 +48,14 @@ lra_status check_common(const lra_shape* sh, const lra_cache* c);
 bool plan_sizes_fit(const lra_shape* sh, const lra_cache* c, int32_t tokens, int32_t max_queries_per_seq);
 Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_queries_per_seq, bool prefill,
                const Tuning& tune);
+
+// lra_cache_append: parts of d_model the tiled GEMM is divided into (1: none), the token side of its
+// tile, and the fp32 workspace the parts need.
+struct AppendSplit {
+  int k_splits, bt;
+  size_t bytes;
+};
+AppendSplit plan_append_split(int n_new, int n_kv_heads, int head_dim, int rank, int d_model, const Tuning& tune);
 
 // Row tiles per workgroup the split-KV MFMA kernels are built for.
 int decode_mfma_row_tiles(int rows_needed);

@@ -118,6 +118,32 @@ int main(int argc, char** argv) {
       }
     }
   }
+  // the split of lra_cache_append over d_model
+  for (int it = 0; it < cases; ++it) {
+    const int64_t n_new = pick({1, 16, 32, 33, 64, 100, 128, 129, 512, 1000, 1024, 4096, 1 << 20, (1 << 20) + 1, INT32_MAX});
+    const int hkv = static_cast<int>(pick({1, 2, 3, 8, 64, 4096}));
+    const int d = static_cast<int>(pick({64, 128}));
+    const int r = static_cast<int>(pick({8, 16, 24, 64}));
+    const int dm = static_cast<int>(pick({64, 128, 704, 768, 1024, 4096, 8192, 1 << 20}));
+    lra_tuning t{};
+    t.append_k_splits = static_cast<int32_t>(pick({0, 0, 1, 2, 3, 8, 16, 17, -1}));
+    t.append_tile = static_cast<int32_t>(pick({0, 0, 0, 64, 128}));
+    t.append_stages = static_cast<int32_t>(pick({0, 0, 0, 3}));
+    const Tuning tune = resolve_tuning(&t);
+    const AppendSplit sp = plan_append_split(static_cast<int>(n_new), hkv, d, r, dm, tune);
+    CHECK(sp.k_splits >= 1 && sp.k_splits <= 16 && (sp.bt == 64 || sp.bt == 128));
+    CHECK((sp.k_splits == 1) == (sp.bytes == 0));
+    if (sp.k_splits > 1) {
+      const int64_t n_feat = 2LL * hkv * d + r;
+      CHECK((dm / 64) % sp.k_splits == 0 && n_new <= (1 << 20));
+      CHECK(sp.bytes >= static_cast<size_t>(sp.k_splits) * n_new * n_feat * 4 && sp.bytes % 256 == 0);
+      CHECK(tune.append_tile == 0 && tune.append_stages == 0 && tune.append_k_splits != 1);
+      if (tune.append_k_splits == 0) {
+        const int64_t tiles = (n_new + sp.bt - 1) / sp.bt * (2 * ((static_cast<int64_t>(hkv) * d + 127) / 128) + 1);
+        CHECK(tiles * sp.k_splits <= kCUs && dm / 64 / sp.k_splits >= 4 && n_new > 32);
+      }
+    }
+  }
   std::printf("plan_fuzz: %d cases, %d accepted by the argument checks, all plans consistent\n", cases, accepted);
   return accepted > cases / 10 ? 0 : 2;
 }

@@ -164,7 +164,7 @@ def test_cache_append_rejects_bad_arguments_before_launch(lib):
         c = c or c0
         pr = LraProjection(w, d_model, theta)
         return lib.lra_cache_append(ctypes.byref(sh), ctypes.byref(c), None if no_proj else ctypes.byref(pr), x, seq,
-                                    n_new, None, None)
+                                    n_new, None, 0, None, None)
 
     assert call(no_proj=True) == NULL
     assert call(w=None) == NULL
@@ -237,8 +237,8 @@ def test_header_is_plain_c(tmp_path):
     src.write_text(
         '#include "lra_attn.h"\n#include "lra_attn_measure.h"\n'
         "lra_status call(const lra_shape* s, const lra_cache* c, const lra_projection* p, const void* x) {\n"
-        "  lra_tuning t = {0, 0, 0, 0, 0, 0, 0, 0, 0};\n"
-        "  return lra_cache_append(s, c, p, x, 0, 1, &t, (void*)0);\n"
+        "  lra_tuning t = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};\n"
+        "  return lra_cache_append(s, c, p, x, 0, 1, (void*)0, 0, &t, (void*)0);\n"
         "}\n"
         "size_t need(const lra_shape* s, const lra_cache* c) { return lra_workspace_bytes(s, c, 4, 4, 0, (const lra_tuning*)0); }\n")
     res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",

@@ -95,8 +95,26 @@ def test_append_tile_sizes(case, tile):
         lra.lra_set_append_skinny(prev_k)
 
 
+GUARD = 4096  # bytes of a bit pattern on either side of a workspace
+
+
+def _guarded_workspace(nbytes):
+    """A 256-byte aligned workspace of nbytes between two guard bands; returns (workspace view, whole buffer)."""
+    whole = torch.full((nbytes + 2 * GUARD,), 0xA5, dtype=torch.uint8, device=DEV)
+    return whole[GUARD:GUARD + nbytes], whole
+
+
+def _guards_intact(whole):
+    return bool((whole[:GUARD] == 0xA5).all()) and bool((whole[-GUARD:] == 0xA5).all())
+
+
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
 def test_append_contiguous(case):
+    _append_contiguous(case, False)
+
+
+def _append_contiguous(case, with_workspace):
+    """Runs one append on a contiguous cache against the oracle; returns the workspace bytes the library asked for."""
     n, n_new, d_model, hkv, d, r, theta = case
     x, w = _inputs(5000 + n + n_new, n_new, d_model, hkv, d, r)
     k_base = torch.full((n, hkv, d), SENTINEL, dtype=torch.bfloat16, device=DEV)
@@ -107,8 +125,16 @@ def test_append_contiguous(case):
     shape = lra.make_shape(q_like, hkv, r, 0.0)
     cache = lra.make_cache(k_base, v_base, l, seq_lens, n, None)
     xd, wd = x.to(DEV), w.to(DEV)
-    lra.lra_cache_append(shape, cache, wd, theta, xd, 0)
+    need = 0
+    if with_workspace:
+        need = lra.lra_append_workspace_bytes(shape, cache, wd, theta, n_new)
+        ws, whole = _guarded_workspace(max(need, 256))
+        lra.lra_cache_append(shape, cache, wd, theta, xd, 0, workspace=ws)
+    else:
+        lra.lra_cache_append(shape, cache, wd, theta, xd, 0)
     torch.cuda.synchronize()
+    if with_workspace:
+        assert _guards_intact(whole)
     f = lambda t: t.to(torch.float64).cpu().numpy()
     pos = np.arange(n - n_new, n)
     k_ref, v_ref, l_ref = oracle.project_new_tokens(f(x), f(w), hkv, d, r, pos, theta)
@@ -117,19 +143,69 @@ def test_append_contiguous(case):
     _gate(f(l)[n - n_new:], l_ref, "L rows")
     for t in (k_base, v_base, l):   # older rows untouched
         assert bool((t[:n - n_new] == SENTINEL).all())
+    return need
 
 
-@pytest.mark.parametrize("skinny,tile", [(0, 64), (0, 128), (0, 256), (1 << 30, 0)], ids=["tile64", "tiled", "wide", "streamed"])
-def test_append_paged_then_attend(skinny, tile):
-    prev, prev_t = lra.lra_set_append_skinny(skinny), lra.lra_set_append_tile(tile)
+SPLIT_CASES = [
+    # n, n_new, d_model, Hkv, d, r, theta, parts the automatic choice takes (0: it keeps one kernel)
+    (100, 17, 512, 2, 128, 16, 500000.0, 0),        # up to 32 tokens: the weight-streaming kernel
+    (200, 40, 512, 2, 128, 16, 500000.0, 2),        # 8 steps of d_model: two parts of four
+    (65000, 33, 1024, 4, 128, 16, 500000.0, 4),
+    (64, 64, 768, 3, 64, 64, 10000.0, 2),           # 12 steps: two parts of six
+    (200, 129, 256, 2, 128, 16, 500000.0, 0),       # 4 steps: too short to divide
+    (700, 300, 704, 3, 64, 24, 10000.0, 0),         # 11 steps: no part count divides them
+    (513, 257, 4096, 8, 128, 64, 0.0, 2),           # Llama-3-8B projection shape, r = 64, unrotated keys
+    (1000, 512, 1024, 4, 128, 32, 500000.0, 2),
+    (4300, 100, 4096, 8, 128, 16, 500000.0, 4),     # Llama-3-8B shape, a trace-sized chunk
+    (40000, 400, 4096, 8, 128, 16, 500000.0, 2),    # ... and about the largest chunk that still divides
+    (40000, 1000, 4096, 8, 128, 16, 500000.0, 0),   # more than half a chip of tiles: one kernel
+    (2048, 2048, 4096, 8, 128, 16, 500000.0, 0),    # enough tiles for the chip: one kernel
+    (31, 16, 4096, 8, 128, 16, 500000.0, 0),        # few tokens: the weight-streaming kernel
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g_auto%d" % c)
+def test_append_split_over_d_model_automatic(case):
+    """lra_cache_append with a workspace: mid-sized chunks divide d_model among several workgroups per output
+    tile and finish in a second kernel.  Same oracle, same gate, guard bands around the workspace intact, and
+    the workspace asked for is the size of the parts the automatic choice takes."""
+    *plain, parts = case
+    n, n_new, d_model, hkv, d, r, theta = plain
+    need = _append_contiguous(tuple(plain), True)
+    expect = parts * n_new * (2 * hkv * d + r) * 4 if parts else 0
+    assert need == (expect + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("parts", [2, 4, 16])
+@pytest.mark.parametrize("case", [(200, 129, 256, 2, 128, 16, 500000.0), (5000, 40, 1024, 2, 64, 8, 10000.0),
+                                  (513, 257, 4096, 8, 128, 64, 0.0), (300, 300, 512, 3, 64, 24, 10000.0)],
+                         ids=lambda c: "n%d_new%d_dm%d_hkv%d_d%d_r%d_th%g" % c)
+def test_append_split_over_d_model_forced(case, parts):
+    """Part counts forced through the tuning struct, down to one step of d_model per part; counts that do not
+    divide the steps leave the call on one kernel (and the workspace request at 0)."""
+    prev = lra.lra_set_append_k_splits(parts)
     try:
-        _paged_then_attend()
+        need = _append_contiguous(case, True)
+    finally:
+        lra.lra_set_append_k_splits(prev)
+    n, n_new, d_model, hkv, d, r, theta = case
+    divides = (d_model // 64) % parts == 0
+    assert (need > 0) == divides
+
+
+@pytest.mark.parametrize("skinny,tile,parts", [(0, 64, 0), (0, 128, 0), (0, 256, 0), (1 << 30, 0, 0), (64, 0, 2), (64, 0, 8)],
+                         ids=["tile64", "tiled", "wide", "streamed", "two_parts", "eight_parts"])
+def test_append_paged_then_attend(skinny, tile, parts):
+    prev, prev_t, prev_p = lra.lra_set_append_skinny(skinny), lra.lra_set_append_tile(tile), lra.lra_set_append_k_splits(parts)
+    try:
+        _paged_then_attend(parts > 1)
     finally:
         lra.lra_set_append_skinny(prev)
         lra.lra_set_append_tile(prev_t)
+        lra.lra_set_append_k_splits(prev_p)
 
 
-def _paged_then_attend():
+def _paged_then_attend(with_workspace=False):
     """Appends to two sequences of a paged cache (a last block that is partly filled, blocks in
     permuted order), checks the written rows and that nothing else moved, then runs the
     attention prefill on the appended tokens and compares it with the oracle evaluated on
@@ -156,7 +232,16 @@ def _paged_then_attend():
     w = None
     for s in range(2):
         x, w = _inputs(6100 + s, n_new[s], d_model, hkv, d, r)
-        lra.lra_cache_append(shape, cache, w.to(DEV), theta, x.to(DEV), s)
+        if with_workspace:
+            wd = w.to(DEV)
+            need = lra.lra_append_workspace_bytes(shape, cache, wd, theta, n_new[s])
+            assert need > 0
+            ws, whole = _guarded_workspace(need)
+            lra.lra_cache_append(shape, cache, wd, theta, x.to(DEV), s, workspace=ws)
+            torch.cuda.synchronize()
+            assert _guards_intact(whole)
+        else:
+            lra.lra_cache_append(shape, cache, w.to(DEV), theta, x.to(DEV), s)
         torch.cuda.synchronize()
         pos = np.arange(seq_lens[s] - n_new[s], seq_lens[s])
         k_ref, v_ref, l_ref = oracle.project_new_tokens(f(x), f(w), hkv, d, r, pos, theta)
