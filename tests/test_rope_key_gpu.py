@@ -116,6 +116,27 @@ def test_rotary_prefill_at_configuration_3_every_row():
         assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
 
 
+def test_rotary_prefill_with_large_key_adapters_at_configuration_3_shape():
+    """Configuration 3's shape with five times larger adapters (B ~ N(0, 0.1^2): the rotated adapter part is a
+    large share of every key, so the second rounding of the completed keys to bf16 weighs most), both ways of
+    completing the keys, on a spread of rows that includes the first and last rows of q tiles."""
+    w = W.make_contiguous("cfg3_b01", "prefill", seed=322, n_agents=1, n_q_heads=32, n_kv_heads=8, head_dim=128, rank=16,
+                          n=18432, n_new=2048, d_model=None, b_std=0.1)
+    rows = np.unique(np.concatenate([np.arange(0, 2048, 24), np.arange(127, 2048, 128), np.arange(128, 2048, 128), [2047]]))
+    a = int(w.query_adapter[0])
+    ref = oracle.prefill(_f64(w.q), _f64(w.k_base), _f64(w.v_base), _f64(w.l), _f64(w.b_k[a]), _f64(w.b_v[a]),
+                         n=w.seq_lens[0], scale=w.scale, rows=rows, key_rope_theta=500000.0)
+    for prepass in (True, False):
+        prev = lra.lra_set_rope_key_prepass(prepass)
+        try:
+            got = _run(w, 500000.0)[rows]
+        finally:
+            lra.lra_set_rope_key_prepass(prev)
+        rel, mx = errors(got, ref)
+        print(f"b_std 0.1, {'key pre-pass' if prepass else 'tiles completed in the kernel'}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+        assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
 def test_rotary_prefill_key_prepass_layouts_and_small_workspace():
     """The pre-pass writes the completed keys in the layout of K_base: token-major and head-major caches give
     the same output; a call whose workspace has no room for them (here: none at all) completes the tiles in the
