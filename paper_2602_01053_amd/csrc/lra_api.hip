@@ -37,6 +37,8 @@ static void fill_params(Params& p, const lra_shape* sh, const lra_cache* c, cons
   p.l_row_stride = c->l_row_stride ? c->l_row_stride : sh->rank;
   p.l_adapter_stride = c->l_adapter_stride;
   p.l_block = pl.l_block;
+  // wide L rows (64 bytes per token and more, or one low-rank cache per adapter): the kv heads of a key share on one XCD
+  p.share_major = (sh->rank >= 32 || pl.l_block != 0) ? 1 : 0;
   p.n_q_heads = sh->n_q_heads;
   p.n_kv_heads = sh->n_kv_heads;
   p.group = sh->n_q_heads / sh->n_kv_heads;

@@ -45,6 +45,7 @@ struct Params {
   int32_t split_keys, n_splits;
   float scale;
   float key_rope_theta;  // > 0: the key-side adapter contribution is rotated by its token's position
+  int32_t share_major;       // decode_stream_kernel: workgroup index laid out so that all kv heads of a key share run on one XCD
 #ifdef LRA_TIMING
   unsigned long long* timing;  // instrumented test build only: per-wave phase stamps
 #endif

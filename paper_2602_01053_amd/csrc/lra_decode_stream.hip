@@ -113,10 +113,20 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
   asm volatile("" ::"s"(p.k_base), "s"(p.v_base), "s"(p.l), "s"(p.seq_lens), "s"(p.query_adapter));
   asm volatile("" ::"s"(p.kv_token_stride), "s"(p.kv_head_stride), "s"(p.l_row_stride), "s"(p.l_adapter_stride));
   asm volatile("" ::"s"(p.rank), "s"(p.group_pad), "s"(p.row_groups), "s"(p.max_seq_len), "s"(p.n_queries), "s"(p.n_adapters),
-               "s"(p.split_keys), "s"(p.l_block));
-  // kv head is the fastest grid index: workgroups go round-robin over the XCDs, so with 8 kv
-  // heads all workgroups of a head run on one XCD and share Q, B_K and L in its L2
-  const int h = blockIdx.x, split = blockIdx.y, rg = blockIdx.z;
+               "s"(p.split_keys), "s"(p.l_block), "s"(p.share_major), "s"(p.n_splits));
+  // Workgroups go round-robin over the 8 XCDs in the order of their linear index, and every XCD
+  // has an L2 of its own.  Two layouts of that index, chosen by the host:
+  //  - kv head fastest (grid (Hkv, key shares, row groups)): with 8 kv heads all workgroups of a
+  //    head run on one XCD, share Q and B_K there, and leave the B_V rows the merge kernel will
+  //    ask for in the L2 it will ask from.  Every XCD then reads all of L.
+  //  - share_major (grid (8 Hkv, key shares / 8, row groups), x = (key share mod 8) + 8 kv head):
+  //    all kv heads of one key share run on ONE XCD, at the same time, and read that share's L rows
+  //    once instead of once per head.  For wide L rows (8 heads, r = 64: 8 x 4.2 MB of a 141 MB call).
+  const int bx = blockIdx.x, by = blockIdx.y;
+  const int h = p.share_major ? bx >> 3 : bx;
+  const int split = p.share_major ? by * 8 + (bx & 7) : by;
+  const int rg = blockIdx.z;
+  if (split >= p.n_splits) return;  // (share_major pads the key shares to a multiple of 8)
   const int t = CAUSAL ? p.seq_index : 0;                      // contiguous caches hold one sequence
   const int32_t len_t = CONST_I32(p.seq_lens)[t];
   const int n_q = CAUSAL ? p.n_new : p.n_queries;
@@ -390,12 +400,14 @@ __global__ __launch_bounds__(512, 2) void decode_stream_kernel(Params p) {
     // (one 4-byte read per 128-byte line), so that they wait in this XCD's L2 instead of in
     // HBM: prologue wave w takes agent slot w of every row tile.
     int warm[RT];
+    // (the merge kernel's rows of kv head h run on XCD h mod 8: under share_major that is where key share h mod 8 runs)
+    const int warm_split = p.share_major ? min(h & 7, p.n_splits - 1) : min(1, p.n_splits - 1);
     auto warm_b_v = [&]() __attribute__((always_inline)) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         warm[rt] = 0;
         const int a = slot_adapter(rt, hw);
-        if (p.b_v != nullptr && split == min(1, p.n_splits - 1) && a >= 0) {
+        if (p.b_v != nullptr && split == warm_split && a >= 0) {
           constexpr int LPR = D * 2 / 128;  // 128-byte lines per B_V row of one kv head
           const int n_lines = r * LPR;      // <= 128
           const char* bv = static_cast<const char*>(p.b_v) +
@@ -829,7 +841,8 @@ static hipError_t launch_stream2(const Params& p, dim3 grid, hipStream_t s) {
 
 // main_kernel_only (measurement): the streaming kernel alone, on whatever Qt an earlier call left
 hipError_t launch_decode_stream(const Params& p, int row_tiles, bool main_kernel_only, hipStream_t s) {
-  const dim3 grid(p.n_kv_heads, p.n_splits, p.row_groups);
+  const dim3 grid = p.share_major ? dim3(8 * p.n_kv_heads, (p.n_splits + 7) / 8, p.row_groups)
+                                  : dim3(p.n_kv_heads, p.n_splits, p.row_groups);  // (see the index layouts in the kernel)
   if (p.qt_ws != nullptr && !main_kernel_only) {
     if (p.head_dim == 128) { if (p.rank > 32) launch_prepass2<128, 64>(p, row_tiles, s); else launch_prepass2<128, 32>(p, row_tiles, s); }
     else { if (p.rank > 32) launch_prepass2<64, 64>(p, row_tiles, s); else launch_prepass2<64, 32>(p, row_tiles, s); }
