@@ -390,12 +390,19 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(Params p) {
   constexpr int SG = 256 / CQ;     // split groups for the O rows
   constexpr int OP = 64 / SG;      // passes over at most 64 splits
   constexpr int BV_PIECES = 64 * D * static_cast<int>(sizeof(T)) / 16 / 256;  // 16-byte pieces of B_V per thread at r = 64
+  // This kernel is a chain of latencies (launch, parameter block, the row's adapter id, the loads,
+  // two barriers), so nothing may stand between them: the parameter block is fetched in one round
+  // trip (left alone the compiler fetches it piece by piece behind each use), the grid is (kv head,
+  // q head of the group, query) so that no index needs a division, and every load is unconditional
+  // from a clamped index (a load under a condition, with zero as the other value, makes the compiler
+  // wait for it on the spot: both write the same register); what a clamped index fetched in vain
+  // gets weight zero below.
+  asm volatile("" ::"s"(p.part_adapter), "s"(p.part_ml), "s"(p.part_o), "s"(p.part_lr), "s"(p.b_v), "s"(p.out));
+  asm volatile("" ::"s"(p.n_q_heads), "s"(p.n_kv_heads), "s"(p.group), "s"(p.head_dim), "s"(p.rank), "s"(p.n_splits),
+               "s"(p.n_adapters));
   const int Hq = p.n_q_heads, r = p.rank, ns = p.n_splits;
-  const int h = blockIdx.x % p.n_kv_heads;
-  const int rest = blockIdx.x / p.n_kv_heads;
-  const int tok = rest / p.group;
-  const int g = h * p.group + rest % p.group;
-  const int row = tok * Hq + g;
+  const int h = blockIdx.x;
+  const int row = static_cast<int>(blockIdx.z) * Hq + h * p.group + static_cast<int>(blockIdx.y);
   const int tid = threadIdx.x, lane = tid & 63;
   const int64_t slot0 = static_cast<int64_t>(row) * ns;
 
@@ -404,39 +411,46 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(Params p) {
   __shared__ __align__(16) float olr_tot[64];
   __shared__ __align__(16) unsigned char bv_sh[64 * D * sizeof(T)];
 
-  // (clamped: whatever the workspace holds, the B_V rows read below exist)
-  const int a = min(max(((const __attribute__((address_space(4))) int32_t*)(p.part_adapter))[row], 0), p.n_adapters - 1);
+  // the row's adapter first: the B_V rows depend on it (clamped: whatever the workspace holds, the
+  // B_V rows read below exist)
+  // (requested here by hand and waited for where the B_V addresses are formed: left to the compiler
+  // the request sinks below the vector loads, and its round trip is then paid after theirs)
+  int a_raw;
+  asm volatile("s_load_dword %0, %1, 0x0" : "=s"(a_raw) : "s"(p.part_adapter + row));
 
   // ---- issue everything ----
-  const float2 st = lane < ns ? reinterpret_cast<const float2*>(p.part_ml)[slot0 + lane] : make_float2(0.f, 0.f);
+  const float2 st_raw = reinterpret_cast<const float2*>(p.part_ml)[slot0 + min(lane, ns - 1)];
   const int sg = tid / CQ, cq = tid % CQ;
   float4 xo[OP];
 #pragma unroll
-  for (int k = 0; k < OP; ++k) {
-    const int s = sg + SG * k;
-    xo[k] = s < ns ? *reinterpret_cast<const float4*>(p.part_o + (slot0 + s) * D + cq * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
+  for (int k = 0; k < OP; ++k)
+    xo[k] = *reinterpret_cast<const float4*>(p.part_o + (slot0 + min(sg + SG * k, ns - 1)) * D + cq * 4);
   const int lg16 = tid >> 4, q = tid & 15;
   const bool q_live = q * 4 < r;
   float4 xl[4];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int s = lg16 + 16 * k;
-    xl[k] = (s < ns && q_live) ? *reinterpret_cast<const float4*>(p.part_lr + (slot0 + s) * r + q * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
+  for (int k = 0; k < 4; ++k)
+    xl[k] = *reinterpret_cast<const float4*>(p.part_lr + (slot0 + min(lg16 + 16 * k, ns - 1)) * r + (q_live ? q * 4 : 0));
   constexpr int ROW_PIECES = D * static_cast<int>(sizeof(T)) / 16;  // 16-byte pieces per B_V row of one kv head
   uint4 bvp[BV_PIECES];
-  {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a_raw));
+  const int a = min(max(a_raw, 0), p.n_adapters - 1);
+  // (Requesting the slices of all adapters of a small table next to the partial rows, to pick the row's
+  // own when its id arrives, takes one dependent round trip off the path and was measured 0.8 us slower.)
+  if (p.b_v != nullptr) {  // (uniform)
     const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * D;
     const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * ld + h * D;
 #pragma unroll
     for (int k = 0; k < BV_PIECES; ++k) {
       const int e = tid + 256 * k;
-      const int rho = e / ROW_PIECES, pc = e % ROW_PIECES;
-      bvp[k] = (p.b_v != nullptr && rho < r) ? *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(bv + rho * ld) + pc * 16)
-                                              : make_uint4(0u, 0u, 0u, 0u);
+      const int rho = min(e / ROW_PIECES, r - 1), pc = e % ROW_PIECES;  // (rows beyond the rank: fetched again, never read)
+      bvp[k] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(bv + rho * ld) + pc * 16);
     }
+  } else {
+#pragma unroll
+    for (int k = 0; k < BV_PIECES; ++k) bvp[k] = make_uint4(0u, 0u, 0u, 0u);
   }
+  const float2 st = lane < ns ? st_raw : make_float2(0.f, 0.f);
 
   // ---- weights (per wave, lane = split) ----
   const bool live = st.y > 0.f;  // a share without a visible key left a zero row sum; its rows were never written
@@ -459,7 +473,7 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(Params p) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const float wk = __shfl(w, lg16 + 16 * k, kWave);
-    if (lg16 + 16 * k < ns && wk > 0.f) {
+    if (lg16 + 16 * k < ns && wk > 0.f && q_live) {
       olr.x = fmaf(wk, xl[k].x, olr.x);
       olr.y = fmaf(wk, xl[k].y, olr.y);
       olr.z = fmaf(wk, xl[k].z, olr.z);
@@ -603,8 +617,11 @@ template <typename T>
 static void launch_merge_t(const Params& p, int rows, hipStream_t s) {
   if (launch_merge_wave<T>(p, rows, s)) return;
   if (p.rank % 4 == 0 && p.n_splits <= 64 && (p.head_dim == 64 || p.head_dim == 128)) {
-    if (p.head_dim == 128) hipLaunchKernelGGL((merge_rows_kernel<T, 128>), dim3(rows), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((merge_rows_kernel<T, 64>), dim3(rows), dim3(256), 0, s, p);
+    // (kv head, q head of the group, query): workgroups go round-robin over the XCDs, so with 8 kv heads
+    // the rows of a head are merged on one XCD
+    const dim3 grid(p.n_kv_heads, p.group, rows / p.n_q_heads);
+    if (p.head_dim == 128) hipLaunchKernelGGL((merge_rows_kernel<T, 128>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((merge_rows_kernel<T, 64>), grid, dim3(256), 0, s, p);
     return;
   }
   // enough 128-thread groups that one pass of kMergeUnroll splits per thread covers the splits
