@@ -669,6 +669,18 @@ typedef __bf16 ap_bf16x2 __attribute__((ext_vector_type(2)));
 template <int D, int NT, bool PAGED>
 __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
   __shared__ float red[4][NT];
+  // A call of this kernel is one round of requests and a handful of dependent latencies; each is
+  // kept off the others' path: the parameter block comes in one round trip, the sequence length
+  // (needed only by the last step) is requested first and by hand, the weight requests (the bytes
+  // that take long) leave before the activations and unconditionally (pieces beyond the row are
+  // fetched from its last piece and multiplied by zero: a load under a condition makes the
+  // compiler wait for earlier loads on the spot), and the rotation rate of the pair (double
+  // precision exp2 and log2) is worked out while the requests are in flight.
+  asm volatile("" ::"s"(p.w), "s"(p.x), "s"(p.seq_lens), "s"(p.k_base), "s"(p.v_base), "s"(p.l));
+  asm volatile("" ::"s"(p.d_model), "s"(p.n_kv_heads), "s"(p.rank), "s"(p.n_new), "s"(p.seq_index), "s"(p.max_seq_len),
+               "s"(p.rope_theta), "s"(p.kv_token_stride), "s"(p.kv_head_stride), "s"(p.l_row_stride));
+  int len_raw;
+  asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_lens + p.seq_index));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -695,32 +707,38 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
   for (int t = 0; t < NT; ++t) acc[t] = 0.f;
   const int n_chunks = p.d_model / 8;  // 16-byte pieces of a row; lane l takes l, l + 64, ...
   constexpr int U = 8;
+  double rate = 0.0;  // revolutions per position of this thread's rotary pair (threads of the last step)
   for (int c0 = lane; c0 < n_chunks; c0 += 64 * U) {
     uint4 wv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int c = c0 + 64 * u;
       // (non-temporal: a weight row is read once per call, by this wave)
-      if (c < n_chunks) {
-        const pf_u32x4 t4 = __builtin_nontemporal_load(reinterpret_cast<const pf_u32x4*>(wp + c));
-        wv[u] = make_uint4(t4[0], t4[1], t4[2], t4[3]);
-      } else {
-        wv[u] = make_uint4(0u, 0u, 0u, 0u);
-      }
+      const pf_u32x4 t4 = __builtin_nontemporal_load(reinterpret_cast<const pf_u32x4*>(wp + min(c0 + 64 * u, n_chunks - 1)));
+      wv[u] = make_uint4(t4[0], t4[1], t4[2], t4[3]);
     }
-    // all requests out before the first use.  (The operands stay HIP's uint4 structs on purpose: with
-    // native 4-vectors this compiler selected element 0 for all four dot products.)
+    // all weight requests out before anything else.  (The operands stay HIP's uint4 structs on purpose:
+    // with native 4-vectors this compiler selected element 0 for all four dot products.)
     __builtin_amdgcn_sched_barrier(0);
+    uint4 xv[NT][U];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int u = 0; u < U; ++u) xv[t][u] = xp[t][min(c0 + 64 * u, n_chunks - 1)];
+    __builtin_amdgcn_sched_barrier(0);
+    if (c0 == lane && tid < 2 * NT && kind == 0 && p.rope_theta > 0.f) {
+      rate = rope_rate_rev(2 * sub + (tid & 1), D, p.rope_theta);
+      asm volatile("" ::"v"(rate));  // (here, under the requests, not after the reduction)
+    }
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int c = c0 + 64 * u;
-        const uint4 xv = xp[t][c < n_chunks ? c : 0];  // (the weight piece is zero there)
-        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].x), __builtin_bit_cast(ap_bf16x2, xv.x), acc[t], false);
-        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].y), __builtin_bit_cast(ap_bf16x2, xv.y), acc[t], false);
-        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].z), __builtin_bit_cast(ap_bf16x2, xv.z), acc[t], false);
-        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].w), __builtin_bit_cast(ap_bf16x2, xv.w), acc[t], false);
+        uint4 x4 = xv[t][u];
+        if (c0 + 64 * u >= n_chunks) x4 = make_uint4(0u, 0u, 0u, 0u);  // (a piece beyond the row)
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].x), __builtin_bit_cast(ap_bf16x2, x4.x), acc[t], false);
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].y), __builtin_bit_cast(ap_bf16x2, x4.y), acc[t], false);
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].z), __builtin_bit_cast(ap_bf16x2, x4.z), acc[t], false);
+        acc[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(ap_bf16x2, wv[u].w), __builtin_bit_cast(ap_bf16x2, x4.w), acc[t], false);
       }
     }
   }
@@ -736,7 +754,8 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
   // thread (pair, token): both halves of a rotary pair (K), two independent features (V, L)
   if (tid >= 2 * NT) return;
   const int q = tid & 1, t = tid >> 1;
-  const int n_t = append_length(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw));
+  const int n_t = append_length(len_raw, p.max_seq_len);
   const int j = n_t - n_new + t;
   if (t >= n_new || j < 0) return;
   float lo = red[q][t], hi = red[2 + q][t];
@@ -757,7 +776,7 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
   const int dd = 2 * sub + q;  // < d/2
   if (kind == 0 && p.rope_theta > 0.f) {
     float sn, cs;
-    rope_sincos(rope_rate_rev(dd, D, p.rope_theta), j, sn, cs);
+    rope_sincos(rate, j, sn, cs);
     const float a = lo, b = hi;
     lo = a * cs - b * sn;
     hi = b * cs + a * sn;
