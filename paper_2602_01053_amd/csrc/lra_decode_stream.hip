@@ -749,8 +749,13 @@ __global__ __launch_bounds__(256) void decode_qt_prepass_kernel(Params p, int ro
   const int lane = threadIdx.x & 63;
   const int cb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // rho block of this wave
   const int ln = lane & 15, lg = lane >> 4;
+  // (the parameter block in one round trip; row_tiles is 1 or 2: no division)
+  asm volatile("" ::"s"(p.q), "s"(p.b_k), "s"(p.query_adapter), "s"(p.qt_ws));
+  asm volatile("" ::"s"(p.n_q_heads), "s"(p.n_kv_heads), "s"(p.group), "s"(p.rank), "s"(p.group_pad), "s"(p.n_queries),
+               "s"(p.n_new), "s"(p.n_adapters), "s"(p.adapter_index), "s"(row_tiles));
   const int h = blockIdx.x, si = blockIdx.z;
-  const int rg = blockIdx.y / row_tiles, rt = blockIdx.y - rg * row_tiles;
+  const int by = blockIdx.y;
+  const int rg = row_tiles == 2 ? by >> 1 : by, rt = row_tiles == 2 ? by & 1 : 0;
   const int n_q = CAUSAL ? p.n_new : p.n_queries;
   const int GP = p.group_pad, G = p.group, r = p.rank;
   const int gps = __builtin_ctz(GP);
