@@ -510,29 +510,33 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(Params p) {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void merge_wave_kernel(Params p) {
   constexpr int CPL = D / 64;  // columns per lane: c = CPL * lane + k
+  // (as in merge_rows_kernel: the parameter block in one round trip, a grid (kv head, group of four q
+  // heads, query) without divisions, the adapter id requested by hand ahead of the vector loads, and
+  // unconditional loads from clamped indices)
+  asm volatile("" ::"s"(p.part_adapter), "s"(p.part_ml), "s"(p.part_o), "s"(p.part_lr), "s"(p.b_v), "s"(p.out));
+  asm volatile("" ::"s"(p.n_q_heads), "s"(p.n_kv_heads), "s"(p.group), "s"(p.head_dim), "s"(p.rank), "s"(p.n_splits),
+               "s"(p.n_adapters));
   const int Hq = p.n_q_heads, r = p.rank, G = p.group;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int GC = (G + 3) >> 2;
-  const int h = blockIdx.x % p.n_kv_heads;
-  const int rest = blockIdx.x / p.n_kv_heads;
-  const int gc = rest % GC, tok = rest / GC;
-  const int gq = gc * 4 + wave;
+  const int h = blockIdx.x;
+  const int gq = static_cast<int>(blockIdx.y) * 4 + wave;
   if (gq >= G) return;
-  const int row = tok * Hq + h * G + gq;
+  const int row = static_cast<int>(blockIdx.z) * Hq + h * G + gq;
   const int ns = p.n_splits;
   const int64_t slot0 = static_cast<int64_t>(row) * ns;
-  const int a = __builtin_amdgcn_readfirstlane(min(max(p.part_adapter[row], 0), p.n_adapters - 1));
+  int a_raw;
+  asm volatile("s_load_dword %0, %1, 0x0" : "=s"(a_raw) : "s"(p.part_adapter + row));
 
-  const float2 st = lane < ns ? reinterpret_cast<const float2*>(p.part_ml)[slot0 + lane] : make_float2(0.f, 0.f);
+  const float2 st_raw = reinterpret_cast<const float2*>(p.part_ml)[slot0 + min(lane, ns - 1)];
+  const float2 st = lane < ns ? st_raw : make_float2(0.f, 0.f);
   const bool live = st.y > 0.f;  // a share without a visible key left a zero row sum; its rows were never written
   const float big = wave_max(live ? st.x : -INFINITY);
   const float w = live ? expf(st.x - big) : 0.f;
   const float ell = wave_sum(w * st.y);
 
   const float* po = p.part_o + slot0 * D + CPL * lane;
-  const float* pl = p.part_lr + slot0 * r + lane;
-  const bool col_l = lane < r;
+  const float* pl = p.part_lr + slot0 * r + (lane < r ? lane : 0);
   float o[CPL], olr = 0.f;
 #pragma unroll
   for (int k = 0; k < CPL; ++k) o[k] = 0.f;
@@ -549,7 +553,7 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(Params p) {
       } else {
         x[u][0] = po[static_cast<int64_t>(sidx) * D];
       }
-      y[u] = col_l ? pl[static_cast<int64_t>(sidx) * r] : 0.f;
+      y[u] = pl[static_cast<int64_t>(sidx) * r];  // (lanes beyond the rank read column 0; their sums are never used)
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -562,6 +566,8 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(Params p) {
     }
   }
   // epilogue O += O_lr B_V, sixteen B_V rows requested at a time
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a_raw));
+  const int a = min(max(a_raw, 0), p.n_adapters - 1);
   if (p.b_v != nullptr) {
     const int64_t ld = static_cast<int64_t>(p.n_kv_heads) * D;
     const T* bv = static_cast<const T*>(p.b_v) + static_cast<int64_t>(a) * r * ld + h * D + CPL * lane;
@@ -593,7 +599,8 @@ static bool launch_merge_wave(const Params& p, int rows, hipStream_t s) {
   // worth it from a few hundred rows on; the statistics need one lane per split
   if (rows < kMergeWaveRows || p.n_splits > 64 || (p.head_dim != 64 && p.head_dim != 128)) return false;
   const int tokens = rows / p.n_q_heads;
-  dim3 grid(static_cast<unsigned>(tokens) * p.n_kv_heads * ((p.group + 3) / 4));
+  if (tokens > 65535) return false;  // (the query index is the grid's z)
+  dim3 grid(p.n_kv_heads, (p.group + 3) / 4, tokens);
   if (p.head_dim == 128) hipLaunchKernelGGL((merge_wave_kernel<T, 128>), grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL((merge_wave_kernel<T, 64>), grid, dim3(256), 0, s, p);
   return true;
@@ -616,7 +623,7 @@ hipError_t launch_generic_partials(const Params& p, bool is_bf16, int rows, hipS
 template <typename T>
 static void launch_merge_t(const Params& p, int rows, hipStream_t s) {
   if (launch_merge_wave<T>(p, rows, s)) return;
-  if (p.rank % 4 == 0 && p.n_splits <= 64 && (p.head_dim == 64 || p.head_dim == 128)) {
+  if (p.rank % 4 == 0 && p.n_splits <= 64 && (p.head_dim == 64 || p.head_dim == 128) && rows / p.n_q_heads <= 65535) {
     // (kv head, q head of the group, query): workgroups go round-robin over the XCDs, so with 8 kv heads
     // the rows of a head are merged on one XCD
     const dim3 grid(p.n_kv_heads, p.group, rows / p.n_q_heads);
