@@ -797,22 +797,50 @@ __global__ __launch_bounds__(256) void append_gemv_kernel(AppendParams p) {
 // workspace, rotates the keys, casts and writes the cache rows.  Grid (new token, chunk of 256
 // items); a thread takes one item, four consecutive features: of V or L as they are, of K together with their
 // rotary partners half a head further on.
-template <int D, bool PAGED>
+template <int D, bool PAGED, int MAXP>  // MAXP: 2, 4, 8 or 16, at least the number of parts
 __global__ __launch_bounds__(256) void append_finish_kernel(AppendParams p) {
+  // A chain of latencies like the other small kernels here: the parameter block in one round trip,
+  // the sequence length requested first and by hand, the loads of ALL parts issued at once (from
+  // clamped part indices: a part beyond the count is fetched again and not added), and the rotation
+  // rates of the pairs worked out while they are in flight.
+  asm volatile("" ::"s"(p.split_ws), "s"(p.seq_lens), "s"(p.k_base), "s"(p.v_base), "s"(p.l), "s"(p.block_table));
+  asm volatile("" ::"s"(p.n_kv_heads), "s"(p.rank), "s"(p.n_new), "s"(p.seq_index), "s"(p.max_seq_len), "s"(p.k_splits),
+               "s"(p.rope_theta), "s"(p.kv_token_stride), "s"(p.kv_head_stride), "s"(p.l_row_stride));
+  int len_raw;
+  asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_lens + p.seq_index));
   const int tid = threadIdx.x;
   const int tok = blockIdx.x;
   const int HD = p.n_kv_heads * D;
   const int n_feat = 2 * HD + p.rank;
   const int k_items = HD / 8, v_items = HD / 4, l_items = p.rank / 4;
-  const int it = blockIdx.y * 256 + tid;
-  // rotation rates of the pairs, for the workgroups that hold key items
+  const int it_raw = blockIdx.y * 256 + tid;
+  const bool has_item = it_raw < k_items + v_items + l_items;
+  const int it = has_item ? it_raw : 0;  // (threads beyond the items repeat item 0 and store nothing)
+  const int ks = p.k_splits;
+  const float* row = p.split_ws + static_cast<int64_t>(tok) * n_feat;
+  const int64_t part_stride = static_cast<int64_t>(p.n_new) * n_feat;
+  // first feature of the item's four, and of their rotary partners (key items only)
+  const bool is_k = it < k_items, is_v = !is_k && it < k_items + v_items;
+  const int head = is_k ? it / (D / 8) : 0, dd = is_k ? (it - head * (D / 8)) * 4 : 0;
+  const int f0 = is_k ? head * D + dd : (is_v ? HD + (it - k_items) * 4 : 2 * HD + (it - k_items - v_items) * 4);
+  const int f1 = is_k ? f0 + D / 2 : f0;
+  float4 x0[MAXP], x1[MAXP];
+#pragma unroll
+  for (int z = 0; z < MAXP; ++z) {
+    const int64_t off = min(z, ks - 1) * part_stride;
+    x0[z] = *reinterpret_cast<const float4*>(row + off + f0);
+    x1[z] = *reinterpret_cast<const float4*>(row + off + f1);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // rotation rates of the pairs, for the workgroups that hold key items (under the loads)
   __shared__ double rope_rate[D / 2];
   if (static_cast<int>(blockIdx.y) * 256 < k_items && p.rope_theta > 0.f) {
     if (tid < D / 2) rope_rate[tid] = rope_rate_rev(tid, D, p.rope_theta);
     __syncthreads();
   }
-  if (it >= k_items + v_items + l_items) return;
-  const int n_t = append_length(PF_CONST_I32(p.seq_lens)[p.seq_index], p.max_seq_len);
+  if (!has_item) return;
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw));
+  const int n_t = append_length(len_raw, p.max_seq_len);
   const int j = n_t - p.n_new + tok;  // cache row of this token, and its position
   if (j < 0) return;
   int64_t kv_off, l_off;  // element offsets of (token j, kv head 0) in K_base / V_base and of row j in L
@@ -824,32 +852,18 @@ __global__ __launch_bounds__(256) void append_finish_kernel(AppendParams p) {
     kv_off = static_cast<int64_t>(j) * p.kv_token_stride;
     l_off = static_cast<int64_t>(j) * p.l_row_stride;
   }
-  const float* row = p.split_ws + static_cast<int64_t>(tok) * n_feat;
-  const int64_t part_stride = static_cast<int64_t>(p.n_new) * n_feat;
-  // the parts in order (the same sum every run); the part count is a power of two >= 2, or any
-  // forced count: pairs of loads in flight, a last single one for odd counts
-  auto sum4 = [&](int f) {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    int z = 0;
-    for (; z + 1 < p.k_splits; z += 2) {
-      const float4 a = *reinterpret_cast<const float4*>(row + z * part_stride + f);
-      const float4 b = *reinterpret_cast<const float4*>(row + (z + 1) * part_stride + f);
-      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
-      v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+  // the parts in order: the same sum every run
+  float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+#pragma unroll
+  for (int z = 0; z < MAXP; ++z)
+    if (z < ks) {
+      lo.x += x0[z].x; lo.y += x0[z].y; lo.z += x0[z].z; lo.w += x0[z].w;
+      hi.x += x1[z].x; hi.y += x1[z].y; hi.z += x1[z].z; hi.w += x1[z].w;
     }
-    if (z < p.k_splits) {
-      const float4 a = *reinterpret_cast<const float4*>(row + z * part_stride + f);
-      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
-    }
-    return v;
-  };
   auto store4 = [&](bf16_t* dst, float4 v) {
     *reinterpret_cast<uint2*>(dst) = make_uint2(pf_pack2(v.x, v.y), pf_pack2(v.z, v.w));
   };
-  if (it < k_items) {
-    // features head*D + dd .. dd+3 (dd < D/2) and their partners at + D/2
-    const int head = it / (D / 8), dd = (it - head * (D / 8)) * 4;
-    float4 lo = sum4(head * D + dd), hi = sum4(head * D + D / 2 + dd);
+  if (is_k) {
     if (p.rope_theta > 0.f) {
       float l4[4] = {lo.x, lo.y, lo.z, lo.w}, h4[4] = {hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
@@ -866,12 +880,11 @@ __global__ __launch_bounds__(256) void append_finish_kernel(AppendParams p) {
     bf16_t* dst = static_cast<bf16_t*>(p.k_base) + kv_off + static_cast<int64_t>(head) * p.kv_head_stride + dd;
     store4(dst, lo);
     store4(dst + D / 2, hi);
-  } else if (it < k_items + v_items) {
-    const int f = (it - k_items) * 4, head = f / D, dd = f - head * D;
-    store4(static_cast<bf16_t*>(p.v_base) + kv_off + static_cast<int64_t>(head) * p.kv_head_stride + dd, sum4(HD + f));
+  } else if (is_v) {
+    const int f = f0 - HD, vh = f / D, vd = f - vh * D;
+    store4(static_cast<bf16_t*>(p.v_base) + kv_off + static_cast<int64_t>(vh) * p.kv_head_stride + vd, lo);
   } else {
-    const int f = (it - k_items - v_items) * 4;
-    store4(static_cast<bf16_t*>(p.l) + l_off + f, sum4(2 * HD + f));
+    store4(static_cast<bf16_t*>(p.l) + l_off + (f0 - 2 * HD), lo);
   }
 }
 
@@ -904,7 +917,11 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s) {
     if (bt == 64) hipLaunchKernelGGL((append_kernel<DD, PG, 4, 64, true>), grid, dim3(256), 0, s, p);                   \
     else hipLaunchKernelGGL((append_kernel<DD, PG, 4, 128, true>), grid, dim3(256), 0, s, p);                           \
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;                                                   \
-    hipLaunchKernelGGL((append_finish_kernel<DD, PG>), dim3(p.n_new, (hd / 8 + hd / 4 + p.rank / 4 + 255) / 256), dim3(256), 0, s, p);                               \
+    const dim3 fgrid(p.n_new, (hd / 8 + hd / 4 + p.rank / 4 + 255) / 256);                                              \
+    if (p.k_splits <= 2) hipLaunchKernelGGL((append_finish_kernel<DD, PG, 2>), fgrid, dim3(256), 0, s, p);              \
+    else if (p.k_splits <= 4) hipLaunchKernelGGL((append_finish_kernel<DD, PG, 4>), fgrid, dim3(256), 0, s, p);         \
+    else if (p.k_splits <= 8) hipLaunchKernelGGL((append_finish_kernel<DD, PG, 8>), fgrid, dim3(256), 0, s, p);         \
+    else hipLaunchKernelGGL((append_finish_kernel<DD, PG, 16>), fgrid, dim3(256), 0, s, p);                             \
   } while (0)
     if (p.head_dim == 128) {
       if (paged) LRA_APPEND_SPLIT(128, true);
