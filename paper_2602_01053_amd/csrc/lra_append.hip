@@ -366,13 +366,6 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
   const int fbase = lr_tile ? 0 : 4 * wr;
   const int tbase = lr_tile ? 2 * wave : 4 * wc;
 
-  pf_f32x16 acc[4][4];  // [feature block][token block]
-#pragma unroll
-  for (int a = 0; a < 4; ++a)
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
   // One step.  A wave issues instructions in order, and a wave-wide request occupies the
   // memory pipe of the compute unit for some sixteen cycles (all four waves share it): sixteen
@@ -380,10 +373,10 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
   // to take them, and the two times add up.  So the requests for the next step go out two at a
   // time between the groups of four MFMAs of the first half of the step, next to the LDS reads of the next k-slice
   // (registers double-buffered); sched_barrier keeps the compiler from regrouping them.
-  auto k_step = [&](int step, auto st_c, auto lr_c, auto more_c) __attribute__((always_inline)) {
+  auto k_step = [&](auto& acc, int step, auto st_c, auto lr_c, auto more_c) __attribute__((always_inline)) {
     constexpr int ST = decltype(st_c)::value;
     constexpr bool LR = decltype(lr_c)::value;
-    constexpr bool MORE = decltype(more_c)::value;  // another step follows: request its tiles
+    const bool MORE = more_c;                       // another step follows: request its tiles (uniform)
     constexpr int NA = LR ? 2 : 4, NB = LR ? 2 : 4;
     constexpr int KS = BK / 16;
     constexpr int GROUPS = KS * NA;          // groups of NB MFMAs in a step
@@ -429,29 +422,29 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto k_loop = [&](auto lr_c) __attribute__((always_inline)) {
-    int step = 0;
-    for (; step + 2 < n_steps; step += 2) {
-      k_step(step, std::integral_constant<int, 0>{}, lr_c, std::true_type{});
-      k_step(step + 1, std::integral_constant<int, 1>{}, lr_c, std::true_type{});
+  auto k_loop = [&](auto& acc, auto lr_c) __attribute__((always_inline)) {
+    constexpr int N = decltype(lr_c)::value ? 2 : 4;
+#pragma unroll
+    for (int a = 0; a < N; ++a)
+#pragma unroll
+      for (int b = 0; b < N; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    // (one loop body for every step: peeled first or last steps make the compiler move the sixteen accumulator
+    // tuples between the copies of the body, through scratch memory)
+    for (int step = 0; step < n_steps; step += 2) {
+      k_step(acc, step, std::integral_constant<int, 0>{}, lr_c, step + 1 < n_steps);
+      if (step + 1 < n_steps) k_step(acc, step + 1, std::integral_constant<int, 1>{}, lr_c, step + 2 < n_steps);
     }
-    if (step + 1 < n_steps) {
-      k_step(step, std::integral_constant<int, 0>{}, lr_c, std::true_type{});
-      k_step(step + 1, std::integral_constant<int, 1>{}, lr_c, std::false_type{});
-    } else {
-      k_step(step, std::integral_constant<int, 0>{}, lr_c, std::false_type{});
-    }
+    pf_wait_vm0();
   };
-  if (lr_tile) k_loop(std::true_type{});
-  else k_loop(std::false_type{});
-  pf_wait_vm0();
 
   // epilogue.  acc[a][b], register i, lane (l32, g2): feature 32 (fbase + a) + 8 (i/4) + 4 g2 + i%4
   // of the tile, token 32 (tbase + b) + l32 of the tile.
   bf16_t* kcache = static_cast<bf16_t*>(kind == 0 ? p.k_base : p.v_base);
-  auto store_block = [&](auto b_c) __attribute__((always_inline)) {
+  auto store_block = [&](auto& acc, auto lr_c, auto b_c) __attribute__((always_inline)) {
     constexpr int b = decltype(b_c)::value;
-    if (b >= 2 && lr_tile) return;
+    constexpr bool LR = decltype(lr_c)::value;
     const int tok = tok0 + 32 * (tbase + b) + l32;
     const int j = pos0 + tok;
     if (tok >= n_new || j < 0) return;
@@ -463,7 +456,7 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
     } else {
       row_off = kind == 2 ? static_cast<int64_t>(j) * p.l_row_stride : static_cast<int64_t>(j) * p.kv_token_stride;
     }
-    if (kind == 2) {
+    if constexpr (LR) {
       bf16_t* lrow = static_cast<bf16_t*>(p.l) + row_off;
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -474,8 +467,7 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
             *reinterpret_cast<uint2*>(lrow + f) =
                 make_uint2(pf_pack2(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]), pf_pack2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]));
         }
-      return;
-    }
+    } else {
     if (kind == 0 && p.rope_theta > 0.f) {
       // rotates the pair of blocks (lo, hi); block_lo = position of lo among the wave's four
       auto rotate = [&](pf_f32x16& lo_v, pf_f32x16& hi_v, int block_lo) __attribute__((always_inline)) {
@@ -508,11 +500,22 @@ __global__ __launch_bounds__(256, 1) void append_wide_kernel(AppendParams p) {
               make_uint2(pf_pack2(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]), pf_pack2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]));
         }
       }
+    }
   };
-  store_block(std::integral_constant<int, 0>{});
-  store_block(std::integral_constant<int, 1>{});
-  store_block(std::integral_constant<int, 2>{});
-  store_block(std::integral_constant<int, 3>{});
+  // (the two kinds of tile keep accumulators of their own: sixteen 16-register tuples leave no room for a copy)
+  if (lr_tile) {
+    pf_f32x16 acc[2][2];  // [feature block][token block]
+    k_loop(acc, std::true_type{});
+    store_block(acc, std::true_type{}, std::integral_constant<int, 0>{});
+    store_block(acc, std::true_type{}, std::integral_constant<int, 1>{});
+  } else {
+    pf_f32x16 acc[4][4];
+    k_loop(acc, std::false_type{});
+    store_block(acc, std::false_type{}, std::integral_constant<int, 0>{});
+    store_block(acc, std::false_type{}, std::integral_constant<int, 1>{});
+    store_block(acc, std::false_type{}, std::integral_constant<int, 2>{});
+    store_block(acc, std::false_type{}, std::integral_constant<int, 3>{});
+  }
 }
 
 // ---------------------------------------------------------------------------------------
