@@ -399,8 +399,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     // finite from the first tile on (key 0 is visible to every row) unless the share starts later
     const float nm = (SPLIT && m_run == -INFINITY) ? 0.f : -m_run;
     pf_bf16x8 pb[2][2];       // [kt][16-key k-step]
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    auto exp_half = [&](int kt) __attribute__((always_inline)) {
       float e[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -411,7 +410,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
       for (int h2 = 0; h2 < 2; ++h2)
         pb[kt][h2] = pf_as_bf16x8(make_uint4(pf_pack2(e[8 * h2 + 0], e[8 * h2 + 1]), pf_pack2(e[8 * h2 + 2], e[8 * h2 + 3]),
                                              pf_pack2(e[8 * h2 + 4], e[8 * h2 + 5]), pf_pack2(e[8 * h2 + 6], e[8 * h2 + 7])));
-    }
+    };
+    // The exponentials of the second 32-key half run under the products of the first: a matrix instruction
+    // occupies its pipe for 32 cycles, and the wave is free to issue vector work meanwhile.
+    exp_half(0);
+    __builtin_amdgcn_sched_barrier(0);
+    exp_half(1);
     // O^T += V^T P^T ; Olr^T += L^T P^T, one 16-key k-step at a time.
     // k-step (kt, h2), element e <-> key 32kt + 16h2 + 8(e/4) + 4g2 + e%4.
 #pragma unroll
@@ -441,7 +445,14 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     // the transposed reads (two per operand) run kReadAheadPV operands ahead
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * kReadAheadPV, 0);
 #pragma unroll
-    for (int i = 0; i < 4 * (DB + RB); ++i) {
+    for (int i = 0; i < 2 * (DB + RB); ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, ONES_ROW ? 3 : 5, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * (DB + RB); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
     }
