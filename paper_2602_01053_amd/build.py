@@ -2,12 +2,15 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblra_attn.so")
+# what the compiler reports per kernel (registers, scratch, LDS, occupancy), written by every build
+RESOURCES_PATH = os.path.join(PKG_DIR, "kernel_resources.json")
 
 SOURCES = ["lra_plan.cpp", "lra_api.hip", "lra_generic.hip", "lra_decode_mfma.hip", "lra_decode_stream.hip", "lra_prefill_mfma.hip", "lra_append.hip", "lra_probe.hip"]
 
@@ -19,6 +22,8 @@ HIPCC_FLAGS = [
     # the LDS transfers set M0 inside their assembly statement and say so in the clobber list
     "-Wno-inline-asm",
 ]
+# (device pass only) one remark block per kernel with its register, scratch and LDS use
+RESOURCE_REMARKS = "-Rpass-analysis=kernel-resource-usage"
 
 
 def source_fingerprint() -> str:
@@ -38,16 +43,44 @@ def source_fingerprint() -> str:
     return h.hexdigest()[:16]
 
 
+def _parse_resource_remarks(stderr: str) -> dict:
+    """{mangled kernel name: {"VGPRs": .., "AGPRs": .., "ScratchSize [bytes/lane]": .., ...}} from the
+    compiler's kernel-resource-usage remarks."""
+    out, cur = {}, None
+    for ln in stderr.splitlines():
+        if "[-Rpass-analysis=kernel-resource-usage]" not in ln:
+            continue
+        m = re.search(r"remark:\s+Function Name: (\S+)", ln)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([^:]+): (\S+) \[-Rpass", ln)
+        if m and cur is not None:
+            v = m.group(2)
+            cur[m.group(1).strip()] = int(v) if v.isdigit() else v
+    return out
+
+
 def _run(cmd, verbose):
+    """Runs one compiler command; returns the kernel resource table its remarks hold (empty for host code)."""
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "packed-fp32-ops"
-    err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
+    remarks, rest, skip = [], [], 0
+    for ln in res.stderr.splitlines():
+        if "[-Rpass-analysis=kernel-resource-usage]" in ln:
+            remarks.append(ln)
+            skip = 2 if "Function Name" in ln else 0  # (the first remark of a kernel is followed by its source line and a caret)
+        elif skip > 0 and re.match(r"^\s+(\d+ \||\|)", ln):
+            skip -= 1
+        elif "packed-fp32-ops" not in ln:
+            rest.append(ln)
+    err = "\n".join(rest)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed ({res.returncode}): {' '.join(cmd)}\n{err}")
     if verbose and err.strip():
         print(err)
+    return _parse_resource_remarks("\n".join(remarks))
 
 
 def build_library(verbose: bool = False) -> str:
@@ -66,10 +99,17 @@ def build_library(verbose: bool = False) -> str:
         if src.endswith(".cpp"):   # host-only C++ (launch planning): no device pass
             jobs.append(([hipcc, "-O2", "-std=c++17", "-fPIC", *inc, "-c", path, "-o", obj], obj))
         else:
-            jobs.append(([hipcc, *HIPCC_FLAGS, *inc, "-c", path, "-o", obj], obj))
+            jobs.append(([hipcc, *HIPCC_FLAGS, RESOURCE_REMARKS, *inc, "-c", path, "-o", obj], obj))
     with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1)) as pool:
-        list(pool.map(lambda j: _run(j[0], verbose), jobs))
+        tables = list(pool.map(lambda j: _run(j[0], verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[o for _, o in jobs], "-o", LIB_PATH], verbose)
+    import json
+    resources = {}
+    for (cmd, _), table in zip(jobs, tables):
+        for name, row in table.items():
+            resources[name] = dict(row, source=os.path.basename(cmd[-3]))
+    with open(RESOURCES_PATH, "w") as f:
+        json.dump({"source_fingerprint": source_fingerprint(), "kernels": resources}, f, indent=0, sort_keys=True)
     return LIB_PATH
 
 
