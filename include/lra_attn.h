@@ -95,7 +95,9 @@ typedef struct {
                          kernels (decode and prefills of a few tokens: the split-KV kernel
                          rotates L B_K per key tile in registers, once for every agent of the
                          tile; other prefills complete each key tile in LDS), everything else
-                         on the vector-ALU kernels. */
+                         on the vector-ALU kernels.  Those other prefills hold the completed
+                         keys as fp16 (a second rounding to bf16 would cost more accuracy than
+                         the rest of the call): key magnitudes must stay below 65504 there. */
 } lra_shape;
 
 /*

@@ -228,6 +228,7 @@ lra_status lra_attn_prefill(const lra_shape* shape, const lra_cache* cache, cons
       p.k_base = kc;
       p.b_k = nullptr;
       p.key_rope_theta = 0.f;
+      p.keys_f16 = 1;
     }
     if (launch_prefill_mfma(p, s) != hipSuccess) return LRA_ERR_HIP;
     if (pl.n_splits > 1 && !tune.main_kernel_only && launch_merge(p, bf16, pl.rows, s) != hipSuccess)

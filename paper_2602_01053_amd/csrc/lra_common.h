@@ -46,6 +46,7 @@ struct Params {
   float scale;
   float key_rope_theta;  // > 0: the key-side adapter contribution is rotated by its token's position
   int32_t share_major;       // decode_stream_kernel: workgroup index laid out so that all kv heads of a key share run on one XCD
+  int32_t keys_f16;          // prefill_mfma_kernel: k_base holds completed keys K_base + RoPE(L B_K) as fp16 (left by the key pre-pass)
 #ifdef LRA_TIMING
   unsigned long long* timing;  // instrumented test build only: per-wave phase stamps
 #endif

@@ -38,9 +38,16 @@ namespace lra {
 // pairs, so both halves of a pair sit in the same lane and register), rotated, and added to
 // the K_base rows of the tile (8-byte read-modify-writes in bf16).  One more barrier per
 // tile; the score loop is the value-only one.
-template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false>
+template <int D, int RP, bool PAGED, bool HAS_BK, bool SPLIT, bool ROPE_K = false, bool KC16 = false>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   static_assert(!(ROPE_K && HAS_BK), "the rotary key side replaces the Qt term");
+  // Completed keys K_base + RoPE(L B_K) are held as fp16, whether the key pre-pass left them in the workspace
+  // (KC16) or this kernel completes the tiles in LDS (ROPE_K): rounding the sum to bf16 a second time costs
+  // 2.5e-3 to 4e-3 of relative error in the output on its own, fp16 (three more bits) a quarter of that.
+  // The scores are then an fp16 product, with Q converted once in the prologue (exact for a bf16 Q of
+  // ordinary magnitudes); V, L and the probabilities stay bf16.
+  constexpr bool KF16 = ROPE_K || KC16;
+  static_assert(!(KC16 && (HAS_BK || ROPE_K || PAGED)), "pre-pass keys: contiguous cache, nothing left to add");
   constexpr int BM = 128, BN = 64;
   constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
   constexpr int RKS = RP / 16; // k-steps over the padded rank
@@ -167,6 +174,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     const bf16_t* qrow = static_cast<const bf16_t*>(p.q) + (static_cast<int64_t>(grow_c) * Hq + head) * D + g2 * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qb[ks] = pf_as_bf16x8(*reinterpret_cast<const uint4*>(qrow + ks * 16));
+  }
+  pf_f16x8 qh[KF16 ? KS : 1];  // the same operands as fp16, for scores against fp16 keys
+  if constexpr (KF16) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qh[ks] = pf_bf16x8_to_f16x8(qb[ks]);
   }
   // Qt^T[rho][row] = B_K[rho][:] . Q[row][:]: C layout lane (row l32; reg i <-> rho = 32b + 8(i/4) + 4g2 + i%4).
   // As B operand of the rank k-steps of S^T, k-step ks' takes registers 8ks'..8ks'+7 of
@@ -314,8 +326,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
             const float* add = sel == 0 ? lo4 : hi4;
             uint2* at = reinterpret_cast<uint2*>(krow + (((4 * (sel == 0 ? fb_lo : fb_hi) + q4) ^ swz) << 4));
             const uint2 old = *at;
-            *at = make_uint2(pf_pack2(__uint_as_float(old.x << 16) + add[0], __uint_as_float(old.x & 0xffff0000u) + add[1]),
-                             pf_pack2(__uint_as_float(old.y << 16) + add[2], __uint_as_float(old.y & 0xffff0000u) + add[3]));
+            *at = make_uint2(pf_pack2_f16(__uint_as_float(old.x << 16) + add[0], __uint_as_float(old.x & 0xffff0000u) + add[1]),
+                             pf_pack2_f16(__uint_as_float(old.y << 16) + add[2], __uint_as_float(old.y & 0xffff0000u) + add[3]));
           }
         }
       }
@@ -339,9 +351,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
-        const pf_bf16x8 a = pf_as_bf16x8(
-            *reinterpret_cast<const uint4*>(ks_l + (k_pre ^ ((2 * ks + g2) << 4)) + kt * 32 * D * 2));
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[ks], s[kt], 0, 0, 0);
+        const uint4 a4 = *reinterpret_cast<const uint4*>(ks_l + (k_pre ^ ((2 * ks + g2) << 4)) + kt * 32 * D * 2);
+        if constexpr (KF16)
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(pf_f16x8, a4), qh[ks], s[kt], 0, 0, 0);
+        else
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf_as_bf16x8(a4), qb[ks], s[kt], 0, 0, 0);
       }
     if (HAS_BK) {
 #pragma unroll
@@ -551,6 +565,11 @@ static hipError_t launch_pf2(const Params& p, dim3 grid, hipStream_t s) {
     else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, SPLIT, true>), grid, dim3(256), 0, s, p);
     return hipGetLastError();
   }
+  if (p.keys_f16) {  // (set by the host only for a contiguous cache whose keys the pre-pass has completed)
+    if (paged || has_bk) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, SPLIT, false, true>), grid, dim3(256), 0, s, p);
+    return hipGetLastError();
+  }
   if (paged && has_bk)
     hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, true, SPLIT>), grid, dim3(256), 0, s, p);
   else if (paged)
@@ -649,8 +668,9 @@ __global__ __launch_bounds__(256) void complete_rope_keys_kernel(Params p, unsig
   for (int i = 0; i < PPL; ++i) {
     float sn, cs;
     rope_sincos(rate[PPL * g + i], j, sn, cs);
-    olo.v[i] = f32_to_bf16(__uint_as_float(static_cast<uint32_t>(klo.v[i]) << 16) + (lo[i] * cs - hi[i] * sn));
-    ohi.v[i] = f32_to_bf16(__uint_as_float(static_cast<uint32_t>(khi.v[i]) << 16) + (hi[i] * cs + lo[i] * sn));
+    // (as fp16: see prefill_mfma_kernel)
+    olo.v[i] = __builtin_bit_cast(unsigned short, static_cast<_Float16>(__uint_as_float(static_cast<uint32_t>(klo.v[i]) << 16) + (lo[i] * cs - hi[i] * sn)));
+    ohi.v[i] = __builtin_bit_cast(unsigned short, static_cast<_Float16>(__uint_as_float(static_cast<uint32_t>(khi.v[i]) << 16) + (hi[i] * cs + lo[i] * sn)));
   }
   *reinterpret_cast<Piece*>(kdst) = olo;
   *reinterpret_cast<Piece*>(kdst + D / 2) = ohi;

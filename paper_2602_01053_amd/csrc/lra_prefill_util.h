@@ -32,6 +32,24 @@ __device__ __forceinline__ pf_bf16x8 pf_join(pf_s16x4 lo, pf_s16x4 hi) {
   return __builtin_bit_cast(pf_bf16x8, v);
 }
 
+typedef _Float16 pf_f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 pf_f16x2 __attribute__((ext_vector_type(2)));
+// two floats rounded to fp16 (nearest even), packed
+__device__ __forceinline__ uint32_t pf_pack2_f16(float a, float b) {
+  const pf_f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, pf_f16x2));
+}
+// eight bf16 values as fp16: exact for magnitudes from 2^-14 (6.1e-5) to 65504; smaller ones lose
+// bits they barely had (below 6e-8 they become zero), larger ones become infinite
+__device__ __forceinline__ pf_f16x8 pf_bf16x8_to_f16x8(pf_bf16x8 v) {
+  const uint4 u = __builtin_bit_cast(uint4, v);
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+  uint32_t o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = pf_pack2_f16(__uint_as_float(w[i] << 16), __uint_as_float(w[i] & 0xffff0000u));
+  return __builtin_bit_cast(pf_f16x8, make_uint4(o[0], o[1], o[2], o[3]));
+}
+
 __device__ __forceinline__ uint32_t pf_pack2(float a, float b) {  // one v_cvt_pk_bf16_f32
   const pf_f32x2 v = {a, b};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, pf_bf16x2));

@@ -54,9 +54,9 @@ SCRATCH_ALLOWED = [
     # one accumulator tuple parked between the loop and the store (none inside the loop)
     (r"append_wide_kernel", 136),
     # rotary prefill that completes key tiles itself and writes partial states: loop-invariant addresses
-    (r"prefill_mfma_kernelILi\d+ELi\d+ELb[01]ELb0ELb1ELb1E", 176),
+    (r"prefill_mfma_kernelILi\d+ELi\d+ELb[01]ELb0ELb1ELb1ELb0E", 192),
     # rank 64 with a Qt term on paged caches: a few registers over 256
-    (r"prefill_mfma_kernelILi128ELi64ELb1ELb1ELb[01]ELb0E", 16),
+    (r"prefill_mfma_kernelILi128ELi64ELb1ELb1ELb[01]ELb0ELb0E", 16),
     # rotary decode at d = 128, ranks up to 16 and 33..64: a few registers over the file (B_K^T operands of four agent
     # slots stay in registers); up to nine values spilled, five reloads per 32-key step
     (r"decode_mfma_kernelILi128ELi1ELi(32|64)ELb[01]ELb1ELb0ELi(16|64)E", 144),
@@ -85,7 +85,7 @@ def test_headline_kernels(table):
                 seen.add("cfg2")
         if "merge_rows_kernel" in name or "merge_wave_kernel" in name:
             assert row[SCRATCH] == 0 and row["VGPRs"] <= 128, (name, row)
-        if "prefill_mfma_kernel" in name and a == [128, 16, False, True, False, False]:  # config 3
+        if "prefill_mfma_kernel" in name and a == [128, 16, False, True, False, False, False]:  # config 3
             assert row[SCRATCH] == 0 and row[OCC] >= 2 and row[LDS] <= 80 * 1024, (name, row)
             seen.add("cfg3")
         if re.search(r"append_kernelILi128ELb0E", name) or "append_gemv_kernel" in name or "append_finish_kernel" in name:
