@@ -9,8 +9,8 @@ import numpy as np
 import pytest
 import torch
 
+import oracle
 import paper_2602_01053_amd as lra
-from oracle import lra_oracle as oracle
 from paper_2602_01053_amd import workloads as W
 from tests.harness import MAX_ABS_TOL, REL_L2_TOL, DeviceWorkload, _f64, errors
 
@@ -122,3 +122,99 @@ def test_rotary_prefills_on_both_key_paths(block):
                               head_dim=d, rank=r, n=n, n_new=n_new, d_model=None, b_std=bstd)
         tag = f"case {case} hq={hq} hkv={hkv} d={d} r={r} theta={theta:g} prepass={prepass} b_std={bstd} n={n} n_new={n_new}"
         _run_and_check(w, tag, theta, prepass=prepass)
+
+
+def _check(got, ref, tag):
+    rel, mx = errors(got, ref)
+    print(f"{tag}: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert np.isfinite(got).all(), tag
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL, (tag, rel, mx)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_append_and_base_shared_calls(block):
+    """lra_cache_append on a contiguous cache (with and without the workspace that lets it divide d_model; guard bands
+    around it; older rows untouched) and BaseShared decode / prefill (one low-rank cache per adapter, both storage
+    orders, agents mapped to adapters out of order), sizes and options drawn at random."""
+    f = lambda t: t.to(torch.float64).cpu().numpy()
+    for case in range(block * BLOCK, (block + 1) * BLOCK):
+        rnd = random.Random(50_000 + case)
+        kind = rnd.choice(["append", "append", "bs_dec", "bs_pre"])
+        hkv, d, r = rnd.choice([1, 2, 3, 4, 8]), rnd.choice([64, 128]), rnd.choice([8, 16, 24, 32, 40, 64])
+        gen = torch.Generator().manual_seed(case)
+        if kind == "append":
+            d_model = 64 * rnd.choice([1, 2, 3, 4, 8, 11, 16, 17, 32, 64])
+            n_new = rnd.choice([1, 2, 3, 4, 5, 8, 16, 17, 32, 33, 64, 100, 128, 129, 256, 300, 512, rnd.randint(1, 700)])
+            n = n_new + rnd.choice([0, 1, 17, rnd.randint(0, 70000)])
+            theta, with_ws = rnd.choice([0.0, 10000.0, 500000.0]), rnd.random() < 0.6
+            tag = f"case {case} append n={n} n_new={n_new} d_model={d_model} hkv={hkv} d={d} r={r} theta={theta:g} workspace={with_ws}"
+            x = torch.randn(n_new, d_model, generator=gen).to(torch.bfloat16)
+            w = (torch.randn(2 * hkv * d + r, d_model, generator=gen) / d_model ** 0.5).to(torch.bfloat16)
+            kb = torch.full((n, hkv, d), 7.0, dtype=torch.bfloat16, device=DEV)
+            vb, l = torch.full_like(kb, 7.0), torch.full((n, r), 7.0, dtype=torch.bfloat16, device=DEV)
+            lens = torch.tensor([n], dtype=torch.int32, device=DEV)
+            shape = lra.make_shape(torch.empty(1, hkv, d, dtype=torch.bfloat16, device=DEV), hkv, r, 0.0)
+            cache = lra.make_cache(kb, vb, l, lens, n, None)
+            xd, wd = x.to(DEV), w.to(DEV)
+            if with_ws:
+                need = max(lra.lra_append_workspace_bytes(shape, cache, wd, theta, n_new), 256)
+                whole = torch.full((need + 8192,), 0xA5, dtype=torch.uint8, device=DEV)
+                lra.lra_cache_append(shape, cache, wd, theta, xd, 0, workspace=whole[4096:4096 + need])
+                torch.cuda.synchronize()
+                assert bool((whole[:4096] == 0xA5).all()) and bool((whole[-4096:] == 0xA5).all()), tag
+            else:
+                lra.lra_cache_append(shape, cache, wd, theta, xd, 0)
+                torch.cuda.synchronize()
+            kr, vr, lr = oracle.project_new_tokens(f(x), f(w), hkv, d, r, np.arange(n - n_new, n), theta)
+            _check(f(kb)[n - n_new:], kr, tag + " K")
+            _check(f(vb)[n - n_new:], vr, tag + " V")
+            _check(f(l)[n - n_new:], lr, tag + " L")
+            assert all(bool((t[:n - n_new] == 7.0).all()) for t in (kb, vb, l)), tag
+            continue
+        g = rnd.choice([1, 2, 4, 7, 8, 16])
+        hkv = min(hkv, max(1, 32 // g))
+        hq = hkv * g
+        agents, n = rnd.randint(1, 9), rnd.choice([1, 33, 257, 1000, rnd.randint(1, 4000)])
+        storage, variant = rnd.choice(["token_major", "adapter_major"]), rnd.choice([0, 0, 1, 2])
+        k = torch.randn(n, hkv, d, generator=gen).to(torch.bfloat16)
+        v = torch.randn(n, hkv, d, generator=gen).to(torch.bfloat16)
+        ls = [torch.randn(n, r, generator=gen).to(torch.bfloat16) for _ in range(agents)]
+        bk = (0.05 * torch.randn(agents, r, hkv * d, generator=gen)).to(torch.bfloat16)
+        bv = (0.05 * torch.randn(agents, r, hkv * d, generator=gen)).to(torch.bfloat16)
+        st = torch.stack(ls)  # [adapter][n][r]
+        l_dev = st.permute(1, 0, 2).contiguous().to(DEV).permute(1, 0, 2) if storage == "token_major" else st.contiguous().to(DEV)
+        kd, vd, bkd, bvd = k.to(DEV), v.to(DEV), bk.to(DEV), bv.to(DEV)
+        lens = torch.tensor([n], dtype=torch.int32, device=DEV)
+        prev = lra.lra_set_kernel_variant(variant)
+        try:
+            if kind == "bs_dec":
+                tag = f"case {case} base_shared decode n={n} agents={agents} hq={hq} hkv={hkv} d={d} r={r} {storage} variant={variant}"
+                q = torch.randn(agents, hq, d, generator=gen).to(torch.bfloat16)
+                qd = q.to(DEV)
+                adapter_of = torch.tensor([(3 * a + 1) % agents for a in range(agents)], dtype=torch.int32)
+                shape = lra.make_shape(qd, hkv, r)
+                cache = lra.make_cache(kd, vd, l_dev, lens, n, None, l_per_adapter=True)
+                out = torch.full_like(qd, float("nan"))
+                ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, agents, agents), 256), dtype=torch.uint8, device=DEV)
+                qa, qs = adapter_of.to(DEV), torch.tensor([0, agents], dtype=torch.int32, device=DEV)
+                lra.lra_attn_decode(shape, cache, bkd, bvd, agents, qd, qa, qs, agents, out, ws)
+                torch.cuda.synchronize()
+                ref = np.concatenate([
+                    oracle.decode(f(q[i:i + 1]), f(k), f(v), f(ls[int(adapter_of[i])]), f(bk), f(bv),
+                                  np.array([int(adapter_of[i])], dtype=np.int32), np.array([0, 1], dtype=np.int32), [n], 1.0 / d ** 0.5)
+                    for i in range(agents)])
+            else:
+                n_new, a = min(n, rnd.choice([1, 7, 32, 33, 130, 300])), rnd.randrange(agents)
+                tag = f"case {case} base_shared prefill n={n} n_new={n_new} adapter={a}/{agents} hq={hq} hkv={hkv} d={d} r={r} {storage} variant={variant}"
+                q = torch.randn(n_new, hq, d, generator=gen).to(torch.bfloat16)
+                qd = q.to(DEV)
+                shape = lra.make_shape(qd, hkv, r)
+                cache = lra.make_cache(kd, vd, l_dev, lens, n, None, l_per_adapter=True)
+                out = torch.full_like(qd, float("nan"))
+                ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, 1, 1, n_new), 256), dtype=torch.uint8, device=DEV)
+                lra.lra_attn_prefill(shape, cache, bkd, bvd, agents, qd, 0, a, out, ws)
+                torch.cuda.synchronize()
+                ref = oracle.prefill(f(q), f(k), f(v), f(ls[a]), f(bk[a]), f(bv[a]), n=n, scale=1.0 / d ** 0.5)
+        finally:
+            lra.lra_set_kernel_variant(prev)
+        _check(out.to(torch.float64).cpu().numpy(), ref, tag)
