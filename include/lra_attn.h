@@ -204,13 +204,16 @@ typedef struct {
  *                      prefill kernel (1..32; more than one ends with the merge kernel);
  *                      0 automatic (two workgroups per CU, at least eight 64-key tiles each)
  *   rope_key_prepass   prefill calls of the tile-walking kernel with the rotary key side
- *                      (key_rope_theta > 0 and a b_k) on a contiguous cache: 0 automatic (the
- *                      completed keys K_base + RoPE(L B_K) of the call's adapter are written once
+ *                      (key_rope_theta > 0 and a b_k): 0 automatic (the completed keys
+ *                      K_base + RoPE(L B_K) of the call's adapter and sequence are written once
  *                      into the workspace by a pre-pass and the call runs on them: the workspace
  *                      then holds a copy of the K_base extent, (max_seq_len - 1) * kv_token_stride
- *                      + (Hkv - 1) * kv_head_stride + head_dim elements; a call whose workspace is
- *                      too small for that but large enough otherwise completes the key tiles
- *                      inside the kernel instead, at a cost in time); negative: never
+ *                      + (Hkv - 1) * kv_head_stride + head_dim elements, or for a paged cache the
+ *                      blocks of one sequence in logical order at the strides of the pool,
+ *                      ((max_seq_len - 1) / 16) * kv_block_stride + (Hkv - 1) * kv_head_stride +
+ *                      15 * kv_token_stride + head_dim elements; up to 4 GB; a call whose
+ *                      workspace is too small for that but large enough otherwise completes the
+ *                      key tiles inside the kernel instead, at a cost in time); negative: never
  *   append_skinny      lra_cache_append calls with at most this many new tokens stream the
  *                      weights instead of tiling; 0 automatic (64), negative: never
  *   append_stages      LDS stages of lra_cache_append's tiled GEMM: 2, 3 or 4; 0 automatic

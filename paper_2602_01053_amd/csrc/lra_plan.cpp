@@ -186,12 +186,18 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     }
     pl.off_qt = pl.bytes;
     pl.bytes_without_kc = pl.bytes;
-    if (rope && c->block_size == 0 && tune.rope_key_prepass) {
+    if (rope && tune.rope_key_prepass) {
       // room for the completed keys of the call's adapter, in the layout of K_base (whether or
-      // not the call has a B_K); caches beyond 4 GB keep completing tiles inside the kernel
-      const int64_t span = (static_cast<int64_t>(c->max_seq_len) - 1) * c->kv_token_stride +
-                           (static_cast<int64_t>(sh->n_kv_heads) - 1) * c->kv_head_stride + sh->head_dim;
-      if (span * 2 <= (int64_t{1} << 32)) {
+      // not the call has a B_K); caches beyond 4 GB keep completing tiles inside the kernel.
+      // Paged caches: the blocks of the call's sequence in logical order, with the strides of the pool.
+      int64_t span = -1;  // elements; -1: no pre-pass
+      if (c->block_size == 0)
+        span = (static_cast<int64_t>(c->max_seq_len) - 1) * c->kv_token_stride +
+               (static_cast<int64_t>(sh->n_kv_heads) - 1) * c->kv_head_stride + sh->head_dim;
+      else if (c->kv_block_stride <= (int64_t{1} << 31))  // (keeps the product below inside int64)
+        span = (static_cast<int64_t>(c->max_seq_len) - 1) / 16 * c->kv_block_stride +
+               (static_cast<int64_t>(sh->n_kv_heads) - 1) * c->kv_head_stride + 15 * c->kv_token_stride + sh->head_dim;
+      if (span >= 0 && span <= (int64_t{1} << 31)) {
         pl.off_kc = pl.bytes;
         pl.kc_bytes = align_up(static_cast<size_t>(span) * 2, 256);
         pl.bytes += pl.kc_bytes;

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   // The scores are then an fp16 product, with Q converted once in the prologue (exact for a bf16 Q of
   // ordinary magnitudes); V, L and the probabilities stay bf16.
   constexpr bool KF16 = ROPE_K || KC16;
-  static_assert(!(KC16 && (HAS_BK || ROPE_K || PAGED)), "pre-pass keys: contiguous cache, nothing left to add");
+  static_assert(!(KC16 && (HAS_BK || ROPE_K)), "pre-pass keys: nothing left to add");
   constexpr int BM = 128, BN = 64;
   constexpr int KS = D / 16;   // k-steps of S^T over the head dimension
   constexpr int RKS = RP / 16; // k-steps over the padded rank
@@ -565,9 +565,10 @@ static hipError_t launch_pf2(const Params& p, dim3 grid, hipStream_t s) {
     else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, SPLIT, true>), grid, dim3(256), 0, s, p);
     return hipGetLastError();
   }
-  if (p.keys_f16) {  // (set by the host only for a contiguous cache whose keys the pre-pass has completed)
-    if (paged || has_bk) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, SPLIT, false, true>), grid, dim3(256), 0, s, p);
+  if (p.keys_f16) {  // (set by the host only where the pre-pass has completed the keys)
+    if (has_bk) return hipErrorInvalidValue;
+    if (paged) hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, true, false, SPLIT, false, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((prefill_mfma_kernel<D, RP, false, false, SPLIT, false, true>), grid, dim3(256), 0, s, p);
     return hipGetLastError();
   }
   if (paged && has_bk)
@@ -615,7 +616,7 @@ hipError_t launch_prefill_mfma(const Params& p, hipStream_t s) {
 // dd = PPL g .. PPL g + PPL - 1, PPL = d/32.  E in fp32, angle = fractional part of position x rate
 // in double precision, as in the producer of the caches.
 // ---------------------------------------------------------------------------------------
-template <int D>
+template <int D, bool PAGED>
 __global__ __launch_bounds__(256) void complete_rope_keys_kernel(Params p, unsigned short* kc) {
   constexpr int PPL = D / 32;              // rotary pairs per lane
   __shared__ __align__(16) unsigned short b_lds[64 * D];  // B_K^a rows of this kv head, [rho][d]
@@ -638,8 +639,12 @@ __global__ __launch_bounds__(256) void complete_rope_keys_kernel(Params p, unsig
   __syncthreads();
   if (j >= n_t) return;
   const int g = tid & 15;
+  // paged: the key's block comes from the sequence's row of the block table; the completed keys are written at
+  // the block's LOGICAL index (the kernel that reads them needs no table for them)
+  const int blk = PAGED ? PF_CONST_I32(p.block_table)[static_cast<int64_t>(p.seq_index) * p.max_blocks_per_seq + (j >> 4)] : 0;
+  const int64_t l_index = PAGED ? static_cast<int64_t>(blk) * 16 + (j & 15) : j;
   const unsigned short* lrow = static_cast<const unsigned short*>(p.l) + static_cast<int64_t>(a) * p.l_adapter_stride +
-                               static_cast<int64_t>(j) * p.l_row_stride;
+                               l_index * p.l_row_stride;
   float lo[PPL], hi[PPL];
 #pragma unroll
   for (int i = 0; i < PPL; ++i) lo[i] = hi[i] = 0.f;
@@ -657,11 +662,13 @@ __global__ __launch_bounds__(256) void complete_rope_keys_kernel(Params p, unsig
       }
     }
   }
-  const int64_t off = static_cast<int64_t>(j) * p.kv_token_stride + static_cast<int64_t>(h) * p.kv_head_stride + PPL * g;
+  const int64_t in_blk = static_cast<int64_t>(PAGED ? (j & 15) : j) * p.kv_token_stride + static_cast<int64_t>(h) * p.kv_head_stride + PPL * g;
+  const int64_t off_src = in_blk + (PAGED ? static_cast<int64_t>(blk) * p.kv_block_stride : 0);
+  const int64_t off_dst = in_blk + (PAGED ? static_cast<int64_t>(j >> 4) * p.kv_block_stride : 0);
   // the lane's PPL consecutive features of either half: one 8-byte (d = 128) or 4-byte (d = 64) piece
   struct alignas(PPL * 2) Piece { unsigned short v[PPL]; };
-  const unsigned short* ksrc = static_cast<const unsigned short*>(p.k_base) + off;
-  unsigned short* kdst = kc + off;
+  const unsigned short* ksrc = static_cast<const unsigned short*>(p.k_base) + off_src;
+  unsigned short* kdst = kc + off_dst;
   const Piece klo = *reinterpret_cast<const Piece*>(ksrc), khi = *reinterpret_cast<const Piece*>(ksrc + D / 2);
   Piece olo, ohi;
 #pragma unroll
@@ -678,8 +685,14 @@ __global__ __launch_bounds__(256) void complete_rope_keys_kernel(Params p, unsig
 
 hipError_t launch_complete_rope_keys(const Params& p, void* kc, hipStream_t s) {
   const dim3 grid((p.max_seq_len + 15) / 16, p.n_kv_heads);
-  if (p.head_dim == 128) hipLaunchKernelGGL((complete_rope_keys_kernel<128>), grid, dim3(256), 0, s, p, static_cast<unsigned short*>(kc));
-  else hipLaunchKernelGGL((complete_rope_keys_kernel<64>), grid, dim3(256), 0, s, p, static_cast<unsigned short*>(kc));
+  unsigned short* dst = static_cast<unsigned short*>(kc);
+  if (p.block_size != 0) {
+    if (p.head_dim == 128) hipLaunchKernelGGL((complete_rope_keys_kernel<128, true>), grid, dim3(256), 0, s, p, dst);
+    else hipLaunchKernelGGL((complete_rope_keys_kernel<64, true>), grid, dim3(256), 0, s, p, dst);
+  } else {
+    if (p.head_dim == 128) hipLaunchKernelGGL((complete_rope_keys_kernel<128, false>), grid, dim3(256), 0, s, p, dst);
+    else hipLaunchKernelGGL((complete_rope_keys_kernel<64, false>), grid, dim3(256), 0, s, p, dst);
+  }
   return hipGetLastError();
 }
 

@@ -208,7 +208,9 @@ struct PfTileLoader {
       const uint32_t bytes = nv > 0 ? static_cast<uint32_t>(nv - 1) * ts2 + D * 2 : 0u;
       const int64_t off = static_cast<int64_t>(blk) * p.kv_block_stride + static_cast<int64_t>(hk) * p.kv_head_stride +
                           static_cast<int64_t>(tok & 15) * p.kv_token_stride;
-      pf_load16_to_lds(pf_rsrc(kb + off, bytes), dst, k_voff, 0);
+      // completed keys left by the pre-pass lie at the block's logical index, with the strides of the pool
+      const int64_t off_k = p.keys_f16 ? off + (static_cast<int64_t>(min(tok >> 4, nb_last)) - blk) * p.kv_block_stride : off;
+      pf_load16_to_lds(pf_rsrc(kb + off_k, bytes), dst, k_voff, 0);
       pf_load16_to_lds(pf_rsrc(vb + off, bytes), dst + K_BYTES, v_voff, 0);
     }
   }

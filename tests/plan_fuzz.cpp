@@ -88,10 +88,14 @@ int main(int argc, char** argv) {
       CHECK(pl.bytes % 256 == 0);
       CHECK(pl.bytes == pl.bytes_without_kc + pl.kc_bytes && pl.off_kc % 256 == 0 && pl.kc_bytes % 256 == 0);
       if (pl.kc_bytes) {  // completed keys of a rotary prefill: a copy of the K_base extent behind everything else
-        CHECK(prefill && pl.mfma && !pl.short_prefill && c.block_size == 0 && sh.key_rope_theta > 0.f);
+        CHECK(prefill && pl.mfma && !pl.short_prefill && sh.key_rope_theta > 0.f);
         CHECK(pl.off_kc >= pl.bytes_without_kc);
-        const int64_t span = (static_cast<int64_t>(c.max_seq_len) - 1) * c.kv_token_stride +
-                             (static_cast<int64_t>(sh.n_kv_heads) - 1) * c.kv_head_stride + sh.head_dim;
+        // contiguous: the extent of K_base; paged: the sequence's blocks in logical order at the strides of the pool
+        const int64_t span = c.block_size == 0
+            ? (static_cast<int64_t>(c.max_seq_len) - 1) * c.kv_token_stride +
+                  (static_cast<int64_t>(sh.n_kv_heads) - 1) * c.kv_head_stride + sh.head_dim
+            : (static_cast<int64_t>(c.max_seq_len) - 1) / 16 * c.kv_block_stride +
+                  (static_cast<int64_t>(sh.n_kv_heads) - 1) * c.kv_head_stride + 15 * c.kv_token_stride + sh.head_dim;
         CHECK(pl.kc_bytes >= static_cast<size_t>(span) * 2 && pl.kc_bytes <= (size_t{1} << 32) + 256);
       }
       if (pl.bytes_without_kc) {

@@ -83,3 +83,44 @@ def test_contiguous_decode_with_prepass_stays_inside_its_buffers():
     assert need > 0
     rel, mx = errors(got, oracle_decode(w))
     assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
+@pytest.mark.parametrize("paged", [False, True], ids=["contiguous", "paged"])
+def test_rotary_prefill_key_prepass_stays_inside_its_workspace(paged):
+    """Rotary key side, tile-walking prefill: the pre-pass writes the completed keys of the call's sequence into the
+    workspace (contiguous: the extent of K_base; paged: the sequence's blocks in logical order, here the longest
+    sequence with a partly filled last block).  Exact-size workspace between guard bands."""
+    import numpy as np
+    import oracle
+    theta, hq, hkv, d, r, n_new = 500000.0, 8, 2, 128, 16, 150
+    gen = torch.Generator().manual_seed(614)
+    q = torch.randn(n_new, hq, d, generator=gen).to(torch.bfloat16)
+    f = lambda t: t.to(torch.float64).numpy()
+    if paged:
+        w = W.make_paged("canary_rot_paged", seed=615, seq_lens=[40, 1003, 333], agents_per_seq=1, n_adapters=2, n_q_heads=hq,
+                         n_kv_heads=hkv, head_dim=d, rank=r, d_model=None, b_std=0.1)
+        seq, n = 1, 1003
+        table = w.block_table.to(DEV)
+        ids = w.block_table[seq].numpy()
+        kb, vb = oracle.gather_paged(f(w.k_base), ids, n), oracle.gather_paged(f(w.v_base), ids, n)
+        lr = oracle.lra_oracle.gather_paged_l(f(w.l), ids, n)
+    else:
+        w = W.make_contiguous("canary_rot", "decode", seed=616, n_agents=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, rank=r,
+                              n=1003, d_model=None, b_std=0.1)
+        seq, n, table = 0, 1003, None
+        kb, vb, lr = f(w.k_base), f(w.v_base), f(w.l)
+    qd, kd, vd, ld, bk, bv = q.to(DEV), w.k_base.to(DEV), w.v_base.to(DEV), w.l.to(DEV), w.b_k.to(DEV), w.b_v.to(DEV)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = lra.make_shape(qd, hkv, r, 0.0, theta)
+    cache = lra.make_cache(kd, vd, ld, lens, max(w.seq_lens), table)
+    need = lra.lra_workspace_bytes(shape, cache, 1, 1, n_new)
+    assert need >= n * hkv * d * 2  # room for the completed keys
+    ws_whole, ws_view, ws_start = _guarded(need)
+    out = torch.full_like(qd, float("nan"))
+    lra.lra_attn_prefill(shape, cache, bk, bv, 2, qd, seq, 1, out, ws_view)
+    torch.cuda.synchronize()
+    assert _margins_intact(ws_whole, ws_start, need), "write outside the workspace"
+    ref = oracle.prefill(f(q), kb, vb, lr, f(w.b_k[1]), f(w.b_v[1]), n=n, scale=1.0 / d ** 0.5, key_rope_theta=theta)
+    rel, mx = errors(out.to(torch.float64).cpu().numpy(), ref)
+    assert np.isfinite(out.float().cpu().numpy()).all()
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL

@@ -235,9 +235,10 @@ def test_prefills_on_paged_caches(block):
         n = lens[seq]
         n_new = min(n, rnd.choice([1, 3, 16, 31, 32, 33, 100, 128, 129, 300]))
         variant, split, a = rnd.choice([0, 0, 0, 1, 2]), rnd.choice([0, 0, 128, 256]), rnd.randrange(3)
+        prepass = rnd.random() < 0.6  # (rotary tile-walking prefills: completed keys from the pre-pass, or tile by tile in the kernel)
         w = W.make_paged("sweep", seed=case, seq_lens=lens, agents_per_seq=1, n_adapters=3, n_q_heads=hq, n_kv_heads=hkv,
                          head_dim=d, rank=r, d_model=None, b_std=0.1 if theta > 0 else 0.05)
-        tag = f"case {case} lens={lens} seq={seq} n_new={n_new} hq={hq} hkv={hkv} d={d} r={r} theta={theta:g} variant={variant} split={split}"
+        tag = f"case {case} lens={lens} seq={seq} n_new={n_new} hq={hq} hkv={hkv} d={d} r={r} theta={theta:g} variant={variant} split={split} prepass={prepass}"
         q = torch.randn(n_new, hq, d, generator=torch.Generator().manual_seed(case + 1)).to(torch.bfloat16)
         qd, kp, vp, lp = q.to(DEV), w.k_base.to(DEV), w.v_base.to(DEV), w.l.to(DEV)
         table, bk, bv = w.block_table.to(DEV), w.b_k.to(DEV), w.b_v.to(DEV)
@@ -245,7 +246,7 @@ def test_prefills_on_paged_caches(block):
         shape = lra.make_shape(qd, hkv, r, 0.0, theta)
         cache = lra.make_cache(kp, vp, lp, lens_d, max(lens), table)
         out = torch.full_like(qd, float("nan"))
-        old = (lra.lra_set_kernel_variant(variant), lra.lra_set_decode_split_keys(split))
+        old = (lra.lra_set_kernel_variant(variant), lra.lra_set_decode_split_keys(split), lra.lra_set_rope_key_prepass(1 if prepass else 0))
         try:
             ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, 1, 1, n_new), 256), dtype=torch.uint8, device=DEV)
             lra.lra_attn_prefill(shape, cache, bk, bv, 3, qd, seq, a, out, ws)
@@ -253,6 +254,7 @@ def test_prefills_on_paged_caches(block):
         finally:
             lra.lra_set_kernel_variant(old[0])
             lra.lra_set_decode_split_keys(old[1])
+            lra.lra_set_rope_key_prepass(old[2])
         ids = w.block_table[seq].numpy()
         ref = oracle.prefill(f(q), oracle.gather_paged(f(w.k_base), ids, n), oracle.gather_paged(f(w.v_base), ids, n),
                              oracle.lra_oracle.gather_paged_l(f(w.l), ids, n), f(w.b_k[a]), f(w.b_v[a]), n=n,
