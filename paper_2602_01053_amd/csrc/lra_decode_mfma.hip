@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
       if (CAUSAL)
         a_slot[rt][si] = (si < 16 / GP && slot < n_q) ? p.adapter_index : -1;
       else
-        a_slot[rt][si] = ((HAS_BK || warm_bv) && si < 16 / GP && slot < n_q)
+        a_slot[rt][si] = ((HAS_BK || warm_bv || (!ROPE && p.l_adapter_stride > 0)) && si < 16 / GP && slot < n_q)
                              ? min(max(CONST_I32(p.query_adapter)[q_begin + slot], 0), p.n_adapters - 1)  // device data: kept inside the table
                              : -1;
     }
@@ -193,9 +193,15 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
 
   const bf16_t* kb = static_cast<const bf16_t*>(p.k_base);
   const bf16_t* vb = static_cast<const bf16_t*>(p.v_base);
-  const bf16_t* lr = static_cast<const bf16_t*>(p.l);
+  // Low-rank rows: dense, or with a pitch of their own; with one low-rank cache per adapter the host gives every
+  // agent a row tile (and this kernel one row tile per workgroup), so the tile's first slot names the cache
+  // (the rotary form is only ever given one dense cache)
+  const int64_t lp = ROPE ? r : p.l_row_stride;
+  const bf16_t* lr = static_cast<const bf16_t*>(p.l) +
+                     (!ROPE && p.l_adapter_stride > 0 ? static_cast<int64_t>(max(a_slot[0][0], 0)) * p.l_adapter_stride : 0);
   const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
   const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
+  const uint32_t lp2 = ROPE ? r2 : static_cast<uint32_t>(lp) * 2u;       // bytes between L rows
 
   // ===================== per-lane constants of the tile traffic =====================
   // The LDS of this chip serves 256 bytes per clock (64 banks): a ds_read_b128 is free of
@@ -220,7 +226,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
     for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
     const int lrow = lane / RCH, lpc = lane % RCH;
     const int lch = lpc ^ ((lrow >> LSW_SHIFT) & (RCH - 1));
-    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * r2 + (lch << 4) : kOob;
+    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * lp2 + (lch << 4) : kOob;
   }
   // LDS -> MFMA operands (byte offsets inside the tile regions).
   // K rows as A operand of S^T: key = 16tt + ln, logical chunk 4ks + lg at chunk ^ swz_k(key):
@@ -258,7 +264,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
     const uint32_t bytes = nk > 0 ? static_cast<uint32_t>(nk - 1) * ts2 + D * 2 : 0u;
     rs_k = make_rsrc_words(kb + base, bytes);
     rs_v = make_rsrc_words(vb + base, bytes);
-    rs_l = make_rsrc_words(lr + static_cast<int64_t>(jw0) * r, static_cast<uint32_t>(nk) * r2);
+    rs_l = make_rsrc_words(lr + static_cast<int64_t>(jw0) * lp, nk > 0 ? static_cast<uint32_t>(nk - 1) * lp2 + r2 : 0u);
   }
   const const_i32_ptr bt = CONST_I32(p.block_table) + static_cast<int64_t>(t) * p.max_blocks_per_seq;
 
@@ -295,7 +301,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
         const uint32_t kv_bytes = nv > 0 ? static_cast<uint32_t>(nv - 1) * ts2 + D * 2 : 0u;
         const u32x4 pk = make_rsrc_words(kb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
         const u32x4 pv = make_rsrc_words(vb + static_cast<int64_t>(blk) * p.kv_block_stride + hoff, kv_bytes);
-        const u32x4 pl = make_rsrc_words(lr + static_cast<int64_t>(blk) * 16 * r, static_cast<uint32_t>(nv) * r2);
+        const u32x4 pl = make_rsrc_words(lr + static_cast<int64_t>(blk) * 16 * lp, nv > 0 ? static_cast<uint32_t>(nv - 1) * lp2 + r2 : 0u);
 #pragma unroll
         for (int i = 0; i < KVL / 2; ++i) {
           const int ii = half * (KVL / 2) + i;
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
 #pragma unroll
         for (int i = 0; i < LL / 2; ++i) {
           const int ii = half * (LL / 2) + i;
-          buf_load16_to_lds(pl, ls_lds + ii * 1024, l_voff, i * LROWS * r2);
+          buf_load16_to_lds(pl, ls_lds + ii * 1024, l_voff, i * LROWS * lp2);
         }
       }
     } else {
@@ -316,7 +322,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
         kv_load(rs_v, vs_lds + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
       }
 #pragma unroll
-      for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * r2);
+      for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * lp2);
     }
   };
 

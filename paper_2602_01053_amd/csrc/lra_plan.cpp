@@ -141,8 +141,13 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   // needs a contiguous cache and no rotary key side, everything else takes the vector-ALU kernels.
   const int64_t l_pitch = c->l_row_stride ? c->l_row_stride : sh->rank;
   const bool custom_l = c->l_adapter_stride > 0 || l_pitch != sh->rank;
-  const bool stream_only = custom_l;
   const bool stream_ok = c->block_size == 0 && !(sh->key_rope_theta > 0.f) && tune.variant != 2;
+  // ... except that the older split-KV kernel reads such rows too when every row tile of a workgroup belongs to
+  // ONE low-rank cache: paged caches and batches then give each agent a row tile (and a workgroup) of its own,
+  // which streams K_base / V_base once per agent of a sequence instead of once per sequence (the other agents'
+  // workgroups find the tiles in L2), still on the matrix cores.  Not with the rotary key side.
+  const bool tile_per_agent = custom_l && !stream_ok && !rope;
+  const bool stream_only = custom_l && !tile_per_agent;
   if (prefill && pl.mfma) {
     // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
     // 32-bit byte offsets inside one buffer resource; larger caches take the other kernels
@@ -210,7 +215,8 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   pl.rows = tokens * sh->n_q_heads;
   pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
   pl.l_block = 0;
-  if (pl.mfma && !prefill && c->l_adapter_stride > 0) {
+  if (tile_per_agent && !prefill && c->l_adapter_stride > 0) pl.group_pad = 16;  // one agent per 16-row tile
+  if (pl.mfma && !prefill && c->l_adapter_stride > 0 && !tile_per_agent) {
     // every agent slot of a row tile brings its own column block of the L tile: 64 columns per tile
     pl.l_block = sh->rank <= 16 ? 16 : (sh->rank <= 32 ? 32 : 64);
     const int min_pad = 16 / (64 / pl.l_block);
@@ -225,7 +231,7 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   if (pl.short_prefill) max_queries_per_seq = tokens;
   if (pl.mfma) {
     int rows_needed = max_queries_per_seq * pl.group_pad;
-    pl.row_tiles = pl.l_block ? 1 : decode_mfma_row_tiles(rows_needed);  // (an L tile holds the column blocks of one row tile's agents)
+    pl.row_tiles = (pl.l_block || (tile_per_agent && !prefill && c->l_adapter_stride > 0)) ? 1 : decode_mfma_row_tiles(rows_needed);  // (an L tile holds the column blocks, or the one cache, of one row tile's agents)
     if (rope_split) {
       // one row tile per workgroup, and (decode) no more agent slots in it than the kernel keeps
       // B_K^T operands for
@@ -270,6 +276,12 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     const int64_t cap = ((int64_t{1} << 31) - 4096) / (c->kv_token_stride * 2) / tile * tile;
     if (cap < tile) pl.mfma = false;
     else if (split_keys > cap) split_keys = static_cast<int>(cap);
+  }
+  if (pl.mfma && tile_per_agent && c->block_size == 0) {
+    // a wave addresses the L rows of its keys with 32-bit byte offsets
+    const int64_t cap_l = ((int64_t{1} << 31) - 4096) / (l_pitch * 2) * 4 / tile * tile;
+    if (cap_l < tile) pl.mfma = false;
+    else if (split_keys > cap_l) split_keys = static_cast<int>(cap_l);
   }
   if (!pl.mfma) pl.short_prefill = false;
   if (pl.mfma && stream_only) {

@@ -59,7 +59,7 @@ SCRATCH_ALLOWED = [
     (r"prefill_mfma_kernelILi128ELi64ELb1ELb1ELb[01]ELb0ELb0E", 16),
     # rotary decode at d = 128, ranks up to 16 and 33..64: a few registers over the file (B_K^T operands of four agent
     # slots stay in registers); up to nine values spilled, five reloads per 32-key step
-    (r"decode_mfma_kernelILi128ELi1ELi(32|64)ELb[01]ELb1ELb0ELi(16|64)E", 144),
+    (r"decode_mfma_kernelILi128ELi1ELi(32|64)ELb[01]ELb1ELb0ELi(16|64)E", 160),
 ]
 
 

@@ -260,3 +260,78 @@ def test_prefills_on_paged_caches(block):
                              oracle.lra_oracle.gather_paged_l(f(w.l), ids, n), f(w.b_k[a]), f(w.b_v[a]), n=n,
                              scale=1.0 / d ** 0.5, key_rope_theta=theta)
         _check(out.to(torch.float64).cpu().numpy(), ref, tag)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_base_shared_on_paged_caches(block):
+    """One low-rank cache per adapter (Sec. 3.2, BaseShared) over a paged ragged batch: decode of every agent of
+    every sequence in one call, and a causal prefill of one sequence's last tokens; L stored adapter-major or
+    token-major (strided rows), plain and (prefill) rotary key side, every kernel choice, forced key shares."""
+    f = lambda t: t.to(torch.float64).numpy()
+    for case in range(block * BLOCK, (block + 1) * BLOCK):
+        rnd = random.Random(110_000 + case)
+        hq, hkv = _heads(rnd)
+        d, r = rnd.choice([64, 128]), rnd.choice([8, 16, 24, 32, 48, 64])
+        lens = [rnd.choice([1, 15, 16, 17, 300, rnd.randint(1, 3000)]) for _ in range(rnd.randint(1, 5))]
+        aps = rnd.randint(1, 5)
+        variant, split = rnd.choice([0, 0, 2, 1]), rnd.choice([0, 0, 128, 512])
+        token_major = rnd.random() < 0.5
+        do_prefill = case % 3 == 2
+        theta = rnd.choice([0.0, 0.0, 500000.0]) if do_prefill else 0.0
+        w = W.make_paged("sweep", seed=case, seq_lens=lens, agents_per_seq=1 if do_prefill else aps, n_adapters=rnd.randint(1, 5),
+                         n_q_heads=hq, n_kv_heads=hkv, head_dim=d, rank=r, d_model=None, b_std=0.1 if theta > 0 else 0.05,
+                         distinct_adapter_per_query=(not do_prefill) and rnd.random() < 0.3)
+        na = w.n_adapters
+        gen = torch.Generator().manual_seed(case + 7)
+        # adapter 0 keeps the workload's pool (NaN in the free slots), the others get values of their own in the used slots
+        l_pools = [w.l] + [torch.where(torch.isnan(w.l.float()), w.l.float(), torch.randn(w.l.shape, generator=gen)).to(torch.bfloat16)
+                           for _ in range(na - 1)]
+        st = torch.stack(l_pools)                                    # [adapter][block][16][r]
+        l_dev = st.permute(1, 2, 0, 3).contiguous().to(DEV).permute(2, 0, 1, 3) if token_major else st.to(DEV)
+        kp, vp = w.k_base.to(DEV), w.v_base.to(DEV)
+        table, bk, bv = w.block_table.to(DEV), w.b_k.to(DEV), w.b_v.to(DEV)
+        lens_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        tag = (f"case {case} {'prefill' if do_prefill else 'decode'} lens={lens} aps={aps} na={na} hq={hq} hkv={hkv} d={d} r={r} "
+               f"theta={theta:g} token_major={token_major} variant={variant} split={split}")
+        old = (lra.lra_set_kernel_variant(variant), lra.lra_set_decode_split_keys(split))
+        try:
+            if do_prefill:
+                seq, a = rnd.randrange(len(lens)), rnd.randrange(na)
+                n = lens[seq]
+                n_new = min(n, rnd.choice([1, 3, 16, 32, 33, 100, 129, 300]))
+                q = torch.randn(n_new, hq, d, generator=gen).to(torch.bfloat16)
+                qd = q.to(DEV)
+                shape = lra.make_shape(qd, hkv, r, 0.0, theta)
+                cache = lra.make_cache(kp, vp, l_dev, lens_d, max(lens), table, l_per_adapter=True)
+                out = torch.full_like(qd, float("nan"))
+                ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, 1, 1, n_new), 256), dtype=torch.uint8, device=DEV)
+                lra.lra_attn_prefill(shape, cache, bk, bv, na, qd, seq, a, out, ws)
+            else:
+                qd = w.q.to(DEV)
+                qa, qs = w.query_adapter.to(DEV), w.seq_query_start.to(DEV)
+                shape = lra.make_shape(qd, hkv, r)
+                cache = lra.make_cache(kp, vp, l_dev, lens_d, max(lens), table, l_per_adapter=True)
+                out = torch.full_like(qd, float("nan"))
+                ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, qd.shape[0], aps), 256), dtype=torch.uint8, device=DEV)
+                lra.lra_attn_decode(shape, cache, bk, bv, na, qd, qa, qs, aps, out, ws)
+            torch.cuda.synchronize()
+        finally:
+            lra.lra_set_kernel_variant(old[0])
+            lra.lra_set_decode_split_keys(old[1])
+        if do_prefill:
+            ids = w.block_table[seq].numpy()
+            ref = oracle.prefill(f(q), oracle.gather_paged(f(w.k_base), ids, n), oracle.gather_paged(f(w.v_base), ids, n),
+                                 oracle.lra_oracle.gather_paged_l(f(l_pools[a]), ids, n), f(w.b_k[a]), f(w.b_v[a]), n=n,
+                                 scale=1.0 / d ** 0.5, key_rope_theta=theta)
+        else:
+            ref = np.zeros(tuple(w.q.shape))
+            starts = w.seq_query_start.numpy()
+            for i in range(qd.shape[0]):
+                a = int(w.query_adapter[i])
+                t = int(np.searchsorted(starts, i, side="right") - 1)
+                # the oracle call sees query i alone, placed on sequence t, with the low-rank pool of its adapter
+                ref[i] = oracle.decode(f(w.q[i:i + 1]), f(w.k_base), f(w.v_base), f(l_pools[a]), f(w.b_k), f(w.b_v),
+                                       np.array([a], dtype=np.int32),
+                                       np.array([0] * (t + 1) + [1] * (len(lens) - t), dtype=np.int32), w.seq_lens, w.scale,
+                                       block_size=16, block_table=w.block_table.numpy())[0]
+        _check(out.to(torch.float64).cpu().numpy(), ref, tag)
