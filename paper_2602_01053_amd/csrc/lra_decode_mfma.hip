@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
       if (CAUSAL)
         a_slot[rt][si] = (si < 16 / GP && slot < n_q) ? p.adapter_index : -1;
       else
-        a_slot[rt][si] = ((HAS_BK || warm_bv || (!ROPE && p.l_adapter_stride > 0)) && si < 16 / GP && slot < n_q)
+        a_slot[rt][si] = ((HAS_BK || warm_bv || p.l_adapter_stride > 0) && si < 16 / GP && slot < n_q)
                              ? min(max(CONST_I32(p.query_adapter)[q_begin + slot], 0), p.n_adapters - 1)  // device data: kept inside the table
                              : -1;
     }
@@ -195,13 +195,12 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   const bf16_t* vb = static_cast<const bf16_t*>(p.v_base);
   // Low-rank rows: dense, or with a pitch of their own; with one low-rank cache per adapter the host gives every
   // agent a row tile (and this kernel one row tile per workgroup), so the tile's first slot names the cache
-  // (the rotary form is only ever given one dense cache)
-  const int64_t lp = ROPE ? r : p.l_row_stride;
+  const int64_t lp = p.l_row_stride;
   const bf16_t* lr = static_cast<const bf16_t*>(p.l) +
-                     (!ROPE && p.l_adapter_stride > 0 ? static_cast<int64_t>(max(a_slot[0][0], 0)) * p.l_adapter_stride : 0);
+                     (p.l_adapter_stride > 0 ? static_cast<int64_t>(max(a_slot[0][0], 0)) * p.l_adapter_stride : 0);
   const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
   const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
-  const uint32_t lp2 = ROPE ? r2 : static_cast<uint32_t>(lp) * 2u;       // bytes between L rows
+  const uint32_t lp2 = static_cast<uint32_t>(lp) * 2u;                   // bytes between L rows
 
   // ===================== per-lane constants of the tile traffic =====================
   // The LDS of this chip serves 256 bytes per clock (64 banks): a ds_read_b128 is free of

@@ -145,8 +145,9 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   // ... except that the older split-KV kernel reads such rows too when every row tile of a workgroup belongs to
   // ONE low-rank cache: paged caches and batches then give each agent a row tile (and a workgroup) of its own,
   // which streams K_base / V_base once per agent of a sequence instead of once per sequence (the other agents'
-  // workgroups find the tiles in L2), still on the matrix cores.  Not with the rotary key side.
-  const bool tile_per_agent = custom_l && !stream_ok && !rope;
+  // workgroups find the tiles in L2), still on the matrix cores.  The rotary form of that kernel likewise (its
+  // tiles then hold one agent slot each).
+  const bool tile_per_agent = custom_l && !stream_ok;
   const bool stream_only = custom_l && !tile_per_agent;
   if (prefill && pl.mfma) {
     // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
@@ -161,7 +162,7 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   // tokens in the place of the agents and a causal limit per row, spreads the context over
   // the chip instead.  (Measured crossover on MI355X: see kShortPrefill.)
   pl.short_prefill = prefill && pl.mfma && tokens <= tune.short_prefill &&
-                     static_cast<int64_t>(tokens) * 4 <= c->max_seq_len && (!stream_only || stream_ok);
+                     static_cast<int64_t>(tokens) * 4 <= c->max_seq_len;
   const bool rope_split = rope && pl.mfma && (!prefill || pl.short_prefill);  // rotary form of the split-KV kernel
   if (prefill && pl.mfma && !pl.short_prefill) {
     // Tile-walking kernel: one workgroup per (128-row q tile, q head).  When that is fewer than
@@ -211,7 +212,6 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     pl.launchable = true;  // at most 32 shares in y
     return pl;
   }
-  if (stream_only && !stream_ok) pl.mfma = false;
   pl.rows = tokens * sh->n_q_heads;
   pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
   pl.l_block = 0;

@@ -188,11 +188,12 @@ def test_append_and_base_shared_calls(block):
         prev = lra.lra_set_kernel_variant(variant)
         try:
             if kind == "bs_dec":
-                tag = f"case {case} base_shared decode n={n} agents={agents} hq={hq} hkv={hkv} d={d} r={r} {storage} variant={variant}"
+                theta = random.Random(case + 999).choice([0.0, 0.0, 500000.0])  # (a third with the rotary key side)
+                tag = f"case {case} base_shared decode n={n} agents={agents} hq={hq} hkv={hkv} d={d} r={r} theta={theta:g} {storage} variant={variant}"
                 q = torch.randn(agents, hq, d, generator=gen).to(torch.bfloat16)
                 qd = q.to(DEV)
                 adapter_of = torch.tensor([(3 * a + 1) % agents for a in range(agents)], dtype=torch.int32)
-                shape = lra.make_shape(qd, hkv, r)
+                shape = lra.make_shape(qd, hkv, r, 0.0, theta)
                 cache = lra.make_cache(kd, vd, l_dev, lens, n, None, l_per_adapter=True)
                 out = torch.full_like(qd, float("nan"))
                 ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, agents, agents), 256), dtype=torch.uint8, device=DEV)
@@ -201,7 +202,8 @@ def test_append_and_base_shared_calls(block):
                 torch.cuda.synchronize()
                 ref = np.concatenate([
                     oracle.decode(f(q[i:i + 1]), f(k), f(v), f(ls[int(adapter_of[i])]), f(bk), f(bv),
-                                  np.array([int(adapter_of[i])], dtype=np.int32), np.array([0, 1], dtype=np.int32), [n], 1.0 / d ** 0.5)
+                                  np.array([int(adapter_of[i])], dtype=np.int32), np.array([0, 1], dtype=np.int32), [n], 1.0 / d ** 0.5,
+                                  key_rope_theta=theta)
                     for i in range(agents)])
             else:
                 n_new, a = min(n, rnd.choice([1, 7, 32, 33, 130, 300])), rnd.randrange(agents)
@@ -266,7 +268,7 @@ def test_prefills_on_paged_caches(block):
 def test_base_shared_on_paged_caches(block):
     """One low-rank cache per adapter (Sec. 3.2, BaseShared) over a paged ragged batch: decode of every agent of
     every sequence in one call, and a causal prefill of one sequence's last tokens; L stored adapter-major or
-    token-major (strided rows), plain and (prefill) rotary key side, every kernel choice, forced key shares."""
+    token-major (strided rows), plain and rotary key side, every kernel choice, forced key shares."""
     f = lambda t: t.to(torch.float64).numpy()
     for case in range(block * BLOCK, (block + 1) * BLOCK):
         rnd = random.Random(110_000 + case)
@@ -277,7 +279,7 @@ def test_base_shared_on_paged_caches(block):
         variant, split = rnd.choice([0, 0, 2, 1]), rnd.choice([0, 0, 128, 512])
         token_major = rnd.random() < 0.5
         do_prefill = case % 3 == 2
-        theta = rnd.choice([0.0, 0.0, 500000.0]) if do_prefill else 0.0
+        theta = rnd.choice([0.0, 0.0, 500000.0])
         w = W.make_paged("sweep", seed=case, seq_lens=lens, agents_per_seq=1 if do_prefill else aps, n_adapters=rnd.randint(1, 5),
                          n_q_heads=hq, n_kv_heads=hkv, head_dim=d, rank=r, d_model=None, b_std=0.1 if theta > 0 else 0.05,
                          distinct_adapter_per_query=(not do_prefill) and rnd.random() < 0.3)
@@ -309,7 +311,7 @@ def test_base_shared_on_paged_caches(block):
             else:
                 qd = w.q.to(DEV)
                 qa, qs = w.query_adapter.to(DEV), w.seq_query_start.to(DEV)
-                shape = lra.make_shape(qd, hkv, r)
+                shape = lra.make_shape(qd, hkv, r, 0.0, theta)
                 cache = lra.make_cache(kp, vp, l_dev, lens_d, max(lens), table, l_per_adapter=True)
                 out = torch.full_like(qd, float("nan"))
                 ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, qd.shape[0], aps), 256), dtype=torch.uint8, device=DEV)
@@ -333,5 +335,5 @@ def test_base_shared_on_paged_caches(block):
                 ref[i] = oracle.decode(f(w.q[i:i + 1]), f(w.k_base), f(w.v_base), f(l_pools[a]), f(w.b_k), f(w.b_v),
                                        np.array([a], dtype=np.int32),
                                        np.array([0] * (t + 1) + [1] * (len(lens) - t), dtype=np.int32), w.seq_lens, w.scale,
-                                       block_size=16, block_table=w.block_table.numpy())[0]
+                                       block_size=16, block_table=w.block_table.numpy(), key_rope_theta=theta)[0]
         _check(out.to(torch.float64).cpu().numpy(), ref, tag)
