@@ -45,7 +45,9 @@
  * Supported: head_dim in {64, 128}; 1 <= rank <= 64; n_q_heads a multiple of
  * n_kv_heads with a group of at most 16; q head g reads kv head g / (Hq/Hkv);
  * block_size 0 (contiguous) or 16; dtype bf16 (MFMA kernels) or fp32 (vector-ALU
- * kernels).  Size caps: n_q_heads <= 4096, n_seqs <= 2^20, max_seq_len <= 2^30,
+ * kernels; bf16 ranks that are not a multiple of 8 take those as well - padding L with zero
+ * columns and B_K, B_V with zero rows to the next multiple of 8 gives the same outputs on the
+ * MFMA kernels).  Size caps: n_q_heads <= 4096, n_seqs <= 2^20, max_seq_len <= 2^30,
  * query rows (queries or new tokens times n_q_heads) <= 2^30, kv_token_stride <= 2^31,
  * kv_head_stride and kv_block_stride <= 2^40 elements, num_blocks * kv_block_stride <= 2^60,
  * at most 65535 key shares per sequence and 65535 (sequence, row group) pairs per call.
@@ -132,10 +134,13 @@ typedef struct {
  *   Both strides are multiples of 8 elements (a row stride equal to the rank is always accepted).
  *   The byte model changes with it: a decode call
  *   streams the L rows of every agent on the sequence (A*r instead of r elements per token).
- *   Kernels: bf16 with rank % 8 == 0 runs on the MFMA kernels for a contiguous cache without
- *   the rotary key side (decode: the agents of a row tile each bring their own column block
- *   of the L tile, so a tile holds 4 agents at rank <= 16, 2 at rank <= 32, 1 above; prefill:
- *   the one agent's rows are read with their stride); everything else on the vector-ALU
+ *   Kernels: bf16 with rank % 8 == 0 runs on the MFMA kernels.  Decode of one sequence in a
+ *   contiguous cache without the rotary key side reads K_base / V_base once for all agents
+ *   (the agents of a row tile each bring their own column block of the L tile, so a tile holds
+ *   4 agents at rank <= 16, 2 at rank <= 32, 1 above); decode on paged caches, of batches, or
+ *   with the rotary key side gives every agent a row tile and a workgroup of its own, which
+ *   requests K_base / V_base once per agent (the later requests are served by L2); prefill
+ *   reads the one agent's rows with their stride.  Other dtypes and ranks run on the vector-ALU
  *   kernels.  lra_cache_append fills adapter 0's rows only (BaseLRShared is the scheme with
  *   one producer call per token).
  */

@@ -58,10 +58,17 @@ constexpr int kRopeSlots64 = 4;
 // registers (RPE = padded rank of that product: 16, 32 or 64, for 4, 2 or 4 slots per tile - at
 // 64 the LDS leaves room for one workgroup per CU only, whose waves then have 512 registers);
 // in the causal form all rows belong to the one adapter of the call.
-template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL, int RPE = 0>
+//
+// PA = true is the decode form for one low-rank cache per adapter (BaseShared, Sec. 3.2) outside the rotary key
+// side: the L tile is a row of column blocks [agent slot][32 keys][l_block ranks], block s requested from the cache
+// of the adapter of agent slot s; Qt of a row stands in the block of its slot and is zero elsewhere, so the same
+// products give Qt_a . L_a^T and P . L_a per agent, and a row keeps only its own block of O_lr.  K_base and V_base are
+// then read once for all agents of a tile, and no zero padding is streamed.
+template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL, int RPE = 0, bool PA = false>
 __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Params p) {
   constexpr int NW = 4;
   constexpr bool ROPE = RPE > 0;
+  static_assert(!PA || (!ROPE && !CAUSAL && RT == 1), "per-adapter low-rank caches: plain decode form, one row tile");
   constexpr int NS = !ROPE ? 1 : (RPE == 16 ? 4 : (RPE == 32 ? 2 : kRopeSlots64));  // agent slots with operands in registers
   constexpr int EK = RPE == 64 ? 2 : 1;                                    // 32-wide k-steps of the E product
   static_assert(!ROPE || (RT == 1 && HAS_BK && (RPE == 64) == (RP == 64)), "rotary form: one row tile");
@@ -197,7 +204,14 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   // agent a row tile (and this kernel one row tile per workgroup), so the tile's first slot names the cache
   const int64_t lp = p.l_row_stride;
   const bf16_t* lr = static_cast<const bf16_t*>(p.l) +
-                     (p.l_adapter_stride > 0 ? static_cast<int64_t>(max(a_slot[0][0], 0)) * p.l_adapter_stride : 0);
+                     (!PA && p.l_adapter_stride > 0 ? static_cast<int64_t>(max(a_slot[0][0], 0)) * p.l_adapter_stride : 0);
+  // PA: ranks per column block (16, 32 or 64), 16-byte chunks per row of a block, bytes per row of a block; the
+  // XOR swizzle of the chunk index inside a block row (none for 32-byte rows: 16 rows fill two clocks densely).
+  // Without PA the tile is one block of RP ranks and all of this folds to the constants of that layout.
+  const int lb = PA ? p.l_block : RP;
+  const int lcpr = lb >> 3, lcs = __builtin_ctz(lcpr), lb2 = lb * 2;
+  auto swz_l = [&](int row) { return lcpr == 8 ? (row & 7) : (lcpr == 4 ? ((row >> 1) & 3) : 0); };
+  const int gps = __builtin_ctz(GP);  // GP is 4, 8 or 16
   const uint32_t ts2 = static_cast<uint32_t>(p.kv_token_stride) * 2u;  // token stride in bytes
   const uint32_t r2 = static_cast<uint32_t>(r) * 2u;                     // L row in bytes
   const uint32_t lp2 = static_cast<uint32_t>(lp) * 2u;                   // bytes between L rows
@@ -217,15 +231,26 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   // i*ROWS + l/CH repeats with period 16/KROWS (K) and 8/KROWS (V) in i.
   constexpr int KPER = KROWS == 4 ? 4 : 2, VPER = KROWS == 4 ? 2 : 1;
   uint32_t k_voff[KPER], v_voff[VPER], l_voff;
+  uint32_t l_in_row = 0;  // PA: byte offset of the lane's chunk inside an L row
+  bool l_ok = true;       // PA: that chunk lies inside the rank
   {
     const int rr = lane / KCH, pc = lane % KCH;
 #pragma unroll
     for (int q = 0; q < KPER; ++q) k_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_k(q * KROWS + rr)) << 4);
 #pragma unroll
     for (int q = 0; q < VPER; ++q) v_voff[q] = static_cast<uint32_t>(rr) * ts2 + ((pc ^ swz_v(q * KROWS + rr)) << 4);
-    const int lrow = lane / RCH, lpc = lane % RCH;
-    const int lch = lpc ^ ((lrow >> LSW_SHIFT) & (RCH - 1));
-    l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * lp2 + (lch << 4) : kOob;
+    if constexpr (PA) {
+      // lane -> (row inside a request, chunk of the block row): the swizzle repeats from request to request
+      const int lrow = lane >> lcs, lpc = lane & (lcpr - 1);
+      const int lch = lpc ^ swz_l(lrow);
+      l_ok = lch * 8 < r;
+      l_in_row = static_cast<uint32_t>(lch) << 4;
+      l_voff = l_ok ? static_cast<uint32_t>(lrow) * lp2 + l_in_row : kOob;
+    } else {
+      const int lrow = lane / RCH, lpc = lane % RCH;
+      const int lch = lpc ^ ((lrow >> LSW_SHIFT) & (RCH - 1));
+      l_voff = (lch * 8 < r) ? static_cast<uint32_t>(lrow) * lp2 + (lch << 4) : kOob;
+    }
   }
   // LDS -> MFMA operands (byte offsets inside the tile regions).
   // K rows as A operand of S^T: key = 16tt + ln, logical chunk 4ks + lg at chunk ^ swz_k(key):
@@ -238,7 +263,19 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   const int v_pre = ka * (2 * D) + ((swz_v(ka) + ((ln & 3) >> 1)) << 4) + (ln & 1) * 8;
   int l_rd[RKS][2];  // L rows as A operand of S^T: two 8-byte pieces per k-step
   int lt_rd[RB];     // L^T as A operand of Olr^T
-  {
+  if constexpr (PA) {
+    // column chunk ch of the tile (8 ranks) lies in block ch / lcpr, chunk ch % lcpr of a row there
+    auto chunk_addr = [&](int ch, int row) {
+      const int blk = ch >> lcs, cc = ch & (lcpr - 1);
+      return blk * (32 * lb2) + row * lb2 + ((cc ^ swz_l(row)) << 4);
+    };
+#pragma unroll
+    for (int ks = 0; ks < RKS; ++ks)
+#pragma unroll
+      for (int pc = 0; pc < 2; ++pc) l_rd[ks][pc] = chunk_addr(4 * ks + 2 * pc + (lg >> 1), ln) + (lg & 1) * 8;
+#pragma unroll
+    for (int b = 0; b < RB; ++b) lt_rd[b] = chunk_addr(2 * b + ((ln & 3) >> 1), ka) + (ln & 1) * 8;
+  } else {
     const int swz_s = (ln >> LSW_SHIFT) & (RCH - 1);
 #pragma unroll
     for (int ks = 0; ks < RKS; ++ks)
@@ -264,6 +301,30 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
     rs_k = make_rsrc_words(kb + base, bytes);
     rs_v = make_rsrc_words(vb + base, bytes);
     rs_l = make_rsrc_words(lr + static_cast<int64_t>(jw0) * lp, nk > 0 ? static_cast<uint32_t>(nk - 1) * lp2 + r2 : 0u);
+  }
+  // PA: one L resource per request of 1 KB - the requests of a column block read the cache of that block's agent
+  // slot (a block beyond the tile's slots, or of an empty slot, reads nothing).  Contiguous cache: the rows of the
+  // wave's keys, as above.  Paged cache: the adapter's whole pool (the host has checked that it fits 32-bit byte
+  // offsets); a lane then addresses its row through the physical block and masks the keys past the wave's range itself.
+  constexpr int LREQ = PA ? LL : 1;
+  u32x4 rs_la[LREQ];
+  uint32_t l_row0[LREQ];  // first tile row of the request
+  if constexpr (PA) {
+    const int rows_per_req = 64 >> lcs;  // 1 KB of rows of lb ranks
+    const int rpb_shift = lcs - 1;       // lb/16 requests per block
+    const int nk = jw1 - jw0;
+    const uint32_t bytes = PAGED ? (static_cast<uint32_t>(p.num_blocks) * 16u - 1u) * lp2 + r2
+                                 : (nk > 0 ? static_cast<uint32_t>(nk - 1) * lp2 + r2 : 0u);
+#pragma unroll
+    for (int i = 0; i < LL; ++i) {
+      const int blk = i >> rpb_shift, qq = i - (blk << rpb_shift);
+      const int a = blk == 0 ? a_slot[0][0] : (blk == 1 ? a_slot[0][1] : (blk == 2 ? a_slot[0][2] : a_slot[0][3]));
+      const bool live = blk < (16 >> gps) && a >= 0;
+      rs_la[i] = make_rsrc_words(static_cast<const bf16_t*>(p.l) + static_cast<int64_t>(live ? a : 0) * p.l_adapter_stride +
+                                     (PAGED ? 0 : static_cast<int64_t>(jw0) * lp),
+                                 live ? bytes : 0u);
+      l_row0[i] = static_cast<uint32_t>(qq * rows_per_req);
+    }
   }
   const const_i32_ptr bt = CONST_I32(p.block_table) + static_cast<int64_t>(t) * p.max_blocks_per_seq;
 
@@ -307,10 +368,25 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
           kv_load(pk, ks_lds + ii * 1024, k_voff[ii % KPER], i * KROWS * ts2);
           kv_load(pv, vs_lds + ii * 1024, v_voff[ii % VPER], i * KROWS * ts2);
         }
+        if constexpr (!PA) {
 #pragma unroll
-        for (int i = 0; i < LL / 2; ++i) {
-          const int ii = half * (LL / 2) + i;
-          buf_load16_to_lds(pl, ls_lds + ii * 1024, l_voff, i * LROWS * lp2);
+          for (int i = 0; i < LL / 2; ++i) {
+            const int ii = half * (LL / 2) + i;
+            buf_load16_to_lds(pl, ls_lds + ii * 1024, l_voff, i * LROWS * lp2);
+          }
+        }
+      }
+      if constexpr (PA) {
+        // tile row of this lane in request i: l_row0[i] + lane / lcpr; its physical block is the first or the
+        // second of the step; rows at or past the end of the wave's range read nothing (zeros)
+        const uint32_t lrow = static_cast<uint32_t>(lane >> lcs);
+        const uint32_t pg0 = static_cast<uint32_t>(blk_cur[0]) * 16u * lp2, pg1 = static_cast<uint32_t>(blk_cur[1]) * 16u * lp2;
+#pragma unroll
+        for (int i = 0; i < LL; ++i) {
+          const uint32_t row = l_row0[i] + lrow;
+          const bool ok = l_ok && j + static_cast<int>(row) < jw1;
+          const uint32_t voff = ok ? (row < 16u ? pg0 : pg1) + (row & 15u) * lp2 + l_in_row : kOob;
+          buf_load16_to_lds(rs_la[i], ls_lds + i * 1024, voff, 0u);
         }
       }
     } else {
@@ -320,8 +396,13 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
         kv_load(rs_k, ks_lds + i * 1024, k_voff[i % KPER], (s0 + i * KROWS) * ts2);
         kv_load(rs_v, vs_lds + i * 1024, v_voff[i % VPER], (s0 + i * KROWS) * ts2);
       }
+      if constexpr (PA) {
 #pragma unroll
-      for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * lp2);
+        for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_la[i], ls_lds + i * 1024, l_voff, (s0 + l_row0[i]) * lp2);
+      } else {
+#pragma unroll
+        for (int i = 0; i < LL; ++i) buf_load16_to_lds(rs_l, ls_lds + i * 1024, l_voff, (s0 + i * LROWS) * lp2);
+      }
     }
   };
 
@@ -418,6 +499,12 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
     if (jw0 < jw1) issue_tile(jw0);
   }
   if (HAS_BK && !ROPE) {
+    if constexpr (PA) {
+      // every piece of the exchange area starts as zero: blocks beyond a slot's rank, the other slots' blocks
+      if (wave < RT * RKS) *reinterpret_cast<uint4*>(qt_lds + (wave * 64 + lane) * 16) = make_uint4(0u, 0u, 0u, 0u);
+      static_assert(!PA || RT * RKS <= NW, "one piece per wave");
+      __syncthreads();
+    }
     const int S = 16 / GP;         // agent slots per 16-row tile
     const int ncb = (r + 15) >> 4;
     const int64_t ldb = static_cast<int64_t>(p.n_kv_heads) * D;
@@ -452,9 +539,12 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
           for (int ks = 0; ks < KS; ++ks)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bt4[rt][it][ks]), qb[rt][ks], acc, 0, 0, 0);
           if (ln / GP == si) {
-            unsigned char* dst = qt_lds + ((rt * RKS + (cb >> 1)) * 64 + lane) * 16;
+            const int kb = PA ? si * (lb >> 4) + cb : cb;  // 16-rank block along the L tile's columns
+            unsigned char* dst = qt_lds + ((rt * RKS + (kb >> 1)) * 64 + lane) * 16;
             const uint2 pk = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
-            if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
+            if constexpr (PA)
+              *reinterpret_cast<uint2*>(dst + (kb & 1) * 8) = pk;
+            else if (!(cb & 1) && cb + 1 >= ncb)  // the odd block next to it lies beyond the rank: zeros
               *reinterpret_cast<uint4*>(dst) = make_uint4(pk.x, pk.y, 0u, 0u);
             else
               *reinterpret_cast<uint2*>(dst + (cb & 1) * 8) = pk;
@@ -467,7 +557,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
 #pragma unroll
       for (int ks = 0; ks < RKS; ++ks) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);  // k-steps entirely beyond the rank were never written
-        if (ks * 32 < r) v = lds_read16(qt_lds + ((rt * RKS + ks) * 64 + lane) * 16);
+        if (PA || ks * 32 < r) v = lds_read16(qt_lds + ((rt * RKS + ks) * 64 + lane) * 16);
         qtb[rt][ks] = as_bf16x8(v);
       }
   }
@@ -511,8 +601,8 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
       if (HAS_BK && !ROPE) {
 #pragma unroll
         for (int ks = 0; ks < RKS; ++ks) {
-          const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 32 * RP);
-          const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 32 * RP);
+          const uint2 lo = lds_read8(ls_lds + l_rd[ks][0] + tt * 16 * lb2);  // (16 rows of a block further)
+          const uint2 hi = lds_read8(ls_lds + l_rd[ks][1] + tt * 16 * lb2);
           const bf16x8 a = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
 #pragma unroll
           for (int rt = 0; rt < RT; ++rt)
@@ -647,7 +737,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
       const unsigned char* src = ls_lds + lt_rd[b];
-      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 32 * RP));
+      const bf16x8 a = join_tr(lds_read_tr16(src), lds_read_tr16(src + 16 * lb2));
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         lr_acc[rt][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rt], lr_acc[rt][b], 0, 0, 0);
@@ -756,11 +846,14 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
 #pragma unroll
       for (int b = 0; b < RB; ++b)
         if (((DB + b) & (NW - 1)) == wave) {
+          // PA: a row keeps the column block of its own agent slot only, as ranks 0 .. r-1 of its state
+          const int cblk = PA ? b >> (lcs - 1) : 0;
+          const bool mine = !PA || cblk == (ln >> gps);
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
-            const int rho = b * 16 + lg * 4 + jj;
+            const int rho = b * 16 + lg * 4 + jj - cblk * lb;
             const float v = total(rt * PER_RT + (DB + b) * 4 + jj);
-            if (rho < r) p.part_lr[slot * r + rho] = v;
+            if (mine && rho < r) p.part_lr[slot * r + rho] = v;
           }
         }
       if (wave == NW - 1 && lg == 0) {
@@ -833,12 +926,15 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
       for (int b = 0; b < DB; ++b)
         *reinterpret_cast<f32x4*>(p.part_o + slot * D + b * 16 + lg * 4) = o_acc[rt][b];
 #pragma unroll
-      for (int b = 0; b < RB; ++b)
+      for (int b = 0; b < RB; ++b) {
+        const int cblk = PA ? b >> (lcs - 1) : 0;
+        const bool mine = !PA || cblk == (ln >> gps);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-          const int rho = b * 16 + lg * 4 + jj;
-          if (rho < r) p.part_lr[slot * r + rho] = lr_acc[rt][b][jj];
+          const int rho = b * 16 + lg * 4 + jj - cblk * lb;
+          if (mine && rho < r) p.part_lr[slot * r + rho] = lr_acc[rt][b][jj];
         }
+      }
     }
   }
 #pragma unroll
@@ -851,6 +947,18 @@ template <int D, int RT, int RP, bool CAUSAL>
 static hipError_t launch_cfg2(const Params& p, dim3 grid, hipStream_t s) {
   const dim3 block(256);
   const bool paged = p.block_size != 0, has_bk = p.b_k != nullptr;
+  if (p.l_block != 0) {
+    // per-adapter low-rank caches, one column block of the L tile per agent slot: decode, one row tile
+    if constexpr (RT == 1 && !CAUSAL) {
+      if (paged && has_bk) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, false, 0, true>), grid, block, 0, s, p);
+      else if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, false, false, 0, true>), grid, block, 0, s, p);
+      else if (has_bk) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, false, 0, true>), grid, block, 0, s, p);
+      else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, false, false, 0, true>), grid, block, 0, s, p);
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
   if (paged && has_bk)
     hipLaunchKernelGGL((decode_mfma_kernel<D, RT, RP, true, true, CAUSAL>), grid, block, 0, s, p);
   else if (paged)
@@ -896,7 +1004,9 @@ hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_
       default: return launch_rope<128, 64, 64>(p, grid, s);
     }
   }
-  const int rp = p.rank <= 32 ? 32 : 64;
+  // columns of the L tile: the rank, or with per-adapter low-rank caches one block per agent slot of a row tile
+  const int tile_rank = (p.l_block != 0 && !p.is_prefill) ? (16 / p.group_pad) * p.l_block : p.rank;
+  const int rp = tile_rank <= 32 ? 32 : 64;
   const int key = (p.head_dim == 128 ? 4 : 0) | (row_tiles == 2 ? 2 : 0) | (rp == 64 ? 1 : 0);
   switch (key) {
     case 0: return launch_cfg<64, 1, 32>(p, grid, s);

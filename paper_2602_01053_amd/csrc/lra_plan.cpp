@@ -148,6 +148,12 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   // workgroups find the tiles in L2), still on the matrix cores.  The rotary form of that kernel likewise (its
   // tiles then hold one agent slot each).
   const bool tile_per_agent = custom_l && !stream_ok;
+  // Plain decode with one low-rank cache per adapter does better: the split-KV kernel has the same column-block L
+  // tile as the streaming form (one block per agent slot of a row tile), so K_base / V_base are requested once for
+  // the agents of a tile.  It addresses a paged pool of low-rank rows with 32-bit byte offsets inside one resource.
+  const bool block_per_slot =
+      tile_per_agent && !prefill && !rope && c->l_adapter_stride > 0 &&
+      (c->block_size == 0 || static_cast<int64_t>(c->num_blocks) * 16 * l_pitch * 2 <= (int64_t{1} << 31) - 4096);
   const bool stream_only = custom_l && !tile_per_agent;
   if (prefill && pl.mfma) {
     // the tile-walking kernel addresses a contiguous kv head slice, and L as a whole, with
@@ -215,8 +221,8 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   pl.rows = tokens * sh->n_q_heads;
   pl.group_pad = G <= 4 ? 4 : (G <= 8 ? 8 : 16);
   pl.l_block = 0;
-  if (tile_per_agent && !prefill && c->l_adapter_stride > 0) pl.group_pad = 16;  // one agent per 16-row tile
-  if (pl.mfma && !prefill && c->l_adapter_stride > 0 && !tile_per_agent) {
+  if (tile_per_agent && !block_per_slot && !prefill && c->l_adapter_stride > 0) pl.group_pad = 16;  // one agent per 16-row tile
+  if (pl.mfma && !prefill && c->l_adapter_stride > 0 && (!tile_per_agent || block_per_slot)) {
     // every agent slot of a row tile brings its own column block of the L tile: 64 columns per tile
     pl.l_block = sh->rank <= 16 ? 16 : (sh->rank <= 32 ? 32 : 64);
     const int min_pad = 16 / (64 / pl.l_block);
@@ -301,6 +307,7 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
       pl.mfma = false;
     if (!pl.mfma) pl.l_block = 0;
   }
+  if (!pl.mfma) pl.l_block = 0;
   pl.split_keys = split_keys;
   pl.n_splits = static_cast<int>((static_cast<int64_t>(c->max_seq_len) + split_keys - 1) / split_keys);
   // grids: (kv head, share, sequence x row group) for the MFMA kernels, (row, share) otherwise

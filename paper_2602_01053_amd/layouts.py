@@ -12,6 +12,12 @@ a wider L with zero-padded up-projections, so they need no kernel of their own:
 * Separate down-projections for keys and values (LoRA on W_K and on W_V have different A):
   L = [L_K | L_V], B'_K = [B_K ; 0], B'_V = [0 ; B_V].
 
+* Ranks that are not a multiple of 8 (the qkvo setting of App. D.1 uses r = 4): the matrix-core
+  kernels move L rows in 16-byte pieces and take ranks that are multiples of 8; other ranks run
+  on the vector-ALU kernels.  pad_rank() appends zero columns to L and zero rows to every B up to
+  the next multiple of 8 - the same outputs (products with zero), at matrix-core speed.  A
+  producer that pads the rows of A the same way (W_cat of lra_cache_append) writes such an L itself.
+
 Both widen the rank to the sum of the parts (the kernels take up to 64) and the low-rank
 cache bytes with it - which is the memory cost the paper attributes to these schemes.
 Pure concatenation and zero padding: no arithmetic of the method lives here.
@@ -59,3 +65,17 @@ def separate_key_value(l_k: torch.Tensor, l_v: torch.Tensor, b_k: torch.Tensor, 
     bk = torch.stack([embed_up_projection(b_k[a], 0, ranks) for a in range(b_k.shape[0])])
     bv = torch.stack([embed_up_projection(b_v[a], 1, ranks) for a in range(b_v.shape[0])])
     return l, bk, bv
+
+
+def pad_rank(l: torch.Tensor, b_k: torch.Tensor, b_v: torch.Tensor, multiple: int = 8
+             ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """L [...][r] and stacks b_k, b_v [agents][r][Hkv*d] (either may be None) -> the same with the rank
+    padded by zeros to the next multiple of `multiple`: L . B is unchanged."""
+    r = int(l.shape[-1])
+    pad = (-r) % multiple
+    if pad == 0:
+        return l, b_k, b_v
+    widen = lambda b: None if b is None else torch.cat(
+        [b, torch.zeros(b.shape[0], pad, b.shape[2], dtype=b.dtype, device=b.device)], dim=1).contiguous()
+    lp = torch.cat([l, torch.zeros(*l.shape[:-1], pad, dtype=l.dtype, device=l.device)], dim=-1).contiguous()
+    return lp, widen(b_k), widen(b_v)

@@ -104,10 +104,20 @@ int main(int argc, char** argv) {
         CHECK(pl.off_adapter >= pl.off_lr + slots * sh.rank * 4 && pl.off_qt >= pl.off_adapter + static_cast<size_t>(pl.rows) * 4);
         CHECK(pl.bytes_without_kc >= pl.off_qt + pl.qt_bytes);
       }
-      if (pl.l_block) {  // per-adapter low-rank caches on the MFMA decode path: streaming form only
-        CHECK(!prefill && pl.mfma && c.block_size == 0 && c.l_adapter_stride > 0 && pl.row_tiles == 1);
+      if (pl.l_block) {  // per-adapter low-rank caches on the MFMA decode path, one column block of the L tile per agent slot
+        CHECK(!prefill && pl.mfma && c.l_adapter_stride > 0 && pl.row_tiles == 1 && !(sh.key_rope_theta > 0.f));
         CHECK(pl.l_block * (16 / pl.group_pad) <= 64 && pl.l_block >= sh.rank && pl.qt_bytes == 0);
-        CHECK(static_cast<int64_t>(sh.n_kv_heads) * pl.n_splits * pl.row_groups <= kCUs);
+        const int64_t pitch = c.l_row_stride ? c.l_row_stride : sh.rank;
+        if (c.block_size == 0 && tune.variant != 2) {
+          // streaming form: at most one workgroup per compute unit
+          CHECK(static_cast<int64_t>(sh.n_kv_heads) * pl.n_splits * pl.row_groups <= kCUs);
+        } else if (c.block_size == 0) {
+          // split-KV form on a contiguous cache: a wave's L rows inside 32-bit byte offsets
+          CHECK(static_cast<int64_t>(pl.split_keys) / 4 * pitch * 2 < (int64_t{1} << 31));
+        } else {
+          // split-KV form on a paged cache: the whole pool of an adapter's L rows inside them
+          CHECK(static_cast<int64_t>(c.num_blocks) * 16 * pitch * 2 < (int64_t{1} << 31));
+        }
       }
       const bool split_path = !prefill || pl.short_prefill || !pl.mfma;
       if (split_path && pl.mfma) {

@@ -37,6 +37,18 @@ def test_embedding_is_exact():
         np.testing.assert_array_equal(_f(l2) @ _f(bv2[a]), _f(c["l_v"][0]) @ _f(c["b_v"][a]))
 
 
+def test_rank_padding_is_exact():
+    """pad_rank: zero columns of L against zero rows of B - the products L B_K and L B_V do not change by a bit."""
+    c = _case(31, 50, 3, 4, 2, 8, 4, dtype=torch.float64)
+    l, bk, bv = layouts.pad_rank(c["l"][0], c["b_k"], c["b_v"])
+    assert l.shape == (50, 8) and bk.shape == (3, 8, 16) and bv.shape == (3, 8, 16)
+    assert bool((l[:, 4:] == 0).all()) and bool((bk[:, 4:] == 0).all()) and bool((bv[:, 4:] == 0).all())
+    for a in range(3):
+        assert torch.equal(l @ bk[a], c["l"][0] @ c["b_k"][a]) and torch.equal(l @ bv[a], c["l"][0] @ c["b_v"][a])
+    same = layouts.pad_rank(l, bk, None)
+    assert same[0] is l and same[1] is bk and same[2] is None
+
+
 def _workload(name, c, l, b_k, b_v, hq, hkv, d):
     agents = c["q"].shape[0]
     n = c["k"].shape[0]
@@ -85,6 +97,22 @@ def test_separate_key_and_value_caches_decode():
             ref[a, h] = (p / p.sum()) @ v_full[:, h // g, :]
     rel, mx = errors(got, ref)
     print(f"separate_kv: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
+@pytest.mark.gpu
+def test_rank_four_padded_to_eight_decode():
+    """The qkvo rank of App. D.1 (r = 4) on the matrix-core kernels through pad_rank; the oracle sees rank 4."""
+    from tests.harness import MAX_ABS_TOL, REL_L2_TOL, errors, run_decode
+    n, agents, hq, hkv, d, r = 2100, 4, 32, 8, 128, 4
+    c = _case(960, n, agents, hq, hkv, d, r)
+    l, bk, bv = layouts.pad_rank(c["l"][0], c["b_k"], c["b_v"])
+    assert l.shape[-1] == 8
+    got = run_decode(_workload("rank4_padded", c, l, bk, bv, hq, hkv, d), "cuda:0")
+    ref = oracle.decode(_f(c["q"]), _f(c["k"]), _f(c["v"]), _f(c["l"][0]), _f(c["b_k"]), _f(c["b_v"]),
+                        np.arange(agents, dtype=np.int32), np.array([0, agents], dtype=np.int32), [n], 1.0 / d ** 0.5)
+    rel, mx = errors(got, ref)
+    print(f"rank 4 padded to 8: relL2={rel:.3e} maxabs={mx:.3e}", flush=True)
     assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
 
 
