@@ -134,13 +134,14 @@ typedef struct {
  *   Both strides are multiples of 8 elements (a row stride equal to the rank is always accepted).
  *   The byte model changes with it: a decode call
  *   streams the L rows of every agent on the sequence (A*r instead of r elements per token).
- *   Kernels: bf16 with rank % 8 == 0 runs on the MFMA kernels.  Decode of one sequence in a
- *   contiguous cache without the rotary key side reads K_base / V_base once for all agents
- *   (the agents of a row tile each bring their own column block of the L tile, so a tile holds
- *   4 agents at rank <= 16, 2 at rank <= 32, 1 above); decode on paged caches, of batches, or
- *   with the rotary key side gives every agent a row tile and a workgroup of its own, which
- *   requests K_base / V_base once per agent (the later requests are served by L2); prefill
- *   reads the one agent's rows with their stride.  Other dtypes and ranks run on the vector-ALU
+ *   Kernels: bf16 with rank % 8 == 0 runs on the MFMA kernels.  Decode without the rotary
+ *   key side reads K_base / V_base once for the agents of a row tile (each brings its own
+ *   column block of the L tile, so a tile holds 4 agents at rank <= 16, 2 at rank <= 32, 1
+ *   above; on a paged cache the low-rank rows of one adapter, num_blocks * 16 rows at the row
+ *   stride, must then lie within 2 GB); decode with the rotary key side, or beyond that
+ *   size, gives every agent a row tile and a workgroup of its own, which requests K_base /
+ *   V_base once per agent (the later requests are served by L2); prefill reads the one
+ *   agent's rows with their stride.  Other dtypes and ranks run on the vector-ALU
  *   kernels.  lra_cache_append fills adapter 0's rows only (BaseLRShared is the scheme with
  *   one producer call per token).
  */

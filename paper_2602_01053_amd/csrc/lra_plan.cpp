@@ -291,21 +291,25 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
   }
   if (!pl.mfma) pl.short_prefill = false;
   if (pl.mfma && stream_only) {
-    // these calls exist only in the streaming form: at most one workgroup per compute unit, and a
-    // wave's L rows inside 32-bit byte offsets
+    // These calls want the streaming form: at most one workgroup per compute unit, and a wave's L rows inside 32-bit
+    // byte offsets.  Where that does not fit (more (kv head, row group) units than compute units, a very wide row
+    // pitch) the split-KV kernel reads the same layouts, a wave addressing a quarter of a key share.
     const int64_t max_shares = kCUs / work;
     const int64_t cap_l = ((int64_t{1} << 31) - 4096) / (l_pitch * 2) / tile * tile;
-    if (max_shares < 1 || cap_l < tile) {
-      pl.mfma = false;
-    } else {
+    int64_t sk = split_keys;
+    bool fits = max_shares >= 1 && cap_l >= tile;
+    if (fits) {
       const int64_t need = ((c->max_seq_len + max_shares - 1) / max_shares + tile - 1) / tile * tile;
-      if (split_keys < need) split_keys = static_cast<int>(need);
-      if (split_keys > cap_l) pl.mfma = false;
+      if (sk < need) sk = need;
+      fits = sk <= cap_l && sk <= ((int64_t{1} << 31) - 4096) / (c->kv_token_stride * 2) / tile * tile;
     }
-    if (pl.mfma && c->block_size == 0 &&
-        split_keys > ((int64_t{1} << 31) - 4096) / (c->kv_token_stride * 2) / tile * tile)
-      pl.mfma = false;
-    if (!pl.mfma) pl.l_block = 0;
+    if (fits) {
+      split_keys = static_cast<int>(sk);
+    } else {
+      const int64_t cap4 = ((int64_t{1} << 31) - 4096) / (l_pitch * 2) * 4 / tile * tile;
+      if (cap4 < tile) pl.mfma = false;
+      else if (split_keys > cap4) split_keys = static_cast<int>(cap4);
+    }
   }
   if (!pl.mfma) pl.l_block = 0;
   pl.split_keys = split_keys;

@@ -108,11 +108,9 @@ int main(int argc, char** argv) {
         CHECK(!prefill && pl.mfma && c.l_adapter_stride > 0 && pl.row_tiles == 1 && !(sh.key_rope_theta > 0.f));
         CHECK(pl.l_block * (16 / pl.group_pad) <= 64 && pl.l_block >= sh.rank && pl.qt_bytes == 0);
         const int64_t pitch = c.l_row_stride ? c.l_row_stride : sh.rank;
-        if (c.block_size == 0 && tune.variant != 2) {
-          // streaming form: at most one workgroup per compute unit
-          CHECK(static_cast<int64_t>(sh.n_kv_heads) * pl.n_splits * pl.row_groups <= kCUs);
-        } else if (c.block_size == 0) {
-          // split-KV form on a contiguous cache: a wave's L rows inside 32-bit byte offsets
+        if (c.block_size == 0) {
+          // contiguous cache (streaming form with at most one workgroup per compute unit, else split-KV form): a
+          // wave's L rows inside 32-bit byte offsets
           CHECK(static_cast<int64_t>(pl.split_keys) / 4 * pitch * 2 < (int64_t{1} << 31));
         } else {
           // split-KV form on a paged cache: the whole pool of an adapter's L rows inside them

@@ -124,3 +124,45 @@ def test_rotary_prefill_key_prepass_stays_inside_its_workspace(paged):
     rel, mx = errors(out.to(torch.float64).cpu().numpy(), ref)
     assert np.isfinite(out.float().cpu().numpy()).all()
     assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL
+
+
+@pytest.mark.parametrize("theta", [0.0, 500000.0], ids=["plain", "rotary"])
+def test_base_shared_paged_batch_stays_inside_its_buffers(theta):
+    """One low-rank cache per adapter over a ragged paged batch (column-block L tile; with the rotary key side one
+    agent per tile): guard bands around out and the workspace, parity with the oracle evaluated query by query."""
+    import numpy as np
+    import oracle
+    w = W.make_paged("canary_bs", seed=612, seq_lens=[1, 16, 17, 250, 1027, 2051], agents_per_seq=3, n_adapters=3,
+                     n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, d_model=None, b_std=0.1 if theta > 0 else 0.05)
+    gen = torch.Generator().manual_seed(613)
+    pools = [w.l] + [torch.where(torch.isnan(w.l.float()), w.l.float(), torch.randn(w.l.shape, generator=gen)).to(torch.bfloat16)
+                     for _ in range(2)]
+    l_dev = torch.stack(pools).to(DEV)
+    qd, k, v = w.q.to(DEV), w.k_base.to(DEV), w.v_base.to(DEV)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    table, bk, bv = w.block_table.to(DEV), w.b_k.to(DEV), w.b_v.to(DEV)
+    qa, qs = w.query_adapter.to(DEV), w.seq_query_start.to(DEV)
+    shape = lra.make_shape(qd, w.n_kv_heads, w.rank, 0.0, theta)
+    cache = lra.make_cache(k, v, l_dev, lens, max(w.seq_lens), table, l_per_adapter=True)
+    nq = qd.shape[0]
+    need = max(lra.lra_workspace_bytes(shape, cache, nq, 3), 256)
+    ws_whole, ws_view, ws_start = _guarded(need)
+    out_bytes = qd.numel() * qd.element_size()
+    out_whole, out_view, out_start = _guarded(out_bytes)
+    out = out_view.view(qd.dtype).view(qd.shape)
+    out.fill_(float("nan"))
+    lra.lra_attn_decode(shape, cache, bk, bv, w.n_adapters, qd, qa, qs, 3, out, ws_view)
+    torch.cuda.synchronize()
+    assert _margins_intact(ws_whole, ws_start, need), "write outside the workspace"
+    assert _margins_intact(out_whole, out_start, out_bytes), "write outside out"
+    f = lambda t: t.to(torch.float64).numpy()
+    ref = np.zeros(tuple(w.q.shape))
+    starts = w.seq_query_start.numpy()
+    for i in range(nq):
+        a = int(w.query_adapter[i])
+        t = int(np.searchsorted(starts, i, side="right") - 1)
+        ref[i] = oracle.decode(f(w.q[i:i + 1]), f(w.k_base), f(w.v_base), f(pools[a]), f(w.b_k), f(w.b_v), np.array([a], dtype=np.int32),
+                               np.array([0] * (t + 1) + [1] * (len(w.seq_lens) - t), dtype=np.int32), w.seq_lens, w.scale,
+                               block_size=16, block_table=w.block_table.numpy(), key_rope_theta=theta)[0]
+    rel, mx = errors(out.to(torch.float64).cpu().numpy(), ref)
+    assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL

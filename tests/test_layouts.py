@@ -136,6 +136,7 @@ NATIVE_SHAPES = [
     (1200, 9, 8, 2, 128, 16),      # more agents than a tile holds: three row groups share the key stream
     (900, 3, 16, 4, 128, 64),      # rank 64: one agent per tile
     (500, 5, 4, 4, 64, 40),        # rank 40 in a 64-rank block, group of 1
+    (300, 140, 32, 8, 128, 16),    # 35 row groups x 8 kv heads: more units than compute units, split-KV form of the column-block tile
     (1, 2, 4, 2, 128, 16),         # a single key
 ]
 
