@@ -324,6 +324,31 @@ def base_shared_decode(args, torch, lra, workloads):
             "kernel_frac_of_hbm_peak": round(alg / ksec / 1e9 / HBM_PEAK_GBS, 4)}
 
 
+def base_shared_paged_decode(args, torch, lra, workloads):
+    """The ragged paged batch (config 5) under BaseShared: one pool of low-rank rows per adapter, every query reads
+    the pool of its own adapter.  Algorithmic bytes: config 5's plus the rows of the other adapters' pools."""
+    from paper_2602_01053_amd.runner import DeviceWorkload
+    dev = torch.device("cuda:0")
+    w = workloads.config(5)
+    gen = torch.Generator().manual_seed(20260305)
+    pools = [w.l] + [torch.where(torch.isnan(w.l.float()), w.l.float(), torch.randn(w.l.shape, generator=gen)).to(torch.bfloat16)
+                     for _ in range(w.n_adapters - 1)]
+    alg = w.algorithmic_bytes() + (w.n_adapters - 1) * sum(w.seq_lens) * w.rank * 2
+    dw = DeviceWorkload(w, dev)
+    dw.l = torch.stack(pools).to(dev)             # [adapter][block][16][r]
+    dw.cache = lra.make_cache(dw.k_base, dw.v_base, dw.l, dw.seq_lens, max(w.seq_lens), dw.block_table, l_per_adapter=True)
+    nbytes = lra.lra_workspace_bytes(dw.shape, dw.cache, w.n_queries, dw.max_queries_per_seq, 0)
+    dw.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    steps = max(20, args.steps // 10)
+    for _ in range(5):
+        dw.decode()
+    sec, _ = graph_seconds(torch, lambda i, st: dw.decode(st), steps)
+    torch.cuda.empty_cache()
+    return {"workload": w.name + " with one pool of low-rank rows per adapter (BaseShared)", "algorithmic_bytes": alg,
+            "value": round(alg / sec / 1e9, 1), "unit": "GB/s", "ms_per_step": round(sec * 1e3, 5),
+            "frac_of_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def bench_prefill(args, torch, lra, workloads, kernel_only=False):
     """Config 3: at least MIN_PREFILL_LAUNCHES timed launches after at least 10 warm-up launches, whatever
     --steps says (a call is one kernel of 0.6 ms; a handful of launches would time the clock ramp)."""
@@ -642,6 +667,7 @@ def main():
         line["other_decode_workloads"] = other_decode_workloads(args, torch, lra, workloads)
         line["value_only_adapters"] = value_only_decode(args, torch, lra, workloads)
         line["base_shared"] = base_shared_decode(args, torch, lra, workloads)
+        line["base_shared"]["paged_batch"] = base_shared_paged_decode(args, torch, lra, workloads)
     if not args.no_append:
         line["cache_append"] = bench_append(args, torch, lra, not args.no_cpu_baseline)
     if not args.no_trace:

@@ -47,6 +47,8 @@ struct Params {
   float key_rope_theta;  // > 0: the key-side adapter contribution is rotated by its token's position
   int32_t share_major;       // decode_stream_kernel: workgroup index laid out so that all kv heads of a key share run on one XCD
   int32_t keys_f16;          // prefill_mfma_kernel: k_base holds completed keys K_base + RoPE(L B_K) as fp16 (left by the key pre-pass)
+  int32_t rg_interleave;     // decode_mfma_kernel with several row groups: 0, or the power of two m of the grid layout that
+                             // puts the row groups of a (sequence, kv head, key share) on one XCD, next to each other in time
 #ifdef LRA_TIMING
   unsigned long long* timing;  // instrumented test build only: per-wave phase stamps
 #endif

@@ -114,9 +114,24 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   LRA_STAMP(0);
   // kv head is the fastest grid index: workgroups go round-robin over the XCDs, so with 8 kv
   // heads all workgroups of a head run on one XCD and share Q and B_K in its L2
-  const int h = blockIdx.x, split = blockIdx.y;
-  const int t = CAUSAL ? p.seq_index : blockIdx.z / p.row_groups;
-  const int rg = CAUSAL ? blockIdx.z : blockIdx.z - t * p.row_groups;
+  const int h = blockIdx.x;
+  int split = blockIdx.y;
+  int t = CAUSAL ? p.seq_index : blockIdx.z / p.row_groups;
+  int rg = CAUSAL ? blockIdx.z : blockIdx.z - t * p.row_groups;
+  if (p.rg_interleave > 0) {
+    // Several row groups share the keys of a (sequence, kv head, key share): only the first to ask reads them from
+    // HBM if the others ask the same L2 soon after.  Workgroups go round-robin over the 8 XCDs in the order of
+    // their linear index x + Hkv * y, so with m = lcm(8, Hkv) / Hkv and y = (share mod m) + m * (row group +
+    // row_groups * (share / m)) the row groups of a share are lcm(8, Hkv) workgroups apart: the same XCD, the next
+    // round of the dispatcher.  (Key shares are padded to a multiple of m; z is the sequence.)
+    const int m = p.rg_interleave, y = blockIdx.y;
+    const int hi = y >> __builtin_ctz(m);
+    const int q = hi / p.row_groups;
+    rg = hi - q * p.row_groups;
+    split = (y & (m - 1)) + m * q;
+    t = CAUSAL ? p.seq_index : blockIdx.z;
+    if (split >= p.n_splits) return;
+  }
   // The first and the last entry of seq_query_start are fixed by the contract (0 and
   // n_queries): a single sequence needs no table read at all, and the adapter ids can be
   // requested at once instead of one memory round trip later.
@@ -988,10 +1003,29 @@ static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
   return hipGetLastError();
 }
 
+static hipError_t launch_decode_mfma_grid(const Params& p, int row_tiles, dim3 grid, hipStream_t s);
+
 hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_form, bool main_kernel_only, hipStream_t s) {
   // calls that give a compute unit at most one workgroup: the form with two tile stages per wave
   if (allow_stream_form && decode_stream_applies(p, row_tiles, 256)) return launch_decode_stream(p, row_tiles, main_kernel_only, s);
   dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
+  Params pi = p;
+  pi.rg_interleave = 0;
+  if (p.row_groups > 1) {
+    // (see the kernel: row groups of a key share next to each other on one XCD)
+    int g = p.n_kv_heads, e = 8;
+    while (e) { const int tmp = g % e; g = e; e = tmp; }  // g = gcd(Hkv, 8)
+    const int m = 8 / g;
+    const int64_t gy = static_cast<int64_t>((p.n_splits + m - 1) / m) * m * p.row_groups;
+    if (gy <= 65535) {
+      pi.rg_interleave = m;
+      grid = dim3(p.n_kv_heads, static_cast<unsigned>(gy), p.is_prefill ? 1 : p.n_seqs);
+    }
+  }
+  return launch_decode_mfma_grid(pi, row_tiles, grid, s);
+}
+
+static hipError_t launch_decode_mfma_grid(const Params& p, int row_tiles, dim3 grid, hipStream_t s) {
   if (p.key_rope_theta > 0.f && p.b_k != nullptr) {
     if (row_tiles != 1 || (!p.is_prefill && 16 / p.group_pad > decode_mfma_rope_slots(p.rank))) return hipErrorInvalidValue;
     const int sel = (p.head_dim == 128 ? 3 : 0) + (p.rank <= 16 ? 0 : (p.rank <= 32 ? 1 : 2));
