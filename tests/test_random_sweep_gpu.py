@@ -337,3 +337,54 @@ def test_base_shared_on_paged_caches(block):
                                        np.array([0] * (t + 1) + [1] * (len(lens) - t), dtype=np.int32), w.seq_lens, w.scale,
                                        block_size=16, block_table=w.block_table.numpy(), key_rope_theta=theta)[0]
         _check(out.to(torch.float64).cpu().numpy(), ref, tag)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_many_agents_per_sequence_on_paged_caches(block):
+    """Decode with up to twelve agents per sequence of a paged ragged batch, so that several workgroups (row groups)
+    share the keys of a (sequence, kv head, key share); kv head counts that do not divide 8; one shared low-rank
+    cache or one per adapter; plain or rotary key side; forced key shares."""
+    f = lambda t: t.to(torch.float64).numpy()
+    for case in range(block * BLOCK, (block + 1) * BLOCK):
+        rnd = random.Random(170_000 + case)
+        g = rnd.choice([1, 2, 4, 7, 8, 16])
+        hkv = min(rnd.choice([1, 2, 3, 4, 6, 8]), max(1, 48 // g))
+        hq = hkv * g
+        d, r = rnd.choice([64, 128]), rnd.choice([8, 16, 24, 32, 48, 64])
+        lens = [rnd.choice([1, 15, 16, 17, 300, rnd.randint(1, 3000)]) for _ in range(rnd.randint(1, 4))]
+        aps, theta, shared = rnd.randint(3, 12), rnd.choice([0.0, 0.0, 500000.0]), rnd.random() < 0.5
+        variant, split = rnd.choice([0, 0, 2]), rnd.choice([0, 0, 128, 512])
+        w = W.make_paged("sweep", seed=case, seq_lens=lens, agents_per_seq=aps, n_adapters=rnd.randint(1, 5), n_q_heads=hq,
+                         n_kv_heads=hkv, head_dim=d, rank=r, d_model=None, b_std=0.1 if theta > 0 else 0.05,
+                         distinct_adapter_per_query=rnd.random() < 0.3)
+        na = w.n_adapters
+        gen = torch.Generator().manual_seed(case + 7)
+        l_pools = [w.l] + [torch.where(torch.isnan(w.l.float()), w.l.float(), torch.randn(w.l.shape, generator=gen)).to(torch.bfloat16)
+                           for _ in range(0 if shared else na - 1)]
+        l_dev = w.l.to(DEV) if shared else torch.stack(l_pools).to(DEV)
+        qd, kp, vp = w.q.to(DEV), w.k_base.to(DEV), w.v_base.to(DEV)
+        table, bk, bv = w.block_table.to(DEV), w.b_k.to(DEV), w.b_v.to(DEV)
+        lens_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        qa, qs = w.query_adapter.to(DEV), w.seq_query_start.to(DEV)
+        tag = (f"case {case} lens={lens} aps={aps} na={na} hq={hq} hkv={hkv} d={d} r={r} theta={theta:g} shared={shared} "
+               f"variant={variant} split={split}")
+        shape = lra.make_shape(qd, hkv, r, 0.0, theta)
+        cache = lra.make_cache(kp, vp, l_dev, lens_d, max(lens), table, l_per_adapter=not shared)
+        out = torch.full_like(qd, float("nan"))
+        old = (lra.lra_set_kernel_variant(variant), lra.lra_set_decode_split_keys(split))
+        try:
+            ws = torch.empty(max(lra.lra_workspace_bytes(shape, cache, qd.shape[0], aps), 256), dtype=torch.uint8, device=DEV)
+            lra.lra_attn_decode(shape, cache, bk, bv, na, qd, qa, qs, aps, out, ws)
+            torch.cuda.synchronize()
+        finally:
+            lra.lra_set_kernel_variant(old[0])
+            lra.lra_set_decode_split_keys(old[1])
+        ref = np.zeros(tuple(w.q.shape))
+        starts = w.seq_query_start.numpy()
+        for i in range(qd.shape[0]):
+            a = int(w.query_adapter[i])
+            t = int(np.searchsorted(starts, i, side="right") - 1)
+            ref[i] = oracle.decode(f(w.q[i:i + 1]), f(w.k_base), f(w.v_base), f(l_pools[0 if shared else a]), f(w.b_k), f(w.b_v),
+                                   np.array([a], dtype=np.int32), np.array([0] * (t + 1) + [1] * (len(lens) - t), dtype=np.int32),
+                                   w.seq_lens, w.scale, block_size=16, block_table=w.block_table.numpy(), key_rope_theta=theta)[0]
+        _check(out.to(torch.float64).cpu().numpy(), ref, tag)
