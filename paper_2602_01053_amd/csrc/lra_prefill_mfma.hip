@@ -83,7 +83,18 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(Params p) {
   const int hk = lin % Hkv;
   const int rest = lin / Hkv;
   const int gq = rest % G;
-  const int qt = rest / G;
+  int qt = rest / G;
+  {
+    // Causal q tiles differ in length (tile i walks the keys up to its diagonal).  The 256 compute units take
+    // workgroups in rounds of 256; a unit that holds two workgroups holds number k and number k + 256.  Every other
+    // round walks its q tiles backwards, so the long tiles of one round sit next to the short tiles of the next
+    // and the units finish together.
+    const int q_tiles = (p.n_new + BM - 1) / BM;
+    const int tpr = max(1, 256 / Hq);              // q tiles per round
+    const int round = qt / tpr, pos = qt - round * tpr;
+    const int cnt = min(tpr, q_tiles - round * tpr);
+    if ((round & 1)) qt = round * tpr + (cnt - 1 - pos);
+  }
   const int t = p.seq_index;
   const int a_idx = p.adapter_index;
   const int n_t = min(PF_CONST_I32(p.seq_lens)[t], p.max_seq_len);
