@@ -37,7 +37,7 @@ class LraCache(ctypes.Structure):
                 ("num_blocks", ctypes.c_int32), ("n_seqs", ctypes.c_int32),
                 ("l_row_stride", ctypes.c_int64), ("l_adapter_stride", ctypes.c_int64),
                 ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
-                ("max_seq_len", ctypes.c_int32)]
+                ("max_seq_len", ctypes.c_int32), ("seq_lens_host", ctypes.c_void_p)]
 
 
 class LraAdapters(ctypes.Structure):
@@ -229,8 +229,10 @@ def make_shape(q: torch.Tensor, n_kv_heads: int, rank: int, scale: float = 0.0,
 
 
 def make_cache(k_base: torch.Tensor, v_base: torch.Tensor, l: torch.Tensor, seq_lens: torch.Tensor,
-               max_seq_len: int, block_table: Optional[torch.Tensor] = None, l_per_adapter: bool = False) -> LraCache:
+               max_seq_len: int, block_table: Optional[torch.Tensor] = None, l_per_adapter: bool = False,
+               seq_lens_host=None) -> LraCache:
     """Describe a cache held in torch tensors.
+    seq_lens_host: optional host copy of the lengths (a sequence of ints) for launch planning.
 
     contiguous: k_base/v_base any strided view indexed [token][kv head][d] with a
     unit stride on d; paged: k_base/v_base [num_blocks][Hkv][16][d] (strided view
@@ -245,17 +247,25 @@ def make_cache(k_base: torch.Tensor, v_base: torch.Tensor, l: torch.Tensor, seq_
         l_adapter_stride, l = l.stride(0), l[0]
     if l.stride(-1) != 1:
         raise LraError(2, "l must have a unit stride on the rank")
+    mirror = None
+    if seq_lens_host is not None:
+        vals = [int(x) for x in seq_lens_host]
+        mirror = (ctypes.c_int32 * len(vals))(*vals)
+    mirror_ptr = None if mirror is None else ctypes.cast(mirror, ctypes.c_void_p)
     if block_table is None:
         if l.dim() != 2:
             raise LraError(2, "contiguous l must be [tokens][r]")
-        return LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(0), k_base.stride(1), 0,
-                        0, 0, 0, 1, l.stride(0), l_adapter_stride, None, _ptr(seq_lens), int(max_seq_len))
-    if l.dim() != 3 or l.stride(0) != 16 * l.stride(1):
-        raise LraError(2, "paged l must be [num_blocks][16][r] with the 16 rows of a block one row stride apart")
-    return LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(2), k_base.stride(1),
-                    k_base.stride(0), int(k_base.shape[2]), int(block_table.shape[1]),
-                    int(k_base.shape[0]), int(block_table.shape[0]), l.stride(1), l_adapter_stride, _ptr(block_table),
-                    _ptr(seq_lens), int(max_seq_len))
+        cache = LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(0), k_base.stride(1), 0,
+                         0, 0, 0, 1, l.stride(0), l_adapter_stride, None, _ptr(seq_lens), int(max_seq_len), mirror_ptr)
+    else:
+        if l.dim() != 3 or l.stride(0) != 16 * l.stride(1):
+            raise LraError(2, "paged l must be [num_blocks][16][r] with the 16 rows of a block one row stride apart")
+        cache = LraCache(_ptr(k_base), _ptr(v_base), _ptr(l), k_base.stride(2), k_base.stride(1),
+                         k_base.stride(0), int(k_base.shape[2]), int(block_table.shape[1]),
+                         int(k_base.shape[0]), int(block_table.shape[0]), l.stride(1), l_adapter_stride, _ptr(block_table),
+                         _ptr(seq_lens), int(max_seq_len), mirror_ptr)
+    cache._host_mirror = mirror  # the struct holds a raw pointer into it
+    return cache
 
 
 def lra_workspace_bytes(shape: LraShape, cache: LraCache, n_queries: int,

@@ -11,7 +11,7 @@ from .workloads import Workload
 class DeviceWorkload:
     """Device copies of a Workload plus the C structs that describe them."""
 
-    def __init__(self, w: Workload, dev, head_major: bool = False, key_rope_theta: float = 0.0):
+    def __init__(self, w: Workload, dev, head_major: bool = False, key_rope_theta: float = 0.0, host_lens: bool = True):
         self.w = w
         self.q = w.q.to(dev)
         if w.block_size == 0 and head_major:
@@ -31,8 +31,10 @@ class DeviceWorkload:
         s = w.seq_query_start.tolist()
         self.max_queries_per_seq = max(b - a for a, b in zip(s[:-1], s[1:]))
         self.shape = lra.make_shape(self.q, w.n_kv_heads, w.rank, w.scale, key_rope_theta)
+        # (the host copy of the lengths only steers launch planning of batches)
         self.cache = lra.make_cache(self.k_base, self.v_base, self.l, self.seq_lens,
-                                    max(w.seq_lens), self.block_table)
+                                    max(w.seq_lens), self.block_table,
+                                    seq_lens_host=list(w.seq_lens) if host_lens else None)
         self.out = torch.empty_like(self.q)
         self.workspace = None
 

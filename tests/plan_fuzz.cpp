@@ -3,6 +3,7 @@
 // and sizes go through the argument checks and, where those accept them, through the planner; every
 // plan must keep its invariants, and the sanitizers must stay silent (signed overflow in the 32-bit
 // offset caps and workspace sizes is what this is after).
+#include <vector>
 #include <cinttypes>
 #include <cstdint>
 #include <cstdio>
@@ -116,6 +117,19 @@ int main(int argc, char** argv) {
           // split-KV form on a paged cache: the whole pool of an adapter's L rows inside them
           CHECK(static_cast<int64_t>(c.num_blocks) * 16 * pitch * 2 < (int64_t{1} << 31));
         }
+      }
+      if (!prefill && c.n_seqs > 1 && c.n_seqs <= 2000) {
+        // with a host copy of the lengths (any values: they are clamped) the key shares only grow, the workspace
+        // only shrinks, and nothing else of the plan moves
+        std::vector<int32_t> lens(static_cast<size_t>(c.n_seqs));
+        for (auto& v : lens) v = static_cast<int32_t>(pick({-3, 0, 1, 17, c.max_seq_len / 2, c.max_seq_len, c.max_seq_len, INT32_MAX}));
+        lra_cache cm = c;
+        cm.seq_lens_host = lens.data();
+        const Plan pm = make_plan(&sh, &cm, static_cast<int>(tokens), static_cast<int>(mq), false, tune);
+        CHECK(pm.mfma == pl.mfma && pm.group_pad == pl.group_pad && pm.row_groups == pl.row_groups && pm.l_block == pl.l_block);
+        CHECK(pm.split_keys >= pl.split_keys && pm.n_splits <= pl.n_splits && pm.bytes <= pl.bytes);
+        CHECK(pm.split_keys % (pm.mfma ? 128 : 64) == 0);
+        if (c.block_size == 0 && pm.mfma) CHECK(static_cast<int64_t>(pm.split_keys) * c.kv_token_stride * 2 < (int64_t{1} << 31));
       }
       const bool split_path = !prefill || pl.short_prefill || !pl.mfma;
       if (split_path && pl.mfma) {

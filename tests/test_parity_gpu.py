@@ -250,6 +250,29 @@ def test_paged_small_ragged_distinct_adapters(variant):
     _gate(run_decode(w, DEV), oracle_decode(w), label=w.name)
 
 
+@pytest.mark.parametrize("mirror", ["none", "exact", "all_zero", "too_long"])
+def test_host_copy_of_the_lengths_only_steers_planning(mirror):
+    """lra_cache.seq_lens_host: the decode of a batch sizes its key shares from it; the results do not depend on
+    it, whatever it holds, and a workspace sized without it serves the call with it."""
+    import paper_2602_01053_amd as lra
+    from paper_2602_01053_amd.runner import DeviceWorkload
+    lens = [6000, 5500, 7000, 6500, 5300, 6900, 5251, 7001]
+    w = W.make_paged("mirror", seed=79, seq_lens=lens, agents_per_seq=2, n_adapters=3, n_q_heads=16, n_kv_heads=4,
+                     head_dim=128, rank=16, d_model=None, b_std=0.05)
+    host = {"none": None, "exact": lens, "all_zero": [0] * len(lens), "too_long": [10 ** 6] * len(lens)}[mirror]
+    dw = DeviceWorkload(w, DEV, host_lens=False)
+    need_without = dw.alloc_workspace()
+    dw.cache = lra.make_cache(dw.k_base, dw.v_base, dw.l, dw.seq_lens, max(lens), dw.block_table, seq_lens_host=host)
+    need_with = lra.lra_workspace_bytes(dw.shape, dw.cache, w.n_queries, dw.max_queries_per_seq, 0)
+    assert need_with <= need_without
+    if mirror in ("exact", "too_long"):
+        assert need_with < need_without  # 8 sequences x 4 kv heads of 5251 to 7001 keys: fewer, longer key shares
+    dw.out.fill_(float("nan"))
+    dw.decode()                        # on the workspace sized without the lengths
+    torch.cuda.synchronize()
+    _gate(dw.out.to(torch.float64).cpu().numpy(), oracle_decode(w), label=f"{w.name} {mirror}")
+
+
 def test_uneven_queries_per_sequence(variant):
     """Sequences with 0, 1 and many queries in one call."""
     w = W.make_paged("uneven", seed=78, seq_lens=[300, 77, 129, 512], agents_per_seq=2, n_adapters=3,
