@@ -12,9 +12,26 @@
 
 namespace lra {
 
+// row . vec, the row read in 16-byte pieces where its length and address allow (every lane of these kernels walks
+// a row of its own, so a piece is one cache-line touch instead of four or eight)
 template <typename T>
 __device__ __forceinline__ float dot_row(const T* __restrict__ row, const float* __restrict__ vec, int len) {
+  constexpr int PER = 16 / static_cast<int>(sizeof(T));  // elements per piece: 4 (fp32) or 8 (bf16)
   float acc = 0.f;
+  if (len % PER == 0 && (reinterpret_cast<uintptr_t>(row) & 15) == 0) {
+    for (int c = 0; c < len; c += PER) {
+      const uint4 piece = *reinterpret_cast<const uint4*>(row + c);
+      const uint32_t w[4] = {piece.x, piece.y, piece.z, piece.w};
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        float x;
+        if constexpr (sizeof(T) == 4) x = __uint_as_float(w[e]);
+        else x = __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+        acc = fmaf(x, vec[c + e], acc);
+      }
+    }
+    return acc;
+  }
   for (int c = 0; c < len; ++c) acc = fmaf(to_f32<T>(row[c]), vec[c], acc);
   return acc;
 }
@@ -81,13 +98,30 @@ __global__ __launch_bounds__(kWave) void generic_partial_kernel(Params p) {
     o0 *= alpha;
     o1 *= alpha;
     olr *= alpha;
+    // O += p_j V_j, O_lr += p_j L_j: lane = column.  Eight keys' rows are requested before the first is used (one
+    // row per trip would pay a memory round trip per key); every load is unconditional from a clamped index, what
+    // it fetched in vain is not added.
     const int cnt = min(kWave, j1 - jb);
-    for (int jj = 0; jj < cnt; ++jj) {
-      const float pjj = __shfl(pj, jj, kWave);
-      const T* v = vb + kv_offset(p, t, jb + jj, h);
-      if (lane < d) o0 = fmaf(pjj, to_f32<T>(v[lane]), o0);
-      if (lane + kWave < d) o1 = fmaf(pjj, to_f32<T>(v[lane + kWave]), o1);
-      if (lane < r) olr = fmaf(pjj, to_f32<T>(lr[l_offset(p, t, jb + jj, a) + lane]), olr);
+    const int c0 = min(lane, d - 1), c1 = min(lane + kWave, d - 1), cl = min(lane, r - 1);
+    for (int jj0 = 0; jj0 < cnt; jj0 += 8) {
+      float v0[8], v1[8], vl[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int jk = jb + min(jj0 + u, cnt - 1);
+        const T* v = vb + kv_offset(p, t, jk, h);
+        v0[u] = to_f32<T>(v[c0]);
+        v1[u] = to_f32<T>(v[c1]);
+        vl[u] = to_f32<T>(lr[l_offset(p, t, jk, a) + cl]);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (jj0 + u < cnt) {  // (uniform)
+          const float pjj = __shfl(pj, jj0 + u, kWave);
+          o0 = fmaf(pjj, v0[u], o0);
+          o1 = fmaf(pjj, v1[u], o1);
+          olr = fmaf(pjj, vl[u], olr);
+        }
+      }
     }
     m = m_new;
   }
