@@ -234,13 +234,26 @@ __global__ __launch_bounds__(kWave) void generic_partial_rope_kernel(Params p) {
     o0 *= alpha;
     o1 *= alpha;
     olr *= alpha;
+    // (as in generic_partial_kernel: the V rows of eight keys requested before the first is used)
     const int cnt = min(kWave, j1 - jb);
-    for (int jj = 0; jj < cnt; ++jj) {
-      const float pjj = __shfl(pj, jj, kWave);
-      const T* v = vb + kv_offset(p, t, jb + jj, h);
-      if (lane < d) o0 = fmaf(pjj, to_f32<T>(v[lane]), o0);
-      if (lane + kWave < d) o1 = fmaf(pjj, to_f32<T>(v[lane + kWave]), o1);
-      if (lane < r) olr = fmaf(pjj, l_s[jj * 65 + lane], olr);
+    const int c0 = min(lane, d - 1), c1 = min(lane + kWave, d - 1);
+    for (int jj0 = 0; jj0 < cnt; jj0 += 8) {
+      float v0[8], v1[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const T* v = vb + kv_offset(p, t, jb + min(jj0 + u, cnt - 1), h);
+        v0[u] = to_f32<T>(v[c0]);
+        v1[u] = to_f32<T>(v[c1]);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (jj0 + u < cnt) {  // (uniform)
+          const float pjj = __shfl(pj, jj0 + u, kWave);
+          o0 = fmaf(pjj, v0[u], o0);
+          o1 = fmaf(pjj, v1[u], o1);
+          if (lane < r) olr = fmaf(pjj, l_s[(jj0 + u) * 65 + lane], olr);
+        }
+      }
     }
     m = m_new;
     __syncthreads();  // before the next step overwrites the staged rows
