@@ -64,7 +64,11 @@ constexpr int kRopeSlots64 = 4;
 // of the adapter of agent slot s; Qt of a row stands in the block of its slot and is zero elsewhere, so the same
 // products give Qt_a . L_a^T and P . L_a per agent, and a row keeps only its own block of O_lr.  K_base and V_base are
 // then read once for all agents of a tile, and no zero padding is streamed.
-template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL, int RPE = 0, bool PA = false>
+// RGI = false leaves out the grid layout for several row groups (below).  The rotary forms sit at the edge of their
+// register file, and the few instructions of that layout at the top of the kernel were enough to move their
+// allocation (config 2 with the rotary key side: 21.9 -> 23.3 us per call): they are built both ways and take the
+// layout only when a call has several row groups.
+template <int D, int RT, int RP, bool PAGED, bool HAS_BK, bool CAUSAL, int RPE = 0, bool PA = false, bool RGI = true>
 __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Params p) {
   constexpr int NW = 4;
   constexpr bool ROPE = RPE > 0;
@@ -118,7 +122,7 @@ __global__ __launch_bounds__(256, RPE == 64 ? 1 : 2) void decode_mfma_kernel(Par
   int split = blockIdx.y;
   int t = CAUSAL ? p.seq_index : blockIdx.z / p.row_groups;
   int rg = CAUSAL ? blockIdx.z : blockIdx.z - t * p.row_groups;
-  if (p.rg_interleave > 0) {
+  if constexpr (RGI) if (p.rg_interleave > 0) {
     // Several row groups share the keys of a (sequence, kv head, key share): only the first to ask reads them from
     // HBM if the others ask the same L2 soon after.  Workgroups go round-robin over the 8 XCDs in the order of
     // their linear index x + Hkv * y, so with m = lcm(8, Hkv) / Hkv and y = (share mod m) + m * (row group +
@@ -994,11 +998,15 @@ template <int D, int RP, int RPE>
 static hipError_t launch_rope(const Params& p, dim3 grid, hipStream_t s) {
   const bool paged = p.block_size != 0;
   if (p.is_prefill) {
-    if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, true, RPE>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, true, RPE>), grid, dim3(256), 0, s, p);
+    // (launch_decode_mfma keeps the plain grid for these)
+    if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, true, RPE, false, false>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, true, RPE, false, false>), grid, dim3(256), 0, s, p);
+  } else if (p.rg_interleave > 0) {
+    if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, false, RPE, false, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, false, RPE, false, true>), grid, dim3(256), 0, s, p);
   } else {
-    if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, false, RPE>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, false, RPE>), grid, dim3(256), 0, s, p);
+    if (paged) hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, true, true, false, RPE, false, false>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((decode_mfma_kernel<D, 1, RP, false, true, false, RPE, false, false>), grid, dim3(256), 0, s, p);
   }
   return hipGetLastError();
 }
@@ -1011,7 +1019,8 @@ hipError_t launch_decode_mfma(const Params& p, int row_tiles, bool allow_stream_
   dim3 grid(p.n_kv_heads, p.n_splits, (p.is_prefill ? 1 : p.n_seqs) * p.row_groups);
   Params pi = p;
   pi.rg_interleave = 0;
-  if (p.row_groups > 1) {
+  const bool rope_prefill = p.is_prefill && p.key_rope_theta > 0.f && p.b_k != nullptr;  // (built without that layout)
+  if (p.row_groups > 1 && !rope_prefill) {
     // (see the kernel: row groups of a key share next to each other on one XCD)
     int g = p.n_kv_heads, e = 8;
     while (e) { const int tmp = g % e; g = e; e = tmp; }  // g = gcd(Hkv, 8)
