@@ -261,7 +261,11 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     // times as many, equal-sized pieces so the CUs stay balanced.  A batch is assumed to be
     // half as long on average as its longest sequence.
     const bool batch = n_seqs_eff > 1;
-    const int64_t wgs = batch ? kCUs * 4 : kCUs;
+    int64_t wgs = batch ? kCUs * 4 : kCUs;
+    // ... and one long sequence in a paged cache (the split-KV kernel, two workgroups per compute unit) with two,
+    // as long as a share then still has 512 keys (32768 tokens x 8 kv heads: 35.7 against 38.6 us, 65536: 49.2
+    // against 53.7; at 256 keys per share the doubling loses)
+    if (!batch && !prefill && c->block_size != 0 && !rope && work * c->max_seq_len >= int64_t{2} * kCUs * 512) wgs = 2 * kCUs;
     if (work >= 2 * wgs) {
       split_keys = c->max_seq_len;  // more units than workgroups wanted: one share per sequence
     } else {
