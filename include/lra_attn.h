@@ -173,10 +173,11 @@ typedef struct {
   const int32_t* seq_lens_host; /* HOST int32 [n_seqs], optional (NULL: unknown): what the caller
                                   believes seq_lens holds.  Read during the call, never after it
                                   returns, and used for launch planning only: the decode of a
-                                  batch of sequences of about equal length sizes its key shares
-                                  so that the workgroups that find keys fill the compute units
-                                  once (without it a batch is taken to be half as long on
-                                  average as max_seq_len: twice as many shares).  The results do
+                                  batch sizes its key shares so that the workgroups that find
+                                  keys fill the compute units once (sequences of about equal
+                                  length) or just under twice (ragged lengths); without it a
+                                  batch is taken to be half as long on average as max_seq_len.
+                                  The results do
                                   not depend on it; entries outside [0, max_seq_len] are clamped.
                                   Key shares only grow with it, so a workspace sized with NULL
                                   here serves every call on the same shapes. */

@@ -286,9 +286,11 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     // keys are all resident at once, two per compute unit, and equal in size (measured on MI355X, 16 sequences of
     // 32768 tokens: 5.7 TB/s at 512 workgroups, 5.0 at 2048, 4.9 at 704): the smallest share size that keeps them
     // within that; never smaller than the choice above, so the workspace of a call without the lengths is large
-    // enough for any call with them.  A ragged batch (shortest sequence below three quarters of the longest) keeps
-    // the choice above: its shares are unequal, workgroups then finish at different times, and more, smaller
-    // workgroups than there are places level that out (16 sequences of 6.5 k to 65 k tokens: 175 us against 199 us).
+    // enough for any call with them.  A ragged batch (shortest sequence below three quarters of the longest) does
+    // best in two rounds - its shares are unequal, and twice as many workgroups as there are places level that out
+    // (16 sequences of 6.5 k to 65 k tokens: 173-175 us at 840 to 960 workgroups, 199 us at 512) - but not in two
+    // rounds and a bit: the time jumps by a tenth between 960 and 1020 workgroups (a second batch, 24 sequences of
+    // 2 k to 40 k tokens: 190 us at 916, 206 us at 1036).  There the bound is 940.
     const int64_t units = static_cast<int64_t>(sh->n_kv_heads) * pl.row_groups;
     int64_t shortest = c->max_seq_len, longest = 0;
     for (int t = 0; t < c->n_seqs; ++t) {
@@ -309,10 +311,11 @@ Plan make_plan(const lra_shape* sh, const lra_cache* c, int tokens, int max_quer
     };
     int64_t lo = split_keys / tile, hi = (static_cast<int64_t>(c->max_seq_len) + tile - 1) / tile;  // in tiles
     if (hi < lo) hi = lo;
-    if (even_lengths && workgroups(lo * tile) > 2 * kCUs) {
+    const int64_t bound = even_lengths ? 2 * kCUs : 940;
+    if (longest > 0 && workgroups(lo * tile) > bound) {
       while (lo < hi) {  // smallest share in (lo, hi] within the bound, else hi
         const int64_t mid = lo + (hi - lo) / 2;
-        if (workgroups(mid * tile) <= 2 * kCUs) hi = mid;
+        if (workgroups(mid * tile) <= bound) hi = mid;
         else lo = mid + 1;
       }
       split_keys = static_cast<int>(hi * tile);
