@@ -273,6 +273,14 @@ def test_host_copy_of_the_lengths_only_steers_planning(mirror):
     _gate(dw.out.to(torch.float64).cpu().numpy(), oracle_decode(w), label=f"{w.name} {mirror}")
 
 
+def test_one_long_sequence_in_a_paged_cache():
+    """One sequence of 33000 tokens in a paged cache with 8 kv heads: long enough that the planner gives the split-KV
+    kernel two workgroups per compute unit (512 key shares x kv heads), with a ragged last share and last block."""
+    w = W.make_paged("long_paged", seed=80, seq_lens=[33001], agents_per_seq=3, n_adapters=3, n_q_heads=32, n_kv_heads=8,
+                     head_dim=128, rank=16, d_model=None, b_std=0.05)
+    _gate(run_decode(w, DEV), oracle_decode(w), label=w.name)
+
+
 def test_uneven_queries_per_sequence(variant):
     """Sequences with 0, 1 and many queries in one call."""
     w = W.make_paged("uneven", seed=78, seq_lens=[300, 77, 129, 512], agents_per_seq=2, n_adapters=3,
